@@ -1,0 +1,417 @@
+/*
+ * CPU oracle for the student-Transformer translation path.  TEST INFRASTRUCTURE ONLY:
+ * it defines what the GPU library must compute and is used by the tests, the smoke
+ * check and the CPU-baseline leg of the benchmark.  It shares no code with the HIP
+ * library and is never called by the product path.
+ *
+ * Plain C, one sentence at a time, no blocking, no fusion, no BLAS.  Weights are the
+ * fp16 values of the blob widened exactly to fp32; every activation and every
+ * reduction is fp64.
+ *
+ * What is computed (citations are to the paper, arXiv 2109.08003):
+ *   - architecture: deep encoder / one-layer decoder student, single head, FFN removed
+ *     (Sec. 1; Sec. 2.2 "Fast Student Models"; Table 2), with the vanilla-Transformer
+ *     defaults the paper refers to (Sec. 2.1, Table 1 caption): sinusoidal positions,
+ *     sqrt(d) embedding scale, pre-LayerNorm residual blocks with a final LayerNorm
+ *     per stack (reading fixed by the benchmark configuration);
+ *   - 1/sqrt(d_k) applied to the query, softmax in full precision (Sec. 3.1 "FP16 Inference");
+ *   - greedy search with no log-softmax on the output layer (Sec. 3.3 "Graph Optimization",
+ *     "Greedy Search"); ties go to the lowest id;
+ *   - relative position keys with clipping distance 8 for the teacher shape (Sec. 2.1);
+ *   - multi-head attention and ReLU FFN for the ablation / teacher shapes (Table 1, Table 2).
+ *
+ * Parity pins live in tests/test_oracle_*.py.  Parity unpinned: translation quality
+ * (BLEU) - it needs trained weights and test sets that are not available.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef struct {
+  int32_t n_enc, n_dec, d_model, n_heads, d_ffn, vocab, max_len, rpr_clip, tie_output, bos_id;
+  double ln_eps;
+} ora_config;
+
+typedef struct { const float *g, *b; } ln_t;
+typedef struct { const float *Wq, *bq, *Wk, *bk, *Wv, *bv, *Wo, *bo, *rk; } attn_t;
+typedef struct { const float *W1, *b1, *W2, *b2; } ffn_t;
+typedef struct { ln_t ln1; attn_t self; ln_t ln2; ffn_t ffn; } enc_layer;
+typedef struct { ln_t ln1; attn_t self; ln_t ln2; attn_t cross; ln_t ln3; ffn_t ffn; } dec_layer;
+
+typedef struct ora_model {
+  ora_config c;
+  float *w;               /* whole blob widened to fp32 */
+  const float *E, *Wout;  /* [V][d] each; Wout == E when tied */
+  enc_layer *enc;
+  ln_t enc_final;
+  dec_layer *dec;
+  ln_t dec_final;
+} ora_model;
+
+/* ---- fp16 -> fp32, exact ---- */
+float ora_half_to_float(uint16_t h) {
+  uint32_t sign = (uint32_t)(h >> 15) << 31, e = (h >> 10) & 31u, m = h & 1023u, bits;
+  if (e == 0) {
+    if (m == 0) bits = sign;
+    else { /* subnormal: value = m * 2^-24 */
+      float f = (float)m * 5.9604644775390625e-8f;
+      memcpy(&bits, &f, 4); bits |= sign;
+    }
+  } else if (e == 31) bits = sign | 0x7f800000u | (m << 13);
+  else bits = sign | ((e + 112u) << 23) | (m << 13);
+  float out; memcpy(&out, &bits, 4); return out;
+}
+
+/* ---- closed-form parameter count of the blob (matrices, biases, LayerNorms) ---- */
+int64_t ora_param_count(const ora_config *c) {
+  int64_t d = c->d_model, V = c->vocab, F = c->d_ffn, dh = d / c->n_heads;
+  int64_t attn = 4 * (d * d + d), ln = 2 * d, ffn = F > 0 ? (2 * d * F + F + d + ln) : 0;
+  int64_t rk = c->rpr_clip > 0 ? (2 * c->rpr_clip + 1) * dh : 0;
+  int64_t n = V * d * (c->tie_output ? 1 : 2);
+  n += c->n_enc * (ln + attn + rk + ffn) + ln;
+  n += c->n_dec * (ln + attn + rk + ln + attn + ffn) + ln;
+  return n;
+}
+
+/* number of greedy steps for a source of `len` tokens: ceil(1.2*len)+2 in integers */
+int32_t ora_n_steps(int32_t len) { return (6 * len + 4) / 5 + 2; }
+
+/* ---- blob parsing ---- */
+static const float *take(const float **p, int64_t n) { const float *r = *p; *p += n; return r; }
+static void take_ln(const float **p, int64_t d, ln_t *l) { l->g = take(p, d); l->b = take(p, d); }
+static void take_attn(const float **p, int64_t d, int64_t rk, attn_t *a) {
+  a->Wq = take(p, d * d); a->bq = take(p, d);
+  a->Wk = take(p, d * d); a->bk = take(p, d);
+  a->Wv = take(p, d * d); a->bv = take(p, d);
+  a->Wo = take(p, d * d); a->bo = take(p, d);
+  a->rk = rk ? take(p, rk) : NULL;
+}
+static void take_ffn(const float **p, int64_t d, int64_t F, ffn_t *f) {
+  f->W1 = take(p, d * F); f->b1 = take(p, F); f->W2 = take(p, F * d); f->b2 = take(p, d);
+}
+
+ora_model *ora_load(const ora_config *c, const uint16_t *blob, int64_t n_halfs) {
+  if (!c || !blob) return NULL;
+  if (c->d_model <= 0 || c->n_heads <= 0 || c->d_model % c->n_heads || c->vocab <= 0 ||
+      c->n_enc < 0 || c->n_dec < 1 || c->d_ffn < 0 || c->rpr_clip < 0) return NULL;
+  if (n_halfs != ora_param_count(c)) return NULL;
+  ora_model *m = (ora_model *)calloc(1, sizeof *m);
+  m->c = *c;
+  m->w = (float *)malloc(sizeof(float) * (size_t)n_halfs);
+  for (int64_t i = 0; i < n_halfs; i++) m->w[i] = ora_half_to_float(blob[i]);
+  int64_t d = c->d_model, V = c->vocab, F = c->d_ffn;
+  int64_t rk = c->rpr_clip > 0 ? (2 * c->rpr_clip + 1) * (d / c->n_heads) : 0;
+  const float *p = m->w;
+  m->E = take(&p, V * d);
+  m->Wout = c->tie_output ? m->E : take(&p, V * d);
+  m->enc = (enc_layer *)calloc((size_t)(c->n_enc > 0 ? c->n_enc : 1), sizeof(enc_layer));
+  m->dec = (dec_layer *)calloc((size_t)c->n_dec, sizeof(dec_layer));
+  for (int l = 0; l < c->n_enc; l++) {
+    take_ln(&p, d, &m->enc[l].ln1);
+    take_attn(&p, d, rk, &m->enc[l].self);
+    if (F > 0) { take_ln(&p, d, &m->enc[l].ln2); take_ffn(&p, d, F, &m->enc[l].ffn); }
+  }
+  take_ln(&p, d, &m->enc_final);
+  for (int l = 0; l < c->n_dec; l++) {
+    take_ln(&p, d, &m->dec[l].ln1);
+    take_attn(&p, d, rk, &m->dec[l].self);
+    take_ln(&p, d, &m->dec[l].ln2);
+    take_attn(&p, d, 0, &m->dec[l].cross);
+    if (F > 0) { take_ln(&p, d, &m->dec[l].ln3); take_ffn(&p, d, F, &m->dec[l].ffn); }
+  }
+  take_ln(&p, d, &m->dec_final);
+  if (p - m->w != n_halfs) { free(m->enc); free(m->dec); free(m->w); free(m); return NULL; }
+  return m;
+}
+
+void ora_free(ora_model *m) {
+  if (!m) return;
+  free(m->enc); free(m->dec); free(m->w); free(m);
+}
+
+/* ---- primitives (exported so that tests can pin each against a library routine) ---- */
+
+/* sinusoidal position row: out[2k] = sin(pos / 10000^(2k/d)), out[2k+1] = cos(same) */
+void ora_pe(int32_t pos, int32_t d, double *out) {
+  for (int k = 0; 2 * k < d; k++) {
+    double ang = (double)pos / pow(10000.0, (2.0 * k) / (double)d);
+    out[2 * k] = sin(ang);
+    if (2 * k + 1 < d) out[2 * k + 1] = cos(ang);
+  }
+}
+
+/* y = g * (x - mean) / sqrt(biased_var + eps) + b */
+void ora_layer_norm(const double *x, const float *g, const float *b, int32_t d, double eps, double *y) {
+  double mean = 0.0, var = 0.0;
+  for (int i = 0; i < d; i++) mean += x[i];
+  mean /= d;
+  for (int i = 0; i < d; i++) var += (x[i] - mean) * (x[i] - mean);
+  var /= d;
+  double r = 1.0 / sqrt(var + eps);
+  for (int i = 0; i < d; i++) y[i] = (double)g[i] * ((x[i] - mean) * r) + (double)b[i];
+}
+
+/* y[n] = b[n] + sum_k x[k] W[k][n],  W stored [n_in][n_out] */
+void ora_linear(const double *x, const float *W, const float *b, int32_t n_in, int32_t n_out, double *y) {
+  for (int n = 0; n < n_out; n++) y[n] = b ? (double)b[n] : 0.0;
+  for (int k = 0; k < n_in; k++) {
+    const float *row = W + (int64_t)k * n_out;
+    double xk = x[k];
+    for (int n = 0; n < n_out; n++) y[n] += xk * (double)row[n];
+  }
+}
+
+/* in-place softmax over s[0..n); entries equal to -INFINITY get probability exactly 0 */
+void ora_softmax(double *s, int32_t n) {
+  double mx = -INFINITY, sum = 0.0;
+  for (int j = 0; j < n; j++) if (s[j] > mx) mx = s[j];
+  for (int j = 0; j < n; j++) { s[j] = (s[j] == -INFINITY) ? 0.0 : exp(s[j] - mx); sum += s[j]; }
+  for (int j = 0; j < n; j++) s[j] /= sum;
+}
+
+/*
+ * One query against n_keys keys, all heads.  q is already scaled by 1/sqrt(d_h).
+ * Key j sits at position j; the query sits at position qpos.  With relative position
+ * keys (rk != NULL, clip c): score_j += q_h . rk[clamp(j - qpos, -c, c) + c].
+ * K, V: [n_keys][d]; out c: [d] (heads concatenated).  probs (optional): [heads][n_keys].
+ */
+void ora_attend(const double *q, const double *K, const double *V, int32_t n_keys, int32_t d,
+                int32_t heads, const float *rk, int32_t clip, int32_t qpos, double *c, double *probs) {
+  int dh = d / heads;
+  double *s = (double *)malloc(sizeof(double) * (size_t)n_keys);
+  for (int h = 0; h < heads; h++) {
+    const double *qh = q + h * dh;
+    for (int j = 0; j < n_keys; j++) {
+      const double *kj = K + (int64_t)j * d + h * dh;
+      double acc = 0.0;
+      for (int e = 0; e < dh; e++) acc += qh[e] * kj[e];
+      if (rk) {
+        int off = j - qpos;
+        if (off < -clip) off = -clip;
+        if (off > clip) off = clip;
+        const float *r = rk + (int64_t)(off + clip) * dh;
+        for (int e = 0; e < dh; e++) acc += qh[e] * (double)r[e];
+      }
+      s[j] = acc;
+    }
+    ora_softmax(s, n_keys);
+    if (probs) memcpy(probs + (int64_t)h * n_keys, s, sizeof(double) * (size_t)n_keys);
+    for (int e = 0; e < dh; e++) c[h * dh + e] = 0.0;
+    for (int j = 0; j < n_keys; j++) {
+      const double *vj = V + (int64_t)j * d + h * dh;
+      for (int e = 0; e < dh; e++) c[h * dh + e] += s[j] * vj[e];
+    }
+  }
+  free(s);
+}
+
+/* ---- model pieces ---- */
+
+static void embed(const ora_model *m, int32_t id, int32_t pos, double *x) {
+  int d = m->c.d_model;
+  double sc = sqrt((double)d);
+  ora_pe(pos, d, x);
+  for (int i = 0; i < d; i++) x[i] += sc * (double)m->E[(int64_t)id * d + i];
+}
+
+/* x += relu(LN(x) W1 + b1) W2 + b2 */
+static void ffn_block(const ora_model *m, const ln_t *ln, const ffn_t *f, double *x) {
+  int d = m->c.d_model, F = m->c.d_ffn;
+  double *a = (double *)malloc(sizeof(double) * (size_t)(2 * d + F)), *u = a + d, *o = u + F;
+  ora_layer_norm(x, ln->g, ln->b, d, m->c.ln_eps, a);
+  ora_linear(a, f->W1, f->b1, d, F, u);
+  for (int i = 0; i < F; i++) if (u[i] < 0.0) u[i] = 0.0;
+  ora_linear(u, f->W2, f->b2, F, d, o);
+  for (int i = 0; i < d; i++) x[i] += o[i];
+  free(a);
+}
+
+/* encoder over one sentence; x: [len][d] in/out scratch, enc: [len][d] result */
+static int encode(const ora_model *m, const int32_t *src, int32_t len, double *enc) {
+  const ora_config *c = &m->c;
+  int d = c->d_model, H = c->n_heads;
+  double qs = 1.0 / sqrt((double)(d / H));
+  for (int i = 0; i < len; i++) if (src[i] < 0 || src[i] >= c->vocab) return -1;
+  size_t n = (size_t)len * d;
+  double *x = (double *)malloc(sizeof(double) * n * 5);
+  double *q = x + n, *k = q + n, *v = k + n, *a = v + n;
+  double *ctx = (double *)malloc(sizeof(double) * 2 * (size_t)d), *o = ctx + d;
+  for (int i = 0; i < len; i++) embed(m, src[i], i, x + (size_t)i * d);
+  for (int l = 0; l < c->n_enc; l++) {
+    const enc_layer *L = &m->enc[l];
+    for (int i = 0; i < len; i++) {
+      double *ai = a + (size_t)i * d;
+      ora_layer_norm(x + (size_t)i * d, L->ln1.g, L->ln1.b, d, c->ln_eps, ai);
+      ora_linear(ai, L->self.Wq, L->self.bq, d, d, q + (size_t)i * d);
+      ora_linear(ai, L->self.Wk, L->self.bk, d, d, k + (size_t)i * d);
+      ora_linear(ai, L->self.Wv, L->self.bv, d, d, v + (size_t)i * d);
+      for (int e = 0; e < d; e++) q[(size_t)i * d + e] *= qs;
+    }
+    for (int i = 0; i < len; i++) {
+      ora_attend(q + (size_t)i * d, k, v, len, d, H, L->self.rk, c->rpr_clip, i, ctx, NULL);
+      ora_linear(ctx, L->self.Wo, L->self.bo, d, d, o);
+      for (int e = 0; e < d; e++) x[(size_t)i * d + e] += o[e];
+    }
+    if (c->d_ffn > 0)
+      for (int i = 0; i < len; i++) ffn_block(m, &L->ln2, &L->ffn, x + (size_t)i * d);
+  }
+  for (int i = 0; i < len; i++)
+    ora_layer_norm(x + (size_t)i * d, m->enc_final.g, m->enc_final.b, d, c->ln_eps, enc + (size_t)i * d);
+  free(ctx); free(x);
+  return 0;
+}
+
+/* decoder state for one sentence: cross keys/values per layer, growing self caches */
+typedef struct {
+  int32_t len, cap;
+  double *ck, *cv;  /* [n_dec][len][d] */
+  double *sk, *sv;  /* [n_dec][cap][d] */
+} dec_state;
+
+static dec_state *dec_begin(const ora_model *m, const double *enc, int32_t len, int32_t cap) {
+  int d = m->c.d_model, Ld = m->c.n_dec;
+  dec_state *s = (dec_state *)calloc(1, sizeof *s);
+  s->len = len; s->cap = cap;
+  s->ck = (double *)malloc(sizeof(double) * 2 * (size_t)Ld * len * d);
+  s->cv = s->ck + (size_t)Ld * len * d;
+  s->sk = (double *)malloc(sizeof(double) * 2 * (size_t)Ld * cap * d);
+  s->sv = s->sk + (size_t)Ld * cap * d;
+  for (int l = 0; l < Ld; l++)
+    for (int j = 0; j < len; j++) {
+      const attn_t *A = &m->dec[l].cross;
+      ora_linear(enc + (size_t)j * d, A->Wk, A->bk, d, d, s->ck + ((size_t)l * len + j) * d);
+      ora_linear(enc + (size_t)j * d, A->Wv, A->bv, d, d, s->cv + ((size_t)l * len + j) * d);
+    }
+  return s;
+}
+static void dec_end(dec_state *s) { free(s->ck); free(s->sk); free(s); }
+
+/* one incremental decoder step at position t with previous token y_prev -> logits[V] */
+static void dec_step(const ora_model *m, dec_state *s, int32_t y_prev, int32_t t, double *logits) {
+  const ora_config *c = &m->c;
+  int d = c->d_model, H = c->n_heads, V = c->vocab;
+  double qs = 1.0 / sqrt((double)(d / H));
+  double *z = (double *)malloc(sizeof(double) * 5 * (size_t)d);
+  double *a = z + d, *q = a + d, *ctx = q + d, *o = ctx + d;
+  embed(m, y_prev, t, z);
+  for (int l = 0; l < c->n_dec; l++) {
+    const dec_layer *L = &m->dec[l];
+    double *sk = s->sk + (size_t)l * s->cap * d, *sv = s->sv + (size_t)l * s->cap * d;
+    /* causal self-attention over positions 0..t; earlier keys/values are the cached ones */
+    ora_layer_norm(z, L->ln1.g, L->ln1.b, d, c->ln_eps, a);
+    ora_linear(a, L->self.Wq, L->self.bq, d, d, q);
+    ora_linear(a, L->self.Wk, L->self.bk, d, d, sk + (size_t)t * d);
+    ora_linear(a, L->self.Wv, L->self.bv, d, d, sv + (size_t)t * d);
+    for (int e = 0; e < d; e++) q[e] *= qs;
+    ora_attend(q, sk, sv, t + 1, d, H, L->self.rk, c->rpr_clip, t, ctx, NULL);
+    ora_linear(ctx, L->self.Wo, L->self.bo, d, d, o);
+    for (int e = 0; e < d; e++) z[e] += o[e];
+    /* cross-attention over the encoder output (no relative positions) */
+    ora_layer_norm(z, L->ln2.g, L->ln2.b, d, c->ln_eps, a);
+    ora_linear(a, L->cross.Wq, L->cross.bq, d, d, q);
+    for (int e = 0; e < d; e++) q[e] *= qs;
+    ora_attend(q, s->ck + (size_t)l * s->len * d, s->cv + (size_t)l * s->len * d, s->len, d, H,
+               NULL, 0, 0, ctx, NULL);
+    ora_linear(ctx, L->cross.Wo, L->cross.bo, d, d, o);
+    for (int e = 0; e < d; e++) z[e] += o[e];
+    if (c->d_ffn > 0) ffn_block(m, &L->ln3, &L->ffn, z);
+  }
+  ora_layer_norm(z, m->dec_final.g, m->dec_final.b, d, c->ln_eps, a);
+  /* output layer: plain logits, no bias, no log-softmax */
+  for (int v = 0; v < V; v++) {
+    const float *w = m->Wout + (int64_t)v * d;
+    double acc = 0.0;
+    for (int e = 0; e < d; e++) acc += a[e] * (double)w[e];
+    logits[v] = acc;
+  }
+  free(z);
+}
+
+/* ---- public calls ---- */
+
+/* enc_out: [len][d] fp64.  Returns 0, or -1 for an id outside [0,V) / bad length. */
+int ora_encode(const ora_model *m, const int32_t *src, int32_t len, double *enc_out) {
+  if (!m || len < 1 || len > m->c.max_len) return -1;
+  return encode(m, src, len, enc_out);
+}
+
+/*
+ * Greedy decode for exactly n_steps steps starting from BOS (EOS is an ordinary token).
+ * out: [n_steps]; margin (optional): [n_steps] top-1 minus top-2 logit at each step.
+ */
+int ora_greedy(const ora_model *m, const int32_t *src, int32_t len, int32_t n_steps, int32_t *out,
+               double *margin) {
+  if (!m || len < 1 || len > m->c.max_len || n_steps < 0 || n_steps > m->c.max_len) return -1;
+  int d = m->c.d_model, V = m->c.vocab;
+  double *enc = (double *)malloc(sizeof(double) * (size_t)len * d);
+  if (encode(m, src, len, enc)) { free(enc); return -1; }
+  dec_state *s = dec_begin(m, enc, len, n_steps > 0 ? n_steps : 1);
+  double *logits = (double *)malloc(sizeof(double) * (size_t)V);
+  int32_t y = m->c.bos_id;
+  int rc = 0;
+  for (int t = 0; t < n_steps; t++) {
+    dec_step(m, s, y, t, logits);
+    int best = 0;
+    double second = -INFINITY;
+    if (logits[0] != logits[0]) rc = -2; /* NaN must never appear on valid input */
+    for (int v = 1; v < V; v++) {
+      if (logits[v] != logits[v]) rc = -2;
+      if (logits[v] > logits[best]) { second = logits[best]; best = v; }
+      else if (logits[v] > second) second = logits[v];
+    }
+    out[t] = y = best;
+    if (margin) margin[t] = logits[best] - second;
+  }
+  free(logits); dec_end(s); free(enc);
+  return rc;
+}
+
+/* logits[t] for t < T when the decoder is fed tgt_in[0..T) (tgt_in[0] is normally BOS) */
+int ora_teacher_forced(const ora_model *m, const int32_t *src, int32_t len, const int32_t *tgt_in,
+                       int32_t T, double *logits) {
+  if (!m || len < 1 || len > m->c.max_len || T < 1 || T > m->c.max_len) return -1;
+  for (int t = 0; t < T; t++) if (tgt_in[t] < 0 || tgt_in[t] >= m->c.vocab) return -1;
+  int d = m->c.d_model, V = m->c.vocab;
+  double *enc = (double *)malloc(sizeof(double) * (size_t)len * d);
+  if (encode(m, src, len, enc)) { free(enc); return -1; }
+  dec_state *s = dec_begin(m, enc, len, T);
+  for (int t = 0; t < T; t++) dec_step(m, s, tgt_in[t], t, logits + (size_t)t * V);
+  dec_end(s); free(enc);
+  return 0;
+}
+
+/*
+ * Translate N sentences (tokens concatenated, offsets[N+1]); sentence i gets
+ * ora_n_steps(len_i) output tokens at out[out_offsets[i]..out_offsets[i+1]).
+ * out_offsets is written here.  Sentences of length 0 produce nothing.  Parallel over
+ * sentences only.  Returns the number of threads used, or a negative error.
+ */
+int ora_translate(const ora_model *m, const int32_t *tokens, const int64_t *offsets, int64_t N,
+                  int32_t *out, int64_t *out_offsets, int32_t n_threads) {
+  if (!m) return -1;
+  out_offsets[0] = 0;
+  for (int64_t i = 0; i < N; i++) {
+    int64_t len = offsets[i + 1] - offsets[i];
+    if (len < 0 || len > m->c.max_len) return -1;
+    out_offsets[i + 1] = out_offsets[i] + (len > 0 ? ora_n_steps((int32_t)len) : 0);
+  }
+  int used = 1, err = 0;
+#ifdef _OPENMP
+  if (n_threads > 0) omp_set_num_threads(n_threads);
+  used = omp_get_max_threads();
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t i = 0; i < N; i++) {
+    int32_t len = (int32_t)(offsets[i + 1] - offsets[i]);
+    if (len == 0) continue;
+    if (ora_greedy(m, tokens + offsets[i], len, ora_n_steps(len), out + out_offsets[i], NULL)) {
+#pragma omp atomic write
+      err = 1;
+    }
+  }
+  return err ? -2 : used;
+}

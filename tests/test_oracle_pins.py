@@ -1,0 +1,294 @@
+"""Pins for the CPU oracle: each part is checked against something other than itself -
+closed forms, library routines used as independent arithmetic, special cases with a
+textbook answer, brute force, and the paper's printed parameter counts."""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import nt_synth
+from oracle import nt_oracle_np as onp
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def tiny(**kw):
+    cfg = nt_synth.model_config("C0", d_model=32, vocab=61, n_enc=2, max_len=64)
+    cfg.update(kw)
+    return cfg
+
+
+# ---------------------------------------------------------------- primitives
+def test_half_to_float_all_patterns(oracle):
+    bits = np.arange(65536, dtype=np.uint16)
+    want = bits.view(np.float16).astype(np.float32)
+    got = np.array([oracle.lib().ora_half_to_float(int(b)) for b in bits], dtype=np.float32)
+    ok = np.isnan(want) | (want.view(np.uint32) == got.view(np.uint32))
+    assert ok.all()
+    assert np.isnan(got[np.isnan(want)]).all()
+
+
+def test_pe_golden_and_closed_form(oracle):
+    for line in open(os.path.join(GOLD, "sinusoid.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        pos, dim, d, val = line.split()
+        assert abs(oracle.pe(int(pos), int(d))[int(dim)] - float(val)) < 1e-15
+    d = 512
+    assert np.array_equal(oracle.pe(0, d), np.tile([0.0, 1.0], d // 2))
+    for p in (1, 7, 241):
+        row = oracle.pe(p, d)
+        assert abs(row[d - 1] - math.cos(p * 10000.0 ** (-(d - 2) / d))) < 1e-12
+        assert abs(row[0] - math.sin(p)) < 1e-12
+        # sin^2 + cos^2 = 1 for every frequency pair
+        assert np.allclose(row[0::2] ** 2 + row[1::2] ** 2, 1.0, atol=1e-12)
+        assert np.allclose(row, onp.positions(p + 1, d)[p], atol=1e-12)
+
+
+def test_layer_norm_invariants_and_library(oracle):
+    rng = np.random.default_rng(0)
+    for d in (32, 256, 512):
+        x = rng.normal(3.0, 2.5, d)
+        one, zero = np.ones(d, np.float32), np.zeros(d, np.float32)
+        y = oracle.layer_norm(x, one, zero, 1e-5)
+        assert abs(y.mean()) < 1e-12
+        assert abs(y.var() - 1.0) < 1e-5          # biased variance; eps shifts it by ~eps/var
+        g = rng.normal(1, 0.1, d).astype(np.float32)
+        b = rng.normal(0, 0.1, d).astype(np.float32)
+        want = torch.nn.functional.layer_norm(torch.from_numpy(x), (d,), torch.from_numpy(g).double(),
+                                              torch.from_numpy(b).double(), 1e-5).numpy()
+        assert np.allclose(oracle.layer_norm(x, g, b, 1e-5), want, atol=1e-12)
+
+
+def test_softmax_sums_to_one_masked_zero_and_library(oracle):
+    rng = np.random.default_rng(1)
+    s = rng.normal(0, 30.0, 77)                     # large scores: must not overflow
+    p = oracle.softmax(s)
+    assert abs(p.sum() - 1.0) < 1e-12 and (p >= 0).all()
+    assert np.allclose(p, torch.softmax(torch.from_numpy(s), 0).numpy(), atol=1e-14)
+    s[[3, 10, 76]] = -np.inf
+    p = oracle.softmax(s)
+    assert p[3] == 0.0 and p[10] == 0.0 and p[76] == 0.0
+    assert abs(p.sum() - 1.0) < 1e-12
+    # numpy path: masked positions exactly zero, rows sum to one
+    sc = rng.normal(0, 5, (2, 3, 9))
+    mask = rng.random((2, 3, 9)) < 0.6
+    mask[..., 0] = True
+    pm = onp.masked_softmax(sc, mask)
+    assert (pm[~mask] == 0).all() and np.allclose(pm.sum(-1), 1.0, atol=1e-12)
+
+
+def test_linear_orientation(oracle):
+    rng = np.random.default_rng(2)
+    W = rng.normal(size=(5, 7)).astype(np.float32)
+    b = rng.normal(size=7).astype(np.float32)
+    x = rng.normal(size=5)
+    assert np.allclose(oracle.linear(x, W, b), x @ W.astype(np.float64) + b, atol=1e-13)
+    assert np.allclose(oracle.linear(x, W, None), x @ W.astype(np.float64), atol=1e-13)
+
+
+@pytest.mark.parametrize("heads", [1, 4])
+def test_attend_matches_sdpa(oracle, heads):
+    rng = np.random.default_rng(3)
+    n, d = 11, 32
+    dh = d // heads
+    q, K, V = rng.normal(size=d), rng.normal(size=(n, d)), rng.normal(size=(n, d))
+    c, probs = oracle.attend(q, K, V, heads=heads)
+    tq = torch.from_numpy(q).reshape(1, heads, 1, dh)
+    tk = torch.from_numpy(K).reshape(1, n, heads, dh).transpose(1, 2)
+    tv = torch.from_numpy(V).reshape(1, n, heads, dh).transpose(1, 2)
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, scale=1.0)
+    assert np.allclose(c, want.transpose(1, 2).reshape(d).numpy(), atol=1e-12)
+    assert np.allclose(probs.sum(-1), 1.0, atol=1e-12)
+
+
+def test_attend_relative_keys_brute_force(oracle):
+    """score_j = q . (k_j + rk[clip(j - i)])  (relative position keys, Sec. 2.1)."""
+    rng = np.random.default_rng(4)
+    n, d, heads, clip = 25, 16, 2, 3
+    dh = d // heads
+    q, K, V = rng.normal(size=d), rng.normal(size=(n, d)), rng.normal(size=(n, d))
+    rk = rng.normal(size=(2 * clip + 1, dh)).astype(np.float32)
+    for qpos in (0, 4, 12, 24):
+        c, probs = oracle.attend(q, K, V, heads=heads, rk=rk, clip=clip, qpos=qpos)
+        want = np.zeros(d)
+        for h in range(heads):
+            sc = []
+            for j in range(n):
+                rel = max(-clip, min(clip, j - qpos))
+                key = K[j, h * dh:(h + 1) * dh] + rk[rel + clip].astype(np.float64)
+                sc.append(float(q[h * dh:(h + 1) * dh] @ key))
+            e = np.exp(np.array(sc) - max(sc))
+            p = e / e.sum()
+            assert np.allclose(probs[h], p, atol=1e-12)
+            want[h * dh:(h + 1) * dh] = p @ V[:, h * dh:(h + 1) * dh]
+        assert np.allclose(c, want, atol=1e-12)
+    # keys farther than the clip distance share one relative embedding: shifting the query
+    # far to the left of every key makes the relative term constant over keys -> no effect
+    c_far, _ = oracle.attend(q, K, V, heads=heads, rk=rk, clip=clip, qpos=-100)
+    c_none, _ = oracle.attend(q, K, V, heads=heads)
+    assert np.allclose(c_far, c_none, atol=1e-12)
+
+
+# ---------------------------------------------------------------- special cases of the network
+def test_len1_layer_is_affine_chain(oracle):
+    """One position -> attention weight 1 -> layer = x + (LN(x) Wv + bv) Wo + bo."""
+    cfg = tiny(n_enc=1)
+    blob = nt_synth.make_weights(cfg, seed=5, random_affine=True)
+    W = onp.Weights(cfg, blob)
+    d = cfg["d_model"]
+    tok = 17
+    x = math.sqrt(d) * W["E"][tok] + np.tile([0.0, 1.0], d // 2)
+    ln = torch.nn.functional.layer_norm
+    a = ln(torch.from_numpy(x), (d,), torch.from_numpy(W["enc0.ln1.g"]), torch.from_numpy(W["enc0.ln1.b"]), 1e-5).numpy()
+    x1 = x + (a @ W["enc0.self.Wv"] + W["enc0.self.bv"]) @ W["enc0.self.Wo"] + W["enc0.self.bo"]
+    want = ln(torch.from_numpy(x1), (d,), torch.from_numpy(W["enc_final.g"]), torch.from_numpy(W["enc_final.b"]), 1e-5).numpy()
+    m = oracle.Model(cfg, blob)
+    assert np.allclose(m.encode([tok])[0], want, atol=1e-11)
+
+
+def test_zero_query_gives_uniform_attention(oracle):
+    """Wq = 0, bq = 0 -> all scores 0 -> context = mean of the values."""
+    cfg = tiny(n_enc=1)
+    blob = nt_synth.make_weights(cfg, seed=6)
+    nt_synth.blob_view(cfg, blob, "enc0.self.Wq")[:] = 0
+    nt_synth.blob_view(cfg, blob, "enc0.self.bq")[:] = 0
+    W = onp.Weights(cfg, blob)
+    d = cfg["d_model"]
+    src = np.array([5, 9, 33, 60, 12, 7])
+    x = math.sqrt(d) * W["E"][src] + onp.positions(len(src), d)
+    a = torch.nn.functional.layer_norm(torch.from_numpy(x), (d,)).numpy()
+    v = a @ W["enc0.self.Wv"] + W["enc0.self.bv"]
+    x1 = x + v.mean(0, keepdims=True) @ W["enc0.self.Wo"] + W["enc0.self.bo"]
+    want = torch.nn.functional.layer_norm(torch.from_numpy(x1), (d,)).numpy()
+    m = oracle.Model(cfg, blob)
+    assert np.allclose(m.encode(src), want, atol=1e-11)
+
+
+CASES = [
+    dict(),                                                          # the student: 1 head, no FFN
+    dict(n_heads=4, d_ffn=48),                                       # ablation shape
+    dict(n_heads=4, d_ffn=48, n_dec=2, rpr_clip=3),                  # teacher shape
+    dict(n_heads=2, rpr_clip=2, tie_output=1),
+]
+
+
+@pytest.mark.parametrize("kw", CASES)
+def test_incremental_equals_full_recompute(oracle, kw):
+    """C oracle (per sentence, cached, incremental) == numpy path (padded batch, masks, full)."""
+    cfg = tiny(**kw)
+    blob = nt_synth.make_weights(cfg, seed=7, random_affine=True)
+    m = oracle.Model(cfg, blob)
+    rng = np.random.default_rng(8)
+    src = [rng.integers(4, cfg["vocab"], size=n) for n in (1, 9, 4, 13)]
+    outs = [m.greedy(s)[0] for s in src]
+    tgt_in = [np.concatenate([[cfg["bos_id"]], o[:-1]]) for o in outs]
+    enc_np, lens = onp.encode(cfg, blob, src)
+    full = onp.teacher_forced_logits(cfg, blob, src, tgt_in)
+    for i, s in enumerate(src):
+        assert np.allclose(m.encode(s), enc_np[i, : len(s)], atol=1e-10)
+        inc = m.teacher_forced(s, tgt_in[i])
+        assert np.allclose(inc, full[i], atol=1e-9)
+        # greedy picks the argmax of those logits, lowest id first
+        assert np.array_equal(np.argmax(inc, -1), outs[i])
+
+
+def test_padding_and_batch_mates_do_not_matter(oracle):
+    cfg = tiny(n_heads=2, rpr_clip=2)
+    blob = nt_synth.make_weights(cfg, seed=9)
+    rng = np.random.default_rng(10)
+    a, b, c = (rng.integers(4, cfg["vocab"], size=n) for n in (6, 15, 3))
+    tgt = [np.array([1, 8, 9, 10]), np.array([1, 5]), np.array([1, 7, 7])]
+    base = onp.teacher_forced_logits(cfg, blob, [a, b, c], tgt)
+    padded = onp.teacher_forced_logits(cfg, blob, [a, b, c], tgt, extra_pad=5)
+    alone = onp.teacher_forced_logits(cfg, blob, [a], tgt[:1])
+    assert np.allclose(base[0], padded[0], atol=1e-12) and np.allclose(base[2], padded[2], atol=1e-12)
+    assert np.allclose(base[0], alone[0], atol=1e-12)
+
+
+def test_argmax_without_log_softmax(oracle):
+    """Greedy needs no log-softmax on the output layer (Sec. 3.3): same argmax."""
+    cfg = tiny()
+    blob = nt_synth.make_weights(cfg, seed=11)
+    m = oracle.Model(cfg, blob)
+    src = np.array([4, 5, 6, 7, 8])
+    out, margin = m.greedy(src)
+    logits = m.teacher_forced(src, np.concatenate([[1], out[:-1]]))
+    lsm = torch.log_softmax(torch.from_numpy(logits), -1).numpy()
+    assert np.array_equal(lsm.argmax(-1), out)
+    top2 = np.sort(logits, -1)[:, -2:]
+    assert np.allclose(margin, top2[:, 1] - top2[:, 0], atol=1e-12) and (margin >= 0).all()
+
+
+def test_tied_embedding_collapse(oracle):
+    """With tied output weights, sqrt(d) embedding scale and random weights the logit of the
+    previous token dominates (~ sqrt(d) |E_y|^2 / sigma_z against N(0,1) for the others), so
+    greedy decoding re-emits BOS at every step: an end-to-end analytic prediction that runs
+    embed -> every layer -> final LayerNorm -> projection -> argmax."""
+    cfg = nt_synth.model_config("C0", tie_output=1)
+    blob = nt_synth.make_weights(cfg, seed=0)
+    m = oracle.Model(cfg, blob)
+    tokens, offsets = nt_synth.workload("C0")
+    for i in range(3):
+        out, margin = m.greedy(tokens[offsets[i]:offsets[i + 1]])
+        assert (out == cfg["bos_id"]).all()
+        assert margin.min() > 1.0
+
+
+def test_translate_matches_per_sentence_and_threads(oracle):
+    cfg = tiny()
+    blob = nt_synth.make_weights(cfg, seed=12)
+    m = oracle.Model(cfg, blob)
+    rng = np.random.default_rng(13)
+    lens = [3, 0, 7, 1, 12]
+    toks = rng.integers(4, cfg["vocab"], size=sum(lens)).astype(np.int32)
+    offs = np.concatenate([[0], np.cumsum(lens)])
+    out, oo, used = m.translate(toks, offs, n_threads=3)
+    assert used == 3
+    for i, n in enumerate(lens):
+        seg = out[oo[i]:oo[i + 1]]
+        if n == 0:
+            assert seg.size == 0
+        else:
+            assert np.array_equal(seg, m.greedy(toks[offs[i]:offs[i + 1]])[0])
+
+
+def test_invalid_inputs_rejected(oracle):
+    cfg = tiny()
+    blob = nt_synth.make_weights(cfg, seed=12)
+    with pytest.raises(ValueError):
+        oracle.Model(cfg, blob[:-1])
+    m = oracle.Model(cfg, blob)
+    with pytest.raises(ValueError):
+        m.encode([cfg["vocab"]])
+    with pytest.raises(ValueError):
+        m.encode(np.full(cfg["max_len"] + 1, 5))
+
+
+# ---------------------------------------------------------------- closed forms
+def test_n_steps_is_ceil_1p2_len_plus_2(oracle):
+    for n in range(1, 201):
+        assert oracle.n_steps(n) == math.ceil(Fraction(12, 10) * n) + 2
+
+
+def test_param_count_matches_layout_and_paper_tables(oracle):
+    for name in ("C0", "C1", "C3", "C4"):
+        cfg = nt_synth.model_config(name)
+        assert oracle.param_count(cfg) == nt_synth.blob_numel(cfg)
+    # the paper's models: encoder keeps the vanilla FFN, Dim-FFN is the decoder's (Table 2 caption)
+    V = 32000
+    for line in open(os.path.join(GOLD, "param_counts.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, ne, nd, d, fe, fd, printed = line.split()
+        ne, nd, d, fe, fd, printed = int(ne), int(nd), int(d), int(fe), int(fd), float(printed)
+        base = nt_synth.model_config("C1", n_enc=ne, n_dec=nd, d_model=d, d_ffn=fe, tie_output=1, vocab=V,
+                                     n_heads=8)
+        n = oracle.param_count(base)
+        # replace the decoder's FFN (sized like the encoder's above) by one of width fd
+        dec_ffn = lambda F: (2 * d * F + F + d + 2 * d) if F else 0
+        n += nd * (dec_ffn(fd) - dec_ffn(fe))
+        assert abs(n / 1e6 - printed) / printed < 0.025, (name, n)
