@@ -1,0 +1,188 @@
+/*
+ * libnt - batched inference of the lightweight student Transformer on one AMD MI355X.
+ *
+ * C ABI.  The boundary is cut at token ids: sentences in, translations out, a whole input
+ * set translated as fast as possible (paper, abstract and Sec. 3.3 "Parallel Execution";
+ * tokenisation and BPE are outside).  Every step of the path runs in hand-written gfx950
+ * kernels; the library uses HIP only and never falls back to the CPU.
+ *
+ * Conventions
+ *   - every function returns NT_OK (0) or a negative nt_status; nothing throws, aborts or
+ *     prints.  nt_last_error() gives a thread-local message for the last failure.
+ *   - "d_" arguments are device pointers, "h_" arguments are host pointers.  The caller owns
+ *     every buffer it passes.  The library owns the weights, the activation arena and the
+ *     key/value caches; it allocates only inside nt_load_weights and frees only in nt_free.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).  nt_encode
+ *     and nt_decode_greedy only enqueue work; nt_translate_batch synchronises the stream
+ *     before it returns host results.
+ *   - one nt_model must not be used from two threads at once; nt_plan_batches is pure.
+ *   - ids: 0 = PAD, 1 = BOS, 2 = EOS, 3 = UNK by convention; only bos_id and pad_id are
+ *     used by the library.  The decoder may emit any id in [0, vocab).
+ */
+#ifndef NT_H
+#define NT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  NT_OK = 0,
+  NT_EINVAL = -1, /* null pointer, bad struct size, bad argument                         */
+  NT_ESHAPE = -2, /* configuration or batch shape the kernels do not support             */
+  NT_EBLOB = -3,  /* weight blob size does not match the configuration                   */
+  NT_ENOMEM = -4, /* device or host allocation failed / batch does not fit the arena     */
+  NT_EHIP = -5,   /* a HIP call or kernel launch failed                                  */
+  NT_ERANGE = -6, /* token id outside [0,vocab), length outside [0,max_len], bad offsets */
+  NT_ESTATE = -7  /* call order: decode without a preceding encode of the same batch     */
+} nt_status;
+
+typedef struct nt_model nt_model; /* opaque */
+
+/*
+ * Model and arena description.  Architecture fields follow the paper's student family
+ * (Sec. 2.2 "Fast Student Models", Table 2) and the vanilla / teacher shapes it is compared
+ * with (Sec. 2.1, Table 1, Table 3):
+ *   n_enc, n_dec   encoder / decoder layers (student: 6 / 1)
+ *   d_model        model width; must be a multiple of 64 and at most 1024
+ *   n_heads        attention heads in every attention (student: 1); head width
+ *                  d_model / n_heads must be 64, 128, 256 or 512
+ *   d_ffn          FFN width in every layer, 0 = the FFN sub-layers are removed (student);
+ *                  a multiple of 64 otherwise
+ *   vocab          shared source/target vocabulary
+ *   max_len        longest source sentence and longest target prefix (positions), <= 512
+ *   rpr_clip       clipping distance of the relative position keys in self-attention
+ *                  (Sec. 2.1: 8 for the teachers), 0 = none
+ *   tie_output     1: the output projection is the embedding matrix (Sec. 2.3); 0: the blob
+ *                  holds a separate W_out
+ *   ln_eps         LayerNorm epsilon (pre-LN blocks, biased variance)
+ *   max_batch_tokens, max_batch_rows
+ *                  largest padded batch (rows x longest row) and most rows per batch the
+ *                  arena must hold; the peak footprint is fixed at load time, in the spirit
+ *                  of the paper's memory optimisation (Sec. 3.3).  max_batch_rows = 0 means
+ *                  max_batch_tokens rows.
+ */
+typedef struct {
+  uint32_t struct_size; /* sizeof(nt_config), checked */
+  int32_t n_enc, n_dec, d_model, n_heads, d_ffn, vocab, max_len;
+  int32_t rpr_clip, tie_output, bos_id, pad_id;
+  float ln_eps;
+  int32_t max_batch_rows;
+  int64_t max_batch_tokens;
+} nt_config;
+
+/* Number of fp16 elements the weight blob of this configuration must hold (0 if invalid). */
+int64_t nt_param_count(const nt_config *cfg);
+
+/*
+ * Number of greedy steps run for a source of `len` tokens: ceil(1.2 * len) + 2, evaluated
+ * in integers (the benchmark's fixed-length decoding rule; EOS is an ordinary token).
+ */
+int32_t nt_n_steps(int32_t len);
+
+/*
+ * Load a model.  h_blob_fp16: host pointer to the flat little-endian fp16 blob, tensors in
+ * the documented order, every matrix as W[in][out].  The matrices are copied to the device
+ * and re-laid-out once into the K-contiguous form the MFMA kernels read (the paper hoists
+ * its transposes to the start of decoding, Sec. 3.3 "Graph Optimization"); the sinusoid
+ * table is built; the arena and caches are allocated.  Synchronises hip_stream.
+ * Errors: NT_EINVAL, NT_ESHAPE, NT_EBLOB (blob_bytes != 2 * nt_param_count), NT_ENOMEM, NT_EHIP.
+ */
+int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_bytes, void *hip_stream,
+                    nt_model **out);
+
+void nt_free(nt_model *m);
+
+/*
+ * Encoder over one padded batch (Sec. 2.2; Sec. 3.1 "FP16 Inference").
+ *   d_src [B, S] int32 row-major, row b holds d_len[b] ids then padding (any value);
+ *   d_len [B] int32, each in [1, S].
+ * Leaves, inside the model: the encoder output and the cross-attention keys/values of every
+ * decoder layer.  Pad positions never influence real ones.  Ids outside [0,vocab) and
+ * lengths outside [1,S] cannot be rejected without reading device memory: they are clamped
+ * in the kernels (id -> pad_id, len -> [1,S]) and a sticky device flag is raised that
+ * nt_check_device_flags reports.
+ * Errors: NT_EINVAL, NT_ESHAPE (S > max_len), NT_ENOMEM (B*S or B beyond the arena), NT_EHIP.
+ */
+int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B, int32_t S, void *hip_stream);
+
+/*
+ * Greedy decoding of the batch left by the last nt_encode (Sec. 3.3 "Greedy Search"; the
+ * output layer's log-softmax is dropped, Sec. 3.3 "Graph Optimization").  Runs exactly
+ * n_steps incremental steps from BOS with key/value caches; the next token of a row is the
+ * arg-max of its logits, lowest id on ties; it stays on the device and feeds the next step.
+ *   d_out [B, n_steps] int32, device.  Row b, step t.
+ *   h_row_steps: optional host array [B], non-increasing, each in [0, n_steps]: row b is only
+ *   advanced for its first h_row_steps[b] steps (rows sorted by length finish in order, so
+ *   the active rows are always a prefix); entries of d_out beyond that are set to pad_id.
+ *   NULL = every row runs n_steps steps.  Results of a row never depend on the other rows.
+ * Errors: NT_EINVAL, NT_ESTATE (B differs from the encoded batch), NT_ERANGE (n_steps >
+ * max_len, h_row_steps not non-increasing), NT_ENOMEM (B * n_steps beyond the self cache), NT_EHIP.
+ */
+int nt_decode_greedy(nt_model *m, int32_t B, int32_t n_steps, const int32_t *h_row_steps, int32_t *d_out,
+                     void *hip_stream);
+
+/*
+ * Translate N sentences end to end (dynamic batching: Sec. 3.1 "Dynamic Batching"; sorting by
+ * descending length and sbatch/wbatch caps: Sec. 3.3 "Graph Optimization", "Better Decoding
+ * Configurations").
+ *   h_tokens: all source ids concatenated; h_offsets [N+1]: sentence i is
+ *   h_tokens[h_offsets[i] .. h_offsets[i+1]).
+ *   token_budget: cap on rows x longest-row per batch (wbatch); max_rows: cap on rows per
+ *   batch (sbatch), 0 = none.  Both are also limited by the arena given at load time.
+ *   h_out: output ids, sentence i at h_out[h_out_offsets[i] .. h_out_offsets[i+1]) with
+ *   nt_n_steps(len_i) ids (0 for an empty sentence); h_out_offsets [N+1] is written by the
+ *   call; h_out must hold sum_i nt_n_steps(len_i) ids.
+ * N = 0 succeeds and writes only h_out_offsets[0] = 0.  The input is validated on the host
+ * before anything is launched: an id outside [0,vocab), a sentence longer than max_len or
+ * non-monotone offsets give NT_ERANGE and no output.
+ */
+int nt_translate_batch(nt_model *m, const int32_t *h_tokens, const int64_t *h_offsets, int64_t N,
+                       int64_t token_budget, int32_t max_rows, int32_t *h_out, int64_t *h_out_offsets,
+                       void *hip_stream);
+
+/*
+ * Host-only batch planner used by nt_translate_batch (same passages).  Stable sort by
+ * descending length (ties by index); batches are maximal prefixes of the sorted list with
+ * rows * longest <= budget and rows <= max_rows (0 = no cap); a sentence longer than the
+ * budget forms a batch of its own; empty sentences are placed last and belong to no batch.
+ *   order [N]: sentence indices in sorted order; batch_starts [N+1 entries available]:
+ *   batch k is order[batch_starts[k] .. batch_starts[k+1]); *n_batches is written.
+ * Errors: NT_EINVAL (null, budget < 1, negative length).
+ */
+int nt_plan_batches(const int32_t *h_lengths, int64_t N, int64_t budget, int32_t max_rows, int64_t *order,
+                    int64_t *batch_starts, int64_t *n_batches);
+
+/* ---- not on the hot path: needed to check parity -------------------------------------- */
+
+/* Copy the encoder output of the last nt_encode as fp32 [B, S, d_model] (pad rows included). */
+int nt_debug_encoder_out(nt_model *m, float *d_out, void *hip_stream);
+
+/*
+ * Teacher-forced decoder logits for the batch left by the last nt_encode: the decoder is fed
+ * d_tgt_in [B, T] (column 0 is normally BOS) instead of its own arg-max and the fp32 logits of
+ * every step are written to d_logits [B, T, vocab].  Same kernels as nt_decode_greedy except
+ * that the output projection stores its tile instead of reducing it.
+ */
+int nt_debug_teacher_forced_logits(nt_model *m, const int32_t *d_tgt_in, int32_t B, int32_t T, float *d_logits,
+                                   void *hip_stream);
+
+/*
+ * Read and clear the sticky device flags (synchronises the stream).  Returns NT_OK, or
+ * NT_ERANGE if a kernel has clamped an out-of-range id or length since the last call.
+ */
+int nt_check_device_flags(nt_model *m, void *hip_stream);
+
+/* Bytes of device memory held by the model (weights, arena, caches). */
+int64_t nt_device_bytes(const nt_model *m);
+
+/* Message for the last error on this thread (valid until the next failing call). */
+const char *nt_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NT_H */

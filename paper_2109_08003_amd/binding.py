@@ -1,0 +1,182 @@
+"""ctypes binding for libnt.so: argument marshalling only, same names as include/nt.h.
+
+Device buffers are torch tensors (torch is used for device memory and streams only).  There is
+no fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnt.so")
+
+EXPORTS = ["nt_param_count", "nt_n_steps", "nt_load_weights", "nt_free", "nt_encode", "nt_decode_greedy",
+           "nt_translate_batch", "nt_plan_batches", "nt_debug_encoder_out", "nt_debug_teacher_forced_logits",
+           "nt_check_device_flags", "nt_device_bytes", "nt_last_error"]
+
+
+class NtConfig(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32)] + [(k, C.c_int32) for k in (
+        "n_enc", "n_dec", "d_model", "n_heads", "d_ffn", "vocab", "max_len", "rpr_clip", "tie_output", "bos_id",
+        "pad_id")] + [("ln_eps", C.c_float), ("max_batch_rows", C.c_int32), ("max_batch_tokens", C.c_int64)]
+
+
+class NtError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libnt error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load libnt.so and declare the signatures; raises if the library is not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is not built: run python -m paper_2109_08003_amd.build")
+    L = C.CDLL(LIB_PATH)
+    p, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    cfgp = C.POINTER(NtConfig)
+    sig = {
+        "nt_param_count": (i64, [cfgp]),
+        "nt_n_steps": (i32, [i32]),
+        "nt_load_weights": (C.c_int, [cfgp, p, C.c_size_t, p, C.POINTER(p)]),
+        "nt_free": (None, [p]),
+        "nt_encode": (C.c_int, [p, p, p, i32, i32, p]),
+        "nt_decode_greedy": (C.c_int, [p, i32, i32, p, p, p]),
+        "nt_translate_batch": (C.c_int, [p, p, p, i64, i64, i32, p, p, p]),
+        "nt_plan_batches": (C.c_int, [p, i64, i64, i32, p, p, C.POINTER(i64)]),
+        "nt_debug_encoder_out": (C.c_int, [p, p, p]),
+        "nt_debug_teacher_forced_logits": (C.c_int, [p, p, i32, i32, p, p]),
+        "nt_check_device_flags": (C.c_int, [p, p]),
+        "nt_device_bytes": (i64, [p]),
+        "nt_last_error": (C.c_char_p, []),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = L
+    return L
+
+
+def lib() -> C.CDLL:
+    return load_library()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise NtError(rc, lib().nt_last_error().decode())
+
+
+def make_config(cfg: dict, max_batch_tokens: int, max_batch_rows: int = 0) -> NtConfig:
+    c = NtConfig()
+    c.struct_size = C.sizeof(NtConfig)
+    for k in ("n_enc", "n_dec", "d_model", "n_heads", "d_ffn", "vocab", "max_len", "rpr_clip", "tie_output", "bos_id",
+              "pad_id"):
+        setattr(c, k, int(cfg[k]))
+    c.ln_eps = float(cfg["ln_eps"])
+    c.max_batch_tokens = int(max_batch_tokens)
+    c.max_batch_rows = int(max_batch_rows)
+    return c
+
+
+def param_count(cfg: dict) -> int:
+    c = make_config(cfg, 1)
+    return int(lib().nt_param_count(C.byref(c)))
+
+
+def n_steps(length: int) -> int:
+    return int(lib().nt_n_steps(int(length)))
+
+
+def plan_batches(lengths, budget: int, max_rows: int = 0):
+    """Returns (order int64 [N], batch_starts int64 [n_batches+1])."""
+    lengths = np.ascontiguousarray(lengths, dtype=np.int32)
+    N = lengths.size
+    order = np.empty(max(N, 1), dtype=np.int64)
+    starts = np.empty(N + 1, dtype=np.int64)
+    nb = C.c_int64(0)
+    _check(lib().nt_plan_batches(lengths.ctypes.data_as(C.c_void_p), N, int(budget), int(max_rows),
+                                 order.ctypes.data_as(C.c_void_p), starts.ctypes.data_as(C.c_void_p), C.byref(nb)))
+    return order[:N], starts[: nb.value + 1]
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+class Model:
+    """Owns one nt_model.  Methods mirror the C entry points."""
+
+    def __init__(self, cfg: dict, blob: np.ndarray, max_batch_tokens: int, max_batch_rows: int = 0, stream=None):
+        assert blob.dtype == np.float16
+        blob = np.ascontiguousarray(blob)
+        self.cfg = dict(cfg)
+        c = make_config(cfg, max_batch_tokens, max_batch_rows)
+        h = C.c_void_p()
+        _check(lib().nt_load_weights(C.byref(c), blob.ctypes.data_as(C.c_void_p), blob.nbytes, _stream_ptr(stream),
+                                     C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().nt_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def device_bytes(self) -> int:
+        return int(lib().nt_device_bytes(self._h))
+
+    def encode(self, d_src, d_len, stream=None):
+        """d_src int32 cuda tensor [B,S], d_len int32 cuda tensor [B]."""
+        B, S = d_src.shape
+        assert d_src.is_cuda and d_len.is_cuda and d_src.is_contiguous() and d_len.is_contiguous()
+        _check(lib().nt_encode(self._h, d_src.data_ptr(), d_len.data_ptr(), B, S, _stream_ptr(stream)))
+
+    def decode_greedy(self, B: int, steps: int, d_out, row_steps=None, stream=None):
+        """d_out int32 cuda tensor [B, steps]; row_steps optional host int32 array [B]."""
+        assert d_out.is_cuda and d_out.is_contiguous() and d_out.numel() >= B * steps
+        rs = None
+        if row_steps is not None:
+            rs = np.ascontiguousarray(row_steps, dtype=np.int32)
+        _check(lib().nt_decode_greedy(self._h, B, steps, rs.ctypes.data_as(C.c_void_p) if rs is not None else None,
+                                      d_out.data_ptr(), _stream_ptr(stream)))
+
+    def debug_encoder_out(self, d_out, stream=None):
+        _check(lib().nt_debug_encoder_out(self._h, d_out.data_ptr(), _stream_ptr(stream)))
+
+    def debug_teacher_forced_logits(self, d_tgt_in, d_logits, stream=None):
+        B, T = d_tgt_in.shape
+        assert d_tgt_in.is_contiguous() and d_logits.is_contiguous()
+        _check(lib().nt_debug_teacher_forced_logits(self._h, d_tgt_in.data_ptr(), B, T, d_logits.data_ptr(),
+                                                    _stream_ptr(stream)))
+
+    def check_device_flags(self, stream=None):
+        _check(lib().nt_check_device_flags(self._h, _stream_ptr(stream)))
+
+    def translate_batch(self, tokens, offsets, token_budget: int, max_rows: int = 0, stream=None):
+        """Host arrays in, host arrays out: returns (out int32, out_offsets int64)."""
+        tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+        offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+        N = offsets.size - 1
+        total = sum(n_steps(int(l)) for l in np.diff(offsets) if l > 0) if N > 0 else 0
+        out = np.empty(max(total, 1), dtype=np.int32)
+        oo = np.empty(N + 1, dtype=np.int64)
+        _check(lib().nt_translate_batch(self._h, tokens.ctypes.data_as(C.c_void_p), offsets.ctypes.data_as(C.c_void_p),
+                                        N, int(token_budget), int(max_rows), out.ctypes.data_as(C.c_void_p),
+                                        oo.ctypes.data_as(C.c_void_p), _stream_ptr(stream)))
+        return out[:total], oo

@@ -1,0 +1,367 @@
+// Attention kernels for gfx950.
+//
+// enc_attention: padded-batch encoder self-attention, one workgroup per (32 queries, head,
+// sentence).  Scores Q K^T and the product P V run on v_mfma_f32_32x32x16_f16; the softmax is
+// fp32 in LDS (the paper converts to full precision around the softmax, Sec. 3.1 "FP16
+// Inference"; the 1/sqrt(d_k) scale was already applied to the query by the projection).
+// Keys beyond the sentence length get -inf before the row maximum, hence weight exactly 0.
+//
+// attn_decode: one query per (row, head) against a key/value cache - the incremental decoder's
+// self-attention (fp32 cache, t+1 keys) and cross-attention (fp16 cache, len keys).  Pure HBM
+// streaming: every key and value is read once, coalesced 16/32 bytes per lane, with an online
+// softmax in registers and a butterfly merge across key groups and waves.
+//
+// Relative position keys (Sec. 2.1, clip distance c): score_ij += q_i . rk[clamp(j-i,-c,c)+c].
+#include <math.h>
+
+#include "nt_kernels.h"
+
+namespace nt {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// ---------------------------------------------------------------------------------------
+// encoder attention
+// ---------------------------------------------------------------------------------------
+constexpr int QT = 32;        // queries per workgroup
+constexpr int MAX_CLIP = 16;  // relative-position clip distance supported
+
+static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+size_t enc_attention_lds_bytes(int S, int dh) {
+  const int SP = round_up(S, 32);
+  return (size_t)QT * (dh + 8) * 2 + (size_t)QT * (SP + 1) * 4 + (size_t)QT * (SP + 8) * 2 +
+         (size_t)QT * (2 * MAX_CLIP + 1) * 4;
+}
+
+template <int DH>
+__global__ __launch_bounds__(256) void enc_attention_kernel(const _Float16 *qkv, const int32_t *len, _Float16 *ctx,
+                                                            int S, int d, const float *rk, int clip) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int SP = (S + 31) / 32 * 32;
+  constexpr int QLD = DH + 8;
+  const int SLD = SP + 1, PLD = SP + 8;
+  _Float16 *sQ = (_Float16 *)smem;  // [QT][QLD]; reused for the V block in phase 3
+  float *sS = (float *)(smem + (size_t)QT * QLD * 2);
+  _Float16 *sP = (_Float16 *)((unsigned char *)sS + (size_t)QT * SLD * 4);
+  float *sR = (float *)((unsigned char *)sP + (size_t)QT * PLD * 2);  // [QT][2*MAX_CLIP+1] q . rk
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, g = lane >> 5;
+  const int b = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * QT;
+  const int L = len[b];  // already clamped to [1,S]
+  const long row0 = (long)b * S;
+  const long ld = 3L * d;
+  const int hoff = h * DH;
+
+  if (q0 >= L) {  // padding queries: defined output, no work
+    for (int i = tid; i < QT * (DH / 8); i += 256) {
+      int r = i / (DH / 8), c = i % (DH / 8);
+      if (q0 + r < S) *(uint4 *)(ctx + (row0 + q0 + r) * d + hoff + c * 8) = make_uint4(0, 0, 0, 0);
+    }
+    return;
+  }
+  const int nkb = (L + 31) / 32;
+
+  // stage the query tile (rows beyond S re-read the last row; they are never stored)
+  for (int i = tid; i < QT * (DH / 8); i += 256) {
+    int r = i / (DH / 8), c = i % (DH / 8);
+    int qr = min(q0 + r, S - 1);
+    *(uint4 *)(sQ + r * QLD + c * 8) = *(const uint4 *)(qkv + (row0 + qr) * ld + hoff + c * 8);
+  }
+  __syncthreads();
+
+  if (rk) {  // q . rk for the 2*clip+1 relative offsets
+    const int nrel = 2 * clip + 1;
+    for (int i = tid; i < QT * nrel; i += 256) {
+      int r = i / nrel, o = i % nrel;
+      float acc = 0.f;
+      for (int e = 0; e < DH; e++) acc += (float)sQ[r * QLD + e] * rk[o * DH + e];
+      sR[r * (2 * MAX_CLIP + 1) + o] = acc;
+    }
+    __syncthreads();
+  }
+
+  // phase 1: scores.  Each lane streams 64 bytes of its key row per 64-wide k chunk straight
+  // from global memory (every key element is used once per query tile, so LDS would add nothing);
+  // lane group g takes k in [c*64 + g*32, +32) and the query fragment uses the same assignment.
+  for (int kb = wave; kb < nkb; kb += 4) {
+    floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; v++) acc[v] = 0.f;
+    const int key = min(kb * 32 + li, S - 1);
+    const _Float16 *kp = qkv + (row0 + key) * ld + d + hoff + g * 32;
+#pragma unroll 2
+    for (int c = 0; c < DH / 64; c++) {
+      half8 kr[4];
+#pragma unroll
+      for (int u = 0; u < 4; u++) kr[u] = *(const half8 *)(kp + c * 64 + u * 8);
+#pragma unroll
+      for (int u = 0; u < 4; u++) {
+        half8 a = *(const half8 *)(sQ + li * QLD + c * 64 + g * 32 + u * 8);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, kr[u], acc, 0, 0, 0);
+      }
+    }
+    const int j = kb * 32 + li;
+#pragma unroll
+    for (int v = 0; v < 16; v++) {
+      const int i = (v >> 2) * 8 + g * 4 + (v & 3);
+      float s = acc[v];
+      if (rk) {
+        int rel = j - (q0 + i);
+        rel = max(-clip, min(clip, rel));
+        s += sR[i * (2 * MAX_CLIP + 1) + rel + clip];
+      }
+      sS[i * SLD + j] = (j < L) ? s : -INFINITY;
+    }
+  }
+  __syncthreads();
+
+  // phase 2: fp32 softmax, 8 threads per query row
+  {
+    const int i = tid >> 3, sub = tid & 7, nk = nkb * 32;
+    float mx = -INFINITY;
+    for (int j = sub; j < nk; j += 8) mx = fmaxf(mx, sS[i * SLD + j]);
+#pragma unroll
+    for (int m = 4; m >= 1; m >>= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+    float sum = 0.f;
+    for (int j = sub; j < nk; j += 8) {
+      float e = __expf(sS[i * SLD + j] - mx);
+      sS[i * SLD + j] = e;
+      sum += e;
+    }
+#pragma unroll
+    for (int m = 4; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, 64);
+    const float inv = 1.f / sum;
+    for (int j = sub; j < nk; j += 8) sP[i * PLD + j] = (_Float16)(sS[i * SLD + j] * inv);
+  }
+
+  // phase 3: context = P V.  The V block is staged in LDS in its natural [key][col] layout and
+  // the MFMA operand (8 keys of one column) is gathered with 16-bit LDS reads.
+  constexpr int NCB = (DH >= 128) ? DH / 128 : 1;  // 32-column blocks per wave
+  constexpr int ACTIVE = (DH / 32 < 4) ? DH / 32 : 4;
+  floatx16 o[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; cb++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) o[cb][v] = 0.f;
+  _Float16 *sV = sQ;
+  for (int kb = 0; kb < nkb; kb++) {
+    __syncthreads();  // sQ / previous V block no longer read; sP complete (first pass)
+    for (int i = tid; i < 32 * (DH / 8); i += 256) {
+      int r = i / (DH / 8), c = i % (DH / 8);
+      int key = min(kb * 32 + r, S - 1);
+      *(uint4 *)(sV + r * QLD + c * 8) = *(const uint4 *)(qkv + (row0 + key) * ld + 2 * d + hoff + c * 8);
+    }
+    __syncthreads();
+    if (wave < ACTIVE) {
+#pragma unroll
+      for (int ks = 0; ks < 2; ks++) {
+        half8 a = *(const half8 *)(sP + li * PLD + kb * 32 + ks * 16 + g * 8);
+#pragma unroll
+        for (int cb = 0; cb < NCB; cb++) {
+          const int col = (wave * NCB + cb) * 32 + li;
+          half8 bv;
+#pragma unroll
+          for (int e = 0; e < 8; e++) bv[e] = sV[(ks * 16 + g * 8 + e) * QLD + col];
+          o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bv, o[cb], 0, 0, 0);
+        }
+      }
+    }
+  }
+  if (wave < ACTIVE) {
+#pragma unroll
+    for (int cb = 0; cb < NCB; cb++) {
+      const int col = (wave * NCB + cb) * 32 + li;
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const int q = q0 + (v >> 2) * 8 + g * 4 + (v & 3);
+        if (q < S) ctx[(row0 + q) * d + hoff + col] = (q < L) ? (_Float16)o[cb][v] : (_Float16)0.f;
+      }
+    }
+  }
+}
+
+template <int DH>
+static hipError_t enc_attention_launch(const _Float16 *qkv, const int32_t *len, _Float16 *ctx, int B, int S, int d,
+                                       int heads, const float *rk, int clip, hipStream_t s) {
+  static size_t configured = 0;
+  size_t lds = enc_attention_lds_bytes(S, DH);
+  if (lds > configured) {
+    hipError_t e = hipFuncSetAttribute((const void *)enc_attention_kernel<DH>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    configured = lds;
+  }
+  dim3 grid((S + QT - 1) / QT, heads, B), block(256);
+  hipLaunchKernelGGL(enc_attention_kernel<DH>, grid, block, lds, s, qkv, len, ctx, S, d, rk, clip);
+  return hipGetLastError();
+}
+
+hipError_t launch_enc_attention(const _Float16 *qkv, const int32_t *len, _Float16 *ctx, int B, int S, int d,
+                                int heads, const float *rk, int clip, hipStream_t s) {
+  if (B <= 0 || S <= 0) return hipSuccess;
+  if (clip > MAX_CLIP) return hipErrorInvalidValue;
+  switch (d / heads) {
+    case 64: return enc_attention_launch<64>(qkv, len, ctx, B, S, d, heads, rk, clip, s);
+    case 128: return enc_attention_launch<128>(qkv, len, ctx, B, S, d, heads, rk, clip, s);
+    case 256: return enc_attention_launch<256>(qkv, len, ctx, B, S, d, heads, rk, clip, s);
+    case 512: return enc_attention_launch<512>(qkv, len, ctx, B, S, d, heads, rk, clip, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// single-query attention against a cache
+// ---------------------------------------------------------------------------------------
+struct Partial {
+  float m, l, acc[8];
+};
+
+__device__ __forceinline__ void merge(Partial &a, const Partial &b) {
+  const float mn = fmaxf(a.m, b.m);
+  const float ca = (a.m == -INFINITY) ? 0.f : __expf(a.m - mn);
+  const float cb = (b.m == -INFINITY) ? 0.f : __expf(b.m - mn);
+  a.l = a.l * ca + b.l * cb;
+#pragma unroll
+  for (int e = 0; e < 8; e++) a.acc[e] = a.acc[e] * ca + b.acc[e] * cb;
+  a.m = mn;
+}
+
+template <bool F32>
+__device__ __forceinline__ void load8(const void *p, float (&o)[8]) {
+  if (F32) {
+    const float4 *f = (const float4 *)p;
+    float4 a = f[0], b = f[1];
+    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+    o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+  } else {
+    half8 hv = *(const half8 *)p;
+#pragma unroll
+    for (int e = 0; e < 8; e++) o[e] = (float)hv[e];
+  }
+}
+
+template <int DH, bool KV_F32>
+__global__ __launch_bounds__(256) void attn_decode_kernel(const float *q, const void *kv, long row_stride,
+                                                          const int32_t *len, int n_keys, int rows, int d, int heads,
+                                                          const float *rk, int clip, int qpos, float *ctx) {
+  constexpr int LPK = DH / 8;              // lanes per key
+  constexpr int G = 64 / LPK;              // keys per wave iteration
+  constexpr int WPP = (DH >= 256) ? 4 : 1; // waves per (row, head) pair
+  constexpr int ESZ = KV_F32 ? 4 : 2;
+  __shared__ Partial sPart[4][LPK > 64 ? 1 : LPK];
+  __shared__ float sQR[4][2 * MAX_CLIP + 1];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const long pair = (WPP == 4) ? (long)blockIdx.x : (long)blockIdx.x * 4 + wave;
+  const int wip = (WPP == 4) ? wave : 0;
+  const bool valid = pair < (long)rows * heads;
+  const int r = valid ? (int)(pair / heads) : 0, h = valid ? (int)(pair % heads) : 0;
+  const int nk = valid ? (len ? len[r] : n_keys) : 0;
+  const int grp = lane / LPK, sub = lane % LPK;
+
+  float qv[8];
+  {
+    const float4 *qp = (const float4 *)(q + (long)r * d + h * DH + sub * 8);
+    float4 a = qp[0], b = qp[1];
+    qv[0] = a.x; qv[1] = a.y; qv[2] = a.z; qv[3] = a.w;
+    qv[4] = b.x; qv[5] = b.y; qv[6] = b.z; qv[7] = b.w;
+  }
+  if (rk) {  // q . rk[o] for every relative offset, one offset per LPK-lane group at a time
+    const int nrel = 2 * clip + 1;
+    for (int o = grp; o < nrel; o += G) {
+      float s = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; e++) s += qv[e] * rk[o * DH + sub * 8 + e];
+#pragma unroll
+      for (int m = LPK / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m, 64);
+      if (sub == 0) sQR[wave][o] = s;
+    }
+    __syncthreads();
+  }
+
+  Partial p;
+  p.m = -INFINITY;
+  p.l = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; e++) p.acc[e] = 0.f;
+  const char *base = (const char *)kv + ((long)r * row_stride + h * DH + sub * 8) * ESZ;
+  for (int j = wip * G + grp; j < nk; j += WPP * G) {
+    const char *kp = base + (long)j * 2 * d * ESZ;
+    float kx[8], vx[8];
+    load8<KV_F32>(kp, kx);
+    load8<KV_F32>(kp + (long)d * ESZ, vx);
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; e++) s += qv[e] * kx[e];
+#pragma unroll
+    for (int m = LPK / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m, 64);
+    if (rk) {
+      int rel = max(-clip, min(clip, j - qpos));
+      s += sQR[wave][rel + clip];
+    }
+    const float mn = fmaxf(p.m, s);
+    const float corr = (p.m == -INFINITY) ? 0.f : __expf(p.m - mn);
+    const float w = __expf(s - mn);
+    p.l = p.l * corr + w;
+#pragma unroll
+    for (int e = 0; e < 8; e++) p.acc[e] = p.acc[e] * corr + w * vx[e];
+    p.m = mn;
+  }
+  // merge the key groups of this wave
+#pragma unroll
+  for (int mask = LPK; mask < 64; mask <<= 1) {
+    Partial o;
+    o.m = __shfl_xor(p.m, mask, 64);
+    o.l = __shfl_xor(p.l, mask, 64);
+#pragma unroll
+    for (int e = 0; e < 8; e++) o.acc[e] = __shfl_xor(p.acc[e], mask, 64);
+    merge(p, o);
+  }
+  if (WPP == 4) {
+    if (lane < LPK) sPart[wave][lane] = p;
+    __syncthreads();
+    if (wave == 0 && lane < LPK) {
+#pragma unroll
+      for (int w = 1; w < 4; w++) merge(p, sPart[w][lane]);
+    }
+    if (wave != 0) return;
+  }
+  if (valid && lane < LPK) {
+    const float inv = (p.l > 0.f) ? 1.f / p.l : 0.f;
+    float4 *o = (float4 *)(ctx + (long)r * d + h * DH + sub * 8);
+    o[0] = make_float4(p.acc[0] * inv, p.acc[1] * inv, p.acc[2] * inv, p.acc[3] * inv);
+    o[1] = make_float4(p.acc[4] * inv, p.acc[5] * inv, p.acc[6] * inv, p.acc[7] * inv);
+  }
+}
+
+template <int DH>
+static hipError_t attn_decode_launch(const float *q, const void *kv, bool kv_f32, long row_stride, const int32_t *len,
+                                     int n_keys, int rows, int d, int heads, const float *rk, int clip, int qpos,
+                                     float *ctx, hipStream_t s) {
+  const long pairs = (long)rows * heads;
+  const unsigned grid = (DH >= 256) ? (unsigned)pairs : (unsigned)((pairs + 3) / 4);
+  if (kv_f32)
+    hipLaunchKernelGGL((attn_decode_kernel<DH, true>), dim3(grid), dim3(256), 0, s, q, kv, row_stride, len, n_keys,
+                       rows, d, heads, rk, clip, qpos, ctx);
+  else
+    hipLaunchKernelGGL((attn_decode_kernel<DH, false>), dim3(grid), dim3(256), 0, s, q, kv, row_stride, len, n_keys,
+                       rows, d, heads, rk, clip, qpos, ctx);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_decode(const float *q, const void *kv, bool kv_f32, long row_stride, const int32_t *len,
+                              int n_keys, int rows, int d, int heads, const float *rk, int clip, int qpos,
+                              float *ctx, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (clip > MAX_CLIP) return hipErrorInvalidValue;
+  switch (d / heads) {
+    case 64: return attn_decode_launch<64>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, s);
+    case 128: return attn_decode_launch<128>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, s);
+    case 256: return attn_decode_launch<256>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, s);
+    case 512: return attn_decode_launch<512>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace nt

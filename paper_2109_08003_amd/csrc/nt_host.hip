@@ -1,0 +1,634 @@
+// Host side of libnt: C ABI entry points, weight re-layout, arena planning, the token-budget
+// batcher and the step scheduler that enqueues the gfx950 kernels.  No CPU fallback exists:
+// every numerical step of the path is a kernel in nt_gemm.hip / nt_rows.hip / nt_attn.hip.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <string>
+#include <vector>
+
+#include "../../include/nt.h"
+#include "nt_kernels.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+int fail(int code, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                      \
+  do {                                                                                     \
+    hipError_t _e = (expr);                                                                \
+    if (_e != hipSuccess) return fail(NT_EHIP, "%s: %s", #expr, hipGetErrorString(_e));    \
+  } while (0)
+
+struct LN {
+  const float *g = nullptr, *b = nullptr;
+};
+struct Attn {
+  const _Float16 *Wqkv = nullptr;  // [3d][d] rows: q | k | v   (self-attention)
+  const _Float16 *Wq = nullptr;    // [d][d]                    (cross-attention query)
+  const _Float16 *Wkv = nullptr;   // [2d][d]                   (cross-attention keys | values)
+  const _Float16 *Wo = nullptr;    // [d][d]
+  const float *bqkv = nullptr, *bq = nullptr, *bkv = nullptr, *bo = nullptr;
+  const float *rk = nullptr;       // [2c+1][dh]
+};
+struct FFN {
+  const _Float16 *W1 = nullptr, *W2 = nullptr;  // [F][d], [d][F]
+  const float *b1 = nullptr, *b2 = nullptr;
+};
+struct EncLayer {
+  LN ln1, ln2;
+  Attn self;
+  FFN ffn;
+};
+struct DecLayer {
+  LN ln1, ln2, ln3;
+  Attn self, cross;
+  FFN ffn;
+};
+
+}  // namespace
+
+struct nt_model {
+  nt_config c{};
+  int64_t max_tokens = 0, max_rows = 0, self_positions = 0, pk_elems = 0;
+  // device weights (one allocation)
+  char *d_w = nullptr;
+  size_t w_bytes = 0;
+  const _Float16 *E = nullptr, *Wout = nullptr;
+  const float *pe = nullptr;
+  std::vector<EncLayer> enc;
+  std::vector<DecLayer> dec;
+  LN enc_final, dec_final;
+  // device arena (one allocation)
+  char *d_arena = nullptr;
+  size_t arena_bytes = 0;
+  float *x = nullptr;          // [Mt,d]  encoder residual stream
+  _Float16 *a16 = nullptr;     // [Mt,d]  LayerNorm output
+  _Float16 *qkv = nullptr;     // [Mt,3d]
+  _Float16 *ctx16 = nullptr;   // [Mt,d]
+  _Float16 *u16 = nullptr;     // [Mt,F]
+  _Float16 *enc_out = nullptr; // [Mt,d]
+  std::vector<_Float16 *> cross;  // per decoder layer [Mt,2d]
+  std::vector<float *> self_kv;   // per decoder layer [self_positions, 2d]
+  float *z = nullptr, *a32 = nullptr, *q32 = nullptr, *ctx32 = nullptr, *u32 = nullptr;  // [Br, d|F]
+  unsigned long long *pk = nullptr;
+  int32_t *len = nullptr, *flags = nullptr;
+  int32_t *d_src = nullptr, *d_len_in = nullptr, *d_out = nullptr;  // staging for nt_translate_batch
+  int32_t *h_src = nullptr, *h_len = nullptr, *h_out = nullptr;     // pinned
+  // state left by nt_encode
+  int32_t B = 0, S = 0;
+  bool encoded = false;
+};
+
+namespace {
+
+struct ConfigCheck {
+  int code;
+};
+
+int check_config(const nt_config *c) {
+  if (!c) return fail(NT_EINVAL, "config is null");
+  if (c->struct_size != sizeof(nt_config)) return fail(NT_EINVAL, "config.struct_size %u != %zu", c->struct_size, sizeof(nt_config));
+  if (c->n_enc < 0 || c->n_dec < 1 || c->vocab < 1 || c->n_heads < 1) return fail(NT_ESHAPE, "layer/vocab/head counts out of range");
+  if (c->d_model < 64 || c->d_model > 1024 || c->d_model % 64) return fail(NT_ESHAPE, "d_model must be a multiple of 64 in [64,1024]");
+  if (c->d_model % c->n_heads) return fail(NT_ESHAPE, "d_model not divisible by n_heads");
+  int dh = c->d_model / c->n_heads;
+  if (dh != 64 && dh != 128 && dh != 256 && dh != 512) return fail(NT_ESHAPE, "head width %d not in {64,128,256,512}", dh);
+  if (c->d_ffn < 0 || c->d_ffn % 64) return fail(NT_ESHAPE, "d_ffn must be 0 or a multiple of 64");
+  if (c->max_len < 1 || c->max_len > 512) return fail(NT_ESHAPE, "max_len must be in [1,512]");
+  if (c->rpr_clip < 0 || c->rpr_clip > 16) return fail(NT_ESHAPE, "rpr_clip must be in [0,16]");
+  if (c->bos_id < 0 || c->bos_id >= c->vocab || c->pad_id < 0 || c->pad_id >= c->vocab) return fail(NT_ERANGE, "bos_id/pad_id outside the vocabulary");
+  if (!(c->ln_eps > 0.f)) return fail(NT_EINVAL, "ln_eps must be positive");
+  return NT_OK;
+}
+
+int64_t param_count(const nt_config *c) {
+  int64_t d = c->d_model, V = c->vocab, F = c->d_ffn, dh = d / c->n_heads;
+  int64_t attn = 4 * (d * d + d), ln = 2 * d;
+  int64_t ffn = F > 0 ? ln + d * F + F + F * d + d : 0;
+  int64_t rk = c->rpr_clip > 0 ? (2 * c->rpr_clip + 1) * dh : 0;
+  int64_t n = (c->tie_output ? 1 : 2) * V * d;
+  n += (int64_t)c->n_enc * (ln + attn + rk + ffn) + ln;
+  n += (int64_t)c->n_dec * (ln + attn + rk + ln + attn + ffn) + ln;
+  return n;
+}
+
+// ---- weight packing: a host image of the device weight buffer ---------------------------
+struct Packer {
+  std::vector<char> img;
+  size_t reserve(size_t bytes) {
+    size_t off = (img.size() + 255) & ~(size_t)255;
+    img.resize(off + bytes);
+    return off;
+  }
+  // W[in][out] fp16 -> rows [out][in] appended at dst (already reserved)
+  static void transpose(const _Float16 *W, int n_in, int n_out, _Float16 *dst) {
+    for (int k = 0; k < n_in; k++)
+      for (int n = 0; n < n_out; n++) dst[(size_t)n * n_in + k] = W[(size_t)k * n_out + n];
+  }
+  static void widen(const _Float16 *src, int n, float *dst) {
+    for (int i = 0; i < n; i++) dst[i] = (float)src[i];
+  }
+};
+
+struct BlobReader {
+  const _Float16 *p;
+  const _Float16 *take(int64_t n) {
+    const _Float16 *r = p;
+    p += n;
+    return r;
+  }
+};
+
+template <typename T>
+T *at(char *base, size_t off) {
+  return (T *)(base + off);
+}
+
+struct Carver {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    size_t o = (off + 255) & ~(size_t)255;
+    off = o + bytes;
+    return o;
+  }
+};
+
+hipStream_t as_stream(void *s) { return (hipStream_t)s; }
+
+}  // namespace
+
+extern "C" {
+
+const char *nt_last_error(void) { return g_err.c_str(); }
+
+int64_t nt_param_count(const nt_config *cfg) {
+  if (check_config(cfg) != NT_OK) return 0;
+  return param_count(cfg);
+}
+
+int32_t nt_n_steps(int32_t len) { return (6 * len + 4) / 5 + 2; }
+
+int64_t nt_device_bytes(const nt_model *m) { return m ? (int64_t)(m->w_bytes + m->arena_bytes) : 0; }
+
+void nt_free(nt_model *m) {
+  if (!m) return;
+  if (m->d_w) (void)hipFree(m->d_w);
+  if (m->d_arena) (void)hipFree(m->d_arena);
+  if (m->h_src) (void)hipHostFree(m->h_src);
+  if (m->h_len) (void)hipHostFree(m->h_len);
+  if (m->h_out) (void)hipHostFree(m->h_out);
+  delete m;
+}
+
+int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_bytes, void *hip_stream,
+                    nt_model **out) try {
+  if (!out) return fail(NT_EINVAL, "out is null");
+  *out = nullptr;
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!h_blob_fp16) return fail(NT_EINVAL, "blob is null");
+  const int64_t np = param_count(cfg);
+  if ((int64_t)blob_bytes != 2 * np) return fail(NT_EBLOB, "blob holds %zu bytes, configuration needs %lld", blob_bytes, (long long)(2 * np));
+  if (cfg->max_batch_tokens < 1) return fail(NT_EINVAL, "max_batch_tokens must be >= 1");
+  if (cfg->max_batch_rows < 0) return fail(NT_EINVAL, "max_batch_rows must be >= 0");
+  const int d = cfg->d_model, V = cfg->vocab, F = cfg->d_ffn, H = cfg->n_heads, dh = d / H, c = cfg->rpr_clip;
+  if (nt::enc_attention_lds_bytes(cfg->max_len, dh) > 160 * 1024) return fail(NT_ESHAPE, "max_len %d with head width %d exceeds the LDS plan", cfg->max_len, dh);
+
+  nt_model *m = new nt_model();
+  struct Guard {
+    nt_model *m;
+    ~Guard() { if (m) nt_free(m); }
+  } guard{m};
+  m->c = *cfg;
+  m->max_tokens = cfg->max_batch_tokens;
+  m->max_rows = cfg->max_batch_rows > 0 ? std::min<int64_t>(cfg->max_batch_rows, m->max_tokens) : m->max_tokens;
+  hipStream_t s = as_stream(hip_stream);
+
+  // ---- pack the weights: K-contiguous matrices, fp32 biases / LayerNorm / tables ----
+  Packer pk;
+  BlobReader br{(const _Float16 *)h_blob_fp16};
+  struct Fix { size_t off; const void **slot; };
+  std::vector<Fix> fixes;
+  auto put_raw = [&](const _Float16 *src, int64_t n, const void **slot) {
+    size_t o = pk.reserve((size_t)n * 2);
+    memcpy(pk.img.data() + o, src, (size_t)n * 2);
+    fixes.push_back({o, slot});
+  };
+  auto put_f32 = [&](const _Float16 *src, int n, const void **slot) {
+    size_t o = pk.reserve((size_t)n * 4);
+    Packer::widen(src, n, (float *)(pk.img.data() + o));
+    fixes.push_back({o, slot});
+  };
+  auto put_ln = [&](LN &ln) {
+    put_f32(br.take(d), d, (const void **)&ln.g);
+    put_f32(br.take(d), d, (const void **)&ln.b);
+  };
+  // self-attention: Wq|Wk|Wv fused into one [3d][d] matrix; cross-attention: Wq and Wk|Wv
+  auto put_attn = [&](Attn &a, bool cross, bool rpr) {
+    const _Float16 *W[4], *b[4];
+    for (int i = 0; i < 4; i++) { W[i] = br.take((int64_t)d * d); b[i] = br.take(d); }
+    auto fused = [&](int first, int count, const void **wslot, const void **bslot) {
+      size_t o = pk.reserve((size_t)count * d * d * 2);
+      for (int i = 0; i < count; i++) Packer::transpose(W[first + i], d, d, (_Float16 *)(pk.img.data() + o) + (size_t)i * d * d);
+      fixes.push_back({o, wslot});
+      size_t ob = pk.reserve((size_t)count * d * 4);
+      for (int i = 0; i < count; i++) Packer::widen(b[first + i], d, (float *)(pk.img.data() + ob) + (size_t)i * d);
+      fixes.push_back({ob, bslot});
+    };
+    if (!cross) fused(0, 3, (const void **)&a.Wqkv, (const void **)&a.bqkv);
+    else {
+      fused(0, 1, (const void **)&a.Wq, (const void **)&a.bq);
+      fused(1, 2, (const void **)&a.Wkv, (const void **)&a.bkv);
+    }
+    fused(3, 1, (const void **)&a.Wo, (const void **)&a.bo);
+    if (rpr && c > 0) put_f32(br.take((int64_t)(2 * c + 1) * dh), (2 * c + 1) * dh, (const void **)&a.rk);
+  };
+  auto put_ffn = [&](FFN &f) {
+    const _Float16 *W1 = br.take((int64_t)d * F), *b1 = br.take(F), *W2 = br.take((int64_t)F * d), *b2 = br.take(d);
+    size_t o = pk.reserve((size_t)d * F * 2);
+    Packer::transpose(W1, d, F, (_Float16 *)(pk.img.data() + o));
+    fixes.push_back({o, (const void **)&f.W1});
+    put_f32(b1, F, (const void **)&f.b1);
+    o = pk.reserve((size_t)d * F * 2);
+    Packer::transpose(W2, F, d, (_Float16 *)(pk.img.data() + o));
+    fixes.push_back({o, (const void **)&f.W2});
+    put_f32(b2, d, (const void **)&f.b2);
+  };
+
+  m->enc.resize(cfg->n_enc);
+  m->dec.resize(cfg->n_dec);
+  put_raw(br.take((int64_t)V * d), (int64_t)V * d, (const void **)&m->E);
+  if (!cfg->tie_output) put_raw(br.take((int64_t)V * d), (int64_t)V * d, (const void **)&m->Wout);
+  for (auto &L : m->enc) {
+    put_ln(L.ln1);
+    put_attn(L.self, false, true);
+    if (F > 0) { put_ln(L.ln2); put_ffn(L.ffn); }
+  }
+  put_ln(m->enc_final);
+  for (auto &L : m->dec) {
+    put_ln(L.ln1);
+    put_attn(L.self, false, true);
+    put_ln(L.ln2);
+    put_attn(L.cross, true, false);
+    if (F > 0) { put_ln(L.ln3); put_ffn(L.ffn); }
+  }
+  put_ln(m->dec_final);
+  if (br.p - (const _Float16 *)h_blob_fp16 != np) return fail(NT_EBLOB, "internal: blob walk mismatch");
+  {  // sinusoid table, evaluated in double
+    size_t o = pk.reserve((size_t)cfg->max_len * d * 4);
+    float *pe = (float *)(pk.img.data() + o);
+    for (int p = 0; p < cfg->max_len; p++)
+      for (int k = 0; 2 * k < d; k++) {
+        double ang = (double)p / std::pow(10000.0, (2.0 * k) / (double)d);
+        pe[(size_t)p * d + 2 * k] = (float)std::sin(ang);
+        if (2 * k + 1 < d) pe[(size_t)p * d + 2 * k + 1] = (float)std::cos(ang);
+      }
+    fixes.push_back({o, (const void **)&m->pe});
+  }
+  m->w_bytes = pk.img.size();
+  if (hipMalloc((void **)&m->d_w, m->w_bytes) != hipSuccess) return fail(NT_ENOMEM, "hipMalloc of %zu weight bytes failed", m->w_bytes);
+  HIP_TRY(hipMemcpyAsync(m->d_w, pk.img.data(), m->w_bytes, hipMemcpyHostToDevice, s));
+  for (auto &f : fixes) *f.slot = m->d_w + f.off;
+  if (cfg->tie_output) m->Wout = m->E;
+
+  // ---- arena: the peak footprint is fixed here, nothing is allocated afterwards ----
+  const int64_t Mt = m->max_tokens, Br = m->max_rows;
+  m->self_positions = (6 * Mt + 4) / 5 + 3 * Br + 8;
+  if (m->self_positions < Br * 1) m->self_positions = Br;
+  {  // arg-max partials: the count per row depends only on ceil(rows / 128)
+    int64_t worst = 0;
+    for (int64_t mt = 1; (mt - 1) * 128 < Br; mt++) {
+      const int64_t rows = std::min<int64_t>(mt * 128, Br);
+      worst = std::max(worst, rows * nt::vocab_argmax_partials((int)rows, V));
+    }
+    m->pk_elems = worst;
+  }
+  Carver cv;
+  const size_t o_x = cv.take((size_t)Mt * d * 4), o_a16 = cv.take((size_t)Mt * d * 2), o_qkv = cv.take((size_t)Mt * 3 * d * 2),
+               o_ctx16 = cv.take((size_t)Mt * d * 2), o_u16 = cv.take((size_t)Mt * std::max(F, 1) * 2),
+               o_enc = cv.take((size_t)Mt * d * 2);
+  std::vector<size_t> o_cross(cfg->n_dec), o_self(cfg->n_dec);
+  for (int l = 0; l < cfg->n_dec; l++) o_cross[l] = cv.take((size_t)Mt * 2 * d * 2);
+  for (int l = 0; l < cfg->n_dec; l++) o_self[l] = cv.take((size_t)m->self_positions * 2 * d * 4);
+  const size_t o_z = cv.take((size_t)Br * d * 4), o_a32 = cv.take((size_t)Br * d * 4), o_q32 = cv.take((size_t)Br * d * 4),
+               o_ctx32 = cv.take((size_t)Br * d * 4), o_u32 = cv.take((size_t)Br * std::max(F, 1) * 4),
+               o_pk = cv.take((size_t)m->pk_elems * 8), o_len = cv.take((size_t)Br * 4), o_flags = cv.take(64),
+               o_src = cv.take((size_t)Mt * 4), o_lin = cv.take((size_t)Br * 4), o_out = cv.take((size_t)m->self_positions * 4);
+  m->arena_bytes = cv.off;
+  if (hipMalloc((void **)&m->d_arena, m->arena_bytes) != hipSuccess) return fail(NT_ENOMEM, "hipMalloc of %zu arena bytes failed", m->arena_bytes);
+  char *A = m->d_arena;
+  m->x = at<float>(A, o_x); m->a16 = at<_Float16>(A, o_a16); m->qkv = at<_Float16>(A, o_qkv);
+  m->ctx16 = at<_Float16>(A, o_ctx16); m->u16 = at<_Float16>(A, o_u16); m->enc_out = at<_Float16>(A, o_enc);
+  for (int l = 0; l < cfg->n_dec; l++) { m->cross.push_back(at<_Float16>(A, o_cross[l])); m->self_kv.push_back(at<float>(A, o_self[l])); }
+  m->z = at<float>(A, o_z); m->a32 = at<float>(A, o_a32); m->q32 = at<float>(A, o_q32); m->ctx32 = at<float>(A, o_ctx32);
+  m->u32 = at<float>(A, o_u32); m->pk = at<unsigned long long>(A, o_pk); m->len = at<int32_t>(A, o_len);
+  m->flags = at<int32_t>(A, o_flags); m->d_src = at<int32_t>(A, o_src); m->d_len_in = at<int32_t>(A, o_lin);
+  m->d_out = at<int32_t>(A, o_out);
+  HIP_TRY(nt::launch_fill_i32(m->flags, 16, 0, s));
+  if (hipHostMalloc((void **)&m->h_src, (size_t)Mt * 4) != hipSuccess || hipHostMalloc((void **)&m->h_len, (size_t)Br * 4) != hipSuccess ||
+      hipHostMalloc((void **)&m->h_out, (size_t)m->self_positions * 4) != hipSuccess)
+    return fail(NT_ENOMEM, "pinned staging allocation failed");
+  HIP_TRY(hipStreamSynchronize(s));  // the packed host image goes out of scope
+  guard.m = nullptr;
+  *out = m;
+  return NT_OK;
+} catch (const std::bad_alloc &) {
+  return fail(NT_ENOMEM, "host allocation failed");
+} catch (...) {
+  return fail(NT_EINVAL, "unexpected exception");
+}
+
+int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B, int32_t S, void *hip_stream) {
+  if (!m || !d_src || !d_len) return fail(NT_EINVAL, "null argument");
+  if (B < 1 || S < 1) return fail(NT_EINVAL, "B and S must be >= 1");
+  const nt_config &c = m->c;
+  if (S > c.max_len) return fail(NT_ESHAPE, "S %d exceeds max_len %d", S, c.max_len);
+  if ((int64_t)B * S > m->max_tokens || B > m->max_rows) return fail(NT_ENOMEM, "batch %d x %d exceeds the arena (%lld tokens, %lld rows)", B, S, (long long)m->max_tokens, (long long)m->max_rows);
+  hipStream_t s = as_stream(hip_stream);
+  const int d = c.d_model, F = c.d_ffn, H = c.n_heads, M = B * S;
+  const float qscale = 1.0f / std::sqrt((float)(d / H));
+  m->encoded = false;
+  HIP_TRY(nt::launch_embed_src(d_src, d_len, m->len, B, S, d, c.vocab, c.pad_id, m->E, m->pe, m->x, m->flags, s));
+  for (auto &L : m->enc) {
+    HIP_TRY(nt::launch_layer_norm(m->x, M, d, L.ln1.g, L.ln1.b, c.ln_eps, m->a16, false, s));
+    nt::GemmEpilogue e;
+    e.bias = L.self.bqkv; e.scale = qscale; e.scale_cols = d; e.dst0 = m->qkv; e.ld0 = 3 * d; e.n_split = 3 * d;
+    HIP_TRY(nt::launch_gemm(false, false, m->a16, d, L.self.Wqkv, M, 3 * d, d, e, s));
+    HIP_TRY(nt::launch_enc_attention(m->qkv, m->len, m->ctx16, B, S, d, H, L.self.rk, c.rpr_clip, s));
+    nt::GemmEpilogue o;
+    o.bias = L.self.bo; o.resid = m->x; o.ldr = d; o.dst0 = m->x; o.ld0 = d; o.n_split = d;
+    HIP_TRY(nt::launch_gemm(false, true, m->ctx16, d, L.self.Wo, M, d, d, o, s));
+    if (F > 0) {
+      HIP_TRY(nt::launch_layer_norm(m->x, M, d, L.ln2.g, L.ln2.b, c.ln_eps, m->a16, false, s));
+      nt::GemmEpilogue f1;
+      f1.bias = L.ffn.b1; f1.relu = 1; f1.dst0 = m->u16; f1.ld0 = F; f1.n_split = F;
+      HIP_TRY(nt::launch_gemm(false, false, m->a16, d, L.ffn.W1, M, F, d, f1, s));
+      nt::GemmEpilogue f2;
+      f2.bias = L.ffn.b2; f2.resid = m->x; f2.ldr = d; f2.dst0 = m->x; f2.ld0 = d; f2.n_split = d;
+      HIP_TRY(nt::launch_gemm(false, true, m->u16, F, L.ffn.W2, M, d, F, f2, s));
+    }
+  }
+  HIP_TRY(nt::launch_layer_norm(m->x, M, d, m->enc_final.g, m->enc_final.b, c.ln_eps, m->enc_out, false, s));
+  for (int l = 0; l < c.n_dec; l++) {
+    nt::GemmEpilogue e;
+    e.bias = m->dec[l].cross.bkv; e.dst0 = m->cross[l]; e.ld0 = 2 * d; e.n_split = 2 * d;
+    HIP_TRY(nt::launch_gemm(false, false, m->enc_out, d, m->dec[l].cross.Wkv, M, 2 * d, d, e, s));
+  }
+  m->B = B; m->S = S; m->encoded = true;
+  return NT_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+// Decoder loop shared by greedy decoding and the teacher-forced debug path.
+int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, const int32_t *d_forced,
+                int32_t *d_out, float *d_logits, hipStream_t s) {
+  const nt_config &c = m->c;
+  const int d = c.d_model, F = c.d_ffn, H = c.n_heads, V = c.vocab, S = m->S;
+  const float qscale = 1.0f / std::sqrt((float)(d / H));
+  const long self_stride = (long)T * 2 * d;
+  // active rows at step t: rows are ordered so that the active set is a prefix
+  auto rows_at = [&](int t) -> int {
+    if (t >= T) return 0;
+    if (!h_row_steps) return B;
+    // number of rows with steps > t (non-increasing array)
+    int lo = 0, hi = B;
+    while (lo < hi) {
+      int mid = (lo + hi) / 2;
+      if (h_row_steps[mid] > t) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+  };
+  int partials_prev = 0;
+  for (int t = 0; t <= T; t++) {
+    const int rows_now = rows_at(t), rows_prev = (t == 0) ? rows_now : rows_at(t - 1);
+    if (rows_prev == 0) break;
+    nt::StepBeginArgs a{};
+    a.t = t; a.rows_prev = rows_prev; a.rows_now = rows_now; a.d = d; a.vocab = V; a.bos_id = c.bos_id; a.pad_id = c.pad_id;
+    a.pk = d_logits ? nullptr : m->pk; a.n_partials = partials_prev; a.out = d_out; a.out_ld = T;
+    a.forced = d_forced; a.forced_ld = T; a.E = m->E; a.pe = m->pe; a.gamma = m->dec[0].ln1.g; a.beta = m->dec[0].ln1.b;
+    a.eps = c.ln_eps; a.z = m->z; a.a = m->a32; a.flags = m->flags;
+    if (d_logits && rows_now == 0) break;  // no tokens to collect in this mode (pk == nullptr)
+    HIP_TRY(nt::launch_step_begin(a, s));
+    if (rows_now == 0) break;
+    const int R = rows_now;
+    for (int l = 0; l < c.n_dec; l++) {
+      const DecLayer &L = m->dec[l];
+      if (l > 0) HIP_TRY(nt::launch_layer_norm(m->z, R, d, L.ln1.g, L.ln1.b, c.ln_eps, m->a32, true, s));
+      {  // self-attention: q (scaled) to q32, k|v appended to the cache at position t
+        nt::GemmEpilogue e;
+        e.bias = L.self.bqkv; e.scale = qscale; e.scale_cols = d; e.dst0 = m->q32; e.ld0 = d; e.n_split = d;
+        e.dst1 = m->self_kv[l] + (long)t * 2 * d; e.ld1 = self_stride;
+        HIP_TRY(nt::launch_gemm(true, true, m->a32, d, L.self.Wqkv, R, 3 * d, d, e, s));
+        HIP_TRY(nt::launch_attn_decode(m->q32, m->self_kv[l], true, self_stride, nullptr, t + 1, R, d, H, L.self.rk,
+                                       c.rpr_clip, t, m->ctx32, s));
+        nt::GemmEpilogue o;
+        o.bias = L.self.bo; o.resid = m->z; o.ldr = d; o.dst0 = m->z; o.ld0 = d; o.n_split = d;
+        HIP_TRY(nt::launch_gemm(true, true, m->ctx32, d, L.self.Wo, R, d, d, o, s));
+      }
+      {  // cross-attention over the encoder keys/values
+        HIP_TRY(nt::launch_layer_norm(m->z, R, d, L.ln2.g, L.ln2.b, c.ln_eps, m->a32, true, s));
+        nt::GemmEpilogue e;
+        e.bias = L.cross.bq; e.scale = qscale; e.scale_cols = d; e.dst0 = m->q32; e.ld0 = d; e.n_split = d;
+        HIP_TRY(nt::launch_gemm(true, true, m->a32, d, L.cross.Wq, R, d, d, e, s));
+        HIP_TRY(nt::launch_attn_decode(m->q32, m->cross[l], false, (long)S * 2 * d, m->len, 0, R, d, H, nullptr, 0, 0,
+                                       m->ctx32, s));
+        nt::GemmEpilogue o;
+        o.bias = L.cross.bo; o.resid = m->z; o.ldr = d; o.dst0 = m->z; o.ld0 = d; o.n_split = d;
+        HIP_TRY(nt::launch_gemm(true, true, m->ctx32, d, L.cross.Wo, R, d, d, o, s));
+      }
+      if (F > 0) {
+        HIP_TRY(nt::launch_layer_norm(m->z, R, d, L.ln3.g, L.ln3.b, c.ln_eps, m->a32, true, s));
+        nt::GemmEpilogue f1;
+        f1.bias = L.ffn.b1; f1.relu = 1; f1.dst0 = m->u32; f1.ld0 = F; f1.n_split = F;
+        HIP_TRY(nt::launch_gemm(true, true, m->a32, d, L.ffn.W1, R, F, d, f1, s));
+        nt::GemmEpilogue f2;
+        f2.bias = L.ffn.b2; f2.resid = m->z; f2.ldr = d; f2.dst0 = m->z; f2.ld0 = d; f2.n_split = d;
+        HIP_TRY(nt::launch_gemm(true, true, m->u32, F, L.ffn.W2, R, d, F, f2, s));
+      }
+    }
+    HIP_TRY(nt::launch_layer_norm(m->z, R, d, m->dec_final.g, m->dec_final.b, c.ln_eps, m->a32, true, s));
+    if (d_logits) {
+      nt::GemmEpilogue e;
+      e.dst0 = d_logits + (long)t * V; e.ld0 = (long)T * V; e.n_split = V;
+      HIP_TRY(nt::launch_gemm(true, true, m->a32, d, m->Wout, R, V, d, e, s));
+    } else {
+      HIP_TRY(nt::launch_vocab_argmax(m->a32, d, m->Wout, R, V, d, m->pk, s));
+      partials_prev = nt::vocab_argmax_partials(R, V);
+    }
+  }
+  return NT_OK;
+}
+
+int check_decode_args(nt_model *m, int32_t B, int32_t T) {
+  if (!m) return fail(NT_EINVAL, "model is null");
+  if (!m->encoded || B != m->B) return fail(NT_ESTATE, "decode of %d rows does not follow an encode of the same batch (%d rows)", B, m->encoded ? m->B : 0);
+  if (T < 0 || T > m->c.max_len) return fail(NT_ERANGE, "step count %d outside [0, max_len=%d]", T, m->c.max_len);
+  if ((int64_t)B * T > m->self_positions) return fail(NT_ENOMEM, "%d rows x %d steps exceed the self-attention cache (%lld positions)", B, T, (long long)m->self_positions);
+  return NT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int nt_decode_greedy(nt_model *m, int32_t B, int32_t n_steps, const int32_t *h_row_steps, int32_t *d_out,
+                     void *hip_stream) {
+  int rc = check_decode_args(m, B, n_steps);
+  if (rc) return rc;
+  if (!d_out) return fail(NT_EINVAL, "d_out is null");
+  if (n_steps == 0) return NT_OK;
+  hipStream_t s = as_stream(hip_stream);
+  if (h_row_steps) {
+    for (int i = 0; i < B; i++) {
+      if (h_row_steps[i] < 0 || h_row_steps[i] > n_steps || (i > 0 && h_row_steps[i] > h_row_steps[i - 1]))
+        return fail(NT_ERANGE, "h_row_steps must be non-increasing and within [0, n_steps]");
+    }
+    HIP_TRY(nt::launch_fill_i32(d_out, (long)B * n_steps, m->c.pad_id, s));
+  }
+  return run_decoder(m, B, n_steps, h_row_steps, nullptr, d_out, nullptr, s);
+}
+
+int nt_debug_teacher_forced_logits(nt_model *m, const int32_t *d_tgt_in, int32_t B, int32_t T, float *d_logits,
+                                   void *hip_stream) {
+  int rc = check_decode_args(m, B, T);
+  if (rc) return rc;
+  if (!d_tgt_in || !d_logits) return fail(NT_EINVAL, "null argument");
+  if (T == 0) return NT_OK;
+  return run_decoder(m, B, T, nullptr, d_tgt_in, nullptr, d_logits, as_stream(hip_stream));
+}
+
+int nt_debug_encoder_out(nt_model *m, float *d_out, void *hip_stream) {
+  if (!m || !d_out) return fail(NT_EINVAL, "null argument");
+  if (!m->encoded) return fail(NT_ESTATE, "no encoded batch");
+  HIP_TRY(nt::launch_half_to_float(m->enc_out, d_out, (long)m->B * m->S * m->c.d_model, as_stream(hip_stream)));
+  return NT_OK;
+}
+
+int nt_check_device_flags(nt_model *m, void *hip_stream) {
+  if (!m) return fail(NT_EINVAL, "model is null");
+  hipStream_t s = as_stream(hip_stream);
+  int32_t f = 0;
+  HIP_TRY(hipMemcpyAsync(&f, m->flags, 4, hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  if (f) {
+    HIP_TRY(nt::launch_fill_i32(m->flags, 1, 0, s));
+    return fail(NT_ERANGE, "a kernel clamped an out-of-range token id or length");
+  }
+  return NT_OK;
+}
+
+int nt_plan_batches(const int32_t *h_lengths, int64_t N, int64_t budget, int32_t max_rows, int64_t *order,
+                    int64_t *batch_starts, int64_t *n_batches) try {
+  if (N < 0 || (N > 0 && (!h_lengths || !order)) || !batch_starts || !n_batches) return fail(NT_EINVAL, "null argument");
+  if (budget < 1) return fail(NT_EINVAL, "budget must be >= 1");
+  if (max_rows < 0) return fail(NT_EINVAL, "max_rows must be >= 0");
+  for (int64_t i = 0; i < N; i++)
+    if (h_lengths[i] < 0) return fail(NT_EINVAL, "negative length at %lld", (long long)i);
+  std::iota(order, order + N, (int64_t)0);
+  std::stable_sort(order, order + N, [&](int64_t a, int64_t b) { return h_lengths[a] > h_lengths[b]; });
+  int64_t nb = 0, i = 0;
+  batch_starts[0] = 0;
+  while (i < N && h_lengths[order[i]] > 0) {
+    const int64_t longest = h_lengths[order[i]];  // first row of a batch is its longest
+    int64_t rows = std::max<int64_t>(1, budget / longest);
+    if (max_rows > 0) rows = std::min<int64_t>(rows, max_rows);
+    int64_t end = std::min(N, i + rows);
+    while (end > i + 1 && h_lengths[order[end - 1]] == 0) end--;  // empty sentences join no batch
+    i = end;
+    batch_starts[++nb] = i;
+  }
+  *n_batches = nb;
+  return NT_OK;
+} catch (...) {
+  return fail(NT_ENOMEM, "host allocation failed");
+}
+
+int nt_translate_batch(nt_model *m, const int32_t *h_tokens, const int64_t *h_offsets, int64_t N, int64_t token_budget,
+                       int32_t max_rows, int32_t *h_out, int64_t *h_out_offsets, void *hip_stream) try {
+  if (!m || !h_offsets || !h_out_offsets || N < 0) return fail(NT_EINVAL, "null argument or negative N");
+  if (token_budget < 1 || max_rows < 0) return fail(NT_EINVAL, "token_budget must be >= 1 and max_rows >= 0");
+  const nt_config &c = m->c;
+  // validate everything before anything is written or launched
+  if (h_offsets[0] < 0) return fail(NT_ERANGE, "offsets must start at >= 0");
+  std::vector<int32_t> lens((size_t)N);
+  int64_t total_out = 0;
+  for (int64_t i = 0; i < N; i++) {
+    const int64_t L = h_offsets[i + 1] - h_offsets[i];
+    if (L < 0) return fail(NT_ERANGE, "offsets decrease at sentence %lld", (long long)i);
+    if (L > c.max_len || nt_n_steps((int32_t)L) > c.max_len) return fail(NT_ERANGE, "sentence %lld has %lld tokens: too long for max_len %d (the decode runs ceil(1.2 len)+2 steps)", (long long)i, (long long)L, c.max_len);
+    lens[(size_t)i] = (int32_t)L;
+    total_out += L > 0 ? nt_n_steps((int32_t)L) : 0;
+  }
+  if (N > 0 && h_offsets[N] > h_offsets[0] && !h_tokens) return fail(NT_EINVAL, "h_tokens is null");
+  for (int64_t k = h_offsets[0]; N > 0 && k < h_offsets[N]; k++)
+    if (h_tokens[k] < 0 || h_tokens[k] >= c.vocab) return fail(NT_ERANGE, "token id %d at position %lld is outside [0,%d)", h_tokens[k], (long long)k, c.vocab);
+  if (total_out > 0 && !h_out) return fail(NT_EINVAL, "h_out is null");
+  const int64_t budget = std::min<int64_t>(token_budget, m->max_tokens);
+  int64_t rows_cap = m->max_rows;
+  if (max_rows > 0) rows_cap = std::min<int64_t>(rows_cap, max_rows);
+  for (int64_t i = 0; i < N; i++)
+    if (lens[(size_t)i] > m->max_tokens) return fail(NT_ERANGE, "sentence %lld (%d tokens) exceeds the arena of %lld tokens", (long long)i, lens[(size_t)i], (long long)m->max_tokens);
+  h_out_offsets[0] = 0;
+  for (int64_t i = 0; i < N; i++) h_out_offsets[i + 1] = h_out_offsets[i] + (lens[(size_t)i] > 0 ? nt_n_steps(lens[(size_t)i]) : 0);
+  if (N == 0) return NT_OK;
+
+  std::vector<int64_t> order((size_t)N), starts((size_t)N + 1);
+  int64_t nb = 0;
+  int rc = nt_plan_batches(lens.data(), N, budget, (int32_t)std::min<int64_t>(rows_cap, INT32_MAX), order.data(), starts.data(), &nb);
+  if (rc) return rc;
+  hipStream_t s = as_stream(hip_stream);
+  std::vector<int32_t> row_steps;
+  for (int64_t k = 0; k < nb; k++) {
+    const int64_t i0 = starts[(size_t)k], i1 = starts[(size_t)k + 1];
+    const int32_t B = (int32_t)(i1 - i0), S = lens[(size_t)order[(size_t)i0]], T = nt_n_steps(S);
+    if ((int64_t)B * T > m->self_positions) return fail(NT_ENOMEM, "batch of %d rows x %d steps exceeds the self-attention cache", B, T);
+    row_steps.resize((size_t)B);
+    for (int32_t r = 0; r < B; r++) {
+      const int64_t si = order[(size_t)(i0 + r)];
+      const int32_t L = lens[(size_t)si];
+      m->h_len[r] = L;
+      row_steps[(size_t)r] = nt_n_steps(L);
+      int32_t *row = m->h_src + (size_t)r * S;
+      memcpy(row, h_tokens + h_offsets[si], (size_t)L * 4);
+      for (int32_t j = L; j < S; j++) row[j] = c.pad_id;
+    }
+    HIP_TRY(hipMemcpyAsync(m->d_src, m->h_src, (size_t)B * S * 4, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(m->d_len_in, m->h_len, (size_t)B * 4, hipMemcpyHostToDevice, s));
+    rc = nt_encode(m, m->d_src, m->d_len_in, B, S, s);
+    if (rc) return rc;
+    rc = nt_decode_greedy(m, B, T, row_steps.data(), m->d_out, s);
+    if (rc) return rc;
+    HIP_TRY(hipMemcpyAsync(m->h_out, m->d_out, (size_t)B * T * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    for (int32_t r = 0; r < B; r++) {
+      const int64_t si = order[(size_t)(i0 + r)];
+      memcpy(h_out + h_out_offsets[si], m->h_out + (size_t)r * T, (size_t)row_steps[(size_t)r] * 4);
+    }
+  }
+  return NT_OK;
+} catch (const std::bad_alloc &) {
+  return fail(NT_ENOMEM, "host allocation failed");
+} catch (...) {
+  return fail(NT_EINVAL, "unexpected exception");
+}
+
+}  // extern "C"

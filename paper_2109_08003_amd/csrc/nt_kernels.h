@@ -1,0 +1,96 @@
+// Internal launch interface between the host side of libnt and its gfx950 kernels.
+// Every launcher validates nothing: the host code checks shapes before calling.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nt {
+
+// ---- GEMM: C[M,N] = A[M,K] * Wt[N,K]^T, fp16 MFMA with fp32 accumulation -------------
+// Epilogue, applied to acc (fp32):  v = acc + bias[n];  if (n < scale_cols) v *= scale;
+// if (relu) v = max(v,0);  if (resid) v += resid[m*ldr+n];  then columns [0,n_split) go to
+// dst0[m*ld0+n] and columns [n_split,N) to dst1[m*ld1+(n-n_split)].
+struct GemmEpilogue {
+  const float *bias = nullptr;
+  float scale = 1.f;
+  int scale_cols = 0;
+  int relu = 0;
+  const float *resid = nullptr;
+  long ldr = 0;
+  void *dst0 = nullptr;
+  long ld0 = 0;
+  int n_split = 0;  // set to N when there is a single destination
+  void *dst1 = nullptr;
+  long ld1 = 0;
+};
+
+// a_f32: A is fp32 and is split into an fp16 head and an fp16 tail inside the kernel (two MFMA
+// passes, ~22 significant bits); otherwise A is fp16.  c_f32: destinations are fp32, else fp16.
+// K must be a multiple of 64; lda in elements.
+hipError_t launch_gemm(bool a_f32, bool c_f32, const void *A, long lda, const _Float16 *Wt, int M, int N, int K,
+                       const GemmEpilogue &e, hipStream_t s);
+
+// ---- output projection fused with row arg-max ------------------------------------------
+// For every row m < M: the largest of h[m,:] . Wt[v,:] over v < N, lowest v on ties, as packed
+// keys.  Each workgroup reduces a strip of columns; partial keys go to pk[m * n_partials + p].
+// vocab_argmax_partials(N) gives n_partials for the launch configuration used with M rows.
+int vocab_argmax_partials(int M, int N);
+hipError_t launch_vocab_argmax(const float *h, long ldh, const _Float16 *Wt, int M, int N, int K,
+                               unsigned long long *pk, hipStream_t s);
+
+// ---- row kernels --------------------------------------------------------------------
+// x[r,:] = sqrt(d) * E[id] + PE[pos]; rows r = b*S + s, pos = s.  Out-of-range ids are
+// replaced by pad_id and flags[0] is set.  Also clamps len into [1,S] -> len_out.
+hipError_t launch_embed_src(const int32_t *src, const int32_t *len, int32_t *len_out, int B, int S, int d, int vocab,
+                            int pad_id, const _Float16 *E, const float *pe, float *x, int32_t *flags, hipStream_t s);
+
+// out = gamma * (x - mean) / sqrt(var + eps) + beta per row of d; out fp16 or fp32.
+hipError_t launch_layer_norm(const float *x, int M, int d, const float *gamma, const float *beta, float eps,
+                             void *out, bool out_f32, hipStream_t s);
+
+// fp16 -> fp32 copy (debug readback)
+hipError_t launch_half_to_float(const _Float16 *in, float *out, long n, hipStream_t s);
+hipError_t launch_fill_i32(int32_t *p, long n, int32_t v, hipStream_t s);
+
+// Start of decoder step t for rows [0, rows_prev): (1) if t > 0, reduce the arg-max partials of
+// step t-1 and store the token in out[r*out_ld + t-1]; (2) for rows < rows_now: take the input
+// token (BOS at t = 0, forced[r*forced_ld + t] if forced, else the token just reduced),
+// z = sqrt(d) * E[y] + PE[t], a = LayerNorm(z).
+struct StepBeginArgs {
+  int t, rows_prev, rows_now, d, vocab, bos_id, pad_id;
+  const unsigned long long *pk;
+  int n_partials;
+  int32_t *out;
+  long out_ld;
+  const int32_t *forced;
+  long forced_ld;
+  const _Float16 *E;
+  const float *pe;
+  const float *gamma, *beta;
+  float eps;
+  float *z, *a;
+  int32_t *flags;
+};
+hipError_t launch_step_begin(const StepBeginArgs &a, hipStream_t s);
+
+// ---- attention ------------------------------------------------------------------------
+// Encoder self-attention on a padded batch.  qkv [B*S, 3d] fp16 (q already scaled | k | v),
+// len [B]; ctx [B*S, d] fp16.  Keys >= len get weight exactly 0; query rows >= len get 0.
+// rk: optional relative-position keys [2*clip+1, dh] fp32.
+hipError_t launch_enc_attention(const _Float16 *qkv, const int32_t *len, _Float16 *ctx, int B, int S, int d,
+                                int heads, const float *rk, int clip, hipStream_t s);
+
+// Single-query attention against a cache, one query per (row, head).
+//   q [rows, d] fp32 (scaled); ctx [rows, d] fp32.
+//   cache row r: kv + r*row_stride elements, position j at + j*2d: k[d] then v[d].
+//   n_keys: fixed count (self-attention: t+1) when len == nullptr, else len[r] (cross).
+//   kv_f32 selects fp32 or fp16 cache elements.
+//   rk (self only): relative keys; the query sits at position qpos, key j at position j.
+hipError_t launch_attn_decode(const float *q, const void *kv, bool kv_f32, long row_stride, const int32_t *len,
+                              int n_keys, int rows, int d, int heads, const float *rk, int clip, int qpos,
+                              float *ctx, hipStream_t s);
+
+// max dynamic LDS the encoder attention needs for (S, dh); used to validate shapes at load.
+size_t enc_attention_lds_bytes(int S, int dh);
+
+}  // namespace nt

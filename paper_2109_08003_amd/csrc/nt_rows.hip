@@ -1,0 +1,189 @@
+// Row-wise kernels: embedding gather + sinusoidal positions, LayerNorm, the start-of-step kernel
+// of the decoder (arg-max reduction of the previous step + embedding + LayerNorm), and helpers.
+// One wave64 per row; a row of d <= 1024 values lives in at most 16 registers per lane and
+// every reduction is a wavefront butterfly (no LDS).  Statistics are fp32: mean first, then the
+// biased variance of the centred values.
+#include "nt_kernels.h"
+
+namespace nt {
+
+constexpr int MAX_PER_LANE = 16;  // d <= 1024
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+  return v;
+}
+
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long x) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    unsigned int lo = __shfl_xor((unsigned int)x, m, 64), hi = __shfl_xor((unsigned int)(x >> 32), m, 64);
+    unsigned long long o = ((unsigned long long)hi << 32) | lo;
+    x = o > x ? o : x;
+  }
+  return x;
+}
+
+// lane holds elements lane + 64*i, i < ne
+__device__ __forceinline__ void row_layer_norm(float (&v)[MAX_PER_LANE], int ne, int d, float eps, int lane,
+                                               const float *gamma, const float *beta) {
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAX_PER_LANE; i++)
+    if (i < ne) s += v[i];
+  const float mean = wave_sum(s) / (float)d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAX_PER_LANE; i++)
+    if (i < ne) {
+      const float c = v[i] - mean;
+      q += c * c;
+    }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
+#pragma unroll
+  for (int i = 0; i < MAX_PER_LANE; i++)
+    if (i < ne) v[i] = gamma[lane + 64 * i] * ((v[i] - mean) * rstd) + beta[lane + 64 * i];
+}
+
+__global__ __launch_bounds__(256) void embed_src_kernel(const int32_t *src, const int32_t *len, int32_t *len_out, int B,
+                                                        int S, int d, int vocab, int pad_id, const _Float16 *E,
+                                                        const float *pe, float *x, int32_t *flags) {
+  const int lane = threadIdx.x & 63;
+  const long r = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= (long)B * S) return;
+  const int b = (int)(r / S), pos = (int)(r % S);
+  if (pos == 0 && lane == 0) {
+    int L = len[b];
+    if (L < 1 || L > S) {
+      flags[0] = 1;
+      L = L < 1 ? 1 : S;
+    }
+    len_out[b] = L;
+  }
+  int id = src[r];
+  int L = len[b];
+  if (pos >= L) id = pad_id;  // padding carries no meaning; make it deterministic
+  if (id < 0 || id >= vocab) {
+    if (lane == 0) flags[0] = 1;
+    id = pad_id;
+  }
+  const float sc = sqrtf((float)d);
+  const _Float16 *e = E + (long)id * d;
+  const float *p = pe + (long)pos * d;
+  float *o = x + r * d;
+  for (int i = lane; i < d; i += 64) o[i] = sc * (float)e[i] + p[i];
+}
+
+hipError_t launch_embed_src(const int32_t *src, const int32_t *len, int32_t *len_out, int B, int S, int d, int vocab,
+                            int pad_id, const _Float16 *E, const float *pe, float *x, int32_t *flags, hipStream_t s) {
+  long rows = (long)B * S;
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(embed_src_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, src, len, len_out, B, S, d,
+                     vocab, pad_id, E, pe, x, flags);
+  return hipGetLastError();
+}
+
+template <bool OUT_F32>
+__global__ __launch_bounds__(256) void layer_norm_kernel(const float *x, int M, int d, const float *gamma,
+                                                         const float *beta, float eps, void *out) {
+  const int lane = threadIdx.x & 63;
+  const long r = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= M) return;
+  const int ne = d >> 6;
+  float v[MAX_PER_LANE];
+  const float *xr = x + r * d;
+#pragma unroll
+  for (int i = 0; i < MAX_PER_LANE; i++)
+    if (i < ne) v[i] = xr[lane + 64 * i];
+  row_layer_norm(v, ne, d, eps, lane, gamma, beta);
+#pragma unroll
+  for (int i = 0; i < MAX_PER_LANE; i++)
+    if (i < ne) {
+      if (OUT_F32)
+        ((float *)out)[r * d + lane + 64 * i] = v[i];
+      else
+        ((_Float16 *)out)[r * d + lane + 64 * i] = (_Float16)v[i];
+    }
+}
+
+hipError_t launch_layer_norm(const float *x, int M, int d, const float *gamma, const float *beta, float eps,
+                             void *out, bool out_f32, hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  dim3 grid((M + 3) / 4), block(256);
+  if (out_f32)
+    hipLaunchKernelGGL(layer_norm_kernel<true>, grid, block, 0, s, x, M, d, gamma, beta, eps, out);
+  else
+    hipLaunchKernelGGL(layer_norm_kernel<false>, grid, block, 0, s, x, M, d, gamma, beta, eps, out);
+  return hipGetLastError();
+}
+
+__global__ void half_to_float_kernel(const _Float16 *in, float *out, long n) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = (float)in[i];
+}
+hipError_t launch_half_to_float(const _Float16 *in, float *out, long n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(half_to_float_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, in, out, n);
+  return hipGetLastError();
+}
+
+__global__ void fill_i32_kernel(int32_t *p, long n, int32_t v) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+hipError_t launch_fill_i32(int32_t *p, long n, int32_t v, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n, v);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void step_begin_kernel(StepBeginArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= a.rows_prev) return;
+  int y = a.bos_id;
+  if (a.t > 0 && a.pk) {
+    unsigned long long k = 0ull;
+    const unsigned long long *p = a.pk + (long)r * a.n_partials;
+    for (int i = lane; i < a.n_partials; i += 64) {
+      unsigned long long c = p[i];
+      k = c > k ? c : k;
+    }
+    k = wave_max_u64(k);
+    y = (int)(0xFFFFFFFFu - (unsigned int)k);
+    if (y < 0 || y >= a.vocab) y = a.pad_id;  // cannot happen: every partial holds a valid id
+    if (lane == 0) a.out[(long)r * a.out_ld + a.t - 1] = y;
+  }
+  if (r >= a.rows_now) return;
+  if (a.forced) {
+    y = a.forced[(long)r * a.forced_ld + a.t];
+    if (y < 0 || y >= a.vocab) {
+      if (lane == 0) a.flags[0] = 1;
+      y = a.pad_id;
+    }
+  }
+  const int d = a.d, ne = d >> 6;
+  const float sc = sqrtf((float)d);
+  const _Float16 *e = a.E + (long)y * d;
+  const float *p = a.pe + (long)a.t * d;
+  float v[MAX_PER_LANE];
+#pragma unroll
+  for (int i = 0; i < MAX_PER_LANE; i++)
+    if (i < ne) {
+      v[i] = sc * (float)e[lane + 64 * i] + p[lane + 64 * i];
+      a.z[(long)r * d + lane + 64 * i] = v[i];
+    }
+  row_layer_norm(v, ne, d, a.eps, lane, a.gamma, a.beta);
+#pragma unroll
+  for (int i = 0; i < MAX_PER_LANE; i++)
+    if (i < ne) a.a[(long)r * d + lane + 64 * i] = v[i];
+}
+
+hipError_t launch_step_begin(const StepBeginArgs &a, hipStream_t s) {
+  if (a.rows_prev <= 0) return hipSuccess;
+  hipLaunchKernelGGL(step_begin_kernel, dim3((a.rows_prev + 3) / 4), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace nt
