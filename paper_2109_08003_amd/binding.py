@@ -40,6 +40,9 @@ def load_library() -> C.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise FileNotFoundError(f"{LIB_PATH} is not built: run python -m paper_2109_08003_amd.build")
+    # torch ships its own HIP runtime (same soname); import it first so that libnt.so binds to
+    # that copy instead of bringing a second runtime into the process
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     p, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     cfgp = C.POINTER(NtConfig)
