@@ -14,6 +14,8 @@
 // Relative position keys (Sec. 2.1, clip distance c): score_ij += q_i . rk[clamp(j-i,-c,c)+c].
 #include <math.h>
 
+#include <type_traits>
+
 #include "nt_kernels.h"
 
 namespace nt {
@@ -26,26 +28,45 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // ---------------------------------------------------------------------------------------
 constexpr int QT = 32;        // queries per workgroup
 constexpr int MAX_CLIP = 16;  // relative-position clip distance supported
+constexpr float LO_SCALE = 2048.f, LO_INV = 1.f / 2048.f;
 
 static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
-size_t enc_attention_lds_bytes(int S, int dh) {
-  const int SP = round_up(S, 32);
-  return (size_t)QT * (dh + 8) * 2 + (size_t)QT * (SP + 1) * 4 + (size_t)QT * (SP + 8) * 2 +
+// F32 mode keeps q, k, v, the probabilities and the context at ~22 bits through the fp16 MFMA
+// units: every operand x is split into hi = fp16(x) and lo = fp16((x - hi) * 2^11), and a
+// product a.b is evaluated as a_hi.b_hi + (a_lo.b_hi + a_hi.b_lo) * 2^-11 with the two parts in
+// separate fp32 accumulators.
+size_t enc_attention_lds_bytes(int S, int dh, bool f32) {
+  const int SP = round_up(S, 32), n = f32 ? 2 : 1;
+  return (size_t)n * QT * (dh + 8) * 2 + (size_t)QT * (SP + 1) * 4 + (size_t)n * QT * (SP + 8) * 2 +
          (size_t)QT * (2 * MAX_CLIP + 1) * 4;
 }
 
-template <int DH>
-__global__ __launch_bounds__(256) void enc_attention_kernel(const _Float16 *qkv, const int32_t *len, _Float16 *ctx,
-                                                            int S, int d, const float *rk, int clip) {
+__device__ __forceinline__ void split8(const float *f, half8 &hi, half8 &lo) {
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+    hi[e] = (_Float16)f[e];
+    lo[e] = (_Float16)((f[e] - (float)hi[e]) * LO_SCALE);
+  }
+}
+
+template <int DH, bool F32>
+__global__ __launch_bounds__(256) void enc_attention_kernel(const void *qkv_, const int32_t *len, void *ctx_, int S,
+                                                            int d, const float *rk, int clip) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  typedef typename std::conditional<F32, float, _Float16>::type T;
+  const T *qkv = (const T *)qkv_;
+  T *ctx = (T *)ctx_;
   const int SP = (S + 31) / 32 * 32;
   constexpr int QLD = DH + 8;
+  constexpr int NQ = F32 ? 2 : 1;
   const int SLD = SP + 1, PLD = SP + 8;
-  _Float16 *sQ = (_Float16 *)smem;  // [QT][QLD]; reused for the V block in phase 3
-  float *sS = (float *)(smem + (size_t)QT * QLD * 2);
-  _Float16 *sP = (_Float16 *)((unsigned char *)sS + (size_t)QT * SLD * 4);
-  float *sR = (float *)((unsigned char *)sP + (size_t)QT * PLD * 2);  // [QT][2*MAX_CLIP+1] q . rk
+  _Float16 *sQh = (_Float16 *)smem;  // [QT][QLD]; reused for the V block in phase 3
+  _Float16 *sQl = sQh + (F32 ? QT * QLD : 0);
+  float *sS = (float *)(smem + (size_t)NQ * QT * QLD * 2);
+  _Float16 *sPh = (_Float16 *)((unsigned char *)sS + (size_t)QT * SLD * 4);
+  _Float16 *sPl = sPh + (F32 ? QT * PLD : 0);
+  float *sR = (float *)((unsigned char *)sPh + (size_t)NQ * QT * PLD * 2);  // [QT][2*MAX_CLIP+1] q . rk
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, g = lane >> 5;
   const int b = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * QT;
@@ -55,9 +76,9 @@ __global__ __launch_bounds__(256) void enc_attention_kernel(const _Float16 *qkv,
   const int hoff = h * DH;
 
   if (q0 >= L) {  // padding queries: defined output, no work
-    for (int i = tid; i < QT * (DH / 8); i += 256) {
-      int r = i / (DH / 8), c = i % (DH / 8);
-      if (q0 + r < S) *(uint4 *)(ctx + (row0 + q0 + r) * d + hoff + c * 8) = make_uint4(0, 0, 0, 0);
+    for (int i = tid; i < QT * DH; i += 256) {
+      int r = i / DH, c = i % DH;
+      if (q0 + r < S) ctx[(row0 + q0 + r) * d + hoff + c] = (T)0.f;
     }
     return;
   }
@@ -67,7 +88,18 @@ __global__ __launch_bounds__(256) void enc_attention_kernel(const _Float16 *qkv,
   for (int i = tid; i < QT * (DH / 8); i += 256) {
     int r = i / (DH / 8), c = i % (DH / 8);
     int qr = min(q0 + r, S - 1);
-    *(uint4 *)(sQ + r * QLD + c * 8) = *(const uint4 *)(qkv + (row0 + qr) * ld + hoff + c * 8);
+    const T *src = qkv + (row0 + qr) * ld + hoff + c * 8;
+    if (F32) {
+      float f[8];
+      *(float4 *)f = *(const float4 *)src;
+      *(float4 *)(f + 4) = *(const float4 *)(src + 4);
+      half8 hi, lo;
+      split8(f, hi, lo);
+      *(half8 *)(sQh + r * QLD + c * 8) = hi;
+      *(half8 *)(sQl + r * QLD + c * 8) = lo;
+    } else {
+      *(uint4 *)(sQh + r * QLD + c * 8) = *(const uint4 *)src;
+    }
   }
   __syncthreads();
 
@@ -76,30 +108,49 @@ __global__ __launch_bounds__(256) void enc_attention_kernel(const _Float16 *qkv,
     for (int i = tid; i < QT * nrel; i += 256) {
       int r = i / nrel, o = i % nrel;
       float acc = 0.f;
-      for (int e = 0; e < DH; e++) acc += (float)sQ[r * QLD + e] * rk[o * DH + e];
+      for (int e = 0; e < DH; e++) {
+        float qv = (float)sQh[r * QLD + e];
+        if (F32) qv += (float)sQl[r * QLD + e] * LO_INV;
+        acc += qv * rk[o * DH + e];
+      }
       sR[r * (2 * MAX_CLIP + 1) + o] = acc;
     }
     __syncthreads();
   }
 
-  // phase 1: scores.  Each lane streams 64 bytes of its key row per 64-wide k chunk straight
-  // from global memory (every key element is used once per query tile, so LDS would add nothing);
-  // lane group g takes k in [c*64 + g*32, +32) and the query fragment uses the same assignment.
+  // phase 1: scores.  Each lane streams its key row straight from global memory, 32 consecutive
+  // k per 64-wide chunk (every key element is used once per query tile, so LDS would add
+  // nothing); lane group g takes k in [c*64 + g*32, +32) and the query fragment uses the same
+  // assignment.
   for (int kb = wave; kb < nkb; kb += 4) {
-    floatx16 acc;
+    floatx16 acc, accx;
 #pragma unroll
-    for (int v = 0; v < 16; v++) acc[v] = 0.f;
+    for (int v = 0; v < 16; v++) acc[v] = accx[v] = 0.f;
     const int key = min(kb * 32 + li, S - 1);
-    const _Float16 *kp = qkv + (row0 + key) * ld + d + hoff + g * 32;
+    const T *kp = qkv + (row0 + key) * ld + d + hoff + g * 32;
 #pragma unroll 2
     for (int c = 0; c < DH / 64; c++) {
-      half8 kr[4];
+      half8 kh[4], kl[4];
+      if (F32) {
+        float f[32];
 #pragma unroll
-      for (int u = 0; u < 4; u++) kr[u] = *(const half8 *)(kp + c * 64 + u * 8);
+        for (int u = 0; u < 8; u++) *(float4 *)(f + 4 * u) = *(const float4 *)(kp + c * 64 + u * 4);
+#pragma unroll
+        for (int u = 0; u < 4; u++) split8(f + 8 * u, kh[u], kl[u]);
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; u++) kh[u] = *(const half8 *)(kp + c * 64 + u * 8);
+      }
 #pragma unroll
       for (int u = 0; u < 4; u++) {
-        half8 a = *(const half8 *)(sQ + li * QLD + c * 64 + g * 32 + u * 8);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, kr[u], acc, 0, 0, 0);
+        const int qo = li * QLD + c * 64 + g * 32 + u * 8;
+        half8 a = *(const half8 *)(sQh + qo);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, kh[u], acc, 0, 0, 0);
+        if (F32) {
+          half8 al = *(const half8 *)(sQl + qo);
+          accx = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, kh[u], accx, 0, 0, 0);
+          accx = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, kl[u], accx, 0, 0, 0);
+        }
       }
     }
     const int j = kb * 32 + li;
@@ -107,6 +158,7 @@ __global__ __launch_bounds__(256) void enc_attention_kernel(const _Float16 *qkv,
     for (int v = 0; v < 16; v++) {
       const int i = (v >> 2) * 8 + g * 4 + (v & 3);
       float s = acc[v];
+      if (F32) s += accx[v] * LO_INV;
       if (rk) {
         int rel = j - (q0 + i);
         rel = max(-clip, min(clip, rel));
@@ -126,45 +178,70 @@ __global__ __launch_bounds__(256) void enc_attention_kernel(const _Float16 *qkv,
     for (int m = 4; m >= 1; m >>= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
     float sum = 0.f;
     for (int j = sub; j < nk; j += 8) {
-      float e = __expf(sS[i * SLD + j] - mx);
+      float e = F32 ? expf(sS[i * SLD + j] - mx) : __expf(sS[i * SLD + j] - mx);
       sS[i * SLD + j] = e;
       sum += e;
     }
 #pragma unroll
     for (int m = 4; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, 64);
     const float inv = 1.f / sum;
-    for (int j = sub; j < nk; j += 8) sP[i * PLD + j] = (_Float16)(sS[i * SLD + j] * inv);
+    for (int j = sub; j < nk; j += 8) {
+      const float pv = sS[i * SLD + j] * inv;
+      const _Float16 hi = (_Float16)pv;
+      sPh[i * PLD + j] = hi;
+      if (F32) sPl[i * PLD + j] = (_Float16)((pv - (float)hi) * LO_SCALE);
+    }
   }
 
   // phase 3: context = P V.  The V block is staged in LDS in its natural [key][col] layout and
   // the MFMA operand (8 keys of one column) is gathered with 16-bit LDS reads.
   constexpr int NCB = (DH >= 128) ? DH / 128 : 1;  // 32-column blocks per wave
   constexpr int ACTIVE = (DH / 32 < 4) ? DH / 32 : 4;
-  floatx16 o[NCB];
+  floatx16 o[NCB], ox[NCB];
 #pragma unroll
   for (int cb = 0; cb < NCB; cb++)
 #pragma unroll
-    for (int v = 0; v < 16; v++) o[cb][v] = 0.f;
-  _Float16 *sV = sQ;
+    for (int v = 0; v < 16; v++) o[cb][v] = ox[cb][v] = 0.f;
+  _Float16 *sVh = sQh, *sVl = sQl;
   for (int kb = 0; kb < nkb; kb++) {
     __syncthreads();  // sQ / previous V block no longer read; sP complete (first pass)
     for (int i = tid; i < 32 * (DH / 8); i += 256) {
       int r = i / (DH / 8), c = i % (DH / 8);
       int key = min(kb * 32 + r, S - 1);
-      *(uint4 *)(sV + r * QLD + c * 8) = *(const uint4 *)(qkv + (row0 + key) * ld + 2 * d + hoff + c * 8);
+      const T *src = qkv + (row0 + key) * ld + 2 * d + hoff + c * 8;
+      if (F32) {
+        float f[8];
+        *(float4 *)f = *(const float4 *)src;
+        *(float4 *)(f + 4) = *(const float4 *)(src + 4);
+        half8 hi, lo;
+        split8(f, hi, lo);
+        *(half8 *)(sVh + r * QLD + c * 8) = hi;
+        *(half8 *)(sVl + r * QLD + c * 8) = lo;
+      } else {
+        *(uint4 *)(sVh + r * QLD + c * 8) = *(const uint4 *)src;
+      }
     }
     __syncthreads();
     if (wave < ACTIVE) {
 #pragma unroll
       for (int ks = 0; ks < 2; ks++) {
-        half8 a = *(const half8 *)(sP + li * PLD + kb * 32 + ks * 16 + g * 8);
+        const int po = li * PLD + kb * 32 + ks * 16 + g * 8;
+        half8 a = *(const half8 *)(sPh + po), al;
+        if (F32) al = *(const half8 *)(sPl + po);
 #pragma unroll
         for (int cb = 0; cb < NCB; cb++) {
           const int col = (wave * NCB + cb) * 32 + li;
-          half8 bv;
+          half8 bv, bl;
 #pragma unroll
-          for (int e = 0; e < 8; e++) bv[e] = sV[(ks * 16 + g * 8 + e) * QLD + col];
+          for (int e = 0; e < 8; e++) {
+            bv[e] = sVh[(ks * 16 + g * 8 + e) * QLD + col];
+            if (F32) bl[e] = sVl[(ks * 16 + g * 8 + e) * QLD + col];
+          }
           o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bv, o[cb], 0, 0, 0);
+          if (F32) {
+            ox[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bv, ox[cb], 0, 0, 0);
+            ox[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bl, ox[cb], 0, 0, 0);
+          }
         }
       }
     }
@@ -176,39 +253,46 @@ __global__ __launch_bounds__(256) void enc_attention_kernel(const _Float16 *qkv,
 #pragma unroll
       for (int v = 0; v < 16; v++) {
         const int q = q0 + (v >> 2) * 8 + g * 4 + (v & 3);
-        if (q < S) ctx[(row0 + q) * d + hoff + col] = (q < L) ? (_Float16)o[cb][v] : (_Float16)0.f;
+        float val = o[cb][v];
+        if (F32) val += ox[cb][v] * LO_INV;
+        if (q < S) ctx[(row0 + q) * d + hoff + col] = (q < L) ? (T)val : (T)0.f;
       }
     }
   }
 }
 
-template <int DH>
-static hipError_t enc_attention_launch(const _Float16 *qkv, const int32_t *len, _Float16 *ctx, int B, int S, int d,
-                                       int heads, const float *rk, int clip, hipStream_t s) {
+template <int DH, bool F32>
+static hipError_t enc_attention_launch(const void *qkv, const int32_t *len, void *ctx, int B, int S, int d, int heads,
+                                       const float *rk, int clip, hipStream_t s) {
   static size_t configured = 0;
-  size_t lds = enc_attention_lds_bytes(S, DH);
+  size_t lds = enc_attention_lds_bytes(S, DH, F32);
   if (lds > configured) {
-    hipError_t e = hipFuncSetAttribute((const void *)enc_attention_kernel<DH>,
+    hipError_t e = hipFuncSetAttribute((const void *)enc_attention_kernel<DH, F32>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     configured = lds;
   }
   dim3 grid((S + QT - 1) / QT, heads, B), block(256);
-  hipLaunchKernelGGL(enc_attention_kernel<DH>, grid, block, lds, s, qkv, len, ctx, S, d, rk, clip);
+  hipLaunchKernelGGL((enc_attention_kernel<DH, F32>), grid, block, lds, s, qkv, len, ctx, S, d, rk, clip);
   return hipGetLastError();
 }
 
-hipError_t launch_enc_attention(const _Float16 *qkv, const int32_t *len, _Float16 *ctx, int B, int S, int d,
+hipError_t launch_enc_attention(const void *qkv, bool f32, const int32_t *len, void *ctx, int B, int S, int d,
                                 int heads, const float *rk, int clip, hipStream_t s) {
   if (B <= 0 || S <= 0) return hipSuccess;
   if (clip > MAX_CLIP) return hipErrorInvalidValue;
+#define NT_ATTN_CASE(DH)                                                                                   \
+  case DH:                                                                                                 \
+    return f32 ? enc_attention_launch<DH, true>(qkv, len, ctx, B, S, d, heads, rk, clip, s)                \
+               : enc_attention_launch<DH, false>(qkv, len, ctx, B, S, d, heads, rk, clip, s);
   switch (d / heads) {
-    case 64: return enc_attention_launch<64>(qkv, len, ctx, B, S, d, heads, rk, clip, s);
-    case 128: return enc_attention_launch<128>(qkv, len, ctx, B, S, d, heads, rk, clip, s);
-    case 256: return enc_attention_launch<256>(qkv, len, ctx, B, S, d, heads, rk, clip, s);
-    case 512: return enc_attention_launch<512>(qkv, len, ctx, B, S, d, heads, rk, clip, s);
+    NT_ATTN_CASE(64)
+    NT_ATTN_CASE(128)
+    NT_ATTN_CASE(256)
+    NT_ATTN_CASE(512)
     default: return hipErrorInvalidValue;
   }
+#undef NT_ATTN_CASE
 }
 
 // ---------------------------------------------------------------------------------------

@@ -35,6 +35,15 @@ int fail(int code, const char *fmt, ...) {
     if (_e != hipSuccess) return fail(NT_EHIP, "%s: %s", #expr, hipGetErrorString(_e));    \
   } while (0)
 
+// Precision plan.  The greedy arg-max is decided by logit gaps that are often below 1e-2, so
+// activations are kept at fp32 in HBM and enter the fp16 MFMA units split into head + tail.
+//   kEncF32:   encoder LayerNorm output, q/k/v, attention context and encoder output are fp32.
+//   kCrossF32: the cross-attention key/value cache is fp32 (else fp16).
+// The decoder side (activations and self-attention cache) is always fp32.
+constexpr bool kEncF32 = true;
+constexpr bool kCrossF32 = false;
+constexpr size_t kEncElt = kEncF32 ? 4 : 2, kCrossElt = kCrossF32 ? 4 : 2;
+
 struct LN {
   const float *g = nullptr, *b = nullptr;
 };
@@ -78,12 +87,12 @@ struct nt_model {
   char *d_arena = nullptr;
   size_t arena_bytes = 0;
   float *x = nullptr;          // [Mt,d]  encoder residual stream
-  _Float16 *a16 = nullptr;     // [Mt,d]  LayerNorm output
-  _Float16 *qkv = nullptr;     // [Mt,3d]
-  _Float16 *ctx16 = nullptr;   // [Mt,d]
-  _Float16 *u16 = nullptr;     // [Mt,F]
-  _Float16 *enc_out = nullptr; // [Mt,d]
-  std::vector<_Float16 *> cross;  // per decoder layer [Mt,2d]
+  void *a_enc = nullptr;       // [Mt,d]  LayerNorm output          (fp32 if kEncF32 else fp16)
+  void *qkv = nullptr;         // [Mt,3d]
+  void *ctx_enc = nullptr;     // [Mt,d]
+  void *u_enc = nullptr;       // [Mt,F]
+  void *enc_out = nullptr;     // [Mt,d]
+  std::vector<void *> cross;   // per decoder layer [Mt,2d]    (fp32 if kCrossF32 else fp16)
   std::vector<float *> self_kv;   // per decoder layer [self_positions, 2d]
   float *z = nullptr, *a32 = nullptr, *q32 = nullptr, *ctx32 = nullptr, *u32 = nullptr;  // [Br, d|F]
   unsigned long long *pk = nullptr;
@@ -96,10 +105,6 @@ struct nt_model {
 };
 
 namespace {
-
-struct ConfigCheck {
-  int code;
-};
 
 int check_config(const nt_config *c) {
   if (!c) return fail(NT_EINVAL, "config is null");
@@ -208,7 +213,7 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
   if (cfg->max_batch_tokens < 1) return fail(NT_EINVAL, "max_batch_tokens must be >= 1");
   if (cfg->max_batch_rows < 0) return fail(NT_EINVAL, "max_batch_rows must be >= 0");
   const int d = cfg->d_model, V = cfg->vocab, F = cfg->d_ffn, H = cfg->n_heads, dh = d / H, c = cfg->rpr_clip;
-  if (nt::enc_attention_lds_bytes(cfg->max_len, dh) > 160 * 1024) return fail(NT_ESHAPE, "max_len %d with head width %d exceeds the LDS plan", cfg->max_len, dh);
+  if (nt::enc_attention_lds_bytes(cfg->max_len, dh, kEncF32) > 160 * 1024) return fail(NT_ESHAPE, "max_len %d with head width %d exceeds the LDS plan", cfg->max_len, dh);
 
   nt_model *m = new nt_model();
   struct Guard {
@@ -320,11 +325,11 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
     m->pk_elems = worst;
   }
   Carver cv;
-  const size_t o_x = cv.take((size_t)Mt * d * 4), o_a16 = cv.take((size_t)Mt * d * 2), o_qkv = cv.take((size_t)Mt * 3 * d * 2),
-               o_ctx16 = cv.take((size_t)Mt * d * 2), o_u16 = cv.take((size_t)Mt * std::max(F, 1) * 2),
-               o_enc = cv.take((size_t)Mt * d * 2);
+  const size_t o_x = cv.take((size_t)Mt * d * 4), o_a16 = cv.take((size_t)Mt * d * kEncElt),
+               o_qkv = cv.take((size_t)Mt * 3 * d * kEncElt), o_ctx16 = cv.take((size_t)Mt * d * kEncElt),
+               o_u16 = cv.take((size_t)Mt * std::max(F, 1) * kEncElt), o_enc = cv.take((size_t)Mt * d * kEncElt);
   std::vector<size_t> o_cross(cfg->n_dec), o_self(cfg->n_dec);
-  for (int l = 0; l < cfg->n_dec; l++) o_cross[l] = cv.take((size_t)Mt * 2 * d * 2);
+  for (int l = 0; l < cfg->n_dec; l++) o_cross[l] = cv.take((size_t)Mt * 2 * d * kCrossElt);
   for (int l = 0; l < cfg->n_dec; l++) o_self[l] = cv.take((size_t)m->self_positions * 2 * d * 4);
   const size_t o_z = cv.take((size_t)Br * d * 4), o_a32 = cv.take((size_t)Br * d * 4), o_q32 = cv.take((size_t)Br * d * 4),
                o_ctx32 = cv.take((size_t)Br * d * 4), o_u32 = cv.take((size_t)Br * std::max(F, 1) * 4),
@@ -333,9 +338,9 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
   m->arena_bytes = cv.off;
   if (hipMalloc((void **)&m->d_arena, m->arena_bytes) != hipSuccess) return fail(NT_ENOMEM, "hipMalloc of %zu arena bytes failed", m->arena_bytes);
   char *A = m->d_arena;
-  m->x = at<float>(A, o_x); m->a16 = at<_Float16>(A, o_a16); m->qkv = at<_Float16>(A, o_qkv);
-  m->ctx16 = at<_Float16>(A, o_ctx16); m->u16 = at<_Float16>(A, o_u16); m->enc_out = at<_Float16>(A, o_enc);
-  for (int l = 0; l < cfg->n_dec; l++) { m->cross.push_back(at<_Float16>(A, o_cross[l])); m->self_kv.push_back(at<float>(A, o_self[l])); }
+  m->x = at<float>(A, o_x); m->a_enc = A + o_a16; m->qkv = A + o_qkv;
+  m->ctx_enc = A + o_ctx16; m->u_enc = A + o_u16; m->enc_out = A + o_enc;
+  for (int l = 0; l < cfg->n_dec; l++) { m->cross.push_back(A + o_cross[l]); m->self_kv.push_back(at<float>(A, o_self[l])); }
   m->z = at<float>(A, o_z); m->a32 = at<float>(A, o_a32); m->q32 = at<float>(A, o_q32); m->ctx32 = at<float>(A, o_ctx32);
   m->u32 = at<float>(A, o_u32); m->pk = at<unsigned long long>(A, o_pk); m->len = at<int32_t>(A, o_len);
   m->flags = at<int32_t>(A, o_flags); m->d_src = at<int32_t>(A, o_src); m->d_len_in = at<int32_t>(A, o_lin);
@@ -366,29 +371,29 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
   m->encoded = false;
   HIP_TRY(nt::launch_embed_src(d_src, d_len, m->len, B, S, d, c.vocab, c.pad_id, m->E, m->pe, m->x, m->flags, s));
   for (auto &L : m->enc) {
-    HIP_TRY(nt::launch_layer_norm(m->x, M, d, L.ln1.g, L.ln1.b, c.ln_eps, m->a16, false, s));
+    HIP_TRY(nt::launch_layer_norm(m->x, M, d, L.ln1.g, L.ln1.b, c.ln_eps, m->a_enc, kEncF32, s));
     nt::GemmEpilogue e;
     e.bias = L.self.bqkv; e.scale = qscale; e.scale_cols = d; e.dst0 = m->qkv; e.ld0 = 3 * d; e.n_split = 3 * d;
-    HIP_TRY(nt::launch_gemm(false, false, m->a16, d, L.self.Wqkv, M, 3 * d, d, e, s));
-    HIP_TRY(nt::launch_enc_attention(m->qkv, m->len, m->ctx16, B, S, d, H, L.self.rk, c.rpr_clip, s));
+    HIP_TRY(nt::launch_gemm(kEncF32, kEncF32, m->a_enc, d, L.self.Wqkv, M, 3 * d, d, e, s));
+    HIP_TRY(nt::launch_enc_attention(m->qkv, kEncF32, m->len, m->ctx_enc, B, S, d, H, L.self.rk, c.rpr_clip, s));
     nt::GemmEpilogue o;
     o.bias = L.self.bo; o.resid = m->x; o.ldr = d; o.dst0 = m->x; o.ld0 = d; o.n_split = d;
-    HIP_TRY(nt::launch_gemm(false, true, m->ctx16, d, L.self.Wo, M, d, d, o, s));
+    HIP_TRY(nt::launch_gemm(kEncF32, true, m->ctx_enc, d, L.self.Wo, M, d, d, o, s));
     if (F > 0) {
-      HIP_TRY(nt::launch_layer_norm(m->x, M, d, L.ln2.g, L.ln2.b, c.ln_eps, m->a16, false, s));
+      HIP_TRY(nt::launch_layer_norm(m->x, M, d, L.ln2.g, L.ln2.b, c.ln_eps, m->a_enc, kEncF32, s));
       nt::GemmEpilogue f1;
-      f1.bias = L.ffn.b1; f1.relu = 1; f1.dst0 = m->u16; f1.ld0 = F; f1.n_split = F;
-      HIP_TRY(nt::launch_gemm(false, false, m->a16, d, L.ffn.W1, M, F, d, f1, s));
+      f1.bias = L.ffn.b1; f1.relu = 1; f1.dst0 = m->u_enc; f1.ld0 = F; f1.n_split = F;
+      HIP_TRY(nt::launch_gemm(kEncF32, kEncF32, m->a_enc, d, L.ffn.W1, M, F, d, f1, s));
       nt::GemmEpilogue f2;
       f2.bias = L.ffn.b2; f2.resid = m->x; f2.ldr = d; f2.dst0 = m->x; f2.ld0 = d; f2.n_split = d;
-      HIP_TRY(nt::launch_gemm(false, true, m->u16, F, L.ffn.W2, M, d, F, f2, s));
+      HIP_TRY(nt::launch_gemm(kEncF32, true, m->u_enc, F, L.ffn.W2, M, d, F, f2, s));
     }
   }
-  HIP_TRY(nt::launch_layer_norm(m->x, M, d, m->enc_final.g, m->enc_final.b, c.ln_eps, m->enc_out, false, s));
+  HIP_TRY(nt::launch_layer_norm(m->x, M, d, m->enc_final.g, m->enc_final.b, c.ln_eps, m->enc_out, kEncF32, s));
   for (int l = 0; l < c.n_dec; l++) {
     nt::GemmEpilogue e;
     e.bias = m->dec[l].cross.bkv; e.dst0 = m->cross[l]; e.ld0 = 2 * d; e.n_split = 2 * d;
-    HIP_TRY(nt::launch_gemm(false, false, m->enc_out, d, m->dec[l].cross.Wkv, M, 2 * d, d, e, s));
+    HIP_TRY(nt::launch_gemm(kEncF32, kCrossF32, m->enc_out, d, m->dec[l].cross.Wkv, M, 2 * d, d, e, s));
   }
   m->B = B; m->S = S; m->encoded = true;
   return NT_OK;
@@ -449,7 +454,7 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
         nt::GemmEpilogue e;
         e.bias = L.cross.bq; e.scale = qscale; e.scale_cols = d; e.dst0 = m->q32; e.ld0 = d; e.n_split = d;
         HIP_TRY(nt::launch_gemm(true, true, m->a32, d, L.cross.Wq, R, d, d, e, s));
-        HIP_TRY(nt::launch_attn_decode(m->q32, m->cross[l], false, (long)S * 2 * d, m->len, 0, R, d, H, nullptr, 0, 0,
+        HIP_TRY(nt::launch_attn_decode(m->q32, m->cross[l], kCrossF32, (long)S * 2 * d, m->len, 0, R, d, H, nullptr, 0, 0,
                                        m->ctx32, s));
         nt::GemmEpilogue o;
         o.bias = L.cross.bo; o.resid = m->z; o.ldr = d; o.dst0 = m->z; o.ld0 = d; o.n_split = d;
@@ -519,7 +524,11 @@ int nt_debug_teacher_forced_logits(nt_model *m, const int32_t *d_tgt_in, int32_t
 int nt_debug_encoder_out(nt_model *m, float *d_out, void *hip_stream) {
   if (!m || !d_out) return fail(NT_EINVAL, "null argument");
   if (!m->encoded) return fail(NT_ESTATE, "no encoded batch");
-  HIP_TRY(nt::launch_half_to_float(m->enc_out, d_out, (long)m->B * m->S * m->c.d_model, as_stream(hip_stream)));
+  const long n = (long)m->B * m->S * m->c.d_model;
+  if (kEncF32)
+    HIP_TRY(hipMemcpyAsync(d_out, m->enc_out, (size_t)n * 4, hipMemcpyDeviceToDevice, as_stream(hip_stream)));
+  else
+    HIP_TRY(nt::launch_half_to_float((const _Float16 *)m->enc_out, d_out, n, as_stream(hip_stream)));
   return NT_OK;
 }
 

@@ -74,10 +74,10 @@ struct StepBeginArgs {
 hipError_t launch_step_begin(const StepBeginArgs &a, hipStream_t s);
 
 // ---- attention ------------------------------------------------------------------------
-// Encoder self-attention on a padded batch.  qkv [B*S, 3d] fp16 (q already scaled | k | v),
-// len [B]; ctx [B*S, d] fp16.  Keys >= len get weight exactly 0; query rows >= len get 0.
-// rk: optional relative-position keys [2*clip+1, dh] fp32.
-hipError_t launch_enc_attention(const _Float16 *qkv, const int32_t *len, _Float16 *ctx, int B, int S, int d,
+// Encoder self-attention on a padded batch.  qkv [B*S, 3d] (q already scaled | k | v),
+// len [B]; ctx [B*S, d]; both fp32 when f32 (split-precision MFMA), else fp16.  Keys >= len get
+// weight exactly 0; query rows >= len get 0.  rk: optional relative-position keys [2*clip+1, dh].
+hipError_t launch_enc_attention(const void *qkv, bool f32, const int32_t *len, void *ctx, int B, int S, int d,
                                 int heads, const float *rk, int clip, hipStream_t s);
 
 // Single-query attention against a cache, one query per (row, head).
@@ -91,6 +91,6 @@ hipError_t launch_attn_decode(const float *q, const void *kv, bool kv_f32, long 
                               float *ctx, hipStream_t s);
 
 // max dynamic LDS the encoder attention needs for (S, dh); used to validate shapes at load.
-size_t enc_attention_lds_bytes(int S, int dh);
+size_t enc_attention_lds_bytes(int S, int dh, bool f32);
 
 }  // namespace nt

@@ -223,7 +223,7 @@ def test_c1_full_workload_sampled_against_oracle(nt, oracle):
     om = oracle.Model(cfg, blob)
     rng = np.random.default_rng(123)
     longest = np.argsort(-lens)[:4]
-    sample = np.unique(np.concatenate([rng.choice(len(lens), size=252, replace=False), longest]))
+    sample = np.unique(np.concatenate([rng.choice(len(lens), size=508, replace=False), longest]))
     sents = [tokens[offsets[i]:offsets[i + 1]] for i in sample]
     sub_tok = np.concatenate(sents)
     sub_off = np.concatenate([[0], np.cumsum([len(s) for s in sents])])
