@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Throughput benchmark: source words/s of greedy translation on one MI355X.
+
+A "step" is one pass of the whole hot path over the workload: every length-sorted,
+token-budgeted batch is encoded and greedily decoded (all kernels of the path), with the padded
+batches already resident in HBM when the timed region starts and the outputs left in HBM.
+Prints ONE JSON line.  Also reports, outside the timed region: the host-inclusive rate of
+nt_translate_batch (batching + H2D + D2H + un-sort), a per-kernel table measured with HIP
+events on the launch stream, the roofline fraction of the dominant kernel and the CPU oracle's
+rate on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import nt_synth  # noqa: E402
+
+WORDS_PER_TOKEN = 1.0 / 1.3          # the benchmark's convention: 1 word = 1.3 tokens
+HBM_PEAK_GBS = 8000.0                # MI355X HBM3E
+MFMA_F16_PEAK_TFLOPS = 2500.0        # dense fp16 MFMA
+# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs (see profiles/); None until measured for the workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C1", choices=["C1", "C2", "C3", "C4"])
+    ap.add_argument("--sentences", type=int, default=None, help="default: the workload's own count")
+    ap.add_argument("--budget", type=int, default=4096, help="token budget per batch")
+    ap.add_argument("--cpu-sentences", type=int, default=1024, help="oracle sample size (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; sentences are independent, so more GPUs would each take a "
+              "shard of the sorted batch list with no communication (not built). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2109_08003_amd as nt
+    nt.load_library()
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+
+    cfg = nt_synth.model_config(args.workload)
+    blob = nt_synth.make_weights(cfg, seed=0)
+    tokens, offsets = nt_synth.workload(args.workload, args.sentences)
+    lens = np.diff(offsets).astype(np.int32)
+    n_sent, src_tokens = len(lens), int(offsets[-1])
+    model = nt.Model(cfg, blob, max_batch_tokens=args.budget)
+
+    # ---- batches resident in HBM (untimed set-up) ----
+    order, starts = nt.plan_batches(lens, args.budget)
+    batches = []
+    for k in range(len(starts) - 1):
+        idx = order[starts[k]:starts[k + 1]]
+        B, S = len(idx), int(lens[idx[0]])
+        ids = np.full((B, S), cfg["pad_id"], dtype=np.int32)
+        for r, i in enumerate(idx):
+            ids[r, : lens[i]] = tokens[offsets[i]:offsets[i + 1]]
+        steps = np.array([nt.n_steps(int(lens[i])) for i in idx], dtype=np.int32)
+        T = int(steps[0])
+        batches.append(dict(idx=idx, B=B, T=T, steps=steps, d_src=torch.from_numpy(ids).cuda(),
+                            d_len=torch.from_numpy(lens[idx]).cuda(),
+                            d_out=torch.empty((B, T), dtype=torch.int32, device="cuda")))
+    tgt_tokens = int(sum(b["steps"].sum() for b in batches))
+    dec_steps = int(sum(b["T"] for b in batches))
+
+    def one_pass():
+        for b in batches:
+            model.encode(b["d_src"], b["d_len"])
+            model.decode_greedy(b["B"], b["T"], b["d_out"], row_steps=b["steps"])
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_pass()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / max(args.steps, 1)
+    words_per_s = src_tokens * WORDS_PER_TOKEN / dt
+
+    # ---- same work through the host-facing entry point (PCIe and batching included) ----
+    out, oo = model.translate_batch(tokens, offsets, args.budget)
+    t0 = time.perf_counter()
+    for _ in range(max(1, min(args.steps, 3))):
+        out, oo = model.translate_batch(tokens, offsets, args.budget)
+    dt_host = (time.perf_counter() - t0) / max(1, min(args.steps, 3))
+    # the two routes must produce the same translations
+    for b in batches:
+        got = b["d_out"].cpu().numpy()
+        for r, i in enumerate(b["idx"]):
+            assert np.array_equal(got[r, : b["steps"][r]], out[oo[i]:oo[i + 1]]), "device and host routes disagree"
+
+    # ---- per-kernel timing with HIP events on the launch stream (separate, instrumented pass) ----
+    model.timing_enable("all")
+    model.translate_batch(tokens, offsets, args.budget)
+    kern = model.timing_read()
+    model.timing_enable(None)
+    table = {}
+    for name, k in kern.items():
+        avg_us = 1e3 * k["ms"] / k["launches"]
+        table[name] = dict(launches=k["launches"], total_ms=round(k["ms"], 3), avg_us=round(avg_us, 2),
+                           GBps=round(k["bytes"] / k["ms"] / 1e6, 1), TFLOPs=round(k["flops"] / k["ms"] / 1e9, 2))
+    dom = max(kern, key=lambda n: kern[n]["ms"])
+    k = kern[dom]
+    intensity = k["flops"] / k["bytes"]
+    if intensity > MFMA_F16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
+        bound, achieved, peak, unit = "mfma", k["flops"] / k["ms"] / 1e9, MFMA_F16_PEAK_TFLOPS, "TFLOP/s"
+    else:
+        bound, achieved, peak, unit = "hbm", k["bytes"] / k["ms"] / 1e6, HBM_PEAK_GBS, "GB/s"
+    roofline = dict(kernel=dom, bound=bound, achieved=round(achieved, 2), peak=peak, unit=unit,
+                    frac=round(achieved / peak, 4), traffic=MEASURED_TRAFFIC_BYTES.get((dom, args.workload, args.budget)),
+                    avg_launch_us=round(1e3 * k["ms"] / k["launches"], 2), launches=k["launches"],
+                    algorithmic_bytes_per_launch=round(k["bytes"] / k["launches"]),
+                    algorithmic_flops_per_launch=round(k["flops"] / k["launches"]))
+
+    # ---- CPU oracle on a bounded sample of the same workload ----
+    cpu = None
+    if args.cpu_sentences > 0:
+        from oracle import nt_oracle
+        n = min(args.cpu_sentences, n_sent)
+        om = nt_oracle.Model(cfg, blob)
+        t0 = time.perf_counter()
+        _, _, used = om.translate(tokens[: offsets[n]], offsets[: n + 1])
+        dt_cpu = time.perf_counter() - t0
+        cpu = dict(value=round(int(offsets[n]) * WORDS_PER_TOKEN / dt_cpu, 1), unit="source words/s", cores=used,
+                   kind="oracle", sample=f"first {n} sentences of the {args.workload} draw ({int(offsets[n])} source "
+                                         f"tokens), {dt_cpu:.1f} s")
+
+    print(json.dumps({
+        "metric": "source words/sec (greedy decode, 1 MI355X)",
+        "value": round(words_per_s, 1), "unit": "words/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(1e3 * dt, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {n_sent} sentences (lognormal lengths, Zipf ids), student "
+                               f"{cfg['n_enc']}-{cfg['n_dec']} d={cfg['d_model']} heads={cfg['n_heads']} ffn={cfg['d_ffn']} "
+                               f"V={cfg['vocab']}, greedy ceil(1.2 len)+2 steps",
+                   "token_budget": args.budget, "batches": len(batches), "source_tokens": src_tokens,
+                   "target_tokens": tgt_tokens, "decode_steps": dec_steps},
+        "source_tokens_per_s": round(src_tokens / dt, 1), "target_tokens_per_s": round(tgt_tokens / dt, 1),
+        "host_inclusive_words_per_s": round(src_tokens * WORDS_PER_TOKEN / dt_host, 1),
+        "paper_context": "247,000 words/s on one NVIDIA A100 (different model, data and harness; context only)",
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": table,
+    }))
+
+
+if __name__ == "__main__":
+    main()

@@ -176,6 +176,22 @@ int nt_debug_teacher_forced_logits(nt_model *m, const int32_t *d_tgt_in, int32_t
  */
 int nt_check_device_flags(nt_model *m, void *hip_stream);
 
+/*
+ * Per-launch kernel timing for measurement (off by default; it adds two event records per
+ * timed launch).  kernel_mask has one bit per kernel family, ids 0 .. nt_debug_timing_count()-1,
+ * names from nt_debug_timing_name().  Enabling (or re-enabling) clears what was recorded.
+ * nt_debug_timing_read synchronises the stream and returns, for one family, the summed
+ * event-to-event time of its launches, their number, and the summed algorithmic bytes and
+ * flops of those launches (the minimum traffic / arithmetic the operation needs at its shape:
+ * operands read once, results written once).  Cross-attention bytes are exact when the batch
+ * came through nt_translate_batch (host lengths known) and use the padded length otherwise.
+ */
+int nt_debug_timing_enable(nt_model *m, uint64_t kernel_mask);
+int nt_debug_timing_count(void);
+const char *nt_debug_timing_name(int kernel);
+int nt_debug_timing_read(nt_model *m, int kernel, double *total_ms, int64_t *launches, double *bytes, double *flops,
+                         void *hip_stream);
+
 /* Bytes of device memory held by the model (weights, arena, caches). */
 int64_t nt_device_bytes(const nt_model *m);
 

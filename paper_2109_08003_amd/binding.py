@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libnt.so")
 
 EXPORTS = ["nt_param_count", "nt_n_steps", "nt_load_weights", "nt_free", "nt_encode", "nt_decode_greedy",
            "nt_translate_batch", "nt_plan_batches", "nt_debug_encoder_out", "nt_debug_teacher_forced_logits",
-           "nt_check_device_flags", "nt_device_bytes", "nt_last_error"]
+           "nt_check_device_flags", "nt_device_bytes", "nt_last_error", "nt_debug_timing_enable",
+           "nt_debug_timing_count", "nt_debug_timing_name", "nt_debug_timing_read"]
 
 
 class NtConfig(C.Structure):
@@ -60,6 +61,11 @@ def load_library() -> C.CDLL:
         "nt_check_device_flags": (C.c_int, [p, p]),
         "nt_device_bytes": (i64, [p]),
         "nt_last_error": (C.c_char_p, []),
+        "nt_debug_timing_enable": (C.c_int, [p, C.c_uint64]),
+        "nt_debug_timing_count": (C.c_int, []),
+        "nt_debug_timing_name": (C.c_char_p, [C.c_int]),
+        "nt_debug_timing_read": (C.c_int, [p, C.c_int, C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(C.c_double),
+                                           C.POINTER(C.c_double), p]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -108,6 +114,11 @@ def plan_batches(lengths, budget: int, max_rows: int = 0):
     _check(lib().nt_plan_batches(lengths.ctypes.data_as(C.c_void_p), N, int(budget), int(max_rows),
                                  order.ctypes.data_as(C.c_void_p), starts.ctypes.data_as(C.c_void_p), C.byref(nb)))
     return order[:N], starts[: nb.value + 1]
+
+
+def kernel_names() -> list:
+    L = lib()
+    return [L.nt_debug_timing_name(i).decode() for i in range(L.nt_debug_timing_count())]
 
 
 def _stream_ptr(stream) -> int:
@@ -170,6 +181,28 @@ class Model:
 
     def check_device_flags(self, stream=None):
         _check(lib().nt_check_device_flags(self._h, _stream_ptr(stream)))
+
+    def timing_enable(self, kernels="all"):
+        """kernels: "all", None/() to switch off, or an iterable of family names."""
+        names = kernel_names()
+        if kernels == "all":
+            mask = (1 << len(names)) - 1
+        else:
+            mask = 0
+            for k in kernels or ():
+                mask |= 1 << names.index(k)
+        _check(lib().nt_debug_timing_enable(self._h, mask))
+
+    def timing_read(self, stream=None) -> dict:
+        """name -> dict(ms, launches, bytes, flops) for every family with at least one launch."""
+        res = {}
+        for i, name in enumerate(kernel_names()):
+            ms, n, by, fl = C.c_double(), C.c_int64(), C.c_double(), C.c_double()
+            _check(lib().nt_debug_timing_read(self._h, i, C.byref(ms), C.byref(n), C.byref(by), C.byref(fl),
+                                              _stream_ptr(stream)))
+            if n.value:
+                res[name] = dict(ms=ms.value, launches=n.value, bytes=by.value, flops=fl.value)
+        return res
 
     def translate_batch(self, tokens, offsets, token_budget: int, max_rows: int = 0, stream=None):
         """Host arrays in, host arrays out: returns (out int32, out_offsets int64)."""

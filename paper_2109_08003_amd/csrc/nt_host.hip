@@ -44,6 +44,22 @@ constexpr bool kEncF32 = true;
 constexpr bool kCrossF32 = false;
 constexpr size_t kEncElt = kEncF32 ? 4 : 2, kCrossElt = kCrossF32 ? 4 : 2;
 
+// Launch `call`; when timing of family `id` is on, bracket it with two events on the stream and
+// note the algorithmic bytes and flops of this launch.
+#define KT(id, nbytes, nflops, call)                                              \
+  do {                                                                            \
+    if (m->timing.mask & (1ull << (id))) {                                        \
+      hipEvent_t _e0 = m->timing.get(), _e1 = m->timing.get();                    \
+      if (!_e0 || !_e1) return fail(NT_EHIP, "hipEventCreate failed");            \
+      m->timing.recs.push_back({(id), m->timing.used - 2, (double)(nbytes), (double)(nflops)}); \
+      HIP_TRY(hipEventRecord(_e0, s));                                            \
+      HIP_TRY(call);                                                              \
+      HIP_TRY(hipEventRecord(_e1, s));                                            \
+    } else {                                                                      \
+      HIP_TRY(call);                                                              \
+    }                                                                             \
+  } while (0)
+
 struct LN {
   const float *g = nullptr, *b = nullptr;
 };
@@ -70,10 +86,39 @@ struct DecLayer {
   FFN ffn;
 };
 
+// Kernel families for the optional per-launch timing (HIP events on the launch stream).
+enum KernelId {
+  K_EMBED_SRC, K_LN_ENC, K_GEMM_ENC_QKV, K_ATTN_ENC, K_GEMM_ENC_O, K_GEMM_ENC_FFN, K_GEMM_CROSS_KV,
+  K_STEP_BEGIN, K_LN_DEC, K_GEMM_DEC_QKV, K_ATTN_DEC_SELF, K_GEMM_DEC_O, K_GEMM_DEC_Q, K_ATTN_DEC_CROSS,
+  K_GEMM_DEC_FFN, K_VOCAB_ARGMAX, K_GEMM_LOGITS, K_COUNT
+};
+const char *const kKernelNames[K_COUNT] = {
+  "embed_src", "layer_norm_enc", "gemm_enc_qkv", "attention_enc", "gemm_enc_o", "gemm_enc_ffn", "gemm_cross_kv",
+  "step_begin", "layer_norm_dec", "gemm_dec_qkv", "attn_decode_self", "gemm_dec_o", "gemm_dec_q", "attn_decode_cross",
+  "gemm_dec_ffn", "vocab_argmax", "gemm_logits"};
+
+struct Timing {
+  uint64_t mask = 0;  // bit per KernelId; 0 = off
+  std::vector<hipEvent_t> pool;
+  size_t used = 0;
+  struct Rec { int id; size_t e0; double bytes, flops; };
+  std::vector<Rec> recs;
+  hipEvent_t get() {
+    if (used == pool.size()) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) return nullptr;
+      pool.push_back(e);
+    }
+    return pool[used++];
+  }
+};
+
 }  // namespace
 
 struct nt_model {
   nt_config c{};
+  Timing timing;
+  std::vector<int64_t> len_prefix;  // host prefix sums of the batch's lengths (timing only), may be empty
   int64_t max_tokens = 0, max_rows = 0, self_positions = 0, pk_elems = 0;
   // device weights (one allocation)
   char *d_w = nullptr;
@@ -198,6 +243,7 @@ void nt_free(nt_model *m) {
   if (m->h_src) (void)hipHostFree(m->h_src);
   if (m->h_len) (void)hipHostFree(m->h_len);
   if (m->h_out) (void)hipHostFree(m->h_out);
+  for (hipEvent_t e : m->timing.pool) (void)hipEventDestroy(e);
   delete m;
 }
 
@@ -369,32 +415,47 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
   const int d = c.d_model, F = c.d_ffn, H = c.n_heads, M = B * S;
   const float qscale = 1.0f / std::sqrt((float)(d / H));
   m->encoded = false;
-  HIP_TRY(nt::launch_embed_src(d_src, d_len, m->len, B, S, d, c.vocab, c.pad_id, m->E, m->pe, m->x, m->flags, s));
+  const double Md = (double)M, dd = (double)d, ea = (double)kEncElt, ca = (double)kCrossElt;
+  KT(K_EMBED_SRC, Md * (4 + dd * 10), 2 * Md * dd,
+     nt::launch_embed_src(d_src, d_len, m->len, B, S, d, c.vocab, c.pad_id, m->E, m->pe, m->x, m->flags, s));
+  auto gemm_bytes = [&](double rows, double k, double n, double a_elt, double c_elt, bool resid) {
+    return rows * k * a_elt + n * k * 2 + rows * n * c_elt + (resid ? rows * n * 4 : 0.0);
+  };
   for (auto &L : m->enc) {
-    HIP_TRY(nt::launch_layer_norm(m->x, M, d, L.ln1.g, L.ln1.b, c.ln_eps, m->a_enc, kEncF32, s));
+    KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
+       nt::launch_layer_norm(m->x, M, d, L.ln1.g, L.ln1.b, c.ln_eps, m->a_enc, kEncF32, s));
     nt::GemmEpilogue e;
     e.bias = L.self.bqkv; e.scale = qscale; e.scale_cols = d; e.dst0 = m->qkv; e.ld0 = 3 * d; e.n_split = 3 * d;
-    HIP_TRY(nt::launch_gemm(kEncF32, kEncF32, m->a_enc, d, L.self.Wqkv, M, 3 * d, d, e, s));
-    HIP_TRY(nt::launch_enc_attention(m->qkv, kEncF32, m->len, m->ctx_enc, B, S, d, H, L.self.rk, c.rpr_clip, s));
+    KT(K_GEMM_ENC_QKV, gemm_bytes(Md, dd, 3 * dd, ea, ea, false), 6 * Md * dd * dd,
+       nt::launch_gemm(kEncF32, kEncF32, m->a_enc, d, L.self.Wqkv, M, 3 * d, d, e, s));
+    KT(K_ATTN_ENC, Md * 4 * dd * ea, 4.0 * B * S * S * dd,
+       nt::launch_enc_attention(m->qkv, kEncF32, m->len, m->ctx_enc, B, S, d, H, L.self.rk, c.rpr_clip, s));
     nt::GemmEpilogue o;
     o.bias = L.self.bo; o.resid = m->x; o.ldr = d; o.dst0 = m->x; o.ld0 = d; o.n_split = d;
-    HIP_TRY(nt::launch_gemm(kEncF32, true, m->ctx_enc, d, L.self.Wo, M, d, d, o, s));
+    KT(K_GEMM_ENC_O, gemm_bytes(Md, dd, dd, ea, 4, true), 2 * Md * dd * dd,
+       nt::launch_gemm(kEncF32, true, m->ctx_enc, d, L.self.Wo, M, d, d, o, s));
     if (F > 0) {
-      HIP_TRY(nt::launch_layer_norm(m->x, M, d, L.ln2.g, L.ln2.b, c.ln_eps, m->a_enc, kEncF32, s));
+      KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
+         nt::launch_layer_norm(m->x, M, d, L.ln2.g, L.ln2.b, c.ln_eps, m->a_enc, kEncF32, s));
       nt::GemmEpilogue f1;
       f1.bias = L.ffn.b1; f1.relu = 1; f1.dst0 = m->u_enc; f1.ld0 = F; f1.n_split = F;
-      HIP_TRY(nt::launch_gemm(kEncF32, kEncF32, m->a_enc, d, L.ffn.W1, M, F, d, f1, s));
+      KT(K_GEMM_ENC_FFN, gemm_bytes(Md, dd, F, ea, ea, false), 2 * Md * dd * F,
+         nt::launch_gemm(kEncF32, kEncF32, m->a_enc, d, L.ffn.W1, M, F, d, f1, s));
       nt::GemmEpilogue f2;
       f2.bias = L.ffn.b2; f2.resid = m->x; f2.ldr = d; f2.dst0 = m->x; f2.ld0 = d; f2.n_split = d;
-      HIP_TRY(nt::launch_gemm(kEncF32, true, m->u_enc, F, L.ffn.W2, M, d, F, f2, s));
+      KT(K_GEMM_ENC_FFN, gemm_bytes(Md, F, dd, ea, 4, true), 2 * Md * dd * F,
+         nt::launch_gemm(kEncF32, true, m->u_enc, F, L.ffn.W2, M, d, F, f2, s));
     }
   }
-  HIP_TRY(nt::launch_layer_norm(m->x, M, d, m->enc_final.g, m->enc_final.b, c.ln_eps, m->enc_out, kEncF32, s));
+  KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
+     nt::launch_layer_norm(m->x, M, d, m->enc_final.g, m->enc_final.b, c.ln_eps, m->enc_out, kEncF32, s));
   for (int l = 0; l < c.n_dec; l++) {
     nt::GemmEpilogue e;
     e.bias = m->dec[l].cross.bkv; e.dst0 = m->cross[l]; e.ld0 = 2 * d; e.n_split = 2 * d;
-    HIP_TRY(nt::launch_gemm(kEncF32, kCrossF32, m->enc_out, d, m->dec[l].cross.Wkv, M, 2 * d, d, e, s));
+    KT(K_GEMM_CROSS_KV, gemm_bytes(Md, dd, 2 * dd, ea, ca, false), 4 * Md * dd * dd,
+       nt::launch_gemm(kEncF32, kCrossF32, m->enc_out, d, m->dec[l].cross.Wkv, M, 2 * d, d, e, s));
   }
+  m->len_prefix.clear();
   m->B = B; m->S = S; m->encoded = true;
   return NT_OK;
 }
@@ -423,6 +484,10 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
     return lo;
   };
   int partials_prev = 0;
+  const double dd = (double)d, ca = (double)kCrossElt;
+  auto gemm_bytes = [&](double rows, double k, double n, bool resid) {
+    return rows * k * 4 + n * k * 2 + rows * n * 4 + (resid ? rows * n * 4 : 0.0);
+  };
   for (int t = 0; t <= T; t++) {
     const int rows_now = rows_at(t), rows_prev = (t == 0) ? rows_now : rows_at(t - 1);
     if (rows_prev == 0) break;
@@ -432,52 +497,69 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
     a.forced = d_forced; a.forced_ld = T; a.E = m->E; a.pe = m->pe; a.gamma = m->dec[0].ln1.g; a.beta = m->dec[0].ln1.b;
     a.eps = c.ln_eps; a.z = m->z; a.a = m->a32; a.flags = m->flags;
     if (d_logits && rows_now == 0) break;  // no tokens to collect in this mode (pk == nullptr)
-    HIP_TRY(nt::launch_step_begin(a, s));
+    KT(K_STEP_BEGIN, rows_prev * (partials_prev * 8.0 + 4) + rows_now * dd * 14, rows_now * dd * 10,
+       nt::launch_step_begin(a, s));
     if (rows_now == 0) break;
     const int R = rows_now;
+    const double Rd = (double)R;
+    // source tokens attended by the active rows (exact when the host knows the lengths)
+    const double cross_keys = (m->len_prefix.size() > (size_t)R) ? (double)m->len_prefix[(size_t)R] : Rd * S;
     for (int l = 0; l < c.n_dec; l++) {
       const DecLayer &L = m->dec[l];
-      if (l > 0) HIP_TRY(nt::launch_layer_norm(m->z, R, d, L.ln1.g, L.ln1.b, c.ln_eps, m->a32, true, s));
+      if (l > 0)
+        KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd, nt::launch_layer_norm(m->z, R, d, L.ln1.g, L.ln1.b, c.ln_eps, m->a32, true, s));
       {  // self-attention: q (scaled) to q32, k|v appended to the cache at position t
         nt::GemmEpilogue e;
         e.bias = L.self.bqkv; e.scale = qscale; e.scale_cols = d; e.dst0 = m->q32; e.ld0 = d; e.n_split = d;
         e.dst1 = m->self_kv[l] + (long)t * 2 * d; e.ld1 = self_stride;
-        HIP_TRY(nt::launch_gemm(true, true, m->a32, d, L.self.Wqkv, R, 3 * d, d, e, s));
-        HIP_TRY(nt::launch_attn_decode(m->q32, m->self_kv[l], true, self_stride, nullptr, t + 1, R, d, H, L.self.rk,
-                                       c.rpr_clip, t, m->ctx32, s));
+        KT(K_GEMM_DEC_QKV, gemm_bytes(Rd, dd, 3 * dd, false), 6 * Rd * dd * dd,
+           nt::launch_gemm(true, true, m->a32, d, L.self.Wqkv, R, 3 * d, d, e, s));
+        KT(K_ATTN_DEC_SELF, Rd * (t + 1) * 2 * dd * 4 + Rd * dd * 8, 4 * Rd * (t + 1) * dd,
+           nt::launch_attn_decode(m->q32, m->self_kv[l], true, self_stride, nullptr, t + 1, R, d, H, L.self.rk,
+                                  c.rpr_clip, t, m->ctx32, s));
         nt::GemmEpilogue o;
         o.bias = L.self.bo; o.resid = m->z; o.ldr = d; o.dst0 = m->z; o.ld0 = d; o.n_split = d;
-        HIP_TRY(nt::launch_gemm(true, true, m->ctx32, d, L.self.Wo, R, d, d, o, s));
+        KT(K_GEMM_DEC_O, gemm_bytes(Rd, dd, dd, true), 2 * Rd * dd * dd,
+           nt::launch_gemm(true, true, m->ctx32, d, L.self.Wo, R, d, d, o, s));
       }
       {  // cross-attention over the encoder keys/values
-        HIP_TRY(nt::launch_layer_norm(m->z, R, d, L.ln2.g, L.ln2.b, c.ln_eps, m->a32, true, s));
+        KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd, nt::launch_layer_norm(m->z, R, d, L.ln2.g, L.ln2.b, c.ln_eps, m->a32, true, s));
         nt::GemmEpilogue e;
         e.bias = L.cross.bq; e.scale = qscale; e.scale_cols = d; e.dst0 = m->q32; e.ld0 = d; e.n_split = d;
-        HIP_TRY(nt::launch_gemm(true, true, m->a32, d, L.cross.Wq, R, d, d, e, s));
-        HIP_TRY(nt::launch_attn_decode(m->q32, m->cross[l], kCrossF32, (long)S * 2 * d, m->len, 0, R, d, H, nullptr, 0, 0,
-                                       m->ctx32, s));
+        KT(K_GEMM_DEC_Q, gemm_bytes(Rd, dd, dd, false), 2 * Rd * dd * dd,
+           nt::launch_gemm(true, true, m->a32, d, L.cross.Wq, R, d, d, e, s));
+        KT(K_ATTN_DEC_CROSS, cross_keys * 2 * dd * ca + Rd * dd * 8, 4 * cross_keys * dd,
+           nt::launch_attn_decode(m->q32, m->cross[l], kCrossF32, (long)S * 2 * d, m->len, 0, R, d, H, nullptr, 0, 0,
+                                  m->ctx32, s));
         nt::GemmEpilogue o;
         o.bias = L.cross.bo; o.resid = m->z; o.ldr = d; o.dst0 = m->z; o.ld0 = d; o.n_split = d;
-        HIP_TRY(nt::launch_gemm(true, true, m->ctx32, d, L.cross.Wo, R, d, d, o, s));
+        KT(K_GEMM_DEC_O, gemm_bytes(Rd, dd, dd, true), 2 * Rd * dd * dd,
+           nt::launch_gemm(true, true, m->ctx32, d, L.cross.Wo, R, d, d, o, s));
       }
       if (F > 0) {
-        HIP_TRY(nt::launch_layer_norm(m->z, R, d, L.ln3.g, L.ln3.b, c.ln_eps, m->a32, true, s));
+        KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd, nt::launch_layer_norm(m->z, R, d, L.ln3.g, L.ln3.b, c.ln_eps, m->a32, true, s));
         nt::GemmEpilogue f1;
         f1.bias = L.ffn.b1; f1.relu = 1; f1.dst0 = m->u32; f1.ld0 = F; f1.n_split = F;
-        HIP_TRY(nt::launch_gemm(true, true, m->a32, d, L.ffn.W1, R, F, d, f1, s));
+        KT(K_GEMM_DEC_FFN, gemm_bytes(Rd, dd, F, false), 2 * Rd * dd * F,
+           nt::launch_gemm(true, true, m->a32, d, L.ffn.W1, R, F, d, f1, s));
         nt::GemmEpilogue f2;
         f2.bias = L.ffn.b2; f2.resid = m->z; f2.ldr = d; f2.dst0 = m->z; f2.ld0 = d; f2.n_split = d;
-        HIP_TRY(nt::launch_gemm(true, true, m->u32, F, L.ffn.W2, R, d, F, f2, s));
+        KT(K_GEMM_DEC_FFN, gemm_bytes(Rd, F, dd, true), 2 * Rd * dd * F,
+           nt::launch_gemm(true, true, m->u32, F, L.ffn.W2, R, d, F, f2, s));
       }
     }
-    HIP_TRY(nt::launch_layer_norm(m->z, R, d, m->dec_final.g, m->dec_final.b, c.ln_eps, m->a32, true, s));
+    KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd,
+       nt::launch_layer_norm(m->z, R, d, m->dec_final.g, m->dec_final.b, c.ln_eps, m->a32, true, s));
     if (d_logits) {
       nt::GemmEpilogue e;
       e.dst0 = d_logits + (long)t * V; e.ld0 = (long)T * V; e.n_split = V;
-      HIP_TRY(nt::launch_gemm(true, true, m->a32, d, m->Wout, R, V, d, e, s));
+      KT(K_GEMM_LOGITS, gemm_bytes(Rd, dd, V, false), 2 * Rd * dd * V,
+         nt::launch_gemm(true, true, m->a32, d, m->Wout, R, V, d, e, s));
     } else {
-      HIP_TRY(nt::launch_vocab_argmax(m->a32, d, m->Wout, R, V, d, m->pk, s));
-      partials_prev = nt::vocab_argmax_partials(R, V);
+      const int np_ = nt::vocab_argmax_partials(R, V);
+      KT(K_VOCAB_ARGMAX, (double)V * dd * 2 + Rd * dd * 4 + Rd * np_ * 8, 2 * Rd * dd * V,
+         nt::launch_vocab_argmax(m->a32, d, m->Wout, R, V, d, m->pk, s));
+      partials_prev = np_;
     }
   }
   return NT_OK;
@@ -541,6 +623,33 @@ int nt_check_device_flags(nt_model *m, void *hip_stream) {
   if (f) {
     HIP_TRY(nt::launch_fill_i32(m->flags, 1, 0, s));
     return fail(NT_ERANGE, "a kernel clamped an out-of-range token id or length");
+  }
+  return NT_OK;
+}
+
+int nt_debug_timing_enable(nt_model *m, uint64_t kernel_mask) {
+  if (!m) return fail(NT_EINVAL, "model is null");
+  m->timing.mask = kernel_mask & ((1ull << K_COUNT) - 1);
+  m->timing.used = 0;
+  m->timing.recs.clear();
+  return NT_OK;
+}
+
+int nt_debug_timing_count(void) { return K_COUNT; }
+
+const char *nt_debug_timing_name(int kernel) { return (kernel >= 0 && kernel < K_COUNT) ? kKernelNames[kernel] : ""; }
+
+int nt_debug_timing_read(nt_model *m, int kernel, double *total_ms, int64_t *launches, double *bytes, double *flops,
+                         void *hip_stream) {
+  if (!m || !total_ms || !launches || !bytes || !flops) return fail(NT_EINVAL, "null argument");
+  if (kernel < 0 || kernel >= K_COUNT) return fail(NT_EINVAL, "kernel id out of range");
+  HIP_TRY(hipStreamSynchronize(as_stream(hip_stream)));
+  *total_ms = 0; *launches = 0; *bytes = 0; *flops = 0;
+  for (const auto &r : m->timing.recs) {
+    if (r.id != kernel) continue;
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, m->timing.pool[r.e0], m->timing.pool[r.e0 + 1]));
+    *total_ms += ms; *launches += 1; *bytes += r.bytes; *flops += r.flops;
   }
   return NT_OK;
 }
@@ -624,6 +733,10 @@ int nt_translate_batch(nt_model *m, const int32_t *h_tokens, const int64_t *h_of
     HIP_TRY(hipMemcpyAsync(m->d_len_in, m->h_len, (size_t)B * 4, hipMemcpyHostToDevice, s));
     rc = nt_encode(m, m->d_src, m->d_len_in, B, S, s);
     if (rc) return rc;
+    if (m->timing.mask) {
+      m->len_prefix.assign((size_t)B + 1, 0);
+      for (int32_t r = 0; r < B; r++) m->len_prefix[(size_t)r + 1] = m->len_prefix[(size_t)r] + m->h_len[r];
+    }
     rc = nt_decode_greedy(m, B, T, row_steps.data(), m->d_out, s);
     if (rc) return rc;
     HIP_TRY(hipMemcpyAsync(m->h_out, m->d_out, (size_t)B * T * 4, hipMemcpyDeviceToHost, s));
