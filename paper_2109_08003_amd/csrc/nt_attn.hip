@@ -51,12 +51,13 @@ __device__ __forceinline__ void split8(const float *f, half8 &hi, half8 &lo) {
 }
 
 template <int DH, bool F32>
-__global__ __launch_bounds__(256) void enc_attention_kernel(const void *qkv_, const int32_t *len, void *ctx_, int S,
-                                                            int d, const float *rk, int clip) {
+__global__ __launch_bounds__(256) void enc_attention_kernel(const void *qkv_, const int32_t *len, void *ctx_,
+                                                            long ctx_lo_offset, int S, int d, const float *rk,
+                                                            int clip) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   typedef typename std::conditional<F32, float, _Float16>::type T;
   const T *qkv = (const T *)qkv_;
-  T *ctx = (T *)ctx_;
+  _Float16 *ctx = (_Float16 *)ctx_;  // F32: head plane, tail plane ctx_lo_offset elements later
   const int SP = (S + 31) / 32 * 32;
   constexpr int QLD = DH + 8;
   constexpr int NQ = F32 ? 2 : 1;
@@ -78,7 +79,10 @@ __global__ __launch_bounds__(256) void enc_attention_kernel(const void *qkv_, co
   if (q0 >= L) {  // padding queries: defined output, no work
     for (int i = tid; i < QT * DH; i += 256) {
       int r = i / DH, c = i % DH;
-      if (q0 + r < S) ctx[(row0 + q0 + r) * d + hoff + c] = (T)0.f;
+      if (q0 + r < S) {
+        ctx[(row0 + q0 + r) * d + hoff + c] = (_Float16)0.f;
+        if (F32) ctx[(row0 + q0 + r) * d + hoff + c + ctx_lo_offset] = (_Float16)0.f;
+      }
     }
     return;
   }
@@ -255,15 +259,19 @@ __global__ __launch_bounds__(256) void enc_attention_kernel(const void *qkv_, co
         const int q = q0 + (v >> 2) * 8 + g * 4 + (v & 3);
         float val = o[cb][v];
         if (F32) val += ox[cb][v] * LO_INV;
-        if (q < S) ctx[(row0 + q) * d + hoff + col] = (q < L) ? (T)val : (T)0.f;
+        if (q >= S) continue;
+        if (q >= L) val = 0.f;
+        const _Float16 hi = (_Float16)val;
+        ctx[(row0 + q) * d + hoff + col] = hi;
+        if (F32) ctx[(row0 + q) * d + hoff + col + ctx_lo_offset] = (_Float16)(val - (float)hi);
       }
     }
   }
 }
 
 template <int DH, bool F32>
-static hipError_t enc_attention_launch(const void *qkv, const int32_t *len, void *ctx, int B, int S, int d, int heads,
-                                       const float *rk, int clip, hipStream_t s) {
+static hipError_t enc_attention_launch(const void *qkv, const int32_t *len, void *ctx, long ctx_lo_offset, int B, int S,
+                                       int d, int heads, const float *rk, int clip, hipStream_t s) {
   static size_t configured = 0;
   size_t lds = enc_attention_lds_bytes(S, DH, F32);
   if (lds > configured) {
@@ -273,18 +281,18 @@ static hipError_t enc_attention_launch(const void *qkv, const int32_t *len, void
     configured = lds;
   }
   dim3 grid((S + QT - 1) / QT, heads, B), block(256);
-  hipLaunchKernelGGL((enc_attention_kernel<DH, F32>), grid, block, lds, s, qkv, len, ctx, S, d, rk, clip);
+  hipLaunchKernelGGL((enc_attention_kernel<DH, F32>), grid, block, lds, s, qkv, len, ctx, ctx_lo_offset, S, d, rk, clip);
   return hipGetLastError();
 }
 
-hipError_t launch_enc_attention(const void *qkv, bool f32, const int32_t *len, void *ctx, int B, int S, int d,
-                                int heads, const float *rk, int clip, hipStream_t s) {
+hipError_t launch_enc_attention(const void *qkv, bool f32, const int32_t *len, void *ctx, long ctx_lo_offset, int B,
+                                int S, int d, int heads, const float *rk, int clip, hipStream_t s) {
   if (B <= 0 || S <= 0) return hipSuccess;
   if (clip > MAX_CLIP) return hipErrorInvalidValue;
 #define NT_ATTN_CASE(DH)                                                                                   \
   case DH:                                                                                                 \
-    return f32 ? enc_attention_launch<DH, true>(qkv, len, ctx, B, S, d, heads, rk, clip, s)                \
-               : enc_attention_launch<DH, false>(qkv, len, ctx, B, S, d, heads, rk, clip, s);
+    return f32 ? enc_attention_launch<DH, true>(qkv, len, ctx, ctx_lo_offset, B, S, d, heads, rk, clip, s) \
+               : enc_attention_launch<DH, false>(qkv, len, ctx, 0, B, S, d, heads, rk, clip, s);
   switch (d / heads) {
     NT_ATTN_CASE(64)
     NT_ATTN_CASE(128)

@@ -1,19 +1,25 @@
-// fp16 MFMA GEMM for gfx950 (wave64, v_mfma_f32_32x32x16_f16) and the output projection fused
-// with the row arg-max.
+// fp16 MFMA GEMMs for gfx950 (wave64, v_mfma_f32_32x32x16_f16): the tiled projection kernel,
+// the output projection fused with the row arg-max, and the small-M decoder-step kernel.
 //
 // C[M,N] = A[M,K] * Wt[N,K]^T.  Both operands are K-contiguous, so an MFMA fragment (8
 // consecutive k of one row) is one 16-byte LDS read.  Weights are laid out as Wt at load time
 // (the paper moves its transposes out of the matrix multiplications to the start of decoding,
 // Sec. 3.3 "Graph Optimization").
 //
-// Tile: 128 x 128 x 64 per workgroup of 4 waves (2 x 2), each wave 64 x 64 = 2 x 2 MFMA blocks.
-// Global -> register prefetch of the next K-slab overlaps the MFMAs of the current one.
+// Tile: 128 x 128 x 64 per workgroup of 4 waves (2 x 2), each wave 64 x 64 = 2 x 2 MFMA blocks;
+// the next K-slab is prefetched into registers while the current one is multiplied.  Workgroup
+// ids are mapped to tiles XCD-aware: ids are dealt round-robin to the 8 XCDs (each with its own
+// L2), so every XCD gets its own slice of the longer tile dimension and walks the shorter one
+// fastest - an operand tile is then pulled into one L2 only.
 //
-// fp32 A operand ("split" mode, used on the decoder side): a = hi + lo with hi = fp16(a) and
-// lo = fp16((a - hi) * 2^11); two MFMA passes share the weight fragment and accumulate
-// separately, result = acc_hi + acc_lo * 2^-11.  The tail is pre-scaled so that it stays in
-// fp16's normal range.  This keeps ~22 bits of the activations at fp16 MFMA rate, which the
-// greedy arg-max needs: a single fp16 rounding of the decoder state flips ~1 % of sentences.
+// Split precision: an activation a is carried as head + tail, hi = fp16(a), lo = fp16(a - hi)
+// (about 22 significant bits; the MFMA keeps fp16 subnormal inputs, so the tail needs no
+// scaling).  Both halves are multiplied with the same weight fragment into one fp32
+// accumulator: two MFMA passes instead of the 16x slower fp32 MFMA.  The greedy arg-max needs
+// this: a single fp16 rounding of the decoder state flips about 1 % of sentences.
+//   A_F16    A is one fp16 plane
+//   A_PLANES A is two fp16 planes (head, tail) written by the producing kernel
+//   A_F32    A is fp32 and is split while it is staged into LDS
 #include "nt_kernels.h"
 
 namespace nt {
@@ -21,84 +27,18 @@ namespace nt {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int LDS_LD = BK + 8;  // halfs per LDS row: 144 B, keeps 16-byte alignment, spreads banks
-constexpr float LO_SCALE = 2048.f, LO_INV = 1.f / 2048.f;
+constexpr int LDS_LD = BK + 8;  // halfs per LDS row: 144 B keeps 16-byte alignment and is bank-conflict free
 
-template <bool A_F32>
-struct Tile {
-  // registers holding the next K-slab
-  uint4 ra[A_F32 ? 8 : 4];
-  uint4 rb[4];
-};
-
-template <bool A_F32>
-__device__ __forceinline__ void load_slab(Tile<A_F32> &t, const void *A, long lda, int M, const _Float16 *Wt,
-                                          int N, int K, int m0, int n0, int k0, int tid) {
-  if (A_F32) {
-    const float *Af = (const float *)A;
-#pragma unroll
-    for (int i = 0; i < 8; i++) {
-      int c = tid + 256 * i, row = c >> 4, kc = c & 15;
-      int m = m0 + row;
-      t.ra[i] = (m < M) ? *(const uint4 *)(Af + (long)m * lda + k0 + kc * 4) : make_uint4(0, 0, 0, 0);
-    }
-  } else {
-    const _Float16 *Ah = (const _Float16 *)A;
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-      int c = tid + 256 * i, row = c >> 3, kc = c & 7;
-      int m = m0 + row;
-      t.ra[i] = (m < M) ? *(const uint4 *)(Ah + (long)m * lda + k0 + kc * 8) : make_uint4(0, 0, 0, 0);
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < 4; i++) {
-    int c = tid + 256 * i, row = c >> 3, kc = c & 7;
-    int n = n0 + row;
-    t.rb[i] = (n < N) ? *(const uint4 *)(Wt + (long)n * K + k0 + kc * 8) : make_uint4(0, 0, 0, 0);
-  }
-}
-
-template <bool A_F32>
-__device__ __forceinline__ void store_slab(const Tile<A_F32> &t, _Float16 *sAhi, _Float16 *sAlo, _Float16 *sB,
-                                           int tid) {
-  if (A_F32) {
-#pragma unroll
-    for (int i = 0; i < 8; i++) {
-      int c = tid + 256 * i, row = c >> 4, kc = c & 15;
-      float f[4];
-      *(uint4 *)f = t.ra[i];
-      half4 hi, lo;
-#pragma unroll
-      for (int j = 0; j < 4; j++) {
-        hi[j] = (_Float16)f[j];
-        lo[j] = (_Float16)((f[j] - (float)hi[j]) * LO_SCALE);
-      }
-      *(half4 *)(sAhi + row * LDS_LD + kc * 4) = hi;
-      *(half4 *)(sAlo + row * LDS_LD + kc * 4) = lo;
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-      int c = tid + 256 * i, row = c >> 3, kc = c & 7;
-      *(uint4 *)(sAhi + row * LDS_LD + kc * 8) = t.ra[i];
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < 4; i++) {
-    int c = tid + 256 * i, row = c >> 3, kc = c & 7;
-    *(uint4 *)(sB + row * LDS_LD + kc * 8) = t.rb[i];
-  }
-}
-
-// Accumulate the 128x128 tile at (m0, n0) over the whole K into acc (and acc_lo in split mode).
+// Accumulate the 128x128 tile at (m0, n0) over the whole K.
 // acc[mb][nb][v] is C[row = wm*64 + mb*32 + (v/4)*8 + (lane/32)*4 + v%4][col = wn*64 + nb*32 + lane%32].
-template <bool A_F32>
-__device__ __forceinline__ void mainloop(const void *A, long lda, int M, const _Float16 *Wt, int N, int K, int m0,
-                                         int n0, _Float16 *sAhi, _Float16 *sAlo, _Float16 *sB,
-                                         floatx16 (&acc)[2][2], floatx16 (&acc_lo)[2][2]) {
+// Rows beyond M / N re-read the last valid row (never stored), which keeps the loads branch-free.
+template <int AMODE>
+__device__ __forceinline__ void mainloop(const void *A, const void *A2, long lda, int M, const _Float16 *Wt, int N,
+                                         int K, int m0, int n0, _Float16 *sAhi, _Float16 *sAlo, _Float16 *sB,
+                                         floatx16 (&acc)[2][2]) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave >> 1, wn = wave & 1, li = lane & 31, g = lane >> 5;
 #pragma unroll
@@ -106,26 +46,81 @@ __device__ __forceinline__ void mainloop(const void *A, long lda, int M, const _
 #pragma unroll
     for (int j = 0; j < 2; j++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) {
-        acc[i][j][v] = 0.f;
-        if (A_F32) acc_lo[i][j][v] = 0.f;
+      for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
+  // registers holding the next K-slab
+  constexpr int NRA = (AMODE == A_F16) ? 4 : 8;
+  u32x4 ra[NRA], rb[4];  // native vectors: HIP's uint4 struct is not reliably kept in registers here
+  auto load_slab = [&](int k0) {
+    if constexpr (AMODE == A_F32) {
+      const float *Af = (const float *)A;
+#pragma unroll
+      for (int i = 0; i < 8; i++) {
+        const int c = tid + 256 * i, row = c >> 4, kc = c & 15;
+        const int m = (m0 + row < M) ? m0 + row : M - 1;
+        ra[i] = *(const u32x4 *)(Af + (long)m * lda + k0 + kc * 4);
       }
-  Tile<A_F32> t;
-  load_slab<A_F32>(t, A, lda, M, Wt, N, K, m0, n0, 0, tid);
-  __syncthreads();  // previous users of the LDS tiles are done
-  store_slab<A_F32>(t, sAhi, sAlo, sB, tid);
-  __syncthreads();
+    } else {
+      const _Float16 *Ah = (const _Float16 *)A, *Al = (const _Float16 *)A2;
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+        const int m = (m0 + row < M) ? m0 + row : M - 1;
+        ra[i] = *(const u32x4 *)(Ah + (long)m * lda + k0 + kc * 8);
+        if constexpr (AMODE == A_PLANES) ra[NRA - 4 + i] = *(const u32x4 *)(Al + (long)m * lda + k0 + kc * 8);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+      const int n = (n0 + row < N) ? n0 + row : N - 1;
+      rb[i] = *(const u32x4 *)(Wt + (long)n * K + k0 + kc * 8);
+    }
+  };
+  auto store_slab = [&]() {
+    if constexpr (AMODE == A_F32) {
+#pragma unroll
+      for (int i = 0; i < 8; i++) {
+        const int c = tid + 256 * i, row = c >> 4, kc = c & 15;
+        const float f[4] = {__uint_as_float(ra[i][0]), __uint_as_float(ra[i][1]), __uint_as_float(ra[i][2]),
+                            __uint_as_float(ra[i][3])};
+        half4 hi, lo;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          hi[j] = (_Float16)f[j];
+          lo[j] = (_Float16)(f[j] - (float)hi[j]);
+        }
+        *(half4 *)(sAhi + row * LDS_LD + kc * 4) = hi;
+        *(half4 *)(sAlo + row * LDS_LD + kc * 4) = lo;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+        *(u32x4 *)(sAhi + row * LDS_LD + kc * 8) = ra[i];
+        if constexpr (AMODE == A_PLANES) *(u32x4 *)(sAlo + row * LDS_LD + kc * 8) = ra[NRA - 4 + i];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+      *(u32x4 *)(sB + row * LDS_LD + kc * 8) = rb[i];
+    }
+  };
+  load_slab(0);
   const int nk = K / BK;
   for (int kt = 0; kt < nk; kt++) {
-    if (kt + 1 < nk) load_slab<A_F32>(t, A, lda, M, Wt, N, K, m0, n0, (kt + 1) * BK, tid);
+    __syncthreads();  // the previous slab (or the previous user of the LDS tiles) is done
+    store_slab();
+    if (kt + 1 < nk) load_slab((kt + 1) * BK);
+    __syncthreads();
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ks++) {
       half8 a[2], al[2], b[2];
 #pragma unroll
       for (int mb = 0; mb < 2; mb++) {
-        int off = (wm * 64 + mb * 32 + li) * LDS_LD + ks * 16 + g * 8;
+        const int off = (wm * 64 + mb * 32 + li) * LDS_LD + ks * 16 + g * 8;
         a[mb] = *(const half8 *)(sAhi + off);
-        if (A_F32) al[mb] = *(const half8 *)(sAlo + off);
+        if constexpr (AMODE != A_F16) al[mb] = *(const half8 *)(sAlo + off);
       }
 #pragma unroll
       for (int nb = 0; nb < 2; nb++) b[nb] = *(const half8 *)(sB + (wn * 64 + nb * 32 + li) * LDS_LD + ks * 16 + g * 8);
@@ -134,26 +129,40 @@ __device__ __forceinline__ void mainloop(const void *A, long lda, int M, const _
 #pragma unroll
         for (int nb = 0; nb < 2; nb++) {
           acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[mb], b[nb], acc[mb][nb], 0, 0, 0);
-          if (A_F32) acc_lo[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[mb], b[nb], acc_lo[mb][nb], 0, 0, 0);
+          if constexpr (AMODE != A_F16)
+            acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[mb], b[nb], acc[mb][nb], 0, 0, 0);
         }
-    }
-    __syncthreads();
-    if (kt + 1 < nk) {
-      store_slab<A_F32>(t, sAhi, sAlo, sB, tid);
-      __syncthreads();
     }
   }
 }
 
-template <bool A_F32, bool C_F32>
-__global__ __launch_bounds__(256) void gemm_kernel(const void *A, long lda, const _Float16 *Wt, int M, int N, int K,
-                                                   GemmEpilogue e) {
+// Workgroup id -> (m tile, n tile), XCD-aware.  Returns false for the padding ids of the grid.
+__device__ __forceinline__ bool tile_of(int id, int tiles_m, int tiles_n, int &mt, int &nt_) {
+  const int xcd = id & 7, j = id >> 3;
+  if (tiles_m >= tiles_n) {  // long M (encoder): an A tile stays in one L2, Wt is small
+    mt = (j / tiles_n) * 8 + xcd;
+    nt_ = j % tiles_n;
+    return mt < tiles_m;
+  }
+  nt_ = (j / tiles_m) * 8 + xcd;  // long N (output projection): a Wt tile stays in one L2
+  mt = j % tiles_m;
+  return nt_ < tiles_n;
+}
+static int tile_grid(int tiles_m, int tiles_n) {
+  return tiles_m >= tiles_n ? ((tiles_m + 7) / 8) * 8 * tiles_n : ((tiles_n + 7) / 8) * 8 * tiles_m;
+}
+
+template <int AMODE, bool C_F32>
+__global__ __launch_bounds__(256) void gemm_kernel(const void *A, const void *A2, long lda, const _Float16 *Wt, int M,
+                                                   int N, int K, GemmEpilogue e) {
   __shared__ __attribute__((aligned(16))) _Float16 sAhi[BM * LDS_LD];
-  __shared__ __attribute__((aligned(16))) _Float16 sAlo[A_F32 ? BM * LDS_LD : 8];
+  __shared__ __attribute__((aligned(16))) _Float16 sAlo[AMODE != A_F16 ? BM * LDS_LD : 8];
   __shared__ __attribute__((aligned(16))) _Float16 sB[BN * LDS_LD];
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-  floatx16 acc[2][2], acc_lo[2][2];
-  mainloop<A_F32>(A, lda, M, Wt, N, K, m0, n0, sAhi, sAlo, sB, acc, acc_lo);
+  int mt, nt_;
+  if (!tile_of(blockIdx.x, (M + BM - 1) / BM, (N + BN - 1) / BN, mt, nt_)) return;
+  const int m0 = mt * BM, n0 = nt_ * BN;
+  floatx16 acc[2][2];
+  mainloop<AMODE>(A, A2, lda, M, Wt, N, K, m0, n0, sAhi, sAlo, sB, acc);
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave >> 1, wn = wave & 1, li = lane & 31, g = lane >> 5;
@@ -173,32 +182,33 @@ __global__ __launch_bounds__(256) void gemm_kernel(const void *A, long lda, cons
       for (int v = 0; v < 16; v++) {
         const int m = m0 + wm * 64 + mb * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
         if (m >= M) continue;
-        float val = acc[mb][nb][v];
-        if (A_F32) val += acc_lo[mb][nb][v] * LO_INV;
-        val = (val + bias) * sc;
+        float val = (acc[mb][nb][v] + bias) * sc;
         if (e.relu) val = fmaxf(val, 0.f);
         if (e.resid) val += e.resid[(long)m * e.ldr + n];
-        if (C_F32)
+        if (C_F32) {
           ((float *)dst)[(long)m * ld + nc] = val;
-        else
-          ((_Float16 *)dst)[(long)m * ld + nc] = (_Float16)val;
+        } else {
+          const _Float16 hi = (_Float16)val;
+          ((_Float16 *)dst)[(long)m * ld + nc] = hi;
+          if (e.dst_lo_offset) ((_Float16 *)dst)[(long)m * ld + nc + e.dst_lo_offset] = (_Float16)(val - (float)hi);
+        }
       }
   }
 }
 
-hipError_t launch_gemm(bool a_f32, bool c_f32, const void *A, long lda, const _Float16 *Wt, int M, int N, int K,
-                       const GemmEpilogue &e, hipStream_t s) {
+hipError_t launch_gemm(int a_mode, bool c_f32, const void *A, const void *A_lo, long lda, const _Float16 *Wt, int M,
+                       int N, int K, const GemmEpilogue &e, hipStream_t s) {
   if (M <= 0 || N <= 0) return hipSuccess;
-  dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM), block(256);
-  if (a_f32 && c_f32)
-    hipLaunchKernelGGL((gemm_kernel<true, true>), grid, block, 0, s, A, lda, Wt, M, N, K, e);
-  else if (!a_f32 && c_f32)
-    hipLaunchKernelGGL((gemm_kernel<false, true>), grid, block, 0, s, A, lda, Wt, M, N, K, e);
-  else if (!a_f32 && !c_f32)
-    hipLaunchKernelGGL((gemm_kernel<false, false>), grid, block, 0, s, A, lda, Wt, M, N, K, e);
-  else
-    hipLaunchKernelGGL((gemm_kernel<true, false>), grid, block, 0, s, A, lda, Wt, M, N, K, e);
-  return hipGetLastError();
+  dim3 grid(tile_grid((M + BM - 1) / BM, (N + BN - 1) / BN)), block(256);
+#define NT_GEMM_CASE(MODE, CF)                                                                                  \
+  if (a_mode == MODE && c_f32 == CF) {                                                                          \
+    hipLaunchKernelGGL((gemm_kernel<MODE, CF>), grid, block, 0, s, A, A_lo, lda, Wt, M, N, K, e);               \
+    return hipGetLastError();                                                                                   \
+  }
+  NT_GEMM_CASE(A_F16, false) NT_GEMM_CASE(A_F16, true) NT_GEMM_CASE(A_PLANES, false) NT_GEMM_CASE(A_PLANES, true)
+  NT_GEMM_CASE(A_F32, false) NT_GEMM_CASE(A_F32, true)
+#undef NT_GEMM_CASE
+  return hipErrorInvalidValue;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -249,23 +259,29 @@ int vocab_argmax_partials(int M, int N) {
   return 2 * ((nt_ + tpw - 1) / tpw);
 }
 
-__global__ __launch_bounds__(256) void vocab_argmax_kernel(const float *h, long ldh, const _Float16 *Wt, int M, int N,
-                                                           int K, int tiles_per_wg, int n_partials,
-                                                           unsigned long long *pk) {
+// h: two fp16 planes (head at h, tail at h_lo), [M][ldh].  Workgroup id -> (strip of vocabulary
+// tiles, m tile), XCD-aware with the strips split over the XCDs.
+__global__ __launch_bounds__(256) void vocab_argmax_kernel(const _Float16 *h, const _Float16 *h_lo, long ldh,
+                                                           const _Float16 *Wt, int M, int N, int K, int tiles_per_wg,
+                                                           int n_partials, unsigned long long *pk) {
   __shared__ __attribute__((aligned(16))) _Float16 sAhi[BM * LDS_LD];
   __shared__ __attribute__((aligned(16))) _Float16 sAlo[BM * LDS_LD];
   __shared__ __attribute__((aligned(16))) _Float16 sB[BN * LDS_LD];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave >> 1, wn = wave & 1, li = lane & 31, g = lane >> 5;
-  const int m0 = blockIdx.y * BM;
+  const int tiles_m = (M + BM - 1) / BM, strips = n_partials / 2;
+  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+  const int strip = (j / tiles_m) * 8 + xcd, mt = j % tiles_m;
+  if (strip >= strips) return;
+  const int m0 = mt * BM;
   const int n_tiles = (N + BN - 1) / BN;
   unsigned long long best = 0ull;
   for (int tt = 0; tt < tiles_per_wg; tt++) {
-    const int tile = blockIdx.x * tiles_per_wg + tt;
+    const int tile = strip * tiles_per_wg + tt;
     if (tile >= n_tiles) break;  // uniform over the workgroup
     const int n0 = tile * BN;
-    floatx16 acc[2][2], acc_lo[2][2];
-    mainloop<true>(h, ldh, M, Wt, N, K, m0, n0, sAhi, sAlo, sB, acc, acc_lo);
+    floatx16 acc[2][2];
+    mainloop<A_PLANES>(h, h_lo, ldh, M, Wt, N, K, m0, n0, sAhi, sAlo, sB, acc);
     unsigned long long keys[32];
 #pragma unroll
     for (int mb = 0; mb < 2; mb++)
@@ -275,8 +291,7 @@ __global__ __launch_bounds__(256) void vocab_argmax_kernel(const float *h, long 
 #pragma unroll
         for (int nb = 0; nb < 2; nb++) {
           const int n = n0 + wn * 64 + nb * 32 + li;
-          const float val = acc[mb][nb][v] + acc_lo[mb][nb][v] * LO_INV;
-          const unsigned long long c = (n < N) ? argmax_key(val, n) : 0ull;
+          const unsigned long long c = (n < N) ? argmax_key(acc[mb][nb][v], n) : 0ull;
           k = c > k ? c : k;
         }
         keys[mb * 16 + v] = k;
@@ -291,16 +306,203 @@ __global__ __launch_bounds__(256) void vocab_argmax_kernel(const float *h, long 
   }
   const int mb = li >> 4, v = li & 15;
   const int m = m0 + wm * 64 + mb * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
-  if (m < M) pk[(long)m * n_partials + blockIdx.x * 2 + wn] = best;
+  if (m < M) pk[(long)m * n_partials + strip * 2 + wn] = best;
 }
 
-hipError_t launch_vocab_argmax(const float *h, long ldh, const _Float16 *Wt, int M, int N, int K,
-                               unsigned long long *pk, hipStream_t s) {
+hipError_t launch_vocab_argmax(const _Float16 *h, const _Float16 *h_lo, long ldh, const _Float16 *Wt, int M, int N,
+                               int K, unsigned long long *pk, hipStream_t s) {
   if (M <= 0) return hipSuccess;
   const int tpw = vocab_tiles_per_wg(M, N), np = vocab_argmax_partials(M, N);
-  dim3 grid(np / 2, (M + BM - 1) / BM), block(256);
-  hipLaunchKernelGGL(vocab_argmax_kernel, grid, block, 0, s, h, ldh, Wt, M, N, K, tpw, np, pk);
+  const int tiles_m = (M + BM - 1) / BM, strips = np / 2;
+  dim3 grid(((strips + 7) / 8) * 8 * tiles_m), block(256);
+  hipLaunchKernelGGL(vocab_argmax_kernel, grid, block, 0, s, h, h_lo, ldh, Wt, M, N, K, tpw, np, pk);
   return hipGetLastError();
+}
+
+}  // namespace nt
+
+// ---------------------------------------------------------------------------------------
+// Skinny GEMM for the decoder step (M = active rows, a few tens to a few hundreds).
+//
+// At these sizes a projection moves ~1 MB and the tiled kernel above spends its time in a chain
+// of dependent K-slab loads on a handful of workgroups.  Here a workgroup owns a 32 x 32 output
+// tile and issues the loads of its whole operand panel (32 rows of A and of Wt over KC columns)
+// at once: one memory round trip, every lane with 24 independent 16-byte loads in flight, and
+// (M/32)*(N/32) workgroups instead of (M/128)*(N/128).  The four waves split K, multiply their
+// quarter with split-precision MFMAs and the partial tiles are summed through LDS in a fixed
+// order (deterministic).
+//
+// Optional prologue: A = LayerNorm(A) with fp32 statistics (needs K == KC: the whole row is in
+// the panel), which removes the separate LayerNorm launches of the decoder step.
+// ---------------------------------------------------------------------------------------
+namespace nt {
+
+template <int KC>
+struct SkinnyCfg {
+  static constexpr int LD = KC + 8;                       // halfs per LDS row
+  static constexpr int PANEL = 32 * LD;                   // halfs per operand panel
+  static constexpr size_t LDS = (size_t)3 * PANEL * 2 + 4 * 32 * 33 * 4;
+};
+
+__device__ __forceinline__ float wave_sum_f(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+  return v;
+}
+
+template <int KC, bool C_F32>
+__global__ __launch_bounds__(256) void skinny_gemm_kernel(const float *A, long lda, const _Float16 *Wt, int M, int N,
+                                                          int K, const float *ln_g, const float *ln_b, float ln_eps,
+                                                          GemmEpilogue e) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_sk[];
+  using Cfg = SkinnyCfg<KC>;
+  constexpr int LD = Cfg::LD;
+  _Float16 *sAhi = (_Float16 *)smem_sk, *sAlo = sAhi + Cfg::PANEL, *sW = sAlo + Cfg::PANEL;
+  float *sRed = (float *)(sW + Cfg::PANEL);  // [4][32][33]
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, g = lane >> 5;
+  const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+  constexpr int CPL = KC / 256;  // float4 chunks per lane per row (wave covers a row: 64 lanes x 4 floats x CPL)
+
+  floatx16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; v++) acc[v] = 0.f;
+
+  for (int k0 = 0; k0 < K; k0 += KC) {
+    // ---- issue every load of the panel: wave w owns rows 8w .. 8w+7 of A ----
+    float4 ra[8][CPL];
+#pragma unroll
+    for (int r = 0; r < 8; r++) {
+      const int m = m0 + wave * 8 + r;
+#pragma unroll
+      for (int c = 0; c < CPL; c++)
+        ra[r][c] = (m < M) ? *(const float4 *)(A + (long)m * lda + k0 + c * 256 + lane * 4) : make_float4(0, 0, 0, 0);
+    }
+    uint4 rw[KC / 64];
+#pragma unroll
+    for (int i = 0; i < KC / 64; i++) {
+      const int c = tid + 256 * i, row = c / (KC / 8), kc = c % (KC / 8);
+      const int n = n0 + row;
+      rw[i] = (n < N) ? *(const uint4 *)(Wt + (long)n * K + k0 + kc * 8) : make_uint4(0, 0, 0, 0);
+    }
+    if (k0 > 0) __syncthreads();  // previous panel fully consumed
+    // ---- optional LayerNorm of the rows, then head/tail split into LDS ----
+    float4 gg[CPL], bb[CPL];
+    if (ln_g) {
+#pragma unroll
+      for (int c = 0; c < CPL; c++) {
+        gg[c] = *(const float4 *)(ln_g + c * 256 + lane * 4);
+        bb[c] = *(const float4 *)(ln_b + c * 256 + lane * 4);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 8; r++) {
+      if (ln_g) {
+        float s = 0.f;
+#pragma unroll
+        for (int c = 0; c < CPL; c++) s += ra[r][c].x + ra[r][c].y + ra[r][c].z + ra[r][c].w;
+        const float mean = wave_sum_f(s) / (float)KC;
+        float q = 0.f;
+#pragma unroll
+        for (int c = 0; c < CPL; c++) {
+          float4 &x = ra[r][c];
+          x.x -= mean; x.y -= mean; x.z -= mean; x.w -= mean;
+          q += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+        }
+        const float rstd = 1.0f / sqrtf(wave_sum_f(q) / (float)KC + ln_eps);
+#pragma unroll
+        for (int c = 0; c < CPL; c++) {
+          float4 &x = ra[r][c];
+          x.x = gg[c].x * (x.x * rstd) + bb[c].x;
+          x.y = gg[c].y * (x.y * rstd) + bb[c].y;
+          x.z = gg[c].z * (x.z * rstd) + bb[c].z;
+          x.w = gg[c].w * (x.w * rstd) + bb[c].w;
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < CPL; c++) {
+        const float f[4] = {ra[r][c].x, ra[r][c].y, ra[r][c].z, ra[r][c].w};
+        half4 hi, lo;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          hi[j] = (_Float16)f[j];
+          lo[j] = (_Float16)(f[j] - (float)hi[j]);
+        }
+        const int off = (wave * 8 + r) * LD + c * 256 + lane * 4;
+        *(half4 *)(sAhi + off) = hi;
+        *(half4 *)(sAlo + off) = lo;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < KC / 64; i++) {
+      const int c = tid + 256 * i, row = c / (KC / 8), kc = c % (KC / 8);
+      *(uint4 *)(sW + row * LD + kc * 8) = rw[i];
+    }
+    __syncthreads();
+    // ---- wave w multiplies its quarter of the panel ----
+#pragma unroll
+    for (int ks = 0; ks < KC / 64; ks++) {
+      const int off = li * LD + wave * (KC / 4) + ks * 16 + g * 8;
+      const half8 a = *(const half8 *)(sAhi + off), al = *(const half8 *)(sAlo + off), b = *(const half8 *)(sW + off);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, b, acc, 0, 0, 0);
+    }
+  }
+  // ---- sum the four K-quarters in a fixed order, then the epilogue ----
+#pragma unroll
+  for (int v = 0; v < 16; v++) {
+    const int row = (v >> 2) * 8 + g * 4 + (v & 3);
+    sRed[(wave * 32 + row) * 33 + li] = acc[v];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 4; j++) {
+    const int idx = tid + 256 * j, row = idx >> 5, col = idx & 31;
+    const int m = m0 + row, n = n0 + col;
+    if (m >= M || n >= N) continue;
+    float val = sRed[(0 * 32 + row) * 33 + col] + sRed[(1 * 32 + row) * 33 + col] + sRed[(2 * 32 + row) * 33 + col] +
+                sRed[(3 * 32 + row) * 33 + col];
+    if (e.bias) val += e.bias[n];
+    if (n < e.scale_cols) val *= e.scale;
+    if (e.relu) val = fmaxf(val, 0.f);
+    if (e.resid) val += e.resid[(long)m * e.ldr + n];
+    const bool first = n < e.n_split;
+    char *dst = (char *)(first ? e.dst0 : e.dst1);
+    const long ld = first ? e.ld0 : e.ld1;
+    const int nc = first ? n : n - e.n_split;
+    if (C_F32)
+      ((float *)dst)[(long)m * ld + nc] = val;
+    else
+      ((_Float16 *)dst)[(long)m * ld + nc] = (_Float16)val;
+  }
+}
+
+template <int KC>
+static hipError_t skinny_launch(const float *A, long lda, const _Float16 *Wt, int M, int N, int K, const float *ln_g,
+                                const float *ln_b, float ln_eps, const GemmEpilogue &e, hipStream_t s) {
+  static bool configured = false;
+  const size_t lds = SkinnyCfg<KC>::LDS;
+  if (!configured) {
+    hipError_t err = hipFuncSetAttribute((const void *)skinny_gemm_kernel<KC, true>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (err != hipSuccess) return err;
+    configured = true;
+  }
+  dim3 grid((N + 31) / 32, (M + 31) / 32), block(256);
+  hipLaunchKernelGGL((skinny_gemm_kernel<KC, true>), grid, block, lds, s, A, lda, Wt, M, N, K, ln_g, ln_b, ln_eps, e);
+  return hipGetLastError();
+}
+
+bool skinny_gemm_supported(int K, bool with_ln) {
+  if (with_ln) return K == 256 || K == 512;
+  return K % 256 == 0;
+}
+
+hipError_t launch_skinny_gemm(const float *A, long lda, const _Float16 *Wt, int M, int N, int K, const float *ln_g,
+                              const float *ln_b, float ln_eps, const GemmEpilogue &e, hipStream_t s) {
+  if (M <= 0 || N <= 0) return hipSuccess;
+  if (K % 512 == 0) return skinny_launch<512>(A, lda, Wt, M, N, K, ln_g, ln_b, ln_eps, e, s);
+  if (K % 256 == 0) return skinny_launch<256>(A, lda, Wt, M, N, K, ln_g, ln_b, ln_eps, e, s);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace nt

@@ -42,6 +42,8 @@ int fail(int code, const char *fmt, ...) {
 // The decoder side (activations and self-attention cache) is always fp32.
 constexpr bool kEncF32 = true;
 constexpr bool kCrossF32 = false;
+// Decoder projections with at most this many active rows use the one-round-trip kernel.
+constexpr int kSkinnyMaxRows = 1024;
 constexpr size_t kEncElt = kEncF32 ? 4 : 2, kCrossElt = kCrossF32 ? 4 : 2;
 
 // Launch `call`; when timing of family `id` is on, bracket it with two events on the stream and
@@ -421,39 +423,45 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
   auto gemm_bytes = [&](double rows, double k, double n, double a_elt, double c_elt, bool resid) {
     return rows * k * a_elt + n * k * 2 + rows * n * c_elt + (resid ? rows * n * 4 : 0.0);
   };
+  // encoder activations that feed a GEMM: head/tail fp16 plane pairs (kEncF32) or one fp16 plane
+  const int amode = kEncF32 ? nt::A_PLANES : nt::A_F16;
+  const int ln_mode = kEncF32 ? nt::OUT_PLANES : nt::OUT_F16;
+  const long lo_d = (long)m->max_tokens * d, lo_F = (long)m->max_tokens * std::max(F, 1);  // tail plane offsets
+  auto lo_of = [&](void *p, long off) -> const void * { return kEncF32 ? (const void *)((_Float16 *)p + off) : nullptr; };
   for (auto &L : m->enc) {
     KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
-       nt::launch_layer_norm(m->x, M, d, L.ln1.g, L.ln1.b, c.ln_eps, m->a_enc, kEncF32, s));
+       nt::launch_layer_norm(m->x, M, d, L.ln1.g, L.ln1.b, c.ln_eps, m->a_enc, ln_mode, lo_d, s));
     nt::GemmEpilogue e;
     e.bias = L.self.bqkv; e.scale = qscale; e.scale_cols = d; e.dst0 = m->qkv; e.ld0 = 3 * d; e.n_split = 3 * d;
     KT(K_GEMM_ENC_QKV, gemm_bytes(Md, dd, 3 * dd, ea, ea, false), 6 * Md * dd * dd,
-       nt::launch_gemm(kEncF32, kEncF32, m->a_enc, d, L.self.Wqkv, M, 3 * d, d, e, s));
+       nt::launch_gemm(amode, kEncF32, m->a_enc, lo_of(m->a_enc, lo_d), d, L.self.Wqkv, M, 3 * d, d, e, s));
     KT(K_ATTN_ENC, Md * 4 * dd * ea, 4.0 * B * S * S * dd,
-       nt::launch_enc_attention(m->qkv, kEncF32, m->len, m->ctx_enc, B, S, d, H, L.self.rk, c.rpr_clip, s));
+       nt::launch_enc_attention(m->qkv, kEncF32, m->len, m->ctx_enc, lo_d, B, S, d, H, L.self.rk, c.rpr_clip, s));
     nt::GemmEpilogue o;
     o.bias = L.self.bo; o.resid = m->x; o.ldr = d; o.dst0 = m->x; o.ld0 = d; o.n_split = d;
     KT(K_GEMM_ENC_O, gemm_bytes(Md, dd, dd, ea, 4, true), 2 * Md * dd * dd,
-       nt::launch_gemm(kEncF32, true, m->ctx_enc, d, L.self.Wo, M, d, d, o, s));
+       nt::launch_gemm(amode, true, m->ctx_enc, lo_of(m->ctx_enc, lo_d), d, L.self.Wo, M, d, d, o, s));
     if (F > 0) {
       KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
-         nt::launch_layer_norm(m->x, M, d, L.ln2.g, L.ln2.b, c.ln_eps, m->a_enc, kEncF32, s));
+         nt::launch_layer_norm(m->x, M, d, L.ln2.g, L.ln2.b, c.ln_eps, m->a_enc, ln_mode, lo_d, s));
       nt::GemmEpilogue f1;
       f1.bias = L.ffn.b1; f1.relu = 1; f1.dst0 = m->u_enc; f1.ld0 = F; f1.n_split = F;
+      f1.dst_lo_offset = kEncF32 ? lo_F : 0;
       KT(K_GEMM_ENC_FFN, gemm_bytes(Md, dd, F, ea, ea, false), 2 * Md * dd * F,
-         nt::launch_gemm(kEncF32, kEncF32, m->a_enc, d, L.ffn.W1, M, F, d, f1, s));
+         nt::launch_gemm(amode, false, m->a_enc, lo_of(m->a_enc, lo_d), d, L.ffn.W1, M, F, d, f1, s));
       nt::GemmEpilogue f2;
       f2.bias = L.ffn.b2; f2.resid = m->x; f2.ldr = d; f2.dst0 = m->x; f2.ld0 = d; f2.n_split = d;
       KT(K_GEMM_ENC_FFN, gemm_bytes(Md, F, dd, ea, 4, true), 2 * Md * dd * F,
-         nt::launch_gemm(kEncF32, true, m->u_enc, F, L.ffn.W2, M, d, F, f2, s));
+         nt::launch_gemm(amode, true, m->u_enc, lo_of(m->u_enc, lo_F), F, L.ffn.W2, M, d, F, f2, s));
     }
   }
   KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
-     nt::launch_layer_norm(m->x, M, d, m->enc_final.g, m->enc_final.b, c.ln_eps, m->enc_out, kEncF32, s));
+     nt::launch_layer_norm(m->x, M, d, m->enc_final.g, m->enc_final.b, c.ln_eps, m->enc_out, ln_mode, lo_d, s));
   for (int l = 0; l < c.n_dec; l++) {
     nt::GemmEpilogue e;
     e.bias = m->dec[l].cross.bkv; e.dst0 = m->cross[l]; e.ld0 = 2 * d; e.n_split = 2 * d;
     KT(K_GEMM_CROSS_KV, gemm_bytes(Md, dd, 2 * dd, ea, ca, false), 4 * Md * dd * dd,
-       nt::launch_gemm(kEncF32, kCrossF32, m->enc_out, d, m->dec[l].cross.Wkv, M, 2 * d, d, e, s));
+       nt::launch_gemm(amode, kCrossF32, m->enc_out, lo_of(m->enc_out, lo_d), d, m->dec[l].cross.Wkv, M, 2 * d, d, e, s));
   }
   m->len_prefix.clear();
   m->B = B; m->S = S; m->encoded = true;
@@ -495,7 +503,7 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
     a.t = t; a.rows_prev = rows_prev; a.rows_now = rows_now; a.d = d; a.vocab = V; a.bos_id = c.bos_id; a.pad_id = c.pad_id;
     a.pk = d_logits ? nullptr : m->pk; a.n_partials = partials_prev; a.out = d_out; a.out_ld = T;
     a.forced = d_forced; a.forced_ld = T; a.E = m->E; a.pe = m->pe; a.gamma = m->dec[0].ln1.g; a.beta = m->dec[0].ln1.b;
-    a.eps = c.ln_eps; a.z = m->z; a.a = m->a32; a.flags = m->flags;
+    a.eps = c.ln_eps; a.z = m->z; a.a = nullptr; a.flags = m->flags;
     if (d_logits && rows_now == 0) break;  // no tokens to collect in this mode (pk == nullptr)
     KT(K_STEP_BEGIN, rows_prev * (partials_prev * 8.0 + 4) + rows_now * dd * 14, rows_now * dd * 10,
        nt::launch_step_begin(a, s));
@@ -504,61 +512,72 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
     const double Rd = (double)R;
     // source tokens attended by the active rows (exact when the host knows the lengths)
     const double cross_keys = (m->len_prefix.size() > (size_t)R) ? (double)m->len_prefix[(size_t)R] : Rd * S;
+    // One decoder projection: C = [LayerNorm](A) * Wt^T with the given epilogue.  Small row counts
+    // take the one-round-trip kernel with the LayerNorm fused into its prologue.
+    auto dec_gemm = [&](int id, const float *A, int K, const _Float16 *Wt, int N, const LN *ln,
+                        const nt::GemmEpilogue &e) -> int {
+      const double by = gemm_bytes(Rd, K, N, e.resid != nullptr), fl = 2 * Rd * K * (double)N;
+      if (R <= kSkinnyMaxRows && nt::skinny_gemm_supported(K, ln != nullptr)) {
+        KT(id, by, fl, nt::launch_skinny_gemm(A, K, Wt, R, N, K, ln ? ln->g : nullptr, ln ? ln->b : nullptr, c.ln_eps, e, s));
+        return NT_OK;
+      }
+      if (ln) {
+        KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd,
+           nt::launch_layer_norm(A, R, K, ln->g, ln->b, c.ln_eps, m->a32, nt::OUT_F32, 0, s));
+        A = m->a32;
+      }
+      KT(id, by, fl, nt::launch_gemm(nt::A_F32, true, A, nullptr, K, Wt, R, N, K, e, s));
+      return NT_OK;
+    };
+    int rc;
     for (int l = 0; l < c.n_dec; l++) {
       const DecLayer &L = m->dec[l];
-      if (l > 0)
-        KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd, nt::launch_layer_norm(m->z, R, d, L.ln1.g, L.ln1.b, c.ln_eps, m->a32, true, s));
       {  // self-attention: q (scaled) to q32, k|v appended to the cache at position t
         nt::GemmEpilogue e;
         e.bias = L.self.bqkv; e.scale = qscale; e.scale_cols = d; e.dst0 = m->q32; e.ld0 = d; e.n_split = d;
         e.dst1 = m->self_kv[l] + (long)t * 2 * d; e.ld1 = self_stride;
-        KT(K_GEMM_DEC_QKV, gemm_bytes(Rd, dd, 3 * dd, false), 6 * Rd * dd * dd,
-           nt::launch_gemm(true, true, m->a32, d, L.self.Wqkv, R, 3 * d, d, e, s));
+        if ((rc = dec_gemm(K_GEMM_DEC_QKV, m->z, d, L.self.Wqkv, 3 * d, &L.ln1, e))) return rc;
         KT(K_ATTN_DEC_SELF, Rd * (t + 1) * 2 * dd * 4 + Rd * dd * 8, 4 * Rd * (t + 1) * dd,
            nt::launch_attn_decode(m->q32, m->self_kv[l], true, self_stride, nullptr, t + 1, R, d, H, L.self.rk,
                                   c.rpr_clip, t, m->ctx32, s));
         nt::GemmEpilogue o;
         o.bias = L.self.bo; o.resid = m->z; o.ldr = d; o.dst0 = m->z; o.ld0 = d; o.n_split = d;
-        KT(K_GEMM_DEC_O, gemm_bytes(Rd, dd, dd, true), 2 * Rd * dd * dd,
-           nt::launch_gemm(true, true, m->ctx32, d, L.self.Wo, R, d, d, o, s));
+        if ((rc = dec_gemm(K_GEMM_DEC_O, m->ctx32, d, L.self.Wo, d, nullptr, o))) return rc;
       }
       {  // cross-attention over the encoder keys/values
-        KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd, nt::launch_layer_norm(m->z, R, d, L.ln2.g, L.ln2.b, c.ln_eps, m->a32, true, s));
         nt::GemmEpilogue e;
         e.bias = L.cross.bq; e.scale = qscale; e.scale_cols = d; e.dst0 = m->q32; e.ld0 = d; e.n_split = d;
-        KT(K_GEMM_DEC_Q, gemm_bytes(Rd, dd, dd, false), 2 * Rd * dd * dd,
-           nt::launch_gemm(true, true, m->a32, d, L.cross.Wq, R, d, d, e, s));
+        if ((rc = dec_gemm(K_GEMM_DEC_Q, m->z, d, L.cross.Wq, d, &L.ln2, e))) return rc;
         KT(K_ATTN_DEC_CROSS, cross_keys * 2 * dd * ca + Rd * dd * 8, 4 * cross_keys * dd,
            nt::launch_attn_decode(m->q32, m->cross[l], kCrossF32, (long)S * 2 * d, m->len, 0, R, d, H, nullptr, 0, 0,
                                   m->ctx32, s));
         nt::GemmEpilogue o;
         o.bias = L.cross.bo; o.resid = m->z; o.ldr = d; o.dst0 = m->z; o.ld0 = d; o.n_split = d;
-        KT(K_GEMM_DEC_O, gemm_bytes(Rd, dd, dd, true), 2 * Rd * dd * dd,
-           nt::launch_gemm(true, true, m->ctx32, d, L.cross.Wo, R, d, d, o, s));
+        if ((rc = dec_gemm(K_GEMM_DEC_O, m->ctx32, d, L.cross.Wo, d, nullptr, o))) return rc;
       }
       if (F > 0) {
-        KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd, nt::launch_layer_norm(m->z, R, d, L.ln3.g, L.ln3.b, c.ln_eps, m->a32, true, s));
         nt::GemmEpilogue f1;
         f1.bias = L.ffn.b1; f1.relu = 1; f1.dst0 = m->u32; f1.ld0 = F; f1.n_split = F;
-        KT(K_GEMM_DEC_FFN, gemm_bytes(Rd, dd, F, false), 2 * Rd * dd * F,
-           nt::launch_gemm(true, true, m->a32, d, L.ffn.W1, R, F, d, f1, s));
+        if ((rc = dec_gemm(K_GEMM_DEC_FFN, m->z, d, L.ffn.W1, F, &L.ln3, f1))) return rc;
         nt::GemmEpilogue f2;
         f2.bias = L.ffn.b2; f2.resid = m->z; f2.ldr = d; f2.dst0 = m->z; f2.ld0 = d; f2.n_split = d;
-        KT(K_GEMM_DEC_FFN, gemm_bytes(Rd, F, dd, true), 2 * Rd * dd * F,
-           nt::launch_gemm(true, true, m->u32, F, L.ffn.W2, R, d, F, f2, s));
+        if ((rc = dec_gemm(K_GEMM_DEC_FFN, m->u32, F, L.ffn.W2, d, nullptr, f2))) return rc;
       }
     }
+    // final LayerNorm as a head/tail plane pair (the planes share the a32 buffer), then the output layer
+    _Float16 *h_hi = (_Float16 *)m->a32, *h_lo = h_hi + (long)m->max_rows * d;
     KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd,
-       nt::launch_layer_norm(m->z, R, d, m->dec_final.g, m->dec_final.b, c.ln_eps, m->a32, true, s));
+       nt::launch_layer_norm(m->z, R, d, m->dec_final.g, m->dec_final.b, c.ln_eps, h_hi, nt::OUT_PLANES,
+                             (long)m->max_rows * d, s));
     if (d_logits) {
       nt::GemmEpilogue e;
       e.dst0 = d_logits + (long)t * V; e.ld0 = (long)T * V; e.n_split = V;
       KT(K_GEMM_LOGITS, gemm_bytes(Rd, dd, V, false), 2 * Rd * dd * V,
-         nt::launch_gemm(true, true, m->a32, d, m->Wout, R, V, d, e, s));
+         nt::launch_gemm(nt::A_PLANES, true, h_hi, h_lo, d, m->Wout, R, V, d, e, s));
     } else {
       const int np_ = nt::vocab_argmax_partials(R, V);
       KT(K_VOCAB_ARGMAX, (double)V * dd * 2 + Rd * dd * 4 + Rd * np_ * 8, 2 * Rd * dd * V,
-         nt::launch_vocab_argmax(m->a32, d, m->Wout, R, V, d, m->pk, s));
+         nt::launch_vocab_argmax(h_hi, h_lo, d, m->Wout, R, V, d, m->pk, s));
       partials_prev = np_;
     }
   }
@@ -608,7 +627,8 @@ int nt_debug_encoder_out(nt_model *m, float *d_out, void *hip_stream) {
   if (!m->encoded) return fail(NT_ESTATE, "no encoded batch");
   const long n = (long)m->B * m->S * m->c.d_model;
   if (kEncF32)
-    HIP_TRY(hipMemcpyAsync(d_out, m->enc_out, (size_t)n * 4, hipMemcpyDeviceToDevice, as_stream(hip_stream)));
+    HIP_TRY(nt::launch_planes_to_float((const _Float16 *)m->enc_out, (const _Float16 *)m->enc_out + m->max_tokens * m->c.d_model,
+                                       d_out, n, as_stream(hip_stream)));
   else
     HIP_TRY(nt::launch_half_to_float((const _Float16 *)m->enc_out, d_out, n, as_stream(hip_stream)));
   return NT_OK;

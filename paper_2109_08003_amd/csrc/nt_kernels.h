@@ -22,21 +22,34 @@ struct GemmEpilogue {
   int n_split = 0;  // set to N when there is a single destination
   void *dst1 = nullptr;
   long ld1 = 0;
+  long dst_lo_offset = 0;  // fp16 destinations only: if != 0 the tail fp16(v - fp16(v)) is also stored, this many
+                           // elements after the head (the result becomes a head/tail plane pair)
 };
 
-// a_f32: A is fp32 and is split into an fp16 head and an fp16 tail inside the kernel (two MFMA
-// passes, ~22 significant bits); otherwise A is fp16.  c_f32: destinations are fp32, else fp16.
-// K must be a multiple of 64; lda in elements.
-hipError_t launch_gemm(bool a_f32, bool c_f32, const void *A, long lda, const _Float16 *Wt, int M, int N, int K,
-                       const GemmEpilogue &e, hipStream_t s);
+// How the A operand is given (see nt_gemm.hip): one fp16 plane, a head/tail pair of fp16 planes
+// (~22 significant bits, two MFMA passes), or fp32 that the kernel splits while staging.
+enum AMode { A_F16 = 0, A_PLANES = 1, A_F32 = 2 };
+
+// a_mode: AMode; A_lo is the tail plane for A_PLANES (ignored otherwise).  c_f32: destinations are
+// fp32, else fp16.  K must be a multiple of 64; lda in elements.
+hipError_t launch_gemm(int a_mode, bool c_f32, const void *A, const void *A_lo, long lda, const _Float16 *Wt, int M,
+                       int N, int K, const GemmEpilogue &e, hipStream_t s);
+
+// Decoder-step variant for small M (fp32 A and C): 32 x 32 tiles, whole-K operand panels loaded
+// in one round trip.  If ln_g != nullptr the rows of A are LayerNorm-ed first (requires K to be
+// the row width, 256 or 512).  K must be a multiple of 256.
+bool skinny_gemm_supported(int K, bool with_ln);
+hipError_t launch_skinny_gemm(const float *A, long lda, const _Float16 *Wt, int M, int N, int K, const float *ln_g,
+                              const float *ln_b, float ln_eps, const GemmEpilogue &e, hipStream_t s);
 
 // ---- output projection fused with row arg-max ------------------------------------------
 // For every row m < M: the largest of h[m,:] . Wt[v,:] over v < N, lowest v on ties, as packed
 // keys.  Each workgroup reduces a strip of columns; partial keys go to pk[m * n_partials + p].
 // vocab_argmax_partials(N) gives n_partials for the launch configuration used with M rows.
 int vocab_argmax_partials(int M, int N);
-hipError_t launch_vocab_argmax(const float *h, long ldh, const _Float16 *Wt, int M, int N, int K,
-                               unsigned long long *pk, hipStream_t s);
+// h is a head/tail pair of fp16 planes.
+hipError_t launch_vocab_argmax(const _Float16 *h, const _Float16 *h_lo, long ldh, const _Float16 *Wt, int M, int N,
+                               int K, unsigned long long *pk, hipStream_t s);
 
 // ---- row kernels --------------------------------------------------------------------
 // x[r,:] = sqrt(d) * E[id] + PE[pos]; rows r = b*S + s, pos = s.  Out-of-range ids are
@@ -44,9 +57,13 @@ hipError_t launch_vocab_argmax(const float *h, long ldh, const _Float16 *Wt, int
 hipError_t launch_embed_src(const int32_t *src, const int32_t *len, int32_t *len_out, int B, int S, int d, int vocab,
                             int pad_id, const _Float16 *E, const float *pe, float *x, int32_t *flags, hipStream_t s);
 
-// out = gamma * (x - mean) / sqrt(var + eps) + beta per row of d; out fp16 or fp32.
+// out = gamma * (x - mean) / sqrt(var + eps) + beta per row of d.
+enum OutMode { OUT_F16 = 0, OUT_F32 = 1, OUT_PLANES = 2 };  // OUT_PLANES: fp16 head at out, tail at out + lo_offset
 hipError_t launch_layer_norm(const float *x, int M, int d, const float *gamma, const float *beta, float eps,
-                             void *out, bool out_f32, hipStream_t s);
+                             void *out, int out_mode, long lo_offset, hipStream_t s);
+
+// out[i] = hi[i] + lo[i] (debug readback of a head/tail plane pair)
+hipError_t launch_planes_to_float(const _Float16 *hi, const _Float16 *lo, float *out, long n, hipStream_t s);
 
 // fp16 -> fp32 copy (debug readback)
 hipError_t launch_half_to_float(const _Float16 *in, float *out, long n, hipStream_t s);
@@ -55,7 +72,7 @@ hipError_t launch_fill_i32(int32_t *p, long n, int32_t v, hipStream_t s);
 // Start of decoder step t for rows [0, rows_prev): (1) if t > 0, reduce the arg-max partials of
 // step t-1 and store the token in out[r*out_ld + t-1]; (2) for rows < rows_now: take the input
 // token (BOS at t = 0, forced[r*forced_ld + t] if forced, else the token just reduced),
-// z = sqrt(d) * E[y] + PE[t], a = LayerNorm(z).
+// z = sqrt(d) * E[y] + PE[t], and a = LayerNorm(z) unless a == nullptr.
 struct StepBeginArgs {
   int t, rows_prev, rows_now, d, vocab, bos_id, pad_id;
   const unsigned long long *pk;
@@ -74,11 +91,12 @@ struct StepBeginArgs {
 hipError_t launch_step_begin(const StepBeginArgs &a, hipStream_t s);
 
 // ---- attention ------------------------------------------------------------------------
-// Encoder self-attention on a padded batch.  qkv [B*S, 3d] (q already scaled | k | v),
-// len [B]; ctx [B*S, d]; both fp32 when f32 (split-precision MFMA), else fp16.  Keys >= len get
-// weight exactly 0; query rows >= len get 0.  rk: optional relative-position keys [2*clip+1, dh].
-hipError_t launch_enc_attention(const void *qkv, bool f32, const int32_t *len, void *ctx, int B, int S, int d,
-                                int heads, const float *rk, int clip, hipStream_t s);
+// Encoder self-attention on a padded batch.  qkv [B*S, 3d] (q already scaled | k | v), len [B];
+// ctx [B*S, d].  f32: qkv is fp32 (split-precision MFMA inside) and ctx is written as a head/tail
+// pair of fp16 planes (tail ctx_lo_offset elements after the head); else both are fp16.  Keys >=
+// len get weight exactly 0; query rows >= len get 0.  rk: optional relative keys [2*clip+1, dh].
+hipError_t launch_enc_attention(const void *qkv, bool f32, const int32_t *len, void *ctx, long ctx_lo_offset, int B,
+                                int S, int d, int heads, const float *rk, int clip, hipStream_t s);
 
 // Single-query attention against a cache, one query per (row, head).
 //   q [rows, d] fp32 (scaled); ctx [rows, d] fp32.

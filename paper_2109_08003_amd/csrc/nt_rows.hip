@@ -84,9 +84,9 @@ hipError_t launch_embed_src(const int32_t *src, const int32_t *len, int32_t *len
   return hipGetLastError();
 }
 
-template <bool OUT_F32>
+template <int MODE>
 __global__ __launch_bounds__(256) void layer_norm_kernel(const float *x, int M, int d, const float *gamma,
-                                                         const float *beta, float eps, void *out) {
+                                                         const float *beta, float eps, void *out, long lo_offset) {
   const int lane = threadIdx.x & 63;
   const long r = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= M) return;
@@ -100,21 +100,37 @@ __global__ __launch_bounds__(256) void layer_norm_kernel(const float *x, int M, 
 #pragma unroll
   for (int i = 0; i < MAX_PER_LANE; i++)
     if (i < ne) {
-      if (OUT_F32)
-        ((float *)out)[r * d + lane + 64 * i] = v[i];
-      else
-        ((_Float16 *)out)[r * d + lane + 64 * i] = (_Float16)v[i];
+      const long o = r * d + lane + 64 * i;
+      if (MODE == OUT_F32) {
+        ((float *)out)[o] = v[i];
+      } else {
+        const _Float16 hi = (_Float16)v[i];
+        ((_Float16 *)out)[o] = hi;
+        if (MODE == OUT_PLANES) ((_Float16 *)out)[o + lo_offset] = (_Float16)(v[i] - (float)hi);
+      }
     }
 }
 
 hipError_t launch_layer_norm(const float *x, int M, int d, const float *gamma, const float *beta, float eps,
-                             void *out, bool out_f32, hipStream_t s) {
+                             void *out, int out_mode, long lo_offset, hipStream_t s) {
   if (M <= 0) return hipSuccess;
   dim3 grid((M + 3) / 4), block(256);
-  if (out_f32)
-    hipLaunchKernelGGL(layer_norm_kernel<true>, grid, block, 0, s, x, M, d, gamma, beta, eps, out);
+  if (out_mode == OUT_F32)
+    hipLaunchKernelGGL(layer_norm_kernel<OUT_F32>, grid, block, 0, s, x, M, d, gamma, beta, eps, out, lo_offset);
+  else if (out_mode == OUT_PLANES)
+    hipLaunchKernelGGL(layer_norm_kernel<OUT_PLANES>, grid, block, 0, s, x, M, d, gamma, beta, eps, out, lo_offset);
   else
-    hipLaunchKernelGGL(layer_norm_kernel<false>, grid, block, 0, s, x, M, d, gamma, beta, eps, out);
+    hipLaunchKernelGGL(layer_norm_kernel<OUT_F16>, grid, block, 0, s, x, M, d, gamma, beta, eps, out, lo_offset);
+  return hipGetLastError();
+}
+
+__global__ void planes_to_float_kernel(const _Float16 *hi, const _Float16 *lo, float *out, long n) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = (float)hi[i] + (float)lo[i];
+}
+hipError_t launch_planes_to_float(const _Float16 *hi, const _Float16 *lo, float *out, long n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(planes_to_float_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, hi, lo, out, n);
   return hipGetLastError();
 }
 
@@ -174,6 +190,7 @@ __global__ __launch_bounds__(256) void step_begin_kernel(StepBeginArgs a) {
       v[i] = sc * (float)e[lane + 64 * i] + p[lane + 64 * i];
       a.z[(long)r * d + lane + 64 * i] = v[i];
     }
+  if (!a.a) return;  // the consumer applies the LayerNorm itself
   row_layer_norm(v, ne, d, a.eps, lane, a.gamma, a.beta);
 #pragma unroll
   for (int i = 0; i < MAX_PER_LANE; i++)
