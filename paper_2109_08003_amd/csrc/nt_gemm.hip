@@ -196,13 +196,149 @@ __global__ __launch_bounds__(256) void gemm_kernel(const void *A, const void *A2
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Mid-size variant: 64 x 64 tiles (4 waves, one 32 x 32 MFMA block each) with the K-slabs
+// prefetched three deep into registers.  Used when the 128 x 128 grid would leave most of the
+// 256 CUs idle (decoder projections with a few thousand rows, short encoder batches): four times
+// the workgroups, and the deep prefetch takes the global-load latency out of the K loop.
+// ---------------------------------------------------------------------------------------
+constexpr int MID = 64, MID_PD = 3;
+
+template <int AMODE, bool C_F32>
+__global__ __launch_bounds__(256) void gemm_mid_kernel(const void *A, const void *A2, long lda, const _Float16 *Wt,
+                                                       int M, int N, int K, GemmEpilogue e) {
+  __shared__ __attribute__((aligned(16))) _Float16 sAhi[MID * LDS_LD];
+  __shared__ __attribute__((aligned(16))) _Float16 sAlo[AMODE != A_F16 ? MID * LDS_LD : 8];
+  __shared__ __attribute__((aligned(16))) _Float16 sB[MID * LDS_LD];
+  int mt, nt_;
+  if (!tile_of(blockIdx.x, (M + MID - 1) / MID, (N + MID - 1) / MID, mt, nt_)) return;
+  const int m0 = mt * MID, n0 = nt_ * MID;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wm = wave >> 1, wn = wave & 1, li = lane & 31, g = lane >> 5;
+  floatx16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; v++) acc[v] = 0.f;
+  // per slab and thread: fp32 A 64x64 -> 4 chunks of 16 B; fp16 planes 64x64 -> 2 chunks each; Wt 64x64 -> 2
+  constexpr int NRA = (AMODE == A_F32) ? 4 : (AMODE == A_PLANES ? 4 : 2);
+  u32x4 ra[MID_PD][NRA], rb[MID_PD][2];
+  auto load_slab = [&](int slot, int k0) {
+    if constexpr (AMODE == A_F32) {
+      const float *Af = (const float *)A;
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const int c = tid + 256 * i, row = c >> 4, kc = c & 15;
+        const int m = (m0 + row < M) ? m0 + row : M - 1;
+        ra[slot][i] = *(const u32x4 *)(Af + (long)m * lda + k0 + kc * 4);
+      }
+    } else {
+      const _Float16 *Ah = (const _Float16 *)A, *Al = (const _Float16 *)A2;
+#pragma unroll
+      for (int i = 0; i < 2; i++) {
+        const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+        const int m = (m0 + row < M) ? m0 + row : M - 1;
+        ra[slot][i] = *(const u32x4 *)(Ah + (long)m * lda + k0 + kc * 8);
+        if constexpr (AMODE == A_PLANES) ra[slot][NRA - 2 + i] = *(const u32x4 *)(Al + (long)m * lda + k0 + kc * 8);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+      const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+      const int n = (n0 + row < N) ? n0 + row : N - 1;
+      rb[slot][i] = *(const u32x4 *)(Wt + (long)n * K + k0 + kc * 8);
+    }
+  };
+  auto store_slab = [&](int slot) {
+    if constexpr (AMODE == A_F32) {
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const int c = tid + 256 * i, row = c >> 4, kc = c & 15;
+        half4 hi, lo;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          const float f = __uint_as_float(ra[slot][i][j]);
+          hi[j] = (_Float16)f;
+          lo[j] = (_Float16)(f - (float)hi[j]);
+        }
+        *(half4 *)(sAhi + row * LDS_LD + kc * 4) = hi;
+        *(half4 *)(sAlo + row * LDS_LD + kc * 4) = lo;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; i++) {
+        const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+        *(u32x4 *)(sAhi + row * LDS_LD + kc * 8) = ra[slot][i];
+        if constexpr (AMODE == A_PLANES) *(u32x4 *)(sAlo + row * LDS_LD + kc * 8) = ra[slot][NRA - 2 + i];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+      const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
+      *(u32x4 *)(sB + row * LDS_LD + kc * 8) = rb[slot][i];
+    }
+  };
+  const int nk = K / BK;
+#pragma unroll
+  for (int p = 0; p < MID_PD; p++)
+    if (p < nk) load_slab(p, p * BK);
+  for (int kt = 0; kt < nk; kt += MID_PD) {
+#pragma unroll
+    for (int p = 0; p < MID_PD; p++) {  // unrolled so that the register slots are static
+      if (kt + p < nk) {
+        __syncthreads();
+        store_slab(p);
+        if (kt + p + MID_PD < nk) load_slab(p, (kt + p + MID_PD) * BK);
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ks++) {
+          const int offa = (wm * 32 + li) * LDS_LD + ks * 16 + g * 8, offb = (wn * 32 + li) * LDS_LD + ks * 16 + g * 8;
+          const half8 a = *(const half8 *)(sAhi + offa), b = *(const half8 *)(sB + offb);
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
+          if constexpr (AMODE != A_F16) {
+            const half8 al = *(const half8 *)(sAlo + offa);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, b, acc, 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+  const int n = n0 + wn * 32 + li;
+  if (n >= N) return;
+  const float bias = e.bias ? e.bias[n] : 0.f;
+  const float sc = (n < e.scale_cols) ? e.scale : 1.f;
+  const bool first = n < e.n_split;
+  char *dst = (char *)(first ? e.dst0 : e.dst1);
+  const long ld = first ? e.ld0 : e.ld1;
+  const int nc = first ? n : n - e.n_split;
+#pragma unroll
+  for (int v = 0; v < 16; v++) {
+    const int m = m0 + wm * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+    if (m >= M) continue;
+    float val = (acc[v] + bias) * sc;
+    if (e.relu) val = fmaxf(val, 0.f);
+    if (e.resid) val += e.resid[(long)m * e.ldr + n];
+    if (C_F32) {
+      ((float *)dst)[(long)m * ld + nc] = val;
+    } else {
+      const _Float16 hi = (_Float16)val;
+      ((_Float16 *)dst)[(long)m * ld + nc] = hi;
+      if (e.dst_lo_offset) ((_Float16 *)dst)[(long)m * ld + nc + e.dst_lo_offset] = (_Float16)(val - (float)hi);
+    }
+  }
+}
+
 hipError_t launch_gemm(int a_mode, bool c_f32, const void *A, const void *A_lo, long lda, const _Float16 *Wt, int M,
                        int N, int K, const GemmEpilogue &e, hipStream_t s) {
   if (M <= 0 || N <= 0) return hipSuccess;
-  dim3 grid(tile_grid((M + BM - 1) / BM, (N + BN - 1) / BN)), block(256);
+  const int big_tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+  const bool mid = big_tiles < 2 * 256;  // fewer than two 128x128 tiles per CU: use the 64x64 variant
+  dim3 grid(mid ? tile_grid((M + MID - 1) / MID, (N + MID - 1) / MID) : tile_grid((M + BM - 1) / BM, (N + BN - 1) / BN)),
+      block(256);
 #define NT_GEMM_CASE(MODE, CF)                                                                                  \
   if (a_mode == MODE && c_f32 == CF) {                                                                          \
-    hipLaunchKernelGGL((gemm_kernel<MODE, CF>), grid, block, 0, s, A, A_lo, lda, Wt, M, N, K, e);               \
+    if (mid)                                                                                                    \
+      hipLaunchKernelGGL((gemm_mid_kernel<MODE, CF>), grid, block, 0, s, A, A_lo, lda, Wt, M, N, K, e);         \
+    else                                                                                                        \
+      hipLaunchKernelGGL((gemm_kernel<MODE, CF>), grid, block, 0, s, A, A_lo, lda, Wt, M, N, K, e);             \
     return hipGetLastError();                                                                                   \
   }
   NT_GEMM_CASE(A_F16, false) NT_GEMM_CASE(A_F16, true) NT_GEMM_CASE(A_PLANES, false) NT_GEMM_CASE(A_PLANES, true)
