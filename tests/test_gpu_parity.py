@@ -235,3 +235,54 @@ def test_c1_full_workload_sampled_against_oracle(nt, oracle):
     print(f"C1 greedy: {len(sample) - bad}/{len(sample)} sampled sentences identical ({100 * frac:.2f} %), "
           f"worst near-tie gap {worst:.2e}")
     assert frac >= 0.99
+
+
+# ------------------------------------------------------------------------------ restored components (C3) and teacher shape (C4)
+def _check_workload_sample(nt, oracle, name, n_sent, budget, tol_frac, **overrides):
+    cfg = nt_synth.model_config(name, **overrides)
+    blob = nt_synth.make_weights(cfg, seed=0, random_affine=True)     # exercises the LayerNorm affine path too
+    tokens, offsets = nt_synth.workload(name, n_sent)
+    gm = nt.Model(cfg, blob, max_batch_tokens=budget)
+    out, oo = gm.translate_batch(tokens, offsets, token_budget=budget)
+    om = oracle.Model(cfg, blob)
+    ref, ro, _ = om.translate(tokens, offsets)
+    sents, gpu, ora = split(tokens, offsets), split(out, oo), split(ref, ro)
+    bad, worst = audit_mismatches(om, sents, gpu, ora, cfg)
+    frac = 1.0 - bad / n_sent
+    print(f"{name} {overrides}: {n_sent - bad}/{n_sent} sentences identical ({100 * frac:.2f} %), worst gap {worst:.2e}")
+    assert frac >= tol_frac
+    return gm, om, cfg, sents
+
+
+def test_c3_multihead_ffn_student(nt, oracle, torch_cuda):
+    """Ablation student: 8 heads of width 64 and a ReLU FFN of 2,048 in every layer."""
+    torch = torch_cuda
+    gm, om, cfg, sents = _check_workload_sample(nt, oracle, "C3", 96, 4096, 0.97)
+    # encoder outputs and teacher-forced logits on one small batch
+    src = sort_desc(sents[:6])
+    ids, lens = pad(src, cfg["pad_id"])
+    B, S = ids.shape
+    gm.encode(torch.from_numpy(ids).cuda(), torch.from_numpy(lens).cuda())
+    enc = torch.empty(B, S, cfg["d_model"], dtype=torch.float32, device="cuda")
+    gm.debug_encoder_out(enc)
+    enc = enc.cpu().numpy().astype(np.float64)
+    T = 6
+    tgt = np.tile(np.array([cfg["bos_id"], 17, 900, 4, 31999, 5], dtype=np.int32), (B, 1))
+    logits = torch.empty(B, T, cfg["vocab"], dtype=torch.float32, device="cuda")
+    gm.debug_teacher_forced_logits(torch.from_numpy(tgt).cuda(), logits)
+    logits = logits.cpu().numpy().astype(np.float64)
+    for i, s in enumerate(src):
+        assert rel_l2(enc[i, : len(s)], om.encode(s)) <= 2e-3
+        want = om.teacher_forced(s, tgt[i])
+        assert np.abs(logits[i] - want).max() <= 2e-2 and rel_l2(logits[i], want) <= 2e-3
+
+
+def test_c4_deep_teacher_shape_with_relative_positions(nt, oracle):
+    """30-layer encoder, 6-layer decoder, 8 heads, FFN, relative position keys with clip 8."""
+    _check_workload_sample(nt, oracle, "C4", 48, 2048, 0.95)
+
+
+def test_relative_positions_small(nt, oracle):
+    """Clip distance smaller than most sentences, 2 decoder layers, single wide head with relative keys."""
+    _check_workload_sample(nt, oracle, "C0", 8, 512, 0.87, rpr_clip=3, n_dec=2)
+    _check_workload_sample(nt, oracle, "C0", 8, 512, 0.87, rpr_clip=16, n_heads=4, d_ffn=256)
