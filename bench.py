@@ -33,12 +33,16 @@ MEASURED_TRAFFIC_BYTES = {}
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="C1", choices=["C1", "C2", "C3", "C4"])
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4"],
+                    help="C2 = the throughput configuration the words/s metric is quoted on")
     ap.add_argument("--sentences", type=int, default=None, help="default: the workload's own count")
-    ap.add_argument("--budget", type=int, default=4096, help="token budget per batch")
+    ap.add_argument("--budget", type=int, default=65536,
+                    help="token budget per batch (best of the 4k/16k/64k sweep of the throughput configuration)")
     ap.add_argument("--cpu-sentences", type=int, default=1024, help="oracle sample size (0 = skip)")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one device-to-device copy of this many MiB (calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; sentences are independent, so more GPUs would each take a "
@@ -124,6 +128,13 @@ def main():
                     avg_launch_us=round(1e3 * k["ms"] / k["launches"], 2), launches=k["launches"],
                     algorithmic_bytes_per_launch=round(k["bytes"] / k["launches"]),
                     algorithmic_flops_per_launch=round(k["flops"] / k["launches"]))
+
+    if args.calib_copy_mib > 0:
+        a = torch.zeros(args.calib_copy_mib << 20, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
 
     # ---- CPU oracle on a bounded sample of the same workload ----
     cpu = None

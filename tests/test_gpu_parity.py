@@ -286,3 +286,31 @@ def test_relative_positions_small(nt, oracle):
     """Clip distance smaller than most sentences, 2 decoder layers, single wide head with relative keys."""
     _check_workload_sample(nt, oracle, "C0", 8, 512, 0.87, rpr_clip=3, n_dec=2)
     _check_workload_sample(nt, oracle, "C0", 8, 512, 0.87, rpr_clip=16, n_heads=4, d_ffn=256)
+
+
+# ------------------------------------------------------------------------------ C2 (throughput configuration, as benchmarked)
+def test_c2_full_workload_sampled_against_oracle(nt, oracle):
+    """All 200,000 sentences at the 65,536-token budget - the launch configuration bench.py times
+    (batches of up to ~6,500 rows: the 128x128 tiled kernels, the fused arg-max with several
+    vocabulary tiles per workgroup).  A seeded sample plus the longest, the shortest and the
+    sentences of the fullest batch's tail are decoded by the oracle one by one; the remaining
+    outputs are checked for shape and range."""
+    cfg = nt_synth.model_config("C2")
+    blob = nt_synth.make_weights(cfg, seed=0)
+    tokens, offsets = nt_synth.workload("C2")
+    lens = np.diff(offsets)
+    gm = nt.Model(cfg, blob, max_batch_tokens=65536)
+    out, oo = gm.translate_batch(tokens, offsets, token_budget=65536)
+    assert np.array_equal(np.diff(oo), [nt.n_steps(int(l)) for l in lens])
+    assert out.min() >= 0 and out.max() < cfg["vocab"]
+    rng = np.random.default_rng(2024)
+    order = np.argsort(-lens, kind="stable")
+    sample = np.unique(np.concatenate([rng.choice(len(lens), size=300, replace=False), order[:3], order[-40:]]))
+    om = oracle.Model(cfg, blob)
+    sents = [tokens[offsets[i]:offsets[i + 1]] for i in sample]
+    sub_off = np.concatenate([[0], np.cumsum([len(s) for s in sents])])
+    o_out, o_oo, _ = om.translate(np.concatenate(sents), sub_off)
+    bad, worst = audit_mismatches(om, sents, [out[oo[i]:oo[i + 1]] for i in sample], split(o_out, o_oo), cfg)
+    frac = 1.0 - bad / len(sample)
+    print(f"C2 greedy: {len(sample) - bad}/{len(sample)} sampled sentences identical ({100 * frac:.2f} %), worst gap {worst:.2e}")
+    assert frac >= 0.99
