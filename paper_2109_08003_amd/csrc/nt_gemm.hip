@@ -35,10 +35,13 @@ constexpr int LDS_LD = BK + 8;  // halfs per LDS row: 144 B keeps 16-byte alignm
 // Accumulate the 128x128 tile at (m0, n0) over the whole K.
 // acc[mb][nb][v] is C[row = wm*64 + mb*32 + (v/4)*8 + (lane/32)*4 + v%4][col = wn*64 + nb*32 + lane%32].
 // Rows beyond M / N re-read the last valid row (never stored), which keeps the loads branch-free.
-template <int AMODE>
+// SWAP exchanges the operand roles of the MFMA, which transposes every 32x32 block: then
+// acc[mb][nb][v] is C[row = wm*64 + mb*32 + lane%32][col = wn*64 + nb*32 + (v/4)*8 + (lane/32)*4 + v%4],
+// i.e. a lane owns one row and its registers run along the columns.
+template <int AMODE, bool SWAP = false>
 __device__ __forceinline__ void mainloop(const void *A, const void *A2, long lda, int M, const _Float16 *Wt, int N,
                                          int K, int m0, int n0, _Float16 *sAhi, _Float16 *sAlo, _Float16 *sB,
-                                         floatx16 (&acc)[2][2]) {
+                                         floatx16 (&acc)[2][2], const int *row_map = nullptr) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave >> 1, wn = wave & 1, li = lane & 31, g = lane >> 5;
 #pragma unroll
@@ -50,6 +53,16 @@ __device__ __forceinline__ void mainloop(const void *A, const void *A2, long lda
   // registers holding the next K-slab
   constexpr int NRA = (AMODE == A_F16) ? 4 : 8;
   u32x4 ra[NRA], rb[4];  // native vectors: HIP's uint4 struct is not reliably kept in registers here
+  // A rows of this thread's four fp16 chunks (optionally gathered through row_map)
+  long arow[4];
+  if constexpr (AMODE != A_F32) {
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int row = (tid + 256 * i) >> 3;
+      const int m = (m0 + row < M) ? m0 + row : M - 1;
+      arow[i] = (long)(row_map ? row_map[m] : m) * lda;
+    }
+  }
   auto load_slab = [&](int k0) {
     if constexpr (AMODE == A_F32) {
       const float *Af = (const float *)A;
@@ -63,10 +76,9 @@ __device__ __forceinline__ void mainloop(const void *A, const void *A2, long lda
       const _Float16 *Ah = (const _Float16 *)A, *Al = (const _Float16 *)A2;
 #pragma unroll
       for (int i = 0; i < 4; i++) {
-        const int c = tid + 256 * i, row = c >> 3, kc = c & 7;
-        const int m = (m0 + row < M) ? m0 + row : M - 1;
-        ra[i] = *(const u32x4 *)(Ah + (long)m * lda + k0 + kc * 8);
-        if constexpr (AMODE == A_PLANES) ra[NRA - 4 + i] = *(const u32x4 *)(Al + (long)m * lda + k0 + kc * 8);
+        const int kc = (tid + 256 * i) & 7;
+        ra[i] = *(const u32x4 *)(Ah + arow[i] + k0 + kc * 8);
+        if constexpr (AMODE == A_PLANES) ra[NRA - 4 + i] = *(const u32x4 *)(Al + arow[i] + k0 + kc * 8);
       }
     }
 #pragma unroll
@@ -128,9 +140,15 @@ __device__ __forceinline__ void mainloop(const void *A, const void *A2, long lda
       for (int mb = 0; mb < 2; mb++)
 #pragma unroll
         for (int nb = 0; nb < 2; nb++) {
-          acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[mb], b[nb], acc[mb][nb], 0, 0, 0);
-          if constexpr (AMODE != A_F16)
-            acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[mb], b[nb], acc[mb][nb], 0, 0, 0);
+          if constexpr (SWAP) {
+            acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b[nb], a[mb], acc[mb][nb], 0, 0, 0);
+            if constexpr (AMODE != A_F16)
+              acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b[nb], al[mb], acc[mb][nb], 0, 0, 0);
+          } else {
+            acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[mb], b[nb], acc[mb][nb], 0, 0, 0);
+            if constexpr (AMODE != A_F16)
+              acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[mb], b[nb], acc[mb][nb], 0, 0, 0);
+          }
         }
     }
   }
@@ -380,13 +398,38 @@ __device__ __forceinline__ void butterfly_step(unsigned long long (&k)[32], int 
   }
 }
 
+__device__ __forceinline__ float key_value(unsigned long long key) {
+  unsigned int b = (unsigned int)(key >> 32);
+  b = (b & 0x80000000u) ? (b & 0x7FFFFFFFu) : ~b;
+  return __uint_as_float(b);
+}
+
+// Butterfly over the 32 column lanes on (best key, runner-up value) pairs.
+template <int HALF>
+__device__ __forceinline__ void butterfly_step2(unsigned long long (&k)[32], float (&s2)[32], int lane) {
+  const bool upper = (lane & HALF) != 0;
+#pragma unroll
+  for (int i = 0; i < HALF; i++) {
+    const unsigned long long a = k[i], b = k[i + HALF];
+    const float sa = s2[i], sb = s2[i + HALF];
+    const unsigned long long send = upper ? a : b, keep = upper ? b : a;
+    const float ssend = upper ? sa : sb, skeep = upper ? sb : sa;
+    const unsigned long long recv = shfl_xor_u64(send, HALF);
+    const float srecv = __shfl_xor(ssend, HALF, 64);
+    const bool take = recv > keep;
+    const unsigned long long loser = take ? keep : recv;
+    k[i] = take ? recv : keep;
+    s2[i] = fmaxf(fmaxf(skeep, srecv), loser ? key_value(loser) : -INFINITY);
+  }
+}
+
 constexpr int VOCAB_TILES_TARGET_WGS = 1024;
 
 static int vocab_tiles_per_wg(int M, int N) {
   int mt = (M + BM - 1) / BM, nt_ = (N + BN - 1) / BN;
   int tpw = (int)(((long)mt * nt_ + VOCAB_TILES_TARGET_WGS - 1) / VOCAB_TILES_TARGET_WGS);
   if (tpw < 1) tpw = 1;
-  if (tpw > 8) tpw = 8;
+  if (tpw > 10) tpw = 10;
   return tpw;
 }
 
@@ -395,54 +438,82 @@ int vocab_argmax_partials(int M, int N) {
   return 2 * ((nt_ + tpw - 1) / tpw);
 }
 
-// h: two fp16 planes (head at h, tail at h_lo), [M][ldh].  Workgroup id -> (strip of vocabulary
-// tiles, m tile), XCD-aware with the strips split over the XCDs.
+// Two variants of one kernel.
+//  CERT = false ("exact"): logits from the head/tail plane pair of h.  Either every row m < M is
+//    processed and per-strip partial keys go to pk[m * n_partials + p], or (row_map != nullptr) the
+//    rows row_map[0 .. *count) are gathered and each result is folded into final_key[slot] with a
+//    64-bit atomic max (order-independent, hence still deterministic).
+//  CERT = true ("single pass"): logits from the head plane only; besides the partial keys the
+//    runner-up logit of every strip goes to ps, so that the caller can certify the arg-max (see
+//    argmax_select_kernel).
+// Workgroup id -> (strip of vocabulary tiles, m slot), XCD-aware with the strips split over the XCDs;
+// a workgroup walks m tiles m_slot, m_slot + m_par, ...
+template <bool CERT>
 __global__ __launch_bounds__(256) void vocab_argmax_kernel(const _Float16 *h, const _Float16 *h_lo, long ldh,
                                                            const _Float16 *Wt, int M, int N, int K, int tiles_per_wg,
-                                                           int n_partials, unsigned long long *pk) {
+                                                           int n_partials, int m_par, unsigned long long *pk, float *ps,
+                                                           const int *row_map, const int *count,
+                                                           unsigned long long *final_key) {
   __shared__ __attribute__((aligned(16))) _Float16 sAhi[BM * LDS_LD];
-  __shared__ __attribute__((aligned(16))) _Float16 sAlo[BM * LDS_LD];
+  __shared__ __attribute__((aligned(16))) _Float16 sAlo[CERT ? 8 : BM * LDS_LD];
   __shared__ __attribute__((aligned(16))) _Float16 sB[BN * LDS_LD];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave >> 1, wn = wave & 1, li = lane & 31, g = lane >> 5;
-  const int tiles_m = (M + BM - 1) / BM, strips = n_partials / 2;
+  const int strips = n_partials / 2;
   const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-  const int strip = (j / tiles_m) * 8 + xcd, mt = j % tiles_m;
+  const int strip = (j / m_par) * 8 + xcd, m_slot = j % m_par;
   if (strip >= strips) return;
-  const int m0 = mt * BM;
+  if (count) M = *count;  // number of gathered rows, decided on the device
   const int n_tiles = (N + BN - 1) / BN;
-  unsigned long long best = 0ull;
-  for (int tt = 0; tt < tiles_per_wg; tt++) {
-    const int tile = strip * tiles_per_wg + tt;
-    if (tile >= n_tiles) break;  // uniform over the workgroup
-    const int n0 = tile * BN;
-    floatx16 acc[2][2];
-    mainloop<A_PLANES>(h, h_lo, ldh, M, Wt, N, K, m0, n0, sAhi, sAlo, sB, acc);
-    unsigned long long keys[32];
+  for (int m0 = m_slot * BM; m0 < M; m0 += m_par * BM) {
+    // The MFMA blocks are transposed (SWAP): a lane owns two rows (one per mb) and its accumulator
+    // registers run along the vocabulary, so the reduction over the vocabulary stays inside the lane:
+    // running largest logit, its column and the runner-up, over all tiles of the strip.
+    float rmax[2] = {-INFINITY, -INFINITY}, rsec[2] = {-INFINITY, -INFINITY};
+    int ridx[2] = {0, 0};
+    for (int tt = 0; tt < tiles_per_wg; tt++) {
+      const int tile = strip * tiles_per_wg + tt;
+      if (tile >= n_tiles) break;  // uniform over the workgroup
+      const int n0 = tile * BN;
+      floatx16 acc[2][2];
+      mainloop<CERT ? A_F16 : A_PLANES, true>(h, h_lo, ldh, M, Wt, N, K, m0, n0, sAhi, sAlo, sB, acc, row_map);
+      const bool full = n0 + BN <= N;
 #pragma unroll
-    for (int mb = 0; mb < 2; mb++)
+      for (int mb = 0; mb < 2; mb++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) {
-        unsigned long long k = 0ull;
+        for (int nb = 0; nb < 2; nb++)
 #pragma unroll
-        for (int nb = 0; nb < 2; nb++) {
-          const int n = n0 + wn * 64 + nb * 32 + li;
-          const unsigned long long c = (n < N) ? argmax_key(acc[mb][nb][v], n) : 0ull;
-          k = c > k ? c : k;
+          for (int v = 0; v < 16; v++) {  // columns ascend with (nb, v): on equal logits the lower column stays
+            const int n = n0 + wn * 64 + nb * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+            const float val = (full || n < N) ? acc[mb][nb][v] : -INFINITY;
+            if (CERT) rsec[mb] = fmaxf(rsec[mb], fminf(rmax[mb], val));
+            const bool gt = val > rmax[mb];
+            rmax[mb] = gt ? val : rmax[mb];
+            ridx[mb] = gt ? n : ridx[mb];
+          }
+    }
+#pragma unroll
+    for (int mb = 0; mb < 2; mb++) {
+      // the two lane groups hold interleaved columns of the same row: merge them
+      unsigned long long key = (rmax[mb] == -INFINITY) ? 0ull : argmax_key(rmax[mb], ridx[mb]);
+      float second = rsec[mb];
+      const unsigned long long okey = shfl_xor_u64(key, 32);
+      const float osec = __shfl_xor(second, 32, 64);
+      const bool take = okey > key;
+      const unsigned long long loser = take ? key : okey;
+      if (CERT) second = fmaxf(fmaxf(second, osec), loser ? key_value(loser) : -INFINITY);
+      key = take ? okey : key;
+      const int m = m0 + wm * 64 + mb * 32 + li;
+      if (g == 0 && m < M) {
+        if (final_key) {
+          atomicMax(final_key + m, key);
+        } else {
+          pk[(long)m * n_partials + strip * 2 + wn] = key;
+          if (CERT) ps[(long)m * n_partials + strip * 2 + wn] = second;
         }
-        keys[mb * 16 + v] = k;
       }
-    // reduce over the 32 column lanes; afterwards lane li holds slot li (mb = li/16, v = li%16)
-    butterfly_step<16>(keys, lane);
-    butterfly_step<8>(keys, lane);
-    butterfly_step<4>(keys, lane);
-    butterfly_step<2>(keys, lane);
-    butterfly_step<1>(keys, lane);
-    best = keys[0] > best ? keys[0] : best;
+    }
   }
-  const int mb = li >> 4, v = li & 15;
-  const int m = m0 + wm * 64 + mb * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
-  if (m < M) pk[(long)m * n_partials + strip * 2 + wn] = best;
 }
 
 hipError_t launch_vocab_argmax(const _Float16 *h, const _Float16 *h_lo, long ldh, const _Float16 *Wt, int M, int N,
@@ -451,7 +522,77 @@ hipError_t launch_vocab_argmax(const _Float16 *h, const _Float16 *h_lo, long ldh
   const int tpw = vocab_tiles_per_wg(M, N), np = vocab_argmax_partials(M, N);
   const int tiles_m = (M + BM - 1) / BM, strips = np / 2;
   dim3 grid(((strips + 7) / 8) * 8 * tiles_m), block(256);
-  hipLaunchKernelGGL(vocab_argmax_kernel, grid, block, 0, s, h, h_lo, ldh, Wt, M, N, K, tpw, np, pk);
+  hipLaunchKernelGGL(vocab_argmax_kernel<false>, grid, block, 0, s, h, h_lo, ldh, Wt, M, N, K, tpw, np, tiles_m, pk,
+                     (float *)nullptr, (const int *)nullptr, (const int *)nullptr, (unsigned long long *)nullptr);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Certified single-pass arg-max.  With h = hi + lo, the head-only logit l'(v) = hi . w_v differs
+// from the head+tail logit by at most |lo . w_v| <= ||lo|| * max_v ||w_v||.  If the head-only
+// winner leads the runner-up by more than twice that bound (plus a little slack for the fp32
+// accumulation order) it is also the winner of the head+tail logits, and the second MFMA pass is
+// not needed.  The few rows that fail the test (about 2 % with flat random logits) are collected
+// and recomputed with both planes by the gathered variant of the kernel above.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void argmax_select_kernel(const unsigned long long *pk, const float *ps, int n_partials,
+                                                            int rows, const float *lo_norm, float w_norm_max,
+                                                            int32_t *tok, int32_t *slot_of_row, int32_t *list,
+                                                            int32_t *count, unsigned long long *final_key) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  unsigned long long best = 0ull;
+  float second = -INFINITY;
+  for (int i = lane; i < n_partials; i += 64) {
+    const unsigned long long k = pk[(long)r * n_partials + i];
+    const float s2 = ps[(long)r * n_partials + i];
+    const bool take = k > best;
+    const unsigned long long loser = take ? best : k;
+    second = fmaxf(fmaxf(second, s2), loser ? key_value(loser) : -INFINITY);
+    best = take ? k : best;
+  }
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    const unsigned long long ob = shfl_xor_u64(best, m);
+    const float os = __shfl_xor(second, m, 64);
+    const bool take = ob > best;
+    const unsigned long long loser = take ? best : ob;
+    second = fmaxf(fmaxf(second, os), loser ? key_value(loser) : -INFINITY);
+    best = take ? ob : best;
+  }
+  if (lane != 0) return;
+  tok[r] = (int32_t)(0xFFFFFFFFu - (unsigned int)best);
+  const float gap = key_value(best) - second;
+  const float bound = 2.f * lo_norm[r] * w_norm_max + 1e-4f;
+  if (gap > bound) {
+    slot_of_row[r] = -1;
+  } else {
+    const int sl = atomicAdd(count, 1);  // which slot a row gets does not affect its result
+    slot_of_row[r] = sl;
+    list[sl] = r;
+    final_key[sl] = 0ull;
+  }
+}
+
+hipError_t launch_vocab_argmax_certified(const _Float16 *h, const _Float16 *h_lo, long ldh, const _Float16 *Wt, int M,
+                                         int N, int K, const float *lo_norm, float w_norm_max, unsigned long long *pk,
+                                         float *ps, int32_t *tok, int32_t *slot_of_row, int32_t *list, int32_t *count,
+                                         unsigned long long *final_key, hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  const int tpw = vocab_tiles_per_wg(M, N), np = vocab_argmax_partials(M, N);
+  const int tiles_m = (M + BM - 1) / BM, strips = np / 2;
+  hipLaunchKernelGGL(vocab_argmax_kernel<true>, dim3(((strips + 7) / 8) * 8 * tiles_m), dim3(256), 0, s, h, h_lo, ldh, Wt,
+                     M, N, K, tpw, np, tiles_m, pk, ps, (const int *)nullptr, (const int *)nullptr,
+                     (unsigned long long *)nullptr);
+  hipLaunchKernelGGL(argmax_select_kernel, dim3((M + 3) / 4), dim3(256), 0, s, pk, ps, np, M, lo_norm, w_norm_max, tok,
+                     slot_of_row, list, count, final_key);
+  // recompute of the uncertified rows: one vocabulary tile per workgroup, every workgroup walks all
+  // gathered m tiles (normally one); the row count is read on the device
+  const int n_tiles = (N + BN - 1) / BN;
+  hipLaunchKernelGGL(vocab_argmax_kernel<false>, dim3(((n_tiles + 7) / 8) * 8), dim3(256), 0, s, h, h_lo, ldh, Wt, M, N, K,
+                     1, 2 * n_tiles, 1, (unsigned long long *)nullptr, (float *)nullptr, (const int *)list,
+                     (const int *)count, final_key);
   return hipGetLastError();
 }
 

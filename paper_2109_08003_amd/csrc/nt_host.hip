@@ -44,6 +44,9 @@ constexpr bool kEncF32 = true;
 constexpr bool kCrossF32 = false;
 // Decoder projections with at most this many active rows use the one-round-trip kernel.
 constexpr int kSkinnyMaxRows = 1024;
+// The output projection uses the certified single-pass arg-max from this many active rows on; below,
+// the step is bound by the weight stream and the two-plane kernel costs the same.
+constexpr int kCertMinRows = 512;
 constexpr size_t kEncElt = kEncF32 ? 4 : 2, kCrossElt = kCrossF32 ? 4 : 2;
 
 // Launch `call`; when timing of family `id` is on, bracket it with two events on the stream and
@@ -143,6 +146,10 @@ struct nt_model {
   std::vector<float *> self_kv;   // per decoder layer [self_positions, 2d]
   float *z = nullptr, *a32 = nullptr, *q32 = nullptr, *ctx32 = nullptr, *u32 = nullptr;  // [Br, d|F]
   unsigned long long *pk = nullptr;
+  float *ps = nullptr, *lo_norm = nullptr;             // certified arg-max: runner-up partials, tail norms
+  int32_t *tok = nullptr, *slot_of_row = nullptr, *cert_list = nullptr;
+  unsigned long long *final_key = nullptr;
+  float w_norm_max = 0.f;                              // max_v ||W_out[v,:]||
   int32_t *len = nullptr, *flags = nullptr;
   int32_t *d_src = nullptr, *d_len_in = nullptr, *d_out = nullptr;  // staging for nt_translate_batch
   int32_t *h_src = nullptr, *h_len = nullptr, *h_out = nullptr;     // pinned
@@ -359,6 +366,16 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
   HIP_TRY(hipMemcpyAsync(m->d_w, pk.img.data(), m->w_bytes, hipMemcpyHostToDevice, s));
   for (auto &f : fixes) *f.slot = m->d_w + f.off;
   if (cfg->tie_output) m->Wout = m->E;
+  {  // largest row norm of the output matrix, rounded up (bound used by the certified arg-max)
+    const _Float16 *Wo = (const _Float16 *)h_blob_fp16 + (cfg->tie_output ? 0 : (int64_t)V * d);
+    double mx = 0.0;
+    for (int v = 0; v < V; v++) {
+      double q = 0.0;
+      for (int k = 0; k < d; k++) { const double w = (double)(float)Wo[(int64_t)v * d + k]; q += w * w; }
+      mx = std::max(mx, q);
+    }
+    m->w_norm_max = (float)(std::sqrt(mx) * 1.0001);
+  }
 
   // ---- arena: the peak footprint is fixed here, nothing is allocated afterwards ----
   const int64_t Mt = m->max_tokens, Br = m->max_rows;
@@ -381,7 +398,10 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
   for (int l = 0; l < cfg->n_dec; l++) o_self[l] = cv.take((size_t)m->self_positions * 2 * d * 4);
   const size_t o_z = cv.take((size_t)Br * d * 4), o_a32 = cv.take((size_t)Br * d * 4), o_q32 = cv.take((size_t)Br * d * 4),
                o_ctx32 = cv.take((size_t)Br * d * 4), o_u32 = cv.take((size_t)Br * std::max(F, 1) * 4),
-               o_pk = cv.take((size_t)m->pk_elems * 8), o_len = cv.take((size_t)Br * 4), o_flags = cv.take(64),
+               o_pk = cv.take((size_t)m->pk_elems * 8), o_ps = cv.take((size_t)m->pk_elems * 4),
+               o_lon = cv.take((size_t)Br * 4), o_tok = cv.take((size_t)Br * 4), o_slot = cv.take((size_t)Br * 4),
+               o_clist = cv.take((size_t)Br * 4), o_fkey = cv.take((size_t)Br * 8),
+               o_len = cv.take((size_t)Br * 4), o_flags = cv.take(64),
                o_src = cv.take((size_t)Mt * 4), o_lin = cv.take((size_t)Br * 4), o_out = cv.take((size_t)m->self_positions * 4);
   m->arena_bytes = cv.off;
   if (hipMalloc((void **)&m->d_arena, m->arena_bytes) != hipSuccess) return fail(NT_ENOMEM, "hipMalloc of %zu arena bytes failed", m->arena_bytes);
@@ -391,6 +411,9 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
   for (int l = 0; l < cfg->n_dec; l++) { m->cross.push_back(A + o_cross[l]); m->self_kv.push_back(at<float>(A, o_self[l])); }
   m->z = at<float>(A, o_z); m->a32 = at<float>(A, o_a32); m->q32 = at<float>(A, o_q32); m->ctx32 = at<float>(A, o_ctx32);
   m->u32 = at<float>(A, o_u32); m->pk = at<unsigned long long>(A, o_pk); m->len = at<int32_t>(A, o_len);
+  m->ps = at<float>(A, o_ps); m->lo_norm = at<float>(A, o_lon); m->tok = at<int32_t>(A, o_tok);
+  m->slot_of_row = at<int32_t>(A, o_slot); m->cert_list = at<int32_t>(A, o_clist);
+  m->final_key = at<unsigned long long>(A, o_fkey);
   m->flags = at<int32_t>(A, o_flags); m->d_src = at<int32_t>(A, o_src); m->d_len_in = at<int32_t>(A, o_lin);
   m->d_out = at<int32_t>(A, o_out);
   HIP_TRY(nt::launch_fill_i32(m->flags, 16, 0, s));
@@ -492,6 +515,7 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
     return lo;
   };
   int partials_prev = 0;
+  bool prev_cert = false;
   const double dd = (double)d, ca = (double)kCrossElt;
   auto gemm_bytes = [&](double rows, double k, double n, bool resid) {
     return rows * k * 4 + n * k * 2 + rows * n * 4 + (resid ? rows * n * 4 : 0.0);
@@ -504,6 +528,8 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
     a.pk = d_logits ? nullptr : m->pk; a.n_partials = partials_prev; a.out = d_out; a.out_ld = T;
     a.forced = d_forced; a.forced_ld = T; a.E = m->E; a.pe = m->pe; a.gamma = m->dec[0].ln1.g; a.beta = m->dec[0].ln1.b;
     a.eps = c.ln_eps; a.z = m->z; a.a = nullptr; a.flags = m->flags;
+    a.prev_cert = prev_cert ? 1 : 0; a.tok = m->tok; a.slot_of_row = m->slot_of_row; a.final_key = m->final_key;
+    a.cert_count = m->flags + 4;
     if (d_logits && rows_now == 0) break;  // no tokens to collect in this mode (pk == nullptr)
     KT(K_STEP_BEGIN, rows_prev * (partials_prev * 8.0 + 4) + rows_now * dd * 14, rows_now * dd * 10,
        nt::launch_step_begin(a, s));
@@ -568,7 +594,7 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
     _Float16 *h_hi = (_Float16 *)m->a32, *h_lo = h_hi + (long)m->max_rows * d;
     KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd,
        nt::launch_layer_norm(m->z, R, d, m->dec_final.g, m->dec_final.b, c.ln_eps, h_hi, nt::OUT_PLANES,
-                             (long)m->max_rows * d, s));
+                             (long)m->max_rows * d, s, m->lo_norm));
     if (d_logits) {
       nt::GemmEpilogue e;
       e.dst0 = d_logits + (long)t * V; e.ld0 = (long)T * V; e.n_split = V;
@@ -576,8 +602,14 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
          nt::launch_gemm(nt::A_PLANES, true, h_hi, h_lo, d, m->Wout, R, V, d, e, s));
     } else {
       const int np_ = nt::vocab_argmax_partials(R, V);
-      KT(K_VOCAB_ARGMAX, (double)V * dd * 2 + Rd * dd * 4 + Rd * np_ * 8, 2 * Rd * dd * V,
-         nt::launch_vocab_argmax(h_hi, h_lo, d, m->Wout, R, V, d, m->pk, s));
+      prev_cert = R >= kCertMinRows;
+      if (prev_cert)
+        KT(K_VOCAB_ARGMAX, (double)V * dd * 2 + Rd * dd * 4 + Rd * np_ * 8, 2 * Rd * dd * V,
+           nt::launch_vocab_argmax_certified(h_hi, h_lo, d, m->Wout, R, V, d, m->lo_norm, m->w_norm_max, m->pk, m->ps,
+                                             m->tok, m->slot_of_row, m->cert_list, m->flags + 4, m->final_key, s));
+      else
+        KT(K_VOCAB_ARGMAX, (double)V * dd * 2 + Rd * dd * 4 + Rd * np_ * 8, 2 * Rd * dd * V,
+           nt::launch_vocab_argmax(h_hi, h_lo, d, m->Wout, R, V, d, m->pk, s));
       partials_prev = np_;
     }
   }

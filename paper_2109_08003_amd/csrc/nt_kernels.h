@@ -51,6 +51,16 @@ int vocab_argmax_partials(int M, int N);
 hipError_t launch_vocab_argmax(const _Float16 *h, const _Float16 *h_lo, long ldh, const _Float16 *Wt, int M, int N,
                                int K, unsigned long long *pk, hipStream_t s);
 
+// Same result as launch_vocab_argmax, usually at half the MFMA work: a head-only pass whose winner is
+// certified against a rigorous bound on the contribution of the tail (lo_norm[m] = ||tail of row m||,
+// w_norm_max = max_v ||Wt[v,:]||); rows that cannot be certified are recomputed with both planes.
+// Results: tok[m] when slot_of_row[m] < 0, else the key in final_key[slot_of_row[m]].
+// *count must be 0 when the call starts (the step-begin kernel clears it).
+hipError_t launch_vocab_argmax_certified(const _Float16 *h, const _Float16 *h_lo, long ldh, const _Float16 *Wt, int M,
+                                         int N, int K, const float *lo_norm, float w_norm_max, unsigned long long *pk,
+                                         float *ps, int32_t *tok, int32_t *slot_of_row, int32_t *list, int32_t *count,
+                                         unsigned long long *final_key, hipStream_t s);
+
 // ---- row kernels --------------------------------------------------------------------
 // x[r,:] = sqrt(d) * E[id] + PE[pos]; rows r = b*S + s, pos = s.  Out-of-range ids are
 // replaced by pad_id and flags[0] is set.  Also clamps len into [1,S] -> len_out.
@@ -59,8 +69,9 @@ hipError_t launch_embed_src(const int32_t *src, const int32_t *len, int32_t *len
 
 // out = gamma * (x - mean) / sqrt(var + eps) + beta per row of d.
 enum OutMode { OUT_F16 = 0, OUT_F32 = 1, OUT_PLANES = 2 };  // OUT_PLANES: fp16 head at out, tail at out + lo_offset
+// lo_norm (OUT_PLANES only, optional): receives the Euclidean norm of every row's tail plane.
 hipError_t launch_layer_norm(const float *x, int M, int d, const float *gamma, const float *beta, float eps,
-                             void *out, int out_mode, long lo_offset, hipStream_t s);
+                             void *out, int out_mode, long lo_offset, hipStream_t s, float *lo_norm = nullptr);
 
 // out[i] = hi[i] + lo[i] (debug readback of a head/tail plane pair)
 hipError_t launch_planes_to_float(const _Float16 *hi, const _Float16 *lo, float *out, long n, hipStream_t s);
@@ -87,6 +98,12 @@ struct StepBeginArgs {
   float eps;
   float *z, *a;
   int32_t *flags;
+  // certified arg-max of the previous step (prev_cert != 0): token = tok[r], or the key in
+  // final_key[slot_of_row[r]] when the row had to be recomputed; cert_count is cleared for this step
+  int prev_cert;
+  const int32_t *tok, *slot_of_row;
+  const unsigned long long *final_key;
+  int32_t *cert_count;
 };
 hipError_t launch_step_begin(const StepBeginArgs &a, hipStream_t s);
 

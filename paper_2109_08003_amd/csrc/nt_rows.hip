@@ -86,7 +86,8 @@ hipError_t launch_embed_src(const int32_t *src, const int32_t *len, int32_t *len
 
 template <int MODE>
 __global__ __launch_bounds__(256) void layer_norm_kernel(const float *x, int M, int d, const float *gamma,
-                                                         const float *beta, float eps, void *out, long lo_offset) {
+                                                         const float *beta, float eps, void *out, long lo_offset,
+                                                         float *lo_norm) {
   const int lane = threadIdx.x & 63;
   const long r = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= M) return;
@@ -97,6 +98,7 @@ __global__ __launch_bounds__(256) void layer_norm_kernel(const float *x, int M, 
   for (int i = 0; i < MAX_PER_LANE; i++)
     if (i < ne) v[i] = xr[lane + 64 * i];
   row_layer_norm(v, ne, d, eps, lane, gamma, beta);
+  float tail2 = 0.f;
 #pragma unroll
   for (int i = 0; i < MAX_PER_LANE; i++)
     if (i < ne) {
@@ -106,21 +108,29 @@ __global__ __launch_bounds__(256) void layer_norm_kernel(const float *x, int M, 
       } else {
         const _Float16 hi = (_Float16)v[i];
         ((_Float16 *)out)[o] = hi;
-        if (MODE == OUT_PLANES) ((_Float16 *)out)[o + lo_offset] = (_Float16)(v[i] - (float)hi);
+        if (MODE == OUT_PLANES) {
+          const _Float16 lo = (_Float16)(v[i] - (float)hi);
+          ((_Float16 *)out)[o + lo_offset] = lo;
+          tail2 += (float)lo * (float)lo;
+        }
       }
     }
+  if (MODE == OUT_PLANES && lo_norm) {
+    tail2 = wave_sum(tail2);
+    if (lane == 0) lo_norm[r] = sqrtf(tail2) * 1.0001f;  // rounded up: it is used as an upper bound
+  }
 }
 
 hipError_t launch_layer_norm(const float *x, int M, int d, const float *gamma, const float *beta, float eps,
-                             void *out, int out_mode, long lo_offset, hipStream_t s) {
+                             void *out, int out_mode, long lo_offset, hipStream_t s, float *lo_norm) {
   if (M <= 0) return hipSuccess;
   dim3 grid((M + 3) / 4), block(256);
   if (out_mode == OUT_F32)
-    hipLaunchKernelGGL(layer_norm_kernel<OUT_F32>, grid, block, 0, s, x, M, d, gamma, beta, eps, out, lo_offset);
+    hipLaunchKernelGGL(layer_norm_kernel<OUT_F32>, grid, block, 0, s, x, M, d, gamma, beta, eps, out, lo_offset, lo_norm);
   else if (out_mode == OUT_PLANES)
-    hipLaunchKernelGGL(layer_norm_kernel<OUT_PLANES>, grid, block, 0, s, x, M, d, gamma, beta, eps, out, lo_offset);
+    hipLaunchKernelGGL(layer_norm_kernel<OUT_PLANES>, grid, block, 0, s, x, M, d, gamma, beta, eps, out, lo_offset, lo_norm);
   else
-    hipLaunchKernelGGL(layer_norm_kernel<OUT_F16>, grid, block, 0, s, x, M, d, gamma, beta, eps, out, lo_offset);
+    hipLaunchKernelGGL(layer_norm_kernel<OUT_F16>, grid, block, 0, s, x, M, d, gamma, beta, eps, out, lo_offset, lo_norm);
   return hipGetLastError();
 }
 
@@ -159,7 +169,13 @@ __global__ __launch_bounds__(256) void step_begin_kernel(StepBeginArgs a) {
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= a.rows_prev) return;
   int y = a.bos_id;
-  if (a.t > 0 && a.pk) {
+  if (a.cert_count && blockIdx.x == 0 && threadIdx.x == 0) *a.cert_count = 0;
+  if (a.t > 0 && a.prev_cert) {
+    const int sl = a.slot_of_row[r];
+    y = (sl < 0) ? a.tok[r] : (int)(0xFFFFFFFFu - (unsigned int)a.final_key[sl]);
+    if (y < 0 || y >= a.vocab) y = a.pad_id;  // cannot happen: every key holds a valid id
+    if (lane == 0) a.out[(long)r * a.out_ld + a.t - 1] = y;
+  } else if (a.t > 0 && a.pk) {
     unsigned long long k = 0ull;
     const unsigned long long *p = a.pk + (long)r * a.n_partials;
     for (int i = lane; i < a.n_partials; i += 64) {
