@@ -285,10 +285,188 @@ static hipError_t enc_attention_launch(const void *qkv, const int32_t *len, void
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// Wave-per-tile variant for sentences of up to 32*NKB tokens (fp32 inputs, no relative keys).
+//
+// One wave owns 32 queries of one (sentence, head) and runs the whole attention in registers:
+// no LDS, no workgroup barrier, four independent waves per workgroup.  The score blocks are
+// computed transposed (A operand = key rows, B operand = query rows), so a lane owns one query
+// and its accumulator registers run over the keys: the softmax reduction stays inside the lane
+// plus one exchange between the two lane groups, and the probabilities are already laid out as
+// the A operand of the P V product (the MFMA contraction index may be permuted freely as long as
+// both operands use the same assignment, so V is gathered with the matching key order).
+// Split precision as above: head + tail for q, k, v and the probabilities, three MFMAs per
+// product into one accumulator (the MFMA keeps fp16 subnormals, the tails need no scaling).
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void split8u(const float *f, half8 &hi, half8 &lo) {
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+    hi[e] = (_Float16)f[e];
+    lo[e] = (_Float16)(f[e] - (float)hi[e]);
+  }
+}
+
+template <int DH, int NKB>
+__global__ __launch_bounds__(256) void enc_attention_wave_kernel(const float *qkv, const int32_t *len, _Float16 *ctx,
+                                                                 long ctx_lo_offset, int B, int S, int d, int heads,
+                                                                 int q_tiles) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, li = lane & 31, g = lane >> 5;
+  const long unit = (long)blockIdx.x * 4 + wave;
+  if (unit >= (long)B * heads * q_tiles) return;
+  const int qt = (int)(unit % q_tiles), h = (int)((unit / q_tiles) % heads), b = (int)(unit / ((long)q_tiles * heads));
+  const int L = len[b], q0 = qt * 32;
+  const long row0 = (long)b * S, ld = 3L * d;
+  const int hoff = h * DH;
+  if (q0 >= L) {  // padding queries: defined output, no work
+    for (int i = lane; i < 32 * DH; i += 64) {
+      const int r = i / DH, c = i % DH;
+      if (q0 + r < S) {
+        ctx[(row0 + q0 + r) * d + hoff + c] = (_Float16)0.f;
+        ctx[(row0 + q0 + r) * d + hoff + c + ctx_lo_offset] = (_Float16)0.f;
+      }
+    }
+    return;
+  }
+  const int nkb = (L + 31) / 32;  // <= NKB, checked by the launcher through S
+
+  // ---- scores, transposed: sc[kb][v] = q_(q0+li) . k_(kb*32 + (v/4)*8 + g*4 + v%4) ----
+  floatx16 sc[NKB];
+#pragma unroll
+  for (int kb = 0; kb < NKB; kb++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) sc[kb][v] = 0.f;
+  const float *qp = qkv + (row0 + min(q0 + li, L - 1)) * ld + hoff + g * 32;
+  for (int c = 0; c < DH / 64; c++) {
+    float f[32];
+#pragma unroll
+    for (int u = 0; u < 8; u++) *(float4 *)(f + 4 * u) = *(const float4 *)(qp + c * 64 + u * 4);
+    half8 qh[4], ql[4];
+#pragma unroll
+    for (int u = 0; u < 4; u++) split8u(f + 8 * u, qh[u], ql[u]);
+#pragma unroll
+    for (int kb = 0; kb < NKB; kb++) {
+      if (kb < nkb) {
+        const float *kp = qkv + (row0 + min(kb * 32 + li, L - 1)) * ld + d + hoff + g * 32 + c * 64;
+#pragma unroll
+        for (int u = 0; u < 8; u++) *(float4 *)(f + 4 * u) = *(const float4 *)(kp + u * 4);
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+          half8 kh, kl;
+          split8u(f + 8 * u, kh, kl);
+          sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kh, qh[u], sc[kb], 0, 0, 0);
+          sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kl, qh[u], sc[kb], 0, 0, 0);
+          sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kh, ql[u], sc[kb], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // ---- fp32 softmax over the keys: in-lane, then one exchange between the lane groups ----
+  float mx = -INFINITY;
+#pragma unroll
+  for (int kb = 0; kb < NKB; kb++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) {
+      const int key = kb * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+      sc[kb][v] = (kb < nkb && key < L) ? sc[kb][v] : -INFINITY;  // masked keys get weight exactly 0
+      mx = fmaxf(mx, sc[kb][v]);
+    }
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  float sum = 0.f;
+#pragma unroll
+  for (int kb = 0; kb < NKB; kb++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) {
+      sc[kb][v] = expf(sc[kb][v] - mx);
+      sum += sc[kb][v];
+    }
+  sum += __shfl_xor(sum, 32, 64);
+  const float inv = 1.f / sum;
+  // probabilities as A-operand fragments: k-step ks of block kb uses registers ks*8 .. ks*8+7
+  half8 ph[NKB][2], pl[NKB][2];
+#pragma unroll
+  for (int kb = 0; kb < NKB; kb++)
+#pragma unroll
+    for (int ks = 0; ks < 2; ks++) {
+      float f[8];
+#pragma unroll
+      for (int e = 0; e < 8; e++) f[e] = sc[kb][ks * 8 + e] * inv;
+      split8u(f, ph[kb][ks], pl[kb][ks]);
+    }
+
+  // ---- context = P V, one 32-column block at a time ----
+  const float *vbase = qkv + row0 * ld + 2 * d + hoff + li;
+  for (int cb = 0; cb < DH / 32; cb++) {
+    floatx16 o;
+#pragma unroll
+    for (int v = 0; v < 16; v++) o[v] = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < NKB; kb++) {
+      if (kb < nkb) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ks++) {
+          float f[8];
+#pragma unroll
+          for (int e = 0; e < 8; e++) {  // same key order as the probability registers
+            const int key = min(kb * 32 + (2 * ks + (e >> 2)) * 8 + g * 4 + (e & 3), L - 1);
+            f[e] = vbase[(long)key * ld + cb * 32];
+          }
+          half8 vh, vl;
+          split8u(f, vh, vl);
+          o = __builtin_amdgcn_mfma_f32_32x32x16_f16(ph[kb][ks], vh, o, 0, 0, 0);
+          o = __builtin_amdgcn_mfma_f32_32x32x16_f16(pl[kb][ks], vh, o, 0, 0, 0);
+          o = __builtin_amdgcn_mfma_f32_32x32x16_f16(ph[kb][ks], vl, o, 0, 0, 0);
+        }
+      }
+    }
+#pragma unroll
+    for (int v = 0; v < 16; v++) {
+      const int q = q0 + (v >> 2) * 8 + g * 4 + (v & 3);
+      if (q >= S) continue;
+      const float val = (q < L) ? o[v] : 0.f;
+      const _Float16 hi = (_Float16)val;
+      const long at_ = (row0 + q) * d + hoff + cb * 32 + li;
+      ctx[at_] = hi;
+      ctx[at_ + ctx_lo_offset] = (_Float16)(val - (float)hi);
+    }
+  }
+}
+
+template <int DH>
+static hipError_t enc_attention_wave_launch(const float *qkv, const int32_t *len, _Float16 *ctx, long ctx_lo_offset,
+                                            int B, int S, int d, int heads, hipStream_t s) {
+  const int q_tiles = (S + 31) / 32;
+  const long units = (long)B * heads * q_tiles;
+  dim3 grid((unsigned)((units + 3) / 4)), block(256);
+#define NT_WAVE_CASE(NKB)                                                                                          \
+  case NKB:                                                                                                        \
+    hipLaunchKernelGGL((enc_attention_wave_kernel<DH, NKB>), grid, block, 0, s, qkv, len, ctx, ctx_lo_offset, B, S, d, \
+                       heads, q_tiles);                                                                            \
+    break;
+  switch (q_tiles) {
+    NT_WAVE_CASE(1)
+    NT_WAVE_CASE(2)
+    NT_WAVE_CASE(3)
+    NT_WAVE_CASE(4)
+    default: return hipErrorInvalidValue;
+  }
+#undef NT_WAVE_CASE
+  return hipGetLastError();
+}
+
 hipError_t launch_enc_attention(const void *qkv, bool f32, const int32_t *len, void *ctx, long ctx_lo_offset, int B,
                                 int S, int d, int heads, const float *rk, int clip, hipStream_t s) {
   if (B <= 0 || S <= 0) return hipSuccess;
   if (clip > MAX_CLIP) return hipErrorInvalidValue;
+  if (f32 && !rk && S <= 128) {  // register-resident wave-per-tile kernel
+    switch (d / heads) {
+      case 64: return enc_attention_wave_launch<64>((const float *)qkv, len, (_Float16 *)ctx, ctx_lo_offset, B, S, d, heads, s);
+      case 128: return enc_attention_wave_launch<128>((const float *)qkv, len, (_Float16 *)ctx, ctx_lo_offset, B, S, d, heads, s);
+      case 256: return enc_attention_wave_launch<256>((const float *)qkv, len, (_Float16 *)ctx, ctx_lo_offset, B, S, d, heads, s);
+      case 512: return enc_attention_wave_launch<512>((const float *)qkv, len, (_Float16 *)ctx, ctx_lo_offset, B, S, d, heads, s);
+      default: return hipErrorInvalidValue;
+    }
+  }
 #define NT_ATTN_CASE(DH)                                                                                   \
   case DH:                                                                                                 \
     return f32 ? enc_attention_launch<DH, true>(qkv, len, ctx, ctx_lo_offset, B, S, d, heads, rk, clip, s) \
