@@ -40,6 +40,7 @@ def main():
     ap.add_argument("--sentences", type=int, default=None, help="default: the workload's own count")
     ap.add_argument("--budget", type=int, default=65536,
                     help="token budget per batch (best of the 4k/16k/64k sweep of the throughput configuration)")
+    ap.add_argument("--lanes", type=int, default=0, help="batches in flight (0 = the library's default)")
     ap.add_argument("--cpu-sentences", type=int, default=1024, help="oracle sample size (0 = skip)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one device-to-device copy of this many MiB (calibrates rocprofv3 byte counters)")
@@ -60,7 +61,10 @@ def main():
     tokens, offsets = nt_synth.workload(args.workload, args.sentences)
     lens = np.diff(offsets).astype(np.int32)
     n_sent, src_tokens = len(lens), int(offsets[-1])
-    model = nt.Model(cfg, blob, max_batch_tokens=args.budget)
+    model = nt.Model(cfg, blob, max_batch_tokens=args.budget, pipeline_lanes=args.lanes)
+    # independent batches run on the model's pipeline lanes (shared weights, one arena and stream each)
+    lanes = [model.lane(i) for i in range(model.n_lanes())]
+    streams = [torch.cuda.Stream() for _ in lanes]
 
     # ---- batches resident in HBM (untimed set-up) ----
     order, starts = nt.plan_batches(lens, args.budget)
@@ -80,9 +84,10 @@ def main():
     dec_steps = int(sum(b["T"] for b in batches))
 
     def one_pass():
-        for b in batches:
-            model.encode(b["d_src"], b["d_len"])
-            model.decode_greedy(b["B"], b["T"], b["d_out"], row_steps=b["steps"])
+        for k, b in enumerate(batches):
+            ln, st = lanes[k % len(lanes)], streams[k % len(lanes)]
+            ln.encode(b["d_src"], b["d_len"], stream=st)
+            ln.decode_greedy(b["B"], b["T"], b["d_out"], row_steps=b["steps"], stream=st)
 
     for _ in range(args.warmup):
         one_pass()
@@ -157,7 +162,7 @@ def main():
         "config": {"workload": f"{args.workload}: {n_sent} sentences (lognormal lengths, Zipf ids), student "
                                f"{cfg['n_enc']}-{cfg['n_dec']} d={cfg['d_model']} heads={cfg['n_heads']} ffn={cfg['d_ffn']} "
                                f"V={cfg['vocab']}, greedy ceil(1.2 len)+2 steps",
-                   "token_budget": args.budget, "batches": len(batches), "source_tokens": src_tokens,
+                   "token_budget": args.budget, "batches": len(batches), "pipeline_lanes": len(lanes), "source_tokens": src_tokens,
                    "target_tokens": tgt_tokens, "decode_steps": dec_steps},
         "source_tokens_per_s": round(src_tokens / dt, 1), "target_tokens_per_s": round(tgt_tokens / dt, 1),
         "host_inclusive_words_per_s": round(src_tokens * WORDS_PER_TOKEN / dt_host, 1),

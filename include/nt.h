@@ -72,6 +72,9 @@ typedef struct {
   float ln_eps;
   int32_t max_batch_rows;
   int64_t max_batch_tokens;
+  int32_t pipeline_lanes; /* batches kept in flight by nt_translate_batch, each with its own arena and
+                             internal stream; 0 = default (3), 1 = no overlap */
+  int32_t reserved;       /* must be 0 */
 } nt_config;
 
 /* Number of fp16 elements the weight blob of this configuration must hold (0 if invalid). */
@@ -191,6 +194,16 @@ int nt_debug_timing_count(void);
 const char *nt_debug_timing_name(int kernel);
 int nt_debug_timing_read(nt_model *m, int kernel, double *total_ms, int64_t *launches, double *bytes, double *flops,
                          void *hip_stream);
+
+/*
+ * Pipeline lanes.  A model holds pipeline_lanes lanes that share the weights; each lane has its own
+ * arena, caches and state.  nt_pipeline_lane(m, i) returns lane i (lane 0 is m itself) as a model
+ * handle that nt_encode / nt_decode_greedy / nt_debug_* accept, so that a caller who keeps its batches
+ * on the device can run independent batches on different streams at the same time.  Lane handles are
+ * owned by m: never pass them to nt_free.  nt_translate_batch uses all lanes by itself.
+ */
+int nt_pipeline_lanes(const nt_model *m);
+nt_model *nt_pipeline_lane(nt_model *m, int i);
 
 /* Bytes of device memory held by the model (weights, arena, caches). */
 int64_t nt_device_bytes(const nt_model *m);

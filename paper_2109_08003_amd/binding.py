@@ -16,13 +16,15 @@ LIB_PATH = os.path.join(_HERE, "libnt.so")
 EXPORTS = ["nt_param_count", "nt_n_steps", "nt_load_weights", "nt_free", "nt_encode", "nt_decode_greedy",
            "nt_translate_batch", "nt_plan_batches", "nt_debug_encoder_out", "nt_debug_teacher_forced_logits",
            "nt_check_device_flags", "nt_device_bytes", "nt_last_error", "nt_debug_timing_enable",
-           "nt_debug_timing_count", "nt_debug_timing_name", "nt_debug_timing_read"]
+           "nt_debug_timing_count", "nt_debug_timing_name", "nt_debug_timing_read", "nt_pipeline_lanes",
+           "nt_pipeline_lane"]
 
 
 class NtConfig(C.Structure):
     _fields_ = [("struct_size", C.c_uint32)] + [(k, C.c_int32) for k in (
         "n_enc", "n_dec", "d_model", "n_heads", "d_ffn", "vocab", "max_len", "rpr_clip", "tie_output", "bos_id",
-        "pad_id")] + [("ln_eps", C.c_float), ("max_batch_rows", C.c_int32), ("max_batch_tokens", C.c_int64)]
+        "pad_id")] + [("ln_eps", C.c_float), ("max_batch_rows", C.c_int32), ("max_batch_tokens", C.c_int64),
+                                ("pipeline_lanes", C.c_int32), ("reserved", C.c_int32)]
 
 
 class NtError(RuntimeError):
@@ -61,6 +63,8 @@ def load_library() -> C.CDLL:
         "nt_check_device_flags": (C.c_int, [p, p]),
         "nt_device_bytes": (i64, [p]),
         "nt_last_error": (C.c_char_p, []),
+        "nt_pipeline_lanes": (C.c_int, [p]),
+        "nt_pipeline_lane": (p, [p, C.c_int]),
         "nt_debug_timing_enable": (C.c_int, [p, C.c_uint64]),
         "nt_debug_timing_count": (C.c_int, []),
         "nt_debug_timing_name": (C.c_char_p, [C.c_int]),
@@ -83,7 +87,7 @@ def _check(rc: int):
         raise NtError(rc, lib().nt_last_error().decode())
 
 
-def make_config(cfg: dict, max_batch_tokens: int, max_batch_rows: int = 0) -> NtConfig:
+def make_config(cfg: dict, max_batch_tokens: int, max_batch_rows: int = 0, pipeline_lanes: int = 0) -> NtConfig:
     c = NtConfig()
     c.struct_size = C.sizeof(NtConfig)
     for k in ("n_enc", "n_dec", "d_model", "n_heads", "d_ffn", "vocab", "max_len", "rpr_clip", "tie_output", "bos_id",
@@ -92,6 +96,8 @@ def make_config(cfg: dict, max_batch_tokens: int, max_batch_rows: int = 0) -> Nt
     c.ln_eps = float(cfg["ln_eps"])
     c.max_batch_tokens = int(max_batch_tokens)
     c.max_batch_rows = int(max_batch_rows)
+    c.pipeline_lanes = int(pipeline_lanes)
+    c.reserved = 0
     return c
 
 
@@ -131,20 +137,35 @@ def _stream_ptr(stream) -> int:
 class Model:
     """Owns one nt_model.  Methods mirror the C entry points."""
 
-    def __init__(self, cfg: dict, blob: np.ndarray, max_batch_tokens: int, max_batch_rows: int = 0, stream=None):
+    def __init__(self, cfg: dict, blob: np.ndarray, max_batch_tokens: int, max_batch_rows: int = 0, stream=None,
+                 pipeline_lanes: int = 0):
         assert blob.dtype == np.float16
         blob = np.ascontiguousarray(blob)
         self.cfg = dict(cfg)
-        c = make_config(cfg, max_batch_tokens, max_batch_rows)
+        c = make_config(cfg, max_batch_tokens, max_batch_rows, pipeline_lanes)
         h = C.c_void_p()
         _check(lib().nt_load_weights(C.byref(c), blob.ctypes.data_as(C.c_void_p), blob.nbytes, _stream_ptr(stream),
                                      C.byref(h)))
         self._h = h
 
     def close(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and getattr(self, "_owner", None) is None:
             lib().nt_free(self._h)
-            self._h = None
+        self._h = None
+
+    def n_lanes(self) -> int:
+        return int(lib().nt_pipeline_lanes(self._h))
+
+    def lane(self, i: int) -> "Model":
+        """Lane i as a Model that shares this model's weights (lane 0 is the model itself)."""
+        if i == 0:
+            return self
+        h = lib().nt_pipeline_lane(self._h, i)
+        if not h:
+            raise IndexError(i)
+        ln = object.__new__(Model)
+        ln.cfg, ln._h, ln._owner = self.cfg, C.c_void_p(h), self   # the owner frees the lanes
+        return ln
 
     def __del__(self):
         try:

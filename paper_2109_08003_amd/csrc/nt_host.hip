@@ -47,6 +47,8 @@ constexpr int kSkinnyMaxRows = 1024;
 // The output projection uses the certified single-pass arg-max from this many active rows on; below,
 // the step is bound by the weight stream and the two-plane kernel costs the same.
 constexpr int kCertMinRows = 512;
+// Batches nt_translate_batch keeps in flight when the configuration does not say (pipeline_lanes = 0).
+constexpr int kDefaultLanes = 3;
 constexpr size_t kEncElt = kEncF32 ? 4 : 2, kCrossElt = kCrossF32 ? 4 : 2;
 
 // Launch `call`; when timing of family `id` is on, bracket it with two events on the stream and
@@ -156,6 +158,17 @@ struct nt_model {
   // state left by nt_encode
   int32_t B = 0, S = 0;
   bool encoded = false;
+  // pipeline lanes: shallow clones that share the weights and own an arena, a stream and staging;
+  // nt_translate_batch keeps one batch in flight per lane so that the latency-bound kernels of
+  // one batch overlap the wide kernels of another
+  bool owns_weights = true;
+  std::vector<nt_model *> lanes;      // extra lanes (this model is lane 0)
+  hipStream_t lane_stream = nullptr;  // internal stream of this lane
+  hipEvent_t lane_done = nullptr, lane_start = nullptr;
+  bool lane_busy = false;
+  int64_t pend_i0 = 0, pend_i1 = 0;   // sentences of the batch in flight on this lane
+  int32_t pend_T = 0;
+  std::vector<int32_t> pend_steps;
 };
 
 namespace {
@@ -173,6 +186,7 @@ int check_config(const nt_config *c) {
   if (c->rpr_clip < 0 || c->rpr_clip > 16) return fail(NT_ESHAPE, "rpr_clip must be in [0,16]");
   if (c->bos_id < 0 || c->bos_id >= c->vocab || c->pad_id < 0 || c->pad_id >= c->vocab) return fail(NT_ERANGE, "bos_id/pad_id outside the vocabulary");
   if (!(c->ln_eps > 0.f)) return fail(NT_EINVAL, "ln_eps must be positive");
+  if (c->pipeline_lanes < 0 || c->pipeline_lanes > 8 || c->reserved != 0) return fail(NT_EINVAL, "pipeline_lanes must be in [0,8] and reserved 0");
   return NT_OK;
 }
 
@@ -230,6 +244,60 @@ struct Carver {
 
 hipStream_t as_stream(void *s) { return (hipStream_t)s; }
 
+// Per-lane state: the arena (activations, caches, arg-max scratch), pinned staging, stream, events.
+// The peak footprint is fixed here; nothing is allocated afterwards.
+int alloc_lane_state(nt_model *m, hipStream_t s) {
+  const nt_config *cfg = &m->c;
+  const int d = cfg->d_model, V = cfg->vocab, F = cfg->d_ffn;
+  const int64_t Mt = m->max_tokens, Br = m->max_rows;
+  m->self_positions = (6 * Mt + 4) / 5 + 3 * Br + 8;
+  if (m->self_positions < Br * 1) m->self_positions = Br;
+  {  // arg-max partials: the count per row depends only on ceil(rows / 128)
+    int64_t worst = 0;
+    for (int64_t mt = 1; (mt - 1) * 128 < Br; mt++) {
+      const int64_t rows = std::min<int64_t>(mt * 128, Br);
+      worst = std::max(worst, rows * nt::vocab_argmax_partials((int)rows, V));
+    }
+    m->pk_elems = worst;
+  }
+  Carver cv;
+  const size_t o_x = cv.take((size_t)Mt * d * 4), o_a16 = cv.take((size_t)Mt * d * kEncElt),
+               o_qkv = cv.take((size_t)Mt * 3 * d * kEncElt), o_ctx16 = cv.take((size_t)Mt * d * kEncElt),
+               o_u16 = cv.take((size_t)Mt * std::max(F, 1) * kEncElt), o_enc = cv.take((size_t)Mt * d * kEncElt);
+  std::vector<size_t> o_cross(cfg->n_dec), o_self(cfg->n_dec);
+  for (int l = 0; l < cfg->n_dec; l++) o_cross[l] = cv.take((size_t)Mt * 2 * d * kCrossElt);
+  for (int l = 0; l < cfg->n_dec; l++) o_self[l] = cv.take((size_t)m->self_positions * 2 * d * 4);
+  const size_t o_z = cv.take((size_t)Br * d * 4), o_a32 = cv.take((size_t)Br * d * 4), o_q32 = cv.take((size_t)Br * d * 4),
+               o_ctx32 = cv.take((size_t)Br * d * 4), o_u32 = cv.take((size_t)Br * std::max(F, 1) * 4),
+               o_pk = cv.take((size_t)m->pk_elems * 8), o_ps = cv.take((size_t)m->pk_elems * 4),
+               o_lon = cv.take((size_t)Br * 4), o_tok = cv.take((size_t)Br * 4), o_slot = cv.take((size_t)Br * 4),
+               o_clist = cv.take((size_t)Br * 4), o_fkey = cv.take((size_t)Br * 8),
+               o_len = cv.take((size_t)Br * 4), o_flags = cv.take(64),
+               o_src = cv.take((size_t)Mt * 4), o_lin = cv.take((size_t)Br * 4), o_out = cv.take((size_t)m->self_positions * 4);
+  m->arena_bytes = cv.off;
+  if (hipMalloc((void **)&m->d_arena, m->arena_bytes) != hipSuccess) return fail(NT_ENOMEM, "hipMalloc of %zu arena bytes failed", m->arena_bytes);
+  char *A = m->d_arena;
+  m->x = at<float>(A, o_x); m->a_enc = A + o_a16; m->qkv = A + o_qkv;
+  m->ctx_enc = A + o_ctx16; m->u_enc = A + o_u16; m->enc_out = A + o_enc;
+  for (int l = 0; l < cfg->n_dec; l++) { m->cross.push_back(A + o_cross[l]); m->self_kv.push_back(at<float>(A, o_self[l])); }
+  m->z = at<float>(A, o_z); m->a32 = at<float>(A, o_a32); m->q32 = at<float>(A, o_q32); m->ctx32 = at<float>(A, o_ctx32);
+  m->u32 = at<float>(A, o_u32); m->pk = at<unsigned long long>(A, o_pk); m->len = at<int32_t>(A, o_len);
+  m->ps = at<float>(A, o_ps); m->lo_norm = at<float>(A, o_lon); m->tok = at<int32_t>(A, o_tok);
+  m->slot_of_row = at<int32_t>(A, o_slot); m->cert_list = at<int32_t>(A, o_clist);
+  m->final_key = at<unsigned long long>(A, o_fkey);
+  m->flags = at<int32_t>(A, o_flags); m->d_src = at<int32_t>(A, o_src); m->d_len_in = at<int32_t>(A, o_lin);
+  m->d_out = at<int32_t>(A, o_out);
+  HIP_TRY(nt::launch_fill_i32(m->flags, 16, 0, s));
+  if (hipHostMalloc((void **)&m->h_src, (size_t)Mt * 4) != hipSuccess || hipHostMalloc((void **)&m->h_len, (size_t)Br * 4) != hipSuccess ||
+      hipHostMalloc((void **)&m->h_out, (size_t)m->self_positions * 4) != hipSuccess)
+    return fail(NT_ENOMEM, "pinned staging allocation failed");
+  if (hipStreamCreateWithFlags(&m->lane_stream, hipStreamNonBlocking) != hipSuccess ||
+      hipEventCreateWithFlags(&m->lane_done, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&m->lane_start, hipEventDisableTiming) != hipSuccess)
+    return fail(NT_EHIP, "stream / event creation failed");
+  return NT_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -243,11 +311,27 @@ int64_t nt_param_count(const nt_config *cfg) {
 
 int32_t nt_n_steps(int32_t len) { return (6 * len + 4) / 5 + 2; }
 
-int64_t nt_device_bytes(const nt_model *m) { return m ? (int64_t)(m->w_bytes + m->arena_bytes) : 0; }
+int64_t nt_device_bytes(const nt_model *m) {
+  if (!m) return 0;
+  int64_t n = (int64_t)(m->w_bytes + m->arena_bytes);
+  for (const nt_model *ln : m->lanes) n += (int64_t)ln->arena_bytes;
+  return n;
+}
+
+int nt_pipeline_lanes(const nt_model *m) { return m ? 1 + (int)m->lanes.size() : 0; }
+
+nt_model *nt_pipeline_lane(nt_model *m, int i) {
+  if (!m || i < 0 || i > (int)m->lanes.size()) return nullptr;
+  return i == 0 ? m : m->lanes[(size_t)i - 1];
+}
 
 void nt_free(nt_model *m) {
   if (!m) return;
-  if (m->d_w) (void)hipFree(m->d_w);
+  for (nt_model *ln : m->lanes) nt_free(ln);
+  if (m->lane_stream) (void)hipStreamDestroy(m->lane_stream);
+  if (m->lane_done) (void)hipEventDestroy(m->lane_done);
+  if (m->lane_start) (void)hipEventDestroy(m->lane_start);
+  if (m->d_w && m->owns_weights) (void)hipFree(m->d_w);
   if (m->d_arena) (void)hipFree(m->d_arena);
   if (m->h_src) (void)hipHostFree(m->h_src);
   if (m->h_len) (void)hipHostFree(m->h_len);
@@ -377,49 +461,23 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
     m->w_norm_max = (float)(std::sqrt(mx) * 1.0001);
   }
 
-  // ---- arena: the peak footprint is fixed here, nothing is allocated afterwards ----
-  const int64_t Mt = m->max_tokens, Br = m->max_rows;
-  m->self_positions = (6 * Mt + 4) / 5 + 3 * Br + 8;
-  if (m->self_positions < Br * 1) m->self_positions = Br;
-  {  // arg-max partials: the count per row depends only on ceil(rows / 128)
-    int64_t worst = 0;
-    for (int64_t mt = 1; (mt - 1) * 128 < Br; mt++) {
-      const int64_t rows = std::min<int64_t>(mt * 128, Br);
-      worst = std::max(worst, rows * nt::vocab_argmax_partials((int)rows, V));
+  rc = alloc_lane_state(m, s);
+  if (rc) return rc;
+  {  // extra pipeline lanes
+    const int n_lanes = cfg->pipeline_lanes > 0 ? cfg->pipeline_lanes : kDefaultLanes;
+    for (int i = 1; i < n_lanes; i++) {
+      nt_model *ln = new nt_model(*m);  // copies the weight pointers and layer tables
+      ln->owns_weights = false;
+      ln->lanes.clear();
+      ln->timing = Timing();
+      ln->d_arena = nullptr; ln->h_src = ln->h_len = ln->h_out = nullptr;
+      ln->lane_stream = nullptr; ln->lane_done = ln->lane_start = nullptr;
+      ln->cross.clear(); ln->self_kv.clear();
+      m->lanes.push_back(ln);
+      rc = alloc_lane_state(ln, s);
+      if (rc) return rc;
     }
-    m->pk_elems = worst;
   }
-  Carver cv;
-  const size_t o_x = cv.take((size_t)Mt * d * 4), o_a16 = cv.take((size_t)Mt * d * kEncElt),
-               o_qkv = cv.take((size_t)Mt * 3 * d * kEncElt), o_ctx16 = cv.take((size_t)Mt * d * kEncElt),
-               o_u16 = cv.take((size_t)Mt * std::max(F, 1) * kEncElt), o_enc = cv.take((size_t)Mt * d * kEncElt);
-  std::vector<size_t> o_cross(cfg->n_dec), o_self(cfg->n_dec);
-  for (int l = 0; l < cfg->n_dec; l++) o_cross[l] = cv.take((size_t)Mt * 2 * d * kCrossElt);
-  for (int l = 0; l < cfg->n_dec; l++) o_self[l] = cv.take((size_t)m->self_positions * 2 * d * 4);
-  const size_t o_z = cv.take((size_t)Br * d * 4), o_a32 = cv.take((size_t)Br * d * 4), o_q32 = cv.take((size_t)Br * d * 4),
-               o_ctx32 = cv.take((size_t)Br * d * 4), o_u32 = cv.take((size_t)Br * std::max(F, 1) * 4),
-               o_pk = cv.take((size_t)m->pk_elems * 8), o_ps = cv.take((size_t)m->pk_elems * 4),
-               o_lon = cv.take((size_t)Br * 4), o_tok = cv.take((size_t)Br * 4), o_slot = cv.take((size_t)Br * 4),
-               o_clist = cv.take((size_t)Br * 4), o_fkey = cv.take((size_t)Br * 8),
-               o_len = cv.take((size_t)Br * 4), o_flags = cv.take(64),
-               o_src = cv.take((size_t)Mt * 4), o_lin = cv.take((size_t)Br * 4), o_out = cv.take((size_t)m->self_positions * 4);
-  m->arena_bytes = cv.off;
-  if (hipMalloc((void **)&m->d_arena, m->arena_bytes) != hipSuccess) return fail(NT_ENOMEM, "hipMalloc of %zu arena bytes failed", m->arena_bytes);
-  char *A = m->d_arena;
-  m->x = at<float>(A, o_x); m->a_enc = A + o_a16; m->qkv = A + o_qkv;
-  m->ctx_enc = A + o_ctx16; m->u_enc = A + o_u16; m->enc_out = A + o_enc;
-  for (int l = 0; l < cfg->n_dec; l++) { m->cross.push_back(A + o_cross[l]); m->self_kv.push_back(at<float>(A, o_self[l])); }
-  m->z = at<float>(A, o_z); m->a32 = at<float>(A, o_a32); m->q32 = at<float>(A, o_q32); m->ctx32 = at<float>(A, o_ctx32);
-  m->u32 = at<float>(A, o_u32); m->pk = at<unsigned long long>(A, o_pk); m->len = at<int32_t>(A, o_len);
-  m->ps = at<float>(A, o_ps); m->lo_norm = at<float>(A, o_lon); m->tok = at<int32_t>(A, o_tok);
-  m->slot_of_row = at<int32_t>(A, o_slot); m->cert_list = at<int32_t>(A, o_clist);
-  m->final_key = at<unsigned long long>(A, o_fkey);
-  m->flags = at<int32_t>(A, o_flags); m->d_src = at<int32_t>(A, o_src); m->d_len_in = at<int32_t>(A, o_lin);
-  m->d_out = at<int32_t>(A, o_out);
-  HIP_TRY(nt::launch_fill_i32(m->flags, 16, 0, s));
-  if (hipHostMalloc((void **)&m->h_src, (size_t)Mt * 4) != hipSuccess || hipHostMalloc((void **)&m->h_len, (size_t)Br * 4) != hipSuccess ||
-      hipHostMalloc((void **)&m->h_out, (size_t)m->self_positions * 4) != hipSuccess)
-    return fail(NT_ENOMEM, "pinned staging allocation failed");
   HIP_TRY(hipStreamSynchronize(s));  // the packed host image goes out of scope
   guard.m = nullptr;
   *out = m;
@@ -681,9 +739,13 @@ int nt_check_device_flags(nt_model *m, void *hip_stream) {
 
 int nt_debug_timing_enable(nt_model *m, uint64_t kernel_mask) {
   if (!m) return fail(NT_EINVAL, "model is null");
-  m->timing.mask = kernel_mask & ((1ull << K_COUNT) - 1);
-  m->timing.used = 0;
-  m->timing.recs.clear();
+  std::vector<nt_model *> all{m};
+  for (nt_model *ln : m->lanes) all.push_back(ln);
+  for (nt_model *x : all) {
+    x->timing.mask = kernel_mask & ((1ull << K_COUNT) - 1);
+    x->timing.used = 0;
+    x->timing.recs.clear();
+  }
   return NT_OK;
 }
 
@@ -697,11 +759,16 @@ int nt_debug_timing_read(nt_model *m, int kernel, double *total_ms, int64_t *lau
   if (kernel < 0 || kernel >= K_COUNT) return fail(NT_EINVAL, "kernel id out of range");
   HIP_TRY(hipStreamSynchronize(as_stream(hip_stream)));
   *total_ms = 0; *launches = 0; *bytes = 0; *flops = 0;
-  for (const auto &r : m->timing.recs) {
-    if (r.id != kernel) continue;
-    float ms = 0.f;
-    HIP_TRY(hipEventElapsedTime(&ms, m->timing.pool[r.e0], m->timing.pool[r.e0 + 1]));
-    *total_ms += ms; *launches += 1; *bytes += r.bytes; *flops += r.flops;
+  std::vector<nt_model *> all{m};
+  for (nt_model *ln : m->lanes) all.push_back(ln);
+  for (nt_model *x : all) {
+    HIP_TRY(hipStreamSynchronize(x->lane_stream));
+    for (const auto &r : x->timing.recs) {
+      if (r.id != kernel) continue;
+      float ms = 0.f;
+      HIP_TRY(hipEventElapsedTime(&ms, x->timing.pool[r.e0], x->timing.pool[r.e0 + 1]));
+      *total_ms += ms; *launches += 1; *bytes += r.bytes; *flops += r.flops;
+    }
   }
   return NT_OK;
 }
@@ -766,38 +833,69 @@ int nt_translate_batch(nt_model *m, const int32_t *h_tokens, const int64_t *h_of
   int rc = nt_plan_batches(lens.data(), N, budget, (int32_t)std::min<int64_t>(rows_cap, INT32_MAX), order.data(), starts.data(), &nb);
   if (rc) return rc;
   hipStream_t s = as_stream(hip_stream);
-  std::vector<int32_t> row_steps;
-  for (int64_t k = 0; k < nb; k++) {
+  // lanes: batch k runs on lane k mod n on that lane's own stream; the host packs the next batch and
+  // unpacks finished ones while the device works
+  std::vector<nt_model *> lane{m};
+  for (nt_model *ln : m->lanes) lane.push_back(ln);
+  HIP_TRY(hipEventRecord(m->lane_start, s));  // work already queued on the caller's stream comes first
+  for (nt_model *ln : lane) {
+    HIP_TRY(hipStreamWaitEvent(ln->lane_stream, m->lane_start, 0));
+    ln->lane_busy = false;
+    ln->timing.mask = m->timing.mask;
+  }
+  auto collect = [&](nt_model *ln) -> int {  // wait for the lane's batch and scatter its rows
+    if (!ln->lane_busy) return NT_OK;
+    HIP_TRY(hipEventSynchronize(ln->lane_done));
+    for (int64_t r = 0; r < ln->pend_i1 - ln->pend_i0; r++) {
+      const int64_t si = order[(size_t)(ln->pend_i0 + r)];
+      memcpy(h_out + h_out_offsets[si], ln->h_out + (size_t)r * ln->pend_T, (size_t)ln->pend_steps[(size_t)r] * 4);
+    }
+    ln->lane_busy = false;
+    return NT_OK;
+  };
+  int first_err = NT_OK;
+  for (int64_t k = 0; k < nb && first_err == NT_OK; k++) {
+    nt_model *ln = lane[(size_t)(k % (int64_t)lane.size())];
+    if ((first_err = collect(ln))) break;
     const int64_t i0 = starts[(size_t)k], i1 = starts[(size_t)k + 1];
     const int32_t B = (int32_t)(i1 - i0), S = lens[(size_t)order[(size_t)i0]], T = nt_n_steps(S);
-    if ((int64_t)B * T > m->self_positions) return fail(NT_ENOMEM, "batch of %d rows x %d steps exceeds the self-attention cache", B, T);
-    row_steps.resize((size_t)B);
+    if ((int64_t)B * T > ln->self_positions) { first_err = fail(NT_ENOMEM, "batch of %d rows x %d steps exceeds the self-attention cache", B, T); break; }
+    ln->pend_steps.resize((size_t)B);
     for (int32_t r = 0; r < B; r++) {
       const int64_t si = order[(size_t)(i0 + r)];
       const int32_t L = lens[(size_t)si];
-      m->h_len[r] = L;
-      row_steps[(size_t)r] = nt_n_steps(L);
-      int32_t *row = m->h_src + (size_t)r * S;
+      ln->h_len[r] = L;
+      ln->pend_steps[(size_t)r] = nt_n_steps(L);
+      int32_t *row = ln->h_src + (size_t)r * S;
       memcpy(row, h_tokens + h_offsets[si], (size_t)L * 4);
       for (int32_t j = L; j < S; j++) row[j] = c.pad_id;
     }
-    HIP_TRY(hipMemcpyAsync(m->d_src, m->h_src, (size_t)B * S * 4, hipMemcpyHostToDevice, s));
-    HIP_TRY(hipMemcpyAsync(m->d_len_in, m->h_len, (size_t)B * 4, hipMemcpyHostToDevice, s));
-    rc = nt_encode(m, m->d_src, m->d_len_in, B, S, s);
-    if (rc) return rc;
-    if (m->timing.mask) {
-      m->len_prefix.assign((size_t)B + 1, 0);
-      for (int32_t r = 0; r < B; r++) m->len_prefix[(size_t)r + 1] = m->len_prefix[(size_t)r] + m->h_len[r];
+    hipStream_t ls = ln->lane_stream;
+    if (hipMemcpyAsync(ln->d_src, ln->h_src, (size_t)B * S * 4, hipMemcpyHostToDevice, ls) != hipSuccess ||
+        hipMemcpyAsync(ln->d_len_in, ln->h_len, (size_t)B * 4, hipMemcpyHostToDevice, ls) != hipSuccess) {
+      first_err = fail(NT_EHIP, "host-to-device copy failed");
+      break;
     }
-    rc = nt_decode_greedy(m, B, T, row_steps.data(), m->d_out, s);
-    if (rc) return rc;
-    HIP_TRY(hipMemcpyAsync(m->h_out, m->d_out, (size_t)B * T * 4, hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipStreamSynchronize(s));
-    for (int32_t r = 0; r < B; r++) {
-      const int64_t si = order[(size_t)(i0 + r)];
-      memcpy(h_out + h_out_offsets[si], m->h_out + (size_t)r * T, (size_t)row_steps[(size_t)r] * 4);
+    if ((first_err = nt_encode(ln, ln->d_src, ln->d_len_in, B, S, ls))) break;
+    if (ln->timing.mask) {
+      ln->len_prefix.assign((size_t)B + 1, 0);
+      for (int32_t r = 0; r < B; r++) ln->len_prefix[(size_t)r + 1] = ln->len_prefix[(size_t)r] + ln->h_len[r];
     }
+    if ((first_err = nt_decode_greedy(ln, B, T, ln->pend_steps.data(), ln->d_out, ls))) break;
+    if (hipMemcpyAsync(ln->h_out, ln->d_out, (size_t)B * T * 4, hipMemcpyDeviceToHost, ls) != hipSuccess ||
+        hipEventRecord(ln->lane_done, ls) != hipSuccess) {
+      first_err = fail(NT_EHIP, "device-to-host copy failed");
+      break;
+    }
+    ln->pend_i0 = i0; ln->pend_i1 = i1; ln->pend_T = T; ln->lane_busy = true;
   }
+  // drain every lane (also after an error: nothing may still be running when the call returns)
+  for (nt_model *ln : lane) {
+    if (first_err == NT_OK) first_err = collect(ln);
+    (void)hipStreamSynchronize(ln->lane_stream);
+    ln->lane_busy = false;
+  }
+  if (first_err) return first_err;
   return NT_OK;
 } catch (const std::bad_alloc &) {
   return fail(NT_ENOMEM, "host allocation failed");
