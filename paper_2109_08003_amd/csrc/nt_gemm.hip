@@ -373,56 +373,6 @@ hipError_t launch_gemm(int a_mode, bool c_f32, const void *A, const void *A_lo, 
 // largest logit and, among equal logits, the lowest id.  Max over keys is associative and
 // commutative, so the result does not depend on the tiling: deterministic without atomics.
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ unsigned long long argmax_key(float val, int v) {
-  unsigned int b = __float_as_uint(val);
-  b = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-  return ((unsigned long long)b << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned int)v);
-}
-
-__device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long x, int mask) {
-  unsigned int lo = (unsigned int)x, hi = (unsigned int)(x >> 32);
-  lo = __shfl_xor(lo, mask, 64);
-  hi = __shfl_xor(hi, mask, 64);
-  return ((unsigned long long)hi << 32) | lo;
-}
-
-template <int HALF>
-__device__ __forceinline__ void butterfly_step(unsigned long long (&k)[32], int lane) {
-  const bool upper = (lane & HALF) != 0;
-#pragma unroll
-  for (int i = 0; i < HALF; i++) {
-    unsigned long long a = k[i], b = k[i + HALF];
-    unsigned long long send = upper ? a : b, keep = upper ? b : a;
-    unsigned long long recv = shfl_xor_u64(send, HALF);
-    k[i] = keep > recv ? keep : recv;
-  }
-}
-
-__device__ __forceinline__ float key_value(unsigned long long key) {
-  unsigned int b = (unsigned int)(key >> 32);
-  b = (b & 0x80000000u) ? (b & 0x7FFFFFFFu) : ~b;
-  return __uint_as_float(b);
-}
-
-// Butterfly over the 32 column lanes on (best key, runner-up value) pairs.
-template <int HALF>
-__device__ __forceinline__ void butterfly_step2(unsigned long long (&k)[32], float (&s2)[32], int lane) {
-  const bool upper = (lane & HALF) != 0;
-#pragma unroll
-  for (int i = 0; i < HALF; i++) {
-    const unsigned long long a = k[i], b = k[i + HALF];
-    const float sa = s2[i], sb = s2[i + HALF];
-    const unsigned long long send = upper ? a : b, keep = upper ? b : a;
-    const float ssend = upper ? sa : sb, skeep = upper ? sb : sa;
-    const unsigned long long recv = shfl_xor_u64(send, HALF);
-    const float srecv = __shfl_xor(ssend, HALF, 64);
-    const bool take = recv > keep;
-    const unsigned long long loser = take ? keep : recv;
-    k[i] = take ? recv : keep;
-    s2[i] = fmaxf(fmaxf(skeep, srecv), loser ? key_value(loser) : -INFINITY);
-  }
-}
-
 constexpr int VOCAB_TILES_TARGET_WGS = 1024;
 
 static int vocab_tiles_per_wg(int M, int N) {
@@ -433,7 +383,7 @@ static int vocab_tiles_per_wg(int M, int N) {
   return tpw;
 }
 
-int vocab_argmax_partials(int M, int N) {
+int vocab_argmax_partials_tiled(int M, int N) {
   int nt_ = (N + BN - 1) / BN, tpw = vocab_tiles_per_wg(M, N);
   return 2 * ((nt_ + tpw - 1) / tpw);
 }
@@ -516,10 +466,10 @@ __global__ __launch_bounds__(256) void vocab_argmax_kernel(const _Float16 *h, co
   }
 }
 
-hipError_t launch_vocab_argmax(const _Float16 *h, const _Float16 *h_lo, long ldh, const _Float16 *Wt, int M, int N,
-                               int K, unsigned long long *pk, hipStream_t s) {
+hipError_t launch_vocab_argmax_tiled(const _Float16 *h, const _Float16 *h_lo, long ldh, const _Float16 *Wt, int M, int N,
+                                     int K, unsigned long long *pk, hipStream_t s) {
   if (M <= 0) return hipSuccess;
-  const int tpw = vocab_tiles_per_wg(M, N), np = vocab_argmax_partials(M, N);
+  const int tpw = vocab_tiles_per_wg(M, N), np = vocab_argmax_partials_tiled(M, N);
   const int tiles_m = (M + BM - 1) / BM, strips = np / 2;
   dim3 grid(((strips + 7) / 8) * 8 * tiles_m), block(256);
   hipLaunchKernelGGL(vocab_argmax_kernel<false>, grid, block, 0, s, h, h_lo, ldh, Wt, M, N, K, tpw, np, tiles_m, pk,
@@ -575,18 +525,28 @@ __global__ __launch_bounds__(256) void argmax_select_kernel(const unsigned long 
   }
 }
 
-hipError_t launch_vocab_argmax_certified(const _Float16 *h, const _Float16 *h_lo, long ldh, const _Float16 *Wt, int M,
-                                         int N, int K, const float *lo_norm, float w_norm_max, unsigned long long *pk,
-                                         float *ps, int32_t *tok, int32_t *slot_of_row, int32_t *list, int32_t *count,
-                                         unsigned long long *final_key, hipStream_t s) {
+hipError_t launch_argmax_select(const unsigned long long *pk, const float *ps, int n_partials, int M, const float *lo_norm,
+                                float w_norm_max, int32_t *tok, int32_t *slot_of_row, int32_t *list, int32_t *count,
+                                unsigned long long *final_key, hipStream_t s) {
   if (M <= 0) return hipSuccess;
-  const int tpw = vocab_tiles_per_wg(M, N), np = vocab_argmax_partials(M, N);
+  hipLaunchKernelGGL(argmax_select_kernel, dim3((M + 3) / 4), dim3(256), 0, s, pk, ps, n_partials, M, lo_norm, w_norm_max,
+                     tok, slot_of_row, list, count, final_key);
+  return hipGetLastError();
+}
+
+hipError_t launch_vocab_argmax_certified_tiled(const _Float16 *h, const _Float16 *h_lo, long ldh, const _Float16 *Wt, int M,
+                                               int N, int K, const float *lo_norm, float w_norm_max,
+                                               unsigned long long *pk, float *ps, int32_t *tok, int32_t *slot_of_row,
+                                               int32_t *list, int32_t *count, unsigned long long *final_key,
+                                               hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  const int tpw = vocab_tiles_per_wg(M, N), np = vocab_argmax_partials_tiled(M, N);
   const int tiles_m = (M + BM - 1) / BM, strips = np / 2;
   hipLaunchKernelGGL(vocab_argmax_kernel<true>, dim3(((strips + 7) / 8) * 8 * tiles_m), dim3(256), 0, s, h, h_lo, ldh, Wt,
                      M, N, K, tpw, np, tiles_m, pk, ps, (const int *)nullptr, (const int *)nullptr,
                      (unsigned long long *)nullptr);
-  hipLaunchKernelGGL(argmax_select_kernel, dim3((M + 3) / 4), dim3(256), 0, s, pk, ps, np, M, lo_norm, w_norm_max, tok,
-                     slot_of_row, list, count, final_key);
+  hipError_t e = launch_argmax_select(pk, ps, np, M, lo_norm, w_norm_max, tok, slot_of_row, list, count, final_key, s);
+  if (e != hipSuccess) return e;
   // recompute of the uncertified rows: one vocabulary tile per workgroup, every workgroup walks all
   // gathered m tiles (normally one); the row count is read on the device
   const int n_tiles = (N + BN - 1) / BN;

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <numeric>
@@ -131,6 +132,8 @@ struct nt_model {
   char *d_w = nullptr;
   size_t w_bytes = 0;
   const _Float16 *E = nullptr, *Wout = nullptr;
+  const _Float16 *Wout_frag = nullptr;  // the output matrix in MFMA fragment order (streaming arg-max kernels)
+  nt::VocabWeights vw;
   const float *pe = nullptr;
   std::vector<EncLayer> enc;
   std::vector<DecLayer> dec;
@@ -248,15 +251,16 @@ hipStream_t as_stream(void *s) { return (hipStream_t)s; }
 // The peak footprint is fixed here; nothing is allocated afterwards.
 int alloc_lane_state(nt_model *m, hipStream_t s) {
   const nt_config *cfg = &m->c;
-  const int d = cfg->d_model, V = cfg->vocab, F = cfg->d_ffn;
+  const int d = cfg->d_model, F = cfg->d_ffn;
   const int64_t Mt = m->max_tokens, Br = m->max_rows;
   m->self_positions = (6 * Mt + 4) / 5 + 3 * Br + 8;
   if (m->self_positions < Br * 1) m->self_positions = Br;
-  {  // arg-max partials: the count per row depends only on ceil(rows / 128)
+  {  // arg-max partials: the count per row depends only on the number of row tiles (64 or 128 rows each)
     int64_t worst = 0;
-    for (int64_t mt = 1; (mt - 1) * 128 < Br; mt++) {
-      const int64_t rows = std::min<int64_t>(mt * 128, Br);
-      worst = std::max(worst, rows * nt::vocab_argmax_partials((int)rows, V));
+    for (int64_t mt = 1; (mt - 1) * 64 < Br; mt++) {
+      const int64_t rows = std::min<int64_t>(mt * 64, Br);
+      worst = std::max(worst, rows * nt::vocab_argmax_partials(m->vw, (int)rows, false));
+      worst = std::max(worst, rows * nt::vocab_argmax_partials(m->vw, (int)rows, true));
     }
     m->pk_elems = worst;
   }
@@ -434,6 +438,12 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
   }
   put_ln(m->dec_final);
   if (br.p - (const _Float16 *)h_blob_fp16 != np) return fail(NT_EBLOB, "internal: blob walk mismatch");
+  if (nt::vocab_stream_supported(d)) {  // the output matrix once more, in MFMA fragment order
+    const _Float16 *Wo = (const _Float16 *)h_blob_fp16 + (cfg->tie_output ? 0 : (int64_t)V * d);
+    size_t o = pk.reserve(nt::vocab_pack_bytes(V, d));
+    nt::vocab_pack(Wo, V, d, (_Float16 *)(pk.img.data() + o));
+    fixes.push_back({o, (const void **)&m->Wout_frag});
+  }
   {  // sinusoid table, evaluated in double
     size_t o = pk.reserve((size_t)cfg->max_len * d * 4);
     float *pe = (float *)(pk.img.data() + o);
@@ -450,6 +460,11 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
   HIP_TRY(hipMemcpyAsync(m->d_w, pk.img.data(), m->w_bytes, hipMemcpyHostToDevice, s));
   for (auto &f : fixes) *f.slot = m->d_w + f.off;
   if (cfg->tie_output) m->Wout = m->E;
+  m->vw.Wt = m->Wout; m->vw.Wp = m->Wout_frag; m->vw.N = V; m->vw.K = d;
+  {
+    const char *f = getenv("NT_VOCAB_TILED");  // testing aid: take the tiled arg-max kernels
+    m->vw.force_tiled = f && f[0] == '1';
+  }
   {  // largest row norm of the output matrix, rounded up (bound used by the certified arg-max)
     const _Float16 *Wo = (const _Float16 *)h_blob_fp16 + (cfg->tie_output ? 0 : (int64_t)V * d);
     double mx = 0.0;
@@ -659,15 +674,15 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
       KT(K_GEMM_LOGITS, gemm_bytes(Rd, dd, V, false), 2 * Rd * dd * V,
          nt::launch_gemm(nt::A_PLANES, true, h_hi, h_lo, d, m->Wout, R, V, d, e, s));
     } else {
-      const int np_ = nt::vocab_argmax_partials(R, V);
       prev_cert = R >= kCertMinRows;
+      const int np_ = nt::vocab_argmax_partials(m->vw, R, prev_cert);
       if (prev_cert)
         KT(K_VOCAB_ARGMAX, (double)V * dd * 2 + Rd * dd * 4 + Rd * np_ * 8, 2 * Rd * dd * V,
-           nt::launch_vocab_argmax_certified(h_hi, h_lo, d, m->Wout, R, V, d, m->lo_norm, m->w_norm_max, m->pk, m->ps,
+           nt::launch_vocab_argmax_certified(h_hi, h_lo, d, m->vw, R, m->lo_norm, m->w_norm_max, m->pk, m->ps,
                                              m->tok, m->slot_of_row, m->cert_list, m->flags + 4, m->final_key, s));
       else
         KT(K_VOCAB_ARGMAX, (double)V * dd * 2 + Rd * dd * 4 + Rd * np_ * 8, 2 * Rd * dd * V,
-           nt::launch_vocab_argmax(h_hi, h_lo, d, m->Wout, R, V, d, m->pk, s));
+           nt::launch_vocab_argmax(h_hi, h_lo, d, m->vw, R, m->pk, s));
       partials_prev = np_;
     }
   }

@@ -43,23 +43,72 @@ hipError_t launch_skinny_gemm(const float *A, long lda, const _Float16 *Wt, int 
                               const float *ln_b, float ln_eps, const GemmEpilogue &e, hipStream_t s);
 
 // ---- output projection fused with row arg-max ------------------------------------------
-// For every row m < M: the largest of h[m,:] . Wt[v,:] over v < N, lowest v on ties, as packed
-// keys.  Each workgroup reduces a strip of columns; partial keys go to pk[m * n_partials + p].
-// vocab_argmax_partials(N) gives n_partials for the launch configuration used with M rows.
-int vocab_argmax_partials(int M, int N);
+// For every row m < M: the largest of h[m,:] . W_out[v,:] over v < N, lowest v on ties, as packed
+// keys.  Each workgroup reduces a range of the vocabulary; partial keys go to pk[m * n_partials + p].
+//
+// Key = (order-preserving bits of the fp32 logit) << 32 | (0xFFFFFFFF - v): the maximum key is the
+// largest logit and, among equal logits, the lowest id.  Max over keys is associative and
+// commutative, so the result does not depend on the tiling: deterministic without float atomics.
+__device__ __forceinline__ unsigned long long argmax_key(float val, int v) {
+  unsigned int b = __float_as_uint(val);
+  b = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+  return ((unsigned long long)b << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned int)v);
+}
+__device__ __forceinline__ float key_value(unsigned long long key) {
+  unsigned int b = (unsigned int)(key >> 32);
+  b = (b & 0x80000000u) ? (b & 0x7FFFFFFFu) : ~b;
+  return __uint_as_float(b);
+}
+__device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long x, int mask) {
+  unsigned int lo = (unsigned int)x, hi = (unsigned int)(x >> 32);
+  lo = __shfl_xor(lo, mask, 64);
+  hi = __shfl_xor(hi, mask, 64);
+  return ((unsigned long long)hi << 32) | lo;
+}
+
+// The output matrix in two layouts: Wt [N][K] row-major, and Wp in MFMA fragment order (see
+// vocab_pack_bytes / vocab_pack; built once at load time).  The streaming kernels need K = 256 or
+// 512 (vocab_stream_supported); other widths, or force_tiled, take the tiled kernels on Wt.
+struct VocabWeights {
+  const _Float16 *Wt = nullptr;
+  const _Float16 *Wp = nullptr;
+  int N = 0, K = 0;
+  bool force_tiled = false;
+};
+bool vocab_stream_supported(int K);
+size_t vocab_pack_bytes(int N, int K);
+// host: dst[vocab_pack_bytes] <- fragment order of Wt [N][K]
+void vocab_pack(const _Float16 *Wt, int N, int K, _Float16 *dst);
+
+// n_partials of the launch configuration used with M rows (exact: head + tail planes; certified:
+// head plane first).  Never more than max(32768, M) / M per row.
+int vocab_argmax_partials(const VocabWeights &w, int M, bool certified);
 // h is a head/tail pair of fp16 planes.
-hipError_t launch_vocab_argmax(const _Float16 *h, const _Float16 *h_lo, long ldh, const _Float16 *Wt, int M, int N,
-                               int K, unsigned long long *pk, hipStream_t s);
+hipError_t launch_vocab_argmax(const _Float16 *h, const _Float16 *h_lo, long ldh, const VocabWeights &w, int M,
+                               unsigned long long *pk, hipStream_t s);
 
 // Same result as launch_vocab_argmax, usually at half the MFMA work: a head-only pass whose winner is
 // certified against a rigorous bound on the contribution of the tail (lo_norm[m] = ||tail of row m||,
-// w_norm_max = max_v ||Wt[v,:]||); rows that cannot be certified are recomputed with both planes.
+// w_norm_max = max_v ||W_out[v,:]||); rows that cannot be certified are recomputed with both planes.
 // Results: tok[m] when slot_of_row[m] < 0, else the key in final_key[slot_of_row[m]].
 // *count must be 0 when the call starts (the step-begin kernel clears it).
-hipError_t launch_vocab_argmax_certified(const _Float16 *h, const _Float16 *h_lo, long ldh, const _Float16 *Wt, int M,
-                                         int N, int K, const float *lo_norm, float w_norm_max, unsigned long long *pk,
-                                         float *ps, int32_t *tok, int32_t *slot_of_row, int32_t *list, int32_t *count,
+hipError_t launch_vocab_argmax_certified(const _Float16 *h, const _Float16 *h_lo, long ldh, const VocabWeights &w, int M,
+                                         const float *lo_norm, float w_norm_max, unsigned long long *pk, float *ps,
+                                         int32_t *tok, int32_t *slot_of_row, int32_t *list, int32_t *count,
                                          unsigned long long *final_key, hipStream_t s);
+
+// the tiled implementations (nt_gemm.hip) and the certification kernel shared by both
+int vocab_argmax_partials_tiled(int M, int N);
+hipError_t launch_vocab_argmax_tiled(const _Float16 *h, const _Float16 *h_lo, long ldh, const _Float16 *Wt, int M, int N,
+                                     int K, unsigned long long *pk, hipStream_t s);
+hipError_t launch_vocab_argmax_certified_tiled(const _Float16 *h, const _Float16 *h_lo, long ldh, const _Float16 *Wt, int M,
+                                               int N, int K, const float *lo_norm, float w_norm_max,
+                                               unsigned long long *pk, float *ps, int32_t *tok, int32_t *slot_of_row,
+                                               int32_t *list, int32_t *count, unsigned long long *final_key,
+                                               hipStream_t s);
+hipError_t launch_argmax_select(const unsigned long long *pk, const float *ps, int n_partials, int M, const float *lo_norm,
+                                float w_norm_max, int32_t *tok, int32_t *slot_of_row, int32_t *list, int32_t *count,
+                                unsigned long long *final_key, hipStream_t s);
 
 // ---- row kernels --------------------------------------------------------------------
 // x[r,:] = sqrt(d) * E[id] + PE[pos]; rows r = b*S + s, pos = s.  Out-of-range ids are
