@@ -515,7 +515,8 @@ __device__ __forceinline__ void load8(const void *p, float (&o)[8]) {
 template <int DH, bool KV_F32>
 __global__ __launch_bounds__(256) void attn_decode_kernel(const float *q, const void *kv, long row_stride,
                                                           const int32_t *len, int n_keys, int rows, int d, int heads,
-                                                          const float *rk, int clip, int qpos, float *ctx) {
+                                                          const float *rk, int clip, int qpos, float *ctx,
+                                                          long ctx_lo_offset) {
   constexpr int LPK = DH / 8;              // lanes per key
   constexpr int G = 64 / LPK;              // keys per wave iteration
   constexpr int WPP = (DH >= 256) ? 4 : 1; // waves per (row, head) pair
@@ -599,37 +600,51 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const float *q, const 
   }
   if (valid && lane < LPK) {
     const float inv = (p.l > 0.f) ? 1.f / p.l : 0.f;
-    float4 *o = (float4 *)(ctx + (long)r * d + h * DH + sub * 8);
-    o[0] = make_float4(p.acc[0] * inv, p.acc[1] * inv, p.acc[2] * inv, p.acc[3] * inv);
-    o[1] = make_float4(p.acc[4] * inv, p.acc[5] * inv, p.acc[6] * inv, p.acc[7] * inv);
+    const long at_ = (long)r * d + h * DH + sub * 8;
+    if (ctx_lo_offset == 0) {
+      float4 *o = (float4 *)(ctx + at_);
+      o[0] = make_float4(p.acc[0] * inv, p.acc[1] * inv, p.acc[2] * inv, p.acc[3] * inv);
+      o[1] = make_float4(p.acc[4] * inv, p.acc[5] * inv, p.acc[6] * inv, p.acc[7] * inv);
+    } else {  // head/tail pair of fp16 planes for a projection that reads planes
+      typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+      half8v hi, lo;
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        const float val = p.acc[e] * inv;
+        hi[e] = (_Float16)val;
+        lo[e] = (_Float16)(val - (float)hi[e]);
+      }
+      *(half8v *)((_Float16 *)ctx + at_) = hi;
+      *(half8v *)((_Float16 *)ctx + at_ + ctx_lo_offset) = lo;
+    }
   }
 }
 
 template <int DH>
 static hipError_t attn_decode_launch(const float *q, const void *kv, bool kv_f32, long row_stride, const int32_t *len,
                                      int n_keys, int rows, int d, int heads, const float *rk, int clip, int qpos,
-                                     float *ctx, hipStream_t s) {
+                                     float *ctx, long ctx_lo_offset, hipStream_t s) {
   const long pairs = (long)rows * heads;
   const unsigned grid = (DH >= 256) ? (unsigned)pairs : (unsigned)((pairs + 3) / 4);
   if (kv_f32)
     hipLaunchKernelGGL((attn_decode_kernel<DH, true>), dim3(grid), dim3(256), 0, s, q, kv, row_stride, len, n_keys,
-                       rows, d, heads, rk, clip, qpos, ctx);
+                       rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset);
   else
     hipLaunchKernelGGL((attn_decode_kernel<DH, false>), dim3(grid), dim3(256), 0, s, q, kv, row_stride, len, n_keys,
-                       rows, d, heads, rk, clip, qpos, ctx);
+                       rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_decode(const float *q, const void *kv, bool kv_f32, long row_stride, const int32_t *len,
                               int n_keys, int rows, int d, int heads, const float *rk, int clip, int qpos,
-                              float *ctx, hipStream_t s) {
+                              float *ctx, hipStream_t s, long ctx_lo_offset) {
   if (rows <= 0) return hipSuccess;
   if (clip > MAX_CLIP) return hipErrorInvalidValue;
   switch (d / heads) {
-    case 64: return attn_decode_launch<64>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, s);
-    case 128: return attn_decode_launch<128>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, s);
-    case 256: return attn_decode_launch<256>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, s);
-    case 512: return attn_decode_launch<512>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, s);
+    case 64: return attn_decode_launch<64>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset, s);
+    case 128: return attn_decode_launch<128>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset, s);
+    case 256: return attn_decode_launch<256>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset, s);
+    case 512: return attn_decode_launch<512>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset, s);
     default: return hipErrorInvalidValue;
   }
 }

@@ -1,0 +1,235 @@
+// Streaming projection GEMM for K = 256 / 512 (gfx950): C[M,N] = A[M,K] * Wt[N,K]^T with A given
+// as a head/tail pair of fp16 planes.
+//
+// Same division of labour as the streaming output projection: a workgroup keeps its tile of A
+// (32 or 64 rows, both planes) in the LDS for its whole life, filled once straight from global
+// memory, and the weights - stored at load time in MFMA fragment order - stream through
+// registers, one fully coalesced 1 KiB load per fragment, running a few k-steps ahead of their
+// use.  The main loop has no LDS writes, no barriers and no address arithmetic; against the tiled
+// kernel (both operand tiles written to and read from the LDS for every 64 MFMAs) the LDS
+// traffic per MFMA drops to a quarter.  Both planes are multiplied with the same weight
+// fragment into one fp32 accumulator.
+//
+// A wave owns strips of 64 output columns (wave, wave + 8, ... of the workgroup's range) and all
+// rows of the tile; the epilogue is the one of the tiled kernel (bias, scale, ReLU, residual, two
+// destinations, optional tail plane).  Here the A fragment is the row operand of the MFMA, so a
+// lane owns an output column and a store instruction covers 128 contiguous bytes per row.
+//
+// Fragment order of Wp: [strip = n / 64][ks = k / 16][nb = (n % 64) / 32][lane][8 halfs] with
+// lane = n % 32 + 32 * ((k % 16) / 8).
+#include "nt_kernels.h"
+
+namespace nt {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int GS_WAVES = 8;
+constexpr int GS_SL = 4;  // register slots of W fragments per wave; the lookahead is GS_SL - 1 k-steps
+
+bool gemm_stream_supported(int N, int K) { return (K == 256 || K == 512) && N % 64 == 0; }
+
+// RB = 32-row blocks per tile (1: decoder-sized M, two workgroups per CU; 2: encoder-sized M)
+template <int RB, int K, bool C_F32>
+__global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float16 *__restrict__ A_hi,
+                                                                   const _Float16 *__restrict__ A_lo, long lda, int M,
+                                                                   const _Float16 *__restrict__ Wp, int N, int col_groups,
+                                                                   GemmEpilogue e) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  _Float16 *sh = (_Float16 *)smem;
+  constexpr int TM = 32 * RB, ROWS = 2 * TM;  // LDS fragment rows: head rows, then tail rows
+  constexpr int LD = K + 8;                   // halfs per LDS row: the 16 B pad keeps the fragment reads conflict-free
+  constexpr int KS = K / 16;
+  constexpr int SL = GS_SL;
+  constexpr int NOPS = 2 * RB;
+  static_assert(KS % SL == 0, "the ring of W slots must divide the k-steps of a strip");
+  const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int mt = blockIdx.x / col_groups, cg = blockIdx.x % col_groups;
+  const int m0 = mt * TM;
+  const int NS = N >> 6;
+  const int sb0 = (int)((long)cg * NS / col_groups), sb1 = (int)((long)(cg + 1) * NS / col_groups);
+
+  const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void *)Wp, 0, NS * 64 * K * 2, 0x00020000);
+  const int wlane = lane * 16;
+  auto wload = [&](int soff, int nb) -> half8 {
+    u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(wrs, wlane + nb * 1024, soff, 0);
+    return __builtin_bit_cast(half8, t);
+  };
+
+  // ---- the A tile: global memory -> LDS.  Rows past M repeat row M - 1 (their results are never stored) ----
+  if (K == 512) {
+#pragma unroll
+    for (int i = 0; i < ROWS / GS_WAVES; i++) {
+      const int R = wave + GS_WAVES * i;
+      const _Float16 *src = R >= TM ? A_lo : A_hi;
+      int m = m0 + (R % TM);
+      m = m < M ? m : M - 1;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + (long)m * lda + lane * 8),
+                                       (__attribute__((address_space(3))) void *)(sh + R * LD), 16, 0, 0);
+    }
+  } else {
+    constexpr int CPR = K / 8, PER_T = ROWS * CPR / (GS_WAVES * 64);
+    u32x4 fr[PER_T];
+#pragma unroll
+    for (int i = 0; i < PER_T; i++) {
+      const int c = tid + GS_WAVES * 64 * i, R = c / CPR, kc = c % CPR;
+      const _Float16 *src = R >= TM ? A_lo : A_hi;
+      int m = m0 + (R % TM);
+      m = m < M ? m : M - 1;
+      fr[i] = *(const u32x4 *)(src + (long)m * lda + kc * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < PER_T; i++) {
+      const int c = tid + GS_WAVES * 64 * i, R = c / CPR, kc = c % CPR;
+      *(u32x4 *)(sh + R * LD + kc * 8) = fr[i];
+    }
+  }
+  half8 wb[SL][2];
+  int strip = sb0 + wave;
+  const bool have = strip < sb1;
+  if (have) {
+    const int sp = strip * (KS * 2048);
+#pragma unroll
+    for (int q = 0; q < SL - 1; q++) {
+      wb[q][0] = wload(sp + q * 2048, 0);
+      wb[q][1] = wload(sp + q * 2048, 1);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's rows have landed in the LDS before the barrier
+  __syncthreads();
+  if (!have) return;
+
+  floatx16 acc[RB][2];
+  // fragment row of operand op: head rows of block op % RB, then the tail rows; two base registers, because the
+  // byte offsets of the upper half do not fit the 16-bit offset field
+  const _Float16 *hrow = sh + li * LD + g * 8;
+  int off2 = (ROWS / 2) * LD;
+  asm volatile("" : "+v"(off2));
+  const _Float16 *hrow2 = hrow + off2;
+  auto frag = [&](int op, int ks) -> half8 {
+    const int R0 = op * 32;  // ops 0 .. RB-1: head planes, RB .. 2RB-1: tail planes
+    return *(const half8 *)((R0 < ROWS / 2 ? hrow : hrow2) + (R0 % (ROWS / 2)) * LD + ks * 16);
+  };
+  half8 hf[NOPS];
+#pragma unroll
+  for (int op = 0; op < NOPS; op++) hf[op] = frag(op, 0);
+
+  for (; strip < sb1; strip += GS_WAVES) {
+    const bool more = strip + GS_WAVES < sb1;
+    const int pcur = strip * (KS * 2048);
+    const int pnext = (more ? strip + GS_WAVES : strip) * (KS * 2048);
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      const int tgt = ks + SL - 1;
+      const int pf = tgt < KS ? pcur + tgt * 2048 : pnext + (tgt - KS) * 2048;
+      const int ksn = (ks + 1) % KS;
+#pragma unroll
+      for (int op = 0; op < NOPS; op++) {
+#pragma unroll
+        for (int nb = 0; nb < 2; nb++) {
+          if (ks == 0 && op < RB) {
+            const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            acc[op % RB][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(hf[op], wb[ks % SL][nb], zero, 0, 0, 0);
+          } else {
+            acc[op % RB][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(hf[op], wb[ks % SL][nb], acc[op % RB][nb], 0, 0, 0);
+          }
+        }
+        // refill what was just consumed; the scheduling barrier keeps the loads this far ahead of their use
+        hf[op] = frag(op, ksn);
+        if (op == 0) {
+          wb[tgt % SL][0] = wload(pf, 0);
+          wb[tgt % SL][1] = wload(pf, 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    // ---- epilogue of the strip: acc[rb][nb][v] is C[m0 + rb*32 + (v/4)*8 + g*4 + v%4][strip*64 + nb*32 + li] ----
+    // Addresses are a uniform 64-bit base per 32 x 32 block plus a 32-bit lane offset (n_split is a multiple of 32,
+    // so a block never straddles the two destinations).
+#pragma unroll
+    for (int nb = 0; nb < 2; nb++) {
+      const int nbase = strip * 64 + nb * 32;  // uniform
+      const int n = nbase + li;
+      const float bias = e.bias ? e.bias[n] : 0.f;
+      const float sc = (n < e.scale_cols) ? e.scale : 1.f;
+      const bool first = nbase < e.n_split;
+      char *dst = (char *)(first ? e.dst0 : e.dst1);
+      const long ld = first ? e.ld0 : e.ld1;
+      const int ncb = first ? nbase : nbase - e.n_split;
+      constexpr int CE = C_F32 ? 4 : 2;
+#pragma unroll
+      for (int rb = 0; rb < RB; rb++) {
+        __builtin_amdgcn_sched_barrier(0);  // one 32 x 32 block at a time: bounds the loads and addresses in flight
+        const int mb = m0 + rb * 32;  // uniform
+        char *dblock = dst + ((long)mb * ld + ncb) * CE;
+        const char *rblock = (const char *)e.resid + ((long)mb * e.ldr + nbase) * 4;
+        const unsigned dlane = (unsigned)((g * 4 * ld + li) * CE), rlane = (unsigned)((g * 4 * e.ldr + li) * 4);
+        // the residual may be the destination itself (in-place update), so the compiler keeps loads and stores in
+        // program order: read the 16 residual values of the block first, then compute and store
+        float res[16];
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          const int r = (v >> 2) * 8 + (v & 3);
+          res[v] = (e.resid && mb + r + g * 4 < M) ? *(const float *)(rblock + (rlane + (unsigned)(r * e.ldr * 4))) : 0.f;
+        }
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          const int r = (v >> 2) * 8 + (v & 3);
+          if (mb + r + g * 4 >= M) continue;
+          float val = (acc[rb][nb][v] + bias) * sc;
+          if (e.relu) val = fmaxf(val, 0.f);
+          val += res[v];
+          char *at_ = dblock + (dlane + (unsigned)(r * ld * CE));
+          if (C_F32) {
+            *(float *)at_ = val;
+          } else {
+            const _Float16 hi = (_Float16)val;
+            *(_Float16 *)at_ = hi;
+            if (e.dst_lo_offset) *((_Float16 *)at_ + e.dst_lo_offset) = (_Float16)(val - (float)hi);
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int RB, int K, bool C_F32>
+static hipError_t gs_launch(const _Float16 *A, const _Float16 *A_lo, long lda, int M, const _Float16 *Wp, int N,
+                            const GemmEpilogue &e, hipStream_t s) {
+  auto kern = gemm_stream_kernel<RB, K, C_F32>;
+  const size_t lds = (size_t)64 * RB * (K + 8) * 2;
+  static bool attr_set = false;  // raising the dynamic LDS limit is per kernel, once per process
+  if (!attr_set) {
+    hipError_t err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (err != hipSuccess) return err;
+    attr_set = true;
+  }
+  const int row_tiles = (M + 32 * RB - 1) / (32 * RB), NS = N / 64;
+  // enough workgroups for the chip: split the strips of a row tile over several workgroups as long as every wave
+  // of a workgroup still gets a strip and the grid stays within a few rounds
+  int col_groups = 1;
+  for (int cg = NS / GS_WAVES; cg > 1; cg--)
+    if (NS % cg == 0 && (long)row_tiles * cg <= 1024) {
+      col_groups = cg;
+      break;
+    }
+  hipLaunchKernelGGL(kern, dim3(row_tiles * col_groups), dim3(GS_WAVES * 64), lds, s, A, A_lo, lda, M, Wp, N, col_groups, e);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_stream(bool c_f32, const _Float16 *A, const _Float16 *A_lo, long lda, const _Float16 *Wp, int M,
+                              int N, int K, const GemmEpilogue &e, hipStream_t s) {
+  if (M <= 0 || N <= 0) return hipSuccess;
+  if (!gemm_stream_supported(N, K) || e.n_split % 32 != 0) return hipErrorInvalidValue;
+  const bool small = M <= 8192;  // 32-row tiles: twice the workgroups, two of them per CU
+#define NT_GS_CASE(RB_, K_, CF_)                                                     \
+  if (small == (RB_ == 1) && K == K_ && c_f32 == CF_) return gs_launch<RB_, K_, CF_>(A, A_lo, lda, M, Wp, N, e, s);
+  NT_GS_CASE(1, 512, true) NT_GS_CASE(1, 512, false) NT_GS_CASE(2, 512, true) NT_GS_CASE(2, 512, false)
+  NT_GS_CASE(1, 256, true) NT_GS_CASE(1, 256, false) NT_GS_CASE(2, 256, true) NT_GS_CASE(2, 256, false)
+#undef NT_GS_CASE
+  return hipErrorInvalidValue;
+}
+
+}  // namespace nt

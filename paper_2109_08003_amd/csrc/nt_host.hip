@@ -76,11 +76,14 @@ struct Attn {
   const _Float16 *Wq = nullptr;    // [d][d]                    (cross-attention query)
   const _Float16 *Wkv = nullptr;   // [2d][d]                   (cross-attention keys | values)
   const _Float16 *Wo = nullptr;    // [d][d]
+  // the same matrices in MFMA fragment order (streaming GEMM), nullptr where the shape is not supported
+  const _Float16 *Wqkv_p = nullptr, *Wq_p = nullptr, *Wkv_p = nullptr, *Wo_p = nullptr;
   const float *bqkv = nullptr, *bq = nullptr, *bkv = nullptr, *bo = nullptr;
   const float *rk = nullptr;       // [2c+1][dh]
 };
 struct FFN {
   const _Float16 *W1 = nullptr, *W2 = nullptr;  // [F][d], [d][F]
+  const _Float16 *W1_p = nullptr;               // W1 in MFMA fragment order, or nullptr
   const float *b1 = nullptr, *b2 = nullptr;
 };
 struct EncLayer {
@@ -391,20 +394,25 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
   auto put_attn = [&](Attn &a, bool cross, bool rpr) {
     const _Float16 *W[4], *b[4];
     for (int i = 0; i < 4; i++) { W[i] = br.take((int64_t)d * d); b[i] = br.take(d); }
-    auto fused = [&](int first, int count, const void **wslot, const void **bslot) {
+    auto fused = [&](int first, int count, const void **wslot, const void **bslot, const void **pslot) {
       size_t o = pk.reserve((size_t)count * d * d * 2);
       for (int i = 0; i < count; i++) Packer::transpose(W[first + i], d, d, (_Float16 *)(pk.img.data() + o) + (size_t)i * d * d);
       fixes.push_back({o, wslot});
+      if (nt::gemm_stream_supported(count * d, d)) {
+        size_t op = pk.reserve(nt::vocab_pack_bytes(count * d, d));
+        nt::vocab_pack((const _Float16 *)(pk.img.data() + o), count * d, d, (_Float16 *)(pk.img.data() + op));
+        fixes.push_back({op, pslot});
+      }
       size_t ob = pk.reserve((size_t)count * d * 4);
       for (int i = 0; i < count; i++) Packer::widen(b[first + i], d, (float *)(pk.img.data() + ob) + (size_t)i * d);
       fixes.push_back({ob, bslot});
     };
-    if (!cross) fused(0, 3, (const void **)&a.Wqkv, (const void **)&a.bqkv);
+    if (!cross) fused(0, 3, (const void **)&a.Wqkv, (const void **)&a.bqkv, (const void **)&a.Wqkv_p);
     else {
-      fused(0, 1, (const void **)&a.Wq, (const void **)&a.bq);
-      fused(1, 2, (const void **)&a.Wkv, (const void **)&a.bkv);
+      fused(0, 1, (const void **)&a.Wq, (const void **)&a.bq, (const void **)&a.Wq_p);
+      fused(1, 2, (const void **)&a.Wkv, (const void **)&a.bkv, (const void **)&a.Wkv_p);
     }
-    fused(3, 1, (const void **)&a.Wo, (const void **)&a.bo);
+    fused(3, 1, (const void **)&a.Wo, (const void **)&a.bo, (const void **)&a.Wo_p);
     if (rpr && c > 0) put_f32(br.take((int64_t)(2 * c + 1) * dh), (2 * c + 1) * dh, (const void **)&a.rk);
   };
   auto put_ffn = [&](FFN &f) {
@@ -412,6 +420,11 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
     size_t o = pk.reserve((size_t)d * F * 2);
     Packer::transpose(W1, d, F, (_Float16 *)(pk.img.data() + o));
     fixes.push_back({o, (const void **)&f.W1});
+    if (nt::gemm_stream_supported(F, d)) {
+      size_t op = pk.reserve(nt::vocab_pack_bytes(F, d));
+      nt::vocab_pack((const _Float16 *)(pk.img.data() + o), F, d, (_Float16 *)(pk.img.data() + op));
+      fixes.push_back({op, (const void **)&f.W1_p});
+    }
     put_f32(b1, F, (const void **)&f.b1);
     o = pk.reserve((size_t)d * F * 2);
     Packer::transpose(W2, F, d, (_Float16 *)(pk.img.data() + o));
@@ -530,13 +543,13 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
     nt::GemmEpilogue e;
     e.bias = L.self.bqkv; e.scale = qscale; e.scale_cols = d; e.dst0 = m->qkv; e.ld0 = 3 * d; e.n_split = 3 * d;
     KT(K_GEMM_ENC_QKV, gemm_bytes(Md, dd, 3 * dd, ea, ea, false), 6 * Md * dd * dd,
-       nt::launch_gemm(amode, kEncF32, m->a_enc, lo_of(m->a_enc, lo_d), d, L.self.Wqkv, M, 3 * d, d, e, s));
+       nt::launch_gemm(amode, kEncF32, m->a_enc, lo_of(m->a_enc, lo_d), d, L.self.Wqkv, M, 3 * d, d, e, s, L.self.Wqkv_p));
     KT(K_ATTN_ENC, Md * 4 * dd * ea, 4.0 * B * S * S * dd,
        nt::launch_enc_attention(m->qkv, kEncF32, m->len, m->ctx_enc, lo_d, B, S, d, H, L.self.rk, c.rpr_clip, s));
     nt::GemmEpilogue o;
     o.bias = L.self.bo; o.resid = m->x; o.ldr = d; o.dst0 = m->x; o.ld0 = d; o.n_split = d;
     KT(K_GEMM_ENC_O, gemm_bytes(Md, dd, dd, ea, 4, true), 2 * Md * dd * dd,
-       nt::launch_gemm(amode, true, m->ctx_enc, lo_of(m->ctx_enc, lo_d), d, L.self.Wo, M, d, d, o, s));
+       nt::launch_gemm(amode, true, m->ctx_enc, lo_of(m->ctx_enc, lo_d), d, L.self.Wo, M, d, d, o, s, L.self.Wo_p));
     if (F > 0) {
       KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
          nt::launch_layer_norm(m->x, M, d, L.ln2.g, L.ln2.b, c.ln_eps, m->a_enc, ln_mode, lo_d, s));
@@ -544,7 +557,7 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
       f1.bias = L.ffn.b1; f1.relu = 1; f1.dst0 = m->u_enc; f1.ld0 = F; f1.n_split = F;
       f1.dst_lo_offset = kEncF32 ? lo_F : 0;
       KT(K_GEMM_ENC_FFN, gemm_bytes(Md, dd, F, ea, ea, false), 2 * Md * dd * F,
-         nt::launch_gemm(amode, false, m->a_enc, lo_of(m->a_enc, lo_d), d, L.ffn.W1, M, F, d, f1, s));
+         nt::launch_gemm(amode, false, m->a_enc, lo_of(m->a_enc, lo_d), d, L.ffn.W1, M, F, d, f1, s, L.ffn.W1_p));
       nt::GemmEpilogue f2;
       f2.bias = L.ffn.b2; f2.resid = m->x; f2.ldr = d; f2.dst0 = m->x; f2.ld0 = d; f2.n_split = d;
       KT(K_GEMM_ENC_FFN, gemm_bytes(Md, F, dd, ea, 4, true), 2 * Md * dd * F,
@@ -557,7 +570,7 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
     nt::GemmEpilogue e;
     e.bias = m->dec[l].cross.bkv; e.dst0 = m->cross[l]; e.ld0 = 2 * d; e.n_split = 2 * d;
     KT(K_GEMM_CROSS_KV, gemm_bytes(Md, dd, 2 * dd, ea, ca, false), 4 * Md * dd * dd,
-       nt::launch_gemm(amode, kCrossF32, m->enc_out, lo_of(m->enc_out, lo_d), d, m->dec[l].cross.Wkv, M, 2 * d, d, e, s));
+       nt::launch_gemm(amode, kCrossF32, m->enc_out, lo_of(m->enc_out, lo_d), d, m->dec[l].cross.Wkv, M, 2 * d, d, e, s, m->dec[l].cross.Wkv_p));
   }
   m->len_prefix.clear();
   m->B = B; m->S = S; m->encoded = true;
@@ -613,19 +626,31 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
     const double cross_keys = (m->len_prefix.size() > (size_t)R) ? (double)m->len_prefix[(size_t)R] : Rd * S;
     // One decoder projection: C = [LayerNorm](A) * Wt^T with the given epilogue.  Small row counts
     // take the one-round-trip kernel with the LayerNorm fused into its prologue.
-    auto dec_gemm = [&](int id, const float *A, int K, const _Float16 *Wt, int N, const LN *ln,
+    // Above the row count of the one-round-trip kernel the projections take the streaming kernel, which reads its
+    // A operand as a head/tail pair of fp16 planes: the LayerNorm and the attention kernels then write planes.
+    const long lo_rows = (long)m->max_rows;
+    auto streams = [&](int N, int K, const _Float16 *Wp, bool with_ln) -> bool {
+      if (R <= kSkinnyMaxRows && nt::skinny_gemm_supported(K, with_ln)) return false;
+      return Wp != nullptr && nt::gemm_stream_supported(N, K);
+    };
+    auto dec_gemm = [&](int id, const float *A, int K, const _Float16 *Wt, const _Float16 *Wp, int N, const LN *ln,
                         const nt::GemmEpilogue &e) -> int {
       const double by = gemm_bytes(Rd, K, N, e.resid != nullptr), fl = 2 * Rd * K * (double)N;
       if (R <= kSkinnyMaxRows && nt::skinny_gemm_supported(K, ln != nullptr)) {
         KT(id, by, fl, nt::launch_skinny_gemm(A, K, Wt, R, N, K, ln ? ln->g : nullptr, ln ? ln->b : nullptr, c.ln_eps, e, s));
         return NT_OK;
       }
+      const bool planes = streams(N, K, Wp, ln != nullptr);
       if (ln) {
         KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd,
-           nt::launch_layer_norm(A, R, K, ln->g, ln->b, c.ln_eps, m->a32, nt::OUT_F32, 0, s));
+           nt::launch_layer_norm(A, R, K, ln->g, ln->b, c.ln_eps, m->a32, planes ? nt::OUT_PLANES : nt::OUT_F32,
+                                 lo_rows * K, s));
         A = m->a32;
       }
-      KT(id, by, fl, nt::launch_gemm(nt::A_F32, true, A, nullptr, K, Wt, R, N, K, e, s));
+      if (planes)  // A is a plane pair: written by the LayerNorm above or by the attention kernel
+        KT(id, by, fl, nt::launch_gemm(nt::A_PLANES, true, A, (const _Float16 *)A + lo_rows * K, K, Wt, R, N, K, e, s, Wp));
+      else
+        KT(id, by, fl, nt::launch_gemm(nt::A_F32, true, A, nullptr, K, Wt, R, N, K, e, s));
       return NT_OK;
     };
     int rc;
@@ -635,32 +660,32 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
         nt::GemmEpilogue e;
         e.bias = L.self.bqkv; e.scale = qscale; e.scale_cols = d; e.dst0 = m->q32; e.ld0 = d; e.n_split = d;
         e.dst1 = m->self_kv[l] + (long)t * 2 * d; e.ld1 = self_stride;
-        if ((rc = dec_gemm(K_GEMM_DEC_QKV, m->z, d, L.self.Wqkv, 3 * d, &L.ln1, e))) return rc;
+        if ((rc = dec_gemm(K_GEMM_DEC_QKV, m->z, d, L.self.Wqkv, L.self.Wqkv_p, 3 * d, &L.ln1, e))) return rc;
         KT(K_ATTN_DEC_SELF, Rd * (t + 1) * 2 * dd * 4 + Rd * dd * 8, 4 * Rd * (t + 1) * dd,
            nt::launch_attn_decode(m->q32, m->self_kv[l], true, self_stride, nullptr, t + 1, R, d, H, L.self.rk,
-                                  c.rpr_clip, t, m->ctx32, s));
+                                  c.rpr_clip, t, m->ctx32, s, streams(d, d, L.self.Wo_p, false) ? lo_rows * d : 0));
         nt::GemmEpilogue o;
         o.bias = L.self.bo; o.resid = m->z; o.ldr = d; o.dst0 = m->z; o.ld0 = d; o.n_split = d;
-        if ((rc = dec_gemm(K_GEMM_DEC_O, m->ctx32, d, L.self.Wo, d, nullptr, o))) return rc;
+        if ((rc = dec_gemm(K_GEMM_DEC_O, m->ctx32, d, L.self.Wo, L.self.Wo_p, d, nullptr, o))) return rc;
       }
       {  // cross-attention over the encoder keys/values
         nt::GemmEpilogue e;
         e.bias = L.cross.bq; e.scale = qscale; e.scale_cols = d; e.dst0 = m->q32; e.ld0 = d; e.n_split = d;
-        if ((rc = dec_gemm(K_GEMM_DEC_Q, m->z, d, L.cross.Wq, d, &L.ln2, e))) return rc;
+        if ((rc = dec_gemm(K_GEMM_DEC_Q, m->z, d, L.cross.Wq, L.cross.Wq_p, d, &L.ln2, e))) return rc;
         KT(K_ATTN_DEC_CROSS, cross_keys * 2 * dd * ca + Rd * dd * 8, 4 * cross_keys * dd,
            nt::launch_attn_decode(m->q32, m->cross[l], kCrossF32, (long)S * 2 * d, m->len, 0, R, d, H, nullptr, 0, 0,
-                                  m->ctx32, s));
+                                  m->ctx32, s, streams(d, d, L.cross.Wo_p, false) ? lo_rows * d : 0));
         nt::GemmEpilogue o;
         o.bias = L.cross.bo; o.resid = m->z; o.ldr = d; o.dst0 = m->z; o.ld0 = d; o.n_split = d;
-        if ((rc = dec_gemm(K_GEMM_DEC_O, m->ctx32, d, L.cross.Wo, d, nullptr, o))) return rc;
+        if ((rc = dec_gemm(K_GEMM_DEC_O, m->ctx32, d, L.cross.Wo, L.cross.Wo_p, d, nullptr, o))) return rc;
       }
       if (F > 0) {
         nt::GemmEpilogue f1;
         f1.bias = L.ffn.b1; f1.relu = 1; f1.dst0 = m->u32; f1.ld0 = F; f1.n_split = F;
-        if ((rc = dec_gemm(K_GEMM_DEC_FFN, m->z, d, L.ffn.W1, F, &L.ln3, f1))) return rc;
+        if ((rc = dec_gemm(K_GEMM_DEC_FFN, m->z, d, L.ffn.W1, L.ffn.W1_p, F, &L.ln3, f1))) return rc;
         nt::GemmEpilogue f2;
         f2.bias = L.ffn.b2; f2.resid = m->z; f2.ldr = d; f2.dst0 = m->z; f2.ld0 = d; f2.n_split = d;
-        if ((rc = dec_gemm(K_GEMM_DEC_FFN, m->u32, F, L.ffn.W2, d, nullptr, f2))) return rc;
+        if ((rc = dec_gemm(K_GEMM_DEC_FFN, m->u32, F, L.ffn.W2, nullptr, d, nullptr, f2))) return rc;
       }
     }
     // final LayerNorm as a head/tail plane pair (the planes share the a32 buffer), then the output layer

@@ -32,8 +32,16 @@ enum AMode { A_F16 = 0, A_PLANES = 1, A_F32 = 2 };
 
 // a_mode: AMode; A_lo is the tail plane for A_PLANES (ignored otherwise).  c_f32: destinations are
 // fp32, else fp16.  K must be a multiple of 64; lda in elements.
+// Wp (optional): the same weights in MFMA fragment order (vocab_pack layout); with A_PLANES and a supported
+// shape the streaming kernel is used.
 hipError_t launch_gemm(int a_mode, bool c_f32, const void *A, const void *A_lo, long lda, const _Float16 *Wt, int M,
-                       int N, int K, const GemmEpilogue &e, hipStream_t s);
+                       int N, int K, const GemmEpilogue &e, hipStream_t s, const _Float16 *Wp = nullptr);
+
+// Streaming form for K = 256 / 512 and N % 64 == 0 (nt_gemm_stream.hip): the A tile (head/tail planes) stays in
+// the LDS, the weights stream through registers in fragment order.
+bool gemm_stream_supported(int N, int K);
+hipError_t launch_gemm_stream(bool c_f32, const _Float16 *A, const _Float16 *A_lo, long lda, const _Float16 *Wp, int M,
+                              int N, int K, const GemmEpilogue &e, hipStream_t s);
 
 // Decoder-step variant for small M (fp32 A and C): 32 x 32 tiles, whole-K operand panels loaded
 // in one round trip.  If ln_g != nullptr the rows of A are LayerNorm-ed first (requires K to be
@@ -170,9 +178,11 @@ hipError_t launch_enc_attention(const void *qkv, bool f32, const int32_t *len, v
 //   n_keys: fixed count (self-attention: t+1) when len == nullptr, else len[r] (cross).
 //   kv_f32 selects fp32 or fp16 cache elements.
 //   rk (self only): relative keys; the query sits at position qpos, key j at position j.
+//   ctx_lo_offset != 0: ctx is written as a head/tail pair of fp16 planes instead (head at ctx, tail that many
+//   elements later).
 hipError_t launch_attn_decode(const float *q, const void *kv, bool kv_f32, long row_stride, const int32_t *len,
                               int n_keys, int rows, int d, int heads, const float *rk, int clip, int qpos,
-                              float *ctx, hipStream_t s);
+                              float *ctx, hipStream_t s, long ctx_lo_offset = 0);
 
 // max dynamic LDS the encoder attention needs for (S, dh); used to validate shapes at load.
 size_t enc_attention_lds_bytes(int S, int dh, bool f32);
