@@ -80,7 +80,8 @@ def main():
     model = nt.Model(cfg, blob, max_batch_tokens=args.budget, pipeline_lanes=args.lanes)
     # independent batches run on the model's pipeline lanes (shared weights, one arena and stream each)
     lanes = [model.lane(i) for i in range(model.n_lanes())]
-    streams = [torch.cuda.Stream() for _ in lanes]
+    # each lane's own stream: the library has checked at load time that these run concurrently
+    streams = [ln.own_stream() for ln in lanes]
 
     # ---- batches resident in HBM (untimed set-up) ----
     order, starts = nt.plan_batches(lens, args.budget)

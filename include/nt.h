@@ -73,7 +73,7 @@ typedef struct {
   int32_t max_batch_rows;
   int64_t max_batch_tokens;
   int32_t pipeline_lanes; /* batches kept in flight by nt_translate_batch, each with its own arena and
-                             internal stream; 0 = default (3), 1 = no overlap */
+                             internal stream; 0 = default (4, one per hardware queue), 1 = no overlap */
   int32_t reserved;       /* must be 0 */
 } nt_config;
 
@@ -201,9 +201,15 @@ int nt_debug_timing_read(nt_model *m, int kernel, double *total_ms, int64_t *lau
  * handle that nt_encode / nt_decode_greedy / nt_debug_* accept, so that a caller who keeps its batches
  * on the device can run independent batches on different streams at the same time.  Lane handles are
  * owned by m: never pass them to nt_free.  nt_translate_batch uses all lanes by itself.
+ * nt_lane_stream returns the HIP stream (hipStream_t) that the library created for a lane and that
+ * nt_translate_batch launches the lane's work on; it is owned by the model.  A caller that drives the
+ * lanes itself may launch on these streams: they were created one after the other, which spreads them
+ * over the hardware queues, whereas streams picked from another pool may share one queue and then do
+ * not overlap.  Returns NULL for a null model.
  */
 int nt_pipeline_lanes(const nt_model *m);
 nt_model *nt_pipeline_lane(nt_model *m, int i);
+void *nt_lane_stream(nt_model *m);
 
 /* Bytes of device memory held by the model (weights, arena, caches). */
 int64_t nt_device_bytes(const nt_model *m);

@@ -17,7 +17,7 @@ EXPORTS = ["nt_param_count", "nt_n_steps", "nt_load_weights", "nt_free", "nt_enc
            "nt_translate_batch", "nt_plan_batches", "nt_debug_encoder_out", "nt_debug_teacher_forced_logits",
            "nt_check_device_flags", "nt_device_bytes", "nt_last_error", "nt_debug_timing_enable",
            "nt_debug_timing_count", "nt_debug_timing_name", "nt_debug_timing_read", "nt_pipeline_lanes",
-           "nt_pipeline_lane"]
+           "nt_pipeline_lane", "nt_lane_stream"]
 
 
 class NtConfig(C.Structure):
@@ -65,6 +65,7 @@ def load_library() -> C.CDLL:
         "nt_last_error": (C.c_char_p, []),
         "nt_pipeline_lanes": (C.c_int, [p]),
         "nt_pipeline_lane": (p, [p, C.c_int]),
+        "nt_lane_stream": (C.c_void_p, [p]),
         "nt_debug_timing_enable": (C.c_int, [p, C.c_uint64]),
         "nt_debug_timing_count": (C.c_int, []),
         "nt_debug_timing_name": (C.c_char_p, [C.c_int]),
@@ -166,6 +167,14 @@ class Model:
         ln = object.__new__(Model)
         ln.cfg, ln._h, ln._owner = self.cfg, C.c_void_p(h), self   # the owner frees the lanes
         return ln
+
+    def own_stream(self):
+        """The lane's own HIP stream as a torch.cuda.ExternalStream (owned by the model)."""
+        import torch
+        ptr = lib().nt_lane_stream(self._h)
+        if not ptr:
+            raise RuntimeError("no lane stream")
+        return torch.cuda.ExternalStream(int(ptr))
 
     def __del__(self):
         try:

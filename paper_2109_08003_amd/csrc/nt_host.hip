@@ -2,6 +2,7 @@
 // batcher and the step scheduler that enqueues the gfx950 kernels.  No CPU fallback exists:
 // every numerical step of the path is a kernel in nt_gemm.hip / nt_rows.hip / nt_attn.hip.
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -49,7 +50,7 @@ constexpr int kSkinnyMaxRows = 1024;
 // the step is bound by the weight stream and the two-plane kernel costs the same.
 constexpr int kCertMinRows = 512;
 // Batches nt_translate_batch keeps in flight when the configuration does not say (pipeline_lanes = 0).
-constexpr int kDefaultLanes = 3;
+constexpr int kDefaultLanes = 4;
 constexpr size_t kEncElt = kEncF32 ? 4 : 2, kCrossElt = kCrossF32 ? 4 : 2;
 
 // Launch `call`; when timing of family `id` is on, bracket it with two events on the stream and
@@ -327,6 +328,8 @@ int64_t nt_device_bytes(const nt_model *m) {
 
 int nt_pipeline_lanes(const nt_model *m) { return m ? 1 + (int)m->lanes.size() : 0; }
 
+void *nt_lane_stream(nt_model *m) { return m ? (void *)m->lane_stream : nullptr; }
+
 nt_model *nt_pipeline_lane(nt_model *m, int i) {
   if (!m || i < 0 || i > (int)m->lanes.size()) return nullptr;
   return i == 0 ? m : m->lanes[(size_t)i - 1];
@@ -346,6 +349,59 @@ void nt_free(nt_model *m) {
   for (hipEvent_t e : m->timing.pool) (void)hipEventDestroy(e);
   delete m;
 }
+
+namespace {
+
+// Two streams overlap only if the runtime has put them on different hardware queues, and there are few of those
+// (four per process by default).  Which queue a new stream gets depends on what else the process has created, so
+// measure instead of guessing: a one-wave kernel that spins for 100 us is launched on two streams at once; if
+// both are done after clearly less than twice that, the streams run concurrently.  The lanes get a set of
+// mutually concurrent streams if one can be found among a few candidates; otherwise they keep what they have
+// (correct either way, only without overlap).
+int spread_lane_streams(nt_model *m) {
+  std::vector<nt_model *> lanes{m};
+  for (nt_model *ln : m->lanes) lanes.push_back(ln);
+  const size_t n = lanes.size();
+  if (n < 2) return NT_OK;
+  std::vector<hipStream_t> cand;
+  for (nt_model *ln : lanes) cand.push_back(ln->lane_stream);
+  for (int i = 0; i < 8; i++) {
+    hipStream_t st;
+    if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) break;
+    cand.push_back(st);
+  }
+  const long ticks = 10000;  // 100 us
+  auto concurrent = [&](hipStream_t a, hipStream_t b) -> bool {
+    double best = 1e30;
+    for (int rep = 0; rep < 2; rep++) {  // the first launch on a stream may carry one-off costs
+      (void)hipStreamSynchronize(a);
+      (void)hipStreamSynchronize(b);
+      const auto t0 = std::chrono::steady_clock::now();
+      if (nt::launch_spin(ticks, m->flags + 8, a) != hipSuccess || nt::launch_spin(ticks, m->flags + 8, b) != hipSuccess) return false;
+      (void)hipStreamSynchronize(a);
+      (void)hipStreamSynchronize(b);
+      best = std::min(best, std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count());
+    }
+    return best < 170.0;
+  };
+  std::vector<size_t> pick{0};
+  for (size_t c = 1; c < cand.size() && pick.size() < n; c++) {
+    bool ok = true;
+    for (size_t p : pick) ok = ok && concurrent(cand[p], cand[c]);
+    if (ok) pick.push_back(c);
+  }
+  std::vector<bool> used(cand.size(), false);
+  for (size_t p : pick) used[p] = true;
+  for (size_t c = 0; c < cand.size() && pick.size() < n; c++)  // not enough concurrent ones: fill up with the rest
+    if (!used[c]) { pick.push_back(c); used[c] = true; }
+  for (size_t i = 0; i < n; i++) lanes[i]->lane_stream = cand[pick[i]];
+  for (size_t c = 0; c < cand.size(); c++)
+    if (!used[c]) (void)hipStreamDestroy(cand[c]);
+  if (hipGetLastError() != hipSuccess) return fail(NT_EHIP, "stream probing failed");
+  return NT_OK;
+}
+
+}  // namespace
 
 int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_bytes, void *hip_stream,
                     nt_model **out) try {
@@ -507,6 +563,8 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
     }
   }
   HIP_TRY(hipStreamSynchronize(s));  // the packed host image goes out of scope
+  rc = spread_lane_streams(m);
+  if (rc) return rc;
   guard.m = nullptr;
   *out = m;
   return NT_OK;

@@ -136,6 +136,8 @@ hipError_t launch_planes_to_float(const _Float16 *hi, const _Float16 *lo, float 
 // fp16 -> fp32 copy (debug readback)
 hipError_t launch_half_to_float(const _Float16 *in, float *out, long n, hipStream_t s);
 hipError_t launch_fill_i32(int32_t *p, long n, int32_t v, hipStream_t s);
+// one wave that busy-waits for `ticks` periods of the 100 MHz wall clock (bounded); sink is never written
+hipError_t launch_spin(long ticks, int *sink, hipStream_t s);
 
 // Start of decoder step t for rows [0, rows_prev): (1) if t > 0, reduce the arg-max partials of
 // step t-1 and store the token in out[r*out_ld + t-1]; (2) for rows < rows_now: take the input

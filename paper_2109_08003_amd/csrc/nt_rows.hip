@@ -164,6 +164,19 @@ hipError_t launch_fill_i32(int32_t *p, long n, int32_t v, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Busy-waits for a given number of 100 MHz ticks (bounded by an iteration count, so it always ends).  Used at
+// load time to find out which streams run concurrently.
+__global__ void spin_kernel(long ticks, int *sink) {
+  const long t0 = wall_clock64();
+  int it = 0;
+  while (wall_clock64() - t0 < ticks && it < 2000000) it++;
+  if (it < 0) *sink = it;
+}
+hipError_t launch_spin(long ticks, int *sink, hipStream_t s) {
+  hipLaunchKernelGGL(spin_kernel, dim3(1), dim3(64), 0, s, ticks, sink);
+  return hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void step_begin_kernel(StepBeginArgs a) {
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);

@@ -36,7 +36,6 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int VS_ROWS = 128;  // LDS fragment rows per tile (exact variant: 64 matrix rows x 2 planes)
 constexpr int VS_WAVES = 8;
-constexpr int VS_SL = 4;      // register slots of W fragments per wave; the lookahead is VS_SL - 1 k-steps
 constexpr int VS_CUS_PER_XCD = 32;
 
 bool vocab_stream_supported(int K) { return K == 256 || K == 512; }
@@ -93,7 +92,9 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
   constexpr int TILE_M = EXACT ? 64 : 128;
   constexpr int LD = K + 8;                 // halfs per LDS row: the 16 B pad keeps the fragment reads conflict-free
   constexpr int KS = K / 16;
-  constexpr int SL = VS_SL;
+  // register slots of W fragments per wave; the lookahead is SL - 1 k-steps (the single-pass variant has 128
+  // accumulator registers and no room for more than four slots)
+  constexpr int SL = EXACT ? 8 : 4;
   static_assert(KS % SL == 0, "the ring of W slots must divide the k-steps of a strip");
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
