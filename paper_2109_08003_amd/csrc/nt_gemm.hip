@@ -490,7 +490,8 @@ hipError_t launch_vocab_argmax_tiled(const _Float16 *h, const _Float16 *h_lo, lo
 __global__ __launch_bounds__(256) void argmax_select_kernel(const unsigned long long *pk, const float *ps, int n_partials,
                                                             int rows, const float *lo_norm, float w_norm_max,
                                                             int32_t *tok, int32_t *slot_of_row, int32_t *list,
-                                                            int32_t *count, unsigned long long *final_key) {
+                                                            int32_t *count, unsigned long long *final_key,
+                                                            unsigned long long *need_mask) {
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= rows) return;
@@ -513,10 +514,21 @@ __global__ __launch_bounds__(256) void argmax_select_kernel(const unsigned long 
     second = fmaxf(fmaxf(second, os), loser ? key_value(loser) : -INFINITY);
     best = take ? ob : best;
   }
-  if (lane != 0) return;
-  tok[r] = (int32_t)(0xFFFFFFFFu - (unsigned int)best);
   const float gap = key_value(best) - second;
   const float bound = 2.f * lo_norm[r] * w_norm_max + 1e-4f;
+  // Ranges of the vocabulary (one per partial) that can hold the arg-max of the head+tail logits: a head-only
+  // logit more than `bound` below the best one cannot win.  Bit p of the mask stands for partial p (up to 64).
+  unsigned long long mask = 0ull;
+  if (n_partials <= 64) {
+    const float floor_ = key_value(best) - bound;
+    const bool cand = lane < n_partials && pk[(long)r * n_partials + lane] != 0ull &&
+                      key_value(pk[(long)r * n_partials + lane]) >= floor_;
+    mask = __ballot(cand);
+  } else {
+    mask = ~0ull;
+  }
+  if (lane != 0) return;
+  tok[r] = (int32_t)(0xFFFFFFFFu - (unsigned int)best);
   if (gap > bound) {
     slot_of_row[r] = -1;
   } else {
@@ -524,15 +536,16 @@ __global__ __launch_bounds__(256) void argmax_select_kernel(const unsigned long 
     slot_of_row[r] = sl;
     list[sl] = r;
     final_key[sl] = 0ull;
+    need_mask[sl] = mask;
   }
 }
 
 hipError_t launch_argmax_select(const unsigned long long *pk, const float *ps, int n_partials, int M, const float *lo_norm,
                                 float w_norm_max, int32_t *tok, int32_t *slot_of_row, int32_t *list, int32_t *count,
-                                unsigned long long *final_key, hipStream_t s) {
+                                unsigned long long *final_key, unsigned long long *need_mask, hipStream_t s) {
   if (M <= 0) return hipSuccess;
   hipLaunchKernelGGL(argmax_select_kernel, dim3((M + 3) / 4), dim3(256), 0, s, pk, ps, n_partials, M, lo_norm, w_norm_max,
-                     tok, slot_of_row, list, count, final_key);
+                     tok, slot_of_row, list, count, final_key, need_mask);
   return hipGetLastError();
 }
 
@@ -540,14 +553,15 @@ hipError_t launch_vocab_argmax_certified_tiled(const _Float16 *h, const _Float16
                                                int N, int K, const float *lo_norm, float w_norm_max,
                                                unsigned long long *pk, float *ps, int32_t *tok, int32_t *slot_of_row,
                                                int32_t *list, int32_t *count, unsigned long long *final_key,
-                                               hipStream_t s) {
+                                               unsigned long long *need_mask, hipStream_t s) {
   if (M <= 0) return hipSuccess;
   const int tpw = vocab_tiles_per_wg(M, N), np = vocab_argmax_partials_tiled(M, N);
   const int tiles_m = (M + BM - 1) / BM, strips = np / 2;
   hipLaunchKernelGGL(vocab_argmax_kernel<true>, dim3(((strips + 7) / 8) * 8 * tiles_m), dim3(256), 0, s, h, h_lo, ldh, Wt,
                      M, N, K, tpw, np, tiles_m, pk, ps, (const int *)nullptr, (const int *)nullptr,
                      (unsigned long long *)nullptr);
-  hipError_t e = launch_argmax_select(pk, ps, np, M, lo_norm, w_norm_max, tok, slot_of_row, list, count, final_key, s);
+  hipError_t e = launch_argmax_select(pk, ps, np, M, lo_norm, w_norm_max, tok, slot_of_row, list, count, final_key,
+                                      need_mask, s);
   if (e != hipSuccess) return e;
   // recompute of the uncertified rows: one vocabulary tile per workgroup, every workgroup walks all
   // gathered m tiles (normally one); the row count is read on the device

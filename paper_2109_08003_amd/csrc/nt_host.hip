@@ -157,7 +157,7 @@ struct nt_model {
   unsigned long long *pk = nullptr;
   float *ps = nullptr, *lo_norm = nullptr;             // certified arg-max: runner-up partials, tail norms
   int32_t *tok = nullptr, *slot_of_row = nullptr, *cert_list = nullptr;
-  unsigned long long *final_key = nullptr;
+  unsigned long long *final_key = nullptr, *need_mask = nullptr;
   float w_norm_max = 0.f;                              // max_v ||W_out[v,:]||
   int32_t *len = nullptr, *flags = nullptr;
   int32_t *d_src = nullptr, *d_len_in = nullptr, *d_out = nullptr;  // staging for nt_translate_batch
@@ -279,7 +279,7 @@ int alloc_lane_state(nt_model *m, hipStream_t s) {
                o_ctx32 = cv.take((size_t)Br * d * 4), o_u32 = cv.take((size_t)Br * std::max(F, 1) * 4),
                o_pk = cv.take((size_t)m->pk_elems * 8), o_ps = cv.take((size_t)m->pk_elems * 4),
                o_lon = cv.take((size_t)Br * 4), o_tok = cv.take((size_t)Br * 4), o_slot = cv.take((size_t)Br * 4),
-               o_clist = cv.take((size_t)Br * 4), o_fkey = cv.take((size_t)Br * 8),
+               o_clist = cv.take((size_t)Br * 4), o_fkey = cv.take((size_t)Br * 8), o_nmask = cv.take((size_t)Br * 8),
                o_len = cv.take((size_t)Br * 4), o_flags = cv.take(64),
                o_src = cv.take((size_t)Mt * 4), o_lin = cv.take((size_t)Br * 4), o_out = cv.take((size_t)m->self_positions * 4);
   m->arena_bytes = cv.off;
@@ -292,7 +292,7 @@ int alloc_lane_state(nt_model *m, hipStream_t s) {
   m->u32 = at<float>(A, o_u32); m->pk = at<unsigned long long>(A, o_pk); m->len = at<int32_t>(A, o_len);
   m->ps = at<float>(A, o_ps); m->lo_norm = at<float>(A, o_lon); m->tok = at<int32_t>(A, o_tok);
   m->slot_of_row = at<int32_t>(A, o_slot); m->cert_list = at<int32_t>(A, o_clist);
-  m->final_key = at<unsigned long long>(A, o_fkey);
+  m->final_key = at<unsigned long long>(A, o_fkey); m->need_mask = at<unsigned long long>(A, o_nmask);
   m->flags = at<int32_t>(A, o_flags); m->d_src = at<int32_t>(A, o_src); m->d_len_in = at<int32_t>(A, o_lin);
   m->d_out = at<int32_t>(A, o_out);
   HIP_TRY(nt::launch_fill_i32(m->flags, 16, 0, s));
@@ -762,7 +762,7 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
       if (prev_cert)
         KT(K_VOCAB_ARGMAX, (double)V * dd * 2 + Rd * dd * 4 + Rd * np_ * 8, 2 * Rd * dd * V,
            nt::launch_vocab_argmax_certified(h_hi, h_lo, d, m->vw, R, m->lo_norm, m->w_norm_max, m->pk, m->ps,
-                                             m->tok, m->slot_of_row, m->cert_list, m->flags + 4, m->final_key, s));
+                                             m->tok, m->slot_of_row, m->cert_list, m->flags + 4, m->final_key, m->need_mask, s));
       else
         KT(K_VOCAB_ARGMAX, (double)V * dd * 2 + Rd * dd * 4 + Rd * np_ * 8, 2 * Rd * dd * V,
            nt::launch_vocab_argmax(h_hi, h_lo, d, m->vw, R, m->pk, s));

@@ -99,11 +99,12 @@ hipError_t launch_vocab_argmax(const _Float16 *h, const _Float16 *h_lo, long ldh
 // certified against a rigorous bound on the contribution of the tail (lo_norm[m] = ||tail of row m||,
 // w_norm_max = max_v ||W_out[v,:]||); rows that cannot be certified are recomputed with both planes.
 // Results: tok[m] when slot_of_row[m] < 0, else the key in final_key[slot_of_row[m]].
-// *count must be 0 when the call starts (the step-begin kernel clears it).
+// *count must be 0 when the call starts (the step-begin kernel clears it).  need_mask [M]: scratch, per recompute
+// slot the ranges of the vocabulary that can still hold the arg-max (the recompute skips the others).
 hipError_t launch_vocab_argmax_certified(const _Float16 *h, const _Float16 *h_lo, long ldh, const VocabWeights &w, int M,
                                          const float *lo_norm, float w_norm_max, unsigned long long *pk, float *ps,
                                          int32_t *tok, int32_t *slot_of_row, int32_t *list, int32_t *count,
-                                         unsigned long long *final_key, hipStream_t s);
+                                         unsigned long long *final_key, unsigned long long *need_mask, hipStream_t s);
 
 // the tiled implementations (nt_gemm.hip) and the certification kernel shared by both
 int vocab_argmax_partials_tiled(int M, int N);
@@ -113,10 +114,10 @@ hipError_t launch_vocab_argmax_certified_tiled(const _Float16 *h, const _Float16
                                                int N, int K, const float *lo_norm, float w_norm_max,
                                                unsigned long long *pk, float *ps, int32_t *tok, int32_t *slot_of_row,
                                                int32_t *list, int32_t *count, unsigned long long *final_key,
-                                               hipStream_t s);
+                                               unsigned long long *need_mask, hipStream_t s);
 hipError_t launch_argmax_select(const unsigned long long *pk, const float *ps, int n_partials, int M, const float *lo_norm,
                                 float w_norm_max, int32_t *tok, int32_t *slot_of_row, int32_t *list, int32_t *count,
-                                unsigned long long *final_key, hipStream_t s);
+                                unsigned long long *final_key, unsigned long long *need_mask, hipStream_t s);
 
 // ---- row kernels --------------------------------------------------------------------
 // x[r,:] = sqrt(d) * E[id] + PE[pos]; rows r = b*S + s, pos = s.  Out-of-range ids are

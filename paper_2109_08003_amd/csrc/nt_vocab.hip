@@ -60,12 +60,13 @@ void vocab_pack(const _Float16 *Wt, int N, int K, _Float16 *dst) {
 struct VsSplit {
   int m_tiles, G, per_xcd;
 };
-static VsSplit vs_split(int M, int tile_m) {
+static VsSplit vs_split(int M, int tile_m, int max_ranges) {
   VsSplit p;
   p.m_tiles = (M + tile_m - 1) / tile_m;
   if (p.m_tiles < 1) p.m_tiles = 1;
   p.G = (8 * VS_CUS_PER_XCD) / p.m_tiles;
   if (p.G < 1) p.G = 1;
+  if (p.G > max_ranges) p.G = max_ranges;
   p.per_xcd = (p.m_tiles * p.G + 7) / 8;
   return p;
 }
@@ -77,7 +78,7 @@ static VsSplit vs_split(int M, int tile_m) {
 //   pk[m * G + range], or (row_map != nullptr) the rows row_map[0 .. *count) are gathered, every workgroup walks
 //   all their tiles, and each result is folded into final_key[slot] with a 64-bit atomic max
 //   (order-independent, hence still deterministic).
-template <bool EXACT, int K>
+template <bool EXACT, int K, bool GATHER>
 __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Float16 *__restrict__ h_hi,
                                                                     const _Float16 *__restrict__ h_lo, long ldh,
                                                                     const int *__restrict__ row_map,
@@ -85,7 +86,9 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
                                                                     const _Float16 *__restrict__ Wp, int N, int m_tiles,
                                                                     int G, int per_xcd, unsigned long long *__restrict__ pk,
                                                                     float *__restrict__ ps,
-                                                                    unsigned long long *__restrict__ final_key) {
+                                                                    unsigned long long *__restrict__ final_key,
+                                                                    const unsigned long long *__restrict__ need_mask,
+                                                                    int mask_ranges) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   _Float16 *sh = (_Float16 *)smem;
   constexpr int NACC = EXACT ? 2 : 4;       // 32-row blocks of h per tile
@@ -107,7 +110,9 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
   const int gi = idx / m_tiles, mt = idx % m_tiles;
   const int NS = (N + 63) >> 6;
   const int sb0 = (int)((long)gi * NS / G), sb1 = (int)((long)(gi + 1) * NS / G);
-  if (count) M = *count;  // number of gathered rows, decided on the device
+  if (GATHER) M = *count;  // number of gathered rows, decided on the device
+  // gathered rows of the current tile and their result slots (beyond the h tile and the per-wave results)
+  int *sel_row = (int *)(smem + VS_ROWS * LD * 2), *sel_slot = sel_row + 64, *wtot = sel_slot + 64;
 
   // W fragments come through a buffer resource: scalar offset per fragment, constant lane offset
   const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void *)Wp, 0, NS * 64 * K * 2, 0x00020000);
@@ -117,7 +122,8 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
     return __builtin_bit_cast(half8, t);
   };
 
-  for (int m0 = mt * TILE_M; m0 < M; m0 += m_tiles * TILE_M) {
+  // One tile: rows m0 .. m0 + TILE_M - 1 below Mlim (gathered: positions in sel_row / sel_slot).
+  auto tile = [&](const int m0, const int Mlim) {
     half8 wb[SL][2];
     int strip = sb0 + wave;
     const bool have = strip < sb1;
@@ -130,8 +136,8 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
         const int rr = EXACT ? (R & 63) : R;
         const _Float16 *src = (EXACT && R >= 64) ? h_lo : h_hi;
         int m = m0 + rr;
-        m = m < M ? m : M - 1;
-        const long gm = row_map ? __builtin_amdgcn_readfirstlane(row_map[m]) : m;
+        m = m < Mlim ? m : Mlim - 1;
+        const long gm = GATHER ? __builtin_amdgcn_readfirstlane(sel_row[m]) : m;
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + gm * ldh + lane * 8),
                                          (__attribute__((address_space(3))) void *)(sh + R * LD), 16, 0, 0);
       }
@@ -144,8 +150,8 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
         const int rr = EXACT ? (R & 63) : R;
         const _Float16 *src = (EXACT && R >= 64) ? h_lo : h_hi;
         int m = m0 + rr;
-        m = m < M ? m : M - 1;
-        const long gm = row_map ? row_map[m] : m;
+        m = m < Mlim ? m : Mlim - 1;
+        const long gm = GATHER ? sel_row[m] : m;
         fr[i] = *(const u32x4 *)(src + gm * ldh + kc * 8);
       }
 #pragma unroll
@@ -280,9 +286,9 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
         best = take ? k : best;
       }
       const int m = m0 + tid;
-      if (m < M) {
-        if (final_key) {
-          atomicMax(final_key + m, best);
+      if (m < Mlim) {
+        if (GATHER) {
+          atomicMax(final_key + sel_slot[m], best);
         } else {
           pk[(long)m * G + gi] = best;
           if (!EXACT) ps[(long)m * G + gi] = second;
@@ -290,16 +296,53 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
       }
     }
     __syncthreads();  // before the next tile overwrites the LDS
+  };
+
+  if (!GATHER) {
+    for (int m0 = mt * TILE_M; m0 < M; m0 += m_tiles * TILE_M) tile(m0, M);
+    return;
+  }
+  // Gathered rows: the caller has marked, per row, which of mask_ranges equal ranges of the vocabulary can hold its
+  // arg-max at all; this workgroup takes the rows whose marks meet its own strips.  The list is walked 512 entries
+  // at a time; the wanted entries are ranked with a workgroup prefix sum and processed 64 rows per tile.
+  unsigned long long mine = 0ull;
+  for (int r = 0; r < mask_ranges; r++) {
+    const int r0 = (int)((long)r * NS / mask_ranges), r1 = (int)((long)(r + 1) * NS / mask_ranges);
+    if (r0 < sb1 && sb0 < r1) mine |= 1ull << r;
+  }
+  for (int c0 = 0; c0 < M; c0 += VS_WAVES * 64) {
+    const int i = c0 + tid;
+    const bool need = i < M && (need_mask[i] & mine) != 0ull;
+    const unsigned long long bal = __ballot(need);
+    if (lane == 0) wtot[wave] = __popcll(bal);
+    __syncthreads();
+    int rank = __popcll(bal & ((1ull << lane) - 1ull)), total = 0;
+#pragma unroll
+    for (int w = 0; w < VS_WAVES; w++) {
+      const int c = wtot[w];
+      rank += w < wave ? c : 0;
+      total += c;
+    }
+    for (int t0 = 0; t0 < total; t0 += 64) {  // total is uniform over the workgroup
+      if (need && rank >= t0 && rank < t0 + 64) {
+        sel_row[rank - t0] = row_map[i];
+        sel_slot[rank - t0] = i;
+      }
+      __syncthreads();
+      tile(0, total - t0 < 64 ? total - t0 : 64);
+    }
+    __syncthreads();  // wtot is rewritten by the next chunk
   }
 }
 
-static size_t vs_lds_bytes(int K) { return (size_t)VS_ROWS * (K + 8) * 2; }
+static size_t vs_lds_bytes(int K) { return (size_t)VS_ROWS * (K + 8) * 2 + 1024; }
 
-template <bool EXACT, int K>
+template <bool EXACT, int K, bool GATHER>
 static hipError_t vs_launch(const _Float16 *h, const _Float16 *h_lo, long ldh, const int *row_map, const int *count, int M,
                             const _Float16 *Wp, int N, const VsSplit &p, unsigned long long *pk, float *ps,
-                            unsigned long long *final_key, hipStream_t s) {
-  auto kern = vocab_stream_kernel<EXACT, K>;
+                            unsigned long long *final_key, const unsigned long long *need_mask, int mask_ranges,
+                            hipStream_t s) {
+  auto kern = vocab_stream_kernel<EXACT, K, GATHER>;
   static bool attr_set = false;  // raising the dynamic LDS limit is per kernel, once per process
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vs_lds_bytes(K));
@@ -307,16 +350,21 @@ static hipError_t vs_launch(const _Float16 *h, const _Float16 *h_lo, long ldh, c
     attr_set = true;
   }
   hipLaunchKernelGGL(kern, dim3(8 * p.per_xcd), dim3(VS_WAVES * 64), vs_lds_bytes(K), s, h, h_lo, ldh, row_map, count, M, Wp,
-                     N, p.m_tiles, p.G, p.per_xcd, pk, ps, final_key);
+                     N, p.m_tiles, p.G, p.per_xcd, pk, ps, final_key, need_mask, mask_ranges);
   return hipGetLastError();
 }
 
-template <bool EXACT>
+template <bool EXACT, bool GATHER>
 static hipError_t vs_launch_k(const _Float16 *h, const _Float16 *h_lo, long ldh, const int *row_map, const int *count,
                               int M, const VocabWeights &w, const VsSplit &p, unsigned long long *pk, float *ps,
-                              unsigned long long *final_key, hipStream_t s) {
-  if (w.K == 512) return vs_launch<EXACT, 512>(h, h_lo, ldh, row_map, count, M, w.Wp, w.N, p, pk, ps, final_key, s);
-  if (w.K == 256) return vs_launch<EXACT, 256>(h, h_lo, ldh, row_map, count, M, w.Wp, w.N, p, pk, ps, final_key, s);
+                              unsigned long long *final_key, const unsigned long long *need_mask, int mask_ranges,
+                              hipStream_t s) {
+  if (w.K == 512)
+    return vs_launch<EXACT, 512, GATHER>(h, h_lo, ldh, row_map, count, M, w.Wp, w.N, p, pk, ps, final_key, need_mask,
+                                         mask_ranges, s);
+  if (w.K == 256)
+    return vs_launch<EXACT, 256, GATHER>(h, h_lo, ldh, row_map, count, M, w.Wp, w.N, p, pk, ps, final_key, need_mask,
+                                         mask_ranges, s);
   return hipErrorInvalidValue;
 }
 
@@ -324,14 +372,14 @@ static bool use_stream(const VocabWeights &w) { return !w.force_tiled && w.Wp &&
 
 int vocab_argmax_partials(const VocabWeights &w, int M, bool certified) {
   if (!use_stream(w)) return vocab_argmax_partials_tiled(M, w.N);
-  return vs_split(M, certified ? 128 : 64).G;
+  return certified ? vs_split(M, 128, 64).G : vs_split(M, 64, 256).G;
 }
 
 hipError_t launch_vocab_argmax(const _Float16 *h, const _Float16 *h_lo, long ldh, const VocabWeights &w, int M,
                                unsigned long long *pk, hipStream_t s) {
   if (M <= 0) return hipSuccess;
   if (!use_stream(w)) return launch_vocab_argmax_tiled(h, h_lo, ldh, w.Wt, M, w.N, w.K, pk, s);
-  return vs_launch_k<true>(h, h_lo, ldh, nullptr, nullptr, M, w, vs_split(M, 64), pk, nullptr, nullptr, s);
+  return vs_launch_k<true, false>(h, h_lo, ldh, nullptr, nullptr, M, w, vs_split(M, 64, 256), pk, nullptr, nullptr, nullptr, 0, s);
 }
 
 // Certified single-pass arg-max.  With h = hi + lo, the head-only logit l'(v) = hi . w_v differs
@@ -343,23 +391,23 @@ hipError_t launch_vocab_argmax(const _Float16 *h, const _Float16 *h_lo, long ldh
 hipError_t launch_vocab_argmax_certified(const _Float16 *h, const _Float16 *h_lo, long ldh, const VocabWeights &w, int M,
                                          const float *lo_norm, float w_norm_max, unsigned long long *pk, float *ps,
                                          int32_t *tok, int32_t *slot_of_row, int32_t *list, int32_t *count,
-                                         unsigned long long *final_key, hipStream_t s) {
+                                         unsigned long long *final_key, unsigned long long *need_mask, hipStream_t s) {
   if (M <= 0) return hipSuccess;
   if (!use_stream(w))
     return launch_vocab_argmax_certified_tiled(h, h_lo, ldh, w.Wt, M, w.N, w.K, lo_norm, w_norm_max, pk, ps, tok,
-                                               slot_of_row, list, count, final_key, s);
-  const VsSplit p = vs_split(M, 128);
-  hipError_t e = vs_launch_k<false>(h, h_lo, ldh, nullptr, nullptr, M, w, p, pk, ps, nullptr, s);
+                                               slot_of_row, list, count, final_key, need_mask, s);
+  const VsSplit p = vs_split(M, 128, 64);  // at most 64 ranges: one bit each in the masks of the recompute
+  hipError_t e = vs_launch_k<false, false>(h, h_lo, ldh, nullptr, nullptr, M, w, p, pk, ps, nullptr, nullptr, 0, s);
   if (e != hipSuccess) return e;
-  e = launch_argmax_select(pk, ps, p.G, M, lo_norm, w_norm_max, tok, slot_of_row, list, count, final_key, s);
+  e = launch_argmax_select(pk, ps, p.G, M, lo_norm, w_norm_max, tok, slot_of_row, list, count, final_key, need_mask, s);
   if (e != hipSuccess) return e;
-  // recompute of the uncertified rows: their number is known on the device only, so every workgroup takes one
-  // of 256 vocabulary ranges and walks all gathered tiles (normally one)
+  // recompute of the uncertified rows: their number is known on the device only, so each of 256 workgroups takes
+  // a range of the vocabulary and those gathered rows that still have a candidate there (often none)
   VsSplit q;
   q.m_tiles = 1;
   q.G = 8 * VS_CUS_PER_XCD;
   q.per_xcd = VS_CUS_PER_XCD;
-  return vs_launch_k<true>(h, h_lo, ldh, list, count, M, w, q, nullptr, nullptr, final_key, s);
+  return vs_launch_k<true, true>(h, h_lo, ldh, list, count, M, w, q, nullptr, nullptr, final_key, need_mask, p.G, s);
 }
 
 }  // namespace nt

@@ -237,6 +237,22 @@ def test_c1_full_workload_sampled_against_oracle(nt, oracle):
     assert frac >= 0.99
 
 
+def test_tiled_argmax_kernels_agree_with_streaming_kernels(nt, monkeypatch):
+    """Model widths other than 256 / 512 take the tiled arg-max kernels; NT_VOCAB_TILED=1 selects them for
+    any width.  Both compute the same head+tail logits (in a different summation order), with batches
+    above and below the row count from which the certified single-pass variant is used."""
+    cfg = nt_synth.model_config("C1")
+    blob = nt_synth.make_weights(cfg, seed=0)
+    tokens, offsets = nt_synth.workload("C1", 1024)
+    ref, ro = nt.Model(cfg, blob, max_batch_tokens=16384).translate_batch(tokens, offsets, token_budget=16384)
+    monkeypatch.setenv("NT_VOCAB_TILED", "1")
+    out, oo = nt.Model(cfg, blob, max_batch_tokens=16384).translate_batch(tokens, offsets, token_budget=16384)
+    assert np.array_equal(ro, oo)
+    same = sum(np.array_equal(a, b) for a, b in zip(split(ref, ro), split(out, oo)))
+    print(f"tiled vs streaming arg-max: {same}/1024 sentences identical")
+    assert same >= 1014   # summation order differs, so an exact tie of fp32 logits may fall the other way
+
+
 # ------------------------------------------------------------------------------ restored components (C3) and teacher shape (C4)
 def _check_workload_sample(nt, oracle, name, n_sent, budget, tol_frac, **overrides):
     cfg = nt_synth.model_config(name, **overrides)
