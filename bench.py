@@ -28,7 +28,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0        # dense fp16 MFMA
 # HBM traffic per launch (decode step) of the dominant kernel family from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs, calibrated against a streaming kernel of known size (see profiles/); None where
 # it has not been measured.
-MEASURED_TRAFFIC_BYTES = {("vocab_argmax", "C2", 65536): 72.5e6}
+MEASURED_TRAFFIC_BYTES = {("vocab_argmax", "C2", 65536): 59.5e6}
 
 
 def calibration_copy(torch, mib):

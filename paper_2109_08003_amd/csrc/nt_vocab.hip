@@ -109,7 +109,7 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
   }
   const int gi = idx / m_tiles, mt = idx % m_tiles;
   const int NS = (N + 63) >> 6;
-  const int sb0 = (int)((long)gi * NS / G), sb1 = (int)((long)(gi + 1) * NS / G);
+  const int sb0 = gi * NS / G, sb1 = (gi + 1) * NS / G;  // G <= 256 and NS < 2^22: no overflow
   if (GATHER) M = *count;  // number of gathered rows, decided on the device
   // gathered rows of the current tile and their result slots (beyond the h tile and the per-wave results)
   int *sel_row = (int *)(smem + VS_ROWS * LD * 2), *sel_slot = sel_row + 64, *wtot = sel_slot + 64;
@@ -305,10 +305,12 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
   // Gathered rows: the caller has marked, per row, which of mask_ranges equal ranges of the vocabulary can hold its
   // arg-max at all; this workgroup takes the rows whose marks meet its own strips.  The list is walked 512 entries
   // at a time; the wanted entries are ranked with a workgroup prefix sum and processed 64 rows per tile.
+  // range r of the caller covers strips [r * NS / mask_ranges, (r + 1) * NS / mask_ranges): strip s lies in range
+  // ((s + 1) * mask_ranges - 1) / NS
   unsigned long long mine = 0ull;
-  for (int r = 0; r < mask_ranges; r++) {
-    const int r0 = (int)((long)r * NS / mask_ranges), r1 = (int)((long)(r + 1) * NS / mask_ranges);
-    if (r0 < sb1 && sb0 < r1) mine |= 1ull << r;
+  if (sb1 > sb0) {
+    const int r_lo = ((sb0 + 1) * mask_ranges - 1) / NS, r_hi = (sb1 * mask_ranges - 1) / NS;
+    mine = (r_hi >= 63 ? ~0ull : (1ull << (r_hi + 1)) - 1ull) & ~((1ull << r_lo) - 1ull);
   }
   for (int c0 = 0; c0 < M; c0 += VS_WAVES * 64) {
     const int i = c0 + tid;
