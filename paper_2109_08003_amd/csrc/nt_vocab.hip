@@ -171,15 +171,15 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's rows have landed in the LDS before the barrier
     __syncthreads();
 
-    // running state per 32-row block: largest logit, runner-up, and where the largest sits (strip, position code)
+    // running state per 32-row block: largest logit, runner-up, and where the largest sits: strip * 32 + position
+    // code (inside the fold of a strip the code is written without the strip, which is added when the strip is done)
     float rmax[NACC], rsec[NACC];
-    int rcode[NACC], rstrip[NACC];
+    int rcode[NACC];
 #pragma unroll
     for (int a = 0; a < NACC; a++) {
       rmax[a] = -INFINITY;
       rsec[a] = -INFINITY;
       rcode[a] = 0;
-      rstrip[a] = 0;
     }
 
     if (have) {
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
                 rmax[a] = gt ? val : rmax[a];
                 rcode[a] = gt ? (nb * 16 + v) : rcode[a];
               }
-            rstrip[a] = rmax[a] > before ? strip : rstrip[a];
+            rcode[a] = rmax[a] > before ? strip * 32 + rcode[a] : rcode[a];
           }
         };
         if (strip * 64 + 64 <= N) fold(std::false_type{}); else fold(std::true_type{});
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
 #pragma unroll
     for (int a = 0; a < NACC; a++) {
       const int c = rcode[a], v = c & 15;
-      const int n = rstrip[a] * 64 + (c >> 4) * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+      const int n = (c >> 5) * 64 + ((c >> 4) & 1) * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
       unsigned long long key = (rmax[a] == -INFINITY) ? 0ull : argmax_key(rmax[a], n);
       float second = rsec[a];
       // the two lane groups hold interleaved columns of the same row: merge them
