@@ -29,12 +29,21 @@ constexpr int GS_WAVES = 8;
 
 bool gemm_stream_supported(int N, int K) { return (K == 256 || K == 512) && N % 64 == 0; }
 
-// RB = 32-row blocks per tile (1: decoder-sized M, two workgroups per CU; 2: encoder-sized M)
-template <int RB, int K, bool C_F32>
+__device__ __forceinline__ float gs_wave_sum(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+  return v;
+}
+
+// RB = 32-row blocks per tile (1: decoder-sized M; 2: encoder-sized M).
+// LN = true: A_hi points to fp32 rows X[M][lda] instead; the tile is LayerNorm-ed (fp32 statistics: mean first, then
+// the biased variance of the centred values) and split into head/tail planes while it is written to the LDS, which
+// saves the separate LayerNorm kernel and the round trip of its output through memory.
+template <int RB, int K, bool C_F32, bool LN>
 __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float16 *__restrict__ A_hi,
                                                                    const _Float16 *__restrict__ A_lo, long lda, int M,
                                                                    const _Float16 *__restrict__ Wp, int N, int col_groups,
-                                                                   GemmEpilogue e) {
+                                                                   GemmEpilogue e, GemmLayerNorm ln) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   _Float16 *sh = (_Float16 *)smem;
   constexpr int TM = 32 * RB, ROWS = 2 * TM;  // LDS fragment rows: head rows, then tail rows
@@ -60,7 +69,51 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   };
 
   // ---- the A tile: global memory -> LDS.  Rows past M repeat row M - 1 (their results are never stored) ----
-  if (K == 512) {
+  if (LN) {
+    // a wave takes rows wave, wave + 8, ...; a lane holds NE consecutive elements of the row
+    constexpr int NE = K / 64, RPW = TM / GS_WAVES;
+    const float *X = (const float *)A_hi;
+    float xv[RPW][NE];
+#pragma unroll
+    for (int i = 0; i < RPW; i++) {
+      int m = m0 + wave + GS_WAVES * i;
+      m = m < M ? m : M - 1;
+      const float *xr = X + (long)m * lda + lane * NE;
+#pragma unroll
+      for (int j = 0; j < NE; j += 4) *(float4 *)&xv[i][j] = *(const float4 *)(xr + j);
+    }
+    float gam[NE], bet[NE];
+#pragma unroll
+    for (int j = 0; j < NE; j += 4) {
+      *(float4 *)&gam[j] = *(const float4 *)(ln.gamma + lane * NE + j);
+      *(float4 *)&bet[j] = *(const float4 *)(ln.beta + lane * NE + j);
+    }
+#pragma unroll
+    for (int i = 0; i < RPW; i++) {
+      float sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < NE; j++) sum += xv[i][j];
+      const float mean = gs_wave_sum(sum) / (float)K;
+      float q = 0.f;
+#pragma unroll
+      for (int j = 0; j < NE; j++) {
+        const float c = xv[i][j] - mean;
+        q += c * c;
+      }
+      const float rstd = 1.0f / sqrtf(gs_wave_sum(q) / (float)K + ln.eps);
+      typedef _Float16 halfNE __attribute__((ext_vector_type(NE)));
+      halfNE hi, lo;
+#pragma unroll
+      for (int j = 0; j < NE; j++) {
+        const float y = gam[j] * ((xv[i][j] - mean) * rstd) + bet[j];
+        hi[j] = (_Float16)y;
+        lo[j] = (_Float16)(y - (float)hi[j]);
+      }
+      const int R = wave + GS_WAVES * i;
+      *(halfNE *)(sh + R * LD + lane * NE) = hi;
+      *(halfNE *)(sh + (R + TM) * LD + lane * NE) = lo;
+    }
+  } else if (K == 512) {
 #pragma unroll
     for (int i = 0; i < ROWS / GS_WAVES; i++) {
       const int R = wave + GS_WAVES * i;
@@ -196,10 +249,10 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   }
 }
 
-template <int RB, int K, bool C_F32>
+template <int RB, int K, bool C_F32, bool LN>
 static hipError_t gs_launch(const _Float16 *A, const _Float16 *A_lo, long lda, int M, const _Float16 *Wp, int N,
-                            const GemmEpilogue &e, hipStream_t s) {
-  auto kern = gemm_stream_kernel<RB, K, C_F32>;
+                            const GemmEpilogue &e, const GemmLayerNorm &ln, hipStream_t s) {
+  auto kern = gemm_stream_kernel<RB, K, C_F32, LN>;
   const size_t lds = (size_t)64 * RB * (K + 8) * 2;
   static bool attr_set = false;  // raising the dynamic LDS limit is per kernel, once per process
   if (!attr_set) {
@@ -216,21 +269,33 @@ static hipError_t gs_launch(const _Float16 *A, const _Float16 *A_lo, long lda, i
       col_groups = cg;
       break;
     }
-  hipLaunchKernelGGL(kern, dim3(row_tiles * col_groups), dim3(GS_WAVES * 64), lds, s, A, A_lo, lda, M, Wp, N, col_groups, e);
+  hipLaunchKernelGGL(kern, dim3(row_tiles * col_groups), dim3(GS_WAVES * 64), lds, s, A, A_lo, lda, M, Wp, N, col_groups, e,
+                     ln);
   return hipGetLastError();
 }
 
-hipError_t launch_gemm_stream(bool c_f32, const _Float16 *A, const _Float16 *A_lo, long lda, const _Float16 *Wp, int M,
-                              int N, int K, const GemmEpilogue &e, hipStream_t s) {
+template <bool LN>
+static hipError_t gs_dispatch(bool c_f32, const _Float16 *A, const _Float16 *A_lo, long lda, const _Float16 *Wp, int M,
+                              int N, int K, const GemmEpilogue &e, const GemmLayerNorm &ln, hipStream_t s) {
   if (M <= 0 || N <= 0) return hipSuccess;
   if (!gemm_stream_supported(N, K) || e.n_split % 32 != 0) return hipErrorInvalidValue;
-  const bool small = M <= 8192;  // 32-row tiles: twice the workgroups, two of them per CU
-#define NT_GS_CASE(RB_, K_, CF_)                                                     \
-  if (small == (RB_ == 1) && K == K_ && c_f32 == CF_) return gs_launch<RB_, K_, CF_>(A, A_lo, lda, M, Wp, N, e, s);
+  const bool small = M <= 8192;  // 32-row tiles: twice the workgroups
+#define NT_GS_CASE(RB_, K_, CF_)                                 \
+  if (small == (RB_ == 1) && K == K_ && c_f32 == CF_) return gs_launch<RB_, K_, CF_, LN>(A, A_lo, lda, M, Wp, N, e, ln, s);
   NT_GS_CASE(1, 512, true) NT_GS_CASE(1, 512, false) NT_GS_CASE(2, 512, true) NT_GS_CASE(2, 512, false)
   NT_GS_CASE(1, 256, true) NT_GS_CASE(1, 256, false) NT_GS_CASE(2, 256, true) NT_GS_CASE(2, 256, false)
 #undef NT_GS_CASE
   return hipErrorInvalidValue;
+}
+
+hipError_t launch_gemm_stream(bool c_f32, const _Float16 *A, const _Float16 *A_lo, long lda, const _Float16 *Wp, int M,
+                              int N, int K, const GemmEpilogue &e, hipStream_t s) {
+  return gs_dispatch<false>(c_f32, A, A_lo, lda, Wp, M, N, K, e, GemmLayerNorm{}, s);
+}
+
+hipError_t launch_gemm_stream_ln(bool c_f32, const float *X, long ldx, const GemmLayerNorm &ln, const _Float16 *Wp, int M,
+                                 int N, int K, const GemmEpilogue &e, hipStream_t s) {
+  return gs_dispatch<true>(c_f32, (const _Float16 *)X, nullptr, ldx, Wp, M, N, K, e, ln, s);
 }
 
 }  // namespace nt

@@ -158,6 +158,7 @@ struct nt_model {
   float *ps = nullptr, *lo_norm = nullptr;             // certified arg-max: runner-up partials, tail norms
   int32_t *tok = nullptr, *slot_of_row = nullptr, *cert_list = nullptr;
   unsigned long long *final_key = nullptr, *need_mask = nullptr;
+  bool enc_out_valid = false;  // false while the encoder output lives only inside the fused cross projections
   float w_norm_max = 0.f;                              // max_v ||W_out[v,:]||
   int32_t *len = nullptr, *flags = nullptr;
   int32_t *d_src = nullptr, *d_len_in = nullptr, *d_out = nullptr;  // staging for nt_translate_batch
@@ -595,13 +596,21 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
   const int ln_mode = kEncF32 ? nt::OUT_PLANES : nt::OUT_F16;
   const long lo_d = (long)m->max_tokens * d, lo_F = (long)m->max_tokens * std::max(F, 1);  // tail plane offsets
   auto lo_of = [&](void *p, long off) -> const void * { return kEncF32 ? (const void *)((_Float16 *)p + off) : nullptr; };
+  // With plane pairs and a supported width the LayerNorm runs inside the projection that consumes it (the tile is
+  // normalised while it is loaded), otherwise as a kernel of its own.
+  auto fused_ln = [&](const _Float16 *Wp, int N) { return kEncF32 && Wp != nullptr && nt::gemm_stream_supported(N, d); };
   for (auto &L : m->enc) {
-    KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
-       nt::launch_layer_norm(m->x, M, d, L.ln1.g, L.ln1.b, c.ln_eps, m->a_enc, ln_mode, lo_d, s));
     nt::GemmEpilogue e;
     e.bias = L.self.bqkv; e.scale = qscale; e.scale_cols = d; e.dst0 = m->qkv; e.ld0 = 3 * d; e.n_split = 3 * d;
-    KT(K_GEMM_ENC_QKV, gemm_bytes(Md, dd, 3 * dd, ea, ea, false), 6 * Md * dd * dd,
-       nt::launch_gemm(amode, kEncF32, m->a_enc, lo_of(m->a_enc, lo_d), d, L.self.Wqkv, M, 3 * d, d, e, s, L.self.Wqkv_p));
+    if (fused_ln(L.self.Wqkv_p, 3 * d)) {
+      KT(K_GEMM_ENC_QKV, gemm_bytes(Md, dd, 3 * dd, 4, ea, false), 6 * Md * dd * dd,
+         nt::launch_gemm_stream_ln(true, m->x, d, nt::GemmLayerNorm{L.ln1.g, L.ln1.b, c.ln_eps}, L.self.Wqkv_p, M, 3 * d, d, e, s));
+    } else {
+      KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
+         nt::launch_layer_norm(m->x, M, d, L.ln1.g, L.ln1.b, c.ln_eps, m->a_enc, ln_mode, lo_d, s));
+      KT(K_GEMM_ENC_QKV, gemm_bytes(Md, dd, 3 * dd, ea, ea, false), 6 * Md * dd * dd,
+         nt::launch_gemm(amode, kEncF32, m->a_enc, lo_of(m->a_enc, lo_d), d, L.self.Wqkv, M, 3 * d, d, e, s, L.self.Wqkv_p));
+    }
     KT(K_ATTN_ENC, Md * 4 * dd * ea, 4.0 * B * S * S * dd,
        nt::launch_enc_attention(m->qkv, kEncF32, m->len, m->ctx_enc, lo_d, B, S, d, H, L.self.rk, c.rpr_clip, s));
     nt::GemmEpilogue o;
@@ -609,26 +618,42 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
     KT(K_GEMM_ENC_O, gemm_bytes(Md, dd, dd, ea, 4, true), 2 * Md * dd * dd,
        nt::launch_gemm(amode, true, m->ctx_enc, lo_of(m->ctx_enc, lo_d), d, L.self.Wo, M, d, d, o, s, L.self.Wo_p));
     if (F > 0) {
-      KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
-         nt::launch_layer_norm(m->x, M, d, L.ln2.g, L.ln2.b, c.ln_eps, m->a_enc, ln_mode, lo_d, s));
       nt::GemmEpilogue f1;
       f1.bias = L.ffn.b1; f1.relu = 1; f1.dst0 = m->u_enc; f1.ld0 = F; f1.n_split = F;
       f1.dst_lo_offset = kEncF32 ? lo_F : 0;
-      KT(K_GEMM_ENC_FFN, gemm_bytes(Md, dd, F, ea, ea, false), 2 * Md * dd * F,
-         nt::launch_gemm(amode, false, m->a_enc, lo_of(m->a_enc, lo_d), d, L.ffn.W1, M, F, d, f1, s, L.ffn.W1_p));
+      if (fused_ln(L.ffn.W1_p, F)) {
+        KT(K_GEMM_ENC_FFN, gemm_bytes(Md, dd, F, 4, ea, false), 2 * Md * dd * F,
+           nt::launch_gemm_stream_ln(false, m->x, d, nt::GemmLayerNorm{L.ln2.g, L.ln2.b, c.ln_eps}, L.ffn.W1_p, M, F, d, f1, s));
+      } else {
+        KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
+           nt::launch_layer_norm(m->x, M, d, L.ln2.g, L.ln2.b, c.ln_eps, m->a_enc, ln_mode, lo_d, s));
+        KT(K_GEMM_ENC_FFN, gemm_bytes(Md, dd, F, ea, ea, false), 2 * Md * dd * F,
+           nt::launch_gemm(amode, false, m->a_enc, lo_of(m->a_enc, lo_d), d, L.ffn.W1, M, F, d, f1, s, L.ffn.W1_p));
+      }
       nt::GemmEpilogue f2;
       f2.bias = L.ffn.b2; f2.resid = m->x; f2.ldr = d; f2.dst0 = m->x; f2.ld0 = d; f2.n_split = d;
       KT(K_GEMM_ENC_FFN, gemm_bytes(Md, F, dd, ea, 4, true), 2 * Md * dd * F,
          nt::launch_gemm(amode, true, m->u_enc, lo_of(m->u_enc, lo_F), F, L.ffn.W2, M, d, F, f2, s));
     }
   }
-  KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
-     nt::launch_layer_norm(m->x, M, d, m->enc_final.g, m->enc_final.b, c.ln_eps, m->enc_out, ln_mode, lo_d, s));
+  // The encoder output exists only inside the cross K|V projections when its LayerNorm is fused there; the debug
+  // readback then computes it on demand.
+  bool all_fused = c.n_dec > 0;
+  for (int l = 0; l < c.n_dec; l++) all_fused = all_fused && fused_ln(m->dec[l].cross.Wkv_p, 2 * d) && !kCrossF32;
+  m->enc_out_valid = !all_fused;
+  if (!all_fused)
+    KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
+       nt::launch_layer_norm(m->x, M, d, m->enc_final.g, m->enc_final.b, c.ln_eps, m->enc_out, ln_mode, lo_d, s));
   for (int l = 0; l < c.n_dec; l++) {
     nt::GemmEpilogue e;
     e.bias = m->dec[l].cross.bkv; e.dst0 = m->cross[l]; e.ld0 = 2 * d; e.n_split = 2 * d;
-    KT(K_GEMM_CROSS_KV, gemm_bytes(Md, dd, 2 * dd, ea, ca, false), 4 * Md * dd * dd,
-       nt::launch_gemm(amode, kCrossF32, m->enc_out, lo_of(m->enc_out, lo_d), d, m->dec[l].cross.Wkv, M, 2 * d, d, e, s, m->dec[l].cross.Wkv_p));
+    if (all_fused)
+      KT(K_GEMM_CROSS_KV, gemm_bytes(Md, dd, 2 * dd, 4, ca, false), 4 * Md * dd * dd,
+         nt::launch_gemm_stream_ln(false, m->x, d, nt::GemmLayerNorm{m->enc_final.g, m->enc_final.b, c.ln_eps},
+                                   m->dec[l].cross.Wkv_p, M, 2 * d, d, e, s));
+    else
+      KT(K_GEMM_CROSS_KV, gemm_bytes(Md, dd, 2 * dd, ea, ca, false), 4 * Md * dd * dd,
+         nt::launch_gemm(amode, kCrossF32, m->enc_out, lo_of(m->enc_out, lo_d), d, m->dec[l].cross.Wkv, M, 2 * d, d, e, s, m->dec[l].cross.Wkv_p));
   }
   m->len_prefix.clear();
   m->B = B; m->S = S; m->encoded = true;
@@ -699,13 +724,15 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
         return NT_OK;
       }
       const bool planes = streams(N, K, Wp, ln != nullptr);
+      if (ln && planes) {  // the LayerNorm runs inside the projection, while the tile is loaded
+        KT(id, by, fl, nt::launch_gemm_stream_ln(true, A, K, nt::GemmLayerNorm{ln->g, ln->b, c.ln_eps}, Wp, R, N, K, e, s));
+        return NT_OK;
+      }
       if (ln) {
-        KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd,
-           nt::launch_layer_norm(A, R, K, ln->g, ln->b, c.ln_eps, m->a32, planes ? nt::OUT_PLANES : nt::OUT_F32,
-                                 lo_rows * K, s));
+        KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd, nt::launch_layer_norm(A, R, K, ln->g, ln->b, c.ln_eps, m->a32, nt::OUT_F32, 0, s));
         A = m->a32;
       }
-      if (planes)  // A is a plane pair: written by the LayerNorm above or by the attention kernel
+      if (planes)  // A is a plane pair written by the attention kernel
         KT(id, by, fl, nt::launch_gemm(nt::A_PLANES, true, A, (const _Float16 *)A + lo_rows * K, K, Wt, R, N, K, e, s, Wp));
       else
         KT(id, by, fl, nt::launch_gemm(nt::A_F32, true, A, nullptr, K, Wt, R, N, K, e, s));
@@ -814,6 +841,12 @@ int nt_debug_encoder_out(nt_model *m, float *d_out, void *hip_stream) {
   if (!m || !d_out) return fail(NT_EINVAL, "null argument");
   if (!m->encoded) return fail(NT_ESTATE, "no encoded batch");
   const long n = (long)m->B * m->S * m->c.d_model;
+  if (!m->enc_out_valid) {  // the final LayerNorm ran fused into the cross projections: produce its output now
+    HIP_TRY(nt::launch_layer_norm(m->x, m->B * m->S, m->c.d_model, m->enc_final.g, m->enc_final.b, m->c.ln_eps, m->enc_out,
+                                  kEncF32 ? nt::OUT_PLANES : nt::OUT_F16, (long)m->max_tokens * m->c.d_model,
+                                  as_stream(hip_stream)));
+    m->enc_out_valid = true;
+  }
   if (kEncF32)
     HIP_TRY(nt::launch_planes_to_float((const _Float16 *)m->enc_out, (const _Float16 *)m->enc_out + m->max_tokens * m->c.d_model,
                                        d_out, n, as_stream(hip_stream)));

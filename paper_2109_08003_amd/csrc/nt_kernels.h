@@ -39,7 +39,14 @@ hipError_t launch_gemm(int a_mode, bool c_f32, const void *A, const void *A_lo, 
 
 // Streaming form for K = 256 / 512 and N % 64 == 0 (nt_gemm_stream.hip): the A tile (head/tail planes) stays in
 // the LDS, the weights stream through registers in fragment order.
+struct GemmLayerNorm {
+  const float *gamma = nullptr, *beta = nullptr;
+  float eps = 0.f;
+};
 bool gemm_stream_supported(int N, int K);
+// C = LayerNorm(X) * Wt^T: X [M][ldx] fp32 is normalised and split into planes while the tile is loaded
+hipError_t launch_gemm_stream_ln(bool c_f32, const float *X, long ldx, const GemmLayerNorm &ln, const _Float16 *Wp, int M,
+                                 int N, int K, const GemmEpilogue &e, hipStream_t s);
 hipError_t launch_gemm_stream(bool c_f32, const _Float16 *A, const _Float16 *A_lo, long lda, const _Float16 *Wp, int M,
                               int N, int K, const GemmEpilogue &e, hipStream_t s);
 
