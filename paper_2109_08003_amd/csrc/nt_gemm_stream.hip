@@ -19,6 +19,8 @@
 // lane = n % 32 + 32 * ((k % 16) / 8).
 #include "nt_kernels.h"
 
+#include <mutex>
+
 namespace nt {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -254,12 +256,13 @@ static hipError_t gs_launch(const _Float16 *A, const _Float16 *A_lo, long lda, i
                             const GemmEpilogue &e, const GemmLayerNorm &ln, hipStream_t s) {
   auto kern = gemm_stream_kernel<RB, K, C_F32, LN>;
   const size_t lds = (size_t)64 * RB * (K + 8) * 2;
-  static bool attr_set = false;  // raising the dynamic LDS limit is per kernel, once per process
-  if (!attr_set) {
-    hipError_t err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (err != hipSuccess) return err;
-    attr_set = true;
-  }
+  // raising the dynamic LDS limit is per kernel, once per process (several host threads may get here at once)
+  static std::once_flag once;
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(once, [&] {
+    attr_err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  });
+  if (attr_err != hipSuccess) return attr_err;
   const int row_tiles = (M + 32 * RB - 1) / (32 * RB), NS = N / 64;
   // enough workgroups for the chip: split the strips of a row tile over several workgroups as long as every wave
   // of a workgroup still gets a strip and the grid stays within a few rounds

@@ -162,7 +162,18 @@ struct nt_model {
   float w_norm_max = 0.f;                              // max_v ||W_out[v,:]||
   int32_t *len = nullptr, *flags = nullptr;
   int32_t *d_src = nullptr, *d_len_in = nullptr, *d_out = nullptr;  // staging for nt_translate_batch
-  int32_t *h_src = nullptr, *h_len = nullptr, *h_out = nullptr;     // pinned
+  // Host side of a batch in flight: pinned staging, its completion event and which sentences it holds.  Two per
+  // lane, so that the next batch of a lane is queued behind the running one instead of after it.
+  struct Staging {
+    int32_t *h_src = nullptr, *h_len = nullptr, *h_out = nullptr;  // pinned
+    hipEvent_t done = nullptr;
+    bool busy = false;
+    int64_t i0 = 0, i1 = 0;
+    int32_t T = 0;
+    std::vector<int32_t> steps;
+  };
+  static constexpr int kStagings = 2;
+  Staging stage[kStagings];
   // state left by nt_encode
   int32_t B = 0, S = 0;
   bool encoded = false;
@@ -172,11 +183,7 @@ struct nt_model {
   bool owns_weights = true;
   std::vector<nt_model *> lanes;      // extra lanes (this model is lane 0)
   hipStream_t lane_stream = nullptr;  // internal stream of this lane
-  hipEvent_t lane_done = nullptr, lane_start = nullptr;
-  bool lane_busy = false;
-  int64_t pend_i0 = 0, pend_i1 = 0;   // sentences of the batch in flight on this lane
-  int32_t pend_T = 0;
-  std::vector<int32_t> pend_steps;
+  hipEvent_t lane_start = nullptr;
 };
 
 namespace {
@@ -297,11 +304,13 @@ int alloc_lane_state(nt_model *m, hipStream_t s) {
   m->flags = at<int32_t>(A, o_flags); m->d_src = at<int32_t>(A, o_src); m->d_len_in = at<int32_t>(A, o_lin);
   m->d_out = at<int32_t>(A, o_out);
   HIP_TRY(nt::launch_fill_i32(m->flags, 16, 0, s));
-  if (hipHostMalloc((void **)&m->h_src, (size_t)Mt * 4) != hipSuccess || hipHostMalloc((void **)&m->h_len, (size_t)Br * 4) != hipSuccess ||
-      hipHostMalloc((void **)&m->h_out, (size_t)m->self_positions * 4) != hipSuccess)
-    return fail(NT_ENOMEM, "pinned staging allocation failed");
+  for (auto &st : m->stage) {
+    if (hipHostMalloc((void **)&st.h_src, (size_t)Mt * 4) != hipSuccess || hipHostMalloc((void **)&st.h_len, (size_t)Br * 4) != hipSuccess ||
+        hipHostMalloc((void **)&st.h_out, (size_t)m->self_positions * 4) != hipSuccess)
+      return fail(NT_ENOMEM, "pinned staging allocation failed");
+    if (hipEventCreateWithFlags(&st.done, hipEventDisableTiming) != hipSuccess) return fail(NT_EHIP, "event creation failed");
+  }
   if (hipStreamCreateWithFlags(&m->lane_stream, hipStreamNonBlocking) != hipSuccess ||
-      hipEventCreateWithFlags(&m->lane_done, hipEventDisableTiming) != hipSuccess ||
       hipEventCreateWithFlags(&m->lane_start, hipEventDisableTiming) != hipSuccess)
     return fail(NT_EHIP, "stream / event creation failed");
   return NT_OK;
@@ -340,13 +349,15 @@ void nt_free(nt_model *m) {
   if (!m) return;
   for (nt_model *ln : m->lanes) nt_free(ln);
   if (m->lane_stream) (void)hipStreamDestroy(m->lane_stream);
-  if (m->lane_done) (void)hipEventDestroy(m->lane_done);
   if (m->lane_start) (void)hipEventDestroy(m->lane_start);
   if (m->d_w && m->owns_weights) (void)hipFree(m->d_w);
   if (m->d_arena) (void)hipFree(m->d_arena);
-  if (m->h_src) (void)hipHostFree(m->h_src);
-  if (m->h_len) (void)hipHostFree(m->h_len);
-  if (m->h_out) (void)hipHostFree(m->h_out);
+  for (auto &st : m->stage) {
+    if (st.done) (void)hipEventDestroy(st.done);
+    if (st.h_src) (void)hipHostFree(st.h_src);
+    if (st.h_len) (void)hipHostFree(st.h_len);
+    if (st.h_out) (void)hipHostFree(st.h_out);
+  }
   for (hipEvent_t e : m->timing.pool) (void)hipEventDestroy(e);
   delete m;
 }
@@ -555,8 +566,9 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
       ln->owns_weights = false;
       ln->lanes.clear();
       ln->timing = Timing();
-      ln->d_arena = nullptr; ln->h_src = ln->h_len = ln->h_out = nullptr;
-      ln->lane_stream = nullptr; ln->lane_done = ln->lane_start = nullptr;
+      ln->d_arena = nullptr;
+      for (auto &st : ln->stage) st = nt_model::Staging();
+      ln->lane_stream = nullptr; ln->lane_start = nullptr;
       ln->cross.clear(); ln->self_kv.clear();
       m->lanes.push_back(ln);
       rc = alloc_lane_state(ln, s);
@@ -964,67 +976,74 @@ int nt_translate_batch(nt_model *m, const int32_t *h_tokens, const int64_t *h_of
   int rc = nt_plan_batches(lens.data(), N, budget, (int32_t)std::min<int64_t>(rows_cap, INT32_MAX), order.data(), starts.data(), &nb);
   if (rc) return rc;
   hipStream_t s = as_stream(hip_stream);
-  // lanes: batch k runs on lane k mod n on that lane's own stream; the host packs the next batch and
-  // unpacks finished ones while the device works
+  // lanes: batch k runs on lane k mod n on that lane's own stream.  Each lane has two sets of host staging, so its
+  // next batch is already queued while the current one runs; the host packs batches and unpacks finished ones while
+  // the device works.
   std::vector<nt_model *> lane{m};
   for (nt_model *ln : m->lanes) lane.push_back(ln);
   HIP_TRY(hipEventRecord(m->lane_start, s));  // work already queued on the caller's stream comes first
   for (nt_model *ln : lane) {
     HIP_TRY(hipStreamWaitEvent(ln->lane_stream, m->lane_start, 0));
-    ln->lane_busy = false;
+    for (auto &st : ln->stage) st.busy = false;
     ln->timing.mask = m->timing.mask;
   }
-  auto collect = [&](nt_model *ln) -> int {  // wait for the lane's batch and scatter its rows
-    if (!ln->lane_busy) return NT_OK;
-    HIP_TRY(hipEventSynchronize(ln->lane_done));
-    for (int64_t r = 0; r < ln->pend_i1 - ln->pend_i0; r++) {
-      const int64_t si = order[(size_t)(ln->pend_i0 + r)];
-      memcpy(h_out + h_out_offsets[si], ln->h_out + (size_t)r * ln->pend_T, (size_t)ln->pend_steps[(size_t)r] * 4);
+  auto collect = [&](nt_model::Staging &st) -> int {  // wait for the batch of this staging set and scatter its rows
+    if (!st.busy) return NT_OK;
+    HIP_TRY(hipEventSynchronize(st.done));
+    for (int64_t r = 0; r < st.i1 - st.i0; r++) {
+      const int64_t si = order[(size_t)(st.i0 + r)];
+      memcpy(h_out + h_out_offsets[si], st.h_out + (size_t)r * st.T, (size_t)st.steps[(size_t)r] * 4);
     }
-    ln->lane_busy = false;
+    st.busy = false;
     return NT_OK;
   };
   int first_err = NT_OK;
+  const int64_t n_lanes = (int64_t)lane.size();
   for (int64_t k = 0; k < nb && first_err == NT_OK; k++) {
-    nt_model *ln = lane[(size_t)(k % (int64_t)lane.size())];
-    if ((first_err = collect(ln))) break;
+    nt_model *ln = lane[(size_t)(k % n_lanes)];
+    nt_model::Staging &st = ln->stage[(k / n_lanes) % nt_model::kStagings];
+    if ((first_err = collect(st))) break;
     const int64_t i0 = starts[(size_t)k], i1 = starts[(size_t)k + 1];
     const int32_t B = (int32_t)(i1 - i0), S = lens[(size_t)order[(size_t)i0]], T = nt_n_steps(S);
     if ((int64_t)B * T > ln->self_positions) { first_err = fail(NT_ENOMEM, "batch of %d rows x %d steps exceeds the self-attention cache", B, T); break; }
-    ln->pend_steps.resize((size_t)B);
+    st.steps.resize((size_t)B);
     for (int32_t r = 0; r < B; r++) {
       const int64_t si = order[(size_t)(i0 + r)];
       const int32_t L = lens[(size_t)si];
-      ln->h_len[r] = L;
-      ln->pend_steps[(size_t)r] = nt_n_steps(L);
-      int32_t *row = ln->h_src + (size_t)r * S;
+      st.h_len[r] = L;
+      st.steps[(size_t)r] = nt_n_steps(L);
+      int32_t *row = st.h_src + (size_t)r * S;
       memcpy(row, h_tokens + h_offsets[si], (size_t)L * 4);
       for (int32_t j = L; j < S; j++) row[j] = c.pad_id;
     }
     hipStream_t ls = ln->lane_stream;
-    if (hipMemcpyAsync(ln->d_src, ln->h_src, (size_t)B * S * 4, hipMemcpyHostToDevice, ls) != hipSuccess ||
-        hipMemcpyAsync(ln->d_len_in, ln->h_len, (size_t)B * 4, hipMemcpyHostToDevice, ls) != hipSuccess) {
+    if (hipMemcpyAsync(ln->d_src, st.h_src, (size_t)B * S * 4, hipMemcpyHostToDevice, ls) != hipSuccess ||
+        hipMemcpyAsync(ln->d_len_in, st.h_len, (size_t)B * 4, hipMemcpyHostToDevice, ls) != hipSuccess) {
       first_err = fail(NT_EHIP, "host-to-device copy failed");
       break;
     }
     if ((first_err = nt_encode(ln, ln->d_src, ln->d_len_in, B, S, ls))) break;
     if (ln->timing.mask) {
       ln->len_prefix.assign((size_t)B + 1, 0);
-      for (int32_t r = 0; r < B; r++) ln->len_prefix[(size_t)r + 1] = ln->len_prefix[(size_t)r] + ln->h_len[r];
+      for (int32_t r = 0; r < B; r++) ln->len_prefix[(size_t)r + 1] = ln->len_prefix[(size_t)r] + st.h_len[r];
     }
-    if ((first_err = nt_decode_greedy(ln, B, T, ln->pend_steps.data(), ln->d_out, ls))) break;
-    if (hipMemcpyAsync(ln->h_out, ln->d_out, (size_t)B * T * 4, hipMemcpyDeviceToHost, ls) != hipSuccess ||
-        hipEventRecord(ln->lane_done, ls) != hipSuccess) {
+    if ((first_err = nt_decode_greedy(ln, B, T, st.steps.data(), ln->d_out, ls))) break;
+    if (hipMemcpyAsync(st.h_out, ln->d_out, (size_t)B * T * 4, hipMemcpyDeviceToHost, ls) != hipSuccess ||
+        hipEventRecord(st.done, ls) != hipSuccess) {
       first_err = fail(NT_EHIP, "device-to-host copy failed");
       break;
     }
-    ln->pend_i0 = i0; ln->pend_i1 = i1; ln->pend_T = T; ln->lane_busy = true;
+    st.i0 = i0; st.i1 = i1; st.T = T; st.busy = true;
   }
-  // drain every lane (also after an error: nothing may still be running when the call returns)
+  // drain every lane (also after an error: nothing may still be running when the call returns); a lane's batches
+  // finish in the order they were queued
   for (nt_model *ln : lane) {
-    if (first_err == NT_OK) first_err = collect(ln);
+    int older = 0;
+    if (ln->stage[0].busy && ln->stage[1].busy && ln->stage[1].i0 < ln->stage[0].i0) older = 1;
+    for (int j = 0; j < nt_model::kStagings; j++)
+      if (first_err == NT_OK) first_err = collect(ln->stage[(older + j) % nt_model::kStagings]);
     (void)hipStreamSynchronize(ln->lane_stream);
-    ln->lane_busy = false;
+    for (auto &st : ln->stage) st.busy = false;
   }
   if (first_err) return first_err;
   return NT_OK;

@@ -26,6 +26,7 @@
 // lane = v % 32 + 32 * ((k % 16) / 8): lane l of the MFMA row operand holds W[v = l % 32][k = 8 * (l / 32) .. + 7].
 #include "nt_kernels.h"
 
+#include <mutex>
 #include <type_traits>
 
 namespace nt {
@@ -345,12 +346,13 @@ static hipError_t vs_launch(const _Float16 *h, const _Float16 *h_lo, long ldh, c
                             unsigned long long *final_key, const unsigned long long *need_mask, int mask_ranges,
                             hipStream_t s) {
   auto kern = vocab_stream_kernel<EXACT, K, GATHER>;
-  static bool attr_set = false;  // raising the dynamic LDS limit is per kernel, once per process
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vs_lds_bytes(K));
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // raising the dynamic LDS limit is per kernel, once per process (several host threads may get here at once)
+  static std::once_flag once;
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(once, [&] {
+    attr_err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vs_lds_bytes(K));
+  });
+  if (attr_err != hipSuccess) return attr_err;
   hipLaunchKernelGGL(kern, dim3(8 * p.per_xcd), dim3(VS_WAVES * 64), vs_lds_bytes(K), s, h, h_lo, ldh, row_map, count, M, Wp,
                      N, p.m_tiles, p.G, p.per_xcd, pk, ps, final_key, need_mask, mask_ranges);
   return hipGetLastError();
