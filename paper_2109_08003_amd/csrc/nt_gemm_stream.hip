@@ -51,9 +51,9 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   constexpr int TM = 32 * RB, ROWS = 2 * TM;  // LDS fragment rows: head rows, then tail rows
   constexpr int LD = K + 8;                   // halfs per LDS row: the 16 B pad keeps the fragment reads conflict-free
   constexpr int KS = K / 16;
-  // register slots of W fragments per wave; the lookahead is SL - 1 k-steps.  With 32-row tiles a k-step is only
-  // four MFMAs, so the ring is deeper to cover the same memory latency.
-  constexpr int SL = RB == 1 ? 16 : 8;
+  // register slots of W fragments per wave; the lookahead is SL - 1 k-steps.  (A deeper ring did not shorten the
+  // decoder-sized launches, and fewer registers leave room for other kernels' waves on the same CU.)
+  constexpr int SL = 8;
   constexpr int NOPS = 2 * RB;
   static_assert(KS % SL == 0, "the ring of W slots must divide the k-steps of a strip");
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, g = lane >> 5;

@@ -555,6 +555,8 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
       mx = std::max(mx, q);
     }
     m->w_norm_max = (float)(std::sqrt(mx) * 1.0001);
+    const char *f = getenv("NT_CERT_DISTRUST");  // testing aid: certify nothing, so every row takes the recompute pass
+    if (f && f[0] == '1') m->w_norm_max = 1e30f;
   }
 
   rc = alloc_lane_state(m, s);

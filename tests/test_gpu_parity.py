@@ -253,6 +253,21 @@ def test_tiled_argmax_kernels_agree_with_streaming_kernels(nt, monkeypatch):
     assert same >= 1014   # summation order differs, so an exact tie of fp32 logits may fall the other way
 
 
+def test_certified_argmax_equals_full_recompute(nt, monkeypatch):
+    """The single-pass arg-max certifies a row only if the head-only winner provably wins the head+tail logits
+    too, so its tokens must be exactly those of recomputing every row with both planes.  NT_CERT_DISTRUST=1
+    makes the bound infinite: every row of every step with >= 512 active rows goes through the gathered
+    recompute kernel (thousands of rows: several list chunks and several tiles per workgroup)."""
+    cfg = nt_synth.model_config("C1")
+    blob = nt_synth.make_weights(cfg, seed=0)
+    tokens, offsets = nt_synth.workload("C2", 6000)
+    ref, ro = nt.Model(cfg, blob, max_batch_tokens=65536).translate_batch(tokens, offsets, token_budget=65536)
+    monkeypatch.setenv("NT_CERT_DISTRUST", "1")
+    out, oo = nt.Model(cfg, blob, max_batch_tokens=65536).translate_batch(tokens, offsets, token_budget=65536)
+    assert np.array_equal(ro, oo)
+    assert np.array_equal(ref, out)
+
+
 # ------------------------------------------------------------------------------ restored components (C3) and teacher shape (C4)
 def _check_workload_sample(nt, oracle, name, n_sent, budget, tol_frac, **overrides):
     cfg = nt_synth.model_config(name, **overrides)
