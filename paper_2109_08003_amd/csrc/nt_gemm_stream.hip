@@ -156,6 +156,10 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's rows have landed in the LDS before the barrier
   __syncthreads();
   if (!have) return;
+  // Two waves share a SIMD.  With equal priority they take turns at the matrix pipe, finish their strips together
+  // and then both sit in the store phase of the epilogue (the long one when the output is fp32) while the pipe
+  // idles.  Giving one of them priority makes the phases alternate instead.
+  if (wave < GS_WAVES / 2) __builtin_amdgcn_s_setprio(2);
 
   floatx16 acc[RB][2];
   // fragment row of operand op: head rows of block op % RB, then the tail rows; two base registers, because the
