@@ -925,8 +925,24 @@ int nt_plan_batches(const int32_t *h_lengths, int64_t N, int64_t budget, int32_t
   if (max_rows < 0) return fail(NT_EINVAL, "max_rows must be >= 0");
   for (int64_t i = 0; i < N; i++)
     if (h_lengths[i] < 0) return fail(NT_EINVAL, "negative length at %lld", (long long)i);
-  std::iota(order, order + N, (int64_t)0);
-  std::stable_sort(order, order + N, [&](int64_t a, int64_t b) { return h_lengths[a] > h_lengths[b]; });
+  // stable sort by descending length: a counting sort while the lengths are small (they are: sentences), else a
+  // comparison sort
+  int32_t longest_all = 0;
+  for (int64_t i = 0; i < N; i++) longest_all = std::max(longest_all, h_lengths[i]);
+  if (longest_all <= (1 << 20)) {
+    std::vector<int64_t> first((size_t)longest_all + 2, 0);  // first[L] = position of the first sentence of length L
+    for (int64_t i = 0; i < N; i++) first[(size_t)h_lengths[i]]++;
+    int64_t at = 0;
+    for (int32_t L = longest_all; L >= 0; L--) {
+      const int64_t c = first[(size_t)L];
+      first[(size_t)L] = at;
+      at += c;
+    }
+    for (int64_t i = 0; i < N; i++) order[first[(size_t)h_lengths[i]]++] = i;
+  } else {
+    std::iota(order, order + N, (int64_t)0);
+    std::stable_sort(order, order + N, [&](int64_t a, int64_t b) { return h_lengths[a] > h_lengths[b]; });
+  }
   int64_t nb = 0, i = 0;
   batch_starts[0] = 0;
   while (i < N && h_lengths[order[i]] > 0) {
