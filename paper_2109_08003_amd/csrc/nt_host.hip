@@ -45,7 +45,7 @@ int fail(int code, const char *fmt, ...) {
 constexpr bool kEncF32 = true;
 constexpr bool kCrossF32 = false;
 // Decoder projections with at most this many active rows use the one-round-trip kernel.
-constexpr int kSkinnyMaxRows = 1024;
+constexpr int kSkinnyMaxRows = 128;
 // The output projection uses the certified single-pass arg-max from this many active rows on; below,
 // the step is bound by the weight stream and the two-plane kernel costs the same.
 constexpr int kCertMinRows = 512;
