@@ -405,12 +405,14 @@ hipError_t launch_vocab_argmax_certified(const _Float16 *h, const _Float16 *h_lo
   if (e != hipSuccess) return e;
   e = launch_argmax_select(pk, ps, p.G, M, lo_norm, w_norm_max, tok, slot_of_row, list, count, final_key, need_mask, s);
   if (e != hipSuccess) return e;
-  // recompute of the uncertified rows: their number is known on the device only, so each of 256 workgroups takes
-  // a range of the vocabulary and those gathered rows that still have a candidate there (often none)
+  // recompute of the uncertified rows: their number is known on the device only, so each of 64 workgroups takes
+  // a range of the vocabulary and those gathered rows that still have a candidate there (often none).  It is
+  // little work; a quarter of the chip is enough and leaves the rest to the kernels of the other pipeline lanes
+  // (measured best among 32 ... 256 workgroups).
   VsSplit q;
   q.m_tiles = 1;
-  q.G = 8 * VS_CUS_PER_XCD;
-  q.per_xcd = VS_CUS_PER_XCD;
+  q.G = 2 * VS_CUS_PER_XCD;
+  q.per_xcd = VS_CUS_PER_XCD / 4;
   return vs_launch_k<true, true>(h, h_lo, ldh, list, count, M, w, q, nullptr, nullptr, final_key, need_mask, p.G, s);
 }
 
