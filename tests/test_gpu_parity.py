@@ -157,6 +157,42 @@ def test_c0_translate_batch_order_and_determinism(c0, oracle, nt):
     assert bad <= 1
 
 
+def test_lanes_driven_by_the_caller_on_their_own_streams(torch_cuda, nt):
+    """Batches kept on the device and run through nt_encode / nt_decode_greedy on the lanes' own streams
+    (nt_lane_stream), several in flight at once, give the tokens of nt_translate_batch."""
+    torch = torch_cuda
+    cfg = nt_synth.model_config("C1")
+    blob = nt_synth.make_weights(cfg, seed=0)
+    tokens, offsets = nt_synth.workload("C1", 600)
+    lens = np.diff(offsets).astype(np.int32)
+    gm = nt.Model(cfg, blob, max_batch_tokens=2048, pipeline_lanes=3)
+    assert gm.n_lanes() == 3
+    lanes = [gm.lane(i) for i in range(3)]
+    streams = [ln.own_stream() for ln in lanes]
+    assert len({s.cuda_stream for s in streams}) == 3
+    ref, ro = gm.translate_batch(tokens, offsets, token_budget=2048)
+    order, starts = nt.plan_batches(lens, 2048)
+    jobs = []
+    for k in range(len(starts) - 1):
+        idx = order[starts[k]:starts[k + 1]]
+        ids, ln_ = pad([tokens[offsets[i]:offsets[i + 1]] for i in idx], cfg["pad_id"])
+        steps = np.array([nt.n_steps(int(l)) for l in ln_], dtype=np.int32)
+        d_out = torch.empty((len(idx), int(steps[0])), dtype=torch.int32, device="cuda")
+        lane, st = lanes[k % 3], streams[k % 3]
+        if k >= 3:
+            st.synchronize()              # a lane holds one batch at a time: its arena is reused
+        d_src, d_len = torch.from_numpy(ids).cuda(), torch.from_numpy(ln_).cuda()
+        torch.cuda.current_stream().synchronize()
+        lane.encode(d_src, d_len, stream=st)
+        lane.decode_greedy(len(idx), int(steps[0]), d_out, row_steps=steps, stream=st)
+        jobs.append((idx, steps, d_out, d_src, d_len))   # the inputs stay alive until the streams are done
+    torch.cuda.synchronize()
+    for idx, steps, d_out, _, _ in jobs:
+        got = d_out.cpu().numpy()
+        for r, i in enumerate(idx):
+            assert np.array_equal(got[r, : steps[r]], ref[ro[i]:ro[i + 1]])
+
+
 # ------------------------------------------------------------------------------ edge cases
 def test_edge_cases(c0, nt, oracle):
     cfg, blob, src, gm, om = c0
