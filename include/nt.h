@@ -203,9 +203,9 @@ int nt_debug_timing_read(nt_model *m, int kernel, double *total_ms, int64_t *lau
  * owned by m: never pass them to nt_free.  nt_translate_batch uses all lanes by itself.
  * nt_lane_stream returns the HIP stream (hipStream_t) that the library created for a lane and that
  * nt_translate_batch launches the lane's work on; it is owned by the model.  A caller that drives the
- * lanes itself may launch on these streams: they were created one after the other, which spreads them
- * over the hardware queues, whereas streams picked from another pool may share one queue and then do
- * not overlap.  Returns NULL for a null model.
+ * lanes itself may launch on these streams: nt_load_weights has checked with a short probe kernel that
+ * they run concurrently (streams that land on the same hardware queue do not overlap; there are four
+ * queues per process unless the runtime is told otherwise).  Returns NULL for a null model.
  */
 int nt_pipeline_lanes(const nt_model *m);
 nt_model *nt_pipeline_lane(nt_model *m, int i);
