@@ -19,8 +19,13 @@ stored in "math" orientation W[in][out] (y = x @ W + b), row-major:
     per decoder layer l = 0..n_dec-1:
         ln1.g ln1.b   self: Wq bq Wk bk Wv bv Wo bo   rk [2c+1, d_h] (if c > 0)
         ln2.g ln2.b   cross: Wq bq Wk bk Wv bv Wo bo
-        ln3.g ln3.b W1 b1 W2 b2                                  only if F > 0
+        ln3.g ln3.b W1 b1 W2 b2                                  only if F_dec > 0
     dec_final.g [d] dec_final.b [d]
+
+The decoder may have its own head count and FFN width (the paper's submitted students: a base
+encoder in front of a single-head decoder, Table 2): dec_n_heads = 0 means "as the encoder",
+dec_d_ffn = 0 means "as the encoder", -1 means no decoder FFN; d_h and F above are then the
+decoder's values in the decoder layers (dec_heads / dec_ffn below resolve them).
 
 Workload recipes (the synthetic stand-ins for the WMT21 efficiency-task input,
 which is not available here):
@@ -37,7 +42,7 @@ N_SPECIAL = 4
 
 _BASE = dict(n_enc=6, n_dec=1, d_model=512, n_heads=1, d_ffn=0, vocab=32000,
              max_len=256, rpr_clip=0, tie_output=0, bos_id=BOS_ID, pad_id=PAD_ID,
-             ln_eps=1e-5)
+             ln_eps=1e-5, dec_n_heads=0, dec_d_ffn=0)
 
 CONFIGS = {
     # tiny parity student
@@ -49,7 +54,19 @@ CONFIGS = {
     "C3": dict(_BASE, n_heads=8, d_ffn=2048),
     # deep teacher-shaped model with relative position keys
     "C4": dict(_BASE, n_enc=30, n_dec=6, n_heads=8, d_ffn=2048, rpr_clip=8),
+    # shape of the paper's fastest GPU submission (Student-3-1-512, Table 2 / Sec. 5): base encoder of 3
+    # layers (8 heads, FFN 2,048), one decoder layer with a single head and an FFN of 512, shared embedding
+    "C5": dict(_BASE, n_enc=3, n_heads=8, d_ffn=2048, dec_n_heads=1, dec_d_ffn=512, tie_output=1),
 }
+
+
+def dec_heads(cfg: dict) -> int:
+    return cfg.get("dec_n_heads", 0) or cfg["n_heads"]
+
+
+def dec_ffn(cfg: dict) -> int:
+    f = cfg.get("dec_d_ffn", 0)
+    return cfg["d_ffn"] if f == 0 else max(f, 0)
 
 
 def model_config(name: str, **overrides) -> dict:
@@ -62,11 +79,12 @@ def blob_layout(cfg: dict) -> list[tuple[str, tuple[int, ...]]]:
     """Ordered (name, shape) list of every tensor in the blob."""
     d, V, F = cfg["d_model"], cfg["vocab"], cfg["d_ffn"]
     c, dh = cfg["rpr_clip"], cfg["d_model"] // cfg["n_heads"]
+    Fd, dhd = dec_ffn(cfg), cfg["d_model"] // dec_heads(cfg)
     out: list[tuple[str, tuple[int, ...]]] = [("E", (V, d))]
     if not cfg["tie_output"]:
         out.append(("W_out", (V, d)))
 
-    def attn(prefix: str, rpr: bool):
+    def attn(prefix: str, rpr: bool, dh: int = dh):
         for w in ("q", "k", "v", "o"):
             out.append((f"{prefix}.W{w}", (d, d)))
             out.append((f"{prefix}.b{w}", (d,)))
@@ -77,7 +95,7 @@ def blob_layout(cfg: dict) -> list[tuple[str, tuple[int, ...]]]:
         out.append((f"{prefix}.g", (d,)))
         out.append((f"{prefix}.b", (d,)))
 
-    def ffn(prefix: str):
+    def ffn(prefix: str, F: int = F):
         out.append((f"{prefix}.W1", (d, F)))
         out.append((f"{prefix}.b1", (F,)))
         out.append((f"{prefix}.W2", (F, d)))
@@ -92,12 +110,12 @@ def blob_layout(cfg: dict) -> list[tuple[str, tuple[int, ...]]]:
     ln("enc_final")
     for l in range(cfg["n_dec"]):
         ln(f"dec{l}.ln1")
-        attn(f"dec{l}.self", True)
+        attn(f"dec{l}.self", True, dhd)
         ln(f"dec{l}.ln2")
-        attn(f"dec{l}.cross", False)
-        if F > 0:
+        attn(f"dec{l}.cross", False, dhd)
+        if Fd > 0:
             ln(f"dec{l}.ln3")
-            ffn(f"dec{l}.ffn")
+            ffn(f"dec{l}.ffn", Fd)
     ln("dec_final")
     return out
 
@@ -179,6 +197,7 @@ WORKLOADS = {
     "C2": ("lognormal_zipf", 200000, 2),
     "C3": ("lognormal_zipf", 16384, 3),
     "C4": ("lognormal_zipf", 2048, 4),
+    "C5": ("lognormal_zipf", 200000, 5),
 }
 
 

@@ -33,8 +33,15 @@
 
 typedef struct {
   int32_t n_enc, n_dec, d_model, n_heads, d_ffn, vocab, max_len, rpr_clip, tie_output, bos_id;
+  /* decoder shape where it differs from the encoder's (Table 2, Sec. 5: the submitted students put a base
+     encoder in front of a one-head decoder whose FFN is 512 wide or absent):
+     dec_n_heads 0 = n_heads;  dec_d_ffn 0 = d_ffn, -1 = no decoder FFN, else the width */
+  int32_t dec_n_heads, dec_d_ffn;
   double ln_eps;
 } ora_config;
+
+static int dec_heads(const ora_config *c) { return c->dec_n_heads > 0 ? c->dec_n_heads : c->n_heads; }
+static int dec_ffn(const ora_config *c) { return c->dec_d_ffn == 0 ? c->d_ffn : (c->dec_d_ffn < 0 ? 0 : c->dec_d_ffn); }
 
 typedef struct { const float *g, *b; } ln_t;
 typedef struct { const float *Wq, *bq, *Wk, *bk, *Wv, *bv, *Wo, *bo, *rk; } attn_t;
@@ -69,11 +76,14 @@ float ora_half_to_float(uint16_t h) {
 /* ---- closed-form parameter count of the blob (matrices, biases, LayerNorms) ---- */
 int64_t ora_param_count(const ora_config *c) {
   int64_t d = c->d_model, V = c->vocab, F = c->d_ffn, dh = d / c->n_heads;
+  int64_t Fd = dec_ffn(c), dhd = d / dec_heads(c);
   int64_t attn = 4 * (d * d + d), ln = 2 * d, ffn = F > 0 ? (2 * d * F + F + d + ln) : 0;
+  int64_t ffnd = Fd > 0 ? (2 * d * Fd + Fd + d + ln) : 0;
   int64_t rk = c->rpr_clip > 0 ? (2 * c->rpr_clip + 1) * dh : 0;
+  int64_t rkd = c->rpr_clip > 0 ? (2 * c->rpr_clip + 1) * dhd : 0;
   int64_t n = V * d * (c->tie_output ? 1 : 2);
   n += c->n_enc * (ln + attn + rk + ffn) + ln;
-  n += c->n_dec * (ln + attn + rk + ln + attn + ffn) + ln;
+  n += c->n_dec * (ln + attn + rkd + ln + attn + ffnd) + ln;
   return n;
 }
 
@@ -98,13 +108,15 @@ ora_model *ora_load(const ora_config *c, const uint16_t *blob, int64_t n_halfs) 
   if (!c || !blob) return NULL;
   if (c->d_model <= 0 || c->n_heads <= 0 || c->d_model % c->n_heads || c->vocab <= 0 ||
       c->n_enc < 0 || c->n_dec < 1 || c->d_ffn < 0 || c->rpr_clip < 0) return NULL;
+  if (c->dec_n_heads < 0 || c->d_model % dec_heads(c) || c->dec_d_ffn < -1) return NULL;
   if (n_halfs != ora_param_count(c)) return NULL;
   ora_model *m = (ora_model *)calloc(1, sizeof *m);
   m->c = *c;
   m->w = (float *)malloc(sizeof(float) * (size_t)n_halfs);
   for (int64_t i = 0; i < n_halfs; i++) m->w[i] = ora_half_to_float(blob[i]);
-  int64_t d = c->d_model, V = c->vocab, F = c->d_ffn;
+  int64_t d = c->d_model, V = c->vocab, F = c->d_ffn, Fd = dec_ffn(c);
   int64_t rk = c->rpr_clip > 0 ? (2 * c->rpr_clip + 1) * (d / c->n_heads) : 0;
+  int64_t rkd = c->rpr_clip > 0 ? (2 * c->rpr_clip + 1) * (d / dec_heads(c)) : 0;
   const float *p = m->w;
   m->E = take(&p, V * d);
   m->Wout = c->tie_output ? m->E : take(&p, V * d);
@@ -118,10 +130,10 @@ ora_model *ora_load(const ora_config *c, const uint16_t *blob, int64_t n_halfs) 
   take_ln(&p, d, &m->enc_final);
   for (int l = 0; l < c->n_dec; l++) {
     take_ln(&p, d, &m->dec[l].ln1);
-    take_attn(&p, d, rk, &m->dec[l].self);
+    take_attn(&p, d, rkd, &m->dec[l].self);
     take_ln(&p, d, &m->dec[l].ln2);
     take_attn(&p, d, 0, &m->dec[l].cross);
-    if (F > 0) { take_ln(&p, d, &m->dec[l].ln3); take_ffn(&p, d, F, &m->dec[l].ffn); }
+    if (Fd > 0) { take_ln(&p, d, &m->dec[l].ln3); take_ffn(&p, d, Fd, &m->dec[l].ffn); }
   }
   take_ln(&p, d, &m->dec_final);
   if (p - m->w != n_halfs) { free(m->enc); free(m->dec); free(m->w); free(m); return NULL; }
@@ -219,8 +231,8 @@ static void embed(const ora_model *m, int32_t id, int32_t pos, double *x) {
 }
 
 /* x += relu(LN(x) W1 + b1) W2 + b2 */
-static void ffn_block(const ora_model *m, const ln_t *ln, const ffn_t *f, double *x) {
-  int d = m->c.d_model, F = m->c.d_ffn;
+static void ffn_block(const ora_model *m, const ln_t *ln, const ffn_t *f, int F, double *x) {
+  int d = m->c.d_model;
   double *a = (double *)malloc(sizeof(double) * (size_t)(2 * d + F)), *u = a + d, *o = u + F;
   ora_layer_norm(x, ln->g, ln->b, d, m->c.ln_eps, a);
   ora_linear(a, f->W1, f->b1, d, F, u);
@@ -257,7 +269,7 @@ static int encode(const ora_model *m, const int32_t *src, int32_t len, double *e
       for (int e = 0; e < d; e++) x[(size_t)i * d + e] += o[e];
     }
     if (c->d_ffn > 0)
-      for (int i = 0; i < len; i++) ffn_block(m, &L->ln2, &L->ffn, x + (size_t)i * d);
+      for (int i = 0; i < len; i++) ffn_block(m, &L->ln2, &L->ffn, c->d_ffn, x + (size_t)i * d);
   }
   for (int i = 0; i < len; i++)
     ora_layer_norm(x + (size_t)i * d, m->enc_final.g, m->enc_final.b, d, c->ln_eps, enc + (size_t)i * d);
@@ -293,7 +305,7 @@ static void dec_end(dec_state *s) { free(s->ck); free(s->sk); free(s); }
 /* one incremental decoder step at position t with previous token y_prev -> logits[V] */
 static void dec_step(const ora_model *m, dec_state *s, int32_t y_prev, int32_t t, double *logits) {
   const ora_config *c = &m->c;
-  int d = c->d_model, H = c->n_heads, V = c->vocab;
+  int d = c->d_model, H = dec_heads(c), V = c->vocab;
   double qs = 1.0 / sqrt((double)(d / H));
   double *z = (double *)malloc(sizeof(double) * 5 * (size_t)d);
   double *a = z + d, *q = a + d, *ctx = q + d, *o = ctx + d;
@@ -318,7 +330,7 @@ static void dec_step(const ora_model *m, dec_state *s, int32_t y_prev, int32_t t
                NULL, 0, 0, ctx, NULL);
     ora_linear(ctx, L->cross.Wo, L->cross.bo, d, d, o);
     for (int e = 0; e < d; e++) z[e] += o[e];
-    if (c->d_ffn > 0) ffn_block(m, &L->ln3, &L->ffn, z);
+    if (dec_ffn(c) > 0) ffn_block(m, &L->ln3, &L->ffn, dec_ffn(c), z);
   }
   ora_layer_norm(z, m->dec_final.g, m->dec_final.b, d, c->ln_eps, a);
   /* output layer: plain logits, no bias, no log-softmax */

@@ -35,7 +35,8 @@ def build(force: bool = True) -> str:
 
 class _Cfg(C.Structure):
     _fields_ = [(k, C.c_int32) for k in ("n_enc", "n_dec", "d_model", "n_heads", "d_ffn", "vocab",
-                                         "max_len", "rpr_clip", "tie_output", "bos_id")] + [("ln_eps", C.c_double)]
+                                         "max_len", "rpr_clip", "tie_output", "bos_id",
+                                         "dec_n_heads", "dec_d_ffn")] + [("ln_eps", C.c_double)]
 
 
 _lib = None
@@ -83,7 +84,7 @@ def lib():
 def _cfg(cfg: dict) -> _Cfg:
     c = _Cfg()
     for k, _ in _Cfg._fields_:
-        setattr(c, k, cfg[k])
+        setattr(c, k, cfg.get(k, 0) if k.startswith("dec_") else cfg[k])
     return c
 
 

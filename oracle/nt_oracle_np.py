@@ -54,10 +54,10 @@ def masked_softmax(s, mask):
     return e / e.sum(-1, keepdims=True)
 
 
-def attention(W: Weights, prefix: str, xq, xkv, mask, rpr: bool):
-    """xq [B,Tq,d], xkv [B,Tk,d], mask [B,Tq,Tk] bool -> (context projected [B,Tq,d], probs)."""
+def attention(W: Weights, prefix: str, xq, xkv, mask, rpr: bool, H: int):
+    """xq [B,Tq,d], xkv [B,Tk,d], mask [B,Tq,Tk] bool, H heads -> (context projected [B,Tq,d], probs)."""
     cfg = W.cfg
-    d, H = cfg["d_model"], cfg["n_heads"]
+    d = cfg["d_model"]
     dh = d // H
     B, Tq, _ = xq.shape
     Tk = xkv.shape[1]
@@ -107,7 +107,7 @@ def encode(cfg: dict, blob: np.ndarray, src: list, extra_pad: int = 0):
     mask = np.broadcast_to(key_ok[:, None, :], (B, S, S))
     for l in range(cfg["n_enc"]):
         a = layer_norm(x, W[f"enc{l}.ln1.g"], W[f"enc{l}.ln1.b"], eps)
-        o, _ = attention(W, f"enc{l}.self", a, a, mask, True)
+        o, _ = attention(W, f"enc{l}.self", a, a, mask, True, cfg["n_heads"])
         x = x + o
         if cfg["d_ffn"] > 0:
             x = ffn(W, f"enc{l}.ln2", f"enc{l}.ffn", x)
@@ -125,14 +125,17 @@ def teacher_forced_logits(cfg: dict, blob: np.ndarray, src: list, tgt_in: list, 
     z = np.sqrt(d) * W["E"][tid] + positions(T, d)[None]
     causal = np.broadcast_to(np.tril(np.ones((T, T), dtype=bool))[None], (B, T, T))
     cross = np.broadcast_to((np.arange(S)[None, :] < lens[:, None])[:, None, :], (B, T, S))
+    # the decoder may have its own head count and FFN width (Table 2: 8-head encoder, 1-head decoder)
+    Hd = cfg.get("dec_n_heads", 0) or cfg["n_heads"]
+    Fd = {0: cfg["d_ffn"], -1: 0}.get(cfg.get("dec_d_ffn", 0), cfg.get("dec_d_ffn", 0))
     for l in range(cfg["n_dec"]):
         a = layer_norm(z, W[f"dec{l}.ln1.g"], W[f"dec{l}.ln1.b"], eps)
-        o, _ = attention(W, f"dec{l}.self", a, a, causal, True)
+        o, _ = attention(W, f"dec{l}.self", a, a, causal, True, Hd)
         z = z + o
         a = layer_norm(z, W[f"dec{l}.ln2.g"], W[f"dec{l}.ln2.b"], eps)
-        o, _ = attention(W, f"dec{l}.cross", a, enc, cross, False)
+        o, _ = attention(W, f"dec{l}.cross", a, enc, cross, False, Hd)
         z = z + o
-        if cfg["d_ffn"] > 0:
+        if Fd > 0:
             z = ffn(W, f"dec{l}.ln3", f"dec{l}.ffn", z)
     h = layer_norm(z, W["dec_final.g"], W["dec_final.b"], eps)
     Wout = W["E"] if cfg["tie_output"] else W["W_out"]

@@ -173,6 +173,10 @@ CASES = [
     dict(n_heads=4, d_ffn=48),                                       # ablation shape
     dict(n_heads=4, d_ffn=48, n_dec=2, rpr_clip=3),                  # teacher shape
     dict(n_heads=2, rpr_clip=2, tie_output=1),
+    # decoder shaped on its own (Table 2: multi-head encoder with FFN, one-head decoder, narrower or no FFN)
+    dict(n_heads=4, d_ffn=48, dec_n_heads=1, dec_d_ffn=24),
+    dict(n_heads=4, d_ffn=48, dec_n_heads=1, dec_d_ffn=-1, rpr_clip=2),
+    dict(n_heads=1, d_ffn=0, dec_n_heads=2, dec_d_ffn=16, rpr_clip=3),
 ]
 
 
@@ -194,6 +198,23 @@ def test_incremental_equals_full_recompute(oracle, kw):
         assert np.allclose(inc, full[i], atol=1e-9)
         # greedy picks the argmax of those logits, lowest id first
         assert np.array_equal(np.argmax(inc, -1), outs[i])
+
+
+def test_decoder_shape_of_its_own_is_not_the_encoder_shape(oracle):
+    """A decoder given its own head count and FFN width differs from the shared-shape model (so the
+    fields are read), and spelling the encoder's shape out for the decoder changes nothing."""
+    cfg = tiny(n_heads=4, d_ffn=48)
+    same = dict(cfg, dec_n_heads=4, dec_d_ffn=48)
+    blob = nt_synth.make_weights(cfg, seed=21, random_affine=True)
+    assert nt_synth.blob_numel(same) == nt_synth.blob_numel(cfg)
+    src, tgt = np.array([9, 8, 7, 6, 5]), np.array([1, 11, 12])
+    a = oracle.Model(cfg, blob).teacher_forced(src, tgt)
+    assert np.array_equal(a, oracle.Model(same, blob).teacher_forced(src, tgt))
+    one = dict(cfg, dec_n_heads=1)                     # same blob layout (no relative keys), other arithmetic
+    b = oracle.Model(one, blob).teacher_forced(src, tgt)
+    assert np.abs(a - b).max() > 1e-3
+    # the encoder half is untouched by the decoder's fields
+    assert np.array_equal(oracle.Model(cfg, blob).encode(src), oracle.Model(one, blob).encode(src))
 
 
 def test_padding_and_batch_mates_do_not_matter(oracle):
@@ -275,7 +296,7 @@ def test_n_steps_is_ceil_1p2_len_plus_2(oracle):
 
 
 def test_param_count_matches_layout_and_paper_tables(oracle):
-    for name in ("C0", "C1", "C3", "C4"):
+    for name in ("C0", "C1", "C3", "C4", "C5"):
         cfg = nt_synth.model_config(name)
         assert oracle.param_count(cfg) == nt_synth.blob_numel(cfg)
     # the paper's models: encoder keeps the vanilla FFN, Dim-FFN is the decoder's (Table 2 caption)
@@ -285,10 +306,15 @@ def test_param_count_matches_layout_and_paper_tables(oracle):
             continue
         name, ne, nd, d, fe, fd, printed = line.split()
         ne, nd, d, fe, fd, printed = int(ne), int(nd), int(d), int(fe), int(fd), float(printed)
-        base = nt_synth.model_config("C1", n_enc=ne, n_dec=nd, d_model=d, d_ffn=fe, tie_output=1, vocab=V,
-                                     n_heads=8)
-        n = oracle.param_count(base)
-        # replace the decoder's FFN (sized like the encoder's above) by one of width fd
-        dec_ffn = lambda F: (2 * d * F + F + d + 2 * d) if F else 0
-        n += nd * (dec_ffn(fd) - dec_ffn(fe))
+        cfg = nt_synth.model_config("C1", n_enc=ne, n_dec=nd, d_model=d, d_ffn=fe, tie_output=1, vocab=V,
+                                    n_heads=8, dec_n_heads=1 if nd == 1 else 0, dec_d_ffn=fd if fd else -1)
+        n = oracle.param_count(cfg)
+        # head counts do not change the count without relative position keys
+        assert n == oracle.param_count(dict(cfg, dec_n_heads=0))
+        # written out: embedding, per layer 4 projections (+bias), FFN (+biases), LayerNorms
+        attn, ln = 4 * (d * d + d), 2 * d
+        ffn = lambda F: (2 * d * F + F + d + ln) if F else 0
+        assert n == V * d + ne * (ln + attn + ffn(fe)) + ln + nd * (2 * (ln + attn) + ffn(fd)) + ln
         assert abs(n / 1e6 - printed) / printed < 0.025, (name, n)
+    c5 = oracle.param_count(nt_synth.model_config("C5"))
+    assert abs(c5 / 1e6 - 28) / 28 < 0.025
