@@ -52,6 +52,12 @@ typedef struct nt_model nt_model; /* opaque */
  *                  d_model / n_heads must be 64, 128, 256 or 512
  *   d_ffn          FFN width in every layer, 0 = the FFN sub-layers are removed (student);
  *                  a multiple of 64 otherwise
+ *   dec_n_heads, dec_d_ffn
+ *                  the decoder's own shape where it differs from the encoder's (Table 2 and
+ *                  Sec. 5: the submitted students put a base encoder, 8 heads and FFN 2,048, in
+ *                  front of a one-head decoder layer whose FFN is 512 wide or absent).
+ *                  dec_n_heads 0 = n_heads; dec_d_ffn 0 = d_ffn, -1 = no decoder FFN, otherwise
+ *                  the width (a multiple of 64).  n_heads and d_ffn then describe the encoder.
  *   vocab          shared source/target vocabulary
  *   max_len        longest source sentence and longest target prefix (positions), <= 512
  *   rpr_clip       clipping distance of the relative position keys in self-attention
@@ -74,6 +80,7 @@ typedef struct {
   int64_t max_batch_tokens;
   int32_t pipeline_lanes; /* batches kept in flight by nt_translate_batch, each with its own arena and
                              internal stream; 0 = default (4, one per hardware queue), 1 = no overlap */
+  int32_t dec_n_heads, dec_d_ffn;
   int32_t reserved;       /* must be 0 */
 } nt_config;
 

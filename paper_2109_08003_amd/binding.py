@@ -24,7 +24,8 @@ class NtConfig(C.Structure):
     _fields_ = [("struct_size", C.c_uint32)] + [(k, C.c_int32) for k in (
         "n_enc", "n_dec", "d_model", "n_heads", "d_ffn", "vocab", "max_len", "rpr_clip", "tie_output", "bos_id",
         "pad_id")] + [("ln_eps", C.c_float), ("max_batch_rows", C.c_int32), ("max_batch_tokens", C.c_int64),
-                                ("pipeline_lanes", C.c_int32), ("reserved", C.c_int32)]
+                                ("pipeline_lanes", C.c_int32), ("dec_n_heads", C.c_int32),
+                                ("dec_d_ffn", C.c_int32), ("reserved", C.c_int32)]
 
 
 class NtError(RuntimeError):
@@ -98,6 +99,8 @@ def make_config(cfg: dict, max_batch_tokens: int, max_batch_rows: int = 0, pipel
     c.max_batch_tokens = int(max_batch_tokens)
     c.max_batch_rows = int(max_batch_rows)
     c.pipeline_lanes = int(pipeline_lanes)
+    c.dec_n_heads = int(cfg.get("dec_n_heads", 0))
+    c.dec_d_ffn = int(cfg.get("dec_d_ffn", 0))
     c.reserved = 0
     return c
 

@@ -85,6 +85,7 @@ struct Attn {
 struct FFN {
   const _Float16 *W1 = nullptr, *W2 = nullptr;  // [F][d], [d][F]
   const _Float16 *W1_p = nullptr;               // W1 in MFMA fragment order, or nullptr
+  const _Float16 *W2_p = nullptr;               // W2 likewise
   const float *b1 = nullptr, *b2 = nullptr;
 };
 struct EncLayer {
@@ -188,6 +189,10 @@ struct nt_model {
 
 namespace {
 
+// the decoder's head count and FFN width (its own where the configuration gives them)
+int dec_heads(const nt_config *c) { return c->dec_n_heads > 0 ? c->dec_n_heads : c->n_heads; }
+int dec_ffn(const nt_config *c) { return c->dec_d_ffn == 0 ? c->d_ffn : std::max(c->dec_d_ffn, 0); }
+
 int check_config(const nt_config *c) {
   if (!c) return fail(NT_EINVAL, "config is null");
   if (c->struct_size != sizeof(nt_config)) return fail(NT_EINVAL, "config.struct_size %u != %zu", c->struct_size, sizeof(nt_config));
@@ -197,6 +202,10 @@ int check_config(const nt_config *c) {
   int dh = c->d_model / c->n_heads;
   if (dh != 64 && dh != 128 && dh != 256 && dh != 512) return fail(NT_ESHAPE, "head width %d not in {64,128,256,512}", dh);
   if (c->d_ffn < 0 || c->d_ffn % 64) return fail(NT_ESHAPE, "d_ffn must be 0 or a multiple of 64");
+  if (c->dec_n_heads < 0 || c->d_model % dec_heads(c)) return fail(NT_ESHAPE, "d_model not divisible by dec_n_heads");
+  const int dhd = c->d_model / dec_heads(c);
+  if (dhd != 64 && dhd != 128 && dhd != 256 && dhd != 512) return fail(NT_ESHAPE, "decoder head width %d not in {64,128,256,512}", dhd);
+  if (c->dec_d_ffn < -1 || (c->dec_d_ffn > 0 && c->dec_d_ffn % 64)) return fail(NT_ESHAPE, "dec_d_ffn must be -1, 0 or a multiple of 64");
   if (c->max_len < 1 || c->max_len > 512) return fail(NT_ESHAPE, "max_len must be in [1,512]");
   if (c->rpr_clip < 0 || c->rpr_clip > 16) return fail(NT_ESHAPE, "rpr_clip must be in [0,16]");
   if (c->bos_id < 0 || c->bos_id >= c->vocab || c->pad_id < 0 || c->pad_id >= c->vocab) return fail(NT_ERANGE, "bos_id/pad_id outside the vocabulary");
@@ -206,13 +215,12 @@ int check_config(const nt_config *c) {
 }
 
 int64_t param_count(const nt_config *c) {
-  int64_t d = c->d_model, V = c->vocab, F = c->d_ffn, dh = d / c->n_heads;
-  int64_t attn = 4 * (d * d + d), ln = 2 * d;
-  int64_t ffn = F > 0 ? ln + d * F + F + F * d + d : 0;
-  int64_t rk = c->rpr_clip > 0 ? (2 * c->rpr_clip + 1) * dh : 0;
+  const int64_t d = c->d_model, V = c->vocab, attn = 4 * (d * d + d), ln = 2 * d;
+  auto ffn = [&](int64_t F) { return F > 0 ? ln + d * F + F + F * d + d : 0; };
+  auto rk = [&](int64_t heads) { return c->rpr_clip > 0 ? (2 * c->rpr_clip + 1) * (d / heads) : 0; };
   int64_t n = (c->tie_output ? 1 : 2) * V * d;
-  n += (int64_t)c->n_enc * (ln + attn + rk + ffn) + ln;
-  n += (int64_t)c->n_dec * (ln + attn + rk + ln + attn + ffn) + ln;
+  n += (int64_t)c->n_enc * (ln + attn + rk(c->n_heads) + ffn(c->d_ffn)) + ln;
+  n += (int64_t)c->n_dec * (ln + attn + rk(dec_heads(c)) + ln + attn + ffn(dec_ffn(c))) + ln;
   return n;
 }
 
@@ -263,7 +271,7 @@ hipStream_t as_stream(void *s) { return (hipStream_t)s; }
 // The peak footprint is fixed here; nothing is allocated afterwards.
 int alloc_lane_state(nt_model *m, hipStream_t s) {
   const nt_config *cfg = &m->c;
-  const int d = cfg->d_model, F = cfg->d_ffn;
+  const int d = cfg->d_model, F = cfg->d_ffn, Fd = dec_ffn(cfg);
   const int64_t Mt = m->max_tokens, Br = m->max_rows;
   m->self_positions = (6 * Mt + 4) / 5 + 3 * Br + 8;
   if (m->self_positions < Br * 1) m->self_positions = Br;
@@ -284,7 +292,7 @@ int alloc_lane_state(nt_model *m, hipStream_t s) {
   for (int l = 0; l < cfg->n_dec; l++) o_cross[l] = cv.take((size_t)Mt * 2 * d * kCrossElt);
   for (int l = 0; l < cfg->n_dec; l++) o_self[l] = cv.take((size_t)m->self_positions * 2 * d * 4);
   const size_t o_z = cv.take((size_t)Br * d * 4), o_a32 = cv.take((size_t)Br * d * 4), o_q32 = cv.take((size_t)Br * d * 4),
-               o_ctx32 = cv.take((size_t)Br * d * 4), o_u32 = cv.take((size_t)Br * std::max(F, 1) * 4),
+               o_ctx32 = cv.take((size_t)Br * d * 4), o_u32 = cv.take((size_t)Br * std::max(Fd, 1) * 4),
                o_pk = cv.take((size_t)m->pk_elems * 8), o_ps = cv.take((size_t)m->pk_elems * 4),
                o_lon = cv.take((size_t)Br * 4), o_tok = cv.take((size_t)Br * 4), o_slot = cv.take((size_t)Br * 4),
                o_clist = cv.take((size_t)Br * 4), o_fkey = cv.take((size_t)Br * 8), o_nmask = cv.take((size_t)Br * 8),
@@ -426,7 +434,8 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
   if ((int64_t)blob_bytes != 2 * np) return fail(NT_EBLOB, "blob holds %zu bytes, configuration needs %lld", blob_bytes, (long long)(2 * np));
   if (cfg->max_batch_tokens < 1) return fail(NT_EINVAL, "max_batch_tokens must be >= 1");
   if (cfg->max_batch_rows < 0) return fail(NT_EINVAL, "max_batch_rows must be >= 0");
-  const int d = cfg->d_model, V = cfg->vocab, F = cfg->d_ffn, H = cfg->n_heads, dh = d / H, c = cfg->rpr_clip;
+  const int d = cfg->d_model, V = cfg->vocab, F = cfg->d_ffn, Fd = dec_ffn(cfg), H = cfg->n_heads, dh = d / H,
+            dhd = d / dec_heads(cfg), c = cfg->rpr_clip;
   if (nt::enc_attention_lds_bytes(cfg->max_len, dh, kEncF32) > 160 * 1024) return fail(NT_ESHAPE, "max_len %d with head width %d exceeds the LDS plan", cfg->max_len, dh);
 
   nt_model *m = new nt_model();
@@ -459,7 +468,7 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
     put_f32(br.take(d), d, (const void **)&ln.b);
   };
   // self-attention: Wq|Wk|Wv fused into one [3d][d] matrix; cross-attention: Wq and Wk|Wv
-  auto put_attn = [&](Attn &a, bool cross, bool rpr) {
+  auto put_attn = [&](Attn &a, bool cross, bool rpr, int dh) {
     const _Float16 *W[4], *b[4];
     for (int i = 0; i < 4; i++) { W[i] = br.take((int64_t)d * d); b[i] = br.take(d); }
     auto fused = [&](int first, int count, const void **wslot, const void **bslot, const void **pslot) {
@@ -483,7 +492,7 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
     fused(3, 1, (const void **)&a.Wo, (const void **)&a.bo, (const void **)&a.Wo_p);
     if (rpr && c > 0) put_f32(br.take((int64_t)(2 * c + 1) * dh), (2 * c + 1) * dh, (const void **)&a.rk);
   };
-  auto put_ffn = [&](FFN &f) {
+  auto put_ffn = [&](FFN &f, int F) {
     const _Float16 *W1 = br.take((int64_t)d * F), *b1 = br.take(F), *W2 = br.take((int64_t)F * d), *b2 = br.take(d);
     size_t o = pk.reserve((size_t)d * F * 2);
     Packer::transpose(W1, d, F, (_Float16 *)(pk.img.data() + o));
@@ -497,6 +506,11 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
     o = pk.reserve((size_t)d * F * 2);
     Packer::transpose(W2, F, d, (_Float16 *)(pk.img.data() + o));
     fixes.push_back({o, (const void **)&f.W2});
+    if (nt::gemm_stream_supported(d, F)) {
+      size_t op = pk.reserve(nt::vocab_pack_bytes(d, F));
+      nt::vocab_pack((const _Float16 *)(pk.img.data() + o), d, F, (_Float16 *)(pk.img.data() + op));
+      fixes.push_back({op, (const void **)&f.W2_p});
+    }
     put_f32(b2, d, (const void **)&f.b2);
   };
 
@@ -506,16 +520,16 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
   if (!cfg->tie_output) put_raw(br.take((int64_t)V * d), (int64_t)V * d, (const void **)&m->Wout);
   for (auto &L : m->enc) {
     put_ln(L.ln1);
-    put_attn(L.self, false, true);
-    if (F > 0) { put_ln(L.ln2); put_ffn(L.ffn); }
+    put_attn(L.self, false, true, dh);
+    if (F > 0) { put_ln(L.ln2); put_ffn(L.ffn, F); }
   }
   put_ln(m->enc_final);
   for (auto &L : m->dec) {
     put_ln(L.ln1);
-    put_attn(L.self, false, true);
+    put_attn(L.self, false, true, dhd);
     put_ln(L.ln2);
-    put_attn(L.cross, true, false);
-    if (F > 0) { put_ln(L.ln3); put_ffn(L.ffn); }
+    put_attn(L.cross, true, false, dhd);
+    if (Fd > 0) { put_ln(L.ln3); put_ffn(L.ffn, Fd); }
   }
   put_ln(m->dec_final);
   if (br.p - (const _Float16 *)h_blob_fp16 != np) return fail(NT_EBLOB, "internal: blob walk mismatch");
@@ -682,7 +696,7 @@ namespace {
 int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, const int32_t *d_forced,
                 int32_t *d_out, float *d_logits, hipStream_t s) {
   const nt_config &c = m->c;
-  const int d = c.d_model, F = c.d_ffn, H = c.n_heads, V = c.vocab, S = m->S;
+  const int d = c.d_model, F = dec_ffn(&c), H = dec_heads(&c), V = c.vocab, S = m->S;
   const float qscale = 1.0f / std::sqrt((float)(d / H));
   const long self_stride = (long)T * 2 * d;
   // active rows at step t: rows are ordered so that the active set is a prefix
@@ -731,7 +745,7 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
       return Wp != nullptr && nt::gemm_stream_supported(N, K);
     };
     auto dec_gemm = [&](int id, const float *A, int K, const _Float16 *Wt, const _Float16 *Wp, int N, const LN *ln,
-                        const nt::GemmEpilogue &e) -> int {
+                        const nt::GemmEpilogue &e, bool c_f32 = true) -> int {
       const double by = gemm_bytes(Rd, K, N, e.resid != nullptr), fl = 2 * Rd * K * (double)N;
       if (R <= kSkinnyMaxRows && nt::skinny_gemm_supported(K, ln != nullptr)) {
         KT(id, by, fl, nt::launch_skinny_gemm(A, K, Wt, R, N, K, ln ? ln->g : nullptr, ln ? ln->b : nullptr, c.ln_eps, e, s));
@@ -739,7 +753,7 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
       }
       const bool planes = streams(N, K, Wp, ln != nullptr);
       if (ln && planes) {  // the LayerNorm runs inside the projection, while the tile is loaded
-        KT(id, by, fl, nt::launch_gemm_stream_ln(true, A, K, nt::GemmLayerNorm{ln->g, ln->b, c.ln_eps}, Wp, R, N, K, e, s));
+        KT(id, by, fl, nt::launch_gemm_stream_ln(c_f32, A, K, nt::GemmLayerNorm{ln->g, ln->b, c.ln_eps}, Wp, R, N, K, e, s));
         return NT_OK;
       }
       if (ln) {
@@ -779,12 +793,16 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
         if ((rc = dec_gemm(K_GEMM_DEC_O, m->ctx32, d, L.cross.Wo, L.cross.Wo_p, d, nullptr, o))) return rc;
       }
       if (F > 0) {
+        // when both FFN projections stream, the hidden activation is handed over as a head/tail plane pair
+        // (the two fp16 planes fill the fp32 buffer exactly)
+        const bool u_planes = streams(F, d, L.ffn.W1_p, true) && streams(d, F, L.ffn.W2_p, false);
         nt::GemmEpilogue f1;
         f1.bias = L.ffn.b1; f1.relu = 1; f1.dst0 = m->u32; f1.ld0 = F; f1.n_split = F;
-        if ((rc = dec_gemm(K_GEMM_DEC_FFN, m->z, d, L.ffn.W1, L.ffn.W1_p, F, &L.ln3, f1))) return rc;
+        f1.dst_lo_offset = u_planes ? lo_rows * F : 0;
+        if ((rc = dec_gemm(K_GEMM_DEC_FFN, m->z, d, L.ffn.W1, L.ffn.W1_p, F, &L.ln3, f1, !u_planes))) return rc;
         nt::GemmEpilogue f2;
         f2.bias = L.ffn.b2; f2.resid = m->z; f2.ldr = d; f2.dst0 = m->z; f2.ld0 = d; f2.n_split = d;
-        if ((rc = dec_gemm(K_GEMM_DEC_FFN, m->u32, F, L.ffn.W2, nullptr, d, nullptr, f2))) return rc;
+        if ((rc = dec_gemm(K_GEMM_DEC_FFN, m->u32, F, L.ffn.W2, u_planes ? L.ffn.W2_p : nullptr, d, nullptr, f2))) return rc;
       }
     }
     // final LayerNorm as a head/tail plane pair (the planes share the a32 buffer), then the output layer

@@ -355,6 +355,74 @@ def test_relative_positions_small(nt, oracle):
     _check_workload_sample(nt, oracle, "C0", 8, 512, 0.87, rpr_clip=16, n_heads=4, d_ffn=256)
 
 
+# ------------------------------------------------------------------------------ C5 (shape of the submitted student)
+def test_c5_submitted_student_shape(nt, oracle, torch_cuda):
+    """Student-3-1-512 (Table 2, Sec. 5): 3 encoder layers with 8 heads and FFN 2,048, one decoder layer
+    with a single head and FFN 512, shared embedding.  With random weights the shared embedding makes
+    greedy decoding re-emit BOS (see the oracle pin on tied embeddings), so the informative checks are
+    the encoder outputs, the teacher-forced logits on random targets, and greedy decoding of the same
+    shape with a separate output matrix."""
+    torch = torch_cuda
+    cfg = nt_synth.model_config("C5")
+    assert cfg["tie_output"] == 1 and cfg["dec_n_heads"] == 1 and cfg["dec_d_ffn"] == 512
+    blob = nt_synth.make_weights(cfg, seed=0, random_affine=True)
+    gm, om = nt.Model(cfg, blob, max_batch_tokens=8192), oracle.Model(cfg, blob)
+    tokens, offsets = nt_synth.workload("C5", 200)
+    sents = split(tokens, offsets)
+    # 150 rows: the decoder projections take the streaming kernels (FFN hidden activation as planes)
+    src = sort_desc([s[:40] for s in sents[:150]])
+    ids, lens = pad(src, cfg["pad_id"])
+    B, S = ids.shape
+    gm.encode(torch.from_numpy(ids).cuda(), torch.from_numpy(lens).cuda())
+    enc = torch.empty(B, S, cfg["d_model"], dtype=torch.float32, device="cuda")
+    gm.debug_encoder_out(enc)
+    enc = enc.cpu().numpy().astype(np.float64)
+    T = 5
+    rng = np.random.default_rng(55)
+    tgt = rng.integers(4, cfg["vocab"], size=(B, T)).astype(np.int32)
+    tgt[:, 0] = cfg["bos_id"]
+    logits = torch.empty(B, T, cfg["vocab"], dtype=torch.float32, device="cuda")
+    gm.debug_teacher_forced_logits(torch.from_numpy(tgt).cuda(), logits)
+    logits = logits.cpu().numpy().astype(np.float64)
+    for i in list(range(0, B, 13)) + [B - 1]:
+        assert rel_l2(enc[i, : len(src[i])], om.encode(src[i])) <= 2e-3
+        want = om.teacher_forced(src[i], tgt[i])
+        assert np.abs(logits[i] - want).max() <= 2e-2 and rel_l2(logits[i], want) <= 2e-3
+    # a handful of rows: the one-round-trip decoder kernels
+    src = sort_desc(sents[150:156])
+    ids, lens = pad(src, cfg["pad_id"])
+    B, S = ids.shape
+    gm.encode(torch.from_numpy(ids).cuda(), torch.from_numpy(lens).cuda())
+    logits = torch.empty(B, T, cfg["vocab"], dtype=torch.float32, device="cuda")
+    gm.debug_teacher_forced_logits(torch.from_numpy(tgt[:B].copy()).cuda(), logits)
+    logits = logits.cpu().numpy().astype(np.float64)
+    for i in range(B):
+        want = om.teacher_forced(src[i], tgt[i])
+        assert np.abs(logits[i] - want).max() <= 2e-2 and rel_l2(logits[i], want) <= 2e-3
+    # greedy, shared embedding: identical to the oracle (BOS at every step)
+    out, oo = gm.translate_batch(tokens, offsets, token_budget=8192)
+    ref, ro, _ = om.translate(tokens[: offsets[24]], offsets[:25])
+    assert np.array_equal(out[: oo[24]], ref) and np.array_equal(oo[:25], ro)
+    del gm
+    # greedy, separate output matrix: 1,200 sentences in batches of hundreds of rows, 200 of them audited
+    cfg_u = nt_synth.model_config("C5", tie_output=0)
+    blob_u = nt_synth.make_weights(cfg_u, seed=0, random_affine=True)
+    gu, ou = nt.Model(cfg_u, blob_u, max_batch_tokens=32768), oracle.Model(cfg_u, blob_u)
+    tokens, offsets = nt_synth.workload("C5", 1200)
+    out, oo = gu.translate_batch(tokens, offsets, token_budget=32768)
+    lens = np.diff(offsets)
+    assert np.array_equal(np.diff(oo), [nt.n_steps(int(l)) for l in lens])
+    order = np.argsort(-lens, kind="stable")
+    sample = np.unique(np.concatenate([rng.choice(1200, size=190, replace=False), order[:3], order[-7:]]))
+    sents = [tokens[offsets[i]:offsets[i + 1]] for i in sample]
+    sub_off = np.concatenate([[0], np.cumsum([len(s) for s in sents])])
+    o_out, o_oo, _ = ou.translate(np.concatenate(sents), sub_off)
+    bad, worst = audit_mismatches(ou, sents, [out[oo[i]:oo[i + 1]] for i in sample], split(o_out, o_oo), cfg_u)
+    frac = 1.0 - bad / len(sample)
+    print(f"C5 greedy: {len(sample) - bad}/{len(sample)} sampled sentences identical ({100 * frac:.2f} %), worst gap {worst:.2e}")
+    assert frac >= 0.99
+
+
 # ------------------------------------------------------------------------------ C2 (throughput configuration, as benchmarked)
 def test_c2_full_workload_sampled_against_oracle(nt, oracle):
     """All 200,000 sentences at the 65,536-token budget - the launch configuration bench.py times

@@ -27,9 +27,14 @@ def test_library_exports_every_declared_symbol():
 def test_n_steps_and_param_count():
     for n in range(0, 250):
         assert nt.n_steps(n) == math.ceil(Fraction(12, 10) * n) + 2
-    for name in ("C0", "C1", "C3", "C4"):
+    for name in ("C0", "C1", "C3", "C4", "C5"):
         cfg = nt_synth.model_config(name)
         assert nt.param_count(cfg) == nt_synth.blob_numel(cfg)
+    # a decoder shaped on its own: heads only matter with relative keys, -1 removes the decoder FFN only
+    for kw in (dict(dec_n_heads=1, rpr_clip=4), dict(dec_d_ffn=-1), dict(dec_d_ffn=512), dict(dec_n_heads=8, dec_d_ffn=2048)):
+        cfg = nt_synth.model_config("C3", **kw)
+        assert nt.param_count(cfg) == nt_synth.blob_numel(cfg), kw
+    assert nt.param_count(nt_synth.model_config("C3", dec_n_heads=8, dec_d_ffn=2048)) == nt.param_count(nt_synth.model_config("C3"))
     assert nt.param_count(nt_synth.model_config("C1", tie_output=1)) == nt_synth.blob_numel(
         nt_synth.model_config("C1", tie_output=1))
 
@@ -95,7 +100,8 @@ def test_load_rejects_bad_config_and_blob_before_touching_the_gpu():
     assert load(c, blob.nbytes - 2) == -3 and b"blob" in L.nt_last_error()
     c.struct_size = 12
     assert load(c, blob.nbytes) == -1
-    for key, val in (("d_model", 100), ("n_heads", 3), ("d_ffn", 100), ("max_len", 4096), ("rpr_clip", 99)):
+    for key, val in (("d_model", 100), ("n_heads", 3), ("d_ffn", 100), ("max_len", 4096), ("rpr_clip", 99),
+                     ("dec_n_heads", 3), ("dec_n_heads", 16), ("dec_d_ffn", 100), ("dec_d_ffn", -2)):
         c = nt.make_config(dict(cfg, **{key: val}), 4096)
         assert load(c, blob.nbytes) == -2, key
     c = nt.make_config(dict(cfg, bos_id=cfg["vocab"]), 4096)
