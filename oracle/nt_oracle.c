@@ -37,6 +37,9 @@ typedef struct {
      encoder in front of a one-head decoder whose FFN is 512 wide or absent):
      dec_n_heads 0 = n_heads;  dec_d_ffn 0 = d_ffn, -1 = no decoder FFN, else the width */
   int32_t dec_n_heads, dec_d_ffn;
+  /* 1: every layer normalisation divides by the scaled mean absolute deviation instead of the standard
+     deviation (Sec. 3.1 "FP16 Inference": the L1-norm replacement; see ora_layer_norm_l1) */
+  int32_t ln_l1;
   double ln_eps;
 } ora_config;
 
@@ -108,7 +111,7 @@ ora_model *ora_load(const ora_config *c, const uint16_t *blob, int64_t n_halfs) 
   if (!c || !blob) return NULL;
   if (c->d_model <= 0 || c->n_heads <= 0 || c->d_model % c->n_heads || c->vocab <= 0 ||
       c->n_enc < 0 || c->n_dec < 1 || c->d_ffn < 0 || c->rpr_clip < 0) return NULL;
-  if (c->dec_n_heads < 0 || c->d_model % dec_heads(c) || c->dec_d_ffn < -1) return NULL;
+  if (c->dec_n_heads < 0 || c->d_model % dec_heads(c) || c->dec_d_ffn < -1 || c->ln_l1 < 0 || c->ln_l1 > 1) return NULL;
   if (n_halfs != ora_param_count(c)) return NULL;
   ora_model *m = (ora_model *)calloc(1, sizeof *m);
   m->c = *c;
@@ -165,6 +168,26 @@ void ora_layer_norm(const double *x, const float *g, const float *b, int32_t d, 
   var /= d;
   double r = 1.0 / sqrt(var + eps);
   for (int i = 0; i < d; i++) y[i] = (double)g[i] * ((x[i] - mean) * r) + (double)b[i];
+}
+
+/* L1-norm layer normalisation (Sec. 3.1 "FP16 Inference" names the replacement and cites Lin et al., IJCAI 2020,
+   without printing a formula; this is the reading taken here): the standard deviation is replaced by the mean
+   absolute deviation scaled by sqrt(pi/2), the factor that makes the two agree for normally distributed
+   activations:   y = g * (x - mean) / (sqrt(pi/2) * mean|x - mean| + eps) + b */
+void ora_layer_norm_l1(const double *x, const float *g, const float *b, int32_t d, double eps, double *y) {
+  double mean = 0.0, mad = 0.0;
+  for (int i = 0; i < d; i++) mean += x[i];
+  mean /= d;
+  for (int i = 0; i < d; i++) mad += fabs(x[i] - mean);
+  mad /= d;
+  double r = 1.0 / (sqrt(acos(-1.0) / 2.0) * mad + eps);
+  for (int i = 0; i < d; i++) y[i] = (double)g[i] * ((x[i] - mean) * r) + (double)b[i];
+}
+
+/* the model's layer normalisation: vanilla or L1-norm, as configured */
+static void norm(const ora_config *c, const double *x, const float *g, const float *b, double *y) {
+  if (c->ln_l1) ora_layer_norm_l1(x, g, b, c->d_model, c->ln_eps, y);
+  else ora_layer_norm(x, g, b, c->d_model, c->ln_eps, y);
 }
 
 /* y[n] = b[n] + sum_k x[k] W[k][n],  W stored [n_in][n_out] */
@@ -234,7 +257,7 @@ static void embed(const ora_model *m, int32_t id, int32_t pos, double *x) {
 static void ffn_block(const ora_model *m, const ln_t *ln, const ffn_t *f, int F, double *x) {
   int d = m->c.d_model;
   double *a = (double *)malloc(sizeof(double) * (size_t)(2 * d + F)), *u = a + d, *o = u + F;
-  ora_layer_norm(x, ln->g, ln->b, d, m->c.ln_eps, a);
+  norm(&m->c, x, ln->g, ln->b, a);
   ora_linear(a, f->W1, f->b1, d, F, u);
   for (int i = 0; i < F; i++) if (u[i] < 0.0) u[i] = 0.0;
   ora_linear(u, f->W2, f->b2, F, d, o);
@@ -257,7 +280,7 @@ static int encode(const ora_model *m, const int32_t *src, int32_t len, double *e
     const enc_layer *L = &m->enc[l];
     for (int i = 0; i < len; i++) {
       double *ai = a + (size_t)i * d;
-      ora_layer_norm(x + (size_t)i * d, L->ln1.g, L->ln1.b, d, c->ln_eps, ai);
+      norm(c, x + (size_t)i * d, L->ln1.g, L->ln1.b, ai);
       ora_linear(ai, L->self.Wq, L->self.bq, d, d, q + (size_t)i * d);
       ora_linear(ai, L->self.Wk, L->self.bk, d, d, k + (size_t)i * d);
       ora_linear(ai, L->self.Wv, L->self.bv, d, d, v + (size_t)i * d);
@@ -272,7 +295,7 @@ static int encode(const ora_model *m, const int32_t *src, int32_t len, double *e
       for (int i = 0; i < len; i++) ffn_block(m, &L->ln2, &L->ffn, c->d_ffn, x + (size_t)i * d);
   }
   for (int i = 0; i < len; i++)
-    ora_layer_norm(x + (size_t)i * d, m->enc_final.g, m->enc_final.b, d, c->ln_eps, enc + (size_t)i * d);
+    norm(c, x + (size_t)i * d, m->enc_final.g, m->enc_final.b, enc + (size_t)i * d);
   free(ctx); free(x);
   return 0;
 }
@@ -314,7 +337,7 @@ static void dec_step(const ora_model *m, dec_state *s, int32_t y_prev, int32_t t
     const dec_layer *L = &m->dec[l];
     double *sk = s->sk + (size_t)l * s->cap * d, *sv = s->sv + (size_t)l * s->cap * d;
     /* causal self-attention over positions 0..t; earlier keys/values are the cached ones */
-    ora_layer_norm(z, L->ln1.g, L->ln1.b, d, c->ln_eps, a);
+    norm(c, z, L->ln1.g, L->ln1.b, a);
     ora_linear(a, L->self.Wq, L->self.bq, d, d, q);
     ora_linear(a, L->self.Wk, L->self.bk, d, d, sk + (size_t)t * d);
     ora_linear(a, L->self.Wv, L->self.bv, d, d, sv + (size_t)t * d);
@@ -323,7 +346,7 @@ static void dec_step(const ora_model *m, dec_state *s, int32_t y_prev, int32_t t
     ora_linear(ctx, L->self.Wo, L->self.bo, d, d, o);
     for (int e = 0; e < d; e++) z[e] += o[e];
     /* cross-attention over the encoder output (no relative positions) */
-    ora_layer_norm(z, L->ln2.g, L->ln2.b, d, c->ln_eps, a);
+    norm(c, z, L->ln2.g, L->ln2.b, a);
     ora_linear(a, L->cross.Wq, L->cross.bq, d, d, q);
     for (int e = 0; e < d; e++) q[e] *= qs;
     ora_attend(q, s->ck + (size_t)l * s->len * d, s->cv + (size_t)l * s->len * d, s->len, d, H,
@@ -332,7 +355,7 @@ static void dec_step(const ora_model *m, dec_state *s, int32_t y_prev, int32_t t
     for (int e = 0; e < d; e++) z[e] += o[e];
     if (dec_ffn(c) > 0) ffn_block(m, &L->ln3, &L->ffn, dec_ffn(c), z);
   }
-  ora_layer_norm(z, m->dec_final.g, m->dec_final.b, d, c->ln_eps, a);
+  norm(c, z, m->dec_final.g, m->dec_final.b, a);
   /* output layer: plain logits, no bias, no log-softmax */
   for (int v = 0; v < V; v++) {
     const float *w = m->Wout + (int64_t)v * d;

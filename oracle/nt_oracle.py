@@ -36,7 +36,7 @@ def build(force: bool = True) -> str:
 class _Cfg(C.Structure):
     _fields_ = [(k, C.c_int32) for k in ("n_enc", "n_dec", "d_model", "n_heads", "d_ffn", "vocab",
                                          "max_len", "rpr_clip", "tie_output", "bos_id",
-                                         "dec_n_heads", "dec_d_ffn")] + [("ln_eps", C.c_double)]
+                                         "dec_n_heads", "dec_d_ffn", "ln_l1")] + [("ln_eps", C.c_double)]
 
 
 _lib = None
@@ -63,6 +63,8 @@ def lib():
         L.ora_pe.argtypes = [i32, i32, p]
         L.ora_layer_norm.restype = None
         L.ora_layer_norm.argtypes = [p, p, p, i32, dbl, p]
+        L.ora_layer_norm_l1.restype = None
+        L.ora_layer_norm_l1.argtypes = [p, p, p, i32, dbl, p]
         L.ora_linear.restype = None
         L.ora_linear.argtypes = [p, p, p, i32, i32, p]
         L.ora_softmax.restype = None
@@ -84,7 +86,7 @@ def lib():
 def _cfg(cfg: dict) -> _Cfg:
     c = _Cfg()
     for k, _ in _Cfg._fields_:
-        setattr(c, k, cfg.get(k, 0) if k.startswith("dec_") else cfg[k])
+        setattr(c, k, cfg.get(k, 0) if k.startswith("dec_") or k == "ln_l1" else cfg[k])
     return c
 
 
@@ -124,6 +126,13 @@ def layer_norm(x, g, b, eps) -> np.ndarray:
     x, g, b = _f64(x), _f32(g), _f32(b)
     y = np.empty_like(x)
     lib().ora_layer_norm(_ptr(x), _ptr(g), _ptr(b), x.size, eps, _ptr(y))
+    return y
+
+
+def layer_norm_l1(x, g, b, eps) -> np.ndarray:
+    x, g, b = _f64(x), _f32(g), _f32(b)
+    y = np.empty_like(x)
+    lib().ora_layer_norm_l1(_ptr(x), _ptr(g), _ptr(b), x.size, eps, _ptr(y))
     return y
 
 

@@ -40,8 +40,10 @@ def positions(n: int, d: int) -> np.ndarray:
     return pe
 
 
-def layer_norm(x, g, b, eps):
+def layer_norm(x, g, b, eps, l1=False):
     mu = x.mean(-1, keepdims=True)
+    if l1:   # L1-norm variant (Sec. 3.1): scaled mean absolute deviation in place of the standard deviation
+        return g * (x - mu) / (np.sqrt(np.pi / 2) * np.abs(x - mu).mean(-1, keepdims=True) + eps) + b
     var = ((x - mu) ** 2).mean(-1, keepdims=True)
     return g * (x - mu) / np.sqrt(var + eps) + b
 
@@ -80,7 +82,7 @@ def attention(W: Weights, prefix: str, xq, xkv, mask, rpr: bool, H: int):
 
 
 def ffn(W: Weights, ln: str, prefix: str, x):
-    a = layer_norm(x, W[f"{ln}.g"], W[f"{ln}.b"], W.cfg["ln_eps"])
+    a = layer_norm(x, W[f"{ln}.g"], W[f"{ln}.b"], W.cfg["ln_eps"], W.cfg.get("ln_l1", 0))
     u = np.maximum(a @ W[f"{prefix}.W1"] + W[f"{prefix}.b1"], 0.0)
     return x + u @ W[f"{prefix}.W2"] + W[f"{prefix}.b2"]
 
@@ -97,7 +99,7 @@ def pad_batch(seqs, pad_id):
 def encode(cfg: dict, blob: np.ndarray, src: list, extra_pad: int = 0):
     """Padded-batch encoder.  Returns (enc [B,S,d], lens)."""
     W = Weights(cfg, blob)
-    d, eps = cfg["d_model"], cfg["ln_eps"]
+    d, eps, l1 = cfg["d_model"], cfg["ln_eps"], cfg.get("ln_l1", 0)
     ids, lens = pad_batch(src, cfg["pad_id"])
     if extra_pad:
         ids = np.concatenate([ids, np.full((ids.shape[0], extra_pad), cfg["pad_id"], dtype=np.int64)], 1)
@@ -106,18 +108,18 @@ def encode(cfg: dict, blob: np.ndarray, src: list, extra_pad: int = 0):
     key_ok = np.arange(S)[None, :] < lens[:, None]                         # [B,S]
     mask = np.broadcast_to(key_ok[:, None, :], (B, S, S))
     for l in range(cfg["n_enc"]):
-        a = layer_norm(x, W[f"enc{l}.ln1.g"], W[f"enc{l}.ln1.b"], eps)
+        a = layer_norm(x, W[f"enc{l}.ln1.g"], W[f"enc{l}.ln1.b"], eps, l1)
         o, _ = attention(W, f"enc{l}.self", a, a, mask, True, cfg["n_heads"])
         x = x + o
         if cfg["d_ffn"] > 0:
             x = ffn(W, f"enc{l}.ln2", f"enc{l}.ffn", x)
-    return layer_norm(x, W["enc_final.g"], W["enc_final.b"], eps), lens
+    return layer_norm(x, W["enc_final.g"], W["enc_final.b"], eps, l1), lens
 
 
 def teacher_forced_logits(cfg: dict, blob: np.ndarray, src: list, tgt_in: list, extra_pad: int = 0):
     """Full (non-incremental) decoder over padded tgt_in; returns list of [T_i, V] logits."""
     W = Weights(cfg, blob)
-    d, eps = cfg["d_model"], cfg["ln_eps"]
+    d, eps, l1 = cfg["d_model"], cfg["ln_eps"], cfg.get("ln_l1", 0)
     enc, lens = encode(cfg, blob, src, extra_pad)
     S = enc.shape[1]
     tid, tlens = pad_batch(tgt_in, cfg["pad_id"])
@@ -129,15 +131,15 @@ def teacher_forced_logits(cfg: dict, blob: np.ndarray, src: list, tgt_in: list, 
     Hd = cfg.get("dec_n_heads", 0) or cfg["n_heads"]
     Fd = {0: cfg["d_ffn"], -1: 0}.get(cfg.get("dec_d_ffn", 0), cfg.get("dec_d_ffn", 0))
     for l in range(cfg["n_dec"]):
-        a = layer_norm(z, W[f"dec{l}.ln1.g"], W[f"dec{l}.ln1.b"], eps)
+        a = layer_norm(z, W[f"dec{l}.ln1.g"], W[f"dec{l}.ln1.b"], eps, l1)
         o, _ = attention(W, f"dec{l}.self", a, a, causal, True, Hd)
         z = z + o
-        a = layer_norm(z, W[f"dec{l}.ln2.g"], W[f"dec{l}.ln2.b"], eps)
+        a = layer_norm(z, W[f"dec{l}.ln2.g"], W[f"dec{l}.ln2.b"], eps, l1)
         o, _ = attention(W, f"dec{l}.cross", a, enc, cross, False, Hd)
         z = z + o
         if Fd > 0:
             z = ffn(W, f"dec{l}.ln3", f"dec{l}.ffn", z)
-    h = layer_norm(z, W["dec_final.g"], W["dec_final.b"], eps)
+    h = layer_norm(z, W["dec_final.g"], W["dec_final.b"], eps, l1)
     Wout = W["E"] if cfg["tie_output"] else W["W_out"]
     logits = h @ Wout.T
     return [logits[i, : tlens[i]] for i in range(B)]

@@ -63,6 +63,47 @@ def test_layer_norm_invariants_and_library(oracle):
         assert np.allclose(oracle.layer_norm(x, g, b, 1e-5), want, atol=1e-12)
 
 
+def test_l1_layer_norm_closed_forms_and_gaussian_limit(oracle):
+    """L1-norm layer normalisation (Sec. 3.1): mean absolute deviation times sqrt(pi/2) in place of the
+    standard deviation.  Pinned by a two-level vector (closed form), by the Gaussian limit in which it must
+    agree with the vanilla normalisation (this fixes the constant), and by its invariances."""
+    d = 64
+    one, zero = np.ones(d, np.float32), np.zeros(d, np.float32)
+    # x = m +- a: mean m, every |x - mean| = a  ->  y = +-1 / sqrt(pi/2) = +-0.79788456...
+    x = 5.0 + 3.0 * np.where(np.arange(d) % 2 == 0, 1.0, -1.0)
+    y = oracle.layer_norm_l1(x, one, zero, 0.0)
+    assert np.allclose(y, np.where(np.arange(d) % 2 == 0, 1.0, -1.0) * 0.7978845608028654, atol=1e-14)
+    # three quarters at 0, one quarter at 4: mean 1, mean |dev| = 1.5 -> y = (-1, 3) / (1.5 sqrt(pi/2))
+    x = np.where(np.arange(d) % 4 == 0, 4.0, 0.0)
+    y = oracle.layer_norm_l1(x, one, zero, 0.0)
+    assert np.allclose(y, np.where(np.arange(d) % 4 == 0, 3.0, -1.0) / (1.5 * 1.2533141373155001), atol=1e-14)
+    # eps sits in the denominator beside the deviation: all-equal input gives exactly the offset
+    b = np.linspace(-1, 1, d).astype(np.float32)
+    assert np.array_equal(oracle.layer_norm_l1(np.full(d, 2.5), one, b, 1e-5), b.astype(np.float64))
+    x = np.array([1.0, -1.0] * (d // 2))
+    assert np.allclose(oracle.layer_norm_l1(x, one, zero, 0.25), x / (1.2533141373155001 + 0.25), atol=1e-14)
+    # Gaussian limit: sqrt(pi/2) E|x - mu| = sigma, so both normalisations agree up to sampling noise
+    rng = np.random.default_rng(5)
+    n = 400000
+    x = rng.normal(-2.0, 7.0, n)
+    g1, b0 = np.ones(n, np.float32), np.zeros(n, np.float32)
+    ya, yb = oracle.layer_norm_l1(x, g1, b0, 0.0), oracle.layer_norm(x, g1, b0, 0.0)
+    assert np.abs(ya / yb - 1.0).max() < 5e-3
+    # a heavy-tailed input separates the two (so the L1 path is not the vanilla one in disguise)
+    x = rng.laplace(0.0, 1.0, n)
+    r = oracle.layer_norm_l1(x, g1, b0, 0.0) / oracle.layer_norm(x, g1, b0, 0.0)
+    assert abs(r.mean() - np.sqrt(2.0) / np.sqrt(np.pi / 2)) < 5e-3      # Laplace: sigma = sqrt(2) b, E|x| = b
+    # invariances: shift, positive scale; sign flip is odd; gain and offset are applied last
+    x = rng.normal(0, 1, d)
+    g = rng.normal(1, 0.1, d).astype(np.float32)
+    y = oracle.layer_norm_l1(x, one, zero, 0.0)
+    assert np.allclose(oracle.layer_norm_l1(x + 11.0, one, zero, 0.0), y, atol=1e-12)
+    assert np.allclose(oracle.layer_norm_l1(3.5 * x, one, zero, 0.0), y, atol=1e-12)
+    assert np.allclose(oracle.layer_norm_l1(-x, one, zero, 0.0), -y, atol=1e-12)
+    assert np.allclose(oracle.layer_norm_l1(x, g, b, 0.0), g.astype(np.float64) * y + b, atol=1e-12)
+    assert abs(y.mean()) < 1e-12 and abs(np.abs(y).mean() - 0.7978845608028654) < 1e-12
+
+
 def test_softmax_sums_to_one_masked_zero_and_library(oracle):
     rng = np.random.default_rng(1)
     s = rng.normal(0, 30.0, 77)                     # large scores: must not overflow
@@ -177,6 +218,9 @@ CASES = [
     dict(n_heads=4, d_ffn=48, dec_n_heads=1, dec_d_ffn=24),
     dict(n_heads=4, d_ffn=48, dec_n_heads=1, dec_d_ffn=-1, rpr_clip=2),
     dict(n_heads=1, d_ffn=0, dec_n_heads=2, dec_d_ffn=16, rpr_clip=3),
+    # L1-norm layer normalisation in every block
+    dict(ln_l1=1),
+    dict(n_heads=4, d_ffn=48, n_dec=2, ln_l1=1),
 ]
 
 
@@ -215,6 +259,21 @@ def test_decoder_shape_of_its_own_is_not_the_encoder_shape(oracle):
     assert np.abs(a - b).max() > 1e-3
     # the encoder half is untouched by the decoder's fields
     assert np.array_equal(oracle.Model(cfg, blob).encode(src), oracle.Model(one, blob).encode(src))
+
+
+def test_l1_model_differs_from_vanilla_and_uses_l1_everywhere(oracle):
+    """The L1 model is not the vanilla model, and the final normalisation's gain and offset act linearly on
+    the logits (they are applied after the division, as in the vanilla form)."""
+    cfg = tiny(d_ffn=48, ln_l1=1)
+    blob = nt_synth.make_weights(cfg, seed=31, random_affine=True)
+    src, tgt = np.array([9, 8, 7, 6, 5]), np.array([1, 11, 12])
+    base = oracle.Model(cfg, blob).teacher_forced(src, tgt)
+    assert np.abs(base - oracle.Model(dict(cfg, ln_l1=0), blob).teacher_forced(src, tgt)).max() > 1e-2
+    # doubling gain and offset of the final decoder normalisation doubles the logits
+    b2 = blob.copy()
+    nt_synth.blob_view(cfg, b2, "dec_final.g")[:] *= np.float16(2.0)
+    nt_synth.blob_view(cfg, b2, "dec_final.b")[:] *= np.float16(2.0)
+    assert np.allclose(oracle.Model(cfg, b2).teacher_forced(src, tgt), 2.0 * base, atol=1e-9)
 
 
 def test_padding_and_batch_mates_do_not_matter(oracle):
