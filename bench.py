@@ -53,6 +53,7 @@ def main():
     ap.add_argument("--tie-output", type=int, default=None, choices=[0, 1],
                     help="override the workload's embedding sharing (random shared embeddings make greedy "
                          "decoding re-emit BOS, which makes every certified arg-max trivially cheap)")
+    ap.add_argument("--ln-l1", action="store_true", help="L1-norm layer normalisation in every block")
     ap.add_argument("--sentences", type=int, default=None, help="default: the workload's own count")
     ap.add_argument("--budget", type=int, default=65536,
                     help="token budget per batch (best of the 4k/16k/64k sweep of the throughput configuration)")
@@ -79,6 +80,7 @@ def main():
     cfg = nt_synth.model_config(args.workload)
     if args.tie_output is not None:
         cfg["tie_output"] = args.tie_output
+    cfg["ln_l1"] = int(args.ln_l1)
     blob = nt_synth.make_weights(cfg, seed=0)
     tokens, offsets = nt_synth.workload(args.workload, args.sentences)
     lens = np.diff(offsets).astype(np.int32)
@@ -206,7 +208,7 @@ def main():
         "config": {"workload": f"{args.workload}: {n_sent} sentences (lognormal lengths, Zipf ids), student "
                                f"{cfg['n_enc']}-{cfg['n_dec']} d={cfg['d_model']} heads={cfg['n_heads']} ffn={cfg['d_ffn']} "
                                f"decoder heads={nt_synth.dec_heads(cfg)} ffn={nt_synth.dec_ffn(cfg)} "
-                               f"V={cfg['vocab']} tied={cfg['tie_output']}, greedy ceil(1.2 len)+2 steps",
+                               f"V={cfg['vocab']} tied={cfg['tie_output']} l1_norm={cfg['ln_l1']}, greedy ceil(1.2 len)+2 steps",
                    "token_budget": args.budget, "batches": len(batches), "pipeline_lanes": len(lanes), "source_tokens": src_tokens,
                    "target_tokens": tgt_tokens, "decode_steps": dec_steps},
         "source_tokens_per_s": round(src_tokens / dt, 1), "target_tokens_per_s": round(tgt_tokens / dt, 1),

@@ -65,6 +65,10 @@ typedef struct nt_model nt_model; /* opaque */
  *   tie_output     1: the output projection is the embedding matrix (Sec. 2.3); 0: the blob
  *                  holds a separate W_out
  *   ln_eps         LayerNorm epsilon (pre-LN blocks, biased variance)
+ *   ln_l1          1: every layer normalisation is the L1-norm variant the paper's GPU systems use
+ *                  (Sec. 3.1 "FP16 Inference"): y = g (x - mean) / (sqrt(pi/2) mean|x - mean| + ln_eps) + b,
+ *                  the mean absolute deviation scaled so that it equals the standard deviation for
+ *                  normal activations; 0: the vanilla form
  *   max_batch_tokens, max_batch_rows
  *                  largest padded batch (rows x longest row) and most rows per batch the
  *                  arena must hold; the peak footprint is fixed at load time, in the spirit
@@ -81,7 +85,7 @@ typedef struct {
   int32_t pipeline_lanes; /* batches kept in flight by nt_translate_batch, each with its own arena and
                              internal stream; 0 = default (4, one per hardware queue), 1 = no overlap */
   int32_t dec_n_heads, dec_d_ffn;
-  int32_t reserved;       /* must be 0 */
+  int32_t ln_l1;
 } nt_config;
 
 /* Number of fp16 elements the weight blob of this configuration must hold (0 if invalid). */

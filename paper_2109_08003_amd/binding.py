@@ -25,7 +25,7 @@ class NtConfig(C.Structure):
         "n_enc", "n_dec", "d_model", "n_heads", "d_ffn", "vocab", "max_len", "rpr_clip", "tie_output", "bos_id",
         "pad_id")] + [("ln_eps", C.c_float), ("max_batch_rows", C.c_int32), ("max_batch_tokens", C.c_int64),
                                 ("pipeline_lanes", C.c_int32), ("dec_n_heads", C.c_int32),
-                                ("dec_d_ffn", C.c_int32), ("reserved", C.c_int32)]
+                                ("dec_d_ffn", C.c_int32), ("ln_l1", C.c_int32)]
 
 
 class NtError(RuntimeError):
@@ -101,7 +101,7 @@ def make_config(cfg: dict, max_batch_tokens: int, max_batch_rows: int = 0, pipel
     c.pipeline_lanes = int(pipeline_lanes)
     c.dec_n_heads = int(cfg.get("dec_n_heads", 0))
     c.dec_d_ffn = int(cfg.get("dec_d_ffn", 0))
-    c.reserved = 0
+    c.ln_l1 = int(cfg.get("ln_l1", 0))
     return c
 
 

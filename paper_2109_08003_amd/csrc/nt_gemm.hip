@@ -605,7 +605,7 @@ __device__ __forceinline__ float wave_sum_f(float v) {
 
 template <int KC, bool C_F32>
 __global__ __launch_bounds__(256) void skinny_gemm_kernel(const float *A, long lda, const _Float16 *Wt, int M, int N,
-                                                          int K, const float *ln_g, const float *ln_b, float ln_eps,
+                                                          int K, const float *ln_g, const float *ln_b, LnEps ln_eps,
                                                           GemmEpilogue e) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_sk[];
   using Cfg = SkinnyCfg<KC>;
@@ -659,9 +659,9 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const float *A, long l
         for (int c = 0; c < CPL; c++) {
           float4 &x = ra[r][c];
           x.x -= mean; x.y -= mean; x.z -= mean; x.w -= mean;
-          q += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+          q += ln_term(x.x, ln_eps.l1) + ln_term(x.y, ln_eps.l1) + ln_term(x.z, ln_eps.l1) + ln_term(x.w, ln_eps.l1);
         }
-        const float rstd = 1.0f / sqrtf(wave_sum_f(q) / (float)KC + ln_eps);
+        const float rstd = ln_rscale(wave_sum_f(q) / (float)KC, ln_eps);
 #pragma unroll
         for (int c = 0; c < CPL; c++) {
           float4 &x = ra[r][c];
@@ -731,7 +731,7 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const float *A, long l
 
 template <int KC>
 static hipError_t skinny_launch(const float *A, long lda, const _Float16 *Wt, int M, int N, int K, const float *ln_g,
-                                const float *ln_b, float ln_eps, const GemmEpilogue &e, hipStream_t s) {
+                                const float *ln_b, LnEps ln_eps, const GemmEpilogue &e, hipStream_t s) {
   static bool configured = false;
   const size_t lds = SkinnyCfg<KC>::LDS;
   if (!configured) {
@@ -751,7 +751,7 @@ bool skinny_gemm_supported(int K, bool with_ln) {
 }
 
 hipError_t launch_skinny_gemm(const float *A, long lda, const _Float16 *Wt, int M, int N, int K, const float *ln_g,
-                              const float *ln_b, float ln_eps, const GemmEpilogue &e, hipStream_t s) {
+                              const float *ln_b, LnEps ln_eps, const GemmEpilogue &e, hipStream_t s) {
   if (M <= 0 || N <= 0) return hipSuccess;
   if (K % 512 == 0) return skinny_launch<512>(A, lda, Wt, M, N, K, ln_g, ln_b, ln_eps, e, s);
   if (K % 256 == 0) return skinny_launch<256>(A, lda, Wt, M, N, K, ln_g, ln_b, ln_eps, e, s);

@@ -100,9 +100,9 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
 #pragma unroll
       for (int j = 0; j < NE; j++) {
         const float c = xv[i][j] - mean;
-        q += c * c;
+        q += ln_term(c, ln.eps.l1);
       }
-      const float rstd = 1.0f / sqrtf(gs_wave_sum(q) / (float)K + ln.eps);
+      const float rstd = ln_rscale(gs_wave_sum(q) / (float)K, ln.eps);
       typedef _Float16 halfNE __attribute__((ext_vector_type(NE)));
       halfNE hi, lo;
 #pragma unroll

@@ -193,6 +193,8 @@ namespace {
 int dec_heads(const nt_config *c) { return c->dec_n_heads > 0 ? c->dec_n_heads : c->n_heads; }
 int dec_ffn(const nt_config *c) { return c->dec_d_ffn == 0 ? c->d_ffn : std::max(c->dec_d_ffn, 0); }
 
+nt::LnEps ln_eps_of(const nt_config &c) { return nt::LnEps{c.ln_eps, c.ln_l1}; }
+
 int check_config(const nt_config *c) {
   if (!c) return fail(NT_EINVAL, "config is null");
   if (c->struct_size != sizeof(nt_config)) return fail(NT_EINVAL, "config.struct_size %u != %zu", c->struct_size, sizeof(nt_config));
@@ -210,7 +212,8 @@ int check_config(const nt_config *c) {
   if (c->rpr_clip < 0 || c->rpr_clip > 16) return fail(NT_ESHAPE, "rpr_clip must be in [0,16]");
   if (c->bos_id < 0 || c->bos_id >= c->vocab || c->pad_id < 0 || c->pad_id >= c->vocab) return fail(NT_ERANGE, "bos_id/pad_id outside the vocabulary");
   if (!(c->ln_eps > 0.f)) return fail(NT_EINVAL, "ln_eps must be positive");
-  if (c->pipeline_lanes < 0 || c->pipeline_lanes > 8 || c->reserved != 0) return fail(NT_EINVAL, "pipeline_lanes must be in [0,8] and reserved 0");
+  if (c->ln_l1 != 0 && c->ln_l1 != 1) return fail(NT_EINVAL, "ln_l1 must be 0 or 1");
+  if (c->pipeline_lanes < 0 || c->pipeline_lanes > 8 ) return fail(NT_EINVAL, "pipeline_lanes must be in [0,8]");
   return NT_OK;
 }
 
@@ -607,6 +610,7 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
   if (!m || !d_src || !d_len) return fail(NT_EINVAL, "null argument");
   if (B < 1 || S < 1) return fail(NT_EINVAL, "B and S must be >= 1");
   const nt_config &c = m->c;
+  const nt::LnEps lne = ln_eps_of(c);
   if (S > c.max_len) return fail(NT_ESHAPE, "S %d exceeds max_len %d", S, c.max_len);
   if ((int64_t)B * S > m->max_tokens || B > m->max_rows) return fail(NT_ENOMEM, "batch %d x %d exceeds the arena (%lld tokens, %lld rows)", B, S, (long long)m->max_tokens, (long long)m->max_rows);
   hipStream_t s = as_stream(hip_stream);
@@ -632,10 +636,10 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
     e.bias = L.self.bqkv; e.scale = qscale; e.scale_cols = d; e.dst0 = m->qkv; e.ld0 = 3 * d; e.n_split = 3 * d;
     if (fused_ln(L.self.Wqkv_p, 3 * d)) {
       KT(K_GEMM_ENC_QKV, gemm_bytes(Md, dd, 3 * dd, 4, ea, false), 6 * Md * dd * dd,
-         nt::launch_gemm_stream_ln(true, m->x, d, nt::GemmLayerNorm{L.ln1.g, L.ln1.b, c.ln_eps}, L.self.Wqkv_p, M, 3 * d, d, e, s));
+         nt::launch_gemm_stream_ln(true, m->x, d, nt::GemmLayerNorm{L.ln1.g, L.ln1.b, lne}, L.self.Wqkv_p, M, 3 * d, d, e, s));
     } else {
       KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
-         nt::launch_layer_norm(m->x, M, d, L.ln1.g, L.ln1.b, c.ln_eps, m->a_enc, ln_mode, lo_d, s));
+         nt::launch_layer_norm(m->x, M, d, L.ln1.g, L.ln1.b, lne, m->a_enc, ln_mode, lo_d, s));
       KT(K_GEMM_ENC_QKV, gemm_bytes(Md, dd, 3 * dd, ea, ea, false), 6 * Md * dd * dd,
          nt::launch_gemm(amode, kEncF32, m->a_enc, lo_of(m->a_enc, lo_d), d, L.self.Wqkv, M, 3 * d, d, e, s, L.self.Wqkv_p));
     }
@@ -651,10 +655,10 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
       f1.dst_lo_offset = kEncF32 ? lo_F : 0;
       if (fused_ln(L.ffn.W1_p, F)) {
         KT(K_GEMM_ENC_FFN, gemm_bytes(Md, dd, F, 4, ea, false), 2 * Md * dd * F,
-           nt::launch_gemm_stream_ln(false, m->x, d, nt::GemmLayerNorm{L.ln2.g, L.ln2.b, c.ln_eps}, L.ffn.W1_p, M, F, d, f1, s));
+           nt::launch_gemm_stream_ln(false, m->x, d, nt::GemmLayerNorm{L.ln2.g, L.ln2.b, lne}, L.ffn.W1_p, M, F, d, f1, s));
       } else {
         KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
-           nt::launch_layer_norm(m->x, M, d, L.ln2.g, L.ln2.b, c.ln_eps, m->a_enc, ln_mode, lo_d, s));
+           nt::launch_layer_norm(m->x, M, d, L.ln2.g, L.ln2.b, lne, m->a_enc, ln_mode, lo_d, s));
         KT(K_GEMM_ENC_FFN, gemm_bytes(Md, dd, F, ea, ea, false), 2 * Md * dd * F,
            nt::launch_gemm(amode, false, m->a_enc, lo_of(m->a_enc, lo_d), d, L.ffn.W1, M, F, d, f1, s, L.ffn.W1_p));
       }
@@ -671,13 +675,13 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
   m->enc_out_valid = !all_fused;
   if (!all_fused)
     KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
-       nt::launch_layer_norm(m->x, M, d, m->enc_final.g, m->enc_final.b, c.ln_eps, m->enc_out, ln_mode, lo_d, s));
+       nt::launch_layer_norm(m->x, M, d, m->enc_final.g, m->enc_final.b, lne, m->enc_out, ln_mode, lo_d, s));
   for (int l = 0; l < c.n_dec; l++) {
     nt::GemmEpilogue e;
     e.bias = m->dec[l].cross.bkv; e.dst0 = m->cross[l]; e.ld0 = 2 * d; e.n_split = 2 * d;
     if (all_fused)
       KT(K_GEMM_CROSS_KV, gemm_bytes(Md, dd, 2 * dd, 4, ca, false), 4 * Md * dd * dd,
-         nt::launch_gemm_stream_ln(false, m->x, d, nt::GemmLayerNorm{m->enc_final.g, m->enc_final.b, c.ln_eps},
+         nt::launch_gemm_stream_ln(false, m->x, d, nt::GemmLayerNorm{m->enc_final.g, m->enc_final.b, lne},
                                    m->dec[l].cross.Wkv_p, M, 2 * d, d, e, s));
     else
       KT(K_GEMM_CROSS_KV, gemm_bytes(Md, dd, 2 * dd, ea, ca, false), 4 * Md * dd * dd,
@@ -696,6 +700,7 @@ namespace {
 int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, const int32_t *d_forced,
                 int32_t *d_out, float *d_logits, hipStream_t s) {
   const nt_config &c = m->c;
+  const nt::LnEps lne = ln_eps_of(c);
   const int d = c.d_model, F = dec_ffn(&c), H = dec_heads(&c), V = c.vocab, S = m->S;
   const float qscale = 1.0f / std::sqrt((float)(d / H));
   const long self_stride = (long)T * 2 * d;
@@ -724,7 +729,7 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
     a.t = t; a.rows_prev = rows_prev; a.rows_now = rows_now; a.d = d; a.vocab = V; a.bos_id = c.bos_id; a.pad_id = c.pad_id;
     a.pk = d_logits ? nullptr : m->pk; a.n_partials = partials_prev; a.out = d_out; a.out_ld = T;
     a.forced = d_forced; a.forced_ld = T; a.E = m->E; a.pe = m->pe; a.gamma = m->dec[0].ln1.g; a.beta = m->dec[0].ln1.b;
-    a.eps = c.ln_eps; a.z = m->z; a.a = nullptr; a.flags = m->flags;
+    a.eps = lne; a.z = m->z; a.a = nullptr; a.flags = m->flags;
     a.prev_cert = prev_cert ? 1 : 0; a.tok = m->tok; a.slot_of_row = m->slot_of_row; a.final_key = m->final_key;
     a.cert_count = m->flags + 4;
     if (d_logits && rows_now == 0) break;  // no tokens to collect in this mode (pk == nullptr)
@@ -748,16 +753,16 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
                         const nt::GemmEpilogue &e, bool c_f32 = true) -> int {
       const double by = gemm_bytes(Rd, K, N, e.resid != nullptr), fl = 2 * Rd * K * (double)N;
       if (R <= kSkinnyMaxRows && nt::skinny_gemm_supported(K, ln != nullptr)) {
-        KT(id, by, fl, nt::launch_skinny_gemm(A, K, Wt, R, N, K, ln ? ln->g : nullptr, ln ? ln->b : nullptr, c.ln_eps, e, s));
+        KT(id, by, fl, nt::launch_skinny_gemm(A, K, Wt, R, N, K, ln ? ln->g : nullptr, ln ? ln->b : nullptr, lne, e, s));
         return NT_OK;
       }
       const bool planes = streams(N, K, Wp, ln != nullptr);
       if (ln && planes) {  // the LayerNorm runs inside the projection, while the tile is loaded
-        KT(id, by, fl, nt::launch_gemm_stream_ln(c_f32, A, K, nt::GemmLayerNorm{ln->g, ln->b, c.ln_eps}, Wp, R, N, K, e, s));
+        KT(id, by, fl, nt::launch_gemm_stream_ln(c_f32, A, K, nt::GemmLayerNorm{ln->g, ln->b, lne}, Wp, R, N, K, e, s));
         return NT_OK;
       }
       if (ln) {
-        KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd, nt::launch_layer_norm(A, R, K, ln->g, ln->b, c.ln_eps, m->a32, nt::OUT_F32, 0, s));
+        KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd, nt::launch_layer_norm(A, R, K, ln->g, ln->b, lne, m->a32, nt::OUT_F32, 0, s));
         A = m->a32;
       }
       if (planes)  // A is a plane pair written by the attention kernel
@@ -808,7 +813,7 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
     // final LayerNorm as a head/tail plane pair (the planes share the a32 buffer), then the output layer
     _Float16 *h_hi = (_Float16 *)m->a32, *h_lo = h_hi + (long)m->max_rows * d;
     KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd,
-       nt::launch_layer_norm(m->z, R, d, m->dec_final.g, m->dec_final.b, c.ln_eps, h_hi, nt::OUT_PLANES,
+       nt::launch_layer_norm(m->z, R, d, m->dec_final.g, m->dec_final.b, lne, h_hi, nt::OUT_PLANES,
                              (long)m->max_rows * d, s, m->lo_norm));
     if (d_logits) {
       nt::GemmEpilogue e;
@@ -874,7 +879,7 @@ int nt_debug_encoder_out(nt_model *m, float *d_out, void *hip_stream) {
   if (!m->encoded) return fail(NT_ESTATE, "no encoded batch");
   const long n = (long)m->B * m->S * m->c.d_model;
   if (!m->enc_out_valid) {  // the final LayerNorm ran fused into the cross projections: produce its output now
-    HIP_TRY(nt::launch_layer_norm(m->x, m->B * m->S, m->c.d_model, m->enc_final.g, m->enc_final.b, m->c.ln_eps, m->enc_out,
+    HIP_TRY(nt::launch_layer_norm(m->x, m->B * m->S, m->c.d_model, m->enc_final.g, m->enc_final.b, ln_eps_of(m->c), m->enc_out,
                                   kEncF32 ? nt::OUT_PLANES : nt::OUT_F16, (long)m->max_tokens * m->c.d_model,
                                   as_stream(hip_stream)));
     m->enc_out_valid = true;

@@ -10,6 +10,21 @@ namespace nt {
 // Epilogue, applied to acc (fp32):  v = acc + bias[n];  if (n < scale_cols) v *= scale;
 // if (relu) v = max(v,0);  if (resid) v += resid[m*ldr+n];  then columns [0,n_split) go to
 // dst0[m*ld0+n] and columns [n_split,N) to dst1[m*ld1+(n-n_split)].
+// Flavour of a layer normalisation y = gamma * (x - mean) * r + beta.  Vanilla: r = 1 / sqrt(var + eps) with the
+// biased variance.  L1-norm (Sec. 3.1 "FP16 Inference"): r = 1 / (sqrt(pi/2) * mean|x - mean| + eps), the scaled
+// mean absolute deviation, which equals the standard deviation for normally distributed activations.
+struct LnEps {
+  float eps = 0.f;
+  int l1 = 0;
+};
+#ifdef __HIPCC__
+// what a row sums over its centred elements, and how the mean of those terms becomes the scale r
+__device__ __forceinline__ float ln_term(float c, int l1) { return l1 ? fabsf(c) : c * c; }
+__device__ __forceinline__ float ln_rscale(float mean_term, LnEps e) {
+  return e.l1 ? 1.0f / (1.2533141373f * mean_term + e.eps) : 1.0f / sqrtf(mean_term + e.eps);
+}
+#endif
+
 struct GemmEpilogue {
   const float *bias = nullptr;
   float scale = 1.f;
@@ -41,7 +56,7 @@ hipError_t launch_gemm(int a_mode, bool c_f32, const void *A, const void *A_lo, 
 // the LDS, the weights stream through registers in fragment order.
 struct GemmLayerNorm {
   const float *gamma = nullptr, *beta = nullptr;
-  float eps = 0.f;
+  LnEps eps;
 };
 bool gemm_stream_supported(int N, int K);
 // C = LayerNorm(X) * Wt^T: X [M][ldx] fp32 is normalised and split into planes while the tile is loaded
@@ -55,7 +70,7 @@ hipError_t launch_gemm_stream(bool c_f32, const _Float16 *A, const _Float16 *A_l
 // the row width, 256 or 512).  K must be a multiple of 256.
 bool skinny_gemm_supported(int K, bool with_ln);
 hipError_t launch_skinny_gemm(const float *A, long lda, const _Float16 *Wt, int M, int N, int K, const float *ln_g,
-                              const float *ln_b, float ln_eps, const GemmEpilogue &e, hipStream_t s);
+                              const float *ln_b, LnEps ln_eps, const GemmEpilogue &e, hipStream_t s);
 
 // ---- output projection fused with row arg-max ------------------------------------------
 // For every row m < M: the largest of h[m,:] . W_out[v,:] over v < N, lowest v on ties, as packed
@@ -132,10 +147,10 @@ hipError_t launch_argmax_select(const unsigned long long *pk, const float *ps, i
 hipError_t launch_embed_src(const int32_t *src, const int32_t *len, int32_t *len_out, int B, int S, int d, int vocab,
                             int pad_id, const _Float16 *E, const float *pe, float *x, int32_t *flags, hipStream_t s);
 
-// out = gamma * (x - mean) / sqrt(var + eps) + beta per row of d.
+// out = gamma * (x - mean) * r + beta per row of d, r as LnEps says.
 enum OutMode { OUT_F16 = 0, OUT_F32 = 1, OUT_PLANES = 2 };  // OUT_PLANES: fp16 head at out, tail at out + lo_offset
 // lo_norm (OUT_PLANES only, optional): receives the Euclidean norm of every row's tail plane.
-hipError_t launch_layer_norm(const float *x, int M, int d, const float *gamma, const float *beta, float eps,
+hipError_t launch_layer_norm(const float *x, int M, int d, const float *gamma, const float *beta, LnEps eps,
                              void *out, int out_mode, long lo_offset, hipStream_t s, float *lo_norm = nullptr);
 
 // out[i] = hi[i] + lo[i] (debug readback of a head/tail plane pair)
@@ -162,7 +177,7 @@ struct StepBeginArgs {
   const _Float16 *E;
   const float *pe;
   const float *gamma, *beta;
-  float eps;
+  LnEps eps;
   float *z, *a;
   int32_t *flags;
   // certified arg-max of the previous step (prev_cert != 0): token = tok[r], or the key in

@@ -26,7 +26,7 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long x)
 }
 
 // lane holds elements lane + 64*i, i < ne
-__device__ __forceinline__ void row_layer_norm(float (&v)[MAX_PER_LANE], int ne, int d, float eps, int lane,
+__device__ __forceinline__ void row_layer_norm(float (&v)[MAX_PER_LANE], int ne, int d, LnEps eps, int lane,
                                                const float *gamma, const float *beta) {
   float s = 0.f;
 #pragma unroll
@@ -38,9 +38,9 @@ __device__ __forceinline__ void row_layer_norm(float (&v)[MAX_PER_LANE], int ne,
   for (int i = 0; i < MAX_PER_LANE; i++)
     if (i < ne) {
       const float c = v[i] - mean;
-      q += c * c;
+      q += ln_term(c, eps.l1);
     }
-  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
+  const float rstd = ln_rscale(wave_sum(q) / (float)d, eps);
 #pragma unroll
   for (int i = 0; i < MAX_PER_LANE; i++)
     if (i < ne) v[i] = gamma[lane + 64 * i] * ((v[i] - mean) * rstd) + beta[lane + 64 * i];
@@ -86,7 +86,7 @@ hipError_t launch_embed_src(const int32_t *src, const int32_t *len, int32_t *len
 
 template <int MODE>
 __global__ __launch_bounds__(256) void layer_norm_kernel(const float *x, int M, int d, const float *gamma,
-                                                         const float *beta, float eps, void *out, long lo_offset,
+                                                         const float *beta, LnEps eps, void *out, long lo_offset,
                                                          float *lo_norm) {
   const int lane = threadIdx.x & 63;
   const long r = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(256) void layer_norm_kernel(const float *x, int M, 
   }
 }
 
-hipError_t launch_layer_norm(const float *x, int M, int d, const float *gamma, const float *beta, float eps,
+hipError_t launch_layer_norm(const float *x, int M, int d, const float *gamma, const float *beta, LnEps eps,
                              void *out, int out_mode, long lo_offset, hipStream_t s, float *lo_norm) {
   if (M <= 0) return hipSuccess;
   dim3 grid((M + 3) / 4), block(256);

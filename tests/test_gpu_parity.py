@@ -355,6 +355,44 @@ def test_relative_positions_small(nt, oracle):
     _check_workload_sample(nt, oracle, "C0", 8, 512, 0.87, rpr_clip=16, n_heads=4, d_ffn=256)
 
 
+# ------------------------------------------------------------------------------ L1-norm layer normalisation
+def _check_encoder_and_logits(torch, gm, om, cfg, src, T, seed):
+    """Encoder outputs and teacher-forced logits on random targets for one padded batch, every row."""
+    src = sort_desc(src)
+    ids, lens = pad(src, cfg["pad_id"])
+    B, S = ids.shape
+    gm.encode(torch.from_numpy(ids).cuda(), torch.from_numpy(lens).cuda())
+    enc = torch.empty(B, S, cfg["d_model"], dtype=torch.float32, device="cuda")
+    gm.debug_encoder_out(enc)
+    enc = enc.cpu().numpy().astype(np.float64)
+    tgt = np.random.default_rng(seed).integers(4, cfg["vocab"], size=(B, T)).astype(np.int32)
+    tgt[:, 0] = cfg["bos_id"]
+    logits = torch.empty(B, T, cfg["vocab"], dtype=torch.float32, device="cuda")
+    gm.debug_teacher_forced_logits(torch.from_numpy(tgt).cuda(), logits)
+    logits = logits.cpu().numpy().astype(np.float64)
+    for i, s in enumerate(src):
+        assert rel_l2(enc[i, : len(s)], om.encode(s)) <= 2e-3
+        want = om.teacher_forced(s, tgt[i])
+        assert np.abs(logits[i] - want).max() <= 2e-2 and rel_l2(logits[i], want) <= 2e-3
+
+
+def test_l1_norm_layer_normalisation(nt, oracle, torch_cuda):
+    """Every layer normalisation in its L1-norm form (Sec. 3.1): the separate kernel, the one fused into the
+    small-batch decoder projections and the one fused into the fill of the streaming projections."""
+    # a handful of rows: one-round-trip decoder kernels, LayerNorm in their prologue
+    gm, om, cfg, sents = _check_workload_sample(nt, oracle, "C0", 8, 512, 0.87, ln_l1=1)
+    _check_encoder_and_logits(torch_cuda, gm, om, cfg, sents, 5, 71)
+    # the L1 model is another model: the vanilla oracle must not accept these encoder outputs
+    blob = nt_synth.make_weights(cfg, seed=0, random_affine=True)
+    vanilla = oracle.Model(dict(cfg, ln_l1=0), blob)
+    assert rel_l2(om.encode(sents[0]), vanilla.encode(sents[0])) > 1e-2
+    # hundreds of rows per batch: streaming projections with the normalisation in their fill, certified arg-max
+    gm, om, cfg, sents = _check_workload_sample(nt, oracle, "C1", 700, 16384, 0.99, ln_l1=1)
+    _check_encoder_and_logits(torch_cuda, gm, om, cfg, [s[:30] for s in sents[:150]][::6], 4, 72)
+    # FFN blocks (their own normalisation) and 8 heads
+    _check_workload_sample(nt, oracle, "C3", 64, 4096, 0.97, ln_l1=1)
+
+
 # ------------------------------------------------------------------------------ C5 (shape of the submitted student)
 def test_c5_submitted_student_shape(nt, oracle, torch_cuda):
     """Student-3-1-512 (Table 2, Sec. 5): 3 encoder layers with 8 heads and FFN 2,048, one decoder layer

@@ -104,6 +104,7 @@ def test_load_rejects_bad_config_and_blob_before_touching_the_gpu():
                      ("dec_n_heads", 3), ("dec_n_heads", 16), ("dec_d_ffn", 100), ("dec_d_ffn", -2)):
         c = nt.make_config(dict(cfg, **{key: val}), 4096)
         assert load(c, blob.nbytes) == -2, key
+    assert load(nt.make_config(dict(cfg, ln_l1=2), 4096), blob.nbytes) == -1
     c = nt.make_config(dict(cfg, bos_id=cfg["vocab"]), 4096)
     assert load(c, blob.nbytes) == -6
     assert L.nt_load_weights(None, None, 0, None, C.byref(h)) == -1
