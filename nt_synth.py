@@ -134,8 +134,13 @@ def blob_numel(cfg: dict) -> int:
     return blob_offsets(cfg)["__total__"][0]
 
 
-def make_weights(cfg: dict, seed: int = 0, random_affine: bool = False) -> np.ndarray:
+def make_weights(cfg: dict, seed: int = 0, random_affine: bool = False, eos_gain: float | None = None) -> np.ndarray:
     """Draw the fp16 weight blob.
+
+    eos_gain (models with their own output matrix only): after the draw, the EOS row of the output matrix is
+    multiplied by this factor.  Logits of a random model are close to N(0, 1), so the row's logit wins a step
+    with probability about P(N(0,1) > 4 / eos_gain): sentences then end at varied, data-dependent steps, which
+    random weights alone never produce (EOS would win about once in `vocab` steps).
 
     One PCG64 stream; tensors are drawn in blob order.  Every matrix, bias and
     embedding entry is N(0, 1/d) (std d^-1/2) rounded to fp16; LayerNorm gain is 1
@@ -155,7 +160,12 @@ def make_weights(cfg: dict, seed: int = 0, random_affine: bool = False) -> np.nd
         else:
             t = std * rng.standard_normal(shape)
         parts.append(np.asarray(t, dtype=np.float64).astype(np.float16).ravel())
-    return np.concatenate(parts)
+    blob = np.concatenate(parts)
+    if eos_gain is not None:
+        assert not cfg["tie_output"], "eos_gain needs a separate output matrix"
+        row = blob_view(cfg, blob, "W_out")[EOS_ID]
+        row[:] = (row.astype(np.float64) * eos_gain).astype(np.float16)
+    return blob
 
 
 def blob_view(cfg: dict, blob: np.ndarray, name: str) -> np.ndarray:

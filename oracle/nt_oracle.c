@@ -375,11 +375,14 @@ int ora_encode(const ora_model *m, const int32_t *src, int32_t len, double *enc_
 }
 
 /*
- * Greedy decode for exactly n_steps steps starting from BOS (EOS is an ordinary token).
- * out: [n_steps]; margin (optional): [n_steps] top-1 minus top-2 logit at each step.
+ * Greedy search from BOS (Sec. 3.3 "Greedy Search"): at every step the token with the largest logit, lowest id on
+ * ties.  eos_id < 0: exactly n_steps steps, EOS an ordinary token (the benchmark's fixed-length rule).
+ * eos_id >= 0: the sentence ends with the first EOS, which is stored, or after n_steps tokens, whichever comes
+ * first.  out: [n_steps]; margin (optional): [n_steps] top-1 minus top-2 logit at each step taken.
+ * Returns the number of tokens stored, or a negative error.
  */
-int ora_greedy(const ora_model *m, const int32_t *src, int32_t len, int32_t n_steps, int32_t *out,
-               double *margin) {
+static int greedy_search(const ora_model *m, const int32_t *src, int32_t len, int32_t n_steps, int32_t eos_id,
+                         int32_t *out, double *margin) {
   if (!m || len < 1 || len > m->c.max_len || n_steps < 0 || n_steps > m->c.max_len) return -1;
   int d = m->c.d_model, V = m->c.vocab;
   double *enc = (double *)malloc(sizeof(double) * (size_t)len * d);
@@ -387,8 +390,8 @@ int ora_greedy(const ora_model *m, const int32_t *src, int32_t len, int32_t n_st
   dec_state *s = dec_begin(m, enc, len, n_steps > 0 ? n_steps : 1);
   double *logits = (double *)malloc(sizeof(double) * (size_t)V);
   int32_t y = m->c.bos_id;
-  int rc = 0;
-  for (int t = 0; t < n_steps; t++) {
+  int rc = 0, t = 0;
+  while (t < n_steps) {
     dec_step(m, s, y, t, logits);
     int best = 0;
     double second = -INFINITY;
@@ -400,9 +403,24 @@ int ora_greedy(const ora_model *m, const int32_t *src, int32_t len, int32_t n_st
     }
     out[t] = y = best;
     if (margin) margin[t] = logits[best] - second;
+    t++;
+    if (eos_id >= 0 && y == eos_id) break;
   }
   free(logits); dec_end(s); free(enc);
-  return rc;
+  return rc ? rc : t;
+}
+
+int ora_greedy(const ora_model *m, const int32_t *src, int32_t len, int32_t n_steps, int32_t *out,
+               double *margin) {
+  int n = greedy_search(m, src, len, n_steps, -1, out, margin);
+  return n < 0 ? n : 0;
+}
+
+/* EOS-terminated greedy search; returns the number of tokens stored (the last one is EOS unless the cap cut it) */
+int ora_greedy_eos(const ora_model *m, const int32_t *src, int32_t len, int32_t max_steps, int32_t eos_id,
+                   int32_t *out, double *margin) {
+  if (!m || eos_id < 0 || eos_id >= m->c.vocab) return -1;
+  return greedy_search(m, src, len, max_steps, eos_id, out, margin);
 }
 
 /* logits[t] for t < T when the decoder is fed tgt_in[0..T) (tgt_in[0] is normally BOS) */
@@ -425,8 +443,8 @@ int ora_teacher_forced(const ora_model *m, const int32_t *src, int32_t len, cons
  * out_offsets is written here.  Sentences of length 0 produce nothing.  Parallel over
  * sentences only.  Returns the number of threads used, or a negative error.
  */
-int ora_translate(const ora_model *m, const int32_t *tokens, const int64_t *offsets, int64_t N,
-                  int32_t *out, int64_t *out_offsets, int32_t n_threads) {
+static int translate(const ora_model *m, const int32_t *tokens, const int64_t *offsets, int64_t N, int32_t eos_id,
+                     int32_t pad_id, int32_t *out, int64_t *out_offsets, int32_t *out_len, int32_t n_threads) {
   if (!m) return -1;
   out_offsets[0] = 0;
   for (int64_t i = 0; i < N; i++) {
@@ -443,10 +461,31 @@ int ora_translate(const ora_model *m, const int32_t *tokens, const int64_t *offs
   for (int64_t i = 0; i < N; i++) {
     int32_t len = (int32_t)(offsets[i + 1] - offsets[i]);
     if (len == 0) continue;
-    if (ora_greedy(m, tokens + offsets[i], len, ora_n_steps(len), out + out_offsets[i], NULL)) {
+    int n = greedy_search(m, tokens + offsets[i], len, ora_n_steps(len), eos_id, out + out_offsets[i], NULL);
+    if (n < 0) {
 #pragma omp atomic write
       err = 1;
+    } else if (out_len) {
+      out_len[i] = n;
+      for (int64_t k = out_offsets[i] + n; k < out_offsets[i + 1]; k++) out[k] = pad_id;
     }
   }
   return err ? -2 : used;
+}
+
+int ora_translate(const ora_model *m, const int32_t *tokens, const int64_t *offsets, int64_t N,
+                  int32_t *out, int64_t *out_offsets, int32_t n_threads) {
+  return translate(m, tokens, offsets, N, -1, 0, out, out_offsets, NULL, n_threads);
+}
+
+/*
+ * The same with EOS-terminated greedy search: sentence i keeps its ora_n_steps(len_i) output slots, out_len[i]
+ * of them hold its tokens (ending with EOS unless the cap cut it) and the rest hold pad_id.  A sentence of
+ * length 0 gets out_len 0.
+ */
+int ora_translate_eos(const ora_model *m, const int32_t *tokens, const int64_t *offsets, int64_t N, int32_t eos_id,
+                      int32_t pad_id, int32_t *out, int64_t *out_offsets, int32_t *out_len, int32_t n_threads) {
+  if (!m || !out_len || eos_id < 0 || eos_id >= m->c.vocab || pad_id < 0 || pad_id >= m->c.vocab) return -1;
+  for (int64_t i = 0; i < N; i++) out_len[i] = 0;
+  return translate(m, tokens, offsets, N, eos_id, pad_id, out, out_offsets, out_len, n_threads);
 }

@@ -75,6 +75,10 @@ def lib():
         L.ora_encode.argtypes = [p, p, i32, p]
         L.ora_greedy.restype = i32
         L.ora_greedy.argtypes = [p, p, i32, i32, p, p]
+        L.ora_greedy_eos.restype = i32
+        L.ora_greedy_eos.argtypes = [p, p, i32, i32, i32, p, p]
+        L.ora_translate_eos.restype = i32
+        L.ora_translate_eos.argtypes = [p, p, p, i64, i32, i32, p, p, p, i32]
         L.ora_teacher_forced.restype = i32
         L.ora_teacher_forced.argtypes = [p, p, i32, p, i32, p]
         L.ora_translate.restype = i32
@@ -198,6 +202,17 @@ class Model:
             raise ValueError(f"oracle: greedy failed ({rc})")
         return out, margin
 
+    def greedy_eos(self, src, eos_id: int, max_steps: int | None = None):
+        """EOS-terminated greedy search: (tokens [n] int32 ending with EOS unless the cap cut it, margins [n])."""
+        src = _i32(src)
+        cap = n_steps(src.size) if max_steps is None else max_steps
+        out = np.empty(max(cap, 1), dtype=np.int32)
+        margin = np.empty(max(cap, 1))
+        n = lib().ora_greedy_eos(self._h, _ptr(src), src.size, cap, eos_id, _ptr(out), _ptr(margin))
+        if n < 0:
+            raise ValueError(f"oracle: greedy failed ({n})")
+        return out[:n].copy(), margin[:n].copy()
+
     def teacher_forced(self, src, tgt_in) -> np.ndarray:
         src, tgt_in = _i32(src), _i32(tgt_in)
         out = np.empty((tgt_in.size, self.cfg["vocab"]))
@@ -218,3 +233,20 @@ class Model:
         if used < 0:
             raise ValueError(f"oracle: translate failed ({used})")
         return out[:total], oo, used
+
+    def translate_eos(self, tokens, offsets, eos_id: int, n_threads: int = 0):
+        """EOS-terminated translate.  Returns (out int32 in the fixed-length layout, padded after each
+        sentence's end; out offsets int64; out lengths int32; threads used)."""
+        tokens = _i32(tokens)
+        offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+        N = offsets.size - 1
+        lens = np.diff(offsets)
+        total = int(sum(n_steps(int(l)) for l in lens if l > 0))
+        out = np.empty(max(total, 1), dtype=np.int32)
+        oo = np.empty(N + 1, dtype=np.int64)
+        ol = np.zeros(max(N, 1), dtype=np.int32)
+        used = lib().ora_translate_eos(self._h, _ptr(tokens), _ptr(offsets), N, eos_id, self.cfg["pad_id"], _ptr(out),
+                                       _ptr(oo), _ptr(ol), n_threads)
+        if used < 0:
+            raise ValueError(f"oracle: translate failed ({used})")
+        return out[:total], oo, ol[:N], used

@@ -303,6 +303,54 @@ def test_argmax_without_log_softmax(oracle):
     assert np.allclose(margin, top2[:, 1] - top2[:, 0], atol=1e-12) and (margin >= 0).all()
 
 
+def test_eos_terminated_greedy_search(oracle):
+    """EOS-terminated greedy search (Sec. 3.3): pinned against (a) the fixed-length search, of which it is the
+    prefix up to and including the first EOS, (b) a search written here that recomputes the whole prefix
+    through the teacher-forced call at every step, (c) the cap."""
+    cfg = tiny(vocab=300)
+    eos = nt_synth.EOS_ID
+    blob = nt_synth.make_weights(cfg, seed=13, random_affine=True, eos_gain=1.8)
+    m = oracle.Model(cfg, blob)
+    rng = np.random.default_rng(14)
+    ended = capped = 0
+    for n in (1, 2, 3, 5, 8, 9, 12, 17, 20, 24, 30, 33):
+        src = rng.integers(4, cfg["vocab"], size=n)
+        fixed, _ = m.greedy(src)
+        got, margin = m.greedy_eos(src, eos)
+        hits = np.nonzero(fixed == eos)[0]
+        want = fixed[: hits[0] + 1] if len(hits) else fixed
+        assert np.array_equal(got, want)
+        assert 1 <= len(got) <= oracle.n_steps(n) and (got[:-1] != eos).all() and len(margin) == len(got)
+        ended += got[-1] == eos
+        capped += got[-1] != eos
+        # step-by-step search that recomputes everything from scratch
+        prefix, mine = [cfg["bos_id"]], []
+        while len(mine) < oracle.n_steps(n):
+            y = int(np.argmax(m.teacher_forced(src, np.array(prefix))[-1]))
+            mine.append(y)
+            prefix.append(y)
+            if y == eos:
+                break
+        assert np.array_equal(got, mine)
+        # a tighter cap cuts the sentence without an EOS
+        if len(got) > 2:
+            cut, _ = m.greedy_eos(src, eos, max_steps=len(got) - 1)
+            assert np.array_equal(cut, got[:-1])
+    assert ended >= 3 and capped >= 3          # the stand-in weights produce both kinds of ending
+    # the translate call: fixed-length slots, lengths, padding after the end; eos outside the vocabulary is refused
+    sents = [rng.integers(4, cfg["vocab"], size=n) for n in (7, 0, 15, 4)]
+    off = np.concatenate([[0], np.cumsum([len(x) for x in sents])])
+    out, oo, ol, _ = m.translate_eos(np.concatenate(sents), off, eos)
+    assert np.array_equal(np.diff(oo), [oracle.n_steps(len(x)) if len(x) else 0 for x in sents]) and ol[1] == 0
+    for i, x in enumerate(sents):
+        if len(x):
+            g, _ = m.greedy_eos(x, eos)
+            assert ol[i] == len(g) and np.array_equal(out[oo[i]: oo[i] + ol[i]], g)
+            assert (out[oo[i] + ol[i]: oo[i + 1]] == cfg["pad_id"]).all()
+    with pytest.raises(ValueError):
+        m.greedy_eos(sents[0], cfg["vocab"])
+
+
 def test_tied_embedding_collapse(oracle):
     """With tied output weights, sqrt(d) embedding scale and random weights the logit of the
     previous token dominates (~ sqrt(d) |E_y|^2 / sigma_z against N(0,1) for the others), so
