@@ -140,6 +140,27 @@ int nt_decode_greedy(nt_model *m, int32_t B, int32_t n_steps, const int32_t *h_r
                      void *hip_stream);
 
 /*
+ * Greedy decoding that ends a sentence at its end symbol (Sec. 3.3 "Greedy Search": the paper's
+ * systems decode with beam size 1 until EOS, where the benchmark's rule above runs a fixed number
+ * of steps).  Row b ends with the first eos_id it emits, which is stored, or after
+ * h_row_steps[b] tokens (n_steps if h_row_steps is NULL), whichever comes first.
+ *   d_out [B, n_steps] int32, device: the tokens of row b, then pad_id.
+ *   d_out_len [B] int32, device: number of tokens of row b (EOS included).
+ * Rows that have ended leave the computation: the rows still decoding are kept as a dense prefix
+ * on the device (their caches stay where they are and are reached through a row map), and the
+ * device publishes their count after every step in pinned host memory.  The count only falls, so
+ * whatever the host last read is a valid upper bound: it sizes every later launch with it and
+ * stops launching once it reads zero.  The host never waits for the stream to drain, but it
+ * enqueues at most a few steps ahead of the device, so the call returns when the device is
+ * within those few steps of the end; the outputs are complete once hip_stream has been
+ * synchronised.  Tokens are those nt_decode_greedy produces, cut after the first EOS.
+ * Errors: as nt_decode_greedy; NT_ERANGE for eos_id outside the vocabulary; NT_EHIP if the device
+ * publishes no progress for 30 seconds.
+ */
+int nt_decode_greedy_eos(nt_model *m, int32_t B, int32_t n_steps, const int32_t *h_row_steps, int32_t eos_id,
+                         int32_t *d_out, int32_t *d_out_len, void *hip_stream);
+
+/*
  * Translate N sentences end to end (dynamic batching: Sec. 3.1 "Dynamic Batching"; sorting by
  * descending length and sbatch/wbatch caps: Sec. 3.3 "Graph Optimization", "Better Decoding
  * Configurations").
@@ -157,6 +178,17 @@ int nt_decode_greedy(nt_model *m, int32_t B, int32_t n_steps, const int32_t *h_r
 int nt_translate_batch(nt_model *m, const int32_t *h_tokens, const int64_t *h_offsets, int64_t N,
                        int64_t token_budget, int32_t max_rows, int32_t *h_out, int64_t *h_out_offsets,
                        void *hip_stream);
+
+/*
+ * The same with EOS-terminated greedy decoding (nt_decode_greedy_eos; cap nt_n_steps(len_i) per
+ * sentence).  Sentence i keeps its nt_n_steps(len_i) slots in h_out: h_out_len[i] tokens, the last
+ * one eos_id unless the cap cut the sentence, then pad_id.  h_out_len [N] is written by the call
+ * (0 for an empty sentence).  The pipeline lanes advance their batches step by step in turn, each
+ * sized by the latest count of rows still decoding that its device side has published.
+ */
+int nt_translate_batch_eos(nt_model *m, const int32_t *h_tokens, const int64_t *h_offsets, int64_t N,
+                           int64_t token_budget, int32_t max_rows, int32_t eos_id, int32_t *h_out,
+                           int64_t *h_out_offsets, int32_t *h_out_len, void *hip_stream);
 
 /*
  * Host-only batch planner used by nt_translate_batch (same passages).  Stable sort by

@@ -17,7 +17,7 @@ EXPORTS = ["nt_param_count", "nt_n_steps", "nt_load_weights", "nt_free", "nt_enc
            "nt_translate_batch", "nt_plan_batches", "nt_debug_encoder_out", "nt_debug_teacher_forced_logits",
            "nt_check_device_flags", "nt_device_bytes", "nt_last_error", "nt_debug_timing_enable",
            "nt_debug_timing_count", "nt_debug_timing_name", "nt_debug_timing_read", "nt_pipeline_lanes",
-           "nt_pipeline_lane", "nt_lane_stream"]
+           "nt_pipeline_lane", "nt_lane_stream", "nt_decode_greedy_eos", "nt_translate_batch_eos"]
 
 
 class NtConfig(C.Structure):
@@ -58,6 +58,8 @@ def load_library() -> C.CDLL:
         "nt_encode": (C.c_int, [p, p, p, i32, i32, p]),
         "nt_decode_greedy": (C.c_int, [p, i32, i32, p, p, p]),
         "nt_translate_batch": (C.c_int, [p, p, p, i64, i64, i32, p, p, p]),
+        "nt_decode_greedy_eos": (C.c_int, [p, i32, i32, p, i32, p, p, p]),
+        "nt_translate_batch_eos": (C.c_int, [p, p, p, i64, i64, i32, i32, p, p, p, p]),
         "nt_plan_batches": (C.c_int, [p, i64, i64, i32, p, p, C.POINTER(i64)]),
         "nt_debug_encoder_out": (C.c_int, [p, p, p]),
         "nt_debug_teacher_forced_logits": (C.c_int, [p, p, i32, i32, p, p]),
@@ -203,6 +205,16 @@ class Model:
         _check(lib().nt_decode_greedy(self._h, B, steps, rs.ctypes.data_as(C.c_void_p) if rs is not None else None,
                                       d_out.data_ptr(), _stream_ptr(stream)))
 
+    def decode_greedy_eos(self, B: int, steps: int, eos_id: int, d_out, d_out_len, row_steps=None, stream=None):
+        """EOS-terminated greedy decoding: d_out int32 cuda [B, steps], d_out_len int32 cuda [B]."""
+        assert d_out.is_cuda and d_out.is_contiguous() and d_out.numel() >= B * steps
+        assert d_out_len.is_cuda and d_out_len.is_contiguous() and d_out_len.numel() >= B
+        rs = None
+        if row_steps is not None:
+            rs = np.ascontiguousarray(row_steps, dtype=np.int32)
+        _check(lib().nt_decode_greedy_eos(self._h, B, steps, rs.ctypes.data_as(C.c_void_p) if rs is not None else None,
+                                          int(eos_id), d_out.data_ptr(), d_out_len.data_ptr(), _stream_ptr(stream)))
+
     def debug_encoder_out(self, d_out, stream=None):
         _check(lib().nt_debug_encoder_out(self._h, d_out.data_ptr(), _stream_ptr(stream)))
 
@@ -249,3 +261,19 @@ class Model:
                                         N, int(token_budget), int(max_rows), out.ctypes.data_as(C.c_void_p),
                                         oo.ctypes.data_as(C.c_void_p), _stream_ptr(stream)))
         return out[:total], oo
+
+    def translate_batch_eos(self, tokens, offsets, token_budget: int, eos_id: int, max_rows: int = 0, stream=None):
+        """EOS-terminated translate: returns (out int32 in the fixed-length slots, padded after each sentence's
+        end; out_offsets int64; out_len int32)."""
+        tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+        offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+        N = offsets.size - 1
+        total = sum(n_steps(int(l)) for l in np.diff(offsets) if l > 0) if N > 0 else 0
+        out = np.empty(max(total, 1), dtype=np.int32)
+        oo = np.empty(N + 1, dtype=np.int64)
+        ol = np.zeros(max(N, 1), dtype=np.int32)
+        _check(lib().nt_translate_batch_eos(self._h, tokens.ctypes.data_as(C.c_void_p),
+                                            offsets.ctypes.data_as(C.c_void_p), N, int(token_budget), int(max_rows),
+                                            int(eos_id), out.ctypes.data_as(C.c_void_p), oo.ctypes.data_as(C.c_void_p),
+                                            ol.ctypes.data_as(C.c_void_p), _stream_ptr(stream)))
+        return out[:total], oo, ol[:N]

@@ -512,11 +512,14 @@ __device__ __forceinline__ void load8(const void *p, float (&o)[8]) {
   }
 }
 
-template <int DH, bool KV_F32>
+// IND: query rows address the cache through `origin` (rows < 0 are skipped), and with kv_new the newest key/value
+// pair of a row is taken from there and stored into the cache on the way.
+template <int DH, bool KV_F32, bool IND>
 __global__ __launch_bounds__(256) void attn_decode_kernel(const float *q, const void *kv, long row_stride,
                                                           const int32_t *len, int n_keys, int rows, int d, int heads,
                                                           const float *rk, int clip, int qpos, float *ctx,
-                                                          long ctx_lo_offset) {
+                                                          long ctx_lo_offset, const int32_t *origin,
+                                                          const float *kv_new) {
   constexpr int LPK = DH / 8;              // lanes per key
   constexpr int G = 64 / LPK;              // keys per wave iteration
   constexpr int WPP = (DH >= 256) ? 4 : 1; // waves per (row, head) pair
@@ -528,7 +531,10 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const float *q, const 
   const int wip = (WPP == 4) ? wave : 0;
   const bool valid = pair < (long)rows * heads;
   const int r = valid ? (int)(pair / heads) : 0, h = valid ? (int)(pair % heads) : 0;
-  const int nk = valid ? (len ? len[r] : n_keys) : 0;
+  int rc = r;  // cache row
+  if (IND) rc = valid ? origin[r] : -1;
+  const int nk = (valid && rc >= 0) ? (len ? len[rc] : n_keys) : 0;
+  if (IND && rc < 0) rc = 0;
   const int grp = lane / LPK, sub = lane % LPK;
 
   float qv[8];
@@ -556,12 +562,23 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const float *q, const 
   p.l = 0.f;
 #pragma unroll
   for (int e = 0; e < 8; e++) p.acc[e] = 0.f;
-  const char *base = (const char *)kv + ((long)r * row_stride + h * DH + sub * 8) * ESZ;
+  const char *base = (const char *)kv + ((long)rc * row_stride + h * DH + sub * 8) * ESZ;
   for (int j = wip * G + grp; j < nk; j += WPP * G) {
     const char *kp = base + (long)j * 2 * d * ESZ;
     float kx[8], vx[8];
-    load8<KV_F32>(kp, kx);
-    load8<KV_F32>(kp + (long)d * ESZ, vx);
+    if (IND && KV_F32 && kv_new && j == nk - 1) {  // the pair computed in this step: use it and append it to the cache
+      const char *np_ = (const char *)(kv_new + (long)r * 2 * d + h * DH + sub * 8);
+      load8<true>(np_, kx);
+      load8<true>(np_ + (long)d * 4, vx);
+      float4 *ck = (float4 *)const_cast<char *>(kp), *cv = (float4 *)const_cast<char *>(kp + (long)d * 4);
+      ck[0] = make_float4(kx[0], kx[1], kx[2], kx[3]);
+      ck[1] = make_float4(kx[4], kx[5], kx[6], kx[7]);
+      cv[0] = make_float4(vx[0], vx[1], vx[2], vx[3]);
+      cv[1] = make_float4(vx[4], vx[5], vx[6], vx[7]);
+    } else {
+      load8<KV_F32>(kp, kx);
+      load8<KV_F32>(kp + (long)d * ESZ, vx);
+    }
     float s = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; e++) s += qv[e] * kx[e];
@@ -623,28 +640,33 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const float *q, const 
 template <int DH>
 static hipError_t attn_decode_launch(const float *q, const void *kv, bool kv_f32, long row_stride, const int32_t *len,
                                      int n_keys, int rows, int d, int heads, const float *rk, int clip, int qpos,
-                                     float *ctx, long ctx_lo_offset, hipStream_t s) {
+                                     float *ctx, long ctx_lo_offset, const int32_t *origin, const float *kv_new,
+                                     hipStream_t s) {
   const long pairs = (long)rows * heads;
   const unsigned grid = (DH >= 256) ? (unsigned)pairs : (unsigned)((pairs + 3) / 4);
-  if (kv_f32)
-    hipLaunchKernelGGL((attn_decode_kernel<DH, true>), dim3(grid), dim3(256), 0, s, q, kv, row_stride, len, n_keys,
-                       rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset);
-  else
-    hipLaunchKernelGGL((attn_decode_kernel<DH, false>), dim3(grid), dim3(256), 0, s, q, kv, row_stride, len, n_keys,
-                       rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset);
+#define NT_ATTN_DECODE(F32, IND)                                                                                       \
+  hipLaunchKernelGGL((attn_decode_kernel<DH, F32, IND>), dim3(grid), dim3(256), 0, s, q, kv, row_stride, len, n_keys, \
+                     rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset, origin, kv_new)
+  if (kv_f32 && origin) NT_ATTN_DECODE(true, true);
+  else if (kv_f32) NT_ATTN_DECODE(true, false);
+  else if (origin) NT_ATTN_DECODE(false, true);
+  else NT_ATTN_DECODE(false, false);
+#undef NT_ATTN_DECODE
   return hipGetLastError();
 }
 
 hipError_t launch_attn_decode(const float *q, const void *kv, bool kv_f32, long row_stride, const int32_t *len,
                               int n_keys, int rows, int d, int heads, const float *rk, int clip, int qpos,
-                              float *ctx, hipStream_t s, long ctx_lo_offset) {
+                              float *ctx, hipStream_t s, long ctx_lo_offset, const int32_t *origin,
+                              const float *kv_new) {
   if (rows <= 0) return hipSuccess;
   if (clip > MAX_CLIP) return hipErrorInvalidValue;
+  if (kv_new && (!origin || !kv_f32 || len)) return hipErrorInvalidValue;
   switch (d / heads) {
-    case 64: return attn_decode_launch<64>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset, s);
-    case 128: return attn_decode_launch<128>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset, s);
-    case 256: return attn_decode_launch<256>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset, s);
-    case 512: return attn_decode_launch<512>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset, s);
+    case 64: return attn_decode_launch<64>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset, origin, kv_new, s);
+    case 128: return attn_decode_launch<128>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset, origin, kv_new, s);
+    case 256: return attn_decode_launch<256>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset, origin, kv_new, s);
+    case 512: return attn_decode_launch<512>(q, kv, kv_f32, row_stride, len, n_keys, rows, d, heads, rk, clip, qpos, ctx, ctx_lo_offset, origin, kv_new, s);
     default: return hipErrorInvalidValue;
   }
 }

@@ -11,6 +11,7 @@
 #include <new>
 #include <numeric>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/nt.h"
@@ -163,10 +164,19 @@ struct nt_model {
   float w_norm_max = 0.f;                              // max_v ||W_out[v,:]||
   int32_t *len = nullptr, *flags = nullptr;
   int32_t *d_src = nullptr, *d_len_in = nullptr, *d_out = nullptr;  // staging for nt_translate_batch
+  // EOS-terminated decoding: dense row -> batch row maps of two consecutive steps, per-row scratch, caps and output
+  // lengths, the newest key|value pairs [Br, 2d], and the word through which the device tells the host how many
+  // rows are still decoding (pinned host memory; d_progress is its device address)
+  int32_t *origin[2] = {nullptr, nullptr}, *eos_y = nullptr, *eos_tok = nullptr, *d_cap = nullptr, *d_out_len = nullptr;
+  float *kv_new = nullptr;
+  uint64_t *h_progress = nullptr;
+  unsigned long long *d_progress = nullptr;
+  uint64_t decode_seq = 0;
   // Host side of a batch in flight: pinned staging, its completion event and which sentences it holds.  Two per
   // lane, so that the next batch of a lane is queued behind the running one instead of after it.
   struct Staging {
     int32_t *h_src = nullptr, *h_len = nullptr, *h_out = nullptr;  // pinned
+    int32_t *h_cap = nullptr, *h_out_len = nullptr;                 // pinned, EOS mode: per-row caps in, lengths out
     hipEvent_t done = nullptr;
     bool busy = false;
     int64_t i0 = 0, i1 = 0;
@@ -300,7 +310,10 @@ int alloc_lane_state(nt_model *m, hipStream_t s) {
                o_lon = cv.take((size_t)Br * 4), o_tok = cv.take((size_t)Br * 4), o_slot = cv.take((size_t)Br * 4),
                o_clist = cv.take((size_t)Br * 4), o_fkey = cv.take((size_t)Br * 8), o_nmask = cv.take((size_t)Br * 8),
                o_len = cv.take((size_t)Br * 4), o_flags = cv.take(64),
-               o_src = cv.take((size_t)Mt * 4), o_lin = cv.take((size_t)Br * 4), o_out = cv.take((size_t)m->self_positions * 4);
+               o_src = cv.take((size_t)Mt * 4), o_lin = cv.take((size_t)Br * 4), o_out = cv.take((size_t)m->self_positions * 4),
+               o_org0 = cv.take((size_t)Br * 4), o_org1 = cv.take((size_t)Br * 4), o_ey = cv.take((size_t)Br * 4),
+               o_etok = cv.take((size_t)Br * 4), o_cap = cv.take((size_t)Br * 4), o_olen = cv.take((size_t)Br * 4),
+               o_kvn = cv.take((size_t)Br * 2 * d * 4);
   m->arena_bytes = cv.off;
   if (hipMalloc((void **)&m->d_arena, m->arena_bytes) != hipSuccess) return fail(NT_ENOMEM, "hipMalloc of %zu arena bytes failed", m->arena_bytes);
   char *A = m->d_arena;
@@ -314,13 +327,21 @@ int alloc_lane_state(nt_model *m, hipStream_t s) {
   m->final_key = at<unsigned long long>(A, o_fkey); m->need_mask = at<unsigned long long>(A, o_nmask);
   m->flags = at<int32_t>(A, o_flags); m->d_src = at<int32_t>(A, o_src); m->d_len_in = at<int32_t>(A, o_lin);
   m->d_out = at<int32_t>(A, o_out);
+  m->origin[0] = at<int32_t>(A, o_org0); m->origin[1] = at<int32_t>(A, o_org1); m->eos_y = at<int32_t>(A, o_ey);
+  m->eos_tok = at<int32_t>(A, o_etok); m->d_cap = at<int32_t>(A, o_cap); m->d_out_len = at<int32_t>(A, o_olen);
+  m->kv_new = at<float>(A, o_kvn);
   HIP_TRY(nt::launch_fill_i32(m->flags, 16, 0, s));
   for (auto &st : m->stage) {
     if (hipHostMalloc((void **)&st.h_src, (size_t)Mt * 4) != hipSuccess || hipHostMalloc((void **)&st.h_len, (size_t)Br * 4) != hipSuccess ||
-        hipHostMalloc((void **)&st.h_out, (size_t)m->self_positions * 4) != hipSuccess)
+        hipHostMalloc((void **)&st.h_out, (size_t)m->self_positions * 4) != hipSuccess ||
+        hipHostMalloc((void **)&st.h_cap, (size_t)Br * 4) != hipSuccess || hipHostMalloc((void **)&st.h_out_len, (size_t)Br * 4) != hipSuccess)
       return fail(NT_ENOMEM, "pinned staging allocation failed");
     if (hipEventCreateWithFlags(&st.done, hipEventDisableTiming) != hipSuccess) return fail(NT_EHIP, "event creation failed");
   }
+  if (hipHostMalloc((void **)&m->h_progress, 64) != hipSuccess ||
+      hipHostGetDevicePointer((void **)&m->d_progress, m->h_progress, 0) != hipSuccess)
+    return fail(NT_ENOMEM, "pinned progress word allocation failed");
+  *m->h_progress = 0;
   if (hipStreamCreateWithFlags(&m->lane_stream, hipStreamNonBlocking) != hipSuccess ||
       hipEventCreateWithFlags(&m->lane_start, hipEventDisableTiming) != hipSuccess)
     return fail(NT_EHIP, "stream / event creation failed");
@@ -368,7 +389,10 @@ void nt_free(nt_model *m) {
     if (st.h_src) (void)hipHostFree(st.h_src);
     if (st.h_len) (void)hipHostFree(st.h_len);
     if (st.h_out) (void)hipHostFree(st.h_out);
+    if (st.h_cap) (void)hipHostFree(st.h_cap);
+    if (st.h_out_len) (void)hipHostFree(st.h_out_len);
   }
+  if (m->h_progress) (void)hipHostFree(m->h_progress);
   for (hipEvent_t e : m->timing.pool) (void)hipEventDestroy(e);
   delete m;
 }
@@ -696,46 +720,98 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
 
 namespace {
 
-// Decoder loop shared by greedy decoding and the teacher-forced debug path.
-int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, const int32_t *d_forced,
-                int32_t *d_out, float *d_logits, hipStream_t s) {
+// One decode in progress: which step comes next and what the previous one left behind.  The fixed-length modes run
+// the steps back to back; the EOS mode interleaves the steps of several lanes and sizes each by what the host has
+// seen of the device's count of rows still decoding.
+struct DecodeCursor {
+  int32_t B = 0, T = 0;
+  const int32_t *h_row_steps = nullptr;  // non-increasing step count per row, or nullptr (all rows run T steps)
+  const int32_t *d_forced = nullptr;
+  int32_t *d_out = nullptr;
+  float *d_logits = nullptr;
+  int t = 0, partials_prev = 0, rows_prev = 0;
+  bool prev_cert = false, finished = false;
+  // EOS mode (eos_id >= 0)
+  int32_t eos_id = -1;
+  int32_t *d_out_len = nullptr;
+  uint64_t tag = 0;       // sequence number of this decode in the high 16 bits of the progress word
+  int64_t live_seen = 0;  // latest count of rows still decoding that the host has read (an upper bound of the true one)
+  int step_seen = -1;     // the step that count belongs to
+};
+
+// number of rows with more than t steps to run (rows are ordered so that these are a prefix)
+int rows_at(const DecodeCursor &cu, int t) {
+  if (t >= cu.T) return 0;
+  if (!cu.h_row_steps) return cu.B;
+  int lo = 0, hi = cu.B;
+  while (lo < hi) {
+    int mid = (lo + hi) / 2;
+    if (cu.h_row_steps[mid] > t) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// EOS mode: read what the device has published about this decode.  The count only falls, so a stale value is
+// still an upper bound of the rows that are live now.
+void poll_progress(nt_model *m, DecodeCursor &cu) {
+  const uint64_t w = __atomic_load_n(m->h_progress, __ATOMIC_ACQUIRE);
+  if ((w & 0xFFFF000000000000ull) != cu.tag) return;  // written for an earlier decode on this lane
+  cu.step_seen = (int)((w >> 32) & 0xFFFFu);
+  cu.live_seen = (int64_t)(w & 0xFFFFFFFFull);
+}
+
+// Enqueue decoder step cu.t (which first collects the tokens of step cu.t - 1) and advance the cursor.
+int decode_step(nt_model *m, DecodeCursor &cu, hipStream_t s) {
   const nt_config &c = m->c;
   const nt::LnEps lne = ln_eps_of(c);
   const int d = c.d_model, F = dec_ffn(&c), H = dec_heads(&c), V = c.vocab, S = m->S;
+  const int32_t B = cu.B, T = cu.T;
+  const int32_t *d_forced = cu.d_forced;
+  int32_t *d_out = cu.d_out;
+  float *d_logits = cu.d_logits;
+  const bool eos = cu.eos_id >= 0;
   const float qscale = 1.0f / std::sqrt((float)(d / H));
   const long self_stride = (long)T * 2 * d;
-  // active rows at step t: rows are ordered so that the active set is a prefix
-  auto rows_at = [&](int t) -> int {
-    if (t >= T) return 0;
-    if (!h_row_steps) return B;
-    // number of rows with steps > t (non-increasing array)
-    int lo = 0, hi = B;
-    while (lo < hi) {
-      int mid = (lo + hi) / 2;
-      if (h_row_steps[mid] > t) lo = mid + 1; else hi = mid;
-    }
-    return lo;
-  };
-  int partials_prev = 0;
-  bool prev_cert = false;
   const double dd = (double)d, ca = (double)kCrossElt;
   auto gemm_bytes = [&](double rows, double k, double n, bool resid) {
     return rows * k * 4 + n * k * 2 + rows * n * 4 + (resid ? rows * n * 4 : 0.0);
   };
-  for (int t = 0; t <= T; t++) {
-    const int rows_now = rows_at(t), rows_prev = (t == 0) ? rows_now : rows_at(t - 1);
-    if (rows_prev == 0) break;
-    nt::StepBeginArgs a{};
-    a.t = t; a.rows_prev = rows_prev; a.rows_now = rows_now; a.d = d; a.vocab = V; a.bos_id = c.bos_id; a.pad_id = c.pad_id;
-    a.pk = d_logits ? nullptr : m->pk; a.n_partials = partials_prev; a.out = d_out; a.out_ld = T;
-    a.forced = d_forced; a.forced_ld = T; a.E = m->E; a.pe = m->pe; a.gamma = m->dec[0].ln1.g; a.beta = m->dec[0].ln1.b;
-    a.eps = lne; a.z = m->z; a.a = nullptr; a.flags = m->flags;
-    a.prev_cert = prev_cert ? 1 : 0; a.tok = m->tok; a.slot_of_row = m->slot_of_row; a.final_key = m->final_key;
-    a.cert_count = m->flags + 4;
-    if (d_logits && rows_now == 0) break;  // no tokens to collect in this mode (pk == nullptr)
-    KT(K_STEP_BEGIN, rows_prev * (partials_prev * 8.0 + 4) + rows_now * dd * 14, rows_now * dd * 10,
-       nt::launch_step_begin(a, s));
-    if (rows_now == 0) break;
+  const int t = cu.t;
+  if (cu.finished || t > T) { cu.finished = true; return NT_OK; }
+  {
+    int rows_now = rows_at(cu, t);
+    const int rows_prev = (t == 0) ? (eos ? B : rows_now) : cu.rows_prev;
+    if (eos) rows_now = (int)std::min<int64_t>(std::min(rows_now, rows_prev), cu.live_seen);
+    if (rows_prev == 0) { cu.finished = true; return NT_OK; }
+    const int partials_prev = cu.partials_prev;
+    const bool prev_cert = cu.prev_cert;
+    // the EOS mode keeps the rows still decoding as a dense prefix: origin maps a dense row to its batch row
+    int32_t *origin = eos ? m->origin[t & 1] : nullptr;
+    if (eos) {
+      nt::EosStepArgs a{};
+      a.t = t; a.rows_prev = rows_prev; a.rows_now = rows_now; a.d = d; a.vocab = V; a.bos_id = c.bos_id; a.pad_id = c.pad_id;
+      a.eos_id = cu.eos_id; a.pk = m->pk; a.n_partials = partials_prev; a.prev_cert = prev_cert ? 1 : 0; a.tok = m->tok;
+      a.slot_of_row = m->slot_of_row; a.final_key = m->final_key; a.cert_count = m->flags + 4; a.out = d_out; a.out_ld = T;
+      a.out_len = cu.d_out_len; a.cap = m->d_cap; a.origin_prev = m->origin[(t + 1) & 1]; a.origin = origin; a.y = m->eos_y;
+      a.tok_in = m->eos_tok; a.live = m->flags + 9; a.progress = m->d_progress;
+      a.progress_tag = cu.tag; a.E = m->E; a.pe = m->pe; a.z = m->z;
+      KT(K_STEP_BEGIN, rows_prev * (partials_prev * 8.0 + 24) + rows_now * dd * 6, rows_now * dd * 2,
+         nt::launch_eos_step_begin(a, s));
+    } else {
+      nt::StepBeginArgs a{};
+      a.t = t; a.rows_prev = rows_prev; a.rows_now = rows_now; a.d = d; a.vocab = V; a.bos_id = c.bos_id; a.pad_id = c.pad_id;
+      a.pk = d_logits ? nullptr : m->pk; a.n_partials = partials_prev; a.out = d_out; a.out_ld = T;
+      a.forced = d_forced; a.forced_ld = T; a.E = m->E; a.pe = m->pe; a.gamma = m->dec[0].ln1.g; a.beta = m->dec[0].ln1.b;
+      a.eps = lne; a.z = m->z; a.a = nullptr; a.flags = m->flags;
+      a.prev_cert = prev_cert ? 1 : 0; a.tok = m->tok; a.slot_of_row = m->slot_of_row; a.final_key = m->final_key;
+      a.cert_count = m->flags + 4;
+      if (d_logits && rows_now == 0) { cu.finished = true; return NT_OK; }  // no tokens to collect in this mode (pk == nullptr)
+      KT(K_STEP_BEGIN, rows_prev * (partials_prev * 8.0 + 4) + rows_now * dd * 14, rows_now * dd * 10,
+         nt::launch_step_begin(a, s));
+    }
+    cu.t = t + 1;
+    cu.rows_prev = rows_now;
+    if (rows_now == 0) { cu.finished = true; return NT_OK; }
     const int R = rows_now;
     const double Rd = (double)R;
     // source tokens attended by the active rows (exact when the host knows the lengths)
@@ -778,10 +854,12 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
         nt::GemmEpilogue e;
         e.bias = L.self.bqkv; e.scale = qscale; e.scale_cols = d; e.dst0 = m->q32; e.ld0 = d; e.n_split = d;
         e.dst1 = m->self_kv[l] + (long)t * 2 * d; e.ld1 = self_stride;
+        if (eos) { e.dst1 = m->kv_new; e.ld1 = 2 * d; }  // appended to the row's own cache by the attention kernel
         if ((rc = dec_gemm(K_GEMM_DEC_QKV, m->z, d, L.self.Wqkv, L.self.Wqkv_p, 3 * d, &L.ln1, e))) return rc;
         KT(K_ATTN_DEC_SELF, Rd * (t + 1) * 2 * dd * 4 + Rd * dd * 8, 4 * Rd * (t + 1) * dd,
            nt::launch_attn_decode(m->q32, m->self_kv[l], true, self_stride, nullptr, t + 1, R, d, H, L.self.rk,
-                                  c.rpr_clip, t, m->ctx32, s, streams(d, d, L.self.Wo_p, false) ? lo_rows * d : 0));
+                                  c.rpr_clip, t, m->ctx32, s, streams(d, d, L.self.Wo_p, false) ? lo_rows * d : 0, origin,
+                                  eos ? m->kv_new : nullptr));
         nt::GemmEpilogue o;
         o.bias = L.self.bo; o.resid = m->z; o.ldr = d; o.dst0 = m->z; o.ld0 = d; o.n_split = d;
         if ((rc = dec_gemm(K_GEMM_DEC_O, m->ctx32, d, L.self.Wo, L.self.Wo_p, d, nullptr, o))) return rc;
@@ -792,7 +870,7 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
         if ((rc = dec_gemm(K_GEMM_DEC_Q, m->z, d, L.cross.Wq, L.cross.Wq_p, d, &L.ln2, e))) return rc;
         KT(K_ATTN_DEC_CROSS, cross_keys * 2 * dd * ca + Rd * dd * 8, 4 * cross_keys * dd,
            nt::launch_attn_decode(m->q32, m->cross[l], kCrossF32, (long)S * 2 * d, m->len, 0, R, d, H, nullptr, 0, 0,
-                                  m->ctx32, s, streams(d, d, L.cross.Wo_p, false) ? lo_rows * d : 0));
+                                  m->ctx32, s, streams(d, d, L.cross.Wo_p, false) ? lo_rows * d : 0, origin));
         nt::GemmEpilogue o;
         o.bias = L.cross.bo; o.resid = m->z; o.ldr = d; o.dst0 = m->z; o.ld0 = d; o.n_split = d;
         if ((rc = dec_gemm(K_GEMM_DEC_O, m->ctx32, d, L.cross.Wo, L.cross.Wo_p, d, nullptr, o))) return rc;
@@ -821,17 +899,49 @@ int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, c
       KT(K_GEMM_LOGITS, gemm_bytes(Rd, dd, V, false), 2 * Rd * dd * V,
          nt::launch_gemm(nt::A_PLANES, true, h_hi, h_lo, d, m->Wout, R, V, d, e, s));
     } else {
-      prev_cert = R >= kCertMinRows;
-      const int np_ = nt::vocab_argmax_partials(m->vw, R, prev_cert);
-      if (prev_cert)
+      cu.prev_cert = R >= kCertMinRows;
+      const int np_ = nt::vocab_argmax_partials(m->vw, R, cu.prev_cert);
+      if (cu.prev_cert)
         KT(K_VOCAB_ARGMAX, (double)V * dd * 2 + Rd * dd * 4 + Rd * np_ * 8, 2 * Rd * dd * V,
            nt::launch_vocab_argmax_certified(h_hi, h_lo, d, m->vw, R, m->lo_norm, m->w_norm_max, m->pk, m->ps,
                                              m->tok, m->slot_of_row, m->cert_list, m->flags + 4, m->final_key, m->need_mask, s));
       else
         KT(K_VOCAB_ARGMAX, (double)V * dd * 2 + Rd * dd * 4 + Rd * np_ * 8, 2 * Rd * dd * V,
            nt::launch_vocab_argmax(h_hi, h_lo, d, m->vw, R, m->pk, s));
-      partials_prev = np_;
+      cu.partials_prev = np_;
     }
+  }
+  return NT_OK;
+}
+
+// ---- EOS mode: how far the host may run ahead of the device -------------------------------------------------------
+// The host sizes step t with the count the device published for some earlier step; the further ahead it enqueues,
+// the staler that count.  A few steps are enough to keep the queue from running dry.
+constexpr int kEosLookahead = 6;
+
+void begin_eos_decode(nt_model *m, DecodeCursor &cu, int32_t B, int32_t T, const int32_t *h_row_steps, int32_t eos_id,
+                      int32_t *d_out, int32_t *d_out_len) {
+  cu = DecodeCursor{};
+  cu.B = B; cu.T = T; cu.h_row_steps = h_row_steps; cu.d_out = d_out; cu.d_out_len = d_out_len; cu.eos_id = eos_id;
+  // the tag tells this decode's progress words from those that steps of an earlier decode on this lane, enqueued
+  // before the host saw it end, may still publish
+  m->decode_seq = (m->decode_seq % 0xFFFFu) + 1;
+  cu.tag = m->decode_seq << 48;
+  cu.live_seen = B;
+  cu.step_seen = -1;
+}
+// every row has ended (seen on the device, so all tokens are collected): nothing more to enqueue
+bool eos_all_ended(const DecodeCursor &cu) { return cu.step_seen >= 0 && cu.live_seen == 0; }
+bool eos_may_advance(const DecodeCursor &cu) { return cu.t - cu.step_seen <= kEosLookahead; }
+
+// Decoder loop shared by fixed-length greedy decoding and the teacher-forced debug path.
+int run_decoder(nt_model *m, int32_t B, int32_t T, const int32_t *h_row_steps, const int32_t *d_forced,
+                int32_t *d_out, float *d_logits, hipStream_t s) {
+  DecodeCursor cu;
+  cu.B = B; cu.T = T; cu.h_row_steps = h_row_steps; cu.d_forced = d_forced; cu.d_out = d_out; cu.d_logits = d_logits;
+  while (!cu.finished) {
+    int rc = decode_step(m, cu, s);
+    if (rc) return rc;
   }
   return NT_OK;
 }
@@ -863,6 +973,42 @@ int nt_decode_greedy(nt_model *m, int32_t B, int32_t n_steps, const int32_t *h_r
     HIP_TRY(nt::launch_fill_i32(d_out, (long)B * n_steps, m->c.pad_id, s));
   }
   return run_decoder(m, B, n_steps, h_row_steps, nullptr, d_out, nullptr, s);
+}
+
+int nt_decode_greedy_eos(nt_model *m, int32_t B, int32_t n_steps, const int32_t *h_row_steps, int32_t eos_id,
+                         int32_t *d_out, int32_t *d_out_len, void *hip_stream) {
+  int rc = check_decode_args(m, B, n_steps);
+  if (rc) return rc;
+  if (!d_out || !d_out_len) return fail(NT_EINVAL, "d_out or d_out_len is null");
+  if (eos_id < 0 || eos_id >= m->c.vocab) return fail(NT_ERANGE, "eos_id %d outside the vocabulary", eos_id);
+  hipStream_t s = as_stream(hip_stream);
+  if (h_row_steps) {
+    for (int i = 0; i < B; i++) {
+      if (h_row_steps[i] < 0 || h_row_steps[i] > n_steps || (i > 0 && h_row_steps[i] > h_row_steps[i - 1]))
+        return fail(NT_ERANGE, "h_row_steps must be non-increasing and within [0, n_steps]");
+    }
+    HIP_TRY(hipMemcpyAsync(m->d_cap, h_row_steps, (size_t)B * 4, hipMemcpyHostToDevice, s));
+  } else {
+    HIP_TRY(nt::launch_fill_i32(m->d_cap, B, n_steps, s));
+  }
+  if (n_steps == 0) return nt::launch_fill_i32(d_out_len, B, 0, s) == hipSuccess ? NT_OK : fail(NT_EHIP, "fill failed");
+  HIP_TRY(nt::launch_fill_i32(d_out, (long)B * n_steps, m->c.pad_id, s));
+  DecodeCursor cu;
+  begin_eos_decode(m, cu, B, n_steps, h_row_steps, eos_id, d_out, d_out_len);
+  auto last_progress = std::chrono::steady_clock::now();
+  int seen = -1;
+  while (!cu.finished && !eos_all_ended(cu)) {
+    poll_progress(m, cu);
+    if (cu.step_seen != seen) { seen = cu.step_seen; last_progress = std::chrono::steady_clock::now(); }
+    if (eos_may_advance(cu)) {
+      if ((rc = decode_step(m, cu, s))) return rc;
+      continue;
+    }
+    if (std::chrono::steady_clock::now() - last_progress > std::chrono::seconds(30))
+      return fail(NT_EHIP, "the device has published no decoding progress for 30 s (step %d enqueued, step %d seen)", cu.t, cu.step_seen);
+    std::this_thread::yield();
+  }
+  return NT_OK;
 }
 
 int nt_debug_teacher_forced_logits(nt_model *m, const int32_t *d_tgt_in, int32_t B, int32_t T, float *d_logits,
@@ -983,14 +1129,26 @@ int nt_plan_batches(const int32_t *h_lengths, int64_t N, int64_t budget, int32_t
   return fail(NT_ENOMEM, "host allocation failed");
 }
 
-int nt_translate_batch(nt_model *m, const int32_t *h_tokens, const int64_t *h_offsets, int64_t N, int64_t token_budget,
-                       int32_t max_rows, int32_t *h_out, int64_t *h_out_offsets, void *hip_stream) try {
+}  // extern "C"
+
+namespace {
+
+// What both translate calls need before anything is launched: validated lengths, output offsets and the batches.
+struct TranslatePlan {
+  std::vector<int32_t> lens;
+  std::vector<int64_t> order, starts;
+  int64_t nb = 0;
+};
+
+int plan_translate(nt_model *m, const int32_t *h_tokens, const int64_t *h_offsets, int64_t N, int64_t token_budget,
+                   int32_t max_rows, const int32_t *h_out, int64_t *h_out_offsets, TranslatePlan &p) {
   if (!m || !h_offsets || !h_out_offsets || N < 0) return fail(NT_EINVAL, "null argument or negative N");
   if (token_budget < 1 || max_rows < 0) return fail(NT_EINVAL, "token_budget must be >= 1 and max_rows >= 0");
   const nt_config &c = m->c;
   // validate everything before anything is written or launched
   if (h_offsets[0] < 0) return fail(NT_ERANGE, "offsets must start at >= 0");
-  std::vector<int32_t> lens((size_t)N);
+  std::vector<int32_t> &lens = p.lens;
+  lens.resize((size_t)N);
   int64_t total_out = 0;
   for (int64_t i = 0; i < N; i++) {
     const int64_t L = h_offsets[i + 1] - h_offsets[i];
@@ -1010,12 +1168,26 @@ int nt_translate_batch(nt_model *m, const int32_t *h_tokens, const int64_t *h_of
     if (lens[(size_t)i] > m->max_tokens) return fail(NT_ERANGE, "sentence %lld (%d tokens) exceeds the arena of %lld tokens", (long long)i, lens[(size_t)i], (long long)m->max_tokens);
   h_out_offsets[0] = 0;
   for (int64_t i = 0; i < N; i++) h_out_offsets[i + 1] = h_out_offsets[i] + (lens[(size_t)i] > 0 ? nt_n_steps(lens[(size_t)i]) : 0);
+  p.nb = 0;
   if (N == 0) return NT_OK;
+  p.order.resize((size_t)N);
+  p.starts.resize((size_t)N + 1);
+  return nt_plan_batches(lens.data(), N, budget, (int32_t)std::min<int64_t>(rows_cap, INT32_MAX), p.order.data(), p.starts.data(), &p.nb);
+}
 
-  std::vector<int64_t> order((size_t)N), starts((size_t)N + 1);
-  int64_t nb = 0;
-  int rc = nt_plan_batches(lens.data(), N, budget, (int32_t)std::min<int64_t>(rows_cap, INT32_MAX), order.data(), starts.data(), &nb);
-  if (rc) return rc;
+}  // namespace
+
+extern "C" {
+
+int nt_translate_batch(nt_model *m, const int32_t *h_tokens, const int64_t *h_offsets, int64_t N, int64_t token_budget,
+                       int32_t max_rows, int32_t *h_out, int64_t *h_out_offsets, void *hip_stream) try {
+  TranslatePlan plan;
+  int rc = plan_translate(m, h_tokens, h_offsets, N, token_budget, max_rows, h_out, h_out_offsets, plan);
+  if (rc || N == 0) return rc;
+  const nt_config &c = m->c;
+  const std::vector<int32_t> &lens = plan.lens;
+  const std::vector<int64_t> &order = plan.order, &starts = plan.starts;
+  const int64_t nb = plan.nb;
   hipStream_t s = as_stream(hip_stream);
   // lanes: batch k runs on lane k mod n on that lane's own stream.  Each lane has two sets of host staging, so its
   // next batch is already queued while the current one runs; the host packs batches and unpacks finished ones while
@@ -1088,6 +1260,154 @@ int nt_translate_batch(nt_model *m, const int32_t *h_tokens, const int64_t *h_of
   }
   if (first_err) return first_err;
   return NT_OK;
+} catch (const std::bad_alloc &) {
+  return fail(NT_ENOMEM, "host allocation failed");
+} catch (...) {
+  return fail(NT_EINVAL, "unexpected exception");
+}
+
+int nt_translate_batch_eos(nt_model *m, const int32_t *h_tokens, const int64_t *h_offsets, int64_t N, int64_t token_budget,
+                           int32_t max_rows, int32_t eos_id, int32_t *h_out, int64_t *h_out_offsets, int32_t *h_out_len,
+                           void *hip_stream) try {
+  TranslatePlan plan;
+  int rc = plan_translate(m, h_tokens, h_offsets, N, token_budget, max_rows, h_out, h_out_offsets, plan);
+  if (rc) return rc;
+  if (eos_id < 0 || eos_id >= m->c.vocab) return fail(NT_ERANGE, "eos_id %d outside the vocabulary", eos_id);
+  if (N > 0 && !h_out_len) return fail(NT_EINVAL, "h_out_len is null");
+  if (N == 0) return NT_OK;
+  const nt_config &c = m->c;
+  const std::vector<int32_t> &lens = plan.lens;
+  const std::vector<int64_t> &order = plan.order, &starts = plan.starts;
+  const int64_t nb = plan.nb;
+  for (int64_t i = 0; i < N; i++) h_out_len[i] = 0;
+  hipStream_t s = as_stream(hip_stream);
+  // One batch per lane at a time; the lanes take turns, each enqueuing the steps its device side allows (a few
+  // ahead of what it has published), so that every lane's launches are sized by a recent count of live rows.
+  struct LaneRun {
+    nt_model *ln = nullptr;
+    bool active = false;
+    int64_t started = 0;  // batches this lane has started: picks the staging set
+    nt_model::Staging *st = nullptr;
+    DecodeCursor cu;
+  };
+  std::vector<LaneRun> runs(1 + m->lanes.size());
+  runs[0].ln = m;
+  for (size_t i = 0; i < m->lanes.size(); i++) runs[i + 1].ln = m->lanes[i];
+  HIP_TRY(hipEventRecord(m->lane_start, s));  // work already queued on the caller's stream comes first
+  for (LaneRun &L : runs) {
+    HIP_TRY(hipStreamWaitEvent(L.ln->lane_stream, m->lane_start, 0));
+    for (auto &st : L.ln->stage) st.busy = false;
+    L.ln->timing.mask = m->timing.mask;
+  }
+  auto collect = [&](nt_model::Staging &st) -> int {  // wait for the batch of this staging set and scatter its rows
+    if (!st.busy) return NT_OK;
+    HIP_TRY(hipEventSynchronize(st.done));
+    for (int64_t r = 0; r < st.i1 - st.i0; r++) {
+      const int64_t si = order[(size_t)(st.i0 + r)];
+      memcpy(h_out + h_out_offsets[si], st.h_out + (size_t)r * st.T, (size_t)st.steps[(size_t)r] * 4);
+      h_out_len[si] = st.h_out_len[r];
+    }
+    st.busy = false;
+    return NT_OK;
+  };
+  auto start_batch = [&](LaneRun &L, int64_t k) -> int {
+    nt_model *ln = L.ln;
+    nt_model::Staging &st = ln->stage[L.started % nt_model::kStagings];
+    int e = collect(st);
+    if (e) return e;
+    const int64_t i0 = starts[(size_t)k], i1 = starts[(size_t)k + 1];
+    const int32_t B = (int32_t)(i1 - i0), S = lens[(size_t)order[(size_t)i0]], T = nt_n_steps(S);
+    if ((int64_t)B * T > ln->self_positions) return fail(NT_ENOMEM, "batch of %d rows x %d steps exceeds the self-attention cache", B, T);
+    st.steps.resize((size_t)B);
+    for (int32_t r = 0; r < B; r++) {
+      const int64_t si = order[(size_t)(i0 + r)];
+      const int32_t Ls = lens[(size_t)si];
+      st.h_len[r] = Ls;
+      st.steps[(size_t)r] = st.h_cap[r] = nt_n_steps(Ls);
+      int32_t *row = st.h_src + (size_t)r * S;
+      memcpy(row, h_tokens + h_offsets[si], (size_t)Ls * 4);
+      for (int32_t j = Ls; j < S; j++) row[j] = c.pad_id;
+    }
+    hipStream_t ls = ln->lane_stream;
+    if (hipMemcpyAsync(ln->d_src, st.h_src, (size_t)B * S * 4, hipMemcpyHostToDevice, ls) != hipSuccess ||
+        hipMemcpyAsync(ln->d_len_in, st.h_len, (size_t)B * 4, hipMemcpyHostToDevice, ls) != hipSuccess ||
+        hipMemcpyAsync(ln->d_cap, st.h_cap, (size_t)B * 4, hipMemcpyHostToDevice, ls) != hipSuccess)
+      return fail(NT_EHIP, "host-to-device copy failed");
+    if ((e = nt_encode(ln, ln->d_src, ln->d_len_in, B, S, ls))) return e;
+    if (ln->timing.mask) {
+      ln->len_prefix.assign((size_t)B + 1, 0);
+      for (int32_t r = 0; r < B; r++) ln->len_prefix[(size_t)r + 1] = ln->len_prefix[(size_t)r] + st.h_len[r];
+    }
+    if ((e = check_decode_args(ln, B, T))) return e;
+    HIP_TRY(nt::launch_fill_i32(ln->d_out, (long)B * T, c.pad_id, ls));
+    begin_eos_decode(ln, L.cu, B, T, st.steps.data(), eos_id, ln->d_out, ln->d_out_len);
+    st.i0 = i0; st.i1 = i1; st.T = T;
+    L.st = &st;
+    L.started++;
+    L.active = true;
+    return NT_OK;
+  };
+  auto finish_batch = [&](LaneRun &L) -> int {
+    nt_model *ln = L.ln;
+    nt_model::Staging &st = *L.st;
+    const int64_t B = st.i1 - st.i0;
+    if (hipMemcpyAsync(st.h_out, ln->d_out, (size_t)B * st.T * 4, hipMemcpyDeviceToHost, ln->lane_stream) != hipSuccess ||
+        hipMemcpyAsync(st.h_out_len, ln->d_out_len, (size_t)B * 4, hipMemcpyDeviceToHost, ln->lane_stream) != hipSuccess ||
+        hipEventRecord(st.done, ln->lane_stream) != hipSuccess)
+      return fail(NT_EHIP, "device-to-host copy failed");
+    st.busy = true;
+    L.active = false;
+    return NT_OK;
+  };
+  int first_err = NT_OK;
+  int64_t next = 0;
+  auto last_progress = std::chrono::steady_clock::now();
+  while (first_err == NT_OK) {
+    bool any_active = false, progressed = false;
+    for (LaneRun &L : runs) {
+      if (first_err) break;
+      if (!L.active && next < nb) {
+        if ((first_err = start_batch(L, next))) break;
+        next++;
+        progressed = true;
+      }
+      if (!L.active) continue;
+      any_active = true;
+      const int seen = L.cu.step_seen;
+      poll_progress(L.ln, L.cu);
+      if (L.cu.step_seen != seen) progressed = true;
+      while (!L.cu.finished && !eos_all_ended(L.cu) && eos_may_advance(L.cu)) {
+        if ((first_err = decode_step(L.ln, L.cu, L.ln->lane_stream))) break;
+        progressed = true;
+      }
+      if (first_err) break;
+      if (L.cu.finished || eos_all_ended(L.cu)) {
+        if ((first_err = finish_batch(L))) break;
+        progressed = true;
+      }
+    }
+    if (first_err || (!any_active && next >= nb)) break;
+    if (progressed) {
+      last_progress = std::chrono::steady_clock::now();
+    } else {
+      if (std::chrono::steady_clock::now() - last_progress > std::chrono::seconds(30)) {
+        first_err = fail(NT_EHIP, "the device has published no decoding progress for 30 s");
+        break;
+      }
+      std::this_thread::yield();
+    }
+  }
+  // drain every lane (also after an error: nothing may still be running when the call returns)
+  for (LaneRun &L : runs) {
+    nt_model *ln = L.ln;
+    int older = 0;
+    if (ln->stage[0].busy && ln->stage[1].busy && ln->stage[1].i0 < ln->stage[0].i0) older = 1;
+    for (int j = 0; j < nt_model::kStagings; j++)
+      if (first_err == NT_OK) first_err = collect(ln->stage[(older + j) % nt_model::kStagings]);
+    (void)hipStreamSynchronize(ln->lane_stream);
+    for (auto &st : ln->stage) st.busy = false;
+  }
+  return first_err;
 } catch (const std::bad_alloc &) {
   return fail(NT_ENOMEM, "host allocation failed");
 } catch (...) {

@@ -189,6 +189,42 @@ struct StepBeginArgs {
 };
 hipError_t launch_step_begin(const StepBeginArgs &a, hipStream_t s);
 
+// Start of decoder step t when sentences end at EOS (Sec. 3.3 "Greedy Search"): the rows still decoding are kept
+// as a dense prefix.  Dense row r of a step belongs to batch row origin[r] (-1: no row; such rows compute on the
+// padding token and store nothing).  Three launches:
+//   collect  (t > 0) token of step t-1 for every previous dense row -> out[b][t-1]; a row ends when the token is
+//            eos_id or when it has cap[b] tokens, and then gets out_len[b] = t
+//   compact  stable compaction of the rows that go on -> origin / tok_in of step t, their count -> *live and, if
+//            progress != nullptr, progress_tag | t << 32 | count into that host-visible word.  At t == 0 the rows
+//            with cap > 0 start with bos_id.
+//   embed    z[r] = sqrt(d) * E[tok_in[r]] + PE[t] for r < rows_now (tok_in is pad_id where origin[r] < 0)
+// rows_prev: dense rows of step t-1 (B at t == 0); rows_now <= rows_prev: dense rows step t will run on, an upper
+// bound of the count the compaction finds.
+struct EosStepArgs {
+  int t, rows_prev, rows_now, d, vocab, bos_id, pad_id, eos_id;
+  // arg-max result of step t-1, as in StepBeginArgs
+  const unsigned long long *pk;
+  int n_partials, prev_cert;
+  const int32_t *tok, *slot_of_row;
+  const unsigned long long *final_key;
+  int32_t *cert_count;
+  int32_t *out;
+  long out_ld;
+  int32_t *out_len;
+  const int32_t *cap;          // [B] most tokens of each batch row
+  const int32_t *origin_prev;  // [rows_prev] of step t-1 (unused at t == 0)
+  int32_t *origin;             // [rows_prev] of step t
+  int32_t *y;                  // [rows_prev] scratch: token of a previous dense row that goes on, else -1
+  int32_t *tok_in;             // [rows_prev] input token of each dense row of step t
+  int32_t *live;
+  unsigned long long *progress;
+  unsigned long long progress_tag;
+  const _Float16 *E;
+  const float *pe;
+  float *z;
+};
+hipError_t launch_eos_step_begin(const EosStepArgs &a, hipStream_t s);
+
 // ---- attention ------------------------------------------------------------------------
 // Encoder self-attention on a padded batch.  qkv [B*S, 3d] (q already scaled | k | v), len [B];
 // ctx [B*S, d].  f32: qkv is fp32 (split-precision MFMA inside) and ctx is written as a head/tail
@@ -205,9 +241,13 @@ hipError_t launch_enc_attention(const void *qkv, bool f32, const int32_t *len, v
 //   rk (self only): relative keys; the query sits at position qpos, key j at position j.
 //   ctx_lo_offset != 0: ctx is written as a head/tail pair of fp16 planes instead (head at ctx, tail that many
 //   elements later).
+//   origin (optional): query row r uses cache row (and len entry) origin[r]; origin[r] < 0 gives a zero context.
+//   kv_new (optional, fp32 caches with a fixed key count only): [rows, 2d], the key and value of position
+//   n_keys-1 of every query row; they are used from there and stored into the cache by this kernel.
 hipError_t launch_attn_decode(const float *q, const void *kv, bool kv_f32, long row_stride, const int32_t *len,
                               int n_keys, int rows, int d, int heads, const float *rk, int clip, int qpos,
-                              float *ctx, hipStream_t s, long ctx_lo_offset = 0);
+                              float *ctx, hipStream_t s, long ctx_lo_offset = 0, const int32_t *origin = nullptr,
+                              const float *kv_new = nullptr);
 
 // max dynamic LDS the encoder attention needs for (S, dh); used to validate shapes at load.
 size_t enc_attention_lds_bytes(int S, int dh, bool f32);

@@ -226,6 +226,118 @@ __global__ __launch_bounds__(256) void step_begin_kernel(StepBeginArgs a) {
     if (i < ne) a.a[(long)r * d + lane + 64 * i] = v[i];
 }
 
+// ---- EOS-terminated decoding: the rows still decoding are a dense prefix ---------------------------------------
+// token of step t-1 for every previous dense row; y[r] = the token if the row goes on, else -1
+__global__ __launch_bounds__(256) void eos_collect_kernel(EosStepArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= a.rows_prev) return;
+  const int b = a.origin_prev[r];
+  if (b < 0) {
+    if (lane == 0) a.y[r] = -1;
+    return;
+  }
+  int y;
+  if (a.prev_cert) {
+    const int sl = a.slot_of_row[r];
+    y = (sl < 0) ? a.tok[r] : (int)(0xFFFFFFFFu - (unsigned int)a.final_key[sl]);
+  } else {
+    unsigned long long k = 0ull;
+    const unsigned long long *p = a.pk + (long)r * a.n_partials;
+    for (int i = lane; i < a.n_partials; i += 64) {
+      unsigned long long c = p[i];
+      k = c > k ? c : k;
+    }
+    k = wave_max_u64(k);
+    y = (int)(0xFFFFFFFFu - (unsigned int)k);
+  }
+  if (y < 0 || y >= a.vocab) y = a.pad_id;  // cannot happen: every key holds a valid id
+  if (lane == 0) {
+    a.out[(long)b * a.out_ld + a.t - 1] = y;
+    const bool ends = (y == a.eos_id) || (a.t >= a.cap[b]);
+    if (ends) a.out_len[b] = a.t;
+    a.y[r] = ends ? -1 : y;
+  }
+}
+
+// One workgroup: stable compaction of the rows with y >= 0.  At t == 0 every batch row with cap > 0 starts.
+__global__ __launch_bounds__(1024) void eos_compact_kernel(EosStepArgs a) {
+  __shared__ int wave_tot[16];
+  __shared__ int base;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) base = 0;
+  __syncthreads();
+  for (int r0 = 0; r0 < a.rows_prev; r0 += 1024) {
+    const int r = r0 + tid;
+    int y = -1, b = -1;
+    if (r < a.rows_prev) {
+      if (a.t == 0) {
+        b = r;
+        y = (a.cap[r] > 0) ? a.bos_id : -1;
+        if (y < 0) a.out_len[r] = 0;
+      } else {
+        y = a.y[r];
+        b = a.origin_prev[r];
+      }
+    }
+    const bool keep = y >= 0;
+    const unsigned long long m = __ballot(keep);
+    const int before = __popcll(m & ((1ull << lane) - 1ull));
+    if (lane == 0) wave_tot[wave] = __popcll(m);
+    __syncthreads();
+    int off = base;
+    for (int w = 0; w < wave; w++) off += wave_tot[w];
+    if (keep) {
+      a.origin[off + before] = b;
+      a.tok_in[off + before] = y;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int tot = 0;
+      for (int w = 0; w < 16; w++) tot += wave_tot[w];
+      base += tot;
+    }
+    __syncthreads();
+  }
+  const int live = base;
+  for (int r = live + tid; r < a.rows_prev; r += 1024) {
+    a.origin[r] = -1;
+    a.tok_in[r] = a.pad_id;
+  }
+  if (tid == 0) {
+    *a.live = live;
+    if (a.cert_count) *a.cert_count = 0;  // the certified arg-max of this step counts from zero
+    if (a.progress)
+      __hip_atomic_store(a.progress, a.progress_tag | ((unsigned long long)(unsigned int)a.t << 32) | (unsigned int)live,
+                         __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+  }
+}
+
+__global__ __launch_bounds__(256) void eos_embed_kernel(EosStepArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= a.rows_now) return;
+  // a dense row without a batch row (origin < 0) embeds pad_id: it computes like any other row (its attention
+  // context is zero) and nothing it produces is stored
+  const int y = a.tok_in[r];
+  const int d = a.d, ne = d >> 6;
+  const float sc = sqrtf((float)d);
+  const _Float16 *e = a.E + (long)y * d;
+  const float *p = a.pe + (long)a.t * d;
+#pragma unroll
+  for (int i = 0; i < MAX_PER_LANE; i++)
+    if (i < ne) a.z[(long)r * d + lane + 64 * i] = sc * (float)e[lane + 64 * i] + p[lane + 64 * i];
+}
+
+hipError_t launch_eos_step_begin(const EosStepArgs &a, hipStream_t s) {
+  if (a.rows_prev <= 0) return hipSuccess;
+  if (a.rows_now > a.rows_prev) return hipErrorInvalidValue;
+  if (a.t > 0) hipLaunchKernelGGL(eos_collect_kernel, dim3((a.rows_prev + 3) / 4), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(eos_compact_kernel, dim3(1), dim3(1024), 0, s, a);
+  if (a.rows_now > 0) hipLaunchKernelGGL(eos_embed_kernel, dim3((a.rows_now + 3) / 4), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_step_begin(const StepBeginArgs &a, hipStream_t s) {
   if (a.rows_prev <= 0) return hipSuccess;
   hipLaunchKernelGGL(step_begin_kernel, dim3((a.rows_prev + 3) / 4), dim3(256), 0, s, a);

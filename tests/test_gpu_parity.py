@@ -393,6 +393,127 @@ def test_l1_norm_layer_normalisation(nt, oracle, torch_cuda):
     _check_workload_sample(nt, oracle, "C3", 64, 4096, 0.97, ln_l1=1)
 
 
+# ------------------------------------------------------------------------------ EOS-terminated greedy decoding
+def cut_at_eos(seq, eos):
+    hits = np.nonzero(seq == eos)[0]
+    return seq[: hits[0] + 1] if len(hits) else seq
+
+
+def audit_eos_mismatches(ora_model, src, gpu_out, ora_out, cfg):
+    """As audit_mismatches for sequences that may differ in length: the first position where they differ must
+    be a near-tie of the oracle's logits (an EOS against another token included)."""
+    bad = 0
+    for s, g, o in zip(src, gpu_out, ora_out):
+        if len(g) == len(o) and np.array_equal(g, o):
+            continue
+        bad += 1
+        n = min(len(g), len(o))
+        diff = np.nonzero(g[:n] != o[:n])[0]
+        assert len(diff), "one output is a strict prefix of the other: an end was missed"
+        t = int(diff[0])
+        tgt_in = np.concatenate([[cfg["bos_id"]], o[:t]]).astype(np.int32)
+        logits = ora_model.teacher_forced(s, tgt_in)[t]
+        gap = float(logits[o[t]] - logits[g[t]])
+        assert 0 <= gap < 1e-2, f"mismatch at step {t} is not a near-tie: oracle gap {gap}"
+    return bad
+
+
+def test_eos_decode_small_batch(nt, oracle, torch_cuda):
+    """nt_decode_greedy_eos on one padded batch of the tiny model: tokens, lengths, padding, caps."""
+    torch = torch_cuda
+    eos = nt_synth.EOS_ID
+    cfg = nt_synth.model_config("C0")
+    blob = nt_synth.make_weights(cfg, seed=0, random_affine=True, eos_gain=1.7)
+    gm, om = nt.Model(cfg, blob, max_batch_tokens=4096), oracle.Model(cfg, blob)
+    tokens, offsets = nt_synth.workload("C1", 40)
+    src = sort_desc([s % cfg["vocab"] for s in split(tokens, offsets)])
+    src = [np.maximum(s, 4).astype(np.int32) for s in src]
+    ids, lens = pad(src, cfg["pad_id"])
+    B, S = ids.shape
+    caps = np.array([nt.n_steps(int(l)) for l in lens], dtype=np.int32)
+    T = int(caps[0])
+    for row_steps in (caps, None):
+        gm.encode(torch.from_numpy(ids).cuda(), torch.from_numpy(lens).cuda())
+        out = torch.full((B, T), -7, dtype=torch.int32, device="cuda")
+        out_len = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+        gm.decode_greedy_eos(B, T, eos, out, out_len, row_steps=row_steps)
+        torch.cuda.synchronize()
+        gm.check_device_flags()
+        out, out_len = out.cpu().numpy(), out_len.cpu().numpy()
+        ended, wants, gots = 0, [], []
+        for i, s in enumerate(src):
+            want, _ = om.greedy_eos(s, eos, max_steps=int(caps[i]) if row_steps is not None else T)
+            assert 1 <= out_len[i] <= (caps[i] if row_steps is not None else T)
+            got = out[i, : out_len[i]]
+            assert (got[:-1] != eos).all() and (out[i, out_len[i]:] == cfg["pad_id"]).all()
+            wants.append(want)
+            gots.append(got)
+            ended += want[-1] == eos
+        bad = audit_eos_mismatches(om, src, gots, wants, cfg)      # any difference must be a near-tie
+        print(f"EOS decode, caps {'per row' if row_steps is not None else 'uniform'}: {B - bad}/{B} rows identical")
+        assert bad <= 2
+        assert 5 <= ended <= B - 2        # the stand-in weights end some rows early and let others reach the cap
+    # zero steps: lengths are zero, nothing else is touched
+    gm.encode(torch.from_numpy(ids).cuda(), torch.from_numpy(lens).cuda())
+    out_len = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    gm.decode_greedy_eos(B, 0, eos, torch.empty(1, dtype=torch.int32, device="cuda"), out_len)
+    torch.cuda.synchronize()
+    assert (out_len.cpu().numpy() == 0).all()
+    with pytest.raises(nt.NtError) as e:
+        gm.decode_greedy_eos(B, T, cfg["vocab"], torch.empty((B, T), dtype=torch.int32, device="cuda"), out_len)
+    assert e.value.code == -6
+
+
+def test_eos_translate_against_oracle_and_fixed_length(nt, oracle):
+    """nt_translate_batch_eos on the paper-shaped student with batches of hundreds to thousands of rows on four
+    lanes: (a) a sample against the oracle's EOS-terminated search, (b) every sentence against the fixed-length
+    call cut after its first EOS (the same kernels on other row counts, so equal up to near-ties), (c) an end
+    symbol that never wins gives the fixed-length output."""
+    eos = nt_synth.EOS_ID
+    cfg = nt_synth.model_config("C1")
+    blob = nt_synth.make_weights(cfg, seed=0, eos_gain=1.6)
+    tokens, offsets = nt_synth.workload("C2", 6000)
+    lens = np.diff(offsets)
+    gm = nt.Model(cfg, blob, max_batch_tokens=32768)
+    out, oo, ol = gm.translate_batch_eos(tokens, offsets, 32768, eos)
+    out2, oo2, ol2 = gm.translate_batch_eos(tokens, offsets, 32768, eos)
+    assert np.array_equal(out, out2) and np.array_equal(ol, ol2)          # deterministic whatever the host saw
+    caps = np.array([nt.n_steps(int(l)) for l in lens])
+    assert np.array_equal(np.diff(oo), caps) and (ol >= 1).all() and (ol <= caps).all()
+    gpu = [out[oo[i]: oo[i] + ol[i]] for i in range(len(lens))]
+    for i, g in enumerate(gpu):
+        assert (g[:-1] != eos).all() and (g[-1] == eos or ol[i] == caps[i])
+        assert (out[oo[i] + ol[i]: oo[i + 1]] == cfg["pad_id"]).all()
+    frac_emitted = ol.sum() / caps.sum()
+    assert 0.3 < frac_emitted < 0.97, frac_emitted
+    # (b) fixed-length output of the same library, cut at the first EOS
+    fixed, fo = gm.translate_batch(tokens, offsets, token_budget=32768)
+    same = sum(np.array_equal(g, cut_at_eos(fixed[fo[i]:fo[i + 1]], eos)) for i, g in enumerate(gpu))
+    assert same >= 0.995 * len(gpu), same
+    # (a) oracle on a seeded sample plus the longest and shortest sentences
+    rng = np.random.default_rng(77)
+    order = np.argsort(-lens, kind="stable")
+    sample = np.unique(np.concatenate([rng.choice(len(lens), size=240, replace=False), order[:3], order[-20:]]))
+    om = oracle.Model(cfg, blob)
+    sents = [tokens[offsets[i]:offsets[i + 1]] for i in sample]
+    sub_off = np.concatenate([[0], np.cumsum([len(s) for s in sents])])
+    o_out, o_oo, o_ol, _ = om.translate_eos(np.concatenate(sents), sub_off, eos)
+    ora = [o_out[o_oo[k]: o_oo[k] + o_ol[k]] for k in range(len(sample))]
+    bad = audit_eos_mismatches(om, sents, [gpu[i] for i in sample], ora, cfg)
+    frac = 1.0 - bad / len(sample)
+    print(f"EOS greedy: {len(sample) - bad}/{len(sample)} sampled sentences identical ({100 * frac:.2f} %), "
+          f"{100 * frac_emitted:.1f} % of the capped tokens emitted, {same}/{len(gpu)} equal to the cut fixed-length output")
+    assert frac >= 0.99
+    # (c) with plain random weights EOS practically never wins: the EOS call returns what the fixed-length call does
+    blob0 = nt_synth.make_weights(cfg, seed=0)
+    g0 = nt.Model(cfg, blob0, max_batch_tokens=32768)
+    t2, o2 = nt_synth.workload("C1", 1500)
+    a, ao, al = g0.translate_batch_eos(t2, o2, 32768, eos)
+    b, bo = g0.translate_batch(t2, o2, token_budget=32768)
+    cut = [cut_at_eos(b[bo[i]:bo[i + 1]], eos) for i in range(1500)]
+    assert sum(np.array_equal(a[ao[i]: ao[i] + al[i]], cut[i]) for i in range(1500)) >= 1493
+
+
 # ------------------------------------------------------------------------------ C5 (shape of the submitted student)
 def test_c5_submitted_student_shape(nt, oracle, torch_cuda):
     """Student-3-1-512 (Table 2, Sec. 5): 3 encoder layers with 8 heads and FFN 2,048, one decoder layer
