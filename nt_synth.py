@@ -42,7 +42,7 @@ N_SPECIAL = 4
 
 _BASE = dict(n_enc=6, n_dec=1, d_model=512, n_heads=1, d_ffn=0, vocab=32000,
              max_len=256, rpr_clip=0, tie_output=0, bos_id=BOS_ID, pad_id=PAD_ID,
-             ln_eps=1e-5, dec_n_heads=0, dec_d_ffn=0, ln_l1=0)
+             ln_eps=1e-5, dec_n_heads=0, dec_d_ffn=0, ln_l1=0, q8_output=0)
 
 CONFIGS = {
     # tiny parity student

@@ -40,6 +40,9 @@ typedef struct {
   /* 1: every layer normalisation divides by the scaled mean absolute deviation instead of the standard
      deviation (Sec. 3.1 "FP16 Inference": the L1-norm replacement; see ora_layer_norm_l1) */
   int32_t ln_l1;
+  /* 1: the output layer is an 8-bit matrix multiplication (Sec. 3.2 "8-bit Matrix Multiplication with Packing",
+     Eq. 3-6; see the q8 functions below) */
+  int32_t q8_output;
   double ln_eps;
 } ora_config;
 
@@ -56,6 +59,10 @@ typedef struct ora_model {
   ora_config c;
   float *w;               /* whole blob widened to fp32 */
   const float *E, *Wout;  /* [V][d] each; Wout == E when tied */
+  /* 8-bit output layer: codes [V][d], scale and zero point per vocabulary entry */
+  int8_t *q8_w;
+  float *q8_scale;
+  int32_t *q8_zero;
   enc_layer *enc;
   ln_t enc_final;
   dec_layer *dec;
@@ -107,11 +114,15 @@ static void take_ffn(const float **p, int64_t d, int64_t F, ffn_t *f) {
   f->W1 = take(p, d * F); f->b1 = take(p, F); f->W2 = take(p, F * d); f->b2 = take(p, d);
 }
 
+void ora_q8_weight_row(const float *w, int32_t d, int8_t *q, float *scale_out, int32_t *zero_out);
+static void q8_logits(const ora_model *m, const double *h, double *logits);
+
 ora_model *ora_load(const ora_config *c, const uint16_t *blob, int64_t n_halfs) {
   if (!c || !blob) return NULL;
   if (c->d_model <= 0 || c->n_heads <= 0 || c->d_model % c->n_heads || c->vocab <= 0 ||
       c->n_enc < 0 || c->n_dec < 1 || c->d_ffn < 0 || c->rpr_clip < 0) return NULL;
-  if (c->dec_n_heads < 0 || c->d_model % dec_heads(c) || c->dec_d_ffn < -1 || c->ln_l1 < 0 || c->ln_l1 > 1) return NULL;
+  if (c->dec_n_heads < 0 || c->d_model % dec_heads(c) || c->dec_d_ffn < -1 || c->ln_l1 < 0 || c->ln_l1 > 1 ||
+      c->q8_output < 0 || c->q8_output > 1) return NULL;
   if (n_halfs != ora_param_count(c)) return NULL;
   ora_model *m = (ora_model *)calloc(1, sizeof *m);
   m->c = *c;
@@ -140,11 +151,19 @@ ora_model *ora_load(const ora_config *c, const uint16_t *blob, int64_t n_halfs) 
   }
   take_ln(&p, d, &m->dec_final);
   if (p - m->w != n_halfs) { free(m->enc); free(m->dec); free(m->w); free(m); return NULL; }
+  if (c->q8_output) {
+    m->q8_w = (int8_t *)malloc((size_t)(V * d));
+    m->q8_scale = (float *)malloc(sizeof(float) * (size_t)V);
+    m->q8_zero = (int32_t *)malloc(sizeof(int32_t) * (size_t)V);
+    for (int64_t v = 0; v < V; v++)
+      ora_q8_weight_row(m->Wout + v * d, (int32_t)d, m->q8_w + v * d, &m->q8_scale[v], &m->q8_zero[v]);
+  }
   return m;
 }
 
 void ora_free(ora_model *m) {
   if (!m) return;
+  free(m->q8_w); free(m->q8_scale); free(m->q8_zero);
   free(m->enc); free(m->dec); free(m->w); free(m);
 }
 
@@ -357,13 +376,118 @@ static void dec_step(const ora_model *m, dec_state *s, int32_t y_prev, int32_t t
   }
   norm(c, z, m->dec_final.g, m->dec_final.b, a);
   /* output layer: plain logits, no bias, no log-softmax */
-  for (int v = 0; v < V; v++) {
+  if (m->q8_w) q8_logits(m, a, logits);
+  else for (int v = 0; v < V; v++) {
     const float *w = m->Wout + (int64_t)v * d;
     double acc = 0.0;
     for (int e = 0; e < d; e++) acc += a[e] * (double)w[e];
     logits[v] = acc;
   }
   free(z);
+}
+
+/* ---- 8-bit output layer (Sec. 3.2 "8-bit Matrix Multiplication with Packing") ----------------------------
+ * The paper quantises every column of a weight matrix on its own (Eq. 3, 4) and the input matrix with one scale
+ * and zero point (Eq. 5, 6).  Readings taken here:
+ *  - a column of the output layer's matrix is one vocabulary entry v (the d weights that produce its logit);
+ *  - Eq. 4 and Eq. 6 as printed divide the whole bracket by the scale, which maps neither end of the range onto
+ *    an end of the 8-bit range; they are read as  zero = 127 - (mean + 7 sd) / scale  and
+ *    zero = 255 - x_max / scale, which send mean + 7 sd to 127 and x_max to 255 (and so mean - 7 sd to -128
+ *    and x_min to 0); zero points are rounded to integers, codes are round-to-nearest-even and clamped;
+ *  - the input is quantised per row (one decoder state) instead of per matrix, so that a sentence's result does
+ *    not depend on its batch mates; weights are signed 8-bit codes, activations unsigned 8-bit codes;
+ *  - weight statistics and codes are computed in double, in index order; the activation side runs in the
+ *    kernel's precision, fp32, one rounding per operation:
+ *        a_scale = (max - min) / 255      a_zero = rint(255 - max / a_scale)      u_k = rint(h_k / a_scale + a_zero)
+ *  - logit[v] = a_scale * (b_scale[v] * float(I_v)),  I_v = sum_k (u_k - a_zero) (q_vk - zero_v)  exactly in
+ *    integers; the arg-max is taken on t_v = b_scale[v] * float(I_v) in fp32 (a_scale > 0 is common to the row).
+ */
+/* (built with -std=c11: gcc then contracts no multiply-add, so every operation below rounds once) */
+
+/* Eq. 3, 4 for one vocabulary entry: w[d] -> codes q[d], scale, zero point */
+void ora_q8_weight_row(const float *w, int32_t d, int8_t *q, float *scale_out, int32_t *zero_out) {
+  double mean = 0.0, var = 0.0;
+  for (int k = 0; k < d; k++) mean += (double)w[k];
+  mean /= (double)d;
+  for (int k = 0; k < d; k++) {
+    double c = (double)w[k] - mean;
+    var += c * c;
+  }
+  var /= (double)d;
+  double sd = sqrt(var);
+  double scale = sd > 0.0 ? 14.0 * sd / 255.0 : 1.0;
+  double zero = rint(127.0 - (mean + 7.0 * sd) / scale);
+  for (int k = 0; k < d; k++) {
+    double c = rint((double)w[k] / scale + zero);
+    q[k] = (int8_t)(c < -128.0 ? -128.0 : (c > 127.0 ? 127.0 : c));
+  }
+  *scale_out = (float)scale;
+  *zero_out = (int32_t)zero;
+}
+
+/* Eq. 5, 6 for one row of activations, in fp32: h[d] -> codes u[d] in [0, 255], scale, zero point */
+void ora_q8_activation_row(const float *h, int32_t d, uint8_t *u, float *scale_out, int32_t *zero_out) {
+  float mn = h[0], mx = h[0];
+  for (int k = 1; k < d; k++) {
+    mn = h[k] < mn ? h[k] : mn;
+    mx = h[k] > mx ? h[k] : mx;
+  }
+  float range = mx - mn;
+  float scale = range > 0.0f ? range / 255.0f : 1.0f;
+  float ratio = mx / scale;
+  float zero = rintf(255.0f - ratio);
+  for (int k = 0; k < d; k++) {
+    float c = h[k] / scale;
+    c = rintf(c + zero);
+    u[k] = (uint8_t)(c < 0.0f ? 0.0f : (c > 255.0f ? 255.0f : c));
+  }
+  *scale_out = scale;
+  *zero_out = (int32_t)zero;
+}
+
+/* logits[V] of the 8-bit output layer for one decoder state h[d] (given in double, rounded to fp32 first) */
+static void q8_logits(const ora_model *m, const double *h, double *logits) {
+  int d = m->c.d_model, V = m->c.vocab;
+  float *hf = (float *)malloc(sizeof(float) * (size_t)d);
+  uint8_t *u = (uint8_t *)malloc((size_t)d);
+  for (int k = 0; k < d; k++) hf[k] = (float)h[k];
+  float a_scale;
+  int32_t a_zero;
+  ora_q8_activation_row(hf, d, u, &a_scale, &a_zero);
+  for (int v = 0; v < V; v++) {
+    const int8_t *q = m->q8_w + (int64_t)v * d;
+    int64_t I = 0;
+    for (int k = 0; k < d; k++) I += (int64_t)((int32_t)u[k] - a_zero) * (int64_t)((int32_t)q[k] - m->q8_zero[v]);
+    float t = m->q8_scale[v] * (float)I;
+    logits[v] = (double)a_scale * (double)t; /* exact in double: the order of the t_v is kept */
+  }
+  free(u); free(hf);
+}
+
+/* the same for a caller's fp32 rows (tests): h [R][d] -> logits [R][V] as fp32 = a_scale * t_v rounded once */
+int ora_q8_output_layer(const ora_model *m, const float *h, int32_t R, float *logits, int32_t *argmax) {
+  if (!m || !m->q8_w) return -1;
+  int d = m->c.d_model, V = m->c.vocab;
+  double *hd = (double *)malloc(sizeof(double) * (size_t)d), *lg = (double *)malloc(sizeof(double) * (size_t)V);
+  for (int r = 0; r < R; r++) {
+    for (int k = 0; k < d; k++) hd[k] = (double)h[(int64_t)r * d + k];
+    q8_logits(m, hd, lg);
+    int best = 0;
+    for (int v = 1; v < V; v++) if (lg[v] > lg[best]) best = v;
+    if (argmax) argmax[r] = best;
+    if (logits) for (int v = 0; v < V; v++) logits[(int64_t)r * V + v] = (float)lg[v];
+  }
+  free(lg); free(hd);
+  return 0;
+}
+
+/* the stored codes of one vocabulary entry (tests) */
+int ora_q8_weights(const ora_model *m, int32_t v, int8_t *q, float *scale, int32_t *zero) {
+  if (!m || !m->q8_w || v < 0 || v >= m->c.vocab) return -1;
+  memcpy(q, m->q8_w + (int64_t)v * m->c.d_model, (size_t)m->c.d_model);
+  *scale = m->q8_scale[v];
+  *zero = m->q8_zero[v];
+  return 0;
 }
 
 /* ---- public calls ---- */

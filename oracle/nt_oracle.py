@@ -36,7 +36,7 @@ def build(force: bool = True) -> str:
 class _Cfg(C.Structure):
     _fields_ = [(k, C.c_int32) for k in ("n_enc", "n_dec", "d_model", "n_heads", "d_ffn", "vocab",
                                          "max_len", "rpr_clip", "tie_output", "bos_id",
-                                         "dec_n_heads", "dec_d_ffn", "ln_l1")] + [("ln_eps", C.c_double)]
+                                         "dec_n_heads", "dec_d_ffn", "ln_l1", "q8_output")] + [("ln_eps", C.c_double)]
 
 
 _lib = None
@@ -79,6 +79,14 @@ def lib():
         L.ora_greedy_eos.argtypes = [p, p, i32, i32, i32, p, p]
         L.ora_translate_eos.restype = i32
         L.ora_translate_eos.argtypes = [p, p, p, i64, i32, i32, p, p, p, i32]
+        L.ora_q8_weight_row.restype = None
+        L.ora_q8_weight_row.argtypes = [p, i32, p, p, p]
+        L.ora_q8_activation_row.restype = None
+        L.ora_q8_activation_row.argtypes = [p, i32, p, p, p]
+        L.ora_q8_output_layer.restype = i32
+        L.ora_q8_output_layer.argtypes = [p, p, i32, p, p]
+        L.ora_q8_weights.restype = i32
+        L.ora_q8_weights.argtypes = [p, i32, p, p, p]
         L.ora_teacher_forced.restype = i32
         L.ora_teacher_forced.argtypes = [p, p, i32, p, i32, p]
         L.ora_translate.restype = i32
@@ -90,7 +98,7 @@ def lib():
 def _cfg(cfg: dict) -> _Cfg:
     c = _Cfg()
     for k, _ in _Cfg._fields_:
-        setattr(c, k, cfg.get(k, 0) if k.startswith("dec_") or k == "ln_l1" else cfg[k])
+        setattr(c, k, cfg.get(k, 0) if k.startswith("dec_") or k in ("ln_l1", "q8_output") else cfg[k])
     return c
 
 
@@ -166,6 +174,24 @@ def attend(q, K, V, heads=1, rk=None, clip=0, qpos=0):
     return c, probs
 
 
+def q8_weight_row(w):
+    """Eq. 3, 4 for one vocabulary entry: (codes int8 [d], scale float32, zero point int)."""
+    w = _f32(w)
+    q = np.empty(w.size, dtype=np.int8)
+    sc, z = C.c_float(), C.c_int32()
+    lib().ora_q8_weight_row(_ptr(w), w.size, _ptr(q), C.byref(sc), C.byref(z))
+    return q, np.float32(sc.value), int(z.value)
+
+
+def q8_activation_row(h):
+    """Eq. 5, 6 for one row, in fp32: (codes uint8 [d], scale float32, zero point int)."""
+    h = _f32(h)
+    u = np.empty(h.size, dtype=np.uint8)
+    sc, z = C.c_float(), C.c_int32()
+    lib().ora_q8_activation_row(_ptr(h), h.size, _ptr(u), C.byref(sc), C.byref(z))
+    return u, np.float32(sc.value), int(z.value)
+
+
 class Model:
     def __init__(self, cfg: dict, blob: np.ndarray):
         assert blob.dtype == np.float16
@@ -212,6 +238,23 @@ class Model:
         if n < 0:
             raise ValueError(f"oracle: greedy failed ({n})")
         return out[:n].copy(), margin[:n].copy()
+
+    def q8_output_layer(self, h):
+        """8-bit output layer on fp32 rows h [R, d]: (logits float32 [R, V], argmax int32 [R])."""
+        h = np.ascontiguousarray(h, dtype=np.float32)
+        R = h.shape[0]
+        logits = np.empty((R, self.cfg["vocab"]), dtype=np.float32)
+        am = np.empty(R, dtype=np.int32)
+        if lib().ora_q8_output_layer(self._h, _ptr(h), R, _ptr(logits), _ptr(am)):
+            raise ValueError("oracle: model has no 8-bit output layer")
+        return logits, am
+
+    def q8_weights(self, v: int):
+        q = np.empty(self.cfg["d_model"], dtype=np.int8)
+        sc, z = C.c_float(), C.c_int32()
+        if lib().ora_q8_weights(self._h, v, _ptr(q), C.byref(sc), C.byref(z)):
+            raise ValueError("oracle: no 8-bit weights")
+        return q, np.float32(sc.value), int(z.value)
 
     def teacher_forced(self, src, tgt_in) -> np.ndarray:
         src, tgt_in = _i32(src), _i32(tgt_in)

@@ -351,6 +351,94 @@ def test_eos_terminated_greedy_search(oracle):
         m.greedy_eos(sents[0], cfg["vocab"])
 
 
+# ---------------------------------------------------------------- 8-bit output layer (Sec. 3.2, Eq. 3-6)
+def test_q8_weight_quantiser_closed_forms_and_error_bound(oracle):
+    d = 64
+    # +-a alternating: mean 0, sd a -> scale 14a/255, zero = rint(127 - 127.5) = rint(-0.5) = 0 (to even),
+    # codes rint(+-255/14) = +-18
+    a = 0.03125
+    q, sc, z = oracle.q8_weight_row(np.where(np.arange(d) % 2 == 0, a, -a))
+    assert sc == np.float32(14 * a / 255) and z == 0
+    assert np.array_equal(q, np.where(np.arange(d) % 2 == 0, 18, -18))
+    # shifted by m = 3a: zero = rint(127 - (3a + 7a) * 255 / (14a)) = rint(127 - 182.142...) = -55,
+    # codes rint((3a +- a) * 255 / (14a) - 55) = rint(72.857 - 55), rint(36.43 - 55) = 18, -19
+    q, sc, z = oracle.q8_weight_row(3 * a + np.where(np.arange(d) % 2 == 0, a, -a))
+    assert z == -55 and np.array_equal(q, np.where(np.arange(d) % 2 == 0, 18, -19))
+    # the ends of the range: mean + 7 sd -> 127 and mean - 7 sd -> -128 (Eq. 3, 4 as read); beyond: clamped.
+    # one large entry among zeros: n = 256 values, one of them b -> mean b/256, sd = b sqrt(255)/256
+    n, b = 256, 1.0
+    w = np.zeros(n); w[7] = b
+    q, sc, z = oracle.q8_weight_row(w)
+    mean, sd = b / n, b * math.sqrt(n - 1) / n
+    scale = 14 * sd / 255
+    assert sc == np.float32(scale) and z == round(127 - (mean + 7 * sd) / scale)
+    assert q[7] == 127 and q[0] == round(0 / scale + z)          # b is 15.9 sd above the mean: clamped
+    # rounding error of everything inside the range is at most half a step
+    rng = np.random.default_rng(3)
+    w = (rng.normal(0.01, 0.05, 512)).astype(np.float16).astype(np.float64)
+    q, sc, z = oracle.q8_weight_row(w)
+    inside = np.abs(w - w.mean()) < 6.9 * w.std()
+    back = float(sc) * (q.astype(np.float64) - z)
+    assert np.abs(back - w)[inside].max() <= 0.5 * float(sc) * (1 + 1e-6)
+    assert inside.all() and -128 <= q.min() and q.max() <= 127
+    # a constant column has no spread: scale 1, every code equal
+    q, sc, z = oracle.q8_weight_row(np.full(d, 0.25))
+    assert sc == 1.0 and len(set(q.tolist())) == 1
+
+
+def test_q8_activation_quantiser_ends_codes_and_error_bound(oracle):
+    rng = np.random.default_rng(4)
+    h = rng.normal(0, 1, 512).astype(np.float32)
+    u, sc, z = oracle.q8_activation_row(h)
+    assert sc == np.float32((h.max() - h.min()) / np.float32(255))
+    assert u[h.argmax()] == 255 and u[h.argmin()] == 0                      # Eq. 5, 6 as read: the ends of the range
+    back = np.float64(sc) * (u.astype(np.float64) - z)
+    assert np.abs(back - h).max() <= 0.5 * float(sc) * 1.001 + 1e-6
+    # exact small case: h = 0, 1, ..., 255 -> scale 1, zero 0, codes = h
+    u, sc, z = oracle.q8_activation_row(np.arange(256, dtype=np.float32))
+    assert sc == 1.0 and z == 0 and np.array_equal(u, np.arange(256))
+    # shifted and scaled: h = 10 + 0.5 k -> scale 0.5, zero = rint(255 - 137.5 / 0.5) = -20, codes k
+    u, sc, z = oracle.q8_activation_row((10 + 0.5 * np.arange(256)).astype(np.float32))
+    assert sc == 0.5 and z == -20 and np.array_equal(u, np.arange(256))
+    u, sc, z = oracle.q8_activation_row(np.full(16, 3.0, dtype=np.float32))           # no spread: scale 1
+    assert sc == 1.0 and len(set(u.tolist())) == 1
+
+
+def test_q8_output_layer_is_the_integer_definition_and_close_to_the_exact_layer(oracle):
+    cfg = tiny(vocab=97, q8_output=1)
+    blob = nt_synth.make_weights(cfg, seed=41, random_affine=True)
+    m, exact = oracle.Model(cfg, blob), oracle.Model(dict(cfg, q8_output=0), blob)
+    d, V = cfg["d_model"], cfg["vocab"]
+    W = onp.Weights(cfg, blob)["W_out"]                                       # [V, d] float64
+    rng = np.random.default_rng(42)
+    h = rng.normal(0, 1, (5, d)).astype(np.float32)
+    logits, am = m.q8_output_layer(h)
+    for r in range(5):
+        u, a_sc, a_z = oracle.q8_activation_row(h[r])
+        worst = 0.0
+        for v in range(V):
+            q, b_sc, b_z = m.q8_weights(v)
+            q2, b_sc2, b_z2 = oracle.q8_weight_row(W[v])
+            assert np.array_equal(q, q2) and b_sc == b_sc2 and b_z == b_z2   # the model holds Eq. 3, 4 of its own matrix
+            I = sum((int(u[k]) - a_z) * (int(q[k]) - b_z) for k in range(d))   # Python integers: exact
+            t = np.float32(b_sc) * np.float32(I)
+            assert logits[r, v] == np.float32(np.float64(a_sc) * np.float64(t))
+            # against the exact product: each factor is off by at most half a step
+            bound = (0.5 * b_sc * np.abs(h[r]).sum() + 0.5 * a_sc * np.abs(W[v]).sum() + 0.25 * a_sc * b_sc * d) * 1.01
+            err = abs(float(logits[r, v]) - float(h[r].astype(np.float64) @ W[v]))
+            assert err <= bound
+            worst = max(worst, err / bound)
+        assert worst > 0.01                                                    # the bound is not vacuous
+        assert am[r] == int(np.argmax(logits[r]))
+    # inside the model: the decoder's logits are this layer applied to its final state; the rest is untouched
+    src, tgt = np.array([9, 8, 7, 6, 5]), np.array([1, 11, 12])
+    lq, le = m.teacher_forced(src, tgt), exact.teacher_forced(src, tgt)
+    assert np.array_equal(m.encode(src), exact.encode(src))
+    assert 1e-4 < np.abs(lq - le).max() < 0.2
+    out, _ = m.greedy(src, 6)
+    assert np.array_equal(out, np.argmax(m.teacher_forced(src, np.concatenate([[1], out[:-1]])), -1))
+
+
 def test_tied_embedding_collapse(oracle):
     """With tied output weights, sqrt(d) embedding scale and random weights the logit of the
     previous token dominates (~ sqrt(d) |E_y|^2 / sigma_z against N(0,1) for the others), so
