@@ -393,7 +393,9 @@ static void dec_step(const ora_model *m, dec_state *s, int32_t y_prev, int32_t t
  *  - Eq. 4 and Eq. 6 as printed divide the whole bracket by the scale, which maps neither end of the range onto
  *    an end of the 8-bit range; they are read as  zero = 127 - (mean + 7 sd) / scale  and
  *    zero = 255 - x_max / scale, which send mean + 7 sd to 127 and x_max to 255 (and so mean - 7 sd to -128
- *    and x_min to 0); zero points are rounded to integers, codes are round-to-nearest-even and clamped;
+ *    and x_min to 0); zero points are rounded to integers and, like the codes, kept inside the 8-bit range
+ *    (the convention of the FBGEMM library the paper uses: a zero point is itself a code; this only matters
+ *    for a column or row whose values all lie far to one side of zero); codes are round-to-nearest-even, clamped;
  *  - the input is quantised per row (one decoder state) instead of per matrix, so that a sentence's result does
  *    not depend on its batch mates; weights are signed 8-bit codes, activations unsigned 8-bit codes;
  *  - weight statistics and codes are computed in double, in index order; the activation side runs in the
@@ -417,6 +419,7 @@ void ora_q8_weight_row(const float *w, int32_t d, int8_t *q, float *scale_out, i
   double sd = sqrt(var);
   double scale = sd > 0.0 ? 14.0 * sd / 255.0 : 1.0;
   double zero = rint(127.0 - (mean + 7.0 * sd) / scale);
+  zero = zero < -128.0 ? -128.0 : (zero > 127.0 ? 127.0 : zero); /* a zero point is a code of the same 8 bits */
   for (int k = 0; k < d; k++) {
     double c = rint((double)w[k] / scale + zero);
     q[k] = (int8_t)(c < -128.0 ? -128.0 : (c > 127.0 ? 127.0 : c));
@@ -436,6 +439,7 @@ void ora_q8_activation_row(const float *h, int32_t d, uint8_t *u, float *scale_o
   float scale = range > 0.0f ? range / 255.0f : 1.0f;
   float ratio = mx / scale;
   float zero = rintf(255.0f - ratio);
+  zero = zero < 0.0f ? 0.0f : (zero > 255.0f ? 255.0f : zero);
   for (int k = 0; k < d; k++) {
     float c = h[k] / scale;
     c = rintf(c + zero);

@@ -397,9 +397,16 @@ def test_q8_activation_quantiser_ends_codes_and_error_bound(oracle):
     # exact small case: h = 0, 1, ..., 255 -> scale 1, zero 0, codes = h
     u, sc, z = oracle.q8_activation_row(np.arange(256, dtype=np.float32))
     assert sc == 1.0 and z == 0 and np.array_equal(u, np.arange(256))
-    # shifted and scaled: h = 10 + 0.5 k -> scale 0.5, zero = rint(255 - 137.5 / 0.5) = -20, codes k
+    # shifted and scaled: h = -10 + 0.5 k -> scale 0.5, zero = rint(255 - 117.5 / 0.5) = 20, codes k
+    u, sc, z = oracle.q8_activation_row((-10 + 0.5 * np.arange(256)).astype(np.float32))
+    assert sc == 0.5 and z == 20 and np.array_equal(u, np.arange(256))
+    # a row entirely above zero: the zero point rint(255 - 137.5 / 0.5) = -20 is kept inside the code range (0),
+    # the codes h / 0.5 = 20 + k saturate at 255
     u, sc, z = oracle.q8_activation_row((10 + 0.5 * np.arange(256)).astype(np.float32))
-    assert sc == 0.5 and z == -20 and np.array_equal(u, np.arange(256))
+    assert sc == 0.5 and z == 0 and np.array_equal(u, np.minimum(20 + np.arange(256), 255))
+    # likewise a weight column far to one side of zero: mean 5, sd 0.01 -> the zero point saturates at -128
+    q, wsc, wz = oracle.q8_weight_row(5.0 + 0.01 * np.where(np.arange(64) % 2 == 0, 1.0, -1.0))
+    assert wz == -128 and (q == 127).all()
     u, sc, z = oracle.q8_activation_row(np.full(16, 3.0, dtype=np.float32))           # no spread: scale 1
     assert sc == 1.0 and len(set(u.tolist())) == 1
 
