@@ -25,6 +25,7 @@ import nt_synth  # noqa: E402
 WORDS_PER_TOKEN = 1.0 / 1.3          # the benchmark's convention: 1 word = 1.3 tokens
 HBM_PEAK_GBS = 8000.0                # MI355X HBM3E
 MFMA_F16_PEAK_TFLOPS = 2500.0        # dense fp16 MFMA
+MFMA_I8_PEAK_TOPS = 5000.0           # dense int8 MFMA
 # HBM traffic per launch (decode step) of the dominant kernel family from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs, calibrated against a streaming kernel of known size (see profiles/); None where
 # it has not been measured.
@@ -54,6 +55,7 @@ def main():
                     help="override the workload's embedding sharing (random shared embeddings make greedy "
                          "decoding re-emit BOS, which makes every certified arg-max trivially cheap)")
     ap.add_argument("--ln-l1", action="store_true", help="L1-norm layer normalisation in every block")
+    ap.add_argument("--q8", action="store_true", help="8-bit output layer (int8 matrix cores) instead of the fp16 one")
     ap.add_argument("--eos-gain", type=float, default=None,
                     help="scale the EOS row of the output matrix by this factor and also time the EOS-terminated "
                          "entry point against the fixed-length one on the same weights (adds an eos_mode object)")
@@ -84,6 +86,7 @@ def main():
     if args.tie_output is not None:
         cfg["tie_output"] = args.tie_output
     cfg["ln_l1"] = int(args.ln_l1)
+    cfg["q8_output"] = int(args.q8)
     blob = nt_synth.make_weights(cfg, seed=0, eos_gain=args.eos_gain)
     tokens, offsets = nt_synth.workload(args.workload, args.sentences)
     lens = np.diff(offsets).astype(np.int32)
@@ -181,10 +184,12 @@ def main():
                            GBps=round(k["bytes"] / k["ms"] / 1e6, 1), TFLOPs=round(k["flops"] / k["ms"] / 1e9, 2))
                 for name, k in kern.items()}
 
-    def roof(k):
+    def roof(k, name=None):
         intensity = k["flops"] / k["bytes"]
-        if intensity > MFMA_F16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
-            bound, achieved, peak, unit = "mfma", k["flops"] / k["ms"] / 1e9, MFMA_F16_PEAK_TFLOPS, "TFLOP/s"
+        # the 8-bit output layer runs on the int8 matrix cores: twice the fp16 peak
+        mfma_peak, unit = (MFMA_I8_PEAK_TOPS, "TOP/s") if (args.q8 and name == "vocab_argmax") else (MFMA_F16_PEAK_TFLOPS, "TFLOP/s")
+        if intensity > mfma_peak * 1e12 / (HBM_PEAK_GBS * 1e9):
+            bound, achieved, peak = "mfma", k["flops"] / k["ms"] / 1e9, mfma_peak
         else:
             bound, achieved, peak, unit = "hbm", k["bytes"] / k["ms"] / 1e6, HBM_PEAK_GBS, "GB/s"
         return dict(bound=bound, achieved=round(achieved, 2), peak=peak, unit=unit, frac=round(achieved / peak, 4),
@@ -206,10 +211,10 @@ def main():
     # is kept beside it.
     dom = max(kern_solo, key=lambda n: kern_solo[n]["ms"])
     k = kern_solo[dom]
-    roofline = dict(kernel=dom, **roof(k), traffic=MEASURED_TRAFFIC_BYTES.get((dom, args.workload, args.budget)),
+    roofline = dict(kernel=dom, **roof(k, dom), traffic=MEASURED_TRAFFIC_BYTES.get((dom, args.workload, args.budget)),
                     algorithmic_bytes_per_launch=round(k["bytes"] / k["launches"]),
                     algorithmic_flops_per_launch=round(k["flops"] / k["launches"]),
-                    as_timed_with_lanes=roof(kern[dom]))
+                    as_timed_with_lanes=roof(kern[dom], dom))
 
     calibration_copy(torch, args.calib_copy_mib)
 
@@ -230,11 +235,11 @@ def main():
         "metric": "source words/sec (greedy decode, 1 MI355X)",
         "value": round(words_per_s, 1), "unit": "words/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(1e3 * dt, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "data": "synthetic",
+        "dtype": "f16 (output layer: int8)" if args.q8 else "f16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {n_sent} sentences (lognormal lengths, Zipf ids), student "
                                f"{cfg['n_enc']}-{cfg['n_dec']} d={cfg['d_model']} heads={cfg['n_heads']} ffn={cfg['d_ffn']} "
                                f"decoder heads={nt_synth.dec_heads(cfg)} ffn={nt_synth.dec_ffn(cfg)} "
-                               f"V={cfg['vocab']} tied={cfg['tie_output']} l1_norm={cfg['ln_l1']}, greedy ceil(1.2 len)+2 steps",
+                               f"V={cfg['vocab']} tied={cfg['tie_output']} l1_norm={cfg['ln_l1']} q8_output={cfg['q8_output']}, greedy ceil(1.2 len)+2 steps",
                    "token_budget": args.budget, "batches": len(batches), "pipeline_lanes": len(lanes), "source_tokens": src_tokens,
                    "target_tokens": tgt_tokens, "decode_steps": dec_steps},
         "source_tokens_per_s": round(src_tokens / dt, 1), "target_tokens_per_s": round(tgt_tokens / dt, 1),

@@ -69,6 +69,16 @@ typedef struct nt_model nt_model; /* opaque */
  *                  (Sec. 3.1 "FP16 Inference"): y = g (x - mean) / (sqrt(pi/2) mean|x - mean| + ln_eps) + b,
  *                  the mean absolute deviation scaled so that it equals the standard deviation for
  *                  normal activations; 0: the vanilla form
+ *   q8_output      1: the output layer is an 8-bit matrix multiplication (Sec. 3.2 "8-bit Matrix
+ *                  Multiplication with Packing", the paper's CPU optimisation, here on the int8 matrix
+ *                  cores).  Every vocabulary entry's d weights are quantised at load time with their own
+ *                  scale 14 sd / 255 and zero point (Eq. 3, 4) and packed in matrix-core order; every
+ *                  decoder state is quantised per row with scale (max - min) / 255 and its zero point
+ *                  (Eq. 5, 6; per row, not per matrix, so that a sentence never depends on its batch
+ *                  mates).  Zero points are integers inside the 8-bit range; Eq. 4 and 6 are read as
+ *                  127 - (mean + 7 sd) / scale and 255 - max / scale.  The logit is
+ *                  a_scale * (b_scale[v] * float(I)) with I = sum_k (u_k - a_zero)(q_vk - zero_v) exact.
+ *                  Needs d_model 256 or 512.  0: fp16 matrix cores with ~22-bit activations.
  *   max_batch_tokens, max_batch_rows
  *                  largest padded batch (rows x longest row) and most rows per batch the
  *                  arena must hold; the peak footprint is fixed at load time, in the spirit
@@ -86,6 +96,7 @@ typedef struct {
                              internal stream; 0 = default (4, one per hardware queue), 1 = no overlap */
   int32_t dec_n_heads, dec_d_ffn;
   int32_t ln_l1;
+  int32_t q8_output;
 } nt_config;
 
 /* Number of fp16 elements the weight blob of this configuration must hold (0 if invalid). */
@@ -138,6 +149,18 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
  */
 int nt_decode_greedy(nt_model *m, int32_t B, int32_t n_steps, const int32_t *h_row_steps, int32_t *d_out,
                      void *hip_stream);
+
+/*
+ * The 8-bit output layer alone (models loaded with q8_output = 1), for checking it against its
+ * definition on given inputs: d_h [R, d_model] fp32 rows (used as they are: no LayerNorm) are
+ * quantised per row and multiplied with the packed 8-bit output matrix.
+ *   d_argmax [R] int32 (optional): arg-max over the vocabulary of b_scale[v] * float(I), lowest id on
+ *   ties, from the fused kernel that greedy decoding uses;
+ *   d_logits [R, vocab] fp32 (optional): a_scale * (b_scale[v] * float(I)).
+ * R must not exceed max_batch_rows.  Errors: NT_ESTATE if the model has no 8-bit output layer.
+ */
+int nt_debug_q8_output_layer(nt_model *m, const float *d_h, int32_t R, int32_t *d_argmax, float *d_logits,
+                             void *hip_stream);
 
 /*
  * Greedy decoding that ends a sentence at its end symbol (Sec. 3.3 "Greedy Search": the paper's

@@ -17,7 +17,8 @@ EXPORTS = ["nt_param_count", "nt_n_steps", "nt_load_weights", "nt_free", "nt_enc
            "nt_translate_batch", "nt_plan_batches", "nt_debug_encoder_out", "nt_debug_teacher_forced_logits",
            "nt_check_device_flags", "nt_device_bytes", "nt_last_error", "nt_debug_timing_enable",
            "nt_debug_timing_count", "nt_debug_timing_name", "nt_debug_timing_read", "nt_pipeline_lanes",
-           "nt_pipeline_lane", "nt_lane_stream", "nt_decode_greedy_eos", "nt_translate_batch_eos"]
+           "nt_pipeline_lane", "nt_lane_stream", "nt_decode_greedy_eos", "nt_translate_batch_eos",
+           "nt_debug_q8_output_layer"]
 
 
 class NtConfig(C.Structure):
@@ -25,7 +26,7 @@ class NtConfig(C.Structure):
         "n_enc", "n_dec", "d_model", "n_heads", "d_ffn", "vocab", "max_len", "rpr_clip", "tie_output", "bos_id",
         "pad_id")] + [("ln_eps", C.c_float), ("max_batch_rows", C.c_int32), ("max_batch_tokens", C.c_int64),
                                 ("pipeline_lanes", C.c_int32), ("dec_n_heads", C.c_int32),
-                                ("dec_d_ffn", C.c_int32), ("ln_l1", C.c_int32)]
+                                ("dec_d_ffn", C.c_int32), ("ln_l1", C.c_int32), ("q8_output", C.c_int32)]
 
 
 class NtError(RuntimeError):
@@ -59,6 +60,7 @@ def load_library() -> C.CDLL:
         "nt_decode_greedy": (C.c_int, [p, i32, i32, p, p, p]),
         "nt_translate_batch": (C.c_int, [p, p, p, i64, i64, i32, p, p, p]),
         "nt_decode_greedy_eos": (C.c_int, [p, i32, i32, p, i32, p, p, p]),
+        "nt_debug_q8_output_layer": (C.c_int, [p, p, i32, p, p, p]),
         "nt_translate_batch_eos": (C.c_int, [p, p, p, i64, i64, i32, i32, p, p, p, p]),
         "nt_plan_batches": (C.c_int, [p, i64, i64, i32, p, p, C.POINTER(i64)]),
         "nt_debug_encoder_out": (C.c_int, [p, p, p]),
@@ -104,6 +106,7 @@ def make_config(cfg: dict, max_batch_tokens: int, max_batch_rows: int = 0, pipel
     c.dec_n_heads = int(cfg.get("dec_n_heads", 0))
     c.dec_d_ffn = int(cfg.get("dec_d_ffn", 0))
     c.ln_l1 = int(cfg.get("ln_l1", 0))
+    c.q8_output = int(cfg.get("q8_output", 0))
     return c
 
 
@@ -214,6 +217,13 @@ class Model:
             rs = np.ascontiguousarray(row_steps, dtype=np.int32)
         _check(lib().nt_decode_greedy_eos(self._h, B, steps, rs.ctypes.data_as(C.c_void_p) if rs is not None else None,
                                           int(eos_id), d_out.data_ptr(), d_out_len.data_ptr(), _stream_ptr(stream)))
+
+    def debug_q8_output_layer(self, d_h, d_argmax=None, d_logits=None, stream=None):
+        """The 8-bit output layer alone on fp32 rows d_h [R, d] (cuda): arg-max int32 [R] and/or logits fp32 [R, V]."""
+        assert d_h.is_cuda and d_h.is_contiguous()
+        _check(lib().nt_debug_q8_output_layer(self._h, d_h.data_ptr(), d_h.shape[0],
+                                              d_argmax.data_ptr() if d_argmax is not None else None,
+                                              d_logits.data_ptr() if d_logits is not None else None, _stream_ptr(stream)))
 
     def debug_encoder_out(self, d_out, stream=None):
         _check(lib().nt_debug_encoder_out(self._h, d_out.data_ptr(), _stream_ptr(stream)))

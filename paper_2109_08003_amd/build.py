@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnt.so")
-SOURCES = ["nt_host.hip", "nt_gemm.hip", "nt_gemm_stream.hip", "nt_vocab.hip", "nt_rows.hip", "nt_attn.hip"]
+SOURCES = ["nt_host.hip", "nt_gemm.hip", "nt_gemm_stream.hip", "nt_vocab.hip", "nt_vocab_q8.hip", "nt_rows.hip", "nt_attn.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

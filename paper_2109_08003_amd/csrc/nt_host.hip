@@ -140,6 +140,12 @@ struct nt_model {
   const _Float16 *E = nullptr, *Wout = nullptr;
   const _Float16 *Wout_frag = nullptr;  // the output matrix in MFMA fragment order (streaming arg-max kernels)
   nt::VocabWeights vw;
+  // 8-bit output layer (q8_output): codes in MFMA fragment order, per-entry constants
+  const int8_t *Wq8 = nullptr;
+  const void *q8_consts = nullptr;
+  int8_t *q8_codes = nullptr;                       // arena: [Br, d] activation codes of the current step
+  float *q8_scale = nullptr;                        // arena: [Br] per-row scale
+  int32_t *q8_c = nullptr, *q8_sa = nullptr;        // arena: [Br] 128 - zero point, sum of the signed codes
   const float *pe = nullptr;
   std::vector<EncLayer> enc;
   std::vector<DecLayer> dec;
@@ -223,6 +229,8 @@ int check_config(const nt_config *c) {
   if (c->bos_id < 0 || c->bos_id >= c->vocab || c->pad_id < 0 || c->pad_id >= c->vocab) return fail(NT_ERANGE, "bos_id/pad_id outside the vocabulary");
   if (!(c->ln_eps > 0.f)) return fail(NT_EINVAL, "ln_eps must be positive");
   if (c->ln_l1 != 0 && c->ln_l1 != 1) return fail(NT_EINVAL, "ln_l1 must be 0 or 1");
+  if (c->q8_output != 0 && c->q8_output != 1) return fail(NT_EINVAL, "q8_output must be 0 or 1");
+  if (c->q8_output && !nt::vocab_q8_supported(c->d_model)) return fail(NT_ESHAPE, "the 8-bit output layer needs d_model 256 or 512");
   if (c->pipeline_lanes < 0 || c->pipeline_lanes > 8 ) return fail(NT_EINVAL, "pipeline_lanes must be in [0,8]");
   return NT_OK;
 }
@@ -294,6 +302,7 @@ int alloc_lane_state(nt_model *m, hipStream_t s) {
       const int64_t rows = std::min<int64_t>(mt * 64, Br);
       worst = std::max(worst, rows * nt::vocab_argmax_partials(m->vw, (int)rows, false));
       worst = std::max(worst, rows * nt::vocab_argmax_partials(m->vw, (int)rows, true));
+      if (cfg->q8_output) worst = std::max(worst, rows * nt::vocab_q8_partials((int)rows));
     }
     m->pk_elems = worst;
   }
@@ -313,7 +322,9 @@ int alloc_lane_state(nt_model *m, hipStream_t s) {
                o_src = cv.take((size_t)Mt * 4), o_lin = cv.take((size_t)Br * 4), o_out = cv.take((size_t)m->self_positions * 4),
                o_org0 = cv.take((size_t)Br * 4), o_org1 = cv.take((size_t)Br * 4), o_ey = cv.take((size_t)Br * 4),
                o_etok = cv.take((size_t)Br * 4), o_cap = cv.take((size_t)Br * 4), o_olen = cv.take((size_t)Br * 4),
-               o_kvn = cv.take((size_t)Br * 2 * d * 4);
+               o_kvn = cv.take((size_t)Br * 2 * d * 4),
+               o_q8c = cv.take(cfg->q8_output ? (size_t)Br * d : 16), o_q8s = cv.take((size_t)Br * 4),
+               o_q8z = cv.take((size_t)Br * 4), o_q8a = cv.take((size_t)Br * 4);
   m->arena_bytes = cv.off;
   if (hipMalloc((void **)&m->d_arena, m->arena_bytes) != hipSuccess) return fail(NT_ENOMEM, "hipMalloc of %zu arena bytes failed", m->arena_bytes);
   char *A = m->d_arena;
@@ -330,6 +341,8 @@ int alloc_lane_state(nt_model *m, hipStream_t s) {
   m->origin[0] = at<int32_t>(A, o_org0); m->origin[1] = at<int32_t>(A, o_org1); m->eos_y = at<int32_t>(A, o_ey);
   m->eos_tok = at<int32_t>(A, o_etok); m->d_cap = at<int32_t>(A, o_cap); m->d_out_len = at<int32_t>(A, o_olen);
   m->kv_new = at<float>(A, o_kvn);
+  m->q8_codes = at<int8_t>(A, o_q8c); m->q8_scale = at<float>(A, o_q8s); m->q8_c = at<int32_t>(A, o_q8z);
+  m->q8_sa = at<int32_t>(A, o_q8a);
   HIP_TRY(nt::launch_fill_i32(m->flags, 16, 0, s));
   for (auto &st : m->stage) {
     if (hipHostMalloc((void **)&st.h_src, (size_t)Mt * 4) != hipSuccess || hipHostMalloc((void **)&st.h_len, (size_t)Br * 4) != hipSuccess ||
@@ -565,6 +578,13 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
     size_t o = pk.reserve(nt::vocab_pack_bytes(V, d));
     nt::vocab_pack(Wo, V, d, (_Float16 *)(pk.img.data() + o));
     fixes.push_back({o, (const void **)&m->Wout_frag});
+  }
+  if (cfg->q8_output) {  // Eq. 3, 4: the output matrix as 8-bit codes, packed
+    const _Float16 *Wo = (const _Float16 *)h_blob_fp16 + (cfg->tie_output ? 0 : (int64_t)V * d);
+    size_t oc = pk.reserve(nt::vocab_q8_pack_bytes(V, d)), ok = pk.reserve(nt::vocab_q8_const_bytes(V));
+    nt::vocab_q8_pack(Wo, V, d, (int8_t *)(pk.img.data() + oc), pk.img.data() + ok);
+    fixes.push_back({oc, (const void **)&m->Wq8});
+    fixes.push_back({ok, (const void **)&m->q8_consts});
   }
   {  // sinusoid table, evaluated in double
     size_t o = pk.reserve((size_t)cfg->max_len * d * 4);
@@ -888,6 +908,24 @@ int decode_step(nt_model *m, DecodeCursor &cu, hipStream_t s) {
         if ((rc = dec_gemm(K_GEMM_DEC_FFN, m->u32, F, L.ffn.W2, u_planes ? L.ffn.W2_p : nullptr, d, nullptr, f2))) return rc;
       }
     }
+    if (c.q8_output) {
+      // 8-bit output layer: the final LayerNorm writes the row's codes, scale and zero point (Eq. 5, 6) ...
+      KT(K_LN_DEC, Rd * dd * 5, 12 * Rd * dd,
+         nt::launch_q8_rows(m->z, R, d, m->dec_final.g, m->dec_final.b, lne, m->q8_codes, m->q8_scale, m->q8_c, m->q8_sa, s));
+      if (d_logits) {
+        KT(K_GEMM_LOGITS, Rd * dd + (double)V * dd + Rd * V * 4, 2 * Rd * dd * V,
+           nt::launch_q8_logits(m->q8_codes, m->q8_scale, m->q8_c, R, m->Wq8, m->q8_consts, V, d,
+                                d_logits + (long)t * V, (long)T * V, s));
+      } else {
+        // ... and the integer product is fused with the arg-max; its result is final, no second pass
+        const int np_ = nt::vocab_q8_partials(R);
+        KT(K_VOCAB_ARGMAX, (double)V * dd + Rd * dd + Rd * np_ * 8, 2 * Rd * dd * V,
+           nt::launch_vocab_q8_argmax(m->q8_codes, m->q8_c, m->q8_sa, R, m->Wq8, m->q8_consts, V, d, m->pk, s));
+        cu.prev_cert = false;
+        cu.partials_prev = np_;
+      }
+      return NT_OK;
+    }
     // final LayerNorm as a head/tail plane pair (the planes share the a32 buffer), then the output layer
     _Float16 *h_hi = (_Float16 *)m->a32, *h_lo = h_hi + (long)m->max_rows * d;
     KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd,
@@ -1018,6 +1056,26 @@ int nt_debug_teacher_forced_logits(nt_model *m, const int32_t *d_tgt_in, int32_t
   if (!d_tgt_in || !d_logits) return fail(NT_EINVAL, "null argument");
   if (T == 0) return NT_OK;
   return run_decoder(m, B, T, nullptr, d_tgt_in, nullptr, d_logits, as_stream(hip_stream));
+}
+
+int nt_debug_q8_output_layer(nt_model *m, const float *d_h, int32_t R, int32_t *d_argmax, float *d_logits,
+                             void *hip_stream) {
+  if (!m || !d_h) return fail(NT_EINVAL, "null argument");
+  if (!m->c.q8_output) return fail(NT_ESTATE, "the model was loaded without the 8-bit output layer");
+  if (R < 1 || R > m->max_rows) return fail(NT_ERANGE, "R = %d outside [1, max_batch_rows = %lld]", R, (long long)m->max_rows);
+  hipStream_t s = as_stream(hip_stream);
+  const int d = m->c.d_model, V = m->c.vocab;
+  HIP_TRY(nt::launch_q8_rows(d_h, R, d, nullptr, nullptr, ln_eps_of(m->c), m->q8_codes, m->q8_scale, m->q8_c, m->q8_sa, s));
+  if (d_logits)
+    HIP_TRY(nt::launch_q8_logits(m->q8_codes, m->q8_scale, m->q8_c, R, m->Wq8, m->q8_consts, V, d, d_logits, V, s));
+  if (d_argmax) {
+    HIP_TRY(nt::launch_vocab_q8_argmax(m->q8_codes, m->q8_c, m->q8_sa, R, m->Wq8, m->q8_consts, V, d, m->pk, s));
+    nt::StepBeginArgs a{};  // only its first half runs: the partial keys of "step 0" are reduced into d_argmax
+    a.t = 1; a.rows_prev = R; a.rows_now = 0; a.d = d; a.vocab = V; a.bos_id = m->c.bos_id; a.pad_id = m->c.pad_id;
+    a.pk = m->pk; a.n_partials = nt::vocab_q8_partials(R); a.out = d_argmax; a.out_ld = 1; a.flags = m->flags;
+    HIP_TRY(nt::launch_step_begin(a, s));
+  }
+  return NT_OK;
 }
 
 int nt_debug_encoder_out(nt_model *m, float *d_out, void *hip_stream) {

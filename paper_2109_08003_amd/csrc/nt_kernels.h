@@ -141,6 +141,27 @@ hipError_t launch_argmax_select(const unsigned long long *pk, const float *ps, i
                                 float w_norm_max, int32_t *tok, int32_t *slot_of_row, int32_t *list, int32_t *count,
                                 unsigned long long *final_key, unsigned long long *need_mask, hipStream_t s);
 
+// ---- 8-bit output layer fused with the row arg-max (nt_vocab_q8.hip; Sec. 3.2, Eq. 3-6) ----------------------------
+bool vocab_q8_supported(int K);
+size_t vocab_q8_pack_bytes(int N, int K);
+size_t vocab_q8_const_bytes(int N);
+// Host: quantise Wt [N][K] per vocabulary entry and lay the codes out in MFMA fragment order, the per-entry
+// constants (scale, zero point, sum of codes - K * zero point) in accumulator order.
+void vocab_q8_pack(const _Float16 *Wt, int N, int K, int8_t *codes, void *consts);
+// x [M][d] fp32 -> [LayerNorm if gamma != nullptr ->] unsigned 8-bit codes per row, stored as signed bytes
+// (code - 128) in codes [M][d]; a_scale [M]; c [M] = 128 - zero point; sa [M] = sum of the signed bytes.  d = 256 / 512.
+hipError_t launch_q8_rows(const float *x, int M, int d, const float *gamma, const float *beta, LnEps eps, int8_t *codes,
+                          float *a_scale, int32_t *c_out, int32_t *sa_out, hipStream_t s);
+// partial keys per row that launch_vocab_q8_argmax writes for M rows
+int vocab_q8_partials(int M);
+// pk[m * vocab_q8_partials(M) + p]: largest b_scale[v] * float(I[m][v]) of a range of the vocabulary, as packed keys
+hipError_t launch_vocab_q8_argmax(const int8_t *codes, const int32_t *c_row, const int32_t *sa_row, int M,
+                                  const int8_t *Wq, const void *consts, int N, int K, unsigned long long *pk,
+                                  hipStream_t s);
+// logits[m * ld + v] = a_scale[m] * (b_scale[v] * float(I[m][v])) by the definition (debug / teacher-forced path)
+hipError_t launch_q8_logits(const int8_t *codes, const float *a_scale, const int32_t *c_row, int M, const int8_t *Wq,
+                            const void *consts, int N, int K, float *logits, long ld, hipStream_t s);
+
 // ---- row kernels --------------------------------------------------------------------
 // x[r,:] = sqrt(d) * E[id] + PE[pos]; rows r = b*S + s, pos = s.  Out-of-range ids are
 // replaced by pad_id and flags[0] is set.  Also clamps len into [1,S] -> len_out.

@@ -514,6 +514,69 @@ def test_eos_translate_against_oracle_and_fixed_length(nt, oracle):
     assert sum(np.array_equal(a[ao[i]: ao[i] + al[i]], cut[i]) for i in range(1500)) >= 1493
 
 
+# ------------------------------------------------------------------------------ 8-bit output layer (Sec. 3.2, Eq. 3-6)
+@pytest.mark.parametrize("name", ["C0", "C1"])
+def test_q8_output_layer_is_bit_exact(nt, oracle, torch_cuda, name):
+    """The 8-bit output layer alone on given fp32 rows: codes, integer products and the fp32 scaling are
+    defined operation by operation, so logits and arg-max must equal the oracle's bit for bit.  C0 has a
+    vocabulary of 4,000 (a ragged last strip of 32 entries), C1 the 32,000 x 512 matrix of the benchmark."""
+    torch = torch_cuda
+    cfg = nt_synth.model_config(name, q8_output=1)
+    blob = nt_synth.make_weights(cfg, seed=0, random_affine=True)
+    gm, om = nt.Model(cfg, blob, max_batch_tokens=4096), oracle.Model(cfg, blob)
+    d, V = cfg["d_model"], cfg["vocab"]
+    rng = np.random.default_rng(91)
+    for R in (1, 37, 129, 300 if name == "C1" else 700):
+        h = rng.normal(0, 1, (R, d)).astype(np.float32)
+        h[0] = np.abs(h[0]) + 0.5                      # a row entirely above zero: its zero point saturates
+        if R > 2:
+            h[1] = 0.75                                # a row without spread
+            h[2] *= 1e-3
+        want_logits, want_am = om.q8_output_layer(h)
+        am = torch.full((R,), -1, dtype=torch.int32, device="cuda")
+        logits = torch.empty((R, V), dtype=torch.float32, device="cuda")
+        gm.debug_q8_output_layer(torch.from_numpy(h).cuda(), am, logits)
+        torch.cuda.synchronize()
+        got_logits, got_am = logits.cpu().numpy(), am.cpu().numpy()
+        assert np.array_equal(got_logits.view(np.uint32), want_logits.view(np.uint32)), (name, R)
+        assert np.array_equal(got_am, want_am), (name, R)
+
+
+def test_q8_greedy_against_oracle(nt, oracle):
+    """Greedy decoding with the 8-bit output layer against the oracle's 8-bit model.  The decoder states that
+    are quantised come from two different pipelines (fp16 matrix cores here, fp64 there), so a code can fall on
+    the other side of a rounding boundary: a mismatch must be a near-tie of the oracle's 8-bit logits."""
+    cfg = nt_synth.model_config("C1", q8_output=1)
+    blob = nt_synth.make_weights(cfg, seed=0)
+    tokens, offsets = nt_synth.workload("C1", 1500)
+    gm = nt.Model(cfg, blob, max_batch_tokens=32768)
+    out, oo = gm.translate_batch(tokens, offsets, token_budget=32768)
+    out2, _ = gm.translate_batch(tokens, offsets, token_budget=32768)
+    assert np.array_equal(out, out2)
+    lens = np.diff(offsets)
+    rng = np.random.default_rng(92)
+    order = np.argsort(-lens, kind="stable")
+    sample = np.unique(np.concatenate([rng.choice(1500, size=200, replace=False), order[:3], order[-5:]]))
+    om = oracle.Model(cfg, blob)
+    sents = [tokens[offsets[i]:offsets[i + 1]] for i in sample]
+    sub_off = np.concatenate([[0], np.cumsum([len(s) for s in sents])])
+    o_out, o_oo, _ = om.translate(np.concatenate(sents), sub_off)
+    gaps, bad = [], 0
+    for k, i in enumerate(sample):
+        g, o = out[oo[i]:oo[i + 1]], o_out[o_oo[k]:o_oo[k + 1]]
+        if np.array_equal(g, o):
+            continue
+        bad += 1
+        t = int(np.nonzero(g != o)[0][0])
+        logits = om.teacher_forced(sents[k], np.concatenate([[cfg["bos_id"]], o[:t]]).astype(np.int32))[t]
+        gaps.append(float(logits[o[t]] - logits[g[t]]))
+    frac = 1.0 - bad / len(sample)
+    print(f"q8 greedy: {len(sample) - bad}/{len(sample)} sampled sentences identical ({100 * frac:.2f} %), "
+          f"gaps of the mismatches: {sorted(round(x, 4) for x in gaps)}")
+    assert all(0 <= x < 5e-2 for x in gaps)
+    assert frac >= 0.80
+
+
 # ------------------------------------------------------------------------------ C5 (shape of the submitted student)
 def test_c5_submitted_student_shape(nt, oracle, torch_cuda):
     """Student-3-1-512 (Table 2, Sec. 5): 3 encoder layers with 8 heads and FFN 2,048, one decoder layer
