@@ -211,7 +211,7 @@ def main():
     # is kept beside it.
     dom = max(kern_solo, key=lambda n: kern_solo[n]["ms"])
     k = kern_solo[dom]
-    roofline = dict(kernel=dom, **roof(k, dom), traffic=MEASURED_TRAFFIC_BYTES.get((dom, args.workload, args.budget)),
+    roofline = dict(kernel=dom, **roof(k, dom), traffic=None if args.q8 else MEASURED_TRAFFIC_BYTES.get((dom, args.workload, args.budget)),
                     algorithmic_bytes_per_launch=round(k["bytes"] / k["launches"]),
                     algorithmic_flops_per_launch=round(k["flops"] / k["launches"]),
                     as_timed_with_lanes=roof(kern[dom], dom))

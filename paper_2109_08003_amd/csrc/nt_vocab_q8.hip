@@ -20,18 +20,19 @@
 // entries at a time and all rows of the tile, a lane owns one row of each 32-row block and folds the strip's
 // logits into its running best.  One 32x32x32 i8 MFMA covers twice the k-range of a 32x32x16 fp16 one in the same
 // time, the bytes per weight halve, and there is no second pass: the integer result is final.
-// The per-entry constants of a strip (scale, zero point, P: 768 B) are copied into a per-wave LDS slot by one
-// asynchronous load at the start of the strip and read back when the strip is folded.
+// The per-entry constants of a strip (scale, zero point, P: 768 B) are fetched at the start of the strip, parked
+// in a per-wave LDS slot half-way through it, and read back when the strip is folded.
 //
 // Fragment order of the packed codes: [strip = v / 64][ks = k / 32][nb = (v % 64) / 32][lane][16 bytes] with
 // lane = v % 32 + 32 * ((k % 32) / 16): lane l of the MFMA row operand holds q[v = l % 32][k = 16 * (l / 32) .. + 15].
-// Constants: [strip][type: scale, zero, P][nb][g = 0, 1][16] where entry e of (nb, g) is column
+// Constants: [strip][type: scale, -zero, P][nb][g = 0, 1][16] where entry e of (nb, g) is column
 // nb * 32 + (e / 4) * 8 + g * 4 + e % 4 of the strip: the order in which a lane's accumulator registers run.
 #include "nt_kernels.h"
 
 #include <cmath>
 #include <cstring>
 #include <mutex>
+#include <type_traits>
 #include <vector>
 
 namespace nt {
@@ -94,7 +95,7 @@ void vocab_q8_pack(const _Float16 *Wt, int N, int K, int8_t *codes, void *consts
     const int g = (c32 >> 2) & 1, e = (c32 >> 3) * 4 + (c32 & 3);
     const size_t base = (size_t)strip * (Q8_CONST_BYTES / 4) + (size_t)nb * 32 + (size_t)g * 16 + (size_t)e;
     cf[base] = sc;
-    ci[base + 64] = zero;
+    ci[base + 64] = -zero;
     ci[base + 128] = sum - K * zero;
   }
   for (int strip = 0; strip < NS; strip++)
@@ -217,7 +218,9 @@ __global__ __launch_bounds__(Q8_WAVES * 64) void vocab_q8_kernel(const int8_t *_
                                                                 const int32_t *__restrict__ sa_row, int M,
                                                                 const int8_t *__restrict__ Wq,
                                                                 const void *__restrict__ consts, int N, int m_tiles,
-                                                                int G, int per_xcd, unsigned long long *__restrict__ pk) {
+                                                                int G, int per_xcd, int ns_div_g, int ns_mod_g,
+                                                                unsigned int m_tiles_magic,
+                                                                unsigned long long *__restrict__ pk) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int LD = K + 16;      // bytes per LDS row: the pad keeps the 16-byte fragment reads conflict-free
   constexpr int KS = K / 32;      // k-steps of one i8 MFMA
@@ -231,9 +234,15 @@ __global__ __launch_bounds__(Q8_WAVES * 64) void vocab_q8_kernel(const int8_t *_
     const int end = ((blockIdx.x & 7) + 1) * per_xcd;
     if (idx >= (end < total ? end : total)) return;  // uniform over the workgroup
   }
-  const int gi = idx / m_tiles, mt = idx % m_tiles;
+  // idx / m_tiles without a division (which would run on the vector unit and leave everything derived from it,
+  // the offsets of the fragment loads included, in vector registers): multiply-high by ceil(2^32 / m_tiles) from
+  // the host, exact for idx * m_tiles < 2^32
+  const int gi = m_tiles_magic ? (int)__umulhi((unsigned int)idx, m_tiles_magic) : idx;  // (2^32 itself does not fit)
+  const int mt = idx - gi * m_tiles;
   const int NS = (N + 63) >> 6;
-  const int sb0 = gi * NS / G, sb1 = (gi + 1) * NS / G;
+  // range gi of G near-equal ranges of the NS strips (quotient and remainder come from the host)
+  const int sb0 = gi * ns_div_g + (gi < ns_mod_g ? gi : ns_mod_g);
+  const int sb1 = sb0 + ns_div_g + (gi < ns_mod_g ? 1 : 0);
   unsigned char *cslot = smem + Q8_ROWS * LD + wave * Q8_CONST_BYTES;  // this wave's copy of a strip's constants
 
   const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void *)Wq, 0, NS * 64 * K, 0x00020000);
@@ -303,12 +312,11 @@ __global__ __launch_bounds__(Q8_WAVES * 64) void vocab_q8_kernel(const int8_t *_
         const bool more = strip + Q8_WAVES < sb1;
         const int pcur = strip * (KS * 2048);
         const int pnext = (more ? strip + Q8_WAVES : strip) * (KS * 2048);
-        // the constants of this strip: one asynchronous 768-byte copy into the wave's LDS slot (48 lanes x 16 B)
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the previous strip's reads of the slot have returned
+        // the constants of this strip (768 B): 48 lanes fetch 16 bytes each now and put them into the wave's LDS
+        // slot half-way through the k-loop, when they have arrived; the fold reads them back from there
+        q8_u32x4 cfrag = {0u, 0u, 0u, 0u};
         if (lane < Q8_CONST_BYTES / 16)
-          __builtin_amdgcn_global_load_lds(
-              (const __attribute__((address_space(1))) void *)((const unsigned char *)consts + (long)strip * Q8_CONST_BYTES + lane * 16),
-              (__attribute__((address_space(3))) void *)cslot, 16, 0, 0);
+          cfrag = *(const q8_u32x4 *)((const unsigned char *)consts + (long)strip * Q8_CONST_BYTES + lane * 16);
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
           const int tgt = ks + SL - 1;
@@ -330,41 +338,48 @@ __global__ __launch_bounds__(Q8_WAVES * 64) void vocab_q8_kernel(const int8_t *_
               wb[tgt % SL][0] = wload(pf, 0);
               wb[tgt % SL][1] = wload(pf, 1);
             }
+            if (ks == KS / 2 && op == 3 && lane < Q8_CONST_BYTES / 16) *(q8_u32x4 *)(cslot + lane * 16) = cfrag;
             __builtin_amdgcn_sched_barrier(0);
           }
         }
-        // The constants were requested before every load of this strip's k-loop; at most the 2 (SL - 1) fragment
-        // loads of the lookahead are younger and may still be in flight.
-        static_assert(SL == 4, "the wait below counts 2 (SL - 1) younger loads");
-        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
         // ---- strip done: logits t = scale[v] * float(D + c[r] P[v] - zero[v] SA[r]), folded into the running best ----
-        const bool masked = strip * 64 + 64 > N;
+        // (the strip that runs past the end of the vocabulary takes the variant that masks those entries)
+        auto fold = [&](auto masked_tag) {
+          constexpr bool MASKED = decltype(masked_tag)::value;
 #pragma unroll
-        for (int nb = 0; nb < 2; nb++) {
+          for (int nb = 0; nb < 2; nb++) {
 #pragma unroll
-          for (int j = 0; j < 4; j++) {
-            const float4 sc4 = *(const float4 *)(cslot + 0 + nb * 128 + g * 64 + j * 16);
-            const int4 ze4 = *(const int4 *)(cslot + 256 + nb * 128 + g * 64 + j * 16);
-            const int4 p4 = *(const int4 *)(cslot + 512 + nb * 128 + g * 64 + j * 16);
-            const float sc[4] = {sc4.x, sc4.y, sc4.z, sc4.w};
-            const int ze[4] = {ze4.x, ze4.y, ze4.z, ze4.w};
-            const int pp[4] = {p4.x, p4.y, p4.z, p4.w};
+            for (int j = 0; j < 4; j++) {
+              const float4 sc4 = *(const float4 *)(cslot + 0 + nb * 128 + g * 64 + j * 16);
+              const int4 nz4 = *(const int4 *)(cslot + 256 + nb * 128 + g * 64 + j * 16);
+              const int4 p4 = *(const int4 *)(cslot + 512 + nb * 128 + g * 64 + j * 16);
+              const float sc[4] = {sc4.x, sc4.y, sc4.z, sc4.w};
+              const int nz[4] = {nz4.x, nz4.y, nz4.z, nz4.w};
+              const int pp[4] = {p4.x, p4.y, p4.z, p4.w};
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
-              const int v = j * 4 + i;
-              const bool dead = masked && (strip * 64 + nb * 32 + j * 8 + g * 4 + i >= N);
+              for (int i = 0; i < 4; i++) {
+                const int v = j * 4 + i;
 #pragma unroll
-              for (int a = 0; a < 4; a++) {
-                const int I = acc[a][nb][v] + __mul24(crow[a], pp[i]) - __mul24(ze[i], sarow[a]);
-                float val = sc[i] * (float)I;
-                val = dead ? -INFINITY : val;
-                const bool gt = val > rmax[a];  // codes ascend with the column: on equal logits the lower column stays
-                rmax[a] = gt ? val : rmax[a];
-                rcode[a] = gt ? (strip * 32 + nb * 16 + v) : rcode[a];
+                for (int a = 0; a < 4; a++) {
+                  // I = D + c P - zero SA as two 24-bit multiply-adds (every factor is below 2^23 in magnitude).  The
+                  // empty asm only keeps the compiler from merging the two additions into a three-operand add behind
+                  // two multiplies; the accumulator itself is read by an instruction the compiler schedules (it knows
+                  // the distance a matrix-core result needs).
+                  int t1 = __mul24(crow[a], pp[i]) + acc[a][nb][v];
+                  asm("" : "+v"(t1));
+                  const int I = __mul24(nz[i], sarow[a]) + t1;
+                  float val = sc[i] * (float)I;
+                  if (MASKED) val = (strip * 64 + nb * 32 + j * 8 + g * 4 + i < N) ? val : -INFINITY;
+                  const bool gt = val > rmax[a];  // codes ascend with the column: on equal logits the lower column stays
+                  rmax[a] = gt ? val : rmax[a];
+                  rcode[a] = gt ? (strip * 32 + nb * 16 + v) : rcode[a];
+                }
               }
+              __builtin_amdgcn_sched_barrier(0);  // one group of constants at a time: keeps the registers for the ring
             }
           }
-        }
+        };
+        if (strip * 64 + 64 <= N) fold(std::false_type{}); else fold(std::true_type{});
       }
     }
     __syncthreads();  // every wave is done with the tile: its LDS now carries the per-wave results
@@ -409,10 +424,12 @@ hipError_t launch_vocab_q8_argmax(const int8_t *codes, const int32_t *c_row, con
   });
   if (attr_err != hipSuccess) return attr_err;
   const dim3 grid(8 * p.per_xcd), block(Q8_WAVES * 64);
+  const int NS = (N + 63) / 64, qd = NS / p.G, qm = NS % p.G;
+  const unsigned int magic = p.m_tiles == 1 ? 0u : (unsigned int)(((1ull << 32) + p.m_tiles - 1) / p.m_tiles);
   if (K == 512)
-    hipLaunchKernelGGL((vocab_q8_kernel<512>), grid, block, lds, s, codes, c_row, sa_row, M, Wq, consts, N, p.m_tiles, p.G, p.per_xcd, pk);
+    hipLaunchKernelGGL((vocab_q8_kernel<512>), grid, block, lds, s, codes, c_row, sa_row, M, Wq, consts, N, p.m_tiles, p.G, p.per_xcd, qd, qm, magic, pk);
   else
-    hipLaunchKernelGGL((vocab_q8_kernel<256>), grid, block, lds, s, codes, c_row, sa_row, M, Wq, consts, N, p.m_tiles, p.G, p.per_xcd, pk);
+    hipLaunchKernelGGL((vocab_q8_kernel<256>), grid, block, lds, s, codes, c_row, sa_row, M, Wq, consts, N, p.m_tiles, p.G, p.per_xcd, qd, qm, magic, pk);
   return hipGetLastError();
 }
 
@@ -429,7 +446,7 @@ __global__ __launch_bounds__(256) void q8_logits_kernel(const int8_t *__restrict
   const int g = (c32 >> 2) & 1, e = (c32 >> 3) * 4 + (c32 & 3);
   const long cb = (long)strip * (Q8_CONST_BYTES / 4) + nb * 32 + g * 16 + e;
   const float sc = ((const float *)consts)[cb];
-  const int zero = ((const int32_t *)consts)[cb + 64];
+  const int zero = -((const int32_t *)consts)[cb + 64];
   const int a_zero = 128 - c_row[r];
   int I = 0;
   for (int k = 0; k < K; k++) {
