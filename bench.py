@@ -29,7 +29,7 @@ MFMA_I8_PEAK_TOPS = 5000.0           # dense int8 MFMA
 # HBM traffic per launch (decode step) of the dominant kernel family from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs, calibrated against a streaming kernel of known size (see profiles/); None where
 # it has not been measured.
-MEASURED_TRAFFIC_BYTES = {("vocab_argmax", "C2", 65536): 59.5e6}
+MEASURED_TRAFFIC_BYTES = {("vocab_argmax", "C2", 65536, 0): 59.5e6, ("vocab_argmax", "C2", 65536, 1): 22.6e6}
 
 
 def calibration_copy(torch, mib):
@@ -211,7 +211,7 @@ def main():
     # is kept beside it.
     dom = max(kern_solo, key=lambda n: kern_solo[n]["ms"])
     k = kern_solo[dom]
-    roofline = dict(kernel=dom, **roof(k, dom), traffic=None if args.q8 else MEASURED_TRAFFIC_BYTES.get((dom, args.workload, args.budget)),
+    roofline = dict(kernel=dom, **roof(k, dom), traffic=MEASURED_TRAFFIC_BYTES.get((dom, args.workload, args.budget, int(args.q8))),
                     algorithmic_bytes_per_launch=round(k["bytes"] / k["launches"]),
                     algorithmic_flops_per_launch=round(k["flops"] / k["launches"]),
                     as_timed_with_lanes=roof(kern[dom], dom))
