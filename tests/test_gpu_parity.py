@@ -577,6 +577,62 @@ def test_q8_greedy_against_oracle(nt, oracle):
     assert frac >= 0.80
 
 
+def test_eos_edge_cases(nt, oracle):
+    """Empty sentences, one-token sentences, no sentences, a row cap, one lane."""
+    eos = nt_synth.EOS_ID
+    cfg = nt_synth.model_config("C0")
+    blob = nt_synth.make_weights(cfg, seed=0, eos_gain=1.7)
+    om = oracle.Model(cfg, blob)
+    rng = np.random.default_rng(5)
+    sents = [rng.integers(4, cfg["vocab"], size=n).astype(np.int32) for n in (0, 1, 30, 0, 5, 1, 17, 2, 0)]
+    tokens = np.concatenate(sents)
+    offsets = np.concatenate([[0], np.cumsum([len(x) for x in sents])])
+    want, w_oo, w_ol, _ = om.translate_eos(tokens, offsets, eos)
+    for lanes, budget, max_rows in ((0, 4096, 0), (1, 4096, 0), (0, 64, 0), (0, 4096, 2)):
+        gm = nt.Model(cfg, blob, max_batch_tokens=4096, pipeline_lanes=lanes)
+        out, oo, ol = gm.translate_batch_eos(tokens, offsets, budget, eos, max_rows=max_rows)
+        assert np.array_equal(oo, w_oo) and np.array_equal(ol, w_ol), (lanes, budget, max_rows)
+        assert np.array_equal(out, want), (lanes, budget, max_rows)
+        e_out, e_oo, e_ol = gm.translate_batch_eos(np.zeros(0, np.int32), np.zeros(1, np.int64), budget, eos)
+        assert len(e_out) == 0 and np.array_equal(e_oo, [0]) and len(e_ol) == 0
+        only_empty = gm.translate_batch_eos(np.zeros(0, np.int32), np.zeros(3, np.int64), budget, eos)
+        assert len(only_empty[0]) == 0 and np.array_equal(only_empty[2], [0, 0])
+        with pytest.raises(nt.NtError) as e:
+            gm.translate_batch_eos(tokens, offsets, budget, cfg["vocab"])
+        assert e.value.code == -6
+
+
+def test_all_options_together(nt, oracle):
+    """The submitted student's shape with L1-norm layer normalisation, the 8-bit output layer and EOS-terminated
+    decoding at once (Table 2, Sec. 3.1, 3.2, 3.3): a sample against the oracle configured the same way."""
+    eos = nt_synth.EOS_ID
+    cfg = nt_synth.model_config("C5", tie_output=0, ln_l1=1, q8_output=1)
+    blob = nt_synth.make_weights(cfg, seed=0, random_affine=True, eos_gain=1.6)
+    tokens, offsets = nt_synth.workload("C5", 900)
+    gm, om = nt.Model(cfg, blob, max_batch_tokens=32768), oracle.Model(cfg, blob)
+    out, oo, ol = gm.translate_batch_eos(tokens, offsets, 32768, eos)
+    rng = np.random.default_rng(6)
+    sample = np.sort(rng.choice(900, size=90, replace=False))
+    sents = [tokens[offsets[i]:offsets[i + 1]] for i in sample]
+    sub_off = np.concatenate([[0], np.cumsum([len(s) for s in sents])])
+    o_out, o_oo, o_ol, _ = om.translate_eos(np.concatenate(sents), sub_off, eos)
+    bad, gaps = 0, []
+    for k, i in enumerate(sample):
+        g, o = out[oo[i]: oo[i] + ol[i]], o_out[o_oo[k]: o_oo[k] + o_ol[k]]
+        if len(g) == len(o) and np.array_equal(g, o):
+            continue
+        bad += 1
+        n = min(len(g), len(o))
+        diff = np.nonzero(g[:n] != o[:n])[0]
+        assert len(diff), "one output is a strict prefix of the other"
+        t = int(diff[0])
+        logits = om.teacher_forced(sents[k], np.concatenate([[cfg["bos_id"]], o[:t]]).astype(np.int32))[t]
+        gaps.append(float(logits[o[t]] - logits[g[t]]))
+    print(f"all options: {len(sample) - bad}/{len(sample)} sampled sentences identical, gaps {sorted(round(x, 4) for x in gaps)}, "
+          f"{100 * ol.sum() / np.diff(oo).sum():.1f} % of the capped tokens emitted")
+    assert all(0 <= x < 5e-2 for x in gaps) and bad <= 0.2 * len(sample)
+
+
 # ------------------------------------------------------------------------------ C5 (shape of the submitted student)
 def test_c5_submitted_student_shape(nt, oracle, torch_cuda):
     """Student-3-1-512 (Table 2, Sec. 5): 3 encoder layers with 8 heads and FFN 2,048, one decoder layer
