@@ -108,7 +108,7 @@ def main():
             ids[r, : lens[i]] = tokens[offsets[i]:offsets[i + 1]]
         steps = np.array([nt.n_steps(int(lens[i])) for i in idx], dtype=np.int32)
         T = int(steps[0])
-        batches.append(dict(idx=idx, B=B, T=T, steps=steps, d_src=torch.from_numpy(ids).cuda(),
+        batches.append(dict(idx=idx, B=B, S=S, T=T, steps=steps, d_src=torch.from_numpy(ids).cuda(),
                             d_len=torch.from_numpy(lens[idx]).cuda(),
                             d_out=torch.empty((B, T), dtype=torch.int32, device="cuda")))
     if args.batch_stride > 1:
@@ -118,9 +118,17 @@ def main():
     tgt_tokens = int(sum(b["steps"].sum() for b in batches))
     dec_steps = int(sum(b["T"] for b in batches))
 
+    # a batch goes to the lane with the least estimated work so far, the rule nt_translate_batch uses (microseconds:
+    # 130 per decode step, 0.08 per row and step, 0.06 per padded source token), so that the lanes finish together
+    load, lane_of = [0.0] * len(lanes), []
+    for b in batches:
+        i = load.index(min(load))
+        lane_of.append(i)
+        load[i] += 130.0 * b["T"] + 0.08 * float(b["steps"].sum()) + 0.06 * b["B"] * b["S"]
+
     def one_pass():
         for k, b in enumerate(batches):
-            ln, st = lanes[k % len(lanes)], streams[k % len(lanes)]
+            ln, st = lanes[lane_of[k]], streams[lane_of[k]]
             ln.encode(b["d_src"], b["d_len"], stream=st)
             ln.decode_greedy(b["B"], b["T"], b["d_out"], row_steps=b["steps"], stream=st)
 

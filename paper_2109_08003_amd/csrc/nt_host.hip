@@ -1270,9 +1270,23 @@ int nt_translate_batch(nt_model *m, const int32_t *h_tokens, const int64_t *h_of
   };
   int first_err = NT_OK;
   const int64_t n_lanes = (int64_t)lane.size();
+  // A batch goes to the lane with the least estimated work so far (batches come in descending length, which is
+  // close to descending cost: longest-processing-time-first), so that the lanes finish together.  Cost in
+  // microseconds, fitted to solo batch times on the 200,000-sentence workload: a decode step costs about
+  // 130 us of launch and weight-stream latency plus 0.08 us per row, the encoder 0.06 us per padded token.
+  std::vector<double> lane_cost((size_t)n_lanes, 0.0);
+  std::vector<int64_t> lane_started((size_t)n_lanes, 0);
   for (int64_t k = 0; k < nb && first_err == NT_OK; k++) {
-    nt_model *ln = lane[(size_t)(k % n_lanes)];
-    nt_model::Staging &st = ln->stage[(k / n_lanes) % nt_model::kStagings];
+    const size_t li = (size_t)(std::min_element(lane_cost.begin(), lane_cost.end()) - lane_cost.begin());
+    nt_model *ln = lane[li];
+    nt_model::Staging &st = ln->stage[lane_started[li]++ % nt_model::kStagings];
+    {
+      const int64_t b0 = starts[(size_t)k], b1 = starts[(size_t)k + 1];
+      const int32_t S0 = lens[(size_t)order[(size_t)b0]];
+      double row_steps = 0.0;
+      for (int64_t i = b0; i < b1; i++) row_steps += nt_n_steps(lens[(size_t)order[(size_t)i]]);
+      lane_cost[li] += 130.0 * nt_n_steps(S0) + 0.08 * row_steps + 0.06 * (double)(b1 - b0) * S0;
+    }
     if ((first_err = collect(st))) break;
     const int64_t i0 = starts[(size_t)k], i1 = starts[(size_t)k + 1];
     const int32_t B = (int32_t)(i1 - i0), S = lens[(size_t)order[(size_t)i0]], T = nt_n_steps(S);
