@@ -1235,6 +1235,104 @@ int plan_translate(nt_model *m, const int32_t *h_tokens, const int64_t *h_offset
 
 }  // namespace
 
+namespace {
+
+// What the two translate calls share: the lanes, the host side of a batch (pack, copy in, encode; copy out, scatter)
+// and the draining of every lane at the end.
+struct Pipeline {
+  nt_model *m;
+  const TranslatePlan &plan;
+  const int32_t *h_tokens;
+  const int64_t *h_offsets;
+  int32_t *h_out;
+  const int64_t *h_out_offsets;
+  int32_t *h_out_len;  // EOS mode only
+  std::vector<nt_model *> lane;
+
+  // lanes wait for the work already queued on the caller's stream
+  int begin(hipStream_t s) {
+    lane.assign(1, m);
+    for (nt_model *ln : m->lanes) lane.push_back(ln);
+    HIP_TRY(hipEventRecord(m->lane_start, s));
+    for (nt_model *ln : lane) {
+      HIP_TRY(hipStreamWaitEvent(ln->lane_stream, m->lane_start, 0));
+      for (auto &st : ln->stage) st.busy = false;
+      ln->timing.mask = m->timing.mask;
+    }
+    return NT_OK;
+  }
+  // wait for the batch of this staging set and scatter its rows to their sentences
+  int collect(nt_model::Staging &st) {
+    if (!st.busy) return NT_OK;
+    HIP_TRY(hipEventSynchronize(st.done));
+    for (int64_t r = 0; r < st.i1 - st.i0; r++) {
+      const int64_t si = plan.order[(size_t)(st.i0 + r)];
+      memcpy(h_out + h_out_offsets[si], st.h_out + (size_t)r * st.T, (size_t)st.steps[(size_t)r] * 4);
+      if (h_out_len) h_out_len[si] = st.h_out_len[r];
+    }
+    st.busy = false;
+    return NT_OK;
+  }
+  // batch k into this staging set (free it first), over to the device, through the encoder
+  int start(nt_model *ln, nt_model::Staging &st, int64_t k, int32_t *B_out, int32_t *T_out) {
+    int rc = collect(st);
+    if (rc) return rc;
+    const nt_config &c = m->c;
+    const int64_t i0 = plan.starts[(size_t)k], i1 = plan.starts[(size_t)k + 1];
+    const int32_t B = (int32_t)(i1 - i0), S = plan.lens[(size_t)plan.order[(size_t)i0]], T = nt_n_steps(S);
+    if ((int64_t)B * T > ln->self_positions) return fail(NT_ENOMEM, "batch of %d rows x %d steps exceeds the self-attention cache", B, T);
+    st.steps.resize((size_t)B);
+    for (int32_t r = 0; r < B; r++) {
+      const int64_t si = plan.order[(size_t)(i0 + r)];
+      const int32_t L = plan.lens[(size_t)si];
+      st.h_len[r] = L;
+      st.steps[(size_t)r] = st.h_cap[r] = nt_n_steps(L);
+      int32_t *row = st.h_src + (size_t)r * S;
+      memcpy(row, h_tokens + h_offsets[si], (size_t)L * 4);
+      for (int32_t j = L; j < S; j++) row[j] = c.pad_id;
+    }
+    hipStream_t ls = ln->lane_stream;
+    if (hipMemcpyAsync(ln->d_src, st.h_src, (size_t)B * S * 4, hipMemcpyHostToDevice, ls) != hipSuccess ||
+        hipMemcpyAsync(ln->d_len_in, st.h_len, (size_t)B * 4, hipMemcpyHostToDevice, ls) != hipSuccess ||
+        (h_out_len && hipMemcpyAsync(ln->d_cap, st.h_cap, (size_t)B * 4, hipMemcpyHostToDevice, ls) != hipSuccess))
+      return fail(NT_EHIP, "host-to-device copy failed");
+    if ((rc = nt_encode(ln, ln->d_src, ln->d_len_in, B, S, ls))) return rc;
+    if (ln->timing.mask) {
+      ln->len_prefix.assign((size_t)B + 1, 0);
+      for (int32_t r = 0; r < B; r++) ln->len_prefix[(size_t)r + 1] = ln->len_prefix[(size_t)r] + st.h_len[r];
+    }
+    st.i0 = i0; st.i1 = i1; st.T = T;
+    *B_out = B; *T_out = T;
+    return NT_OK;
+  }
+  // the decode of this staging set's batch is queued: its outputs follow
+  int finish(nt_model *ln, nt_model::Staging &st) {
+    const int64_t B = st.i1 - st.i0;
+    hipStream_t ls = ln->lane_stream;
+    if (hipMemcpyAsync(st.h_out, ln->d_out, (size_t)B * st.T * 4, hipMemcpyDeviceToHost, ls) != hipSuccess ||
+        (h_out_len && hipMemcpyAsync(st.h_out_len, ln->d_out_len, (size_t)B * 4, hipMemcpyDeviceToHost, ls) != hipSuccess) ||
+        hipEventRecord(st.done, ls) != hipSuccess)
+      return fail(NT_EHIP, "device-to-host copy failed");
+    st.busy = true;
+    return NT_OK;
+  }
+  // every lane runs dry (also after an error: nothing may still be running when the call returns); a lane's batches
+  // finish in the order they were queued
+  int drain(int first_err) {
+    for (nt_model *ln : lane) {
+      int older = 0;
+      if (ln->stage[0].busy && ln->stage[1].busy && ln->stage[1].i0 < ln->stage[0].i0) older = 1;
+      for (int j = 0; j < nt_model::kStagings; j++)
+        if (first_err == NT_OK) first_err = collect(ln->stage[(older + j) % nt_model::kStagings]);
+      (void)hipStreamSynchronize(ln->lane_stream);
+      for (auto &st : ln->stage) st.busy = false;
+    }
+    return first_err;
+  }
+};
+
+}  // namespace
+
 extern "C" {
 
 int nt_translate_batch(nt_model *m, const int32_t *h_tokens, const int64_t *h_offsets, int64_t N, int64_t token_budget,
@@ -1242,96 +1340,31 @@ int nt_translate_batch(nt_model *m, const int32_t *h_tokens, const int64_t *h_of
   TranslatePlan plan;
   int rc = plan_translate(m, h_tokens, h_offsets, N, token_budget, max_rows, h_out, h_out_offsets, plan);
   if (rc || N == 0) return rc;
-  const nt_config &c = m->c;
-  const std::vector<int32_t> &lens = plan.lens;
-  const std::vector<int64_t> &order = plan.order, &starts = plan.starts;
-  const int64_t nb = plan.nb;
-  hipStream_t s = as_stream(hip_stream);
-  // lanes: batch k runs on lane k mod n on that lane's own stream.  Each lane has two sets of host staging, so its
-  // next batch is already queued while the current one runs; the host packs batches and unpacks finished ones while
-  // the device works.
-  std::vector<nt_model *> lane{m};
-  for (nt_model *ln : m->lanes) lane.push_back(ln);
-  HIP_TRY(hipEventRecord(m->lane_start, s));  // work already queued on the caller's stream comes first
-  for (nt_model *ln : lane) {
-    HIP_TRY(hipStreamWaitEvent(ln->lane_stream, m->lane_start, 0));
-    for (auto &st : ln->stage) st.busy = false;
-    ln->timing.mask = m->timing.mask;
-  }
-  auto collect = [&](nt_model::Staging &st) -> int {  // wait for the batch of this staging set and scatter its rows
-    if (!st.busy) return NT_OK;
-    HIP_TRY(hipEventSynchronize(st.done));
-    for (int64_t r = 0; r < st.i1 - st.i0; r++) {
-      const int64_t si = order[(size_t)(st.i0 + r)];
-      memcpy(h_out + h_out_offsets[si], st.h_out + (size_t)r * st.T, (size_t)st.steps[(size_t)r] * 4);
-    }
-    st.busy = false;
-    return NT_OK;
-  };
-  int first_err = NT_OK;
-  const int64_t n_lanes = (int64_t)lane.size();
+  // Each lane has two sets of host staging, so its next batch is already queued while the current one runs; the
+  // host packs batches and unpacks finished ones while the device works.
+  Pipeline pl{m, plan, h_tokens, h_offsets, h_out, h_out_offsets, nullptr, {}};
+  if ((rc = pl.begin(as_stream(hip_stream)))) return rc;
   // A batch goes to the lane with the least estimated work so far (batches come in descending length, which is
   // close to descending cost: longest-processing-time-first), so that the lanes finish together.  Cost in
   // microseconds, fitted to solo batch times on the 200,000-sentence workload: a decode step costs about
   // 130 us of launch and weight-stream latency plus 0.08 us per row, the encoder 0.06 us per padded token.
-  std::vector<double> lane_cost((size_t)n_lanes, 0.0);
-  std::vector<int64_t> lane_started((size_t)n_lanes, 0);
-  for (int64_t k = 0; k < nb && first_err == NT_OK; k++) {
+  const size_t n_lanes = pl.lane.size();
+  std::vector<double> lane_cost(n_lanes, 0.0);
+  std::vector<int64_t> lane_started(n_lanes, 0);
+  int first_err = NT_OK;
+  for (int64_t k = 0; k < plan.nb && first_err == NT_OK; k++) {
     const size_t li = (size_t)(std::min_element(lane_cost.begin(), lane_cost.end()) - lane_cost.begin());
-    nt_model *ln = lane[li];
+    nt_model *ln = pl.lane[li];
     nt_model::Staging &st = ln->stage[lane_started[li]++ % nt_model::kStagings];
-    {
-      const int64_t b0 = starts[(size_t)k], b1 = starts[(size_t)k + 1];
-      const int32_t S0 = lens[(size_t)order[(size_t)b0]];
-      double row_steps = 0.0;
-      for (int64_t i = b0; i < b1; i++) row_steps += nt_n_steps(lens[(size_t)order[(size_t)i]]);
-      lane_cost[li] += 130.0 * nt_n_steps(S0) + 0.08 * row_steps + 0.06 * (double)(b1 - b0) * S0;
-    }
-    if ((first_err = collect(st))) break;
-    const int64_t i0 = starts[(size_t)k], i1 = starts[(size_t)k + 1];
-    const int32_t B = (int32_t)(i1 - i0), S = lens[(size_t)order[(size_t)i0]], T = nt_n_steps(S);
-    if ((int64_t)B * T > ln->self_positions) { first_err = fail(NT_ENOMEM, "batch of %d rows x %d steps exceeds the self-attention cache", B, T); break; }
-    st.steps.resize((size_t)B);
-    for (int32_t r = 0; r < B; r++) {
-      const int64_t si = order[(size_t)(i0 + r)];
-      const int32_t L = lens[(size_t)si];
-      st.h_len[r] = L;
-      st.steps[(size_t)r] = nt_n_steps(L);
-      int32_t *row = st.h_src + (size_t)r * S;
-      memcpy(row, h_tokens + h_offsets[si], (size_t)L * 4);
-      for (int32_t j = L; j < S; j++) row[j] = c.pad_id;
-    }
-    hipStream_t ls = ln->lane_stream;
-    if (hipMemcpyAsync(ln->d_src, st.h_src, (size_t)B * S * 4, hipMemcpyHostToDevice, ls) != hipSuccess ||
-        hipMemcpyAsync(ln->d_len_in, st.h_len, (size_t)B * 4, hipMemcpyHostToDevice, ls) != hipSuccess) {
-      first_err = fail(NT_EHIP, "host-to-device copy failed");
-      break;
-    }
-    if ((first_err = nt_encode(ln, ln->d_src, ln->d_len_in, B, S, ls))) break;
-    if (ln->timing.mask) {
-      ln->len_prefix.assign((size_t)B + 1, 0);
-      for (int32_t r = 0; r < B; r++) ln->len_prefix[(size_t)r + 1] = ln->len_prefix[(size_t)r] + st.h_len[r];
-    }
-    if ((first_err = nt_decode_greedy(ln, B, T, st.steps.data(), ln->d_out, ls))) break;
-    if (hipMemcpyAsync(st.h_out, ln->d_out, (size_t)B * T * 4, hipMemcpyDeviceToHost, ls) != hipSuccess ||
-        hipEventRecord(st.done, ls) != hipSuccess) {
-      first_err = fail(NT_EHIP, "device-to-host copy failed");
-      break;
-    }
-    st.i0 = i0; st.i1 = i1; st.T = T; st.busy = true;
+    int32_t B = 0, T = 0;
+    if ((first_err = pl.start(ln, st, k, &B, &T))) break;
+    double row_steps = 0.0;
+    for (int32_t r = 0; r < B; r++) row_steps += st.steps[(size_t)r];
+    lane_cost[li] += 130.0 * T + 0.08 * row_steps + 0.06 * (double)B * plan.lens[(size_t)plan.order[(size_t)st.i0]];
+    if ((first_err = nt_decode_greedy(ln, B, T, st.steps.data(), ln->d_out, ln->lane_stream))) break;
+    first_err = pl.finish(ln, st);
   }
-  // drain every lane (also after an error: nothing may still be running when the call returns); a lane's batches
-  // finish in the order they were queued
-  for (nt_model *ln : lane) {
-    int older = 0;
-    if (ln->stage[0].busy && ln->stage[1].busy && ln->stage[1].i0 < ln->stage[0].i0) older = 1;
-    for (int j = 0; j < nt_model::kStagings; j++)
-      if (first_err == NT_OK) first_err = collect(ln->stage[(older + j) % nt_model::kStagings]);
-    (void)hipStreamSynchronize(ln->lane_stream);
-    for (auto &st : ln->stage) st.busy = false;
-  }
-  if (first_err) return first_err;
-  return NT_OK;
+  return pl.drain(first_err);
 } catch (const std::bad_alloc &) {
   return fail(NT_ENOMEM, "host allocation failed");
 } catch (...) {
@@ -1347,12 +1380,9 @@ int nt_translate_batch_eos(nt_model *m, const int32_t *h_tokens, const int64_t *
   if (eos_id < 0 || eos_id >= m->c.vocab) return fail(NT_ERANGE, "eos_id %d outside the vocabulary", eos_id);
   if (N > 0 && !h_out_len) return fail(NT_EINVAL, "h_out_len is null");
   if (N == 0) return NT_OK;
-  const nt_config &c = m->c;
-  const std::vector<int32_t> &lens = plan.lens;
-  const std::vector<int64_t> &order = plan.order, &starts = plan.starts;
-  const int64_t nb = plan.nb;
   for (int64_t i = 0; i < N; i++) h_out_len[i] = 0;
-  hipStream_t s = as_stream(hip_stream);
+  Pipeline pl{m, plan, h_tokens, h_offsets, h_out, h_out_offsets, h_out_len, {}};
+  if ((rc = pl.begin(as_stream(hip_stream)))) return rc;
   // One batch per lane at a time; the lanes take turns, each enqueuing the steps its device side allows (a few
   // ahead of what it has published), so that every lane's launches are sized by a recent count of live rows.
   struct LaneRun {
@@ -1362,73 +1392,19 @@ int nt_translate_batch_eos(nt_model *m, const int32_t *h_tokens, const int64_t *
     nt_model::Staging *st = nullptr;
     DecodeCursor cu;
   };
-  std::vector<LaneRun> runs(1 + m->lanes.size());
-  runs[0].ln = m;
-  for (size_t i = 0; i < m->lanes.size(); i++) runs[i + 1].ln = m->lanes[i];
-  HIP_TRY(hipEventRecord(m->lane_start, s));  // work already queued on the caller's stream comes first
-  for (LaneRun &L : runs) {
-    HIP_TRY(hipStreamWaitEvent(L.ln->lane_stream, m->lane_start, 0));
-    for (auto &st : L.ln->stage) st.busy = false;
-    L.ln->timing.mask = m->timing.mask;
-  }
-  auto collect = [&](nt_model::Staging &st) -> int {  // wait for the batch of this staging set and scatter its rows
-    if (!st.busy) return NT_OK;
-    HIP_TRY(hipEventSynchronize(st.done));
-    for (int64_t r = 0; r < st.i1 - st.i0; r++) {
-      const int64_t si = order[(size_t)(st.i0 + r)];
-      memcpy(h_out + h_out_offsets[si], st.h_out + (size_t)r * st.T, (size_t)st.steps[(size_t)r] * 4);
-      h_out_len[si] = st.h_out_len[r];
-    }
-    st.busy = false;
-    return NT_OK;
-  };
+  std::vector<LaneRun> runs(pl.lane.size());
+  for (size_t i = 0; i < runs.size(); i++) runs[i].ln = pl.lane[i];
   auto start_batch = [&](LaneRun &L, int64_t k) -> int {
     nt_model *ln = L.ln;
     nt_model::Staging &st = ln->stage[L.started % nt_model::kStagings];
-    int e = collect(st);
-    if (e) return e;
-    const int64_t i0 = starts[(size_t)k], i1 = starts[(size_t)k + 1];
-    const int32_t B = (int32_t)(i1 - i0), S = lens[(size_t)order[(size_t)i0]], T = nt_n_steps(S);
-    if ((int64_t)B * T > ln->self_positions) return fail(NT_ENOMEM, "batch of %d rows x %d steps exceeds the self-attention cache", B, T);
-    st.steps.resize((size_t)B);
-    for (int32_t r = 0; r < B; r++) {
-      const int64_t si = order[(size_t)(i0 + r)];
-      const int32_t Ls = lens[(size_t)si];
-      st.h_len[r] = Ls;
-      st.steps[(size_t)r] = st.h_cap[r] = nt_n_steps(Ls);
-      int32_t *row = st.h_src + (size_t)r * S;
-      memcpy(row, h_tokens + h_offsets[si], (size_t)Ls * 4);
-      for (int32_t j = Ls; j < S; j++) row[j] = c.pad_id;
-    }
-    hipStream_t ls = ln->lane_stream;
-    if (hipMemcpyAsync(ln->d_src, st.h_src, (size_t)B * S * 4, hipMemcpyHostToDevice, ls) != hipSuccess ||
-        hipMemcpyAsync(ln->d_len_in, st.h_len, (size_t)B * 4, hipMemcpyHostToDevice, ls) != hipSuccess ||
-        hipMemcpyAsync(ln->d_cap, st.h_cap, (size_t)B * 4, hipMemcpyHostToDevice, ls) != hipSuccess)
-      return fail(NT_EHIP, "host-to-device copy failed");
-    if ((e = nt_encode(ln, ln->d_src, ln->d_len_in, B, S, ls))) return e;
-    if (ln->timing.mask) {
-      ln->len_prefix.assign((size_t)B + 1, 0);
-      for (int32_t r = 0; r < B; r++) ln->len_prefix[(size_t)r + 1] = ln->len_prefix[(size_t)r] + st.h_len[r];
-    }
-    if ((e = check_decode_args(ln, B, T))) return e;
-    HIP_TRY(nt::launch_fill_i32(ln->d_out, (long)B * T, c.pad_id, ls));
+    int32_t B = 0, T = 0;
+    int e = pl.start(ln, st, k, &B, &T);
+    if (e || (e = check_decode_args(ln, B, T))) return e;
+    HIP_TRY(nt::launch_fill_i32(ln->d_out, (long)B * T, m->c.pad_id, ln->lane_stream));
     begin_eos_decode(ln, L.cu, B, T, st.steps.data(), eos_id, ln->d_out, ln->d_out_len);
-    st.i0 = i0; st.i1 = i1; st.T = T;
     L.st = &st;
     L.started++;
     L.active = true;
-    return NT_OK;
-  };
-  auto finish_batch = [&](LaneRun &L) -> int {
-    nt_model *ln = L.ln;
-    nt_model::Staging &st = *L.st;
-    const int64_t B = st.i1 - st.i0;
-    if (hipMemcpyAsync(st.h_out, ln->d_out, (size_t)B * st.T * 4, hipMemcpyDeviceToHost, ln->lane_stream) != hipSuccess ||
-        hipMemcpyAsync(st.h_out_len, ln->d_out_len, (size_t)B * 4, hipMemcpyDeviceToHost, ln->lane_stream) != hipSuccess ||
-        hipEventRecord(st.done, ln->lane_stream) != hipSuccess)
-      return fail(NT_EHIP, "device-to-host copy failed");
-    st.busy = true;
-    L.active = false;
     return NT_OK;
   };
   int first_err = NT_OK;
@@ -1438,7 +1414,7 @@ int nt_translate_batch_eos(nt_model *m, const int32_t *h_tokens, const int64_t *
     bool any_active = false, progressed = false;
     for (LaneRun &L : runs) {
       if (first_err) break;
-      if (!L.active && next < nb) {
+      if (!L.active && next < plan.nb) {
         if ((first_err = start_batch(L, next))) break;
         next++;
         progressed = true;
@@ -1454,11 +1430,12 @@ int nt_translate_batch_eos(nt_model *m, const int32_t *h_tokens, const int64_t *
       }
       if (first_err) break;
       if (L.cu.finished || eos_all_ended(L.cu)) {
-        if ((first_err = finish_batch(L))) break;
+        if ((first_err = pl.finish(L.ln, *L.st))) break;
+        L.active = false;
         progressed = true;
       }
     }
-    if (first_err || (!any_active && next >= nb)) break;
+    if (first_err || (!any_active && next >= plan.nb)) break;
     if (progressed) {
       last_progress = std::chrono::steady_clock::now();
     } else {
@@ -1469,17 +1446,7 @@ int nt_translate_batch_eos(nt_model *m, const int32_t *h_tokens, const int64_t *
       std::this_thread::yield();
     }
   }
-  // drain every lane (also after an error: nothing may still be running when the call returns)
-  for (LaneRun &L : runs) {
-    nt_model *ln = L.ln;
-    int older = 0;
-    if (ln->stage[0].busy && ln->stage[1].busy && ln->stage[1].i0 < ln->stage[0].i0) older = 1;
-    for (int j = 0; j < nt_model::kStagings; j++)
-      if (first_err == NT_OK) first_err = collect(ln->stage[(older + j) % nt_model::kStagings]);
-    (void)hipStreamSynchronize(ln->lane_stream);
-    for (auto &st : ln->stage) st.busy = false;
-  }
-  return first_err;
+  return pl.drain(first_err);
 } catch (const std::bad_alloc &) {
   return fail(NT_ENOMEM, "host allocation failed");
 } catch (...) {
