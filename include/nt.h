@@ -13,11 +13,13 @@
  *     every buffer it passes.  The library owns the weights, the activation arena and the
  *     key/value caches; it allocates only inside nt_load_weights and frees only in nt_free.
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).  nt_encode
- *     and nt_decode_greedy only enqueue work; nt_translate_batch synchronises the stream
- *     before it returns host results.
+ *     and nt_decode_greedy only enqueue work; nt_decode_greedy_eos enqueues a few steps ahead
+ *     of the device and returns when the device is that close to the end; the two
+ *     nt_translate_batch calls synchronise before they return host results.
  *   - one nt_model must not be used from two threads at once; nt_plan_batches is pure.
- *   - ids: 0 = PAD, 1 = BOS, 2 = EOS, 3 = UNK by convention; only bos_id and pad_id are
- *     used by the library.  The decoder may emit any id in [0, vocab).
+ *   - ids: 0 = PAD, 1 = BOS, 2 = EOS, 3 = UNK by convention; the library uses bos_id and
+ *     pad_id of the configuration and the eos_id argument of the EOS-terminated calls.  The
+ *     decoder may emit any id in [0, vocab).
  */
 #ifndef NT_H
 #define NT_H
