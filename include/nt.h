@@ -165,6 +165,13 @@ int nt_debug_q8_output_layer(nt_model *m, const float *d_h, int32_t R, int32_t *
                              void *hip_stream);
 
 /*
+ * The weight side of the 8-bit output layer for one vocabulary entry, as nt_load_weights applies it to every row
+ * of the output matrix (Eq. 3, 4): h_w_fp16 [K] fp16 host -> h_codes [K] signed 8-bit, *h_scale, *h_zero.  Runs on
+ * the host; needs no model and no GPU.
+ */
+int nt_debug_q8_quantize_row(const void *h_w_fp16, int32_t K, int8_t *h_codes, float *h_scale, int32_t *h_zero);
+
+/*
  * Greedy decoding that ends a sentence at its end symbol (Sec. 3.3 "Greedy Search": the paper's
  * systems decode with beam size 1 until EOS, where the benchmark's rule above runs a fixed number
  * of steps).  Row b ends with the first eos_id it emits, which is stored, or after

@@ -18,7 +18,7 @@ EXPORTS = ["nt_param_count", "nt_n_steps", "nt_load_weights", "nt_free", "nt_enc
            "nt_check_device_flags", "nt_device_bytes", "nt_last_error", "nt_debug_timing_enable",
            "nt_debug_timing_count", "nt_debug_timing_name", "nt_debug_timing_read", "nt_pipeline_lanes",
            "nt_pipeline_lane", "nt_lane_stream", "nt_decode_greedy_eos", "nt_translate_batch_eos",
-           "nt_debug_q8_output_layer"]
+           "nt_debug_q8_output_layer", "nt_debug_q8_quantize_row"]
 
 
 class NtConfig(C.Structure):
@@ -61,6 +61,7 @@ def load_library() -> C.CDLL:
         "nt_translate_batch": (C.c_int, [p, p, p, i64, i64, i32, p, p, p]),
         "nt_decode_greedy_eos": (C.c_int, [p, i32, i32, p, i32, p, p, p]),
         "nt_debug_q8_output_layer": (C.c_int, [p, p, i32, p, p, p]),
+        "nt_debug_q8_quantize_row": (C.c_int, [p, i32, p, p, p]),
         "nt_translate_batch_eos": (C.c_int, [p, p, p, i64, i64, i32, i32, p, p, p, p]),
         "nt_plan_batches": (C.c_int, [p, i64, i64, i32, p, p, C.POINTER(i64)]),
         "nt_debug_encoder_out": (C.c_int, [p, p, p]),
@@ -108,6 +109,16 @@ def make_config(cfg: dict, max_batch_tokens: int, max_batch_rows: int = 0, pipel
     c.ln_l1 = int(cfg.get("ln_l1", 0))
     c.q8_output = int(cfg.get("q8_output", 0))
     return c
+
+
+def q8_quantize_row(w):
+    """Weight side of the 8-bit output layer for one fp16 row (host only): (codes int8, scale float32, zero int)."""
+    w = np.ascontiguousarray(w, dtype=np.float16)
+    q = np.empty(w.size, dtype=np.int8)
+    sc, z = C.c_float(), C.c_int32()
+    _check(lib().nt_debug_q8_quantize_row(w.ctypes.data_as(C.c_void_p), w.size, q.ctypes.data_as(C.c_void_p),
+                                          C.byref(sc), C.byref(z)))
+    return q, np.float32(sc.value), int(z.value)
 
 
 def param_count(cfg: dict) -> int:

@@ -1058,6 +1058,12 @@ int nt_debug_teacher_forced_logits(nt_model *m, const int32_t *d_tgt_in, int32_t
   return run_decoder(m, B, T, nullptr, d_tgt_in, nullptr, d_logits, as_stream(hip_stream));
 }
 
+int nt_debug_q8_quantize_row(const void *h_w_fp16, int32_t K, int8_t *h_codes, float *h_scale, int32_t *h_zero) {
+  if (!h_w_fp16 || !h_codes || !h_scale || !h_zero || K < 1) return fail(NT_EINVAL, "null argument or K < 1");
+  nt::vocab_q8_quantize_row((const _Float16 *)h_w_fp16, K, h_codes, h_scale, h_zero);
+  return NT_OK;
+}
+
 int nt_debug_q8_output_layer(nt_model *m, const float *d_h, int32_t R, int32_t *d_argmax, float *d_logits,
                              void *hip_stream) {
   if (!m || !d_h) return fail(NT_EINVAL, "null argument");

@@ -148,6 +148,8 @@ size_t vocab_q8_const_bytes(int N);
 // Host: quantise Wt [N][K] per vocabulary entry and lay the codes out in MFMA fragment order, the per-entry
 // constants (scale, zero point, sum of codes - K * zero point) in accumulator order.
 void vocab_q8_pack(const _Float16 *Wt, int N, int K, int8_t *codes, void *consts);
+// Host: Eq. 3, 4 for one vocabulary entry (what vocab_q8_pack applies to every row)
+void vocab_q8_quantize_row(const _Float16 *w, int K, int8_t *q, float *scale, int32_t *zero);
 // x [M][d] fp32 -> [LayerNorm if gamma != nullptr ->] unsigned 8-bit codes per row, stored as signed bytes
 // (code - 128) in codes [M][d]; a_scale [M]; c [M] = 128 - zero point; sa [M] = sum of the signed bytes.  d = 256 / 512.
 hipError_t launch_q8_rows(const float *x, int M, int d, const float *gamma, const float *beta, LnEps eps, int8_t *codes,

@@ -75,6 +75,8 @@ static void q8_weight_row(const _Float16 *w, int K, int8_t *q, float *scale_out,
   *zero_out = (int32_t)zero;
 }
 
+void vocab_q8_quantize_row(const _Float16 *w, int K, int8_t *q, float *scale, int32_t *zero) { q8_weight_row(w, K, q, scale, zero); }
+
 // Wt: [N][K] fp16 (K contiguous).  codes: vocab_q8_pack_bytes(N, K); consts: vocab_q8_const_bytes(N).
 // Entries beyond N get zero codes and zero constants (their logits are masked in the kernel).
 void vocab_q8_pack(const _Float16 *Wt, int N, int K, int8_t *codes, void *consts) {

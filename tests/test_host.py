@@ -111,6 +111,21 @@ def test_load_rejects_bad_config_and_blob_before_touching_the_gpu():
     assert nt.param_count(dict(cfg, d_model=100)) == 0
 
 
+def test_q8_weight_quantiser_of_the_library_equals_the_oracles(oracle):
+    """Eq. 3, 4 on the host side of the library (what nt_load_weights applies to the output matrix) against the
+    oracle's, bit for bit: codes, scale and zero point, on random rows, shifted rows, flat rows and rows whose
+    zero point saturates."""
+    rng = np.random.default_rng(12)
+    rows = [rng.normal(0, 512 ** -0.5, 512), rng.normal(0.3, 0.05, 512), rng.normal(-2.0, 0.01, 256),
+            np.full(256, 0.125), np.zeros(512), rng.standard_cauchy(512) * 0.01, rng.normal(0, 1e-4, 512)]
+    rows += [rng.normal(rng.normal(0, 0.05), abs(rng.normal(0.05, 0.02)) + 1e-4, 512) for _ in range(40)]
+    for w in rows:
+        w = np.asarray(w, dtype=np.float64).astype(np.float16)
+        q, sc, z = nt.q8_quantize_row(w)
+        oq, osc, oz = oracle.q8_weight_row(w.astype(np.float32))
+        assert np.array_equal(q, oq) and sc == osc and z == oz
+
+
 def test_workload_recipe_statistics():
     """The synthetic stand-in has the length and token structure the benchmark describes."""
     tokens, offsets = nt_synth.workload("C1")
