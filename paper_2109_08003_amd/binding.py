@@ -130,6 +130,18 @@ def n_steps(length: int) -> int:
     return int(lib().nt_n_steps(int(length)))
 
 
+def _output_slots(offsets) -> int:
+    """Size of the output buffer of the translate calls: nt_n_steps(len) slots per non-empty sentence.  The rule
+    (6 len + 4) div 5 + 2 is nt_n_steps's, applied to the whole array at once (a call per sentence costs more than
+    the translation of a large input set)."""
+    lens = np.diff(offsets)
+    lens = lens[lens > 0]
+    total = int(((6 * lens + 4) // 5 + 2).sum())
+    if lens.size:  # the library's own value, on the longest sentence, guards the vectorised copy of the rule
+        assert (6 * int(lens.max()) + 4) // 5 + 2 == n_steps(int(lens.max()))
+    return total
+
+
 def plan_batches(lengths, budget: int, max_rows: int = 0):
     """Returns (order int64 [N], batch_starts int64 [n_batches+1])."""
     lengths = np.ascontiguousarray(lengths, dtype=np.int32)
@@ -275,7 +287,7 @@ class Model:
         tokens = np.ascontiguousarray(tokens, dtype=np.int32)
         offsets = np.ascontiguousarray(offsets, dtype=np.int64)
         N = offsets.size - 1
-        total = sum(n_steps(int(l)) for l in np.diff(offsets) if l > 0) if N > 0 else 0
+        total = _output_slots(offsets) if N > 0 else 0
         out = np.empty(max(total, 1), dtype=np.int32)
         oo = np.empty(N + 1, dtype=np.int64)
         _check(lib().nt_translate_batch(self._h, tokens.ctypes.data_as(C.c_void_p), offsets.ctypes.data_as(C.c_void_p),
@@ -289,7 +301,7 @@ class Model:
         tokens = np.ascontiguousarray(tokens, dtype=np.int32)
         offsets = np.ascontiguousarray(offsets, dtype=np.int64)
         N = offsets.size - 1
-        total = sum(n_steps(int(l)) for l in np.diff(offsets) if l > 0) if N > 0 else 0
+        total = _output_slots(offsets) if N > 0 else 0
         out = np.empty(max(total, 1), dtype=np.int32)
         oo = np.empty(N + 1, dtype=np.int64)
         ol = np.zeros(max(N, 1), dtype=np.int32)
