@@ -841,14 +841,17 @@ int decode_step(nt_model *m, DecodeCursor &cu, hipStream_t s) {
     // Above the row count of the one-round-trip kernel the projections take the streaming kernel, which reads its
     // A operand as a head/tail pair of fp16 planes: the LayerNorm and the attention kernels then write planes.
     const long lo_rows = (long)m->max_rows;
+    // Which of the two kernels a projection takes must not depend on what the host happened to read of the device's
+    // progress (they round differently in the last bit): the EOS mode chooses by the row count the caps alone allow.
+    const int rows_for_choice = eos ? rows_at(cu, t) : R;
     auto streams = [&](int N, int K, const _Float16 *Wp, bool with_ln) -> bool {
-      if (R <= kSkinnyMaxRows && nt::skinny_gemm_supported(K, with_ln)) return false;
+      if (rows_for_choice <= kSkinnyMaxRows && nt::skinny_gemm_supported(K, with_ln)) return false;
       return Wp != nullptr && nt::gemm_stream_supported(N, K);
     };
     auto dec_gemm = [&](int id, const float *A, int K, const _Float16 *Wt, const _Float16 *Wp, int N, const LN *ln,
                         const nt::GemmEpilogue &e, bool c_f32 = true) -> int {
       const double by = gemm_bytes(Rd, K, N, e.resid != nullptr), fl = 2 * Rd * K * (double)N;
-      if (R <= kSkinnyMaxRows && nt::skinny_gemm_supported(K, ln != nullptr)) {
+      if (rows_for_choice <= kSkinnyMaxRows && nt::skinny_gemm_supported(K, ln != nullptr)) {
         KT(id, by, fl, nt::launch_skinny_gemm(A, K, Wt, R, N, K, ln ? ln->g : nullptr, ln ? ln->b : nullptr, lne, e, s));
         return NT_OK;
       }
