@@ -62,6 +62,7 @@ def main():
     ap.add_argument("--sentences", type=int, default=None, help="default: the workload's own count")
     ap.add_argument("--budget", type=int, default=65536,
                     help="token budget per batch (best of the 4k/16k/64k sweep of the throughput configuration)")
+    ap.add_argument("--max-rows", type=int, default=0, help="cap on the sentences per batch (the paper's sbatch), 0 = none")
     ap.add_argument("--lanes", type=int, default=0, help="batches in flight (0 = the library's default)")
     ap.add_argument("--cpu-sentences", type=int, default=1024, help="oracle sample size (0 = skip)")
     ap.add_argument("--batch-stride", type=int, default=1,
@@ -98,7 +99,7 @@ def main():
     streams = [ln.own_stream() for ln in lanes]
 
     # ---- batches resident in HBM (untimed set-up) ----
-    order, starts = nt.plan_batches(lens, args.budget)
+    order, starts = nt.plan_batches(lens, args.budget, args.max_rows)
     batches = []
     for k in range(len(starts) - 1):
         idx = order[starts[k]:starts[k + 1]]
@@ -149,10 +150,10 @@ def main():
         return
 
     # ---- same work through the host-facing entry point (PCIe and batching included) ----
-    out, oo = model.translate_batch(tokens, offsets, args.budget)
+    out, oo = model.translate_batch(tokens, offsets, args.budget, max_rows=args.max_rows)
     t0 = time.perf_counter()
     for _ in range(max(1, min(args.steps, 3))):
-        out, oo = model.translate_batch(tokens, offsets, args.budget)
+        out, oo = model.translate_batch(tokens, offsets, args.budget, max_rows=args.max_rows)
     dt_host = (time.perf_counter() - t0) / max(1, min(args.steps, 3))
     # the two routes must produce the same translations
     for b in batches:

@@ -157,6 +157,25 @@ def test_c0_translate_batch_order_and_determinism(c0, oracle, nt):
     assert bad <= 1
 
 
+def test_papers_batch_caps_give_the_same_translations(nt):
+    """sbatch / wbatch = 3,072 / 64,000 (Sec. 3.3 "Better Decoding Configurations"): a cap on the sentences per
+    batch changes the batches, not the translations (a sentence never depends on its batch mates, up to the
+    kernel a batch size selects: compare as sets of near-identical outputs)."""
+    cfg = nt_synth.model_config("C1")
+    blob = nt_synth.make_weights(cfg, seed=0)
+    tokens, offsets = nt_synth.workload("C2", 20000)
+    lens = np.diff(offsets)
+    gm = nt.Model(cfg, blob, max_batch_tokens=65536)
+    order, starts = nt.plan_batches(lens, 64000, 3072)
+    assert np.diff(starts).max() <= 3072 and (np.diff(starts) * lens[order[starts[:-1]]]).max() <= 64000
+    assert np.diff(starts).max() == 3072                                   # the cap binds for the short sentences
+    capped, co = gm.translate_batch(tokens, offsets, token_budget=64000, max_rows=3072)
+    free, fo = gm.translate_batch(tokens, offsets, token_budget=64000)
+    assert np.array_equal(co, fo)
+    same = sum(np.array_equal(capped[co[i]:co[i + 1]], free[fo[i]:fo[i + 1]]) for i in range(len(lens)))
+    assert same >= 0.999 * len(lens), same
+
+
 def test_lanes_driven_by_the_caller_on_their_own_streams(torch_cuda, nt):
     """Batches kept on the device and run through nt_encode / nt_decode_greedy on the lanes' own streams
     (nt_lane_stream), several in flight at once, give the tokens of nt_translate_batch."""
