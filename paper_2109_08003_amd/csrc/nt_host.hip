@@ -1,6 +1,7 @@
-// Host side of libnt: C ABI entry points, weight re-layout, arena planning, the token-budget
-// batcher and the step scheduler that enqueues the gfx950 kernels.  No CPU fallback exists:
-// every numerical step of the path is a kernel in nt_gemm.hip / nt_rows.hip / nt_attn.hip.
+// Host side of libnt: C ABI entry points, weight re-layout (and, for the 8-bit output layer, quantisation), arena
+// planning, the token-budget batcher, the step scheduler that enqueues the gfx950 kernels (fixed-length and
+// EOS-terminated) and the pipeline lanes.  No CPU fallback exists: every numerical step of the path is a kernel in
+// nt_gemm.hip / nt_gemm_stream.hip / nt_vocab.hip / nt_vocab_q8.hip / nt_rows.hip / nt_attn.hip.
 #include <algorithm>
 #include <chrono>
 #include <cmath>
