@@ -27,8 +27,6 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int GS_WAVES = 8;
-
 bool gemm_stream_supported(int N, int K) { return (K == 256 || K == 512) && N % 64 == 0; }
 
 __device__ __forceinline__ float gs_wave_sum(float v) {
@@ -41,7 +39,7 @@ __device__ __forceinline__ float gs_wave_sum(float v) {
 // LN = true: A_hi points to fp32 rows X[M][lda] instead; the tile is LayerNorm-ed (fp32 statistics: mean first, then
 // the biased variance of the centred values) and split into head/tail planes while it is written to the LDS, which
 // saves the separate LayerNorm kernel and the round trip of its output through memory.
-template <int RB, int K, bool C_F32, bool LN>
+template <int RB, int K, bool C_F32, bool LN, int GS_WAVES>
 __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float16 *__restrict__ A_hi,
                                                                    const _Float16 *__restrict__ A_lo, long lda, int M,
                                                                    const _Float16 *__restrict__ Wp, int N, int col_groups,
@@ -53,7 +51,8 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   constexpr int KS = K / 16;
   // register slots of W fragments per wave; the lookahead is SL - 1 k-steps.  (A deeper ring did not shorten the
   // decoder-sized launches, and fewer registers leave room for other kernels' waves on the same CU.)
-  constexpr int SL = 8;
+  // With three waves per SIMD the register budget is 168, and the other waves cover a shorter lookahead.
+  constexpr int SL = GS_WAVES > 8 ? 4 : 8;
   constexpr int NOPS = 2 * RB;
   static_assert(KS % SL == 0, "the ring of W slots must divide the k-steps of a strip");
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, g = lane >> 5;
@@ -71,14 +70,14 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   };
 
   // ---- the A tile: global memory -> LDS.  Rows past M repeat row M - 1 (their results are never stored) ----
-  if (LN) {
+  if constexpr (LN) {
     // a wave takes rows wave, wave + 8, ...; a lane holds NE consecutive elements of the row
-    constexpr int NE = K / 64, RPW = TM / GS_WAVES;
+    constexpr int NE = K / 64, RPW = (TM + GS_WAVES - 1) / GS_WAVES;
     const float *X = (const float *)A_hi;
     float xv[RPW][NE];
 #pragma unroll
     for (int i = 0; i < RPW; i++) {
-      int m = m0 + wave + GS_WAVES * i;
+      int m = m0 + wave + GS_WAVES * i;  // (rows past the tile, when the waves do not divide it, are not written)
       m = m < M ? m : M - 1;
       const float *xr = X + (long)m * lda + lane * NE;
 #pragma unroll
@@ -112,13 +111,15 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
         lo[j] = (_Float16)(y - (float)hi[j]);
       }
       const int R = wave + GS_WAVES * i;
+      if (TM % GS_WAVES != 0 && R >= TM) continue;
       *(halfNE *)(sh + R * LD + lane * NE) = hi;
       *(halfNE *)(sh + (R + TM) * LD + lane * NE) = lo;
     }
   } else if (K == 512) {
 #pragma unroll
-    for (int i = 0; i < ROWS / GS_WAVES; i++) {
+    for (int i = 0; i < (ROWS + GS_WAVES - 1) / GS_WAVES; i++) {
       const int R = wave + GS_WAVES * i;
+      if (ROWS % GS_WAVES != 0 && R >= ROWS) continue;
       const _Float16 *src = R >= TM ? A_lo : A_hi;
       int m = m0 + (R % TM);
       m = m < M ? m : M - 1;
@@ -126,11 +127,13 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
                                        (__attribute__((address_space(3))) void *)(sh + R * LD), 16, 0, 0);
     }
   } else {
-    constexpr int CPR = K / 8, PER_T = ROWS * CPR / (GS_WAVES * 64);
+    constexpr int CPR = K / 8, PER_T = (ROWS * CPR + GS_WAVES * 64 - 1) / (GS_WAVES * 64);
     u32x4 fr[PER_T];
 #pragma unroll
     for (int i = 0; i < PER_T; i++) {
-      const int c = tid + GS_WAVES * 64 * i, R = c / CPR, kc = c % CPR;
+      int c = tid + GS_WAVES * 64 * i;
+      c = c < ROWS * CPR ? c : ROWS * CPR - 1;
+      const int R = c / CPR, kc = c % CPR;
       const _Float16 *src = R >= TM ? A_lo : A_hi;
       int m = m0 + (R % TM);
       m = m < M ? m : M - 1;
@@ -139,7 +142,7 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
 #pragma unroll
     for (int i = 0; i < PER_T; i++) {
       const int c = tid + GS_WAVES * 64 * i, R = c / CPR, kc = c % CPR;
-      *(u32x4 *)(sh + R * LD + kc * 8) = fr[i];
+      if (c < ROWS * CPR) *(u32x4 *)(sh + R * LD + kc * 8) = fr[i];
     }
   }
   half8 wb[SL][2];
@@ -159,7 +162,8 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   // Two waves share a SIMD.  With equal priority they take turns at the matrix pipe, finish their strips together
   // and then both sit in the store phase of the epilogue (the long one when the output is fp32) while the pipe
   // idles.  Giving one of them priority makes the phases alternate instead.
-  if (wave < GS_WAVES / 2) __builtin_amdgcn_s_setprio(2);
+  if (wave < 4) __builtin_amdgcn_s_setprio(2);
+  else if (GS_WAVES > 8 && wave < 8) __builtin_amdgcn_s_setprio(1);
 
   floatx16 acc[RB][2];
   // fragment row of operand op: head rows of block op % RB, then the tail rows; two base registers, because the
@@ -180,6 +184,15 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
     const bool more = strip + GS_WAVES < sb1;
     const int pcur = strip * (KS * 2048);
     const int pnext = (more ? strip + GS_WAVES : strip) * (KS * 2048);
+    // bias and scale of the strip's columns, requested here so that the epilogue does not wait for them behind the
+    // weight fragments in flight
+    float bias[2] = {0.f, 0.f}, scl[2];
+#pragma unroll
+    for (int nb = 0; nb < 2; nb++) {
+      const int n = strip * 64 + nb * 32 + li;
+      if (e.bias) bias[nb] = e.bias[n];
+      scl[nb] = (n < e.scale_cols) ? e.scale : 1.f;
+    }
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
       const int tgt = ks + SL - 1;
@@ -204,30 +217,90 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
         }
         __builtin_amdgcn_sched_barrier(0);
       }
+      // the wait for bias and scale is taken here, where it counts only the fragments requested since; left to the
+      // epilogue it becomes a wait for everything in flight
+      if (ks == SL) asm volatile("" ::"v"(bias[0]), "v"(bias[1]), "v"(scl[0]), "v"(scl[1]));
     }
     // ---- epilogue of the strip: acc[rb][nb][v] is C[m0 + rb*32 + (v/4)*8 + g*4 + v%4][strip*64 + nb*32 + li] ----
     // Addresses are a uniform 64-bit base per 32 x 32 block plus a 32-bit lane offset (n_split is a multiple of 32,
     // so a block never straddles the two destinations).
-#pragma unroll
-    for (int nb = 0; nb < 2; nb++) {
+    //
+    // The stores of a strip must go out back to back.  Loads and stores of a wave complete in order on one counter;
+    // with a per-row guard around every store the compiler can no longer count what is outstanding and waits for
+    // the counter to reach zero before each store, i.e. for the acknowledgement of the previous one (150 ns each,
+    // 10 us per strip).  So the guards are hoisted: a tile that lies within M (all but the last) and the
+    // presence of a residual are decided once, uniformly, and the path taken is straight-line code.  The residual
+    // may be the destination itself (in-place update); a block's residual values are requested before the
+    // stores of the block before it, so that waiting for them does not wait for those stores.
+    constexpr int CE = C_F32 ? 4 : 2;
+    constexpr int NBLK = 2 * RB;  // 32 x 32 blocks of the strip: block = nb * RB + rb
+    auto block_at = [&](int blk, char *&dblock, const char *&rblock, unsigned &dlane, unsigned &rlane, long &ld,
+                        int &mb) {
+      const int nb = blk / RB, rb = blk % RB;
       const int nbase = strip * 64 + nb * 32;  // uniform
-      const int n = nbase + li;
-      const float bias = e.bias ? e.bias[n] : 0.f;
-      const float sc = (n < e.scale_cols) ? e.scale : 1.f;
       const bool first = nbase < e.n_split;
       char *dst = (char *)(first ? e.dst0 : e.dst1);
-      const long ld = first ? e.ld0 : e.ld1;
+      ld = first ? e.ld0 : e.ld1;
       const int ncb = first ? nbase : nbase - e.n_split;
-      constexpr int CE = C_F32 ? 4 : 2;
+      mb = m0 + rb * 32;  // uniform
+      dblock = dst + ((long)mb * ld + ncb) * CE;
+      rblock = (const char *)e.resid + ((long)mb * e.ldr + nbase) * 4;
+      dlane = (unsigned)((g * 4 * ld + li) * CE);
+      rlane = (unsigned)((g * 4 * e.ldr + li) * 4);
+      // the per-row offsets derived from these do not depend on the strip; computed once and kept, they would hold
+      // dozens of registers through the main loop
+      asm volatile("" : "+v"(dlane), "+v"(rlane));
+    };
+    auto finish = [&](int blk, int v, float r) -> float {
+      float val = (acc[blk % RB][blk / RB][v] + bias[blk / RB]) * scl[blk / RB];
+      if (e.relu) val = fmaxf(val, 0.f);
+      return val + r;
+    };
+    auto put = [&](char *at_, float val) {
+      if (C_F32) {
+        *(float *)at_ = val;
+      } else {
+        const _Float16 hi = (_Float16)val;
+        *(_Float16 *)at_ = hi;
+        if (e.dst_lo_offset) *((_Float16 *)at_ + e.dst_lo_offset) = (_Float16)(val - (float)hi);
+      }
+    };
+    // The projections that follow a LayerNorm add no residual, and the others all do: the straight-line path is
+    // compiled for that case only; anything else takes the guarded path below.
+    constexpr bool RESID = !LN;
+    if (__builtin_expect(m0 + TM <= M && RESID == (e.resid != nullptr), 1)) {
+      float res[RESID ? 2 : 1][16];
+      auto request = [&](int blk) {
+        char *dblock; const char *rblock; unsigned dlane, rlane; long ld; int mb;
+        block_at(blk, dblock, rblock, dlane, rlane, ld, mb);
 #pragma unroll
-      for (int rb = 0; rb < RB; rb++) {
-        __builtin_amdgcn_sched_barrier(0);  // one 32 x 32 block at a time: bounds the loads and addresses in flight
-        const int mb = m0 + rb * 32;  // uniform
-        char *dblock = dst + ((long)mb * ld + ncb) * CE;
-        const char *rblock = (const char *)e.resid + ((long)mb * e.ldr + nbase) * 4;
-        const unsigned dlane = (unsigned)((g * 4 * ld + li) * CE), rlane = (unsigned)((g * 4 * e.ldr + li) * 4);
-        // the residual may be the destination itself (in-place update), so the compiler keeps loads and stores in
-        // program order: read the 16 residual values of the block first, then compute and store
+        for (int v = 0; v < 16; v++) {
+          const int r = (v >> 2) * 8 + (v & 3);
+          res[blk & 1][v] = *(const float *)(rblock + (rlane + (unsigned)(r * e.ldr * 4)));
+        }
+      };
+      if (RESID) request(0);
+#pragma unroll
+      for (int blk = 0; blk < NBLK; blk++) {
+        __builtin_amdgcn_sched_barrier(0);  // one block at a time: bounds the loads and addresses in flight
+        if (RESID && blk + 1 < NBLK) request(blk + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        char *dblock; const char *rblock; unsigned dlane, rlane; long ld; int mb;
+        block_at(blk, dblock, rblock, dlane, rlane, ld, mb);
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          const int r = (v >> 2) * 8 + (v & 3);
+          put(dblock + (dlane + (unsigned)(r * ld * CE)), finish(blk, v, RESID ? res[blk & 1][v] : 0.f));
+        }
+      }
+    } else {
+      // the last row tile (or the unusual residual case): every row is checked against M
+#pragma unroll
+      for (int blk = 0; blk < NBLK; blk++) {
+        __builtin_amdgcn_sched_barrier(0);
+        char *dblock; const char *rblock; unsigned dlane, rlane; long ld; int mb;
+        block_at(blk, dblock, rblock, dlane, rlane, ld, mb);
+        // read the 16 residual values of the block first, then compute and store
         float res[16];
 #pragma unroll
         for (int v = 0; v < 16; v++) {
@@ -238,27 +311,20 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
         for (int v = 0; v < 16; v++) {
           const int r = (v >> 2) * 8 + (v & 3);
           if (mb + r + g * 4 >= M) continue;
-          float val = (acc[rb][nb][v] + bias) * sc;
-          if (e.relu) val = fmaxf(val, 0.f);
-          val += res[v];
-          char *at_ = dblock + (dlane + (unsigned)(r * ld * CE));
-          if (C_F32) {
-            *(float *)at_ = val;
-          } else {
-            const _Float16 hi = (_Float16)val;
-            *(_Float16 *)at_ = hi;
-            if (e.dst_lo_offset) *((_Float16 *)at_ + e.dst_lo_offset) = (_Float16)(val - (float)hi);
-          }
+          put(dblock + (dlane + (unsigned)(r * ld * CE)), finish(blk, v, res[v]));
         }
       }
+      // Nothing of this path may be left in flight at the end of the iteration: what is pending here (loads into
+      // registers that the other path reuses) is also assumed pending there, and costs it a full wait per strip.
+      __builtin_amdgcn_s_waitcnt(0x0F70);
     }
   }
 }
 
-template <int RB, int K, bool C_F32, bool LN>
+template <int RB, int K, bool C_F32, bool LN, int GS_WAVES>
 static hipError_t gs_launch(const _Float16 *A, const _Float16 *A_lo, long lda, int M, const _Float16 *Wp, int N,
                             const GemmEpilogue &e, const GemmLayerNorm &ln, hipStream_t s) {
-  auto kern = gemm_stream_kernel<RB, K, C_F32, LN>;
+  auto kern = gemm_stream_kernel<RB, K, C_F32, LN, GS_WAVES>;
   const size_t lds = (size_t)64 * RB * (K + 8) * 2;
   // raising the dynamic LDS limit is per kernel, once per process (several host threads may get here at once)
   static std::once_flag once;
@@ -287,10 +353,17 @@ static hipError_t gs_dispatch(bool c_f32, const _Float16 *A, const _Float16 *A_l
   if (M <= 0 || N <= 0) return hipSuccess;
   if (!gemm_stream_supported(N, K) || e.n_split % 32 != 0) return hipErrorInvalidValue;
   const bool small = M <= 8192;  // 32-row tiles: twice the workgroups
-#define NT_GS_CASE(RB_, K_, CF_)                                 \
-  if (small == (RB_ == 1) && K == K_ && c_f32 == CF_) return gs_launch<RB_, K_, CF_, LN>(A, A_lo, lda, M, Wp, N, e, ln, s);
-  NT_GS_CASE(1, 512, true) NT_GS_CASE(1, 512, false) NT_GS_CASE(2, 512, true) NT_GS_CASE(2, 512, false)
-  NT_GS_CASE(1, 256, true) NT_GS_CASE(1, 256, false) NT_GS_CASE(2, 256, true) NT_GS_CASE(2, 256, false)
+  // Encoder-sized launches with an fp32 output spend two thirds of a wave's time in the store phase of the epilogue;
+  // a third wave per SIMD (where the strips divide among twelve) keeps the matrix pipe busy meanwhile.
+  const int waves = (LN && !small && c_f32 && (N / 64) % 12 == 0) ? 12 : 8;
+#define NT_GS_CASE(RB_, K_, CF_, W_)                                  \
+  if (small == (RB_ == 1) && K == K_ && c_f32 == CF_ && waves == W_) \
+    return gs_launch<RB_, K_, CF_, LN, W_>(A, A_lo, lda, M, Wp, N, e, ln, s);
+  NT_GS_CASE(1, 512, true, 8) NT_GS_CASE(1, 512, false, 8) NT_GS_CASE(2, 512, true, 8) NT_GS_CASE(2, 512, false, 8)
+  NT_GS_CASE(1, 256, true, 8) NT_GS_CASE(1, 256, false, 8) NT_GS_CASE(2, 256, true, 8) NT_GS_CASE(2, 256, false, 8)
+  if constexpr (LN) {
+    NT_GS_CASE(2, 512, true, 12) NT_GS_CASE(2, 256, true, 12)
+  }
 #undef NT_GS_CASE
   return hipErrorInvalidValue;
 }
