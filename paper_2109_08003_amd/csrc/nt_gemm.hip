@@ -154,6 +154,97 @@ __device__ __forceinline__ void mainloop(const void *A, const void *A2, long lda
   }
 }
 
+// Epilogue of NB 32 x 32 accumulator blocks of one wave: block i has its origin at row mb0[i], column nb0[i] (both
+// uniform over the wave); lane (g, li) holds, in acc[i][v], the element at row (v/4)*8 + g*4 + v%4, column li of it.
+// When all blocks lie inside the matrix the code is straight-line: a block's 16 residual values are requested before
+// the stores of the block before it, and every store is issued without waiting for the one before it.  (With a guard
+// around each store the compiler waits for the memory counter to reach zero before every store, i.e. for the
+// acknowledgement of the previous one.)  Addresses are a uniform 64-bit base plus a 32-bit lane offset.  Blocks that
+// stick out of the matrix take the path that checks every element.
+template <int NB, bool C_F32>
+__device__ __forceinline__ void blocks_epilogue(const floatx16 *acc, const int *mb0, const int *nb0, int g, int li,
+                                                bool inside, int M, int N, const GemmEpilogue &e) {
+  constexpr int CE = C_F32 ? 4 : 2;
+  auto finish = [&](float a, float bias, float sc, float r) -> float {
+    float val = (a + bias) * sc;
+    if (e.relu) val = fmaxf(val, 0.f);
+    return val + r;
+  };
+  auto put = [&](char *at_, float val) {
+    if (C_F32) {
+      *(float *)at_ = val;
+    } else {
+      const _Float16 hi = (_Float16)val;
+      *(_Float16 *)at_ = hi;
+      if (e.dst_lo_offset) *((_Float16 *)at_ + e.dst_lo_offset) = (_Float16)(val - (float)hi);
+    }
+  };
+  if (inside) {
+    float bias[NB], sc[NB];
+#pragma unroll
+    for (int i = 0; i < NB; i++) {
+      const int n = nb0[i] + li;
+      bias[i] = e.bias ? e.bias[n] : 0.f;
+      sc[i] = (n < e.scale_cols) ? e.scale : 1.f;
+    }
+    auto store_block = [&](int i, const float *res) {
+      const bool first = nb0[i] < e.n_split;  // n_split is a multiple of 32: a block never straddles the destinations
+      char *dst = (char *)(first ? e.dst0 : e.dst1);
+      const long ld = first ? e.ld0 : e.ld1;
+      char *dblock = dst + ((long)mb0[i] * ld + (first ? nb0[i] : nb0[i] - e.n_split)) * CE;
+      unsigned dlane = (unsigned)((g * 4 * ld + li) * CE);
+      asm volatile("" : "+v"(dlane));
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const int r = (v >> 2) * 8 + (v & 3);
+        put(dblock + (dlane + (unsigned)(r * ld * CE)), finish(acc[i][v], bias[i], sc[i], res ? res[v] : 0.f));
+      }
+    };
+    if (e.resid) {
+      float res[2][16];
+      auto request = [&](int i) {
+        const char *rblock = (const char *)e.resid + ((long)mb0[i] * e.ldr + nb0[i]) * 4;
+        unsigned rlane = (unsigned)((g * 4 * e.ldr + li) * 4);
+        asm volatile("" : "+v"(rlane));
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          const int r = (v >> 2) * 8 + (v & 3);
+          res[i & 1][v] = *(const float *)(rblock + (rlane + (unsigned)(r * e.ldr * 4)));
+        }
+      };
+      request(0);
+#pragma unroll
+      for (int i = 0; i < NB; i++) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (i + 1 < NB) request(i + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        store_block(i, res[i & 1]);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NB; i++) store_block(i, nullptr);
+    }
+    return;
+  }
+#pragma unroll
+  for (int i = 0; i < NB; i++) {
+    const int n = nb0[i] + li;
+    if (n >= N) continue;
+    const float bias = e.bias ? e.bias[n] : 0.f;
+    const float sc = (n < e.scale_cols) ? e.scale : 1.f;
+    const bool first = n < e.n_split;
+    char *dst = (char *)(first ? e.dst0 : e.dst1);
+    const long ld = first ? e.ld0 : e.ld1;
+    const int nc = first ? n : n - e.n_split;
+#pragma unroll
+    for (int v = 0; v < 16; v++) {
+      const int m = mb0[i] + (v >> 2) * 8 + g * 4 + (v & 3);
+      if (m >= M) continue;
+      put(dst + ((long)m * ld + nc) * CE, finish(acc[i][v], bias, sc, e.resid ? e.resid[(long)m * e.ldr + n] : 0.f));
+    }
+  }
+}
+
 // Workgroup id -> (m tile, n tile), XCD-aware.  Returns false for the padding ids of the grid.
 __device__ __forceinline__ bool tile_of(int id, int tiles_m, int tiles_n, int &mt, int &nt_) {
   const int xcd = id & 7, j = id >> 3;
@@ -184,34 +275,17 @@ __global__ __launch_bounds__(256) void gemm_kernel(const void *A, const void *A2
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave >> 1, wn = wave & 1, li = lane & 31, g = lane >> 5;
+  const int wmu = __builtin_amdgcn_readfirstlane(wm), wnu = __builtin_amdgcn_readfirstlane(wn);
+  int mb0[4], nb0[4];
 #pragma unroll
-  for (int nb = 0; nb < 2; nb++) {
-    const int n = n0 + wn * 64 + nb * 32 + li;
-    if (n >= N) continue;
-    const float bias = e.bias ? e.bias[n] : 0.f;
-    const float sc = (n < e.scale_cols) ? e.scale : 1.f;
-    const bool first = n < e.n_split;
-    char *dst = (char *)(first ? e.dst0 : e.dst1);
-    const long ld = first ? e.ld0 : e.ld1;
-    const int nc = first ? n : n - e.n_split;
+  for (int mb = 0; mb < 2; mb++)
 #pragma unroll
-    for (int mb = 0; mb < 2; mb++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) {
-        const int m = m0 + wm * 64 + mb * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
-        if (m >= M) continue;
-        float val = (acc[mb][nb][v] + bias) * sc;
-        if (e.relu) val = fmaxf(val, 0.f);
-        if (e.resid) val += e.resid[(long)m * e.ldr + n];
-        if (C_F32) {
-          ((float *)dst)[(long)m * ld + nc] = val;
-        } else {
-          const _Float16 hi = (_Float16)val;
-          ((_Float16 *)dst)[(long)m * ld + nc] = hi;
-          if (e.dst_lo_offset) ((_Float16 *)dst)[(long)m * ld + nc + e.dst_lo_offset] = (_Float16)(val - (float)hi);
-        }
-      }
-  }
+    for (int nb = 0; nb < 2; nb++) {
+      mb0[mb * 2 + nb] = m0 + wmu * 64 + mb * 32;
+      nb0[mb * 2 + nb] = n0 + wnu * 64 + nb * 32;
+    }
+  const bool inside = m0 + wmu * 64 + 64 <= M && n0 + wnu * 64 + 64 <= N && e.n_split % 32 == 0;
+  blocks_epilogue<4, C_F32>(&acc[0][0], mb0, nb0, g, li, inside, M, N, e);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -319,29 +393,9 @@ __global__ __launch_bounds__(256) void gemm_mid_kernel(const void *A, const void
       }
     }
   }
-  const int n = n0 + wn * 32 + li;
-  if (n >= N) return;
-  const float bias = e.bias ? e.bias[n] : 0.f;
-  const float sc = (n < e.scale_cols) ? e.scale : 1.f;
-  const bool first = n < e.n_split;
-  char *dst = (char *)(first ? e.dst0 : e.dst1);
-  const long ld = first ? e.ld0 : e.ld1;
-  const int nc = first ? n : n - e.n_split;
-#pragma unroll
-  for (int v = 0; v < 16; v++) {
-    const int m = m0 + wm * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
-    if (m >= M) continue;
-    float val = (acc[v] + bias) * sc;
-    if (e.relu) val = fmaxf(val, 0.f);
-    if (e.resid) val += e.resid[(long)m * e.ldr + n];
-    if (C_F32) {
-      ((float *)dst)[(long)m * ld + nc] = val;
-    } else {
-      const _Float16 hi = (_Float16)val;
-      ((_Float16 *)dst)[(long)m * ld + nc] = hi;
-      if (e.dst_lo_offset) ((_Float16 *)dst)[(long)m * ld + nc + e.dst_lo_offset] = (_Float16)(val - (float)hi);
-    }
-  }
+  const int mb0 = m0 + __builtin_amdgcn_readfirstlane(wm) * 32, nb0 = n0 + __builtin_amdgcn_readfirstlane(wn) * 32;
+  const bool inside = mb0 + 32 <= M && nb0 + 32 <= N && e.n_split % 32 == 0;
+  blocks_epilogue<1, C_F32>(&acc, &mb0, &nb0, g, li, inside, M, N, e);
 }
 
 hipError_t launch_gemm(int a_mode, bool c_f32, const void *A, const void *A_lo, long lda, const _Float16 *Wt, int M,
