@@ -9,6 +9,15 @@ namespace nt {
 
 constexpr int MAX_PER_LANE = 16;  // d <= 1024
 
+// The kernels are compiled for the row lengths in use (NE = d / 64 elements per lane: 4, 8, 16) and once for any
+// other length (NE = 0: the count is a run-time value and every element is guarded).  The fixed counts matter for
+// more than the loop overhead: loads and stores of a wave complete in order on one counter, and around guarded
+// accesses the compiler waits for that counter to reach zero, so that every store would wait for the acknowledgement
+// of the one before it.
+#define NT_FOR_LANE_ELEMS(i) \
+  _Pragma("unroll") for (int i = 0; i < (NE ? NE : MAX_PER_LANE); i++) if (NE || i < ne)
+static int ne_case(int d) { return (d == 256 || d == 512 || d == 1024) ? d / 64 : 0; }
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
@@ -26,26 +35,27 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long x)
 }
 
 // lane holds elements lane + 64*i, i < ne
+template <int NE>
 __device__ __forceinline__ void row_layer_norm(float (&v)[MAX_PER_LANE], int ne, int d, LnEps eps, int lane,
                                                const float *gamma, const float *beta) {
+  float ga[MAX_PER_LANE], be[MAX_PER_LANE];
+  NT_FOR_LANE_ELEMS(i) {
+    ga[i] = gamma[lane + 64 * i];
+    be[i] = beta[lane + 64 * i];
+  }
   float s = 0.f;
-#pragma unroll
-  for (int i = 0; i < MAX_PER_LANE; i++)
-    if (i < ne) s += v[i];
+  NT_FOR_LANE_ELEMS(i) s += v[i];
   const float mean = wave_sum(s) / (float)d;
   float q = 0.f;
-#pragma unroll
-  for (int i = 0; i < MAX_PER_LANE; i++)
-    if (i < ne) {
-      const float c = v[i] - mean;
-      q += ln_term(c, eps.l1);
-    }
+  NT_FOR_LANE_ELEMS(i) {
+    const float c = v[i] - mean;
+    q += ln_term(c, eps.l1);
+  }
   const float rstd = ln_rscale(wave_sum(q) / (float)d, eps);
-#pragma unroll
-  for (int i = 0; i < MAX_PER_LANE; i++)
-    if (i < ne) v[i] = gamma[lane + 64 * i] * ((v[i] - mean) * rstd) + beta[lane + 64 * i];
+  NT_FOR_LANE_ELEMS(i) v[i] = ga[i] * ((v[i] - mean) * rstd) + be[i];
 }
 
+template <int NE>
 __global__ __launch_bounds__(256) void embed_src_kernel(const int32_t *src, const int32_t *len, int32_t *len_out, int B,
                                                         int S, int d, int vocab, int pad_id, const _Float16 *E,
                                                         const float *pe, float *x, int32_t *flags) {
@@ -72,19 +82,31 @@ __global__ __launch_bounds__(256) void embed_src_kernel(const int32_t *src, cons
   const _Float16 *e = E + (long)id * d;
   const float *p = pe + (long)pos * d;
   float *o = x + r * d;
-  for (int i = lane; i < d; i += 64) o[i] = sc * (float)e[i] + p[i];
+  if (NE) {
+    float v[MAX_PER_LANE];
+    const int ne = NE;
+    NT_FOR_LANE_ELEMS(i) v[i] = sc * (float)e[lane + 64 * i] + p[lane + 64 * i];
+    NT_FOR_LANE_ELEMS(i) o[lane + 64 * i] = v[i];
+  } else {
+    for (int i = lane; i < d; i += 64) o[i] = sc * (float)e[i] + p[i];
+  }
 }
 
 hipError_t launch_embed_src(const int32_t *src, const int32_t *len, int32_t *len_out, int B, int S, int d, int vocab,
                             int pad_id, const _Float16 *E, const float *pe, float *x, int32_t *flags, hipStream_t s) {
   long rows = (long)B * S;
   if (rows <= 0) return hipSuccess;
-  hipLaunchKernelGGL(embed_src_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, src, len, len_out, B, S, d,
-                     vocab, pad_id, E, pe, x, flags);
+#define NT_CASE(NE_)                                                                                                  \
+  case NE_:                                                                                                           \
+    hipLaunchKernelGGL(embed_src_kernel<NE_>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, src, len, len_out, B, \
+                       S, d, vocab, pad_id, E, pe, x, flags);                                                         \
+    break;
+  switch (ne_case(d)) { NT_CASE(4) NT_CASE(8) NT_CASE(16) NT_CASE(0) }
+#undef NT_CASE
   return hipGetLastError();
 }
 
-template <int MODE>
+template <int MODE, int NE>
 __global__ __launch_bounds__(256) void layer_norm_kernel(const float *x, int M, int d, const float *gamma,
                                                          const float *beta, LnEps eps, void *out, long lo_offset,
                                                          float *lo_norm) {
@@ -94,14 +116,10 @@ __global__ __launch_bounds__(256) void layer_norm_kernel(const float *x, int M, 
   const int ne = d >> 6;
   float v[MAX_PER_LANE];
   const float *xr = x + r * d;
-#pragma unroll
-  for (int i = 0; i < MAX_PER_LANE; i++)
-    if (i < ne) v[i] = xr[lane + 64 * i];
-  row_layer_norm(v, ne, d, eps, lane, gamma, beta);
+  NT_FOR_LANE_ELEMS(i) v[i] = xr[lane + 64 * i];
+  row_layer_norm<NE>(v, ne, d, eps, lane, gamma, beta);
   float tail2 = 0.f;
-#pragma unroll
-  for (int i = 0; i < MAX_PER_LANE; i++)
-    if (i < ne) {
+  NT_FOR_LANE_ELEMS(i) {
       const long o = r * d + lane + 64 * i;
       if (MODE == OUT_F32) {
         ((float *)out)[o] = v[i];
@@ -125,12 +143,20 @@ hipError_t launch_layer_norm(const float *x, int M, int d, const float *gamma, c
                              void *out, int out_mode, long lo_offset, hipStream_t s, float *lo_norm) {
   if (M <= 0) return hipSuccess;
   dim3 grid((M + 3) / 4), block(256);
-  if (out_mode == OUT_F32)
-    hipLaunchKernelGGL(layer_norm_kernel<OUT_F32>, grid, block, 0, s, x, M, d, gamma, beta, eps, out, lo_offset, lo_norm);
-  else if (out_mode == OUT_PLANES)
-    hipLaunchKernelGGL(layer_norm_kernel<OUT_PLANES>, grid, block, 0, s, x, M, d, gamma, beta, eps, out, lo_offset, lo_norm);
-  else
-    hipLaunchKernelGGL(layer_norm_kernel<OUT_F16>, grid, block, 0, s, x, M, d, gamma, beta, eps, out, lo_offset, lo_norm);
+#define NT_CASE(NE_)                                                                                             \
+  case NE_:                                                                                                      \
+    if (out_mode == OUT_F32)                                                                                     \
+      hipLaunchKernelGGL((layer_norm_kernel<OUT_F32, NE_>), grid, block, 0, s, x, M, d, gamma, beta, eps, out,     \
+                         lo_offset, lo_norm);                                                                    \
+    else if (out_mode == OUT_PLANES)                                                                             \
+      hipLaunchKernelGGL((layer_norm_kernel<OUT_PLANES, NE_>), grid, block, 0, s, x, M, d, gamma, beta, eps, out,  \
+                         lo_offset, lo_norm);                                                                    \
+    else                                                                                                         \
+      hipLaunchKernelGGL((layer_norm_kernel<OUT_F16, NE_>), grid, block, 0, s, x, M, d, gamma, beta, eps, out,     \
+                         lo_offset, lo_norm);                                                                    \
+    break;
+  switch (ne_case(d)) { NT_CASE(4) NT_CASE(8) NT_CASE(16) NT_CASE(0) }
+#undef NT_CASE
   return hipGetLastError();
 }
 
@@ -177,6 +203,7 @@ hipError_t launch_spin(long ticks, int *sink, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int NE>
 __global__ __launch_bounds__(256) void step_begin_kernel(StepBeginArgs a) {
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -213,17 +240,11 @@ __global__ __launch_bounds__(256) void step_begin_kernel(StepBeginArgs a) {
   const _Float16 *e = a.E + (long)y * d;
   const float *p = a.pe + (long)a.t * d;
   float v[MAX_PER_LANE];
-#pragma unroll
-  for (int i = 0; i < MAX_PER_LANE; i++)
-    if (i < ne) {
-      v[i] = sc * (float)e[lane + 64 * i] + p[lane + 64 * i];
-      a.z[(long)r * d + lane + 64 * i] = v[i];
-    }
+  NT_FOR_LANE_ELEMS(i) v[i] = sc * (float)e[lane + 64 * i] + p[lane + 64 * i];
+  NT_FOR_LANE_ELEMS(i) a.z[(long)r * d + lane + 64 * i] = v[i];
   if (!a.a) return;  // the consumer applies the LayerNorm itself
-  row_layer_norm(v, ne, d, a.eps, lane, a.gamma, a.beta);
-#pragma unroll
-  for (int i = 0; i < MAX_PER_LANE; i++)
-    if (i < ne) a.a[(long)r * d + lane + 64 * i] = v[i];
+  row_layer_norm<NE>(v, ne, d, a.eps, lane, a.gamma, a.beta);
+  NT_FOR_LANE_ELEMS(i) a.a[(long)r * d + lane + 64 * i] = v[i];
 }
 
 // ---- EOS-terminated decoding: the rows still decoding are a dense prefix ---------------------------------------
@@ -313,6 +334,7 @@ __global__ __launch_bounds__(1024) void eos_compact_kernel(EosStepArgs a) {
   }
 }
 
+template <int NE>
 __global__ __launch_bounds__(256) void eos_embed_kernel(EosStepArgs a) {
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -324,9 +346,9 @@ __global__ __launch_bounds__(256) void eos_embed_kernel(EosStepArgs a) {
   const float sc = sqrtf((float)d);
   const _Float16 *e = a.E + (long)y * d;
   const float *p = a.pe + (long)a.t * d;
-#pragma unroll
-  for (int i = 0; i < MAX_PER_LANE; i++)
-    if (i < ne) a.z[(long)r * d + lane + 64 * i] = sc * (float)e[lane + 64 * i] + p[lane + 64 * i];
+  float v[MAX_PER_LANE];
+  NT_FOR_LANE_ELEMS(i) v[i] = sc * (float)e[lane + 64 * i] + p[lane + 64 * i];
+  NT_FOR_LANE_ELEMS(i) a.z[(long)r * d + lane + 64 * i] = v[i];
 }
 
 hipError_t launch_eos_step_begin(const EosStepArgs &a, hipStream_t s) {
@@ -334,13 +356,23 @@ hipError_t launch_eos_step_begin(const EosStepArgs &a, hipStream_t s) {
   if (a.rows_now > a.rows_prev) return hipErrorInvalidValue;
   if (a.t > 0) hipLaunchKernelGGL(eos_collect_kernel, dim3((a.rows_prev + 3) / 4), dim3(256), 0, s, a);
   hipLaunchKernelGGL(eos_compact_kernel, dim3(1), dim3(1024), 0, s, a);
-  if (a.rows_now > 0) hipLaunchKernelGGL(eos_embed_kernel, dim3((a.rows_now + 3) / 4), dim3(256), 0, s, a);
+#define NT_CASE(NE_)                                                                              \
+  case NE_:                                                                                       \
+    hipLaunchKernelGGL(eos_embed_kernel<NE_>, dim3((a.rows_now + 3) / 4), dim3(256), 0, s, a); \
+    break;
+  if (a.rows_now > 0) switch (ne_case(a.d)) { NT_CASE(4) NT_CASE(8) NT_CASE(16) NT_CASE(0) }
+#undef NT_CASE
   return hipGetLastError();
 }
 
 hipError_t launch_step_begin(const StepBeginArgs &a, hipStream_t s) {
   if (a.rows_prev <= 0) return hipSuccess;
-  hipLaunchKernelGGL(step_begin_kernel, dim3((a.rows_prev + 3) / 4), dim3(256), 0, s, a);
+#define NT_CASE(NE_)                                                                                \
+  case NE_:                                                                                         \
+    hipLaunchKernelGGL(step_begin_kernel<NE_>, dim3((a.rows_prev + 3) / 4), dim3(256), 0, s, a); \
+    break;
+  switch (ne_case(a.d)) { NT_CASE(4) NT_CASE(8) NT_CASE(16) NT_CASE(0) }
+#undef NT_CASE
   return hipGetLastError();
 }
 
