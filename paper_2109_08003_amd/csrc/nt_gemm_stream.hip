@@ -27,6 +27,8 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+constexpr int GS_WAVES = 8;
+
 bool gemm_stream_supported(int N, int K) { return (K == 256 || K == 512) && N % 64 == 0; }
 
 __device__ __forceinline__ float gs_wave_sum(float v) {
@@ -39,7 +41,7 @@ __device__ __forceinline__ float gs_wave_sum(float v) {
 // LN = true: A_hi points to fp32 rows X[M][lda] instead; the tile is LayerNorm-ed (fp32 statistics: mean first, then
 // the biased variance of the centred values) and split into head/tail planes while it is written to the LDS, which
 // saves the separate LayerNorm kernel and the round trip of its output through memory.
-template <int RB, int K, bool C_F32, bool LN, int GS_WAVES>
+template <int RB, int K, bool C_F32, bool LN>
 __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float16 *__restrict__ A_hi,
                                                                    const _Float16 *__restrict__ A_lo, long lda, int M,
                                                                    const _Float16 *__restrict__ Wp, int N, int col_groups,
@@ -51,8 +53,7 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   constexpr int KS = K / 16;
   // register slots of W fragments per wave; the lookahead is SL - 1 k-steps.  (A deeper ring did not shorten the
   // decoder-sized launches, and fewer registers leave room for other kernels' waves on the same CU.)
-  // With three waves per SIMD the register budget is 168, and the other waves cover a shorter lookahead.
-  constexpr int SL = GS_WAVES > 8 ? 4 : 8;
+  constexpr int SL = 8;
   constexpr int NOPS = 2 * RB;
   static_assert(KS % SL == 0, "the ring of W slots must divide the k-steps of a strip");
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, g = lane >> 5;
@@ -72,12 +73,12 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   // ---- the A tile: global memory -> LDS.  Rows past M repeat row M - 1 (their results are never stored) ----
   if constexpr (LN) {
     // a wave takes rows wave, wave + 8, ...; a lane holds NE consecutive elements of the row
-    constexpr int NE = K / 64, RPW = (TM + GS_WAVES - 1) / GS_WAVES;
+    constexpr int NE = K / 64, RPW = TM / GS_WAVES;
     const float *X = (const float *)A_hi;
     float xv[RPW][NE];
 #pragma unroll
     for (int i = 0; i < RPW; i++) {
-      int m = m0 + wave + GS_WAVES * i;  // (rows past the tile, when the waves do not divide it, are not written)
+      int m = m0 + wave + GS_WAVES * i;
       m = m < M ? m : M - 1;
       const float *xr = X + (long)m * lda + lane * NE;
 #pragma unroll
@@ -111,15 +112,13 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
         lo[j] = (_Float16)(y - (float)hi[j]);
       }
       const int R = wave + GS_WAVES * i;
-      if (TM % GS_WAVES != 0 && R >= TM) continue;
       *(halfNE *)(sh + R * LD + lane * NE) = hi;
       *(halfNE *)(sh + (R + TM) * LD + lane * NE) = lo;
     }
   } else if (K == 512) {
 #pragma unroll
-    for (int i = 0; i < (ROWS + GS_WAVES - 1) / GS_WAVES; i++) {
+    for (int i = 0; i < ROWS / GS_WAVES; i++) {
       const int R = wave + GS_WAVES * i;
-      if (ROWS % GS_WAVES != 0 && R >= ROWS) continue;
       const _Float16 *src = R >= TM ? A_lo : A_hi;
       int m = m0 + (R % TM);
       m = m < M ? m : M - 1;
@@ -127,13 +126,11 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
                                        (__attribute__((address_space(3))) void *)(sh + R * LD), 16, 0, 0);
     }
   } else {
-    constexpr int CPR = K / 8, PER_T = (ROWS * CPR + GS_WAVES * 64 - 1) / (GS_WAVES * 64);
+    constexpr int CPR = K / 8, PER_T = ROWS * CPR / (GS_WAVES * 64);
     u32x4 fr[PER_T];
 #pragma unroll
     for (int i = 0; i < PER_T; i++) {
-      int c = tid + GS_WAVES * 64 * i;
-      c = c < ROWS * CPR ? c : ROWS * CPR - 1;
-      const int R = c / CPR, kc = c % CPR;
+      const int c = tid + GS_WAVES * 64 * i, R = c / CPR, kc = c % CPR;
       const _Float16 *src = R >= TM ? A_lo : A_hi;
       int m = m0 + (R % TM);
       m = m < M ? m : M - 1;
@@ -142,7 +139,7 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
 #pragma unroll
     for (int i = 0; i < PER_T; i++) {
       const int c = tid + GS_WAVES * 64 * i, R = c / CPR, kc = c % CPR;
-      if (c < ROWS * CPR) *(u32x4 *)(sh + R * LD + kc * 8) = fr[i];
+      *(u32x4 *)(sh + R * LD + kc * 8) = fr[i];
     }
   }
   half8 wb[SL][2];
@@ -162,8 +159,7 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   // Two waves share a SIMD.  With equal priority they take turns at the matrix pipe, finish their strips together
   // and then both sit in the store phase of the epilogue (the long one when the output is fp32) while the pipe
   // idles.  Giving one of them priority makes the phases alternate instead.
-  if (wave < 4) __builtin_amdgcn_s_setprio(2);
-  else if (GS_WAVES > 8 && wave < 8) __builtin_amdgcn_s_setprio(1);
+  if (wave < GS_WAVES / 2) __builtin_amdgcn_s_setprio(2);
 
   floatx16 acc[RB][2];
   // fragment row of operand op: head rows of block op % RB, then the tail rows; two base registers, because the
@@ -321,10 +317,10 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   }
 }
 
-template <int RB, int K, bool C_F32, bool LN, int GS_WAVES>
+template <int RB, int K, bool C_F32, bool LN>
 static hipError_t gs_launch(const _Float16 *A, const _Float16 *A_lo, long lda, int M, const _Float16 *Wp, int N,
                             const GemmEpilogue &e, const GemmLayerNorm &ln, hipStream_t s) {
-  auto kern = gemm_stream_kernel<RB, K, C_F32, LN, GS_WAVES>;
+  auto kern = gemm_stream_kernel<RB, K, C_F32, LN>;
   const size_t lds = (size_t)64 * RB * (K + 8) * 2;
   // raising the dynamic LDS limit is per kernel, once per process (several host threads may get here at once)
   static std::once_flag once;
@@ -353,17 +349,10 @@ static hipError_t gs_dispatch(bool c_f32, const _Float16 *A, const _Float16 *A_l
   if (M <= 0 || N <= 0) return hipSuccess;
   if (!gemm_stream_supported(N, K) || e.n_split % 32 != 0) return hipErrorInvalidValue;
   const bool small = M <= 8192;  // 32-row tiles: twice the workgroups
-  // Encoder-sized launches with an fp32 output spend two thirds of a wave's time in the store phase of the epilogue;
-  // a third wave per SIMD (where the strips divide among twelve) keeps the matrix pipe busy meanwhile.
-  const int waves = (LN && !small && c_f32 && (N / 64) % 12 == 0) ? 12 : 8;
-#define NT_GS_CASE(RB_, K_, CF_, W_)                                  \
-  if (small == (RB_ == 1) && K == K_ && c_f32 == CF_ && waves == W_) \
-    return gs_launch<RB_, K_, CF_, LN, W_>(A, A_lo, lda, M, Wp, N, e, ln, s);
-  NT_GS_CASE(1, 512, true, 8) NT_GS_CASE(1, 512, false, 8) NT_GS_CASE(2, 512, true, 8) NT_GS_CASE(2, 512, false, 8)
-  NT_GS_CASE(1, 256, true, 8) NT_GS_CASE(1, 256, false, 8) NT_GS_CASE(2, 256, true, 8) NT_GS_CASE(2, 256, false, 8)
-  if constexpr (LN) {
-    NT_GS_CASE(2, 512, true, 12) NT_GS_CASE(2, 256, true, 12)
-  }
+#define NT_GS_CASE(RB_, K_, CF_)                                 \
+  if (small == (RB_ == 1) && K == K_ && c_f32 == CF_) return gs_launch<RB_, K_, CF_, LN>(A, A_lo, lda, M, Wp, N, e, ln, s);
+  NT_GS_CASE(1, 512, true) NT_GS_CASE(1, 512, false) NT_GS_CASE(2, 512, true) NT_GS_CASE(2, 512, false)
+  NT_GS_CASE(1, 256, true) NT_GS_CASE(1, 256, false) NT_GS_CASE(2, 256, true) NT_GS_CASE(2, 256, false)
 #undef NT_GS_CASE
   return hipErrorInvalidValue;
 }
