@@ -31,12 +31,6 @@ constexpr int GS_WAVES = 8;
 
 bool gemm_stream_supported(int N, int K) { return (K == 256 || K == 512) && N % 64 == 0; }
 
-__device__ __forceinline__ float gs_wave_sum(float v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-  return v;
-}
-
 // RB = 32-row blocks per tile (1: decoder-sized M; 2: encoder-sized M).
 // LN = true: A_hi points to fp32 rows X[M][lda] instead; the tile is LayerNorm-ed (fp32 statistics: mean first, then
 // the biased variance of the centred values) and split into head/tail planes while it is written to the LDS, which
@@ -90,24 +84,51 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
       *(float4 *)&gam[j] = *(const float4 *)(ln.gamma + lane * NE + j);
       *(float4 *)&bet[j] = *(const float4 *)(ln.beta + lane * NE + j);
     }
+    // The butterflies of all rows advance together, one exchange step at a time: a step of one row waits for the
+    // cross-lane exchange before it (about 150 clocks), and row after row these waits were most of the fill.
+    float mean[RPW], rstd[RPW];
 #pragma unroll
     for (int i = 0; i < RPW; i++) {
       float sum = 0.f;
 #pragma unroll
       for (int j = 0; j < NE; j++) sum += xv[i][j];
-      const float mean = gs_wave_sum(sum) / (float)K;
+      mean[i] = sum;
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+      float o[RPW];
+#pragma unroll
+      for (int i = 0; i < RPW; i++) o[i] = __shfl_xor(mean[i], m, 64);
+#pragma unroll
+      for (int i = 0; i < RPW; i++) mean[i] += o[i];
+    }
+#pragma unroll
+    for (int i = 0; i < RPW; i++) {
+      mean[i] = mean[i] / (float)K;
       float q = 0.f;
 #pragma unroll
       for (int j = 0; j < NE; j++) {
-        const float c = xv[i][j] - mean;
+        const float c = xv[i][j] - mean[i];
         q += ln_term(c, ln.eps.l1);
       }
-      const float rstd = ln_rscale(gs_wave_sum(q) / (float)K, ln.eps);
+      rstd[i] = q;
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+      float o[RPW];
+#pragma unroll
+      for (int i = 0; i < RPW; i++) o[i] = __shfl_xor(rstd[i], m, 64);
+#pragma unroll
+      for (int i = 0; i < RPW; i++) rstd[i] += o[i];
+    }
+#pragma unroll
+    for (int i = 0; i < RPW; i++) {
+      rstd[i] = ln_rscale(rstd[i] / (float)K, ln.eps);
       typedef _Float16 halfNE __attribute__((ext_vector_type(NE)));
       halfNE hi, lo;
 #pragma unroll
       for (int j = 0; j < NE; j++) {
-        const float y = gam[j] * ((xv[i][j] - mean) * rstd) + bet[j];
+        const float y = gam[j] * ((xv[i][j] - mean[i]) * rstd[i]) + bet[j];
         hi[j] = (_Float16)y;
         lo[j] = (_Float16)(y - (float)hi[j]);
       }
