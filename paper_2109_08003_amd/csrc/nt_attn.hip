@@ -307,14 +307,15 @@ __device__ __forceinline__ void split8u(const float *f, half8 &hi, half8 &lo) {
 }
 
 template <int DH, int NKB>
-__global__ __launch_bounds__(256) void enc_attention_wave_kernel(const float *qkv, const int32_t *len, _Float16 *ctx,
+__global__ __launch_bounds__(256, NKB == 1 ? 3 : NKB == 2 ? 2 : 1) void enc_attention_wave_kernel(const float *qkv, const int32_t *len, _Float16 *ctx,
                                                                  long ctx_lo_offset, int B, int S, int d, int heads,
                                                                  int q_tiles) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, li = lane & 31, g = lane >> 5;
-  const long unit = (long)blockIdx.x * 4 + wave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, li = lane & 31, g = lane >> 5;
+  const long unit = (long)blockIdx.x * 4 + wave;  // uniform over the wave, and known to be: addresses below are a
+                                                   // uniform 64-bit base plus a 32-bit lane offset
   if (unit >= (long)B * heads * q_tiles) return;
   const int qt = (int)(unit % q_tiles), h = (int)((unit / q_tiles) % heads), b = (int)(unit / ((long)q_tiles * heads));
-  const int L = len[b], q0 = qt * 32;
+  const int L = __builtin_amdgcn_readfirstlane(len[b]), q0 = qt * 32;
   const long row0 = (long)b * S, ld = 3L * d;
   const int hoff = h * DH;
   if (q0 >= L) {  // padding queries: defined output, no work
@@ -335,29 +336,61 @@ __global__ __launch_bounds__(256) void enc_attention_wave_kernel(const float *qk
   for (int kb = 0; kb < NKB; kb++)
 #pragma unroll
     for (int v = 0; v < 16; v++) sc[kb][v] = 0.f;
+  // A lane's share of a 64-wide slice of the head is 32 consecutive values (its lane group's half), consumed by four
+  // MFMAs of 8; the loop takes them 16 at a time (two MFMAs) and, up to two key blocks, requests the next 16 of q and
+  // of every key block before multiplying the current ones, so that a wave always has loads in flight.
   const float *qp = qkv + (row0 + min(q0 + li, L - 1)) * ld + hoff + g * 32;
-  for (int c = 0; c < DH / 64; c++) {
-    float f[32];
+  const float *kp[NKB];
 #pragma unroll
-    for (int u = 0; u < 8; u++) *(float4 *)(f + 4 * u) = *(const float4 *)(qp + c * 64 + u * 4);
-    half8 qh[4], ql[4];
+  for (int kb = 0; kb < NKB; kb++) kp[kb] = qkv + (row0 + min(kb * 32 + li, L - 1)) * ld + d + hoff + g * 32;
+  constexpr bool QK_PREFETCH = NKB <= 2;
+  constexpr int NIT = DH / 32;  // iteration it: slice it / 2, half it % 2 of the lane's 32 values
+  float fq[QK_PREFETCH ? 2 : 1][16], fk[QK_PREFETCH ? 2 : 1][NKB][16];
+  auto qk_request = [&](int it, int slot) {
+    const int off = (it >> 1) * 64 + (it & 1) * 16;
 #pragma unroll
-    for (int u = 0; u < 4; u++) split8u(f + 8 * u, qh[u], ql[u]);
+    for (int u = 0; u < 4; u++) *(float4 *)(fq[slot] + 4 * u) = *(const float4 *)(qp + off + u * 4);
 #pragma unroll
     for (int kb = 0; kb < NKB; kb++) {
       if (kb < nkb) {
-        const float *kp = qkv + (row0 + min(kb * 32 + li, L - 1)) * ld + d + hoff + g * 32 + c * 64;
 #pragma unroll
-        for (int u = 0; u < 8; u++) *(float4 *)(f + 4 * u) = *(const float4 *)(kp + u * 4);
+        for (int u = 0; u < 4; u++) *(float4 *)(fk[slot][kb] + 4 * u) = *(const float4 *)(kp[kb] + off + u * 4);
+      }
+    }
+  };
+  auto qk_multiply = [&](int slot) {
+    half8 qh[2], ql[2];
 #pragma unroll
-        for (int u = 0; u < 4; u++) {
+    for (int u = 0; u < 2; u++) split8u(fq[slot] + 8 * u, qh[u], ql[u]);
+#pragma unroll
+    for (int kb = 0; kb < NKB; kb++) {
+      if (kb < nkb) {
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
           half8 kh, kl;
-          split8u(f + 8 * u, kh, kl);
+          split8u(fk[slot][kb] + 8 * u, kh, kl);
           sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kh, qh[u], sc[kb], 0, 0, 0);
           sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kl, qh[u], sc[kb], 0, 0, 0);
           sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kh, ql[u], sc[kb], 0, 0, 0);
         }
       }
+    }
+  };
+  if constexpr (QK_PREFETCH) {
+    static_assert(NIT % 2 == 0, "the two slots alternate over an even number of iterations");
+    qk_request(0, 0);
+#pragma nounroll
+    for (int it = 0; it < NIT; it += 2) {
+      qk_request(it + 1, 1);
+      qk_multiply(0);
+      if (it + 2 < NIT) qk_request(it + 2, 0);
+      qk_multiply(1);
+    }
+  } else {
+#pragma nounroll
+    for (int it = 0; it < NIT; it++) {
+      qk_request(it, 0);
+      qk_multiply(0);
     }
   }
 
@@ -395,8 +428,33 @@ __global__ __launch_bounds__(256) void enc_attention_wave_kernel(const float *qk
     }
 
   // ---- context = P V, one 32-column block at a time ----
-  const float *vbase = qkv + row0 * ld + 2 * d + hoff + li;
-  for (int cb = 0; cb < DH / 32; cb++) {
+  // The V values of the next block are requested before the MFMAs and stores of the current one (up to two key
+  // blocks; beyond that the registers do not allow it), so that a wave always has a block of loads in flight.
+  const char *vbase = (const char *)(qkv + row0 * ld + 2 * d + hoff);
+  char *obase = (char *)(ctx + row0 * d + hoff);
+  constexpr bool PREFETCH = NKB <= 2;
+  float fv[PREFETCH ? 2 : 1][NKB][2][8];
+  auto request = [&](int cb, int slot) {
+    // the block's base stays one opaque scalar pair: otherwise every one of the 16 addresses becomes a 64-bit
+    // induction variable of its own
+    const char *vb = vbase + cb * 128;
+    asm volatile("" : "+s"(vb));
+#pragma unroll
+    for (int kb = 0; kb < NKB; kb++) {
+      if (kb < nkb) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ks++)
+#pragma unroll
+          for (int e = 0; e < 8; e++) {  // same key order as the probability registers
+            const int key = min(kb * 32 + (2 * ks + (e >> 2)) * 8 + g * 4 + (e & 3), L - 1);
+            fv[slot][kb][ks][e] = *(const float *)(vb + (unsigned)((key * (int)ld + li) * 4));
+          }
+      }
+    }
+  };
+  auto block = [&](int cb, int slot) {
+    char *ob = obase + cb * 64;
+    asm volatile("" : "+s"(ob));
     floatx16 o;
 #pragma unroll
     for (int v = 0; v < 16; v++) o[v] = 0.f;
@@ -405,14 +463,8 @@ __global__ __launch_bounds__(256) void enc_attention_wave_kernel(const float *qk
       if (kb < nkb) {
 #pragma unroll
         for (int ks = 0; ks < 2; ks++) {
-          float f[8];
-#pragma unroll
-          for (int e = 0; e < 8; e++) {  // same key order as the probability registers
-            const int key = min(kb * 32 + (2 * ks + (e >> 2)) * 8 + g * 4 + (e & 3), L - 1);
-            f[e] = vbase[(long)key * ld + cb * 32];
-          }
           half8 vh, vl;
-          split8u(f, vh, vl);
+          split8u(fv[slot][kb][ks], vh, vl);
           o = __builtin_amdgcn_mfma_f32_32x32x16_f16(ph[kb][ks], vh, o, 0, 0, 0);
           o = __builtin_amdgcn_mfma_f32_32x32x16_f16(pl[kb][ks], vh, o, 0, 0, 0);
           o = __builtin_amdgcn_mfma_f32_32x32x16_f16(ph[kb][ks], vl, o, 0, 0, 0);
@@ -425,9 +477,26 @@ __global__ __launch_bounds__(256) void enc_attention_wave_kernel(const float *qk
       if (q >= S) continue;
       const float val = (q < L) ? o[v] : 0.f;
       const _Float16 hi = (_Float16)val;
-      const long at_ = (row0 + q) * d + hoff + cb * 32 + li;
-      ctx[at_] = hi;
-      ctx[at_ + ctx_lo_offset] = (_Float16)(val - (float)hi);
+      char *at_ = ob + (unsigned)((q * d + li) * 2);
+      *(_Float16 *)at_ = hi;
+      *((_Float16 *)at_ + ctx_lo_offset) = (_Float16)(val - (float)hi);
+    }
+  };
+  if constexpr (PREFETCH) {
+    static_assert((DH / 32) % 2 == 0, "the two slots alternate over an even number of column blocks");
+    request(0, 0);
+#pragma nounroll
+    for (int cb = 0; cb < DH / 32; cb += 2) {
+      request(cb + 1, 1);
+      block(cb, 0);
+      if (cb + 2 < DH / 32) request(cb + 2, 0);
+      block(cb + 1, 1);
+    }
+  } else {
+#pragma nounroll
+    for (int cb = 0; cb < DH / 32; cb++) {
+      request(cb, 0);
+      block(cb, 0);
     }
   }
 }
