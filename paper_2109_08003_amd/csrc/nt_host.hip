@@ -663,7 +663,9 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
   const float qscale = 1.0f / std::sqrt((float)(d / H));
   m->encoded = false;
   const double Md = (double)M, dd = (double)d, ea = (double)kEncElt, ca = (double)kCrossElt;
-  KT(K_EMBED_SRC, Md * (4 + dd * 10), 2 * Md * dd,
+  // ids in, one fp16 embedding row per token (counted in full: repeated ids hit the caches), the S position rows
+  // once, fp32 rows out
+  KT(K_EMBED_SRC, Md * (4 + dd * 6) + (double)S * dd * 4, 2 * Md * dd,
      nt::launch_embed_src(d_src, d_len, m->len, B, S, d, c.vocab, c.pad_id, m->E, m->pe, m->x, m->flags, s));
   auto gemm_bytes = [&](double rows, double k, double n, double a_elt, double c_elt, bool resid) {
     return rows * k * a_elt + n * k * 2 + rows * n * c_elt + (resid ? rows * n * 4 : 0.0);
