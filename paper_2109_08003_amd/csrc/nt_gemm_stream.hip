@@ -76,7 +76,13 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
       m = m < M ? m : M - 1;
       const float *xr = X + (long)m * lda + lane * NE;
 #pragma unroll
-      for (int j = 0; j < NE; j += 4) *(float4 *)&xv[i][j] = *(const float4 *)(xr + j);
+      for (int j = 0; j < NE; j += 4) {
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        // encoder-sized launches stream their rows and outputs past the L2 (non-temporal), so that the weight
+        // fragments, which every workgroup reads, stay in it
+        const f32x4 t = RB == 2 ? __builtin_nontemporal_load((const f32x4 *)(xr + j)) : *(const f32x4 *)(xr + j);
+        xv[i][j] = t[0], xv[i][j + 1] = t[1], xv[i][j + 2] = t[2], xv[i][j + 3] = t[3];
+      }
     }
     float gam[NE], bet[NE];
 #pragma unroll
@@ -275,10 +281,12 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
     };
     auto put = [&](char *at_, float val) {
       if (C_F32) {
-        *(float *)at_ = val;
+        if (RB == 2) __builtin_nontemporal_store(val, (float *)at_);
+        else *(float *)at_ = val;
       } else {
         const _Float16 hi = (_Float16)val;
-        *(_Float16 *)at_ = hi;
+        if (RB == 2) __builtin_nontemporal_store(hi, (_Float16 *)at_);
+        else *(_Float16 *)at_ = hi;
         if (e.dst_lo_offset) *((_Float16 *)at_ + e.dst_lo_offset) = (_Float16)(val - (float)hi);
       }
     };
