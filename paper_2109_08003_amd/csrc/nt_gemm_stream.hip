@@ -78,8 +78,10 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
 #pragma unroll
       for (int j = 0; j < NE; j += 4) {
         typedef float f32x4 __attribute__((ext_vector_type(4)));
-        // encoder-sized launches stream their rows and outputs past the L2 (non-temporal), so that the weight
-        // fragments, which every workgroup reads, stay in it
+        // encoder-sized launches stream their rows, residuals and fp32 outputs past the L2 (non-temporal), so that
+        // the weight fragments, which every workgroup reads, stay in it.  Only whole-line accesses are marked:
+        // where a line is consumed or produced in pieces (the q/k/v reads and half-line context stores of the encoder
+        // attention), the pieces rely on the cache and the hint cost 7 % of the whole job
         const f32x4 t = RB == 2 ? __builtin_nontemporal_load((const f32x4 *)(xr + j)) : *(const f32x4 *)(xr + j);
         xv[i][j] = t[0], xv[i][j + 1] = t[1], xv[i][j + 2] = t[2], xv[i][j + 3] = t[3];
       }
@@ -150,7 +152,7 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
       int m = m0 + (R % TM);
       m = m < M ? m : M - 1;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + (long)m * lda + lane * 8),
-                                       (__attribute__((address_space(3))) void *)(sh + R * LD), 16, 0, 0);
+                                       (__attribute__((address_space(3))) void *)(sh + R * LD), 16, 0, RB == 2 ? 2 : 0);
     }
   } else {
     constexpr int CPR = K / 8, PER_T = ROWS * CPR / (GS_WAVES * 64);
@@ -285,8 +287,7 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
         else *(float *)at_ = val;
       } else {
         const _Float16 hi = (_Float16)val;
-        if (RB == 2) __builtin_nontemporal_store(hi, (_Float16 *)at_);
-        else *(_Float16 *)at_ = hi;
+        *(_Float16 *)at_ = hi;  // 64 bytes per row and instruction: the other half of the line follows, keep it cached
         if (e.dst_lo_offset) *((_Float16 *)at_ + e.dst_lo_offset) = (_Float16)(val - (float)hi);
       }
     };
@@ -301,7 +302,8 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
 #pragma unroll
         for (int v = 0; v < 16; v++) {
           const int r = (v >> 2) * 8 + (v & 3);
-          res[blk & 1][v] = *(const float *)(rblock + (rlane + (unsigned)(r * e.ldr * 4)));
+          const float *rp = (const float *)(rblock + (rlane + (unsigned)(r * e.ldr * 4)));
+          res[blk & 1][v] = RB == 2 ? __builtin_nontemporal_load(rp) : *rp;
         }
       };
       if (RESID) request(0);

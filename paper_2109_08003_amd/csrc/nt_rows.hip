@@ -86,7 +86,7 @@ __global__ __launch_bounds__(256) void embed_src_kernel(const int32_t *src, cons
     float v[MAX_PER_LANE];
     const int ne = NE;
     NT_FOR_LANE_ELEMS(i) v[i] = sc * (float)e[lane + 64 * i] + p[lane + 64 * i];
-    NT_FOR_LANE_ELEMS(i) o[lane + 64 * i] = v[i];
+    NT_FOR_LANE_ELEMS(i) __builtin_nontemporal_store(v[i], o + lane + 64 * i);  // 134 MB per batch, read once later
   } else {
     for (int i = lane; i < d; i += 64) o[i] = sc * (float)e[i] + p[i];
   }
