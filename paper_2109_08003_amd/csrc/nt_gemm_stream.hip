@@ -11,9 +11,11 @@
 // fragment into one fp32 accumulator.
 //
 // A wave owns strips of 64 output columns (wave, wave + 8, ... of the workgroup's range) and all
-// rows of the tile; the epilogue is the one of the tiled kernel (bias, scale, ReLU, residual, two
+// rows of the tile; the epilogue does what the tiled kernel's does (bias, scale, ReLU, residual, two
 // destinations, optional tail plane).  Here the A fragment is the row operand of the MFMA, so a
-// lane owns an output column and a store instruction covers 128 contiguous bytes per row.
+// lane owns an output column and a store instruction covers 128 contiguous bytes per row.  Tiles
+// inside the matrix take an epilogue without branches, so that the stores of a strip are issued
+// back to back; encoder-sized launches mark their whole-line streams non-temporal.
 //
 // Fragment order of Wp: [strip = n / 64][ks = k / 16][nb = (n % 64) / 32][lane][8 halfs] with
 // lane = n % 32 + 32 * ((k % 16) / 8).
