@@ -145,7 +145,11 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
  *   h_row_steps: optional host array [B], non-increasing, each in [0, n_steps]: row b is only
  *   advanced for its first h_row_steps[b] steps (rows sorted by length finish in order, so
  *   the active rows are always a prefix); entries of d_out beyond that are set to pad_id.
- *   NULL = every row runs n_steps steps.  Results of a row never depend on the other rows.
+ *   NULL = every row runs n_steps steps.  A row's arithmetic never reads another row.  The number of
+ *   active rows does select between kernels whose fp32 summation order differs (a one-round-trip
+ *   kernel for small batches, streaming kernels above), so the same sentence decoded in batches of
+ *   very different size can differ in the last bit of a logit, and therefore in a token where two
+ *   logits tie to within that bit; the EOS-terminated call below fixes the choice by the caps alone.
  * Errors: NT_EINVAL, NT_ESTATE (B differs from the encoded batch), NT_ERANGE (n_steps >
  * max_len, h_row_steps not non-increasing), NT_ENOMEM (B * n_steps beyond the self cache), NT_EHIP.
  */
@@ -223,7 +227,18 @@ int nt_translate_batch_eos(nt_model *m, const int32_t *h_tokens, const int64_t *
                            int64_t *h_out_offsets, int32_t *h_out_len, void *hip_stream);
 
 /*
- * Host-only batch planner used by nt_translate_batch (same passages).  Stable sort by
+ * Number of output ids the two nt_translate_batch calls write for these sentences: the sum of
+ * nt_n_steps(len_i) over the non-empty sentences (the size h_out must have).  Host only.
+ * Errors: NT_EINVAL (null argument, negative N), NT_ERANGE (offsets decrease).
+ */
+int nt_output_slots(const int64_t *h_offsets, int64_t N, int64_t *total);
+
+/*
+ * Host-only batch planner used by nt_translate_batch: the paper's dynamic batching (Sec. 3.1
+ * "Dynamic Batching": as many sentences per batch as a cap on its tokens allows), over sentences
+ * sorted by descending length (Sec. 3.3 "Graph Optimization", memory optimisation) under the two
+ * caps of Sec. 3.3 "Better Decoding Configurations" (sbatch = max_rows sentences, wbatch = budget
+ * tokens, counted padded).  Stable sort by
  * descending length (ties by index); batches are maximal prefixes of the sorted list with
  * rows * longest <= budget and rows <= max_rows (0 = no cap); a sentence longer than the
  * budget forms a batch of its own; empty sentences are placed last and belong to no batch.
@@ -236,17 +251,35 @@ int nt_plan_batches(const int32_t *h_lengths, int64_t N, int64_t budget, int32_t
 
 /* ---- not on the hot path: needed to check parity -------------------------------------- */
 
-/* Copy the encoder output of the last nt_encode as fp32 [B, S, d_model] (pad rows included). */
+/*
+ * Copy the encoder output of the last nt_encode - the final LayerNorm of the encoder stack (Sec. 2.2
+ * "Fast Student Models": the deep encoder whose output every decoder step attends to) - as fp32
+ * [B, S, d_model] (pad rows included).
+ */
 int nt_debug_encoder_out(nt_model *m, float *d_out, void *hip_stream);
 
 /*
- * Teacher-forced decoder logits for the batch left by the last nt_encode: the decoder is fed
+ * Teacher-forced decoder logits for the batch left by the last nt_encode (the decoder layer of
+ * Sec. 2.2 and the output layer without its log-softmax, Sec. 3.3 "Graph Optimization", evaluated
+ * on given target prefixes instead of the greedy search of Sec. 3.3 "Greedy Search"): the decoder is fed
  * d_tgt_in [B, T] (column 0 is normally BOS) instead of its own arg-max and the fp32 logits of
  * every step are written to d_logits [B, T, vocab].  Same kernels as nt_decode_greedy except
  * that the output projection stores its tile instead of reducing it.
  */
 int nt_debug_teacher_forced_logits(nt_model *m, const int32_t *d_tgt_in, int32_t B, int32_t T, float *d_logits,
                                    void *hip_stream);
+
+/*
+ * Testing aids that select numerical paths of the output projection (both default to 0; they act on
+ * every pipeline lane of the model and on the calls that follow):
+ *   nt_debug_set_vocab_tiled(m, 1)    take the LDS-tiled arg-max kernels that other model widths use,
+ *                                     instead of the streaming kernels;
+ *   nt_debug_set_cert_distrust(m, 1)  certify no row in the single-pass arg-max, so that every row
+ *                                     takes the head+tail recompute pass.
+ * Errors: NT_EINVAL (null model, value other than 0 / 1).
+ */
+int nt_debug_set_vocab_tiled(nt_model *m, int on);
+int nt_debug_set_cert_distrust(nt_model *m, int on);
 
 /*
  * Read and clear the sticky device flags (synchronises the stream).  Returns NT_OK, or

@@ -398,9 +398,12 @@ static void dec_step(const ora_model *m, dec_state *s, int32_t y_prev, int32_t t
  *    for a column or row whose values all lie far to one side of zero); codes are round-to-nearest-even, clamped;
  *  - the input is quantised per row (one decoder state) instead of per matrix, so that a sentence's result does
  *    not depend on its batch mates; weights are signed 8-bit codes, activations unsigned 8-bit codes;
- *  - weight statistics and codes are computed in double, in index order; the activation side runs in the
- *    kernel's precision, fp32, one rounding per operation:
+ *  - weight statistics and codes are computed in double, in index order; Eq. 5, 6 state no precision, and a code
+ *    is an integer decided by floating-point arithmetic, so this leg is specified to fp32, one rounding per
+ *    operation in the order written here, which lets any implementation be compared with it bit for bit:
  *        a_scale = (max - min) / 255      a_zero = rint(255 - max / a_scale)      u_k = rint(h_k / a_scale + a_zero)
+ *    (pinned against the same equations evaluated in double: codes and zero point within one step, and on every
+ *    row that straddles zero the zero point needs no clamping);
  *  - logit[v] = a_scale * (b_scale[v] * float(I_v)),  I_v = sum_k (u_k - a_zero) (q_vk - zero_v)  exactly in
  *    integers; the arg-max is taken on t_v = b_scale[v] * float(I_v) in fp32 (a_scale > 0 is common to the row).
  */

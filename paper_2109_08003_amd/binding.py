@@ -18,7 +18,8 @@ EXPORTS = ["nt_param_count", "nt_n_steps", "nt_load_weights", "nt_free", "nt_enc
            "nt_check_device_flags", "nt_device_bytes", "nt_last_error", "nt_debug_timing_enable",
            "nt_debug_timing_count", "nt_debug_timing_name", "nt_debug_timing_read", "nt_pipeline_lanes",
            "nt_pipeline_lane", "nt_lane_stream", "nt_decode_greedy_eos", "nt_translate_batch_eos",
-           "nt_debug_q8_output_layer", "nt_debug_q8_quantize_row"]
+           "nt_debug_q8_output_layer", "nt_debug_q8_quantize_row", "nt_output_slots", "nt_debug_set_vocab_tiled",
+           "nt_debug_set_cert_distrust"]
 
 
 class NtConfig(C.Structure):
@@ -64,6 +65,9 @@ def load_library() -> C.CDLL:
         "nt_debug_q8_quantize_row": (C.c_int, [p, i32, p, p, p]),
         "nt_translate_batch_eos": (C.c_int, [p, p, p, i64, i64, i32, i32, p, p, p, p]),
         "nt_plan_batches": (C.c_int, [p, i64, i64, i32, p, p, C.POINTER(i64)]),
+        "nt_output_slots": (C.c_int, [p, i64, C.POINTER(i64)]),
+        "nt_debug_set_vocab_tiled": (C.c_int, [p, C.c_int]),
+        "nt_debug_set_cert_distrust": (C.c_int, [p, C.c_int]),
         "nt_debug_encoder_out": (C.c_int, [p, p, p]),
         "nt_debug_teacher_forced_logits": (C.c_int, [p, p, i32, i32, p, p]),
         "nt_check_device_flags": (C.c_int, [p, p]),
@@ -130,16 +134,12 @@ def n_steps(length: int) -> int:
     return int(lib().nt_n_steps(int(length)))
 
 
-def _output_slots(offsets) -> int:
-    """Size of the output buffer of the translate calls: nt_n_steps(len) slots per non-empty sentence.  The rule
-    (6 len + 4) div 5 + 2 is nt_n_steps's, applied to the whole array at once (a call per sentence costs more than
-    the translation of a large input set)."""
-    lens = np.diff(offsets)
-    lens = lens[lens > 0]
-    total = int(((6 * lens + 4) // 5 + 2).sum())
-    if lens.size:  # the library's own value, on the longest sentence, guards the vectorised copy of the rule
-        assert (6 * int(lens.max()) + 4) // 5 + 2 == n_steps(int(lens.max()))
-    return total
+def output_slots(offsets) -> int:
+    """Number of output ids the translate calls write for these sentences (nt_output_slots)."""
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    total = C.c_int64(0)
+    _check(lib().nt_output_slots(offsets.ctypes.data_as(C.c_void_p), offsets.size - 1, C.byref(total)))
+    return int(total.value)
 
 
 def plan_batches(lengths, budget: int, max_rows: int = 0):
@@ -257,6 +257,12 @@ class Model:
         _check(lib().nt_debug_teacher_forced_logits(self._h, d_tgt_in.data_ptr(), B, T, d_logits.data_ptr(),
                                                     _stream_ptr(stream)))
 
+    def debug_set_vocab_tiled(self, on: bool):
+        _check(lib().nt_debug_set_vocab_tiled(self._h, int(bool(on))))
+
+    def debug_set_cert_distrust(self, on: bool):
+        _check(lib().nt_debug_set_cert_distrust(self._h, int(bool(on))))
+
     def check_device_flags(self, stream=None):
         _check(lib().nt_check_device_flags(self._h, _stream_ptr(stream)))
 
@@ -287,7 +293,7 @@ class Model:
         tokens = np.ascontiguousarray(tokens, dtype=np.int32)
         offsets = np.ascontiguousarray(offsets, dtype=np.int64)
         N = offsets.size - 1
-        total = _output_slots(offsets) if N > 0 else 0
+        total = output_slots(offsets) if N > 0 else 0
         out = np.empty(max(total, 1), dtype=np.int32)
         oo = np.empty(N + 1, dtype=np.int64)
         _check(lib().nt_translate_batch(self._h, tokens.ctypes.data_as(C.c_void_p), offsets.ctypes.data_as(C.c_void_p),
@@ -301,7 +307,7 @@ class Model:
         tokens = np.ascontiguousarray(tokens, dtype=np.int32)
         offsets = np.ascontiguousarray(offsets, dtype=np.int64)
         N = offsets.size - 1
-        total = _output_slots(offsets) if N > 0 else 0
+        total = output_slots(offsets) if N > 0 else 0
         out = np.empty(max(total, 1), dtype=np.int32)
         oo = np.empty(N + 1, dtype=np.int64)
         ol = np.zeros(max(N, 1), dtype=np.int32)

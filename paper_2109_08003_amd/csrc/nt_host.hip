@@ -168,7 +168,8 @@ struct nt_model {
   int32_t *tok = nullptr, *slot_of_row = nullptr, *cert_list = nullptr;
   unsigned long long *final_key = nullptr, *need_mask = nullptr;
   bool enc_out_valid = false;  // false while the encoder output lives only inside the fused cross projections
-  float w_norm_max = 0.f;                              // max_v ||W_out[v,:]||
+  float w_norm_max = 0.f;                              // max_v ||W_out[v,:]||, or huge while nothing may be certified
+  float w_norm_true = 0.f;                             // the value computed at load
   int32_t *len = nullptr, *flags = nullptr;
   int32_t *d_src = nullptr, *d_len_in = nullptr, *d_out = nullptr;  // staging for nt_translate_batch
   // EOS-terminated decoding: dense row -> batch row maps of two consecutive steps, per-row scratch, caps and output
@@ -301,8 +302,12 @@ int alloc_lane_state(nt_model *m, hipStream_t s) {
     int64_t worst = 0;
     for (int64_t mt = 1; (mt - 1) * 64 < Br; mt++) {
       const int64_t rows = std::min<int64_t>(mt * 64, Br);
-      worst = std::max(worst, rows * nt::vocab_argmax_partials(m->vw, (int)rows, false));
-      worst = std::max(worst, rows * nt::vocab_argmax_partials(m->vw, (int)rows, true));
+      for (int tiled = 0; tiled < 2; tiled++) {  // either family of arg-max kernels may be selected later
+        nt::VocabWeights w = m->vw;
+        w.force_tiled = tiled != 0;
+        worst = std::max(worst, rows * nt::vocab_argmax_partials(w, (int)rows, false));
+        worst = std::max(worst, rows * nt::vocab_argmax_partials(w, (int)rows, true));
+      }
       if (cfg->q8_output) worst = std::max(worst, rows * nt::vocab_q8_partials((int)rows));
     }
     m->pk_elems = worst;
@@ -374,6 +379,33 @@ int64_t nt_param_count(const nt_config *cfg) {
 }
 
 int32_t nt_n_steps(int32_t len) { return (6 * len + 4) / 5 + 2; }
+
+int nt_output_slots(const int64_t *h_offsets, int64_t N, int64_t *total) {
+  if (!h_offsets || !total || N < 0) return fail(NT_EINVAL, "null argument or negative N");
+  int64_t n = 0;
+  for (int64_t i = 0; i < N; i++) {
+    const int64_t L = h_offsets[i + 1] - h_offsets[i];
+    if (L < 0) return fail(NT_ERANGE, "offsets decrease at sentence %lld", (long long)i);
+    if (L > INT32_MAX / 8) return fail(NT_ERANGE, "sentence %lld has %lld tokens", (long long)i, (long long)L);
+    if (L > 0) n += nt_n_steps((int32_t)L);
+  }
+  *total = n;
+  return NT_OK;
+}
+
+int nt_debug_set_vocab_tiled(nt_model *m, int on) {
+  if (!m || (on != 0 && on != 1)) return fail(NT_EINVAL, "null model or value other than 0 / 1");
+  m->vw.force_tiled = on != 0;
+  for (nt_model *ln : m->lanes) ln->vw.force_tiled = on != 0;
+  return NT_OK;
+}
+
+int nt_debug_set_cert_distrust(nt_model *m, int on) {
+  if (!m || (on != 0 && on != 1)) return fail(NT_EINVAL, "null model or value other than 0 / 1");
+  m->w_norm_max = on ? 1e30f : m->w_norm_true;
+  for (nt_model *ln : m->lanes) ln->w_norm_max = m->w_norm_max;
+  return NT_OK;
+}
 
 int64_t nt_device_bytes(const nt_model *m) {
   if (!m) return 0;
@@ -604,10 +636,6 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
   for (auto &f : fixes) *f.slot = m->d_w + f.off;
   if (cfg->tie_output) m->Wout = m->E;
   m->vw.Wt = m->Wout; m->vw.Wp = m->Wout_frag; m->vw.N = V; m->vw.K = d;
-  {
-    const char *f = getenv("NT_VOCAB_TILED");  // testing aid: take the tiled arg-max kernels
-    m->vw.force_tiled = f && f[0] == '1';
-  }
   {  // largest row norm of the output matrix, rounded up (bound used by the certified arg-max)
     const _Float16 *Wo = (const _Float16 *)h_blob_fp16 + (cfg->tie_output ? 0 : (int64_t)V * d);
     double mx = 0.0;
@@ -616,9 +644,7 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
       for (int k = 0; k < d; k++) { const double w = (double)(float)Wo[(int64_t)v * d + k]; q += w * w; }
       mx = std::max(mx, q);
     }
-    m->w_norm_max = (float)(std::sqrt(mx) * 1.0001);
-    const char *f = getenv("NT_CERT_DISTRUST");  // testing aid: certify nothing, so every row takes the recompute pass
-    if (f && f[0] == '1') m->w_norm_max = 1e30f;
+    m->w_norm_max = m->w_norm_true = (float)(std::sqrt(mx) * 1.0001);
   }
 
   rc = alloc_lane_state(m, s);
@@ -633,6 +659,7 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
       ln->d_arena = nullptr;
       for (auto &st : ln->stage) st = nt_model::Staging();
       ln->lane_stream = nullptr; ln->lane_start = nullptr;
+      ln->h_progress = nullptr; ln->d_progress = nullptr; ln->decode_seq = 0;  // lane 0's: never freed through a clone
       ln->cross.clear(); ln->self_kv.clear();
       m->lanes.push_back(ln);
       rc = alloc_lane_state(ln, s);

@@ -157,7 +157,7 @@ def test_c0_translate_batch_order_and_determinism(c0, oracle, nt):
     assert bad <= 1
 
 
-def test_papers_batch_caps_give_the_same_translations(nt):
+def test_papers_batch_caps_give_the_same_translations(nt, oracle):
     """sbatch / wbatch = 3,072 / 64,000 (Sec. 3.3 "Better Decoding Configurations"): a cap on the sentences per
     batch changes the batches, not the translations (a sentence never depends on its batch mates, up to the
     kernel a batch size selects: compare as sets of near-identical outputs)."""
@@ -172,8 +172,17 @@ def test_papers_batch_caps_give_the_same_translations(nt):
     capped, co = gm.translate_batch(tokens, offsets, token_budget=64000, max_rows=3072)
     free, fo = gm.translate_batch(tokens, offsets, token_budget=64000)
     assert np.array_equal(co, fo)
-    same = sum(np.array_equal(capped[co[i]:co[i + 1]], free[fo[i]:fo[i + 1]]) for i in range(len(lens)))
-    assert same >= 0.999 * len(lens), same
+    differ = [i for i in range(len(lens)) if not np.array_equal(capped[co[i]:co[i + 1]], free[fo[i]:fo[i + 1]])]
+    assert len(differ) <= 0.001 * len(lens), len(differ)
+    # the batch size selects between decoder kernels whose fp32 summation order differs: where the two runs part,
+    # the oracle's logits of the two tokens must be a near-tie
+    om = oracle.Model(cfg, blob)
+    for i in differ:
+        a, b = capped[co[i]:co[i + 1]], free[fo[i]:fo[i + 1]]
+        t = int(np.nonzero(a != b)[0][0])
+        s = tokens[offsets[i]:offsets[i + 1]]
+        logits = om.teacher_forced(s, np.concatenate([[cfg["bos_id"]], a[:t]]).astype(np.int32))[t]
+        assert abs(float(logits[a[t]] - logits[b[t]])) < 1e-2
 
 
 def test_lanes_driven_by_the_caller_on_their_own_streams(torch_cuda, nt):
@@ -292,58 +301,121 @@ def test_c1_full_workload_sampled_against_oracle(nt, oracle):
     assert frac >= 0.99
 
 
-def test_tiled_argmax_kernels_agree_with_streaming_kernels(nt, monkeypatch):
-    """Model widths other than 256 / 512 take the tiled arg-max kernels; NT_VOCAB_TILED=1 selects them for
+def test_c1_encoder_and_logit_tolerances_at_benchmark_row_counts(nt, oracle, torch_cuda):
+    """Encoder outputs and teacher-forced logits of the vanilla student at the kernel paths the benchmark takes:
+    one batch of 2,048 rows of 20-26 tokens (51,000 encoder rows: 64-row streaming tiles with the fused LayerNorm,
+    the register-resident encoder attention, plane-pair decoder projections on 2,048 rows), and one batch whose
+    longest sentence has more than 128 tokens (the tiled encoder attention).  A seeded subset of rows, with the
+    first and last row and rows either side of tile boundaries, is compared with the oracle."""
+    torch = torch_cuda
+    cfg = nt_synth.model_config("C1")
+    blob = nt_synth.make_weights(cfg, seed=0)
+    gm, om = nt.Model(cfg, blob, max_batch_tokens=65536), oracle.Model(cfg, blob)
+    tokens, offsets = nt_synth.workload("C2", 30000)
+    sents = split(tokens, offsets)
+    rng = np.random.default_rng(321)
+    mid = [x for x in sents if 20 <= len(x) <= 26][:2048]
+    long_ = [x for x in sents if len(x) > 128][:3] + [rng.integers(4, cfg["vocab"], size=n).astype(np.int32)
+                                                      for n in (200, 171, 150, 140, 133, 129)]
+    long_ += [x for x in sents if 90 <= len(x) <= 128][:16]
+    assert len(mid) == 2048
+    for src, rows, T in ((sort_desc(mid), np.unique(np.concatenate([[0, 31, 32, 63, 64, 127, 128, 2047],
+                                                                    rng.choice(2048, size=56, replace=False)])), 3),
+                         (sort_desc(long_), np.arange(0, len(long_), 3), 3)):
+        ids, lens = pad(src, cfg["pad_id"])
+        B, S = ids.shape
+        gm.encode(torch.from_numpy(ids).cuda(), torch.from_numpy(lens).cuda())
+        enc = torch.empty(B, S, cfg["d_model"], dtype=torch.float32, device="cuda")
+        gm.debug_encoder_out(enc)
+        tgt = rng.integers(4, cfg["vocab"], size=(B, T)).astype(np.int32)
+        tgt[:, 0] = cfg["bos_id"]
+        logits = torch.empty(B, T, cfg["vocab"], dtype=torch.float32, device="cuda")
+        gm.debug_teacher_forced_logits(torch.from_numpy(tgt).cuda(), logits)
+        gm.check_device_flags()
+        idx = torch.from_numpy(rows.astype(np.int64)).cuda()
+        enc = enc[idx].cpu().numpy().astype(np.float64)
+        logits = logits[idx].cpu().numpy().astype(np.float64)
+        worst_enc = worst_abs = worst_rel = 0.0
+        for k, i in enumerate(rows):
+            x = src[i]
+            worst_enc = max(worst_enc, rel_l2(enc[k, : len(x)], om.encode(x)))
+            want = om.teacher_forced(x, tgt[i])
+            worst_abs = max(worst_abs, float(np.abs(logits[k] - want).max()))
+            worst_rel = max(worst_rel, rel_l2(logits[k], want))
+        print(f"C1 student, batch {B} x {S}: {len(rows)} rows against the oracle: encoder rel-L2 {worst_enc:.2e}, "
+              f"logits max-abs {worst_abs:.2e}, rel-L2 {worst_rel:.2e}")
+        assert worst_enc <= 2e-3 and worst_abs <= 2e-2 and worst_rel <= 2e-3
+
+
+def test_tiled_argmax_kernels_agree_with_streaming_kernels(nt):
+    """Model widths other than 256 / 512 take the tiled arg-max kernels; nt_debug_set_vocab_tiled selects them for
     any width.  Both compute the same head+tail logits (in a different summation order), with batches
     above and below the row count from which the certified single-pass variant is used."""
     cfg = nt_synth.model_config("C1")
     blob = nt_synth.make_weights(cfg, seed=0)
     tokens, offsets = nt_synth.workload("C1", 1024)
     ref, ro = nt.Model(cfg, blob, max_batch_tokens=16384).translate_batch(tokens, offsets, token_budget=16384)
-    monkeypatch.setenv("NT_VOCAB_TILED", "1")
-    out, oo = nt.Model(cfg, blob, max_batch_tokens=16384).translate_batch(tokens, offsets, token_budget=16384)
+    gm = nt.Model(cfg, blob, max_batch_tokens=16384)
+    gm.debug_set_vocab_tiled(True)
+    out, oo = gm.translate_batch(tokens, offsets, token_budget=16384)
     assert np.array_equal(ro, oo)
     same = sum(np.array_equal(a, b) for a, b in zip(split(ref, ro), split(out, oo)))
     print(f"tiled vs streaming arg-max: {same}/1024 sentences identical")
     assert same >= 1014   # summation order differs, so an exact tie of fp32 logits may fall the other way
 
 
-def test_certified_argmax_equals_full_recompute(nt, monkeypatch):
+def test_certified_argmax_equals_full_recompute(nt):
     """The single-pass arg-max certifies a row only if the head-only winner provably wins the head+tail logits
-    too, so its tokens must be exactly those of recomputing every row with both planes.  NT_CERT_DISTRUST=1
-    makes the bound infinite: every row of every step with >= 512 active rows goes through the gathered
+    too, so its tokens must be exactly those of recomputing every row with both planes.
+    nt_debug_set_cert_distrust makes the bound infinite: every row of every step with >= 512 active rows goes through the gathered
     recompute kernel (thousands of rows: several list chunks and several tiles per workgroup)."""
     cfg = nt_synth.model_config("C1")
     blob = nt_synth.make_weights(cfg, seed=0)
     tokens, offsets = nt_synth.workload("C2", 6000)
-    ref, ro = nt.Model(cfg, blob, max_batch_tokens=65536).translate_batch(tokens, offsets, token_budget=65536)
-    monkeypatch.setenv("NT_CERT_DISTRUST", "1")
-    out, oo = nt.Model(cfg, blob, max_batch_tokens=65536).translate_batch(tokens, offsets, token_budget=65536)
+    gm = nt.Model(cfg, blob, max_batch_tokens=65536)
+    ref, ro = gm.translate_batch(tokens, offsets, token_budget=65536)
+    gm.debug_set_cert_distrust(True)
+    out, oo = gm.translate_batch(tokens, offsets, token_budget=65536)
     assert np.array_equal(ro, oo)
     assert np.array_equal(ref, out)
 
 
 # ------------------------------------------------------------------------------ restored components (C3) and teacher shape (C4)
-def _check_workload_sample(nt, oracle, name, n_sent, budget, tol_frac, **overrides):
+def _check_workload_sample(nt, oracle, name, n_sent, budget, n_audit=None, **overrides):
+    """Translate n_sent sentences of a workload at a token budget and audit a seeded sample of n_audit of them (all,
+    if None) plus the longest against the oracle: >= 99 % identical and every mismatch a near-tie below 1e-2; a
+    sample too small to resolve 1 % may hold one such near-tie at most."""
     cfg = nt_synth.model_config(name, **overrides)
     blob = nt_synth.make_weights(cfg, seed=0, random_affine=True)     # exercises the LayerNorm affine path too
     tokens, offsets = nt_synth.workload(name, n_sent)
     gm = nt.Model(cfg, blob, max_batch_tokens=budget)
     out, oo = gm.translate_batch(tokens, offsets, token_budget=budget)
+    lens = np.diff(offsets)
+    assert np.array_equal(np.diff(oo), [nt.n_steps(int(l)) for l in lens])
+    assert out.min() >= 0 and out.max() < cfg["vocab"]
     om = oracle.Model(cfg, blob)
-    ref, ro, _ = om.translate(tokens, offsets)
-    sents, gpu, ora = split(tokens, offsets), split(out, oo), split(ref, ro)
-    bad, worst = audit_mismatches(om, sents, gpu, ora, cfg)
-    frac = 1.0 - bad / n_sent
-    print(f"{name} {overrides}: {n_sent - bad}/{n_sent} sentences identical ({100 * frac:.2f} %), worst gap {worst:.2e}")
-    assert frac >= tol_frac
-    return gm, om, cfg, sents
+    if n_audit is None or n_audit >= n_sent:
+        sample = np.arange(n_sent)
+    else:
+        rng = np.random.default_rng(1000 + n_sent)
+        sample = np.unique(np.concatenate([rng.choice(n_sent, size=n_audit, replace=False), np.argsort(-lens)[:2]]))
+    sents = [tokens[offsets[i]:offsets[i + 1]] for i in sample]
+    sub_off = np.concatenate([[0], np.cumsum([len(x) for x in sents])])
+    ref, ro, _ = om.translate(np.concatenate(sents), sub_off)
+    bad, worst = audit_mismatches(om, sents, [out[oo[i]:oo[i + 1]] for i in sample], split(ref, ro), cfg)
+    frac = 1.0 - bad / len(sample)
+    print(f"{name} {overrides}: {len(sample) - bad}/{len(sample)} audited sentences of {n_sent} identical "
+          f"({100 * frac:.2f} %), worst gap {worst:.2e}")
+    assert bad <= max(1, int(0.01 * len(sample)))
+    return gm, om, cfg, split(tokens, offsets)
 
 
 def test_c3_multihead_ffn_student(nt, oracle, torch_cuda):
     """Ablation student: 8 heads of width 64 and a ReLU FFN of 2,048 in every layer."""
     torch = torch_cuda
-    gm, om, cfg, sents = _check_workload_sample(nt, oracle, "C3", 96, 4096, 0.97)
+    # the configured workload: 16,384 sentences at the 16,384-token budget (batches of hundreds of rows: streaming
+    # projections with 8 heads and FFN, certified arg-max), 300 of them audited
+    gm, om, cfg, sents = _check_workload_sample(nt, oracle, "C3", 16384, 16384, 300)
     # encoder outputs and teacher-forced logits on one small batch
     src = sort_desc(sents[:6])
     ids, lens = pad(src, cfg["pad_id"])
@@ -364,14 +436,15 @@ def test_c3_multihead_ffn_student(nt, oracle, torch_cuda):
 
 
 def test_c4_deep_teacher_shape_with_relative_positions(nt, oracle):
-    """30-layer encoder, 6-layer decoder, 8 heads, FFN, relative position keys with clip 8."""
-    _check_workload_sample(nt, oracle, "C4", 48, 2048, 0.95)
+    """30-layer encoder, 6-layer decoder, 8 heads, FFN, relative position keys with clip 8: the configured 2,048
+    sentences at a 8,192-token budget, 100 of them audited."""
+    _check_workload_sample(nt, oracle, "C4", 2048, 8192, 100)
 
 
 def test_relative_positions_small(nt, oracle):
     """Clip distance smaller than most sentences, 2 decoder layers, single wide head with relative keys."""
-    _check_workload_sample(nt, oracle, "C0", 8, 512, 0.87, rpr_clip=3, n_dec=2)
-    _check_workload_sample(nt, oracle, "C0", 8, 512, 0.87, rpr_clip=16, n_heads=4, d_ffn=256)
+    _check_workload_sample(nt, oracle, "C0", 8, 512, rpr_clip=3, n_dec=2)
+    _check_workload_sample(nt, oracle, "C0", 8, 512, rpr_clip=16, n_heads=4, d_ffn=256)
 
 
 # ------------------------------------------------------------------------------ L1-norm layer normalisation
@@ -399,17 +472,17 @@ def test_l1_norm_layer_normalisation(nt, oracle, torch_cuda):
     """Every layer normalisation in its L1-norm form (Sec. 3.1): the separate kernel, the one fused into the
     small-batch decoder projections and the one fused into the fill of the streaming projections."""
     # a handful of rows: one-round-trip decoder kernels, LayerNorm in their prologue
-    gm, om, cfg, sents = _check_workload_sample(nt, oracle, "C0", 8, 512, 0.87, ln_l1=1)
+    gm, om, cfg, sents = _check_workload_sample(nt, oracle, "C0", 8, 512, ln_l1=1)
     _check_encoder_and_logits(torch_cuda, gm, om, cfg, sents, 5, 71)
     # the L1 model is another model: the vanilla oracle must not accept these encoder outputs
     blob = nt_synth.make_weights(cfg, seed=0, random_affine=True)
     vanilla = oracle.Model(dict(cfg, ln_l1=0), blob)
     assert rel_l2(om.encode(sents[0]), vanilla.encode(sents[0])) > 1e-2
     # hundreds of rows per batch: streaming projections with the normalisation in their fill, certified arg-max
-    gm, om, cfg, sents = _check_workload_sample(nt, oracle, "C1", 700, 16384, 0.99, ln_l1=1)
+    gm, om, cfg, sents = _check_workload_sample(nt, oracle, "C1", 700, 16384, ln_l1=1)
     _check_encoder_and_logits(torch_cuda, gm, om, cfg, [s[:30] for s in sents[:150]][::6], 4, 72)
     # FFN blocks (their own normalisation) and 8 heads
-    _check_workload_sample(nt, oracle, "C3", 64, 4096, 0.97, ln_l1=1)
+    _check_workload_sample(nt, oracle, "C3", 2000, 16384, 150, ln_l1=1)
 
 
 # ------------------------------------------------------------------------------ EOS-terminated greedy decoding
@@ -592,8 +665,10 @@ def test_q8_greedy_against_oracle(nt, oracle):
     frac = 1.0 - bad / len(sample)
     print(f"q8 greedy: {len(sample) - bad}/{len(sample)} sampled sentences identical ({100 * frac:.2f} %), "
           f"gaps of the mismatches: {sorted(round(x, 4) for x in gaps)}")
-    assert all(0 <= x < 5e-2 for x in gaps)
-    assert frac >= 0.80
+    # tolerance: a relative 1e-4 between the two pipelines' states flips the arg-max of a few steps in a thousand,
+    # always between 8-bit logits closer than 1e-2 (pinned on the CPU: test_q8_argmax_sensitivity_...)
+    assert all(0 <= x < 1e-2 for x in gaps)
+    assert frac >= 0.90
 
 
 def test_eos_edge_cases(nt, oracle):
@@ -649,7 +724,7 @@ def test_all_options_together(nt, oracle):
         gaps.append(float(logits[o[t]] - logits[g[t]]))
     print(f"all options: {len(sample) - bad}/{len(sample)} sampled sentences identical, gaps {sorted(round(x, 4) for x in gaps)}, "
           f"{100 * ol.sum() / np.diff(oo).sum():.1f} % of the capped tokens emitted")
-    assert all(0 <= x < 5e-2 for x in gaps) and bad <= 0.2 * len(sample)
+    assert all(0 <= x < 1e-2 for x in gaps) and bad <= 0.15 * len(sample)   # the 8-bit model: up to one sentence in ten (CPU pin), plus sampling noise on 90
 
 
 # ------------------------------------------------------------------------------ C5 (shape of the submitted student)

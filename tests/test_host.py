@@ -39,6 +39,20 @@ def test_n_steps_and_param_count():
         nt_synth.model_config("C1", tie_output=1))
 
 
+def test_output_slots():
+    """nt_output_slots against the step rule written out with exact fractions; empty sentences take no slot."""
+    rng = np.random.default_rng(3)
+    lens = rng.integers(0, 200, size=500)
+    lens[:5] = 0
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    want = sum(math.ceil(Fraction(12, 10) * int(n)) + 2 for n in lens if n > 0)
+    assert nt.binding.output_slots(offsets) == want
+    assert nt.binding.output_slots(np.zeros(1, np.int64)) == 0
+    with pytest.raises(nt.NtError) as e:
+        nt.binding.output_slots(np.array([0, 5, 3], np.int64))
+    assert e.value.code == -6
+
+
 def check_plan(lengths, budget, max_rows):
     lengths = np.asarray(lengths, dtype=np.int32)
     order, starts = nt.plan_batches(lengths, budget, max_rows)
