@@ -169,6 +169,21 @@ int nt_debug_q8_output_layer(nt_model *m, const float *d_h, int32_t R, int32_t *
                              void *hip_stream);
 
 /*
+ * nt_debug_q8_output_layer for callers that cannot allocate device memory or let a library do so (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid it): same arguments and results, but
+ * the layer's scratch (activation codes, per-row constants, arg-max partial keys) is a fixed array inside
+ * the library's code object, NT_STATIC_MAX_ROWS rows of at most 512 columns (0.8 MiB per GPU, held until
+ * the process ends), instead of the model's arena.  The call uses no memory of the model's arena besides
+ * the weights, allocates nothing and only enqueues kernels on hip_stream.  Every call on a GPU shares
+ * that GPU's array: calls that overlap on one GPU (two streams, two threads, two models) race; calls in
+ * stream order do not.  Errors: NT_ERANGE if R is outside [1, NT_STATIC_MAX_ROWS]; otherwise as
+ * nt_debug_q8_output_layer.
+ */
+#define NT_STATIC_MAX_ROWS 1024
+int nt_q8_output_layer_static(nt_model *m, const float *d_h, int32_t R, int32_t *d_argmax, float *d_logits,
+                              void *hip_stream);
+
+/*
  * The weight side of the 8-bit output layer for one vocabulary entry, as nt_load_weights applies it to every row
  * of the output matrix (Eq. 3, 4): h_w_fp16 [K] fp16 host -> h_codes [K] signed 8-bit, *h_scale, *h_zero.  Runs on
  * the host; needs no model and no GPU.

@@ -19,7 +19,7 @@ EXPORTS = ["nt_param_count", "nt_n_steps", "nt_load_weights", "nt_free", "nt_enc
            "nt_debug_timing_count", "nt_debug_timing_name", "nt_debug_timing_read", "nt_pipeline_lanes",
            "nt_pipeline_lane", "nt_lane_stream", "nt_decode_greedy_eos", "nt_translate_batch_eos",
            "nt_debug_q8_output_layer", "nt_debug_q8_quantize_row", "nt_output_slots", "nt_debug_set_vocab_tiled",
-           "nt_debug_set_cert_distrust"]
+           "nt_debug_set_cert_distrust", "nt_q8_output_layer_static"]
 
 
 class NtConfig(C.Structure):
@@ -63,6 +63,7 @@ def load_library() -> C.CDLL:
         "nt_decode_greedy_eos": (C.c_int, [p, i32, i32, p, i32, p, p, p]),
         "nt_debug_q8_output_layer": (C.c_int, [p, p, i32, p, p, p]),
         "nt_debug_q8_quantize_row": (C.c_int, [p, i32, p, p, p]),
+        "nt_q8_output_layer_static": (C.c_int, [p, p, i32, p, p, p]),
         "nt_translate_batch_eos": (C.c_int, [p, p, p, i64, i64, i32, i32, p, p, p, p]),
         "nt_plan_batches": (C.c_int, [p, i64, i64, i32, p, p, C.POINTER(i64)]),
         "nt_output_slots": (C.c_int, [p, i64, C.POINTER(i64)]),
@@ -247,6 +248,13 @@ class Model:
         _check(lib().nt_debug_q8_output_layer(self._h, d_h.data_ptr(), d_h.shape[0],
                                               d_argmax.data_ptr() if d_argmax is not None else None,
                                               d_logits.data_ptr() if d_logits is not None else None, _stream_ptr(stream)))
+
+    def q8_output_layer_static(self, d_h, d_argmax=None, d_logits=None, stream=None):
+        """debug_q8_output_layer through the entry point that allocates nothing (at most NT_STATIC_MAX_ROWS rows)."""
+        assert d_h.is_cuda and d_h.is_contiguous()
+        _check(lib().nt_q8_output_layer_static(self._h, d_h.data_ptr(), d_h.shape[0],
+                                               d_argmax.data_ptr() if d_argmax is not None else None,
+                                               d_logits.data_ptr() if d_logits is not None else None, _stream_ptr(stream)))
 
     def debug_encoder_out(self, d_out, stream=None):
         _check(lib().nt_debug_encoder_out(self._h, d_out.data_ptr(), _stream_ptr(stream)))

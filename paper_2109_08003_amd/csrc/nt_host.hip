@@ -18,7 +18,20 @@
 #include "../../include/nt.h"
 #include "nt_kernels.h"
 
+// Scratch of nt_q8_output_layer_static: activation codes, per-row constants and arg-max partial keys for at most
+// NT_STATIC_MAX_ROWS rows of width <= 512.  It lives in the code object, so the entry point never allocates; every GPU
+// the library runs on holds its own copy until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress: kernels get the device address kept in g_static_scratch[device].
+constexpr size_t kStaticCodes = (size_t)NT_STATIC_MAX_ROWS * 512;           // int8 [rows, d]
+constexpr size_t kStaticRowWords = (size_t)NT_STATIC_MAX_ROWS * 4;          // fp32 / int32 [rows], three of them
+constexpr size_t kStaticKeys = (size_t)32768 * 8;                           // rows x partials <= 32768 for rows <= 1024
+constexpr size_t kStaticBytes = kStaticCodes + 3 * kStaticRowWords + kStaticKeys;
+static __device__ __align__(256) unsigned char nt_static_scratch[kStaticBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void *g_static_scratch[kMaxDevices] = {};  // device address of nt_static_scratch on each device, set on first use
 
 thread_local std::string g_err;
 
@@ -38,6 +51,21 @@ int fail(int code, const char *fmt, ...) {
     hipError_t _e = (expr);                                                                \
     if (_e != hipSuccess) return fail(NT_EHIP, "%s: %s", #expr, hipGetErrorString(_e));    \
   } while (0)
+
+// device address of this device's copy of the static scratch (looked up once per device; allocates nothing)
+int static_scratch_for_current_device(unsigned char **out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(NT_EHIP, "device ordinal %d out of range", dev);
+  void *p = __atomic_load_n(&g_static_scratch[dev], __ATOMIC_ACQUIRE);
+  if (!p) {
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(nt_static_scratch)));
+    if (!p) return fail(NT_EHIP, "hipGetSymbolAddress returned a null address");
+    __atomic_store_n(&g_static_scratch[dev], p, __ATOMIC_RELEASE);
+  }
+  *out = (unsigned char *)p;
+  return NT_OK;
+}
 
 // Precision plan.  The greedy arg-max is decided by logit gaps that are often below 1e-2, so
 // activations are kept at fp32 in HBM and enter the fp16 MFMA units split into head + tail.
@@ -647,6 +675,11 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
     m->w_norm_max = m->w_norm_true = (float)(std::sqrt(mx) * 1.0001);
   }
 
+  {  // the static scratch of nt_q8_output_layer_static: find its address on this device now, so that the entry
+     // point itself has nothing left to set up
+    unsigned char *unused = nullptr;
+    if ((rc = static_scratch_for_current_device(&unused))) return rc;
+  }
   rc = alloc_lane_state(m, s);
   if (rc) return rc;
   {  // extra pipeline lanes
@@ -1112,6 +1145,36 @@ int nt_debug_q8_output_layer(nt_model *m, const float *d_h, int32_t R, int32_t *
     nt::StepBeginArgs a{};  // only its first half runs: the partial keys of "step 0" are reduced into d_argmax
     a.t = 1; a.rows_prev = R; a.rows_now = 0; a.d = d; a.vocab = V; a.bos_id = m->c.bos_id; a.pad_id = m->c.pad_id;
     a.pk = m->pk; a.n_partials = nt::vocab_q8_partials(R); a.out = d_argmax; a.out_ld = 1; a.flags = m->flags;
+    HIP_TRY(nt::launch_step_begin(a, s));
+  }
+  return NT_OK;
+}
+
+int nt_q8_output_layer_static(nt_model *m, const float *d_h, int32_t R, int32_t *d_argmax, float *d_logits,
+                              void *hip_stream) {
+  if (!m || !d_h) return fail(NT_EINVAL, "null argument");
+  if (!m->c.q8_output) return fail(NT_ESTATE, "the model was loaded without the 8-bit output layer");
+  if (R < 1 || R > NT_STATIC_MAX_ROWS) return fail(NT_ERANGE, "R = %d outside [1, NT_STATIC_MAX_ROWS = %d]", R, NT_STATIC_MAX_ROWS);
+  const int d = m->c.d_model, V = m->c.vocab;
+  const int np_ = nt::vocab_q8_partials(R);
+  if (d > 512 || (size_t)R * np_ * 8 > kStaticKeys) return fail(NT_ERANGE, "shape exceeds the static scratch");
+  unsigned char *base = nullptr;
+  int rc = static_scratch_for_current_device(&base);
+  if (rc) return rc;
+  int8_t *codes = (int8_t *)base;
+  float *scale = (float *)(base + kStaticCodes);
+  int32_t *c_row = (int32_t *)(base + kStaticCodes + kStaticRowWords);
+  int32_t *sa_row = (int32_t *)(base + kStaticCodes + 2 * kStaticRowWords);
+  unsigned long long *pk = (unsigned long long *)(base + kStaticCodes + 3 * kStaticRowWords);
+  hipStream_t s = as_stream(hip_stream);
+  // every word the kernels below read from the scratch is written by the kernel before it: nothing needs clearing
+  HIP_TRY(nt::launch_q8_rows(d_h, R, d, nullptr, nullptr, ln_eps_of(m->c), codes, scale, c_row, sa_row, s));
+  if (d_logits) HIP_TRY(nt::launch_q8_logits(codes, scale, c_row, R, m->Wq8, m->q8_consts, V, d, d_logits, V, s));
+  if (d_argmax) {
+    HIP_TRY(nt::launch_vocab_q8_argmax(codes, c_row, sa_row, R, m->Wq8, m->q8_consts, V, d, pk, s));
+    nt::StepBeginArgs a{};  // only its first half runs: the partial keys are reduced into d_argmax
+    a.t = 1; a.rows_prev = R; a.rows_now = 0; a.d = d; a.vocab = V; a.bos_id = m->c.bos_id; a.pad_id = m->c.pad_id;
+    a.pk = pk; a.n_partials = np_; a.out = d_argmax; a.out_ld = 1; a.flags = m->flags;
     HIP_TRY(nt::launch_step_begin(a, s));
   }
   return NT_OK;
