@@ -85,8 +85,12 @@ constexpr size_t kEncElt = kEncF32 ? 4 : 2, kCrossElt = kCrossF32 ? 4 : 2;
 
 // Launch `call`; when timing of family `id` is on, bracket it with two events on the stream and
 // note the algorithmic bytes and flops of this launch.
+#ifndef NT_ABLATE_MASK
+#define NT_ABLATE_MASK 0ull  /* measurement builds only: kernel families whose launches are skipped (wrong results) */
+#endif
 #define KT(id, nbytes, nflops, call)                                              \
   do {                                                                            \
+    if ((NT_ABLATE_MASK >> (id)) & 1ull) break;                                   \
     if (m->timing.mask & (1ull << (id))) {                                        \
       hipEvent_t _e0 = m->timing.get(), _e1 = m->timing.get();                    \
       if (!_e0 || !_e1) return fail(NT_EHIP, "hipEventCreate failed");            \
@@ -133,12 +137,12 @@ struct DecLayer {
 enum KernelId {
   K_EMBED_SRC, K_LN_ENC, K_GEMM_ENC_QKV, K_ATTN_ENC, K_GEMM_ENC_O, K_GEMM_ENC_FFN, K_GEMM_CROSS_KV,
   K_STEP_BEGIN, K_LN_DEC, K_GEMM_DEC_QKV, K_ATTN_DEC_SELF, K_GEMM_DEC_O, K_GEMM_DEC_Q, K_ATTN_DEC_CROSS,
-  K_GEMM_DEC_FFN, K_VOCAB_ARGMAX, K_GEMM_LOGITS, K_COUNT
+  K_GEMM_DEC_FFN, K_VOCAB_ARGMAX, K_GEMM_LOGITS, K_DEC_O_LN_PROJ, K_DEC_O_LN_OUT, K_COUNT
 };
 const char *const kKernelNames[K_COUNT] = {
   "embed_src", "layer_norm_enc", "gemm_enc_qkv", "attention_enc", "gemm_enc_o", "gemm_enc_ffn", "gemm_cross_kv",
   "step_begin", "layer_norm_dec", "gemm_dec_qkv", "attn_decode_self", "gemm_dec_o", "gemm_dec_q", "attn_decode_cross",
-  "gemm_dec_ffn", "vocab_argmax", "gemm_logits"};
+  "gemm_dec_ffn", "vocab_argmax", "gemm_logits", "dec_o_ln_proj", "dec_o_ln_out"};
 
 struct Timing {
   uint64_t mask = 0;  // bit per KernelId; 0 = off
@@ -377,7 +381,7 @@ int alloc_lane_state(nt_model *m, hipStream_t s) {
   m->kv_new = at<float>(A, o_kvn);
   m->q8_codes = at<int8_t>(A, o_q8c); m->q8_scale = at<float>(A, o_q8s); m->q8_c = at<int32_t>(A, o_q8z);
   m->q8_sa = at<int32_t>(A, o_q8a);
-  HIP_TRY(nt::launch_fill_i32(m->flags, 16, 0, s));
+  HIP_TRY(hipMemsetAsync(m->d_arena, 0, m->arena_bytes, s));  // load time only: no kernel ever reads an undefined word
   for (auto &st : m->stage) {
     if (hipHostMalloc((void **)&st.h_src, (size_t)Mt * 4) != hipSuccess || hipHostMalloc((void **)&st.h_len, (size_t)Br * 4) != hipSuccess ||
         hipHostMalloc((void **)&st.h_out, (size_t)m->self_positions * 4) != hipSuccess ||
@@ -868,6 +872,13 @@ int decode_step(nt_model *m, DecodeCursor &cu, hipStream_t s) {
     if (rows_prev == 0) { cu.finished = true; return NT_OK; }
     const int partials_prev = cu.partials_prev;
     const bool prev_cert = cu.prev_cert;
+    // Above the row count of the one-round-trip kernels, and for the model widths the streaming kernels support, the
+    // step runs as fused row-tile kernels: step start + LayerNorm + Q|K|V, output projection + LayerNorm + next
+    // projection, output projection + final LayerNorm.  Like the choice between the two projection kernels, this must
+    // not depend on what the host happened to read of the device's progress: the EOS mode decides by the caps alone.
+    const bool fused = nt::dec_fused_supported(d) && (eos ? rows_at(cu, t) : rows_now) > kSkinnyMaxRows &&
+                       m->dec[0].self.Wqkv_p != nullptr;
+    const bool fused_start = fused && rows_now > 0;
     // the EOS mode keeps the rows still decoding as a dense prefix: origin maps a dense row to its batch row
     int32_t *origin = eos ? m->origin[t & 1] : nullptr;
     if (eos) {
@@ -878,10 +889,13 @@ int decode_step(nt_model *m, DecodeCursor &cu, hipStream_t s) {
       a.out_len = cu.d_out_len; a.cap = m->d_cap; a.origin_prev = m->origin[(t + 1) & 1]; a.origin = origin; a.y = m->eos_y;
       a.tok_in = m->eos_tok; a.live = m->flags + 9; a.progress = m->d_progress;
       a.progress_tag = cu.tag; a.E = m->E; a.pe = m->pe; a.z = m->z;
-      KT(K_STEP_BEGIN, rows_prev * (partials_prev * 8.0 + 24) + rows_now * dd * 6, rows_now * dd * 2,
-         nt::launch_eos_step_begin(a, s));
-    } else {
-      nt::StepBeginArgs a{};
+      a.skip_embed = fused_start ? 1 : 0;  // the embedding then happens inside the first projection
+      KT(K_STEP_BEGIN, rows_prev * (partials_prev * 8.0 + 24) + (fused_start ? 0.0 : rows_now * dd * 6),
+         fused_start ? 0.0 : rows_now * dd * 2, nt::launch_eos_step_begin(a, s));
+    }
+    nt::StepBeginArgs sba{};  // fixed-length modes: the start of the step (a launch of its own, or part of the first projection)
+    if (!eos) {
+      nt::StepBeginArgs &a = sba;
       a.t = t; a.rows_prev = rows_prev; a.rows_now = rows_now; a.d = d; a.vocab = V; a.bos_id = c.bos_id; a.pad_id = c.pad_id;
       a.pk = d_logits ? nullptr : m->pk; a.n_partials = partials_prev; a.out = d_out; a.out_ld = T;
       a.forced = d_forced; a.forced_ld = T; a.E = m->E; a.pe = m->pe; a.gamma = m->dec[0].ln1.g; a.beta = m->dec[0].ln1.b;
@@ -889,8 +903,9 @@ int decode_step(nt_model *m, DecodeCursor &cu, hipStream_t s) {
       a.prev_cert = prev_cert ? 1 : 0; a.tok = m->tok; a.slot_of_row = m->slot_of_row; a.final_key = m->final_key;
       a.cert_count = m->flags + 4;
       if (d_logits && rows_now == 0) { cu.finished = true; return NT_OK; }  // no tokens to collect in this mode (pk == nullptr)
-      KT(K_STEP_BEGIN, rows_prev * (partials_prev * 8.0 + 4) + rows_now * dd * 14, rows_now * dd * 10,
-         nt::launch_step_begin(a, s));
+      if (!fused_start)
+        KT(K_STEP_BEGIN, rows_prev * (partials_prev * 8.0 + 4) + rows_now * dd * 14, rows_now * dd * 10,
+           nt::launch_step_begin(a, s));
     }
     cu.t = t + 1;
     cu.rows_prev = rows_now;
@@ -934,44 +949,92 @@ int decode_step(nt_model *m, DecodeCursor &cu, hipStream_t s) {
       return NT_OK;
     };
     int rc;
+    // final hidden state as a head/tail plane pair (the planes share the a32 buffer)
+    _Float16 *h_hi = (_Float16 *)m->a32, *h_lo = h_hi + (long)m->max_rows * d;
+    bool final_ln_done = false;
+    // a chain that starts from the attention context (plane pair in ctx32): projection + bias + residual, LayerNorm
+    auto chain_from = [&](const _Float16 *W1p, const float *b1, const LN &ln) {
+      nt::DecChainArgs ch{};
+      ch.A_hi = (const _Float16 *)m->ctx32; ch.A_lo = ch.A_hi + lo_rows * d; ch.lda = d;
+      ch.W1p = W1p; ch.b1 = b1; ch.z = m->z; ch.ldz = d; ch.write_z = 1; ch.M = R;
+      ch.gamma = ln.g; ch.beta = ln.b; ch.eps = lne;
+      return ch;
+    };
     for (int l = 0; l < c.n_dec; l++) {
       const DecLayer &L = m->dec[l];
+      const bool last = l + 1 == c.n_dec;
       {  // self-attention: q (scaled) to q32, k|v appended to the cache at position t
         nt::GemmEpilogue e;
         e.bias = L.self.bqkv; e.scale = qscale; e.scale_cols = d; e.dst0 = m->q32; e.ld0 = d; e.n_split = d;
         e.dst1 = m->self_kv[l] + (long)t * 2 * d; e.ld1 = self_stride;
         if (eos) { e.dst1 = m->kv_new; e.ld1 = 2 * d; }  // appended to the row's own cache by the attention kernel
-        if ((rc = dec_gemm(K_GEMM_DEC_QKV, m->z, d, L.self.Wqkv, L.self.Wqkv_p, 3 * d, &L.ln1, e))) return rc;
+        if (fused_start && l == 0) {
+          nt::DecQkvArgs q{};
+          q.sb = sba;
+          if (eos) {  // tokens and row map come from the compaction kernel; nothing to collect here
+            q.sb.t = t; q.sb.rows_prev = R; q.sb.rows_now = R; q.sb.d = d; q.sb.vocab = V; q.sb.bos_id = c.bos_id;
+            q.sb.pad_id = c.pad_id; q.sb.E = m->E; q.sb.pe = m->pe; q.sb.z = m->z; q.sb.flags = m->flags;
+            q.tok_in = m->eos_tok;
+          }
+          q.sb.gamma = L.ln1.g; q.sb.beta = L.ln1.b; q.sb.eps = lne;
+          q.Wp = L.self.Wqkv_p; q.N = 3 * d; q.e = e;
+          KT(K_GEMM_DEC_QKV, gemm_bytes(Rd, d, 3 * d, false) + (eos ? 0.0 : rows_prev * (partials_prev * 8.0 + 4)) + Rd * dd * 6,
+             6 * Rd * dd * dd, nt::launch_dec_qkv(q, s));
+        } else if ((rc = dec_gemm(K_GEMM_DEC_QKV, m->z, d, L.self.Wqkv, L.self.Wqkv_p, 3 * d, &L.ln1, e))) return rc;
         KT(K_ATTN_DEC_SELF, Rd * (t + 1) * 2 * dd * 4 + Rd * dd * 8, 4 * Rd * (t + 1) * dd,
            nt::launch_attn_decode(m->q32, m->self_kv[l], true, self_stride, nullptr, t + 1, R, d, H, L.self.rk,
                                   c.rpr_clip, t, m->ctx32, s, streams(d, d, L.self.Wo_p, false) ? lo_rows * d : 0, origin,
                                   eos ? m->kv_new : nullptr));
         nt::GemmEpilogue o;
         o.bias = L.self.bo; o.resid = m->z; o.ldr = d; o.dst0 = m->z; o.ld0 = d; o.n_split = d;
-        if ((rc = dec_gemm(K_GEMM_DEC_O, m->ctx32, d, L.self.Wo, L.self.Wo_p, d, nullptr, o))) return rc;
+        if (!fused && (rc = dec_gemm(K_GEMM_DEC_O, m->ctx32, d, L.self.Wo, L.self.Wo_p, d, nullptr, o))) return rc;
       }
       {  // cross-attention over the encoder keys/values
         nt::GemmEpilogue e;
         e.bias = L.cross.bq; e.scale = qscale; e.scale_cols = d; e.dst0 = m->q32; e.ld0 = d; e.n_split = d;
-        if ((rc = dec_gemm(K_GEMM_DEC_Q, m->z, d, L.cross.Wq, L.cross.Wq_p, d, &L.ln2, e))) return rc;
+        if (fused) {  // self output projection + residual, LayerNorm, cross query projection: one launch
+          nt::DecChainArgs ch = chain_from(L.self.Wo_p, L.self.bo, L.ln2);
+          ch.W2p = L.cross.Wq_p; ch.N2 = d; ch.e2 = e;
+          KT(K_DEC_O_LN_PROJ, 2 * gemm_bytes(Rd, d, d, true) - Rd * dd * 4, 4 * Rd * dd * dd, nt::launch_dec_chain(ch, d, true, s));
+        } else if ((rc = dec_gemm(K_GEMM_DEC_Q, m->z, d, L.cross.Wq, L.cross.Wq_p, d, &L.ln2, e))) return rc;
         KT(K_ATTN_DEC_CROSS, cross_keys * 2 * dd * ca + Rd * dd * 8, 4 * cross_keys * dd,
            nt::launch_attn_decode(m->q32, m->cross[l], kCrossF32, (long)S * 2 * d, m->len, 0, R, d, H, nullptr, 0, 0,
                                   m->ctx32, s, streams(d, d, L.cross.Wo_p, false) ? lo_rows * d : 0, origin));
+        // The cross output projection starts the last chain of the layer.  Without an FFN: the final LayerNorm
+        // (last layer) follows it; with a narrow FFN: its LayerNorm and first matrix.
+        const bool u_planes = F > 0 && streams(F, d, L.ffn.W1_p, true) && streams(d, F, L.ffn.W2_p, false);
+        const bool o_to_final = fused && F == 0 && last && !c.q8_output;
+        const bool o_to_ffn = fused && F > 0 && F <= 1024 && L.ffn.W1_p != nullptr;
         nt::GemmEpilogue o;
         o.bias = L.cross.bo; o.resid = m->z; o.ldr = d; o.dst0 = m->z; o.ld0 = d; o.n_split = d;
-        if ((rc = dec_gemm(K_GEMM_DEC_O, m->ctx32, d, L.cross.Wo, L.cross.Wo_p, d, nullptr, o))) return rc;
-      }
-      if (F > 0) {
         // when both FFN projections stream, the hidden activation is handed over as a head/tail plane pair
         // (the two fp16 planes fill the fp32 buffer exactly)
-        const bool u_planes = streams(F, d, L.ffn.W1_p, true) && streams(d, F, L.ffn.W2_p, false);
         nt::GemmEpilogue f1;
         f1.bias = L.ffn.b1; f1.relu = 1; f1.dst0 = m->u32; f1.ld0 = F; f1.n_split = F;
         f1.dst_lo_offset = u_planes ? lo_rows * F : 0;
-        if ((rc = dec_gemm(K_GEMM_DEC_FFN, m->z, d, L.ffn.W1, L.ffn.W1_p, F, &L.ln3, f1, !u_planes))) return rc;
-        nt::GemmEpilogue f2;
-        f2.bias = L.ffn.b2; f2.resid = m->z; f2.ldr = d; f2.dst0 = m->z; f2.ld0 = d; f2.n_split = d;
-        if ((rc = dec_gemm(K_GEMM_DEC_FFN, m->u32, F, L.ffn.W2, u_planes ? L.ffn.W2_p : nullptr, d, nullptr, f2))) return rc;
+        if (o_to_final) {
+          nt::DecChainArgs ch = chain_from(L.cross.Wo_p, L.cross.bo, m->dec_final);
+          ch.write_z = 0; ch.h_hi = h_hi; ch.h_lo_offset = (long)m->max_rows * d; ch.lo_norm = m->lo_norm;
+          KT(K_DEC_O_LN_OUT, gemm_bytes(Rd, d, d, true), 2 * Rd * dd * dd, nt::launch_dec_chain(ch, d, true, s));
+          final_ln_done = true;
+        } else if (o_to_ffn) {
+          nt::DecChainArgs ch = chain_from(L.cross.Wo_p, L.cross.bo, L.ln3);
+          ch.W2p = L.ffn.W1_p; ch.N2 = F; ch.e2 = f1;
+          KT(K_DEC_O_LN_PROJ, gemm_bytes(Rd, d, d, true) + gemm_bytes(Rd, d, F, false) - Rd * dd * 4, 2 * Rd * dd * (dd + F),
+             nt::launch_dec_chain(ch, d, !u_planes, s));
+        } else if ((rc = dec_gemm(K_GEMM_DEC_O, m->ctx32, d, L.cross.Wo, L.cross.Wo_p, d, nullptr, o))) return rc;
+        if (F > 0) {
+          if (!o_to_ffn && (rc = dec_gemm(K_GEMM_DEC_FFN, m->z, d, L.ffn.W1, L.ffn.W1_p, F, &L.ln3, f1, !u_planes))) return rc;
+          nt::GemmEpilogue f2;
+          f2.bias = L.ffn.b2; f2.resid = m->z; f2.ldr = d; f2.dst0 = m->z; f2.ld0 = d; f2.n_split = d;
+          if (fused && u_planes && F == d && last && !c.q8_output) {  // second FFN matrix + residual + final LayerNorm
+            nt::DecChainArgs ch = chain_from(L.ffn.W2_p, L.ffn.b2, m->dec_final);
+            ch.A_hi = (const _Float16 *)m->u32; ch.A_lo = ch.A_hi + lo_rows * F; ch.lda = F;
+            ch.write_z = 0; ch.h_hi = h_hi; ch.h_lo_offset = (long)m->max_rows * d; ch.lo_norm = m->lo_norm;
+            KT(K_DEC_O_LN_OUT, gemm_bytes(Rd, F, d, true), 2 * Rd * dd * F, nt::launch_dec_chain(ch, d, true, s));
+            final_ln_done = true;
+          } else if ((rc = dec_gemm(K_GEMM_DEC_FFN, m->u32, F, L.ffn.W2, u_planes ? L.ffn.W2_p : nullptr, d, nullptr, f2))) return rc;
+        }
       }
     }
     if (c.q8_output) {
@@ -992,11 +1055,11 @@ int decode_step(nt_model *m, DecodeCursor &cu, hipStream_t s) {
       }
       return NT_OK;
     }
-    // final LayerNorm as a head/tail plane pair (the planes share the a32 buffer), then the output layer
-    _Float16 *h_hi = (_Float16 *)m->a32, *h_lo = h_hi + (long)m->max_rows * d;
-    KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd,
-       nt::launch_layer_norm(m->z, R, d, m->dec_final.g, m->dec_final.b, lne, h_hi, nt::OUT_PLANES,
-                             (long)m->max_rows * d, s, m->lo_norm));
+    // final LayerNorm as a head/tail plane pair (unless the last chain has produced it), then the output layer
+    if (!final_ln_done)
+      KT(K_LN_DEC, Rd * dd * 8, 8 * Rd * dd,
+         nt::launch_layer_norm(m->z, R, d, m->dec_final.g, m->dec_final.b, lne, h_hi, nt::OUT_PLANES,
+                               (long)m->max_rows * d, s, m->lo_norm));
     if (d_logits) {
       nt::GemmEpilogue e;
       e.dst0 = d_logits + (long)t * V; e.ld0 = (long)T * V; e.n_split = V;

@@ -212,6 +212,44 @@ struct StepBeginArgs {
 };
 hipError_t launch_step_begin(const StepBeginArgs &a, hipStream_t s);
 
+// ---- fused decoder-step kernels (nt_decoder.hip), model widths 256 / 512 ----------------------------------------
+bool dec_fused_supported(int K);
+// Step start fused into the first layer's self-attention projection: tokens as launch_step_begin takes them (or
+// tok_in[r] directly when tok_in != nullptr: the EOS mode's dense rows), z = sqrt(d) * E[y] + PE[t] written to sb.z,
+// LayerNorm (sb.gamma, sb.beta), then [q|k|v] = a * Wp^T with epilogue e (N columns; Wp in MFMA fragment order).
+// sb.a is ignored.  Rows in [rows_now, rows_prev) only have their token collected.
+struct DecQkvArgs {
+  StepBeginArgs sb;
+  const int32_t *tok_in;
+  const _Float16 *Wp;
+  int N;
+  GemmEpilogue e;
+};
+hipError_t launch_dec_qkv(const DecQkvArgs &a, hipStream_t s);
+// One launch for: z' = A * W1^T + b1 + z (A: head/tail planes [M][lda], W1 [K][K] in fragment order; z' is written
+// back to z if write_z), y = LayerNorm(z'), then either (W2p == nullptr) y as head/tail planes at h_hi /
+// h_hi + h_lo_offset with row stride K, plus lo_norm[m] = ||tail|| (optional), or C = y * W2^T with epilogue e2
+// (N2 columns, fp32 or fp16 destinations).
+struct DecChainArgs {
+  const _Float16 *A_hi, *A_lo;
+  long lda;
+  const _Float16 *W1p;
+  const float *b1;
+  float *z;
+  long ldz;
+  int write_z;
+  int M;
+  const float *gamma, *beta;
+  LnEps eps;
+  _Float16 *h_hi;
+  long h_lo_offset;
+  float *lo_norm;
+  const _Float16 *W2p;
+  int N2;
+  GemmEpilogue e2;
+};
+hipError_t launch_dec_chain(const DecChainArgs &a, int K, bool c2_f32, hipStream_t s);
+
 // Start of decoder step t when sentences end at EOS (Sec. 3.3 "Greedy Search"): the rows still decoding are kept
 // as a dense prefix.  Dense row r of a step belongs to batch row origin[r] (-1: no row; such rows compute on the
 // padding token and store nothing).  Three launches:
@@ -245,6 +283,7 @@ struct EosStepArgs {
   const _Float16 *E;
   const float *pe;
   float *z;
+  int skip_embed;              // != 0: no embedding launch (the first projection of the step embeds tok_in itself)
 };
 hipError_t launch_eos_step_begin(const EosStepArgs &a, hipStream_t s);
 

@@ -360,7 +360,7 @@ hipError_t launch_eos_step_begin(const EosStepArgs &a, hipStream_t s) {
   case NE_:                                                                                       \
     hipLaunchKernelGGL(eos_embed_kernel<NE_>, dim3((a.rows_now + 3) / 4), dim3(256), 0, s, a); \
     break;
-  if (a.rows_now > 0) switch (ne_case(a.d)) { NT_CASE(4) NT_CASE(8) NT_CASE(16) NT_CASE(0) }
+  if (a.rows_now > 0 && !a.skip_embed) switch (ne_case(a.d)) { NT_CASE(4) NT_CASE(8) NT_CASE(16) NT_CASE(0) }
 #undef NT_CASE
   return hipGetLastError();
 }

@@ -441,6 +441,14 @@ def test_c4_deep_teacher_shape_with_relative_positions(nt, oracle):
     _check_workload_sample(nt, oracle, "C4", 2048, 8192, 100)
 
 
+def test_narrow_model_at_hundreds_of_rows(nt, oracle):
+    """The tiny configuration's width (d = 256) in batches of hundreds of rows: the K = 256 instances of the streaming
+    projections, of the fused decoder-step kernels and of the certified arg-max; then the same with a narrow FFN in
+    the decoder only (its two matrices inside the fused chains) and two decoder layers."""
+    _check_workload_sample(nt, oracle, "C0", 1500, 16384, 150)
+    _check_workload_sample(nt, oracle, "C0", 600, 8192, 60, dec_d_ffn=256, n_dec=2)
+
+
 def test_relative_positions_small(nt, oracle):
     """Clip distance smaller than most sentences, 2 decoder layers, single wide head with relative keys."""
     _check_workload_sample(nt, oracle, "C0", 8, 512, rpr_clip=3, n_dec=2)
