@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnt.so")
 SOURCES = ["nt_host.hip", "nt_gemm.hip", "nt_gemm_stream.hip", "nt_vocab.hip", "nt_vocab_q8.hip", "nt_rows.hip",
-           "nt_attn.hip", "nt_decoder.hip"]
+           "nt_attn.hip", "nt_attn16.hip", "nt_decoder.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

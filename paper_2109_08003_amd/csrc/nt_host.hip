@@ -137,12 +137,12 @@ struct DecLayer {
 enum KernelId {
   K_EMBED_SRC, K_LN_ENC, K_GEMM_ENC_QKV, K_ATTN_ENC, K_GEMM_ENC_O, K_GEMM_ENC_FFN, K_GEMM_CROSS_KV,
   K_STEP_BEGIN, K_LN_DEC, K_GEMM_DEC_QKV, K_ATTN_DEC_SELF, K_GEMM_DEC_O, K_GEMM_DEC_Q, K_ATTN_DEC_CROSS,
-  K_GEMM_DEC_FFN, K_VOCAB_ARGMAX, K_GEMM_LOGITS, K_DEC_O_LN_PROJ, K_DEC_O_LN_OUT, K_COUNT
+  K_GEMM_DEC_FFN, K_VOCAB_ARGMAX, K_GEMM_LOGITS, K_DEC_O_LN_PROJ, K_DEC_O_LN_OUT, K_KV_QUANT, K_COUNT
 };
 const char *const kKernelNames[K_COUNT] = {
   "embed_src", "layer_norm_enc", "gemm_enc_qkv", "attention_enc", "gemm_enc_o", "gemm_enc_ffn", "gemm_cross_kv",
   "step_begin", "layer_norm_dec", "gemm_dec_qkv", "attn_decode_self", "gemm_dec_o", "gemm_dec_q", "attn_decode_cross",
-  "gemm_dec_ffn", "vocab_argmax", "gemm_logits", "dec_o_ln_proj", "dec_o_ln_out"};
+  "gemm_dec_ffn", "vocab_argmax", "gemm_logits", "dec_o_ln_proj", "dec_o_ln_out", "cross_kv_quantize"};
 
 struct Timing {
   uint64_t mask = 0;  // bit per KernelId; 0 = off
@@ -192,8 +192,12 @@ struct nt_model {
   void *ctx_enc = nullptr;     // [Mt,d]
   void *u_enc = nullptr;       // [Mt,F]
   void *enc_out = nullptr;     // [Mt,d]
-  std::vector<void *> cross;   // per decoder layer [Mt,2d]    (fp32 if kCrossF32 else fp16)
-  std::vector<float *> self_kv;   // per decoder layer [self_positions, 2d]
+  std::vector<void *> cross;   // per decoder layer [Mt,2d]    (fp32 if kCrossF32 else fp16; int16 codes if kv_i16)
+  std::vector<float *> self_kv;   // per decoder layer [self_positions, 2d]  (int16 codes if kv_i16)
+  // Single-head decoders of width 256 / 512 without relative keys keep both caches as 16-bit integers with one fp32
+  // scale per vector (nt_attn16.hip): half the bytes of the fp32 self cache, and far less rounding than fp16.
+  bool kv_i16 = false;
+  std::vector<float *> cross_sc, self_sc;  // per decoder layer [Mt,2] / [self_positions,2] scales
   float *z = nullptr, *a32 = nullptr, *q32 = nullptr, *ctx32 = nullptr, *u32 = nullptr;  // [Br, d|F]
   unsigned long long *pk = nullptr;
   float *ps = nullptr, *lo_norm = nullptr;             // certified arg-max: runner-up partials, tail norms
@@ -348,9 +352,11 @@ int alloc_lane_state(nt_model *m, hipStream_t s) {
   const size_t o_x = cv.take((size_t)Mt * d * 4), o_a16 = cv.take((size_t)Mt * d * kEncElt),
                o_qkv = cv.take((size_t)Mt * 3 * d * kEncElt), o_ctx16 = cv.take((size_t)Mt * d * kEncElt),
                o_u16 = cv.take((size_t)Mt * std::max(F, 1) * kEncElt), o_enc = cv.take((size_t)Mt * d * kEncElt);
-  std::vector<size_t> o_cross(cfg->n_dec), o_self(cfg->n_dec);
-  for (int l = 0; l < cfg->n_dec; l++) o_cross[l] = cv.take((size_t)Mt * 2 * d * kCrossElt);
-  for (int l = 0; l < cfg->n_dec; l++) o_self[l] = cv.take((size_t)m->self_positions * 2 * d * 4);
+  std::vector<size_t> o_cross(cfg->n_dec), o_self(cfg->n_dec), o_cross_sc(cfg->n_dec), o_self_sc(cfg->n_dec);
+  for (int l = 0; l < cfg->n_dec; l++) o_cross[l] = cv.take((size_t)Mt * 2 * d * (m->kv_i16 ? 2 : kCrossElt));
+  for (int l = 0; l < cfg->n_dec; l++) o_self[l] = cv.take((size_t)m->self_positions * 2 * d * (m->kv_i16 ? 2 : 4));
+  for (int l = 0; l < cfg->n_dec; l++) o_cross_sc[l] = cv.take(m->kv_i16 ? (size_t)Mt * 2 * 4 : 16);
+  for (int l = 0; l < cfg->n_dec; l++) o_self_sc[l] = cv.take(m->kv_i16 ? (size_t)m->self_positions * 2 * 4 : 16);
   const size_t o_z = cv.take((size_t)Br * d * 4), o_a32 = cv.take((size_t)Br * d * 4), o_q32 = cv.take((size_t)Br * d * 4),
                o_ctx32 = cv.take((size_t)Br * d * 4), o_u32 = cv.take((size_t)Br * std::max(Fd, 1) * 4),
                o_pk = cv.take((size_t)m->pk_elems * 8), o_ps = cv.take((size_t)m->pk_elems * 4),
@@ -368,7 +374,10 @@ int alloc_lane_state(nt_model *m, hipStream_t s) {
   char *A = m->d_arena;
   m->x = at<float>(A, o_x); m->a_enc = A + o_a16; m->qkv = A + o_qkv;
   m->ctx_enc = A + o_ctx16; m->u_enc = A + o_u16; m->enc_out = A + o_enc;
-  for (int l = 0; l < cfg->n_dec; l++) { m->cross.push_back(A + o_cross[l]); m->self_kv.push_back(at<float>(A, o_self[l])); }
+  for (int l = 0; l < cfg->n_dec; l++) {
+    m->cross.push_back(A + o_cross[l]); m->self_kv.push_back(at<float>(A, o_self[l]));
+    m->cross_sc.push_back(at<float>(A, o_cross_sc[l])); m->self_sc.push_back(at<float>(A, o_self_sc[l]));
+  }
   m->z = at<float>(A, o_z); m->a32 = at<float>(A, o_a32); m->q32 = at<float>(A, o_q32); m->ctx32 = at<float>(A, o_ctx32);
   m->u32 = at<float>(A, o_u32); m->pk = at<unsigned long long>(A, o_pk); m->len = at<int32_t>(A, o_len);
   m->ps = at<float>(A, o_ps); m->lo_norm = at<float>(A, o_lon); m->tok = at<int32_t>(A, o_tok);
@@ -551,6 +560,7 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
   m->c = *cfg;
   m->max_tokens = cfg->max_batch_tokens;
   m->max_rows = cfg->max_batch_rows > 0 ? std::min<int64_t>(cfg->max_batch_rows, m->max_tokens) : m->max_tokens;
+  m->kv_i16 = nt::attn_i16_supported(cfg->d_model, dec_heads(cfg), cfg->rpr_clip);
   hipStream_t s = as_stream(hip_stream);
 
   // ---- pack the weights: K-contiguous matrices, fp32 biases / LayerNorm / tables ----
@@ -697,7 +707,7 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
       for (auto &st : ln->stage) st = nt_model::Staging();
       ln->lane_stream = nullptr; ln->lane_start = nullptr;
       ln->h_progress = nullptr; ln->d_progress = nullptr; ln->decode_seq = 0;  // lane 0's: never freed through a clone
-      ln->cross.clear(); ln->self_kv.clear();
+      ln->cross.clear(); ln->self_kv.clear(); ln->cross_sc.clear(); ln->self_sc.clear();
       m->lanes.push_back(ln);
       rc = alloc_lane_state(ln, s);
       if (rc) return rc;
@@ -782,7 +792,7 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
   // The encoder output exists only inside the cross K|V projections when its LayerNorm is fused there; the debug
   // readback then computes it on demand.
   bool all_fused = c.n_dec > 0;
-  for (int l = 0; l < c.n_dec; l++) all_fused = all_fused && fused_ln(m->dec[l].cross.Wkv_p, 2 * d) && !kCrossF32;
+  for (int l = 0; l < c.n_dec; l++) all_fused = all_fused && fused_ln(m->dec[l].cross.Wkv_p, 2 * d) && (!kCrossF32 || m->kv_i16);
   m->enc_out_valid = !all_fused;
   if (!all_fused)
     KT(K_LN_ENC, Md * dd * (4 + ea), 8 * Md * dd,
@@ -790,13 +800,20 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
   for (int l = 0; l < c.n_dec; l++) {
     nt::GemmEpilogue e;
     e.bias = m->dec[l].cross.bkv; e.dst0 = m->cross[l]; e.ld0 = 2 * d; e.n_split = 2 * d;
+    // integer caches: the projection leaves fp32 keys | values in the (now free) q|k|v buffer, a row kernel then finds
+    // every vector's scale and writes the codes
+    const bool c32 = m->kv_i16 || kCrossF32;
+    if (m->kv_i16) e.dst0 = m->qkv;
     if (all_fused)
       KT(K_GEMM_CROSS_KV, gemm_bytes(Md, dd, 2 * dd, 4, ca, false), 4 * Md * dd * dd,
-         nt::launch_gemm_stream_ln(false, m->x, d, nt::GemmLayerNorm{m->enc_final.g, m->enc_final.b, lne},
+         nt::launch_gemm_stream_ln(c32, m->x, d, nt::GemmLayerNorm{m->enc_final.g, m->enc_final.b, lne},
                                    m->dec[l].cross.Wkv_p, M, 2 * d, d, e, s));
     else
       KT(K_GEMM_CROSS_KV, gemm_bytes(Md, dd, 2 * dd, ea, ca, false), 4 * Md * dd * dd,
-         nt::launch_gemm(amode, kCrossF32, m->enc_out, lo_of(m->enc_out, lo_d), d, m->dec[l].cross.Wkv, M, 2 * d, d, e, s, m->dec[l].cross.Wkv_p));
+         nt::launch_gemm(amode, c32, m->enc_out, lo_of(m->enc_out, lo_d), d, m->dec[l].cross.Wkv, M, 2 * d, d, e, s, m->dec[l].cross.Wkv_p));
+    if (m->kv_i16)
+      KT(K_KV_QUANT, Md * 2 * dd * 6, Md * 2 * dd * 4,
+         nt::launch_quantize_kv_i16((const float *)m->qkv, M, d, (short *)m->cross[l], m->cross_sc[l], s));
   }
   m->len_prefix.clear();
   m->B = B; m->S = S; m->encoded = true;
@@ -967,7 +984,8 @@ int decode_step(nt_model *m, DecodeCursor &cu, hipStream_t s) {
         nt::GemmEpilogue e;
         e.bias = L.self.bqkv; e.scale = qscale; e.scale_cols = d; e.dst0 = m->q32; e.ld0 = d; e.n_split = d;
         e.dst1 = m->self_kv[l] + (long)t * 2 * d; e.ld1 = self_stride;
-        if (eos) { e.dst1 = m->kv_new; e.ld1 = 2 * d; }  // appended to the row's own cache by the attention kernel
+        // the EOS mode and the integer caches: the pair goes to kv_new and the attention kernel appends it to the cache
+        if (eos || m->kv_i16) { e.dst1 = m->kv_new; e.ld1 = 2 * d; }
         if (fused_start && l == 0) {
           nt::DecQkvArgs q{};
           q.sb = sba;
@@ -981,6 +999,13 @@ int decode_step(nt_model *m, DecodeCursor &cu, hipStream_t s) {
           KT(K_GEMM_DEC_QKV, gemm_bytes(Rd, d, 3 * d, false) + (eos ? 0.0 : rows_prev * (partials_prev * 8.0 + 4)) + Rd * dd * 6,
              6 * Rd * dd * dd, nt::launch_dec_qkv(q, s));
         } else if ((rc = dec_gemm(K_GEMM_DEC_QKV, m->z, d, L.self.Wqkv, L.self.Wqkv_p, 3 * d, &L.ln1, e))) return rc;
+        if (m->kv_i16) {
+          nt::AttnI16Args at{};
+          at.q = m->q32; at.kv = (short *)m->self_kv[l]; at.sc = m->self_sc[l]; at.row_positions = T; at.n_keys = t + 1;
+          at.rows = R; at.d = d; at.kv_new = m->kv_new; at.origin = origin; at.ctx = m->ctx32;
+          at.ctx_lo_offset = streams(d, d, L.self.Wo_p, false) ? lo_rows * d : 0;
+          KT(K_ATTN_DEC_SELF, Rd * t * (2 * dd * 2 + 8) + Rd * dd * 20, 4 * Rd * (t + 1) * dd, nt::launch_attn_decode_i16(at, s));
+        } else
         KT(K_ATTN_DEC_SELF, Rd * (t + 1) * 2 * dd * 4 + Rd * dd * 8, 4 * Rd * (t + 1) * dd,
            nt::launch_attn_decode(m->q32, m->self_kv[l], true, self_stride, nullptr, t + 1, R, d, H, L.self.rk,
                                   c.rpr_clip, t, m->ctx32, s, streams(d, d, L.self.Wo_p, false) ? lo_rows * d : 0, origin,
@@ -997,6 +1022,13 @@ int decode_step(nt_model *m, DecodeCursor &cu, hipStream_t s) {
           ch.W2p = L.cross.Wq_p; ch.N2 = d; ch.e2 = e;
           KT(K_DEC_O_LN_PROJ, 2 * gemm_bytes(Rd, d, d, true) - Rd * dd * 4, 4 * Rd * dd * dd, nt::launch_dec_chain(ch, d, true, s));
         } else if ((rc = dec_gemm(K_GEMM_DEC_Q, m->z, d, L.cross.Wq, L.cross.Wq_p, d, &L.ln2, e))) return rc;
+        if (m->kv_i16) {
+          nt::AttnI16Args at{};
+          at.q = m->q32; at.kv = (short *)m->cross[l]; at.sc = m->cross_sc[l]; at.row_positions = S; at.len = m->len;
+          at.rows = R; at.d = d; at.origin = origin; at.ctx = m->ctx32;
+          at.ctx_lo_offset = streams(d, d, L.cross.Wo_p, false) ? lo_rows * d : 0;
+          KT(K_ATTN_DEC_CROSS, cross_keys * (2 * dd * 2 + 8) + Rd * dd * 8, 4 * cross_keys * dd, nt::launch_attn_decode_i16(at, s));
+        } else
         KT(K_ATTN_DEC_CROSS, cross_keys * 2 * dd * ca + Rd * dd * 8, 4 * cross_keys * dd,
            nt::launch_attn_decode(m->q32, m->cross[l], kCrossF32, (long)S * 2 * d, m->len, 0, R, d, H, nullptr, 0, 0,
                                   m->ctx32, s, streams(d, d, L.cross.Wo_p, false) ? lo_rows * d : 0, origin));

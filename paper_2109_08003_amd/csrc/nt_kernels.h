@@ -311,6 +311,27 @@ hipError_t launch_attn_decode(const float *q, const void *kv, bool kv_f32, long 
                               float *ctx, hipStream_t s, long ctx_lo_offset = 0, const int32_t *origin = nullptr,
                               const float *kv_new = nullptr);
 
+// ---- single-query attention against 16-bit integer caches (nt_attn16.hip): one head, d = 256 / 512, no relative keys
+bool attn_i16_supported(int d, int heads, int clip);
+// Cache row c, position p: key codes at kv + ((c * row_positions + p) * 2) * d, value codes d elements later; their
+// scales at sc[(c * row_positions + p) * 2] and [... + 1] (value = code * scale).
+struct AttnI16Args {
+  const float *q;        // [rows, d] fp32, already scaled
+  short *kv;
+  float *sc;
+  long row_positions;    // positions a cache row holds (self: steps of the decode, cross: padded source length)
+  const int32_t *len;    // cross-attention: keys of each cache row; nullptr for self-attention
+  int n_keys;            // self-attention: t + 1; the last key/value pair is kv_new's, appended to the cache by the kernel
+  int rows, d;
+  const float *kv_new;   // self-attention: [rows, 2 d] fp32 (key | value of this step); nullptr for cross-attention
+  const int32_t *origin; // optional: query row r uses cache row origin[r] (< 0: zero context)
+  float *ctx;            // [rows, d] fp32, or (ctx_lo_offset != 0) head/tail fp16 planes
+  long ctx_lo_offset;
+};
+hipError_t launch_attn_decode_i16(const AttnI16Args &a, hipStream_t s);
+// x [M][2 d] fp32 (key | value of M positions) -> codes [M][2][d] and scales [M][2]
+hipError_t launch_quantize_kv_i16(const float *x, long M, int d, short *cache, float *sc, hipStream_t s);
+
 // max dynamic LDS the encoder attention needs for (S, dh); used to validate shapes at load.
 size_t enc_attention_lds_bytes(int S, int dh, bool f32);
 
