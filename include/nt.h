@@ -291,10 +291,19 @@ int nt_debug_teacher_forced_logits(nt_model *m, const int32_t *d_tgt_in, int32_t
  *                                     instead of the streaming kernels;
  *   nt_debug_set_cert_distrust(m, 1)  certify no row in the single-pass arg-max, so that every row
  *                                     takes the head+tail recompute pass.
- * Errors: NT_EINVAL (null model, value other than 0 / 1).
+ *   nt_debug_set_encoder_tails(m, mask)  which encoder projections multiply the tail plane of their activations
+ *                                     (about 22 significant bits) and which the head plane only (fp16, half the
+ *                                     matrix-core work): bit 0 LayerNorm -> Q|K|V, bit 1 attention context -> output
+ *                                     projection, bit 2 final LayerNorm -> cross-attention K|V, bit 3 first FFN
+ *                                     matrix; with bit 0 clear, bits 4 / 5 / 6 select the q / k / v columns of
+ *                                     Q|K|V alone (a contiguous group).  The library's default is the plan its
+ *                                     precision study adopted: the v columns alone for the one-head student
+ *                                     without FFN, every tail for other encoders.
+ * Errors: NT_EINVAL (null model, value other than 0 / 1, mask beyond 7 bits).
  */
 int nt_debug_set_vocab_tiled(nt_model *m, int on);
 int nt_debug_set_cert_distrust(nt_model *m, int on);
+int nt_debug_set_encoder_tails(nt_model *m, uint32_t mask);
 
 /*
  * Read and clear the sticky device flags (synchronises the stream).  Returns NT_OK, or

@@ -19,7 +19,7 @@ EXPORTS = ["nt_param_count", "nt_n_steps", "nt_load_weights", "nt_free", "nt_enc
            "nt_debug_timing_count", "nt_debug_timing_name", "nt_debug_timing_read", "nt_pipeline_lanes",
            "nt_pipeline_lane", "nt_lane_stream", "nt_decode_greedy_eos", "nt_translate_batch_eos",
            "nt_debug_q8_output_layer", "nt_debug_q8_quantize_row", "nt_output_slots", "nt_debug_set_vocab_tiled",
-           "nt_debug_set_cert_distrust", "nt_q8_output_layer_static"]
+           "nt_debug_set_cert_distrust", "nt_q8_output_layer_static", "nt_debug_set_encoder_tails"]
 
 
 class NtConfig(C.Structure):
@@ -69,6 +69,7 @@ def load_library() -> C.CDLL:
         "nt_output_slots": (C.c_int, [p, i64, C.POINTER(i64)]),
         "nt_debug_set_vocab_tiled": (C.c_int, [p, C.c_int]),
         "nt_debug_set_cert_distrust": (C.c_int, [p, C.c_int]),
+        "nt_debug_set_encoder_tails": (C.c_int, [p, C.c_uint32]),
         "nt_debug_encoder_out": (C.c_int, [p, p, p]),
         "nt_debug_teacher_forced_logits": (C.c_int, [p, p, i32, i32, p, p]),
         "nt_check_device_flags": (C.c_int, [p, p]),
@@ -270,6 +271,9 @@ class Model:
 
     def debug_set_cert_distrust(self, on: bool):
         _check(lib().nt_debug_set_cert_distrust(self._h, int(bool(on))))
+
+    def debug_set_encoder_tails(self, mask: int):
+        _check(lib().nt_debug_set_encoder_tails(self._h, int(mask)))
 
     def check_device_flags(self, stream=None):
         _check(lib().nt_check_device_flags(self._h, _stream_ptr(stream)))

@@ -22,6 +22,7 @@
 #include "nt_kernels.h"
 
 #include <mutex>
+#include <type_traits>
 
 namespace nt {
 
@@ -37,20 +38,21 @@ bool gemm_stream_supported(int N, int K) { return (K == 256 || K == 512) && N % 
 // LN = true: A_hi points to fp32 rows X[M][lda] instead; the tile is LayerNorm-ed (fp32 statistics: mean first, then
 // the biased variance of the centred values) and split into head/tail planes while it is written to the LDS, which
 // saves the separate LayerNorm kernel and the round trip of its output through memory.
-template <int RB, int K, bool C_F32, bool LN>
+// TAIL = false: only the head plane of A is multiplied (11 significant bits: half the MFMA work and half the tile).
+template <int RB, int K, bool C_F32, bool LN, bool TAIL>
 __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float16 *__restrict__ A_hi,
                                                                    const _Float16 *__restrict__ A_lo, long lda, int M,
                                                                    const _Float16 *__restrict__ Wp, int N, int col_groups,
                                                                    GemmEpilogue e, GemmLayerNorm ln) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   _Float16 *sh = (_Float16 *)smem;
-  constexpr int TM = 32 * RB, ROWS = 2 * TM;  // LDS fragment rows: head rows, then tail rows
+  constexpr int TM = 32 * RB, ROWS = (TAIL ? 2 : 1) * TM;  // LDS fragment rows: head rows, then tail rows
   constexpr int LD = K + 8;                   // halfs per LDS row: the 16 B pad keeps the fragment reads conflict-free
   constexpr int KS = K / 16;
   // register slots of W fragments per wave; the lookahead is SL - 1 k-steps.  (A deeper ring did not shorten the
   // decoder-sized launches, and fewer registers leave room for other kernels' waves on the same CU.)
   constexpr int SL = 8;
-  constexpr int NOPS = 2 * RB;
+  constexpr int NOPS = (TAIL ? 2 : 1) * RB;
   static_assert(KS % SL == 0, "the ring of W slots must divide the k-steps of a strip");
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -144,7 +146,7 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
       }
       const int R = wave + GS_WAVES * i;
       *(halfNE *)(sh + R * LD + lane * NE) = hi;
-      *(halfNE *)(sh + (R + TM) * LD + lane * NE) = lo;
+      if (TAIL) *(halfNE *)(sh + (R + TM) * LD + lane * NE) = lo;
     }
   } else if (K == 512) {
 #pragma unroll
@@ -196,12 +198,13 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   // fragment row of operand op: head rows of block op % RB, then the tail rows; two base registers, because the
   // byte offsets of the upper half do not fit the 16-bit offset field
   const _Float16 *hrow = sh + li * LD + g * 8;
-  int off2 = (ROWS / 2) * LD;
+  constexpr int HALF = ROWS > 32 ? ROWS / 2 : ROWS;  // LDS rows reached from the first base register
+  int off2 = HALF * LD;
   asm volatile("" : "+v"(off2));
   const _Float16 *hrow2 = hrow + off2;
   auto frag = [&](int op, int ks) -> half8 {
     const int R0 = op * 32;  // ops 0 .. RB-1: head planes, RB .. 2RB-1: tail planes
-    return *(const half8 *)((R0 < ROWS / 2 ? hrow : hrow2) + (R0 % (ROWS / 2)) * LD + ks * 16);
+    return *(const half8 *)((R0 < HALF ? hrow : hrow2) + (R0 % HALF) * LD + ks * 16);
   };
   half8 hf[NOPS];
 #pragma unroll
@@ -220,34 +223,41 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
       if (e.bias) bias[nb] = e.bias[n];
       scl[nb] = (n < e.scale_cols) ? e.scale : 1.f;
     }
+    // The k-loop of a strip, over the head plane's row blocks alone (NO = RB) or over both planes' (NO = NOPS): the
+    // epilogue's tail_col0 .. tail_col1 name the output columns whose strips take the tail plane as well.
+    auto k_loop = [&](auto nops_tag, const float (&bias_)[2], const float (&scl_)[2]) {
+      constexpr int NO = decltype(nops_tag)::value;
 #pragma unroll
-    for (int ks = 0; ks < KS; ks++) {
-      const int tgt = ks + SL - 1;
-      const int pf = tgt < KS ? pcur + tgt * 2048 : pnext + (tgt - KS) * 2048;
-      const int ksn = (ks + 1) % KS;
+      for (int ks = 0; ks < KS; ks++) {
+        const int tgt = ks + SL - 1;
+        const int pf = tgt < KS ? pcur + tgt * 2048 : pnext + (tgt - KS) * 2048;
+        const int ksn = (ks + 1) % KS;
 #pragma unroll
-      for (int op = 0; op < NOPS; op++) {
+        for (int op = 0; op < NO; op++) {
 #pragma unroll
-        for (int nb = 0; nb < 2; nb++) {
-          if (ks == 0 && op < RB) {
-            const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            acc[op % RB][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(hf[op], wb[ks % SL][nb], zero, 0, 0, 0);
-          } else {
-            acc[op % RB][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(hf[op], wb[ks % SL][nb], acc[op % RB][nb], 0, 0, 0);
+          for (int nb = 0; nb < 2; nb++) {
+            if (ks == 0 && op < RB) {
+              const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+              acc[op % RB][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(hf[op], wb[ks % SL][nb], zero, 0, 0, 0);
+            } else {
+              acc[op % RB][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(hf[op], wb[ks % SL][nb], acc[op % RB][nb], 0, 0, 0);
+            }
           }
+          // refill what was just consumed; the scheduling barrier keeps the loads this far ahead of their use
+          hf[op] = frag(op, ksn);
+          if (op == 0) {
+            wb[tgt % SL][0] = wload(pf, 0);
+            wb[tgt % SL][1] = wload(pf, 1);
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
-        // refill what was just consumed; the scheduling barrier keeps the loads this far ahead of their use
-        hf[op] = frag(op, ksn);
-        if (op == 0) {
-          wb[tgt % SL][0] = wload(pf, 0);
-          wb[tgt % SL][1] = wload(pf, 1);
-        }
-        __builtin_amdgcn_sched_barrier(0);
+        // the wait for bias and scale is taken here, where it counts only the fragments requested since; left to the
+        // epilogue it becomes a wait for everything in flight
+        if (ks == SL) asm volatile("" ::"v"(bias_[0]), "v"(bias_[1]), "v"(scl_[0]), "v"(scl_[1]));
       }
-      // the wait for bias and scale is taken here, where it counts only the fragments requested since; left to the
-      // epilogue it becomes a wait for everything in flight
-      if (ks == SL) asm volatile("" ::"v"(bias[0]), "v"(bias[1]), "v"(scl[0]), "v"(scl[1]));
-    }
+    };
+    if (TAIL && strip * 64 >= e.tail_col0 && strip * 64 < e.tail_col1) k_loop(std::integral_constant<int, NOPS>{}, bias, scl);
+    else k_loop(std::integral_constant<int, RB>{}, bias, scl);
     // ---- epilogue of the strip: acc[rb][nb][v] is C[m0 + rb*32 + (v/4)*8 + g*4 + v%4][strip*64 + nb*32 + li] ----
     // Addresses are a uniform 64-bit base per 32 x 32 block plus a 32-bit lane offset (n_split is a multiple of 32,
     // so a block never straddles the two destinations).
@@ -350,11 +360,11 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   }
 }
 
-template <int RB, int K, bool C_F32, bool LN>
+template <int RB, int K, bool C_F32, bool LN, bool TAIL>
 static hipError_t gs_launch(const _Float16 *A, const _Float16 *A_lo, long lda, int M, const _Float16 *Wp, int N,
                             const GemmEpilogue &e, const GemmLayerNorm &ln, hipStream_t s) {
-  auto kern = gemm_stream_kernel<RB, K, C_F32, LN>;
-  const size_t lds = (size_t)64 * RB * (K + 8) * 2;
+  auto kern = gemm_stream_kernel<RB, K, C_F32, LN, TAIL>;
+  const size_t lds = (size_t)(TAIL ? 64 : 32) * RB * (K + 8) * 2;
   // raising the dynamic LDS limit is per kernel, once per process (several host threads may get here at once)
   static std::once_flag once;
   static hipError_t attr_err = hipSuccess;
@@ -378,12 +388,14 @@ static hipError_t gs_launch(const _Float16 *A, const _Float16 *A_lo, long lda, i
 
 template <bool LN>
 static hipError_t gs_dispatch(bool c_f32, const _Float16 *A, const _Float16 *A_lo, long lda, const _Float16 *Wp, int M,
-                              int N, int K, const GemmEpilogue &e, const GemmLayerNorm &ln, hipStream_t s) {
+                              int N, int K, const GemmEpilogue &e, const GemmLayerNorm &ln, bool tail, hipStream_t s) {
   if (M <= 0 || N <= 0) return hipSuccess;
   if (!gemm_stream_supported(N, K) || e.n_split % 32 != 0) return hipErrorInvalidValue;
   const bool small = M <= 8192;  // 32-row tiles: twice the workgroups
-#define NT_GS_CASE(RB_, K_, CF_)                                 \
-  if (small == (RB_ == 1) && K == K_ && c_f32 == CF_) return gs_launch<RB_, K_, CF_, LN>(A, A_lo, lda, M, Wp, N, e, ln, s);
+#define NT_GS_CASE(RB_, K_, CF_)                                                                                       \
+  if (small == (RB_ == 1) && K == K_ && c_f32 == CF_)                                                                  \
+    return tail ? gs_launch<RB_, K_, CF_, LN, true>(A, A_lo, lda, M, Wp, N, e, ln, s)                                  \
+                : gs_launch<RB_, K_, CF_, LN, false>(A, A_lo, lda, M, Wp, N, e, ln, s);
   NT_GS_CASE(1, 512, true) NT_GS_CASE(1, 512, false) NT_GS_CASE(2, 512, true) NT_GS_CASE(2, 512, false)
   NT_GS_CASE(1, 256, true) NT_GS_CASE(1, 256, false) NT_GS_CASE(2, 256, true) NT_GS_CASE(2, 256, false)
 #undef NT_GS_CASE
@@ -391,13 +403,13 @@ static hipError_t gs_dispatch(bool c_f32, const _Float16 *A, const _Float16 *A_l
 }
 
 hipError_t launch_gemm_stream(bool c_f32, const _Float16 *A, const _Float16 *A_lo, long lda, const _Float16 *Wp, int M,
-                              int N, int K, const GemmEpilogue &e, hipStream_t s) {
-  return gs_dispatch<false>(c_f32, A, A_lo, lda, Wp, M, N, K, e, GemmLayerNorm{}, s);
+                              int N, int K, const GemmEpilogue &e, hipStream_t s, bool tail) {
+  return gs_dispatch<false>(c_f32, A, A_lo, lda, Wp, M, N, K, e, GemmLayerNorm{}, tail && A_lo != nullptr, s);
 }
 
 hipError_t launch_gemm_stream_ln(bool c_f32, const float *X, long ldx, const GemmLayerNorm &ln, const _Float16 *Wp, int M,
-                                 int N, int K, const GemmEpilogue &e, hipStream_t s) {
-  return gs_dispatch<true>(c_f32, (const _Float16 *)X, nullptr, ldx, Wp, M, N, K, e, ln, s);
+                                 int N, int K, const GemmEpilogue &e, hipStream_t s, bool tail) {
+  return gs_dispatch<true>(c_f32, (const _Float16 *)X, nullptr, ldx, Wp, M, N, K, e, ln, tail, s);
 }
 
 }  // namespace nt

@@ -37,6 +37,9 @@ struct GemmEpilogue {
   int n_split = 0;  // set to N when there is a single destination
   void *dst1 = nullptr;
   long ld1 = 0;
+  // streaming kernels with a head/tail A operand: only the strips of 64 output columns that start in
+  // [tail_col0, tail_col1) multiply the tail plane too (the others see fp16 activations: half the MFMA work)
+  int tail_col0 = 0, tail_col1 = 1 << 30;
   long dst_lo_offset = 0;  // fp16 destinations only: if != 0 the tail fp16(v - fp16(v)) is also stored, this many
                            // elements after the head (the result becomes a head/tail plane pair)
 };
@@ -48,9 +51,9 @@ enum AMode { A_F16 = 0, A_PLANES = 1, A_F32 = 2 };
 // a_mode: AMode; A_lo is the tail plane for A_PLANES (ignored otherwise).  c_f32: destinations are
 // fp32, else fp16.  K must be a multiple of 64; lda in elements.
 // Wp (optional): the same weights in MFMA fragment order (vocab_pack layout); with A_PLANES and a supported
-// shape the streaming kernel is used.
+// shape the streaming kernel is used, and tail = false then leaves the tail plane out of the product.
 hipError_t launch_gemm(int a_mode, bool c_f32, const void *A, const void *A_lo, long lda, const _Float16 *Wt, int M,
-                       int N, int K, const GemmEpilogue &e, hipStream_t s, const _Float16 *Wp = nullptr);
+                       int N, int K, const GemmEpilogue &e, hipStream_t s, const _Float16 *Wp = nullptr, bool tail = true);
 
 // Streaming form for K = 256 / 512 and N % 64 == 0 (nt_gemm_stream.hip): the A tile (head/tail planes) stays in
 // the LDS, the weights stream through registers in fragment order.
@@ -60,10 +63,11 @@ struct GemmLayerNorm {
 };
 bool gemm_stream_supported(int N, int K);
 // C = LayerNorm(X) * Wt^T: X [M][ldx] fp32 is normalised and split into planes while the tile is loaded
+// tail = false: only the head plane of A enters the product (fp16 activations: half the matrix-core work)
 hipError_t launch_gemm_stream_ln(bool c_f32, const float *X, long ldx, const GemmLayerNorm &ln, const _Float16 *Wp, int M,
-                                 int N, int K, const GemmEpilogue &e, hipStream_t s);
+                                 int N, int K, const GemmEpilogue &e, hipStream_t s, bool tail = true);
 hipError_t launch_gemm_stream(bool c_f32, const _Float16 *A, const _Float16 *A_lo, long lda, const _Float16 *Wp, int M,
-                              int N, int K, const GemmEpilogue &e, hipStream_t s);
+                              int N, int K, const GemmEpilogue &e, hipStream_t s, bool tail = true);
 
 // Decoder-step variant for small M (fp32 A and C): 32 x 32 tiles, whole-K operand panels loaded
 // in one round trip.  If ln_g != nullptr the rows of A are LayerNorm-ed first (requires K to be
