@@ -146,10 +146,11 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
  *   advanced for its first h_row_steps[b] steps (rows sorted by length finish in order, so
  *   the active rows are always a prefix); entries of d_out beyond that are set to pad_id.
  *   NULL = every row runs n_steps steps.  A row's arithmetic never reads another row.  The number of
- *   active rows does select between kernels whose fp32 summation order differs (a one-round-trip
- *   kernel for small batches, streaming kernels above), so the same sentence decoded in batches of
- *   very different size can differ in the last bit of a logit, and therefore in a token where two
- *   logits tie to within that bit; the EOS-terminated call below fixes the choice by the caps alone.
+ *   active rows does select between kernel forms whose fp32 summation order differs (how many waves
+ *   share a row's keys in the attention kernels; for model widths other than 256 / 512 a
+ *   one-round-trip projection kernel below 128 rows), so the same sentence decoded in batches of very
+ *   different size can differ in the last bit of a logit, and therefore in a token where two logits
+ *   tie to within that bit; the EOS-terminated call below fixes the choice by the caps alone.
  * Errors: NT_EINVAL, NT_ESTATE (B differs from the encoded batch), NT_ERANGE (n_steps >
  * max_len, h_row_steps not non-increasing), NT_ENOMEM (B * n_steps beyond the self cache), NT_EHIP.
  */
