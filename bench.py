@@ -26,10 +26,20 @@ WORDS_PER_TOKEN = 1.0 / 1.3          # the benchmark's convention: 1 word = 1.3 
 HBM_PEAK_GBS = 8000.0                # MI355X HBM3E
 MFMA_F16_PEAK_TFLOPS = 2500.0        # dense fp16 MFMA
 MFMA_I8_PEAK_TOPS = 5000.0           # dense int8 MFMA
-# HBM traffic per launch (decode step) of the dominant kernel family from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs, calibrated against a streaming kernel of known size (see profiles/); None where
-# it has not been measured.
-MEASURED_TRAFFIC_BYTES = {("vocab_argmax", "C2", 65536, 0): 59.5e6, ("vocab_argmax", "C2", 65536, 1): 22.6e6}
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def measured_traffic(kernel, workload, budget, q8):
+    """HBM bytes per launch of a kernel family from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary the profiling
+    step wrote under profiles/ (calibrated against a streaming kernel of known size); None where none exists.  The
+    summary carries the figure on a line "traffic bytes per launch: <number>"."""
+    name = f"{kernel}{'_q8' if q8 else ''}_{workload}_budget{budget}_hbm_counters.md"
+    try:
+        import re
+        m = re.search(r"traffic bytes per launch:\s*([0-9.eE+]+)", open(os.path.join(PROFILES, name)).read())
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
 
 
 def calibration_copy(torch, mib):
@@ -187,11 +197,22 @@ def main():
     # ---- per-kernel timing with HIP events on the launch stream (separate, instrumented passes) ----
     # (1) as timed: every lane busy, kernels of different batches share the GPU;
     # (2) solo: the same batches one after the other on lane 0, each kernel alone on the GPU.
+    peaks = model.probe_peaks(stream=streams[0])   # what this machine reaches on plain probes, in this run
+
     def kernel_table(kern):
-        return {name: dict(launches=k["launches"], total_ms=round(k["ms"], 3),
-                           avg_us=round(1e3 * k["ms"] / k["launches"], 2),
-                           GBps=round(k["bytes"] / k["ms"] / 1e6, 1), TFLOPs=round(k["flops"] / k["ms"] / 1e9, 2))
-                for name, k in kern.items()}
+        """Per family: algorithmic GB/s and TFLOP/s over the event-to-event time of its launches, as percentages of
+        the datasheet peaks (HBM 8 TB/s, fp16 MFMA 2.5 PFLOP/s; the 8-bit output layer against 5 POP/s) and of the
+        peaks the probes measured in this run."""
+        tab = {}
+        for name, k in kern.items():
+            gbs, tfs = k["bytes"] / k["ms"] / 1e6, k["flops"] / k["ms"] / 1e9
+            mfma_peak = MFMA_I8_PEAK_TOPS if (args.q8 and name.startswith("vocab_argmax")) else MFMA_F16_PEAK_TFLOPS
+            tab[name] = dict(launches=k["launches"], total_ms=round(k["ms"], 3), avg_us=round(1e3 * k["ms"] / k["launches"], 2),
+                             GBps=round(gbs, 1), TFLOPs=round(tfs, 2),
+                             pct_hbm_peak=round(100 * gbs / HBM_PEAK_GBS, 1), pct_mfma_peak=round(100 * tfs / mfma_peak, 1),
+                             pct_hbm_measured=round(100 * gbs / peaks["hbm_read_gbs"], 1),
+                             pct_mfma_measured=round(100 * tfs / peaks["mfma_f16_tflops"], 1))
+        return tab
 
     def roof(k, name=None):
         intensity = k["flops"] / k["bytes"]
@@ -201,7 +222,9 @@ def main():
             bound, achieved, peak = "mfma", k["flops"] / k["ms"] / 1e9, mfma_peak
         else:
             bound, achieved, peak, unit = "hbm", k["bytes"] / k["ms"] / 1e6, HBM_PEAK_GBS, "GB/s"
+        measured = peaks["mfma_f16_tflops"] if bound == "mfma" else peaks["hbm_read_gbs"]
         return dict(bound=bound, achieved=round(achieved, 2), peak=peak, unit=unit, frac=round(achieved / peak, 4),
+                    measured_peak=round(measured, 1), frac_of_measured_peak=round(achieved / measured, 4),
                     avg_launch_us=round(1e3 * k["ms"] / k["launches"], 2), launches=k["launches"])
 
     model.timing_enable("all")
@@ -220,12 +243,27 @@ def main():
     # is kept beside it.
     dom = max(kern_solo, key=lambda n: kern_solo[n]["ms"])
     k = kern_solo[dom]
-    roofline = dict(kernel=dom, **roof(k, dom), traffic=MEASURED_TRAFFIC_BYTES.get((dom, args.workload, args.budget, int(args.q8))),
+    roofline = dict(kernel=dom, **roof(k, dom), traffic=measured_traffic(dom, args.workload, args.budget, args.q8),
                     algorithmic_bytes_per_launch=round(k["bytes"] / k["launches"]),
                     algorithmic_flops_per_launch=round(k["flops"] / k["launches"]),
                     as_timed_with_lanes=roof(kern[dom], dom))
 
     calibration_copy(torch, args.calib_copy_mib)
+
+    # ---- the paper-shaped 4,096-sentence configuration at its own 4,096-token budget (same student, same weights) ----
+    c1 = None
+    if args.workload == "C2" and not (args.ln_l1 or args.q8 or args.eos_gain is not None):
+        t1, o1 = nt_synth.workload("C1")
+        model.translate_batch(t1, o1, 4096)
+        best = 1e30
+        for _ in range(5):
+            t0 = time.perf_counter()
+            model.translate_batch(t1, o1, 4096)
+            best = min(best, time.perf_counter() - t0)
+        _, st1 = nt.plan_batches(np.diff(o1).astype(np.int32), 4096, 0)
+        c1 = {"workload": "C1: 4096 sentences, token budget 4096, through nt_translate_batch (host buffers in and out)",
+              "words_per_s": round(int(o1[-1]) * WORDS_PER_TOKEN / best, 1), "source_tokens_per_s": round(int(o1[-1]) / best, 1),
+              "batches": int(len(st1) - 1), "ms": round(1e3 * best, 3), "timing": "best of 5 after 1 warm-up"}
 
     # ---- CPU oracle on a bounded sample of the same workload ----
     cpu = None
@@ -252,7 +290,13 @@ def main():
                    "token_budget": args.budget, "batches": len(batches), "pipeline_lanes": len(lanes), "source_tokens": src_tokens,
                    "target_tokens": tgt_tokens, "decode_steps": dec_steps},
         "source_tokens_per_s": round(src_tokens / dt, 1), "target_tokens_per_s": round(tgt_tokens / dt, 1),
+        "value_region": "batches resident in HBM, outputs left in HBM (the metric's contract); the same job through "
+                        "nt_translate_batch - batching, H2D, D2H and un-sorting included - is host_inclusive_words_per_s",
         "host_inclusive_words_per_s": round(src_tokens * WORDS_PER_TOKEN / dt_host, 1),
+        "measured_peaks": {"mfma_f16_tflops": round(peaks["mfma_f16_tflops"], 1), "hbm_read_gbs": round(peaks["hbm_read_gbs"], 1),
+                           "how": "nt_debug_probe_peaks in this run: a loop of independent 32x32x16 fp16 MFMAs on every "
+                                  "SIMD; a streaming read of 1 GiB"},
+        "c1_budget4096": c1,
         "paper_context": "247,000 words/s on one NVIDIA A100 (different model, data and harness; context only)",
         "eos_mode": eos_mode, "roofline": roofline, "cpu_baseline": cpu, "kernels": table, "kernels_solo": table_solo,
     }))

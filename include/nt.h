@@ -329,6 +329,13 @@ int nt_debug_timing_read(nt_model *m, int kernel, double *total_ms, int64_t *lau
                          void *hip_stream);
 
 /*
+ * What this GPU reaches on two plain probes, for rooflines against measured rather than datasheet peaks: a loop of
+ * independent fp16 MFMAs on every SIMD (TFLOP/s) and a streaming read of up to 1 GiB of the model's arena (GB/s).
+ * Best of three runs each; synchronises hip_stream.  Measurement aid, a few milliseconds.
+ */
+int nt_debug_probe_peaks(nt_model *m, double *mfma_tflops, double *hbm_read_gbs, void *hip_stream);
+
+/*
  * Pipeline lanes.  A model holds pipeline_lanes lanes that share the weights; each lane has its own
  * arena, caches and state.  nt_pipeline_lane(m, i) returns lane i (lane 0 is m itself) as a model
  * handle that nt_encode / nt_decode_greedy / nt_debug_* accept, so that a caller who keeps its batches

@@ -19,7 +19,7 @@ EXPORTS = ["nt_param_count", "nt_n_steps", "nt_load_weights", "nt_free", "nt_enc
            "nt_debug_timing_count", "nt_debug_timing_name", "nt_debug_timing_read", "nt_pipeline_lanes",
            "nt_pipeline_lane", "nt_lane_stream", "nt_decode_greedy_eos", "nt_translate_batch_eos",
            "nt_debug_q8_output_layer", "nt_debug_q8_quantize_row", "nt_output_slots", "nt_debug_set_vocab_tiled",
-           "nt_debug_set_cert_distrust", "nt_q8_output_layer_static", "nt_debug_set_encoder_tails"]
+           "nt_debug_set_cert_distrust", "nt_q8_output_layer_static", "nt_debug_set_encoder_tails", "nt_debug_probe_peaks"]
 
 
 class NtConfig(C.Structure):
@@ -79,6 +79,7 @@ def load_library() -> C.CDLL:
         "nt_pipeline_lane": (p, [p, C.c_int]),
         "nt_lane_stream": (C.c_void_p, [p]),
         "nt_debug_timing_enable": (C.c_int, [p, C.c_uint64]),
+        "nt_debug_probe_peaks": (C.c_int, [p, C.POINTER(C.c_double), C.POINTER(C.c_double), p]),
         "nt_debug_timing_count": (C.c_int, []),
         "nt_debug_timing_name": (C.c_char_p, [C.c_int]),
         "nt_debug_timing_read": (C.c_int, [p, C.c_int, C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(C.c_double),
@@ -277,6 +278,12 @@ class Model:
 
     def check_device_flags(self, stream=None):
         _check(lib().nt_check_device_flags(self._h, _stream_ptr(stream)))
+
+    def probe_peaks(self, stream=None) -> dict:
+        """Measured peaks of this GPU: {"mfma_f16_tflops": ..., "hbm_read_gbs": ...} (nt_debug_probe_peaks)."""
+        a, b = C.c_double(), C.c_double()
+        _check(lib().nt_debug_probe_peaks(self._h, C.byref(a), C.byref(b), _stream_ptr(stream)))
+        return {"mfma_f16_tflops": a.value, "hbm_read_gbs": b.value}
 
     def timing_enable(self, kernels="all"):
         """kernels: "all", None/() to switch off, or an iterable of family names."""

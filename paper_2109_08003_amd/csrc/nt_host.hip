@@ -144,12 +144,12 @@ struct DecLayer {
 enum KernelId {
   K_EMBED_SRC, K_LN_ENC, K_GEMM_ENC_QKV, K_ATTN_ENC, K_GEMM_ENC_O, K_GEMM_ENC_FFN, K_GEMM_CROSS_KV,
   K_STEP_BEGIN, K_LN_DEC, K_GEMM_DEC_QKV, K_ATTN_DEC_SELF, K_GEMM_DEC_O, K_GEMM_DEC_Q, K_ATTN_DEC_CROSS,
-  K_GEMM_DEC_FFN, K_VOCAB_ARGMAX, K_GEMM_LOGITS, K_DEC_O_LN_PROJ, K_DEC_O_LN_OUT, K_KV_QUANT, K_COUNT
+  K_GEMM_DEC_FFN, K_VOCAB_ARGMAX, K_GEMM_LOGITS, K_DEC_O_LN_PROJ, K_DEC_O_LN_OUT, K_KV_QUANT, K_VOCAB_ARGMAX_SMALL, K_COUNT
 };
 const char *const kKernelNames[K_COUNT] = {
   "embed_src", "layer_norm_enc", "gemm_enc_qkv", "attention_enc", "gemm_enc_o", "gemm_enc_ffn", "gemm_cross_kv",
   "step_begin", "layer_norm_dec", "gemm_dec_qkv", "attn_decode_self", "gemm_dec_o", "gemm_dec_q", "attn_decode_cross",
-  "gemm_dec_ffn", "vocab_argmax", "gemm_logits", "dec_o_ln_proj", "dec_o_ln_out", "cross_kv_quantize"};
+  "gemm_dec_ffn", "vocab_argmax", "gemm_logits", "dec_o_ln_proj", "dec_o_ln_out", "cross_kv_quantize", "vocab_argmax_small"};
 
 struct Timing {
   uint64_t mask = 0;  // bit per KernelId; 0 = off
@@ -1133,8 +1133,8 @@ int decode_step(nt_model *m, DecodeCursor &cu, hipStream_t s) {
         KT(K_VOCAB_ARGMAX, (double)V * dd * 2 + Rd * dd * 4 + Rd * np_ * 8, 2 * Rd * dd * V,
            nt::launch_vocab_argmax_certified(h_hi, h_lo, d, m->vw, R, m->lo_norm, m->w_norm_max, m->pk, m->ps,
                                              m->tok, m->slot_of_row, m->cert_list, m->flags + 4, m->final_key, m->need_mask, s));
-      else
-        KT(K_VOCAB_ARGMAX, (double)V * dd * 2 + Rd * dd * 4 + Rd * np_ * 8, 2 * Rd * dd * V,
+      else  // below the certified variant's row count the step is bound by the stream of the output matrix
+        KT(K_VOCAB_ARGMAX_SMALL, (double)V * dd * 2 + Rd * dd * 4 + Rd * np_ * 8, 2 * Rd * dd * V,
            nt::launch_vocab_argmax(h_hi, h_lo, d, m->vw, R, m->pk, s));
       cu.partials_prev = np_;
     }
@@ -1344,6 +1344,39 @@ int nt_debug_timing_enable(nt_model *m, uint64_t kernel_mask) {
     x->timing.used = 0;
     x->timing.recs.clear();
   }
+  return NT_OK;
+}
+
+int nt_debug_probe_peaks(nt_model *m, double *mfma_tflops, double *hbm_read_gbs, void *hip_stream) {
+  if (!m || !mfma_tflops || !hbm_read_gbs) return fail(NT_EINVAL, "null argument");
+  hipStream_t s = as_stream(hip_stream);
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+    if (e0) (void)hipEventDestroy(e0);
+    return fail(NT_EHIP, "hipEventCreate failed");
+  }
+  struct Ev { hipEvent_t a, b; ~Ev() { (void)hipEventDestroy(a); (void)hipEventDestroy(b); } } ev{e0, e1};
+  float *sink = (float *)(m->flags + 12);
+  const int iters = 4000, blocks = 512;  // two workgroups of four waves per CU: two waves per SIMD
+  const long bytes = (long)std::min<size_t>(m->arena_bytes, (size_t)1 << 30) & ~15l;
+  double best_mfma = 0.0, best_read = 0.0;
+  for (int rep = 0; rep < 3; rep++) {
+    float ms = 0.f;
+    HIP_TRY(hipEventRecord(e0, s));
+    HIP_TRY(nt::launch_probe_mfma(iters, blocks, sink, s));
+    HIP_TRY(hipEventRecord(e1, s));
+    HIP_TRY(hipEventSynchronize(e1));
+    HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+    if (ms > 0.f) best_mfma = std::max(best_mfma, (double)blocks * 4 * iters * 4 * (2.0 * 32 * 32 * 16) / (ms * 1e-3) / 1e12);
+    HIP_TRY(hipEventRecord(e0, s));
+    HIP_TRY(nt::launch_probe_read(m->d_arena, bytes, sink, s));
+    HIP_TRY(hipEventRecord(e1, s));
+    HIP_TRY(hipEventSynchronize(e1));
+    HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+    if (ms > 0.f) best_read = std::max(best_read, (double)bytes / (ms * 1e-3) / 1e9);
+  }
+  *mfma_tflops = best_mfma;
+  *hbm_read_gbs = best_read;
   return NT_OK;
 }
 

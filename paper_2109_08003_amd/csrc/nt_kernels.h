@@ -189,6 +189,11 @@ hipError_t launch_fill_i32(int32_t *p, long n, int32_t v, hipStream_t s);
 // one wave that busy-waits for `ticks` periods of the 100 MHz wall clock (bounded); sink is never written
 hipError_t launch_spin(long ticks, int *sink, hipStream_t s);
 
+// Probes: `blocks` workgroups of four waves, each wave `iters` x 4 independent 32x32x16 fp16 MFMAs (2 * 32 * 32 * 16
+// flops each); a grid-stride read of `bytes` bytes (a multiple of 16).  sink is never written.
+hipError_t launch_probe_mfma(int iters, int blocks, float *sink, hipStream_t s);
+hipError_t launch_probe_read(const void *src, long bytes, float *sink, hipStream_t s);
+
 // Start of decoder step t for rows [0, rows_prev): (1) if t > 0, reduce the arg-max partials of
 // step t-1 and store the token in out[r*out_ld + t-1]; (2) for rows < rows_now: take the input
 // token (BOS at t = 0, forced[r*forced_ld + t] if forced, else the token just reduced),

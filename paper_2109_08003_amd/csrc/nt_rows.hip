@@ -203,6 +203,47 @@ hipError_t launch_spin(long ticks, int *sink, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ---- probes of what the machine reaches: a loop of independent MFMAs, and a streaming read ----------------------
+typedef _Float16 probe_half8 __attribute__((ext_vector_type(8)));
+typedef float probe_floatx16 __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float *sink) {
+  probe_half8 a, b;
+#pragma unroll
+  for (int e = 0; e < 8; e++) {
+    a[e] = (_Float16)(0.001f * (float)((threadIdx.x + e) & 15));
+    b[e] = (_Float16)(0.002f * (float)((threadIdx.x * 3 + e) & 7));
+  }
+  probe_floatx16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) acc[i][v] = 0.f;
+  for (int it = 0; it < iters; it++) {
+#pragma unroll
+    for (int i = 0; i < 4; i++) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[i], 0, 0, 0);
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; i++) t += acc[i][0] + acc[i][7];
+  if (t == -1.f) *sink = t;  // never true (the sums are non-negative): keeps the loop alive
+}
+__global__ __launch_bounds__(256) void probe_read_kernel(const float4 *src, long n4, float *sink) {
+  float t = 0.f;
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (long)gridDim.x * blockDim.x) {
+    const float4 v = src[i];
+    t += v.x + v.y + v.z + v.w;
+  }
+  if (t == 1.2345e33f) *sink = t;  // practically never: keeps the loads alive
+}
+hipError_t launch_probe_mfma(int iters, int blocks, float *sink, hipStream_t s) {
+  hipLaunchKernelGGL(probe_mfma_kernel, dim3(blocks), dim3(256), 0, s, iters, sink);
+  return hipGetLastError();
+}
+hipError_t launch_probe_read(const void *src, long bytes, float *sink, hipStream_t s) {
+  hipLaunchKernelGGL(probe_read_kernel, dim3(256 * 16), dim3(256), 0, s, (const float4 *)src, bytes / 16, sink);
+  return hipGetLastError();
+}
+
 template <int NE>
 __global__ __launch_bounds__(256) void step_begin_kernel(StepBeginArgs a) {
   const int lane = threadIdx.x & 63;
