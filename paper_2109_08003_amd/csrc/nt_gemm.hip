@@ -403,6 +403,8 @@ hipError_t launch_gemm(int a_mode, bool c_f32, const void *A, const void *A_lo, 
   if (M <= 0 || N <= 0) return hipSuccess;
   if (a_mode == A_PLANES && Wp && gemm_stream_supported(N, K) && e.n_split % 32 == 0)
     return launch_gemm_stream(c_f32, (const _Float16 *)A, (const _Float16 *)A_lo, lda, Wp, M, N, K, e, s, tail);
+  if (a_mode == A_PLANES && Wp && c_f32 && gemm_stream_k_supported(N, K) && e.n_split % 32 == 0)
+    return launch_gemm_stream_k(c_f32, (const _Float16 *)A, (const _Float16 *)A_lo, lda, Wp, M, N, K, e, s, tail);
   const int big_tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
   const bool mid = big_tiles < 2 * 256;  // fewer than two 128x128 tiles per CU: use the 64x64 variant
   dim3 grid(mid ? tile_grid((M + MID - 1) / MID, (N + MID - 1) / MID) : tile_grid((M + BM - 1) / BM, (N + BN - 1) / BN)),

@@ -39,7 +39,10 @@ bool gemm_stream_supported(int N, int K) { return (K == 256 || K == 512) && N % 
 // the biased variance of the centred values) and split into head/tail planes while it is written to the LDS, which
 // saves the separate LayerNorm kernel and the round trip of its output through memory.
 // TAIL = false: only the head plane of A is multiplied (11 significant bits: half the MFMA work and half the tile).
-template <int RB, int K, bool C_F32, bool LN, bool TAIL>
+// NC > 1: the contraction runs over NC * K columns of A in NC passes over the K-wide tile (K = 512, planes from memory):
+// between passes the tile is refilled behind a barrier while the weight ring keeps streaming, and every wave keeps the
+// accumulators of its one strip (N is 512 per column group) - the second matrix of an FFN, whose K is the FFN width.
+template <int RB, int K, bool C_F32, bool LN, bool TAIL, int NC>
 __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float16 *__restrict__ A_hi,
                                                                    const _Float16 *__restrict__ A_lo, long lda, int M,
                                                                    const _Float16 *__restrict__ Wp, int N, int col_groups,
@@ -54,6 +57,8 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   constexpr int SL = 8;
   constexpr int NOPS = (TAIL ? 2 : 1) * RB;
   static_assert(KS % SL == 0, "the ring of W slots must divide the k-steps of a strip");
+  static_assert(NC == 1 || (K == 512 && !LN), "several passes: 512-wide tiles of planes only");
+  constexpr int KST = NC * KS;  // k-steps of a whole strip
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int mt = blockIdx.x / col_groups, cg = blockIdx.x % col_groups;
@@ -61,7 +66,7 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   const int NS = N >> 6;
   const int sb0 = (int)((long)cg * NS / col_groups), sb1 = (int)((long)(cg + 1) * NS / col_groups);
 
-  const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void *)Wp, 0, NS * 64 * K * 2, 0x00020000);
+  const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void *)Wp, 0, NS * 64 * (NC * K) * 2, 0x00020000);
   const int wlane = lane * 16;
   auto wload = [&](int soff, int nb) -> half8 {
     u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(wrs, wlane + nb * 1024, soff, 0);
@@ -69,6 +74,20 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   };
 
   // ---- the A tile: global memory -> LDS.  Rows past M repeat row M - 1 (their results are never stored) ----
+  // planes, K = 512: one wave instruction moves one row of one plane (1 KiB) without passing through registers;
+  // pass c of NC takes columns c * K .. c * K + K - 1 of A
+  auto fill_planes = [&](int c) {
+#pragma unroll
+    for (int i = 0; i < ROWS / GS_WAVES; i++) {
+      const int R = wave + GS_WAVES * i;
+      const _Float16 *src = R >= TM ? A_lo : A_hi;
+      int m = m0 + (R % TM);
+      m = m < M ? m : M - 1;
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void *)(src + (long)m * lda + c * K + lane * 8),
+          (__attribute__((address_space(3))) void *)(sh + R * LD), 16, 0, RB == 2 ? 2 : 0);
+    }
+  };
   if constexpr (LN) {
     // a wave takes rows wave, wave + 8, ...; a lane holds NE consecutive elements of the row
     constexpr int NE = K / 64, RPW = TM / GS_WAVES;
@@ -149,15 +168,7 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
       if (TAIL) *(halfNE *)(sh + (R + TM) * LD + lane * NE) = lo;
     }
   } else if (K == 512) {
-#pragma unroll
-    for (int i = 0; i < ROWS / GS_WAVES; i++) {
-      const int R = wave + GS_WAVES * i;
-      const _Float16 *src = R >= TM ? A_lo : A_hi;
-      int m = m0 + (R % TM);
-      m = m < M ? m : M - 1;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + (long)m * lda + lane * 8),
-                                       (__attribute__((address_space(3))) void *)(sh + R * LD), 16, 0, RB == 2 ? 2 : 0);
-    }
+    fill_planes(0);
   } else {
     constexpr int CPR = K / 8, PER_T = ROWS * CPR / (GS_WAVES * 64);
     u32x4 fr[PER_T];
@@ -179,7 +190,7 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   int strip = sb0 + wave;
   const bool have = strip < sb1;
   if (have) {
-    const int sp = strip * (KS * 2048);
+    const int sp = strip * (KST * 2048);
 #pragma unroll
     for (int q = 0; q < SL - 1; q++) {
       wb[q][0] = wload(sp + q * 2048, 0);
@@ -210,10 +221,18 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
 #pragma unroll
   for (int op = 0; op < NOPS; op++) hf[op] = frag(op, 0);
 
+  if (NC > 1) {
+#pragma unroll
+    for (int rb = 0; rb < RB; rb++)
+#pragma unroll
+      for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) acc[rb][nb][v] = 0.f;
+  }
   for (; strip < sb1; strip += GS_WAVES) {
     const bool more = strip + GS_WAVES < sb1;
-    const int pcur = strip * (KS * 2048);
-    const int pnext = (more ? strip + GS_WAVES : strip) * (KS * 2048);
+    int pcur = strip * (KST * 2048);
+    const int pnext = (more ? strip + GS_WAVES : strip) * (KST * 2048);
     // bias and scale of the strip's columns, requested here so that the epilogue does not wait for them behind the
     // weight fragments in flight
     float bias[2] = {0.f, 0.f}, scl[2];
@@ -230,13 +249,15 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
 #pragma unroll
       for (int ks = 0; ks < KS; ks++) {
         const int tgt = ks + SL - 1;
-        const int pf = tgt < KS ? pcur + tgt * 2048 : pnext + (tgt - KS) * 2048;
+        // several passes: the ring simply runs on into the next pass's fragments of the same strip (past the last
+        // pass it reads the next strip, or zeros beyond the matrix: unused either way)
+        const int pf = (NC > 1 || tgt < KS) ? pcur + tgt * 2048 : pnext + (tgt - KS) * 2048;
         const int ksn = (ks + 1) % KS;
 #pragma unroll
         for (int op = 0; op < NO; op++) {
 #pragma unroll
           for (int nb = 0; nb < 2; nb++) {
-            if (ks == 0 && op < RB) {
+            if (NC == 1 && ks == 0 && op < RB) {
               const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
               acc[op % RB][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(hf[op], wb[ks % SL][nb], zero, 0, 0, 0);
             } else {
@@ -256,8 +277,23 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
         if (ks == SL) asm volatile("" ::"v"(bias_[0]), "v"(bias_[1]), "v"(scl_[0]), "v"(scl_[1]));
       }
     };
-    if (TAIL && strip * 64 >= e.tail_col0 && strip * 64 < e.tail_col1) k_loop(std::integral_constant<int, NOPS>{}, bias, scl);
-    else k_loop(std::integral_constant<int, RB>{}, bias, scl);
+    const bool with_tail = TAIL && strip * 64 >= e.tail_col0 && strip * 64 < e.tail_col1;
+#pragma unroll 1
+    for (int c = 0; c < NC; c++) {
+      if (NC > 1 && c > 0) {
+        // next pass: every wave is done with the tile, it is refilled, and the first fragments are read again
+        __syncthreads();
+        fill_planes(c);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+#pragma unroll
+        for (int op = 0; op < NOPS; op++) hf[op] = frag(op, 0);
+        pcur += KS * 2048;
+      }
+      // (the choice by output columns is for the single-pass form; a second instance of the loop here costs registers)
+      if (NC > 1 || with_tail) k_loop(std::integral_constant<int, NOPS>{}, bias, scl);
+      else k_loop(std::integral_constant<int, RB>{}, bias, scl);
+    }
     // ---- epilogue of the strip: acc[rb][nb][v] is C[m0 + rb*32 + (v/4)*8 + g*4 + v%4][strip*64 + nb*32 + li] ----
     // Addresses are a uniform 64-bit base per 32 x 32 block plus a 32-bit lane offset (n_split is a multiple of 32,
     // so a block never straddles the two destinations).
@@ -360,10 +396,10 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
   }
 }
 
-template <int RB, int K, bool C_F32, bool LN, bool TAIL>
+template <int RB, int K, bool C_F32, bool LN, bool TAIL, int NC = 1>
 static hipError_t gs_launch(const _Float16 *A, const _Float16 *A_lo, long lda, int M, const _Float16 *Wp, int N,
                             const GemmEpilogue &e, const GemmLayerNorm &ln, hipStream_t s) {
-  auto kern = gemm_stream_kernel<RB, K, C_F32, LN, TAIL>;
+  auto kern = gemm_stream_kernel<RB, K, C_F32, LN, TAIL, NC>;
   const size_t lds = (size_t)(TAIL ? 64 : 32) * RB * (K + 8) * 2;
   // raising the dynamic LDS limit is per kernel, once per process (several host threads may get here at once)
   static std::once_flag once;
@@ -381,6 +417,7 @@ static hipError_t gs_launch(const _Float16 *A, const _Float16 *A_lo, long lda, i
       col_groups = cg;
       break;
     }
+  if (NC > 1) col_groups = NS / GS_WAVES;  // several passes: exactly one strip per wave
   hipLaunchKernelGGL(kern, dim3(row_tiles * col_groups), dim3(GS_WAVES * 64), lds, s, A, A_lo, lda, M, Wp, N, col_groups, e,
                      ln);
   return hipGetLastError();
@@ -399,6 +436,24 @@ static hipError_t gs_dispatch(bool c_f32, const _Float16 *A, const _Float16 *A_l
   NT_GS_CASE(1, 512, true) NT_GS_CASE(1, 512, false) NT_GS_CASE(2, 512, true) NT_GS_CASE(2, 512, false)
   NT_GS_CASE(1, 256, true) NT_GS_CASE(1, 256, false) NT_GS_CASE(2, 256, true) NT_GS_CASE(2, 256, false)
 #undef NT_GS_CASE
+  return hipErrorInvalidValue;
+}
+
+// K = 1024 / 2048 in passes over a 512-wide tile; N a multiple of 512 (one strip per wave and column group)
+bool gemm_stream_k_supported(int N, int K) { return (K == 1024 || K == 2048) && N >= 512 && N % 512 == 0; }
+
+hipError_t launch_gemm_stream_k(bool c_f32, const _Float16 *A, const _Float16 *A_lo, long lda, const _Float16 *Wp, int M,
+                                int N, int K, const GemmEpilogue &e, hipStream_t s, bool tail) {
+  if (M <= 0 || N <= 0) return hipSuccess;
+  if (!gemm_stream_k_supported(N, K) || e.n_split % 32 != 0) return hipErrorInvalidValue;
+  tail = tail && A_lo != nullptr;
+  const GemmLayerNorm ln{};
+#define NT_GSK_CASE(NC_, CF_, TL_)                        \
+  if (K == 512 * NC_ && c_f32 == CF_ && tail == TL_)      \
+    return M <= 8192 ? gs_launch<1, 512, CF_, false, TL_, NC_>(A, A_lo, lda, M, Wp, N, e, ln, s) \
+                     : gs_launch<2, 512, CF_, false, TL_, NC_>(A, A_lo, lda, M, Wp, N, e, ln, s);
+  NT_GSK_CASE(2, true, true) NT_GSK_CASE(2, true, false) NT_GSK_CASE(4, true, true) NT_GSK_CASE(4, true, false)
+#undef NT_GSK_CASE
   return hipErrorInvalidValue;
 }
 

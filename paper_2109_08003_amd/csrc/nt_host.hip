@@ -640,7 +640,7 @@ int nt_load_weights(const nt_config *cfg, const void *h_blob_fp16, size_t blob_b
     o = pk.reserve((size_t)d * F * 2);
     Packer::transpose(W2, F, d, (_Float16 *)(pk.img.data() + o));
     fixes.push_back({o, (const void **)&f.W2});
-    if (nt::gemm_stream_supported(d, F)) {
+    if (nt::gemm_stream_supported(d, F) || nt::gemm_stream_k_supported(d, F)) {
       size_t op = pk.reserve(nt::vocab_pack_bytes(d, F));
       nt::vocab_pack((const _Float16 *)(pk.img.data() + o), d, F, (_Float16 *)(pk.img.data() + op));
       fixes.push_back({op, (const void **)&f.W2_p});
@@ -815,7 +815,7 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
       nt::GemmEpilogue f2;
       f2.bias = L.ffn.b2; f2.resid = m->x; f2.ldr = d; f2.dst0 = m->x; f2.ld0 = d; f2.n_split = d;
       KT(K_GEMM_ENC_FFN, gemm_bytes(Md, F, dd, ea, 4, true), 2 * Md * dd * F,
-         nt::launch_gemm(amode, true, m->u_enc, lo_of(m->u_enc, lo_F), F, L.ffn.W2, M, d, F, f2, s));
+         nt::launch_gemm(amode, true, m->u_enc, lo_of(m->u_enc, lo_F), F, L.ffn.W2, M, d, F, f2, s, L.ffn.W2_p));
     }
   }
   // The encoder output exists only inside the cross K|V projections when its LayerNorm is fused there; the debug

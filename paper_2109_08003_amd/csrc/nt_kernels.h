@@ -63,6 +63,11 @@ struct GemmLayerNorm {
 };
 bool gemm_stream_supported(int N, int K);
 // C = LayerNorm(X) * Wt^T: X [M][ldx] fp32 is normalised and split into planes while the tile is loaded
+// The same with K = 1024 / 2048 (an FFN's second matrix), fp32 results: NC passes over a 512-wide tile of the planes,
+// Wp = vocab_pack of Wt [N][K]; N a multiple of 512.
+bool gemm_stream_k_supported(int N, int K);
+hipError_t launch_gemm_stream_k(bool c_f32, const _Float16 *A, const _Float16 *A_lo, long lda, const _Float16 *Wp, int M,
+                                int N, int K, const GemmEpilogue &e, hipStream_t s, bool tail = true);
 // tail = false: only the head plane of A enters the product (fp16 activations: half the matrix-core work)
 hipError_t launch_gemm_stream_ln(bool c_f32, const float *X, long ldx, const GemmLayerNorm &ln, const _Float16 *Wp, int M,
                                  int N, int K, const GemmEpilogue &e, hipStream_t s, bool tail = true);
