@@ -297,10 +297,12 @@ int nt_debug_teacher_forced_logits(nt_model *m, const int32_t *d_tgt_in, int32_t
  *                                     matrix-core work): bit 0 LayerNorm -> Q|K|V, bit 1 attention context -> output
  *                                     projection, bit 2 final LayerNorm -> cross-attention K|V, bit 3 first FFN
  *                                     matrix; with bit 0 clear, bits 4 / 5 / 6 select the q / k / v columns of
- *                                     Q|K|V alone (a contiguous group).  The library's default is the plan its
- *                                     precision study adopted: the v columns alone for the one-head student
- *                                     without FFN, every tail for other encoders.
- * Errors: NT_EINVAL (null model, value other than 0 / 1, mask beyond 7 bits).
+ *                                     Q|K|V alone (a contiguous group); bit 7: the scaled query and the key are
+ *                                     stored as plain fp16 (sentences of at most 128 tokens, one head, width
+ *                                     512).  The library's default is the plan its precision study adopted: the
+ *                                     v columns alone plus bit 7 for the one-head student without FFN, every
+ *                                     tail for other encoders.
+ * Errors: NT_EINVAL (null model, value other than 0 / 1, mask beyond 8 bits).
  */
 int nt_debug_set_vocab_tiled(nt_model *m, int on);
 int nt_debug_set_cert_distrust(nt_model *m, int on);

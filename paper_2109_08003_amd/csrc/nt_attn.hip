@@ -306,8 +306,10 @@ __device__ __forceinline__ void split8u(const float *f, half8 &hi, half8 &lo) {
   }
 }
 
-template <int DH, int NKB>
-__global__ __launch_bounds__(256, NKB == 1 ? 3 : NKB == 2 ? 2 : 1) void enc_attention_wave_kernel(const float *qkv, const int32_t *len, _Float16 *ctx,
+// QK16: the scaled query and the key come as plain fp16 from qk16 [B*S, 2d] (q | k) and the value as fp32 from
+// qkv = v [B*S, d]; one MFMA per score product.
+template <int DH, int NKB, bool QK16>
+__global__ __launch_bounds__(256, NKB == 1 ? 3 : NKB == 2 ? 2 : 1) void enc_attention_wave_kernel(const float *qkv, const _Float16 *qk16, const int32_t *len, _Float16 *ctx,
                                                                  long ctx_lo_offset, int B, int S, int d, int heads,
                                                                  int q_tiles) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, li = lane & 31, g = lane >> 5;
@@ -316,7 +318,7 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : NKB == 2 ? 2 : 1) void enc_atte
   if (unit >= (long)B * heads * q_tiles) return;
   const int qt = (int)(unit % q_tiles), h = (int)((unit / q_tiles) % heads), b = (int)(unit / ((long)q_tiles * heads));
   const int L = __builtin_amdgcn_readfirstlane(len[b]), q0 = qt * 32;
-  const long row0 = (long)b * S, ld = 3L * d;
+  const long row0 = (long)b * S, ld = QK16 ? (long)d : 3L * d;  // row stride of the fp32 array (v alone, or q|k|v)
   const int hoff = h * DH;
   if (q0 >= L) {  // padding queries: defined output, no work
     for (int i = lane; i < 32 * DH; i += 64) {
@@ -336,12 +338,32 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : NKB == 2 ? 2 : 1) void enc_atte
   for (int kb = 0; kb < NKB; kb++)
 #pragma unroll
     for (int v = 0; v < 16; v++) sc[kb][v] = 0.f;
+  if constexpr (QK16) {
+    const _Float16 *qp16 = qk16 + (row0 + min(q0 + li, L - 1)) * (2L * d) + hoff + g * 32;
+#pragma nounroll
+    for (int c = 0; c < DH / 64; c++) {
+      half8 qh[4];
+#pragma unroll
+      for (int u = 0; u < 4; u++) qh[u] = *(const half8 *)(qp16 + c * 64 + u * 8);  // one 64-byte half line
+#pragma unroll
+      for (int kb = 0; kb < NKB; kb++) {
+        if (kb < nkb) {
+          const _Float16 *kp16 = qk16 + (row0 + min(kb * 32 + li, L - 1)) * (2L * d) + d + hoff + g * 32 + c * 64;
+          half8 kh[4];
+#pragma unroll
+          for (int u = 0; u < 4; u++) kh[u] = *(const half8 *)(kp16 + u * 8);
+#pragma unroll
+          for (int u = 0; u < 4; u++) sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kh[u], qh[u], sc[kb], 0, 0, 0);
+        }
+      }
+    }
+  }
   const float *qp = qkv + (row0 + min(q0 + li, L - 1)) * ld + hoff + g * 32;
   // A lane takes its 32 consecutive values of a 64-wide slice (one whole 128-byte line) in one go: taking them in
   // two halves, the second half a loop iteration later, was measured to fetch 17 % more from HBM (the line is
   // evicted in between) for no gain in time.
 #pragma nounroll
-  for (int c = 0; c < DH / 64; c++) {
+  for (int c = 0; c < (QK16 ? 0 : DH / 64); c++) {
     float f[32];
 #pragma unroll
     for (int u = 0; u < 8; u++) *(float4 *)(f + 4 * u) = *(const float4 *)(qp + c * 64 + u * 4);
@@ -403,7 +425,7 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : NKB == 2 ? 2 : 1) void enc_atte
   // With two key blocks the V values of the next block are requested before the MFMAs and stores of the current one
   // (with one block nothing is gained and the registers of the third wave per SIMD are exceeded; beyond two the
   // registers do not allow it).
-  const char *vbase = (const char *)(qkv + row0 * ld + 2 * d + hoff);
+  const char *vbase = (const char *)(qkv + row0 * ld + (QK16 ? 0 : 2 * d) + hoff);
   char *obase = (char *)(ctx + row0 * d + hoff);
   constexpr bool PREFETCH = NKB == 2;
   float fv[PREFETCH ? 2 : 1][NKB][2][8];
@@ -474,16 +496,16 @@ __global__ __launch_bounds__(256, NKB == 1 ? 3 : NKB == 2 ? 2 : 1) void enc_atte
   }
 }
 
-template <int DH>
+template <int DH, bool QK16 = false>
 static hipError_t enc_attention_wave_launch(const float *qkv, const int32_t *len, _Float16 *ctx, long ctx_lo_offset,
-                                            int B, int S, int d, int heads, hipStream_t s) {
+                                            int B, int S, int d, int heads, hipStream_t s, const _Float16 *qk16 = nullptr) {
   const int q_tiles = (S + 31) / 32;
   const long units = (long)B * heads * q_tiles;
   dim3 grid((unsigned)((units + 3) / 4)), block(256);
 #define NT_WAVE_CASE(NKB)                                                                                          \
   case NKB:                                                                                                        \
-    hipLaunchKernelGGL((enc_attention_wave_kernel<DH, NKB>), grid, block, 0, s, qkv, len, ctx, ctx_lo_offset, B, S, d, \
-                       heads, q_tiles);                                                                            \
+    hipLaunchKernelGGL((enc_attention_wave_kernel<DH, NKB, QK16>), grid, block, 0, s, qkv, qk16, len, ctx, ctx_lo_offset, \
+                       B, S, d, heads, q_tiles);                                                                   \
     break;
   switch (q_tiles) {
     NT_WAVE_CASE(1)
@@ -494,6 +516,17 @@ static hipError_t enc_attention_wave_launch(const float *qkv, const int32_t *len
   }
 #undef NT_WAVE_CASE
   return hipGetLastError();
+}
+
+bool enc_attention_qk16_supported(int S, int d, int heads, const float *rk) {
+  return !rk && S <= 128 && heads == 1 && d == 512;
+}
+
+hipError_t launch_enc_attention_qk16(const _Float16 *qk, const float *v, const int32_t *len, void *ctx, long ctx_lo_offset,
+                                     int B, int S, int d, int heads, hipStream_t s) {
+  if (B <= 0 || S <= 0) return hipSuccess;
+  if (!enc_attention_qk16_supported(S, d, heads, nullptr)) return hipErrorInvalidValue;
+  return enc_attention_wave_launch<512, true>(v, len, (_Float16 *)ctx, ctx_lo_offset, B, S, d, heads, s, qk);
 }
 
 hipError_t launch_enc_attention(const void *qkv, bool f32, const int32_t *len, void *ctx, long ctx_lo_offset, int B,

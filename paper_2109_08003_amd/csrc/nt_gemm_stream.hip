@@ -307,8 +307,10 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
     // stores of the block before it, so that waiting for them does not wait for those stores.
     constexpr int CE = C_F32 ? 4 : 2;
     constexpr int NBLK = 2 * RB;  // 32 x 32 blocks of the strip: block = nb * RB + rb
+    // ce: bytes per element of the block's destination (fp32 kernels may write their first destination as plain
+    // fp16: GemmEpilogue::first_f16; the choice is uniform over a block)
     auto block_at = [&](int blk, char *&dblock, const char *&rblock, unsigned &dlane, unsigned &rlane, long &ld,
-                        int &mb) {
+                        int &mb, int &ce) {
       const int nb = blk / RB, rb = blk % RB;
       const int nbase = strip * 64 + nb * 32;  // uniform
       const bool first = nbase < e.n_split;
@@ -316,9 +318,10 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
       ld = first ? e.ld0 : e.ld1;
       const int ncb = first ? nbase : nbase - e.n_split;
       mb = m0 + rb * 32;  // uniform
-      dblock = dst + ((long)mb * ld + ncb) * CE;
+      ce = (C_F32 && e.first_f16 && first) ? 2 : CE;
+      dblock = dst + ((long)mb * ld + ncb) * ce;
       rblock = (const char *)e.resid + ((long)mb * e.ldr + nbase) * 4;
-      dlane = (unsigned)((g * 4 * ld + li) * CE);
+      dlane = (unsigned)((g * 4 * ld + li) * ce);
       rlane = (unsigned)((g * 4 * e.ldr + li) * 4);
       // the per-row offsets derived from these do not depend on the strip; computed once and kept, they would hold
       // dozens of registers through the main loop
@@ -329,8 +332,10 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
       if (e.relu) val = fmaxf(val, 0.f);
       return val + r;
     };
-    auto put = [&](char *at_, float val) {
-      if (C_F32) {
+    auto put = [&](char *at_, float val, int ce) {
+      if (C_F32 && ce == 2) {
+        *(_Float16 *)at_ = (_Float16)val;
+      } else if (C_F32) {
         if (RB == 2) __builtin_nontemporal_store(val, (float *)at_);
         else *(float *)at_ = val;
       } else {
@@ -345,8 +350,8 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
     if (__builtin_expect(m0 + TM <= M && RESID == (e.resid != nullptr), 1)) {
       float res[RESID ? 2 : 1][16];
       auto request = [&](int blk) {
-        char *dblock; const char *rblock; unsigned dlane, rlane; long ld; int mb;
-        block_at(blk, dblock, rblock, dlane, rlane, ld, mb);
+        char *dblock; const char *rblock; unsigned dlane, rlane; long ld; int mb, ce;
+        block_at(blk, dblock, rblock, dlane, rlane, ld, mb, ce);
 #pragma unroll
         for (int v = 0; v < 16; v++) {
           const int r = (v >> 2) * 8 + (v & 3);
@@ -360,12 +365,20 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
         __builtin_amdgcn_sched_barrier(0);  // one block at a time: bounds the loads and addresses in flight
         if (RESID && blk + 1 < NBLK) request(blk + 1);
         __builtin_amdgcn_sched_barrier(0);
-        char *dblock; const char *rblock; unsigned dlane, rlane; long ld; int mb;
-        block_at(blk, dblock, rblock, dlane, rlane, ld, mb);
+        char *dblock; const char *rblock; unsigned dlane, rlane; long ld; int mb, ce;
+        block_at(blk, dblock, rblock, dlane, rlane, ld, mb, ce);
+        if (C_F32 && ce == 2) {  // uniform: the stores of a block stay straight-line code of one kind
 #pragma unroll
-        for (int v = 0; v < 16; v++) {
-          const int r = (v >> 2) * 8 + (v & 3);
-          put(dblock + (dlane + (unsigned)(r * ld * CE)), finish(blk, v, RESID ? res[blk & 1][v] : 0.f));
+          for (int v = 0; v < 16; v++) {
+            const int r = (v >> 2) * 8 + (v & 3);
+            put(dblock + (dlane + (unsigned)(r * ld * 2)), finish(blk, v, RESID ? res[blk & 1][v] : 0.f), 2);
+          }
+        } else {
+#pragma unroll
+          for (int v = 0; v < 16; v++) {
+            const int r = (v >> 2) * 8 + (v & 3);
+            put(dblock + (dlane + (unsigned)(r * ld * CE)), finish(blk, v, RESID ? res[blk & 1][v] : 0.f), CE);
+          }
         }
       }
     } else {
@@ -373,8 +386,8 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
 #pragma unroll
       for (int blk = 0; blk < NBLK; blk++) {
         __builtin_amdgcn_sched_barrier(0);
-        char *dblock; const char *rblock; unsigned dlane, rlane; long ld; int mb;
-        block_at(blk, dblock, rblock, dlane, rlane, ld, mb);
+        char *dblock; const char *rblock; unsigned dlane, rlane; long ld; int mb, ce;
+        block_at(blk, dblock, rblock, dlane, rlane, ld, mb, ce);
         // read the 16 residual values of the block first, then compute and store
         float res[16];
 #pragma unroll
@@ -386,7 +399,7 @@ __global__ __launch_bounds__(GS_WAVES * 64) void gemm_stream_kernel(const _Float
         for (int v = 0; v < 16; v++) {
           const int r = (v >> 2) * 8 + (v & 3);
           if (mb + r + g * 4 >= M) continue;
-          put(dblock + (dlane + (unsigned)(r * ld * CE)), finish(blk, v, res[v]));
+          put(dblock + (dlane + (unsigned)(r * ld * ce)), finish(blk, v, res[v]), ce);
         }
       }
       // Nothing of this path may be left in flight at the end of the iteration: what is pending here (loads into

@@ -88,7 +88,9 @@ constexpr size_t kEncElt = kEncF32 ? 4 : 2, kCrossElt = kCrossF32 ? 4 : 2;
 // (a third of the Q|K|V projection: 1.33 x the matrix-core work of plain fp16 instead of 2 x).  That study is the
 // student's (one head, no FFN); encoders with several heads or an FFN keep every tail: with the student's plan the
 // ablation model's 16,384-sentence test fell from 300 to 297 of 302 audited sentences, below its 99 % bar.
-constexpr unsigned kEncTailsStudent = 64u, kEncTailsAll = 15u;
+// On top of it the student's scaled query and key are stored as plain fp16 and its attention scores take one MFMA
+// per product instead of three (bit 7): 13-14 differing translations of 4,096 (0.33 %) for +2.6 % words/s.
+constexpr unsigned kEncTailsStudent = 64u | 128u, kEncTailsAll = 15u;
 
 // Launch `call`; when timing of family `id` is on, bracket it with two events on the stream and
 // note the algorithmic bytes and flops of this launch.
@@ -206,7 +208,7 @@ struct nt_model {
   bool kv_i16 = false;
   // which encoder projections multiply the tail plane of their activations as well (bit 0: LayerNorm -> Q|K|V,
   // bit 1: attention context -> output projection, bit 2: final LayerNorm -> cross K|V, bit 3: the FFN's first matrix;
-  // with bit 0 clear, bits 4 / 5 / 6: the q / k / v columns of Q|K|V alone)
+  // with bit 0 clear, bits 4 / 5 / 6: the q / k / v columns of Q|K|V alone; bit 7: q and k stored as plain fp16)
   unsigned enc_tails = kEncTailsAll;
   std::vector<float *> cross_sc, self_sc;  // per decoder layer [Mt,2] / [self_positions,2] scales
   float *z = nullptr, *a32 = nullptr, *q32 = nullptr, *ctx32 = nullptr, *u32 = nullptr;  // [Br, d|F]
@@ -453,7 +455,7 @@ int nt_debug_set_vocab_tiled(nt_model *m, int on) {
 }
 
 int nt_debug_set_encoder_tails(nt_model *m, uint32_t mask) {
-  if (!m || mask > 127u) return fail(NT_EINVAL, "null model or mask beyond 7 bits");
+  if (!m || mask > 255u) return fail(NT_EINVAL, "null model or mask beyond 8 bits");
   m->enc_tails = mask;
   for (nt_model *ln : m->lanes) ln->enc_tails = mask;
   return NT_OK;
@@ -782,8 +784,15 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
       while (g1 > g0 && !((sel >> (g1 - 1)) & 1u)) g1--;
       e.tail_col0 = g0 * d; e.tail_col1 = g1 * d;
     }
+    // bit 7 of the plan: the scaled query and the key leave the projection as plain fp16 (q | k in one array, the
+    // value as fp32 behind it in the same buffer) and the attention kernel multiplies them with one MFMA per product
+    const bool qk16 = (m->enc_tails & 128u) && kEncF32 && fused_ln(L.self.Wqkv_p, 3 * d) &&
+                      nt::enc_attention_qk16_supported(S, d, H, L.self.rk);
+    _Float16 *qk_half = (_Float16 *)m->qkv;
+    float *v_f32 = (float *)((char *)m->qkv + (size_t)m->max_tokens * 2 * d * 2);
+    if (qk16) { e.first_f16 = 1; e.dst0 = qk_half; e.ld0 = 2 * d; e.n_split = 2 * d; e.dst1 = v_f32; e.ld1 = d; }
     if (fused_ln(L.self.Wqkv_p, 3 * d)) {
-      KT(K_GEMM_ENC_QKV, gemm_bytes(Md, dd, 3 * dd, 4, ea, false), 6 * Md * dd * dd,
+      KT(K_GEMM_ENC_QKV, gemm_bytes(Md, dd, 3 * dd, 4, qk16 ? 8.0 / 3.0 : ea, false), 6 * Md * dd * dd,
          nt::launch_gemm_stream_ln(true, m->x, d, nt::GemmLayerNorm{L.ln1.g, L.ln1.b, lne}, L.self.Wqkv_p, M, 3 * d, d, e, s,
                                    (m->enc_tails & 0x71u) != 0));
     } else {
@@ -792,6 +801,10 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
       KT(K_GEMM_ENC_QKV, gemm_bytes(Md, dd, 3 * dd, ea, ea, false), 6 * Md * dd * dd,
          nt::launch_gemm(amode, kEncF32, m->a_enc, lo_of(m->a_enc, lo_d), d, L.self.Wqkv, M, 3 * d, d, e, s, L.self.Wqkv_p));
     }
+    if (qk16)
+      KT(K_ATTN_ENC, Md * dd * (2 * 2 + 4 + 4), 4.0 * B * S * S * dd,
+         nt::launch_enc_attention_qk16(qk_half, v_f32, m->len, m->ctx_enc, lo_d, B, S, d, H, s));
+    else
     KT(K_ATTN_ENC, Md * 4 * dd * ea, 4.0 * B * S * S * dd,
        nt::launch_enc_attention(m->qkv, kEncF32, m->len, m->ctx_enc, lo_d, B, S, d, H, L.self.rk, c.rpr_clip, s));
     nt::GemmEpilogue o;

@@ -40,6 +40,7 @@ struct GemmEpilogue {
   // streaming kernels with a head/tail A operand: only the strips of 64 output columns that start in
   // [tail_col0, tail_col1) multiply the tail plane too (the others see fp16 activations: half the MFMA work)
   int tail_col0 = 0, tail_col1 = 1 << 30;
+  int first_f16 = 0;       // streaming kernels with fp32 destinations: the first destination is plain fp16 instead
   long dst_lo_offset = 0;  // fp16 destinations only: if != 0 the tail fp16(v - fp16(v)) is also stored, this many
                            // elements after the head (the result becomes a head/tail plane pair)
 };
@@ -308,6 +309,12 @@ hipError_t launch_eos_step_begin(const EosStepArgs &a, hipStream_t s);
 // len get weight exactly 0; query rows >= len get 0.  rk: optional relative keys [2*clip+1, dh].
 hipError_t launch_enc_attention(const void *qkv, bool f32, const int32_t *len, void *ctx, long ctx_lo_offset, int B,
                                 int S, int d, int heads, const float *rk, int clip, hipStream_t s);
+// The register-resident form with the scaled query and the key as plain fp16 (qk [B*S, 2d]: q | k) and the value as
+// fp32 (v [B*S, d]); sentences of at most 128 tokens, no relative keys (enc_attention_qk16_supported).  Scores then
+// take one MFMA per product instead of three; probabilities, values and the context keep head + tail.
+bool enc_attention_qk16_supported(int S, int d, int heads, const float *rk);
+hipError_t launch_enc_attention_qk16(const _Float16 *qk, const float *v, const int32_t *len, void *ctx, long ctx_lo_offset,
+                                     int B, int S, int d, int heads, hipStream_t s);
 
 // Single-query attention against a cache, one query per (row, head).
 //   q [rows, d] fp32 (scaled); ctx [rows, d] fp32.
