@@ -300,8 +300,8 @@ int nt_debug_teacher_forced_logits(nt_model *m, const int32_t *d_tgt_in, int32_t
  *                                     Q|K|V alone (a contiguous group); bit 7: the scaled query and the key are
  *                                     stored as plain fp16 (sentences of at most 128 tokens, one head, width
  *                                     512).  The library's default is the plan its precision study adopted: the
- *                                     v columns alone plus bit 7 for the one-head student without FFN, every
- *                                     tail for other encoders.
+ *                                     v columns, the output projection and bit 7 for the one-head student
+ *                                     without FFN, every tail for other encoders.
  * Errors: NT_EINVAL (null model, value other than 0 / 1, mask beyond 8 bits).
  */
 int nt_debug_set_vocab_tiled(nt_model *m, int on);

@@ -69,12 +69,15 @@ int static_scratch_for_current_device(unsigned char **out) {
 
 // Precision plan.  The greedy arg-max is decided by logit gaps that are often below 1e-2, so
 // activations are kept at fp32 in HBM and enter the fp16 MFMA units split into head + tail.
-//   kEncF32:   encoder LayerNorm output, q/k/v, attention context and encoder output are fp32.
-//   kCrossF32: the cross-attention key/value cache is fp32 (else fp16).
-// The decoder side (activations and self-attention cache) is always fp32.
+//   kEncF32:   encoder LayerNorm output, q/k/v, attention context and encoder output are fp32 (which tail planes
+//              are then multiplied, and whether q and k are stored as fp16, is the plan in nt_model::enc_tails).
+//   kCrossF32: the cross-attention key/value cache is fp32 (else fp16), where it is not kept as 16-bit integers.
+// The decoder's activations are always fp32; its caches are 16-bit integers with a scale per vector for one-head
+// decoders of width 256 / 512 (nt_model::kv_i16), else fp32 (self) and fp16 (cross).
 constexpr bool kEncF32 = true;
 constexpr bool kCrossF32 = false;
-// Decoder projections with at most this many active rows use the one-round-trip kernel.
+// Model widths without the fused decoder kernels: projections with at most this many active rows use the
+// one-round-trip kernel.
 constexpr int kSkinnyMaxRows = 128;
 // The output projection uses the certified single-pass arg-max from this many active rows on; below,
 // the step is bound by the weight stream and the two-plane kernel costs the same.
@@ -82,15 +85,16 @@ constexpr int kCertMinRows = 512;
 // Batches nt_translate_batch keeps in flight when the configuration does not say (pipeline_lanes = 0).
 constexpr int kDefaultLanes = 4;
 constexpr size_t kEncElt = kEncF32 ? 4 : 2, kCrossElt = kCrossF32 ? 4 : 2;
-// Encoder precision plan (measured on the 4,096 paper-shaped sentences against the oracle, translations that differ):
-// every tail 4-5; none 20-21; tail on the q / k / v columns of the Q|K|V projection alone 19 / 21 / 10; the tails of
-// the output projection and of the cross K|V projection change nothing.  Adopted: the tail plane enters the V columns
-// (a third of the Q|K|V projection: 1.33 x the matrix-core work of plain fp16 instead of 2 x).  That study is the
-// student's (one head, no FFN); encoders with several heads or an FFN keep every tail: with the student's plan the
-// ablation model's 16,384-sentence test fell from 300 to 297 of 302 audited sentences, below its 99 % bar.
-// On top of it the student's scaled query and key are stored as plain fp16 and its attention scores take one MFMA
-// per product instead of three (bit 7): 13-14 differing translations of 4,096 (0.33 %) for +2.6 % words/s.
-constexpr unsigned kEncTailsStudent = 64u | 128u, kEncTailsAll = 15u;
+// Encoder precision plan (measured on the 4,096 paper-shaped sentences against the oracle, translations that differ,
+// with the 16-bit integer decoder caches): every tail 4-5; none 20-21; in the Q|K|V projection the tail on the q / k / v
+// columns alone 19 / 21 / 10; the tail of the cross K|V projection changes nothing; without the tail of the attention
+// output projection 27-29 instead of 13-14 (+1.6 % words/s: not taken).  Adopted for the student (one head, no FFN):
+// the tail plane enters the V columns (a third of the Q|K|V projection: 1.33 x the matrix-core work of plain fp16
+// instead of 2 x) and the output projection (bit 1); the scaled query and the key are stored as plain fp16 and the
+// attention scores take one MFMA per product instead of three (bit 7): together 13-14 of 4,096 (0.33 %).  Encoders
+// with several heads or an FFN keep every tail: with the student's plan the ablation model's 16,384-sentence test fell
+// from 300 to 297 of 302 audited sentences, below its 99 % bar.
+constexpr unsigned kEncTailsStudent = 2u | 64u | 128u, kEncTailsAll = 15u;
 
 // Launch `call`; when timing of family `id` is on, bracket it with two events on the stream and
 // note the algorithmic bytes and flops of this launch.
@@ -810,7 +814,8 @@ int nt_encode(nt_model *m, const int32_t *d_src, const int32_t *d_len, int32_t B
     nt::GemmEpilogue o;
     o.bias = L.self.bo; o.resid = m->x; o.ldr = d; o.dst0 = m->x; o.ld0 = d; o.n_split = d;
     KT(K_GEMM_ENC_O, gemm_bytes(Md, dd, dd, ea, 4, true), 2 * Md * dd * dd,
-       nt::launch_gemm(amode, true, m->ctx_enc, lo_of(m->ctx_enc, lo_d), d, L.self.Wo, M, d, d, o, s, L.self.Wo_p));
+       nt::launch_gemm(amode, true, m->ctx_enc, lo_of(m->ctx_enc, lo_d), d, L.self.Wo, M, d, d, o, s, L.self.Wo_p,
+                       (m->enc_tails & 2u) != 0));
     if (F > 0) {
       nt::GemmEpilogue f1;
       f1.bias = L.ffn.b1; f1.relu = 1; f1.dst0 = m->u_enc; f1.ld0 = F; f1.n_split = F;
