@@ -15,9 +15,9 @@
 //
 // A wave owns a query row (or, for small batches, four waves share it and merge); lane l holds elements
 // l * NE .. l * NE + NE - 1 of every vector, so a wave instruction reads one whole vector, fully coalesced.  Keys are
-// taken eight at a time: eight partial dot products per lane are reduced with a reduce-scatter butterfly (ten
-// exchanges for eight keys instead of six per key), the eight scores become wave-uniform, and the online softmax
-// rescales once per block.  The next block's vectors are requested before the current block is used.
+// taken four at a time: the partial dot products of a lane are reduced with a reduce-scatter butterfly (seven
+// exchanges for four keys instead of six per key), the scores become wave-uniform, and the online softmax rescales
+// once per block.
 //
 // Self-attention: the newest key/value pair arrives as fp32 from the projection (kv_new), is used at full precision,
 // and is appended to the cache in integer form by this kernel.
@@ -27,7 +27,11 @@
 
 namespace nt {
 
-constexpr int A16_NK = 8;  // keys per block
+// Keys per block.  Four, with the block's vectors requested right before their use, keeps the kernel at 80-100
+// registers: measured on the whole job (four pipeline lanes) +1.2 % over blocks of eight with the next block
+// requested ahead (220-250 registers), which is faster alone but leaves no room for its waves beside the workgroups
+// of another lane's output projection; forcing 64 registers (spills) was 2 % slower than either.
+constexpr int A16_NK = 4;
 
 bool attn_i16_supported(int d, int heads, int clip) { return heads == 1 && clip == 0 && (d == 256 || d == 512); }
 
@@ -182,29 +186,50 @@ __global__ __launch_bounds__(256) void attn_decode_i16_kernel(AttnI16Args a) {
       for (int e = 0; e < NE; e++) s += q[e] * (float)b.k[i][e];
       p[i] = s;
     }
-    // reduce-scatter: after the exchanges over lane bits 5, 4, 3 a lane holds the sum over those bits of the key
-    // numbered by them; three more exchanges complete it.  Lanes 8 i .. 8 i + 7 then hold the dot product of key i.
-    float r4[4], r2[2], r1;
-    {
-      const bool up = lane & 32;
+    // reduce-scatter: after the exchanges over the top lane bits a lane holds the sum over those bits of the key
+    // numbered by them; the remaining exchanges complete it.  Lanes (64 / NK) i .. (64 / NK) (i + 1) - 1 then hold
+    // the dot product of key i.
+    float r1;
+    if constexpr (NK == 8) {
+      float r4[4], r2[2];
+      {
+        const bool up = lane & 32;
 #pragma unroll
-      for (int i = 0; i < 4; i++) {
-        const float send = up ? p[i] : p[i + 4], keep = up ? p[i + 4] : p[i];
-        r4[i] = keep + __shfl_xor(send, 32, 64);
+        for (int i = 0; i < 4; i++) {
+          const float send = up ? p[i] : p[i + 4], keep = up ? p[i + 4] : p[i];
+          r4[i] = keep + __shfl_xor(send, 32, 64);
+        }
       }
-    }
-    {
-      const bool up = lane & 16;
+      {
+        const bool up = lane & 16;
 #pragma unroll
-      for (int i = 0; i < 2; i++) {
-        const float send = up ? r4[i] : r4[i + 2], keep = up ? r4[i + 2] : r4[i];
-        r2[i] = keep + __shfl_xor(send, 16, 64);
+        for (int i = 0; i < 2; i++) {
+          const float send = up ? r4[i] : r4[i + 2], keep = up ? r4[i + 2] : r4[i];
+          r2[i] = keep + __shfl_xor(send, 16, 64);
+        }
       }
-    }
-    {
-      const bool up = lane & 8;
-      const float send = up ? r2[0] : r2[1], keep = up ? r2[1] : r2[0];
-      r1 = keep + __shfl_xor(send, 8, 64);
+      {
+        const bool up = lane & 8;
+        const float send = up ? r2[0] : r2[1], keep = up ? r2[1] : r2[0];
+        r1 = keep + __shfl_xor(send, 8, 64);
+      }
+    } else {
+      static_assert(NK == 4, "blocks of 4 or 8 keys");
+      float r2[2];
+      {
+        const bool up = lane & 32;
+#pragma unroll
+        for (int i = 0; i < 2; i++) {
+          const float send = up ? p[i] : p[i + 2], keep = up ? p[i + 2] : p[i];
+          r2[i] = keep + __shfl_xor(send, 32, 64);
+        }
+      }
+      {
+        const bool up = lane & 16;
+        const float send = up ? r2[0] : r2[1], keep = up ? r2[1] : r2[0];
+        r1 = keep + __shfl_xor(send, 16, 64);
+      }
+      r1 += __shfl_xor(r1, 8, 64);
     }
     r1 += __shfl_xor(r1, 4, 64);
     r1 += __shfl_xor(r1, 2, 64);
@@ -212,7 +237,7 @@ __global__ __launch_bounds__(256) void attn_decode_i16_kernel(AttnI16Args a) {
     float s[NK], bm = -INFINITY;
 #pragma unroll
     for (int i = 0; i < NK; i++) {
-      s[i] = __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)__float_as_uint(r1), 8 * i)) * b.ks[i];
+      s[i] = __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)__float_as_uint(r1), (64 / NK) * i)) * b.ks[i];
       if (j0 + i >= n_cached) s[i] = -INFINITY;
       bm = fmaxf(bm, s[i]);
     }
@@ -236,20 +261,11 @@ __global__ __launch_bounds__(256) void attn_decode_i16_kernel(AttnI16Args a) {
     m = mn;
   };
   {
-    Block A, B;
-    const int step = WPP * NK;
-    int j0 = wip * NK;
-    if (j0 < n_cached) load(j0, A);
-    new_key();  // while the first block travels
-    while (j0 < n_cached) {
-      const int j1 = j0 + step;
-      if (j1 < n_cached) load(j1, B);
+    Block A;
+    new_key();
+    for (int j0 = wip * NK; j0 < n_cached; j0 += WPP * NK) {
+      load(j0, A);
       compute(j0, A);
-      if (j1 >= n_cached) break;
-      const int j2 = j1 + step;
-      if (j2 < n_cached) load(j2, A);
-      compute(j1, B);
-      j0 = j2;
     }
   }
   if (WPP == 4) {
