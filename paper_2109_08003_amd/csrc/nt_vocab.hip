@@ -74,8 +74,8 @@ static VsSplit vs_split(int M, int tile_m, int max_ranges) {
 
 // EXACT = false ("single pass"): 128 rows per tile, logits from the head plane only; besides the partial keys the
 //   runner-up logit of every range goes to ps, so that the caller can certify the arg-max.
-// EXACT = true: 64 rows per tile, logits from the head/tail plane pair (both multiplied with the same W
-//   fragment into one accumulator).  Either every row m < M is processed and partial keys go to
+// EXACT = true: 64 rows per tile (32 for gathered rows, which are few), logits from the head/tail plane pair (both
+//   multiplied with the same W fragment into one accumulator).  Either every row m < M is processed and partial keys go to
 //   pk[m * G + range], or (row_map != nullptr) the rows row_map[0 .. *count) are gathered, every workgroup walks
 //   all their tiles, and each result is folded into final_key[slot] with a 64-bit atomic max
 //   (order-independent, hence still deterministic).
@@ -92,8 +92,11 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
                                                                     int mask_ranges) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   _Float16 *sh = (_Float16 *)smem;
-  constexpr int NACC = EXACT ? 2 : 4;       // 32-row blocks of h per tile
-  constexpr int TILE_M = EXACT ? 64 : 128;
+  constexpr int NACC = EXACT ? (GATHER ? 1 : 2) : 4;  // 32-row blocks of h per tile
+  constexpr int NW = VS_WAVES;
+  constexpr int TILE_M = 32 * NACC;
+  constexpr int FR = EXACT ? 2 * TILE_M : TILE_M;  // fragment rows in the LDS: head rows, then tail rows
+  constexpr int NOP = FR / 32;
   constexpr int LD = K + 8;                 // halfs per LDS row: the 16 B pad keeps the fragment reads conflict-free
   constexpr int KS = K / 16;
   // register slots of W fragments per wave; the lookahead is SL - 1 k-steps (the single-pass variant has 128
@@ -113,7 +116,7 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
   const int sb0 = gi * NS / G, sb1 = (gi + 1) * NS / G;  // G <= 256 and NS < 2^22: no overflow
   if (GATHER) M = *count;  // number of gathered rows, decided on the device
   // gathered rows of the current tile and their result slots (beyond the h tile and the per-wave results)
-  int *sel_row = (int *)(smem + VS_ROWS * LD * 2), *sel_slot = sel_row + 64, *wtot = sel_slot + 64;
+  int *sel_row = (int *)(smem + FR * LD * 2), *sel_slot = sel_row + 64, *wtot = sel_slot + 64;
 
   // W fragments come through a buffer resource: scalar offset per fragment, constant lane offset
   const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void *)Wp, 0, NS * 64 * K * 2, 0x00020000);
@@ -132,10 +135,10 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
     if (K == 512) {
       // one wave instruction moves one row (1 KiB) without passing through registers
 #pragma unroll
-      for (int i = 0; i < VS_ROWS / VS_WAVES; i++) {
-        const int R = wave + VS_WAVES * i;
-        const int rr = EXACT ? (R & 63) : R;
-        const _Float16 *src = (EXACT && R >= 64) ? h_lo : h_hi;
+      for (int i = 0; i < FR / NW; i++) {
+        const int R = wave + NW * i;
+        const int rr = EXACT ? (R & (TILE_M - 1)) : R;
+        const _Float16 *src = (EXACT && R >= TILE_M) ? h_lo : h_hi;
         int m = m0 + rr;
         m = m < Mlim ? m : Mlim - 1;
         const long gm = GATHER ? __builtin_amdgcn_readfirstlane(sel_row[m]) : m;
@@ -143,13 +146,13 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
                                          (__attribute__((address_space(3))) void *)(sh + R * LD), 16, 0, 0);
       }
     } else {
-      constexpr int CPR = K / 8, PER_T = VS_ROWS * CPR / (VS_WAVES * 64);
+      constexpr int CPR = K / 8, PER_T = FR * CPR / (NW * 64);
       u32x4 fr[PER_T];
 #pragma unroll
       for (int i = 0; i < PER_T; i++) {
-        const int c = tid + VS_WAVES * 64 * i, R = c / CPR, kc = c % CPR;
-        const int rr = EXACT ? (R & 63) : R;
-        const _Float16 *src = (EXACT && R >= 64) ? h_lo : h_hi;
+        const int c = tid + NW * 64 * i, R = c / CPR, kc = c % CPR;
+        const int rr = EXACT ? (R & (TILE_M - 1)) : R;
+        const _Float16 *src = (EXACT && R >= TILE_M) ? h_lo : h_hi;
         int m = m0 + rr;
         m = m < Mlim ? m : Mlim - 1;
         const long gm = GATHER ? sel_row[m] : m;
@@ -157,7 +160,7 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
       }
 #pragma unroll
       for (int i = 0; i < PER_T; i++) {
-        const int c = tid + VS_WAVES * 64 * i, R = c / CPR, kc = c % CPR;
+        const int c = tid + NW * 64 * i, R = c / CPR, kc = c % CPR;
         *(u32x4 *)(sh + R * LD + kc * 8) = fr[i];
       }
     }
@@ -189,13 +192,13 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
       int off2 = 64 * LD;  // second base register: the byte offsets of fragment rows 64.. do not fit 16 bits
       asm volatile("" : "+v"(off2));
       const _Float16 *hrow2 = hrow + off2;
-      half8 hf[4];
+      half8 hf[NOP];
 #pragma unroll
-      for (int op = 0; op < 4; op++) hf[op] = *(const half8 *)((op < 2 ? hrow : hrow2) + (op & 1) * 32 * LD);
-      for (; strip < sb1; strip += VS_WAVES) {
-        const bool more = strip + VS_WAVES < sb1;
+      for (int op = 0; op < NOP; op++) hf[op] = *(const half8 *)((op < 2 ? hrow : hrow2) + (op & 1) * 32 * LD);
+      for (; strip < sb1; strip += NW) {
+        const bool more = strip + NW < sb1;
         const int pcur = strip * (KS * 2048);
-        const int pnext = (more ? strip + VS_WAVES : strip) * (KS * 2048);
+        const int pnext = (more ? strip + NW : strip) * (KS * 2048);
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
           // the lookahead runs into the next strip of this wave at the end of a strip (at the very end it
@@ -204,7 +207,7 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
           const int pf = tgt < KS ? pcur + tgt * 2048 : pnext + (tgt - KS) * 2048;
           const int ksn = (ks + 1) % KS;
 #pragma unroll
-          for (int op = 0; op < 4; op++) {
+          for (int op = 0; op < NOP; op++) {
 #pragma unroll
             for (int nb = 0; nb < 2; nb++) {
               if (ks == 0 && op < NACC) {
@@ -253,8 +256,8 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
       }
     }
     __syncthreads();  // every wave is done with the h tile: its LDS now carries the per-wave results
-    unsigned long long *skey = (unsigned long long *)smem;  // [VS_WAVES][TILE_M]
-    float *ssec = (float *)(smem + VS_WAVES * TILE_M * 8);  // [VS_WAVES][TILE_M]
+    unsigned long long *skey = (unsigned long long *)smem;  // [NW][TILE_M]
+    float *ssec = (float *)(smem + NW * TILE_M * 8);  // [NW][TILE_M]
 #pragma unroll
     for (int a = 0; a < NACC; a++) {
       const int c = rcode[a], v = c & 15;
@@ -278,7 +281,7 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
       unsigned long long best = 0ull;
       float second = -INFINITY;
 #pragma unroll
-      for (int w = 0; w < VS_WAVES; w++) {
+      for (int w = 0; w < NW; w++) {
         const unsigned long long k = skey[w * TILE_M + tid];
         const float s2 = ssec[w * TILE_M + tid];
         const bool take = k > best;
@@ -305,7 +308,7 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
   }
   // Gathered rows: the caller has marked, per row, which of mask_ranges equal ranges of the vocabulary can hold its
   // arg-max at all; this workgroup takes the rows whose marks meet its own strips.  The list is walked 512 entries
-  // at a time; the wanted entries are ranked with a workgroup prefix sum and processed 64 rows per tile.
+  // at a time; the wanted entries are ranked with a workgroup prefix sum and processed 32 rows per tile.
   // range r of the caller covers strips [r * NS / mask_ranges, (r + 1) * NS / mask_ranges): strip s lies in range
   // ((s + 1) * mask_ranges - 1) / NS
   unsigned long long mine = 0ull;
@@ -313,7 +316,7 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
     const int r_lo = ((sb0 + 1) * mask_ranges - 1) / NS, r_hi = (sb1 * mask_ranges - 1) / NS;
     mine = (r_hi >= 63 ? ~0ull : (1ull << (r_hi + 1)) - 1ull) & ~((1ull << r_lo) - 1ull);
   }
-  for (int c0 = 0; c0 < M; c0 += VS_WAVES * 64) {
+  for (int c0 = 0; c0 < M; c0 += NW * 64) {
     const int i = c0 + tid;
     const bool need = i < M && (need_mask[i] & mine) != 0ull;
     const unsigned long long bal = __ballot(need);
@@ -321,24 +324,24 @@ __global__ __launch_bounds__(VS_WAVES * 64) void vocab_stream_kernel(const _Floa
     __syncthreads();
     int rank = __popcll(bal & ((1ull << lane) - 1ull)), total = 0;
 #pragma unroll
-    for (int w = 0; w < VS_WAVES; w++) {
+    for (int w = 0; w < NW; w++) {
       const int c = wtot[w];
       rank += w < wave ? c : 0;
       total += c;
     }
-    for (int t0 = 0; t0 < total; t0 += 64) {  // total is uniform over the workgroup
-      if (need && rank >= t0 && rank < t0 + 64) {
+    for (int t0 = 0; t0 < total; t0 += TILE_M) {  // total is uniform over the workgroup
+      if (need && rank >= t0 && rank < t0 + TILE_M) {
         sel_row[rank - t0] = row_map[i];
         sel_slot[rank - t0] = i;
       }
       __syncthreads();
-      tile(0, total - t0 < 64 ? total - t0 : 64);
+      tile(0, total - t0 < TILE_M ? total - t0 : TILE_M);
     }
     __syncthreads();  // wtot is rewritten by the next chunk
   }
 }
 
-static size_t vs_lds_bytes(int K) { return (size_t)VS_ROWS * (K + 8) * 2 + 1024; }
+static size_t vs_lds_bytes(int K, int frag_rows) { return (size_t)frag_rows * (K + 8) * 2 + 1024; }
 
 template <bool EXACT, int K, bool GATHER>
 static hipError_t vs_launch(const _Float16 *h, const _Float16 *h_lo, long ldh, const int *row_map, const int *count, int M,
@@ -346,14 +349,15 @@ static hipError_t vs_launch(const _Float16 *h, const _Float16 *h_lo, long ldh, c
                             unsigned long long *final_key, const unsigned long long *need_mask, int mask_ranges,
                             hipStream_t s) {
   auto kern = vocab_stream_kernel<EXACT, K, GATHER>;
+  constexpr int FR = (EXACT && GATHER) ? 64 : VS_ROWS;  // as in the kernel
   // raising the dynamic LDS limit is per kernel, once per process (several host threads may get here at once)
   static std::once_flag once;
   static hipError_t attr_err = hipSuccess;
   std::call_once(once, [&] {
-    attr_err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vs_lds_bytes(K));
+    attr_err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)vs_lds_bytes(K, FR));
   });
   if (attr_err != hipSuccess) return attr_err;
-  hipLaunchKernelGGL(kern, dim3(8 * p.per_xcd), dim3(VS_WAVES * 64), vs_lds_bytes(K), s, h, h_lo, ldh, row_map, count, M, Wp,
+  hipLaunchKernelGGL(kern, dim3(8 * p.per_xcd), dim3(VS_WAVES * 64), vs_lds_bytes(K, FR), s, h, h_lo, ldh, row_map, count, M, Wp,
                      N, p.m_tiles, p.G, p.per_xcd, pk, ps, final_key, need_mask, mask_ranges);
   return hipGetLastError();
 }
@@ -405,14 +409,14 @@ hipError_t launch_vocab_argmax_certified(const _Float16 *h, const _Float16 *h_lo
   if (e != hipSuccess) return e;
   e = launch_argmax_select(pk, ps, p.G, M, lo_norm, w_norm_max, tok, slot_of_row, list, count, final_key, need_mask, s);
   if (e != hipSuccess) return e;
-  // recompute of the uncertified rows: their number is known on the device only, so each of 64 workgroups takes
+  // recompute of the uncertified rows: their number is known on the device only, so each of 128 workgroups takes
   // a range of the vocabulary and those gathered rows that still have a candidate there (often none).  It is
-  // little work; a quarter of the chip is enough and leaves the rest to the kernels of the other pipeline lanes
-  // (measured best among 32 ... 256 workgroups).
+  // little work, bound by the latency of one strip per wave: half the chip gives the shortest launch, and the
+  // whole job runs as fast with it as with a quarter (measured among 32 ... 256 workgroups).
   VsSplit q;
   q.m_tiles = 1;
-  q.G = 2 * VS_CUS_PER_XCD;
-  q.per_xcd = VS_CUS_PER_XCD / 4;
+  q.G = 4 * VS_CUS_PER_XCD;
+  q.per_xcd = VS_CUS_PER_XCD / 2;
   return vs_launch_k<true, true>(h, h_lo, ldh, list, count, M, w, q, nullptr, nullptr, final_key, need_mask, p.G, s);
 }
 
