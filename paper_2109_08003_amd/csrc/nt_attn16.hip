@@ -313,7 +313,8 @@ template <int NE, bool SELF>
 static hipError_t a16_launch(const AttnI16Args &a, hipStream_t s) {
   // a wave per row keeps every SIMD busy once there are a few rows per SIMD; below that the four waves of a
   // workgroup share a row's keys
-  const bool shared = a.rows < 1024;
+  // (up to 4,096 rows the shared form was measured as fast alone and slower with other kernels beside it)
+  const bool shared = (a.shape_rows > 0 ? a.shape_rows : a.rows) < 1024;
   const unsigned grid = shared ? (unsigned)a.rows : (unsigned)((a.rows + 3) / 4);
 #define NT_A16(WPP_, IND_) hipLaunchKernelGGL((attn_decode_i16_kernel<NE, WPP_, SELF, IND_>), dim3(grid), dim3(256), 0, s, a)
   if (shared && a.origin) NT_A16(4, true);

@@ -1049,7 +1049,7 @@ int decode_step(nt_model *m, DecodeCursor &cu, hipStream_t s) {
         if (m->kv_i16) {
           nt::AttnI16Args at{};
           at.q = m->q32; at.kv = (short *)m->self_kv[l]; at.sc = m->self_sc[l]; at.row_positions = T; at.n_keys = t + 1;
-          at.rows = R; at.d = d; at.kv_new = m->kv_new; at.origin = origin; at.ctx = m->ctx32;
+          at.rows = R; at.shape_rows = rows_for_choice; at.d = d; at.kv_new = m->kv_new; at.origin = origin; at.ctx = m->ctx32;
           at.ctx_lo_offset = streams(d, d, L.self.Wo_p, false) ? lo_rows * d : 0;
           KT(K_ATTN_DEC_SELF, Rd * t * (2 * dd * 2 + 8) + Rd * dd * 20, 4 * Rd * (t + 1) * dd, nt::launch_attn_decode_i16(at, s));
         } else
@@ -1072,7 +1072,7 @@ int decode_step(nt_model *m, DecodeCursor &cu, hipStream_t s) {
         if (m->kv_i16) {
           nt::AttnI16Args at{};
           at.q = m->q32; at.kv = (short *)m->cross[l]; at.sc = m->cross_sc[l]; at.row_positions = S; at.len = m->len;
-          at.rows = R; at.d = d; at.origin = origin; at.ctx = m->ctx32;
+          at.rows = R; at.shape_rows = rows_for_choice; at.d = d; at.origin = origin; at.ctx = m->ctx32;
           at.ctx_lo_offset = streams(d, d, L.cross.Wo_p, false) ? lo_rows * d : 0;
           KT(K_ATTN_DEC_CROSS, cross_keys * (2 * dd * 2 + 8) + Rd * dd * 8, 4 * cross_keys * dd, nt::launch_attn_decode_i16(at, s));
         } else

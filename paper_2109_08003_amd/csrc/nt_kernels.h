@@ -344,6 +344,8 @@ struct AttnI16Args {
   const int32_t *len;    // cross-attention: keys of each cache row; nullptr for self-attention
   int n_keys;            // self-attention: t + 1; the last key/value pair is kv_new's, appended to the cache by the kernel
   int rows, d;
+  int shape_rows;        // row count that selects the kernel form (0: rows).  The forms differ in the last bit, so a
+                         // caller whose row count depends on timing passes one that does not
   const float *kv_new;   // self-attention: [rows, 2 d] fp32 (key | value of this step); nullptr for cross-attention
   const int32_t *origin; // optional: query row r uses cache row origin[r] (< 0: zero context)
   float *ctx;            // [rows, d] fp32, or (ctx_lo_offset != 0) head/tail fp16 planes
