@@ -29,8 +29,9 @@ namespace nt {
 
 // Keys per block.  Four, with the block's vectors requested right before their use, keeps the kernel at 80-100
 // registers: measured on the whole job (four pipeline lanes) +1.2 % over blocks of eight with the next block
-// requested ahead (220-250 registers), which is faster alone but leaves no room for its waves beside the workgroups
-// of another lane's output projection; forcing 64 registers (spills) was 2 % slower than either.
+// requested ahead (220-250 registers), which is faster alone; blocks of two in 64 registers were no faster on the job
+// either (the kernel's waves start as the workgroups of the other lanes' kernels end, and more of them fit sooner
+// when they are small).
 constexpr int A16_NK = 4;
 
 bool attn_i16_supported(int d, int heads, int clip) { return heads == 1 && clip == 0 && (d == 256 || d == 512); }
