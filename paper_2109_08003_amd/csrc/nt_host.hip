@@ -1654,21 +1654,27 @@ int nt_translate_batch(nt_model *m, const int32_t *h_tokens, const int64_t *h_of
     if (hipGetDevice(&dev) != hipSuccess) return pl.drain(fail(NT_EHIP, "hipGetDevice failed"));
     std::vector<int> lane_rc(n_lanes, NT_OK);
     std::vector<std::string> lane_err(n_lanes);
+    auto feed = [&](size_t li) {
+      try {
+        if (hipSetDevice(dev) != hipSuccess) lane_rc[li] = fail(NT_EHIP, "hipSetDevice failed in a lane's thread");
+        for (size_t n = 0; n < lane_batches[li].size() && lane_rc[li] == NT_OK; n++)
+          lane_rc[li] = run_batch(li, lane_batches[li][n], (int64_t)n);
+      } catch (const std::bad_alloc &) {
+        lane_rc[li] = fail(NT_ENOMEM, "host allocation failed");
+      } catch (...) {
+        lane_rc[li] = fail(NT_EINVAL, "unexpected exception");
+      }
+      if (lane_rc[li]) lane_err[li] = g_err;  // the message lives in the feeding thread: hand it over
+    };
     std::vector<std::thread> workers;
-    for (size_t li = 0; li < n_lanes; li++)
-      workers.emplace_back([&, li] {
-        try {
-          if (hipSetDevice(dev) != hipSuccess) lane_rc[li] = fail(NT_EHIP, "hipSetDevice failed in a lane's thread");
-          for (size_t n = 0; n < lane_batches[li].size() && lane_rc[li] == NT_OK; n++)
-            lane_rc[li] = run_batch(li, lane_batches[li][n], (int64_t)n);
-        } catch (const std::bad_alloc &) {
-          lane_rc[li] = fail(NT_ENOMEM, "host allocation failed");
-        } catch (...) {
-          lane_rc[li] = fail(NT_EINVAL, "unexpected exception");
-        }
-        if (lane_rc[li]) lane_err[li] = g_err;  // the message lives in this thread: hand it over
-      });
+    workers.reserve(n_lanes);
+    size_t li = 0;
+    try {
+      for (; li < n_lanes; li++) workers.emplace_back(feed, li);
+    } catch (...) {  // no further thread to be had: this one feeds the remaining lanes once the others are done
+    }
     for (auto &w : workers) w.join();
+    for (; li < n_lanes; li++) feed(li);
     for (size_t li = 0; li < n_lanes && first_err == NT_OK; li++)
       if (lane_rc[li]) { first_err = lane_rc[li]; g_err = lane_err[li]; }
   } else {
