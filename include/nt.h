@@ -331,11 +331,19 @@ int nt_debug_timing_read(nt_model *m, int kernel, double *total_ms, int64_t *lau
                          void *hip_stream);
 
 /*
- * What this GPU reaches on two plain probes, for rooflines against measured rather than datasheet peaks: a loop of
- * independent fp16 MFMAs on every SIMD (TFLOP/s) and a streaming read of up to 1 GiB of the model's arena (GB/s).
- * Best of three runs each; synchronises hip_stream.  Measurement aid, a few milliseconds.
+ * What this GPU reaches on plain probes, for rooflines against measured rather than datasheet peaks:
+ *   mfma_tflops                     a loop of independent 32x32x16 fp16 MFMAs on every SIMD whose operands are random
+ *                                   values that change from one instruction to the next, as a model's weights and
+ *                                   activations do (TFLOP/s): what the power limit lets the matrix pipes sustain on
+ *                                   real data;
+ *   mfma_tflops_constant_operands   the same loop on two constant operands: little switching in the multipliers, the
+ *                                   chip holds its clock, close to the datasheet figure;
+ *   hbm_read_gbs                    a streaming read of up to 1 GiB of the model's arena (GB/s).
+ * Best of three runs each; synchronises hip_stream.  Measurement aid, a few tens of milliseconds.
+ * Errors: NT_EINVAL (null argument), NT_EHIP.
  */
-int nt_debug_probe_peaks(nt_model *m, double *mfma_tflops, double *hbm_read_gbs, void *hip_stream);
+int nt_debug_probe_peaks(nt_model *m, double *mfma_tflops, double *mfma_tflops_constant_operands, double *hbm_read_gbs,
+                         void *hip_stream);
 
 /*
  * Pipeline lanes.  A model holds pipeline_lanes lanes that share the weights; each lane has its own

@@ -1365,8 +1365,9 @@ int nt_debug_timing_enable(nt_model *m, uint64_t kernel_mask) {
   return NT_OK;
 }
 
-int nt_debug_probe_peaks(nt_model *m, double *mfma_tflops, double *hbm_read_gbs, void *hip_stream) {
-  if (!m || !mfma_tflops || !hbm_read_gbs) return fail(NT_EINVAL, "null argument");
+int nt_debug_probe_peaks(nt_model *m, double *mfma_tflops, double *mfma_tflops_constant_operands, double *hbm_read_gbs,
+                         void *hip_stream) {
+  if (!m || !mfma_tflops || !mfma_tflops_constant_operands || !hbm_read_gbs) return fail(NT_EINVAL, "null argument");
   hipStream_t s = as_stream(hip_stream);
   hipEvent_t e0 = nullptr, e1 = nullptr;
   if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
@@ -1375,26 +1376,25 @@ int nt_debug_probe_peaks(nt_model *m, double *mfma_tflops, double *hbm_read_gbs,
   }
   struct Ev { hipEvent_t a, b; ~Ev() { (void)hipEventDestroy(a); (void)hipEventDestroy(b); } } ev{e0, e1};
   float *sink = (float *)(m->flags + 12);
-  const int iters = 4000, blocks = 512;  // two workgroups of four waves per CU: two waves per SIMD
+  const int iters = 16000, blocks = 256;  // a workgroup of eight waves per CU: two waves per SIMD, 4 to 5 ms a run
   const long bytes = (long)std::min<size_t>(m->arena_bytes, (size_t)1 << 30) & ~15l;
-  double best_mfma = 0.0, best_read = 0.0;
-  for (int rep = 0; rep < 3; rep++) {
-    float ms = 0.f;
-    HIP_TRY(hipEventRecord(e0, s));
-    HIP_TRY(nt::launch_probe_mfma(iters, blocks, sink, s));
-    HIP_TRY(hipEventRecord(e1, s));
-    HIP_TRY(hipEventSynchronize(e1));
-    HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
-    if (ms > 0.f) best_mfma = std::max(best_mfma, (double)blocks * 4 * iters * 4 * (2.0 * 32 * 32 * 16) / (ms * 1e-3) / 1e12);
-    HIP_TRY(hipEventRecord(e0, s));
-    HIP_TRY(nt::launch_probe_read(m->d_arena, bytes, sink, s));
-    HIP_TRY(hipEventRecord(e1, s));
-    HIP_TRY(hipEventSynchronize(e1));
-    HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
-    if (ms > 0.f) best_read = std::max(best_read, (double)bytes / (ms * 1e-3) / 1e9);
-  }
-  *mfma_tflops = best_mfma;
-  *hbm_read_gbs = best_read;
+  double best[3] = {0.0, 0.0, 0.0};  // MFMA with changing operands, with constant operands, streaming read
+  for (int what = 0; what < 3; what++)
+    for (int rep = 0; rep < 3; rep++) {
+      float ms = 0.f;
+      HIP_TRY(hipEventRecord(e0, s));
+      if (what < 2) HIP_TRY(nt::launch_probe_mfma(iters, blocks, what == 0, sink, s));
+      else HIP_TRY(nt::launch_probe_read(m->d_arena, bytes, sink, s));
+      HIP_TRY(hipEventRecord(e1, s));
+      HIP_TRY(hipEventSynchronize(e1));
+      HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+      if (ms <= 0.f) continue;
+      const double work = what < 2 ? (double)blocks * 8 * iters * 8 * (2.0 * 32 * 32 * 16) / 1e12 : (double)bytes / 1e9;
+      best[what] = std::max(best[what], work / (ms * 1e-3));
+    }
+  *mfma_tflops = best[0];
+  *mfma_tflops_constant_operands = best[1];
+  *hbm_read_gbs = best[2];
   return NT_OK;
 }
 

@@ -197,7 +197,8 @@ hipError_t launch_spin(long ticks, int *sink, hipStream_t s);
 
 // Probes: `blocks` workgroups of four waves, each wave `iters` x 4 independent 32x32x16 fp16 MFMAs (2 * 32 * 32 * 16
 // flops each); a grid-stride read of `bytes` bytes (a multiple of 16).  sink is never written.
-hipError_t launch_probe_mfma(int iters, int blocks, float *sink, hipStream_t s);
+// workgroups of eight waves, iters (a multiple of 8) rounds of eight independent 32x32x16 fp16 MFMAs per wave
+hipError_t launch_probe_mfma(int iters, int blocks, bool random_operands, float *sink, hipStream_t s);
 hipError_t launch_probe_read(const void *src, long bytes, float *sink, hipStream_t s);
 
 // Start of decoder step t for rows [0, rows_prev): (1) if t > 0, reduce the arg-max partials of

@@ -206,26 +206,39 @@ hipError_t launch_spin(long ticks, int *sink, hipStream_t s) {
 // ---- probes of what the machine reaches: a loop of independent MFMAs, and a streaming read ----------------------
 typedef _Float16 probe_half8 __attribute__((ext_vector_type(8)));
 typedef float probe_floatx16 __attribute__((ext_vector_type(16)));
-__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float *sink) {
-  probe_half8 a, b;
+// RANDOM = false: every MFMA multiplies the same two constant operands, the most the pipes ever do (little switching
+// in the multipliers, so the chip holds its clock).  RANDOM = true: eight A and eight B operands of random fp16 values
+// in rotation, so that the operand bits change from one instruction to the next as they do on a model's weights and
+// activations: the rate the power limit then allows, which is the ceiling of a real matrix product.
+template <bool RANDOM>
+__global__ __launch_bounds__(512) void probe_mfma_kernel(int iters, float *sink) {
+  probe_half8 a[8], b[8];
+  unsigned x = 12345u ^ (threadIdx.x * 2654435761u) ^ (blockIdx.x * 40503u);
 #pragma unroll
-  for (int e = 0; e < 8; e++) {
-    a[e] = (_Float16)(0.001f * (float)((threadIdx.x + e) & 15));
-    b[e] = (_Float16)(0.002f * (float)((threadIdx.x * 3 + e) & 7));
-  }
-  probe_floatx16 acc[4];
+  for (int i = 0; i < 8; i++)
 #pragma unroll
-  for (int i = 0; i < 4; i++)
+    for (int e = 0; e < 8; e++) {
+      x = x * 1664525u + 1013904223u;
+      a[i][e] = (_Float16)(RANDOM ? (float)(x >> 8) * (1.f / 8388608.f) - 1.f : 0.5f);
+      x = x * 1664525u + 1013904223u;
+      b[i][e] = (_Float16)(RANDOM ? ((float)(x >> 8) * (1.f / 8388608.f) - 1.f) * 0.05f : 0.01f);
+    }
+  probe_floatx16 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; i++)
 #pragma unroll
     for (int v = 0; v < 16; v++) acc[i][v] = 0.f;
-  for (int it = 0; it < iters; it++) {
+  for (int it = 0; it < iters; it += 8) {
 #pragma unroll
-    for (int i = 0; i < 4; i++) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[i], 0, 0, 0);
+    for (int j = 0; j < 8; j++)
+#pragma unroll
+      for (int i = 0; i < 8; i++)
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[(i + 3 * j) & 7], b[(i + j) & 7], acc[i], 0, 0, 0);
   }
   float t = 0.f;
 #pragma unroll
-  for (int i = 0; i < 4; i++) t += acc[i][0] + acc[i][7];
-  if (t == -1.f) *sink = t;  // never true (the sums are non-negative): keeps the loop alive
+  for (int i = 0; i < 8; i++) t += acc[i][0] + acc[i][7];
+  if (t == 1.2345e33f) *sink = t;  // practically never: keeps the loop alive
 }
 __global__ __launch_bounds__(256) void probe_read_kernel(const float4 *src, long n4, float *sink) {
   float t = 0.f;
@@ -235,8 +248,9 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const float4 *src, long
   }
   if (t == 1.2345e33f) *sink = t;  // practically never: keeps the loads alive
 }
-hipError_t launch_probe_mfma(int iters, int blocks, float *sink, hipStream_t s) {
-  hipLaunchKernelGGL(probe_mfma_kernel, dim3(blocks), dim3(256), 0, s, iters, sink);
+hipError_t launch_probe_mfma(int iters, int blocks, bool random_operands, float *sink, hipStream_t s) {
+  if (random_operands) hipLaunchKernelGGL(probe_mfma_kernel<true>, dim3(blocks), dim3(512), 0, s, iters, sink);
+  else hipLaunchKernelGGL(probe_mfma_kernel<false>, dim3(blocks), dim3(512), 0, s, iters, sink);
   return hipGetLastError();
 }
 hipError_t launch_probe_read(const void *src, long bytes, float *sink, hipStream_t s) {
