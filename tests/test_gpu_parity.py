@@ -347,6 +347,27 @@ def test_c1_encoder_and_logit_tolerances_at_benchmark_row_counts(nt, oracle, tor
         assert worst_enc <= 2e-3 and worst_abs <= 2e-2 and worst_rel <= 2e-3
 
 
+def test_measurement_aids_report_plausible_figures(c0, nt):
+    """nt_debug_probe_peaks and the per-family timing table, as bench.py uses them: the probes stay below the
+    datasheet peaks of the MI355X (2.5 PFLOP/s fp16 MFMA, 8 TB/s), operands that change cost matrix rate, and the
+    table counts the launches of a translation with their algorithmic bytes."""
+    cfg, blob, src, gm, om = c0
+    pk = gm.probe_peaks()
+    assert 200.0 < pk["mfma_f16_tflops"] <= pk["mfma_f16_tflops_constant_operands"] * 1.02
+    assert pk["mfma_f16_tflops_constant_operands"] < 2500.0 * 1.02
+    assert pk["hbm_read_gbs"] > 100.0   # this small model's arena is read from the caches: no upper bound here
+    tokens = np.concatenate(src[:32]).astype(np.int32)
+    offsets = np.concatenate([[0], np.cumsum([len(x) for x in src[:32]])]).astype(np.int64)
+    gm.timing_enable("all")
+    gm.translate_batch(tokens, offsets, token_budget=4096)
+    tab = gm.timing_read()
+    gm.timing_enable(None)
+    assert tab and set(tab) <= set(nt.kernel_names())
+    for name, k in tab.items():
+        assert k["launches"] > 0 and k["ms"] > 0.0 and k["bytes"] > 0, name
+    assert any(n.startswith("vocab_argmax") for n in tab) and any(n.startswith("attn_decode") for n in tab)
+
+
 def test_tiled_argmax_kernels_agree_with_streaming_kernels(nt):
     """Model widths other than 256 / 512 take the tiled arg-max kernels; nt_debug_set_vocab_tiled selects them for
     any width.  Both compute the same head+tail logits (in a different summation order), with batches
