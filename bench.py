@@ -211,6 +211,7 @@ def main():
                              GBps=round(gbs, 1), TFLOPs=round(tfs, 2),
                              pct_hbm_peak=round(100 * gbs / HBM_PEAK_GBS, 1), pct_mfma_peak=round(100 * tfs / mfma_peak, 1),
                              pct_hbm_measured=round(100 * gbs / peaks["hbm_read_gbs"], 1),
+                             pct_hbm_copy_measured=round(100 * gbs / peaks["hbm_copy_gbs"], 1),
                              pct_mfma_measured=round(100 * tfs / peaks["mfma_f16_tflops"], 1))
         return tab
 
@@ -296,10 +297,12 @@ def main():
         "measured_peaks": {"mfma_f16_tflops": round(peaks["mfma_f16_tflops"], 1),
                            "mfma_f16_tflops_constant_operands": round(peaks["mfma_f16_tflops_constant_operands"], 1),
                            "hbm_read_gbs": round(peaks["hbm_read_gbs"], 1),
+                           "hbm_copy_gbs": round(peaks["hbm_copy_gbs"], 1),
                            "how": "nt_debug_probe_peaks in this run: a loop of independent 32x32x16 fp16 MFMAs on every "
                                   "SIMD, on random operands that change with every instruction (what the power limit "
                                   "allows on real data; the figure measured_peak uses) and on constant operands; a "
-                                  "streaming read of 1 GiB"},
+                                  "streaming read of 1 GiB; the same GiB read and written back (bytes read + written "
+                                  "per second: the ceiling of kernels that write as much as they read)"},
         "c1_budget4096": c1,
         "paper_context": "247,000 words/s on one NVIDIA A100 (different model, data and harness; context only)",
         "eos_mode": eos_mode, "roofline": roofline, "cpu_baseline": cpu, "kernels": table, "kernels_solo": table_solo,

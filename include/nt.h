@@ -338,12 +338,15 @@ int nt_debug_timing_read(nt_model *m, int kernel, double *total_ms, int64_t *lau
  *                                   real data;
  *   mfma_tflops_constant_operands   the same loop on two constant operands: little switching in the multipliers, the
  *                                   chip holds its clock, close to the datasheet figure;
- *   hbm_read_gbs                    a streaming read of up to 1 GiB of the model's arena (GB/s).
- * Best of three runs each; synchronises hip_stream.  Measurement aid, a few tens of milliseconds.
+ *   hbm_read_gbs                    a streaming read of up to 1 GiB of the model's arena (GB/s);
+ *   hbm_copy_gbs                    the same bytes read and written back in place, bytes read + bytes written per
+ *                                   second (GB/s): what kernels that write as much as they read can reach.
+ * Best of three runs each; synchronises hip_stream; the arena keeps its contents (no other stream may use this
+ * model meanwhile).  Measurement aid, a few tens of milliseconds.
  * Errors: NT_EINVAL (null argument), NT_EHIP.
  */
 int nt_debug_probe_peaks(nt_model *m, double *mfma_tflops, double *mfma_tflops_constant_operands, double *hbm_read_gbs,
-                         void *hip_stream);
+                         double *hbm_copy_gbs, void *hip_stream);
 
 /*
  * Pipeline lanes.  A model holds pipeline_lanes lanes that share the weights; each lane has its own

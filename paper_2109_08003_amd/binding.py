@@ -79,7 +79,7 @@ def load_library() -> C.CDLL:
         "nt_pipeline_lane": (p, [p, C.c_int]),
         "nt_lane_stream": (C.c_void_p, [p]),
         "nt_debug_timing_enable": (C.c_int, [p, C.c_uint64]),
-        "nt_debug_probe_peaks": (C.c_int, [p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), p]),
+        "nt_debug_probe_peaks": (C.c_int, [p] + [C.POINTER(C.c_double)] * 4 + [p]),
         "nt_debug_timing_count": (C.c_int, []),
         "nt_debug_timing_name": (C.c_char_p, [C.c_int]),
         "nt_debug_timing_read": (C.c_int, [p, C.c_int, C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(C.c_double),
@@ -281,10 +281,11 @@ class Model:
 
     def probe_peaks(self, stream=None) -> dict:
         """Measured peaks of this GPU (nt_debug_probe_peaks): fp16 MFMA rate on changing random operands and on
-        constant operands (TFLOP/s), streaming read (GB/s)."""
-        a, c, b = C.c_double(), C.c_double(), C.c_double()
-        _check(lib().nt_debug_probe_peaks(self._h, C.byref(a), C.byref(c), C.byref(b), _stream_ptr(stream)))
-        return {"mfma_f16_tflops": a.value, "mfma_f16_tflops_constant_operands": c.value, "hbm_read_gbs": b.value}
+        constant operands (TFLOP/s), streaming read and in-place copy (GB/s, the copy counting bytes read + written)."""
+        a, c, b, d = C.c_double(), C.c_double(), C.c_double(), C.c_double()
+        _check(lib().nt_debug_probe_peaks(self._h, C.byref(a), C.byref(c), C.byref(b), C.byref(d), _stream_ptr(stream)))
+        return {"mfma_f16_tflops": a.value, "mfma_f16_tflops_constant_operands": c.value, "hbm_read_gbs": b.value,
+                "hbm_copy_gbs": d.value}
 
     def timing_enable(self, kernels="all"):
         """kernels: "all", None/() to switch off, or an iterable of family names."""

@@ -1366,8 +1366,9 @@ int nt_debug_timing_enable(nt_model *m, uint64_t kernel_mask) {
 }
 
 int nt_debug_probe_peaks(nt_model *m, double *mfma_tflops, double *mfma_tflops_constant_operands, double *hbm_read_gbs,
-                         void *hip_stream) {
-  if (!m || !mfma_tflops || !mfma_tflops_constant_operands || !hbm_read_gbs) return fail(NT_EINVAL, "null argument");
+                         double *hbm_copy_gbs, void *hip_stream) {
+  if (!m || !mfma_tflops || !mfma_tflops_constant_operands || !hbm_read_gbs || !hbm_copy_gbs)
+    return fail(NT_EINVAL, "null argument");
   hipStream_t s = as_stream(hip_stream);
   hipEvent_t e0 = nullptr, e1 = nullptr;
   if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
@@ -1378,23 +1379,27 @@ int nt_debug_probe_peaks(nt_model *m, double *mfma_tflops, double *mfma_tflops_c
   float *sink = (float *)(m->flags + 12);
   const int iters = 16000, blocks = 256;  // a workgroup of eight waves per CU: two waves per SIMD, 4 to 5 ms a run
   const long bytes = (long)std::min<size_t>(m->arena_bytes, (size_t)1 << 30) & ~15l;
-  double best[3] = {0.0, 0.0, 0.0};  // MFMA with changing operands, with constant operands, streaming read
-  for (int what = 0; what < 3; what++)
+  // MFMA with changing operands, with constant operands, streaming read, read + write back in place
+  double best[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int what = 0; what < 4; what++)
     for (int rep = 0; rep < 3; rep++) {
       float ms = 0.f;
       HIP_TRY(hipEventRecord(e0, s));
       if (what < 2) HIP_TRY(nt::launch_probe_mfma(iters, blocks, what == 0, sink, s));
-      else HIP_TRY(nt::launch_probe_read(m->d_arena, bytes, sink, s));
+      else if (what == 2) HIP_TRY(nt::launch_probe_read(m->d_arena, bytes, sink, s));
+      else HIP_TRY(nt::launch_probe_copy(m->d_arena, bytes, s));
       HIP_TRY(hipEventRecord(e1, s));
       HIP_TRY(hipEventSynchronize(e1));
       HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
       if (ms <= 0.f) continue;
-      const double work = what < 2 ? (double)blocks * 8 * iters * 8 * (2.0 * 32 * 32 * 16) / 1e12 : (double)bytes / 1e9;
+      const double work = what < 2 ? (double)blocks * 8 * iters * 8 * (2.0 * 32 * 32 * 16) / 1e12
+                                   : (what == 2 ? 1.0 : 2.0) * (double)bytes / 1e9;
       best[what] = std::max(best[what], work / (ms * 1e-3));
     }
   *mfma_tflops = best[0];
   *mfma_tflops_constant_operands = best[1];
   *hbm_read_gbs = best[2];
+  *hbm_copy_gbs = best[3];
   return NT_OK;
 }
 

@@ -200,6 +200,8 @@ hipError_t launch_spin(long ticks, int *sink, hipStream_t s);
 // workgroups of eight waves, iters (a multiple of 8) rounds of eight independent 32x32x16 fp16 MFMAs per wave
 hipError_t launch_probe_mfma(int iters, int blocks, bool random_operands, float *sink, hipStream_t s);
 hipError_t launch_probe_read(const void *src, long bytes, float *sink, hipStream_t s);
+// reads bytes of buf and writes them back in place (the contents do not change)
+hipError_t launch_probe_copy(void *buf, long bytes, hipStream_t s);
 
 // Start of decoder step t for rows [0, rows_prev): (1) if t > 0, reduce the arg-max partials of
 // step t-1 and store the token in out[r*out_ld + t-1]; (2) for rows < rows_now: take the input

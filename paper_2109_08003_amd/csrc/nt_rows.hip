@@ -248,6 +248,10 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const float4 *src, long
   }
   if (t == 1.2345e33f) *sink = t;  // practically never: keeps the loads alive
 }
+// dst may be src itself: every thread writes back what it has read, so the buffer keeps its contents
+__global__ __launch_bounds__(256) void probe_copy_kernel(const float4 *src, float4 *dst, long n4) {
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (long)gridDim.x * blockDim.x) dst[i] = src[i];
+}
 hipError_t launch_probe_mfma(int iters, int blocks, bool random_operands, float *sink, hipStream_t s) {
   if (random_operands) hipLaunchKernelGGL(probe_mfma_kernel<true>, dim3(blocks), dim3(512), 0, s, iters, sink);
   else hipLaunchKernelGGL(probe_mfma_kernel<false>, dim3(blocks), dim3(512), 0, s, iters, sink);
@@ -255,6 +259,10 @@ hipError_t launch_probe_mfma(int iters, int blocks, bool random_operands, float 
 }
 hipError_t launch_probe_read(const void *src, long bytes, float *sink, hipStream_t s) {
   hipLaunchKernelGGL(probe_read_kernel, dim3(256 * 16), dim3(256), 0, s, (const float4 *)src, bytes / 16, sink);
+  return hipGetLastError();
+}
+hipError_t launch_probe_copy(void *buf, long bytes, hipStream_t s) {
+  hipLaunchKernelGGL(probe_copy_kernel, dim3(256 * 16), dim3(256), 0, s, (const float4 *)buf, (float4 *)buf, bytes / 16);
   return hipGetLastError();
 }
 

@@ -356,6 +356,7 @@ def test_measurement_aids_report_plausible_figures(c0, nt):
     assert 200.0 < pk["mfma_f16_tflops"] <= pk["mfma_f16_tflops_constant_operands"] * 1.02
     assert pk["mfma_f16_tflops_constant_operands"] < 2500.0 * 1.02
     assert pk["hbm_read_gbs"] > 100.0   # this small model's arena is read from the caches: no upper bound here
+    assert pk["hbm_copy_gbs"] > 100.0
     tokens = np.concatenate(src[:32]).astype(np.int32)
     offsets = np.concatenate([[0], np.cumsum([len(x) for x in src[:32]])]).astype(np.int64)
     gm.timing_enable("all")
