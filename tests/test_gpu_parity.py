@@ -221,6 +221,22 @@ def test_lanes_driven_by_the_caller_on_their_own_streams(torch_cuda, nt):
             assert np.array_equal(got[r, : steps[r]], ref[ro[i]:ro[i + 1]])
 
 
+def test_lane_count_and_feeding_threads_do_not_change_translations(nt):
+    """nt_translate_batch with one lane, and with four lanes at a small token budget (every lane fed by a host thread
+    of its own) and at a large one (one thread feeds the lanes in turn): the batches are the same, so the tokens are."""
+    cfg = nt_synth.model_config("C1")
+    blob = nt_synth.make_weights(cfg, seed=0)
+    tokens, offsets = nt_synth.workload("C1", 3000)
+    one = nt.Model(cfg, blob, max_batch_tokens=65536, pipeline_lanes=1)
+    four = nt.Model(cfg, blob, max_batch_tokens=65536, pipeline_lanes=4)
+    assert one.n_lanes() == 1 and four.n_lanes() == 4
+    for budget in (2048, 40000):
+        ref, ro = one.translate_batch(tokens, offsets, token_budget=budget)
+        for rep in range(2):
+            out, oo = four.translate_batch(tokens, offsets, token_budget=budget)
+            assert np.array_equal(ro, oo) and np.array_equal(ref, out), (budget, rep)
+
+
 # ------------------------------------------------------------------------------ edge cases
 def test_edge_cases(c0, nt, oracle):
     cfg, blob, src, gm, om = c0
