@@ -38,6 +38,11 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int VS_ROWS = 128;  // LDS fragment rows per tile (exact variant: 64 matrix rows x 2 planes)
 constexpr int VS_WAVES = 8;
 constexpr int VS_CUS_PER_XCD = 32;
+// Ranges of the vocabulary for the head+tail kernel that serves steps of fewer than 512 rows.  64 ranges are 7.8 strips
+// each, one per wave; more ranges only spread the same strips over more CUs with idle waves (up to 256 workgroups of
+// two busy waves), as fast for a launch alone but in the way of the other pipeline lanes' kernels: 64 instead of 256
+// gave +8 % on a 4,096-token budget with four lanes and the same with one (32: +9 % and -7 %).
+constexpr int VS_EXACT_MAX_RANGES = 64;
 
 bool vocab_stream_supported(int K) { return K == 256 || K == 512; }
 
@@ -380,14 +385,14 @@ static bool use_stream(const VocabWeights &w) { return !w.force_tiled && w.Wp &&
 
 int vocab_argmax_partials(const VocabWeights &w, int M, bool certified) {
   if (!use_stream(w)) return vocab_argmax_partials_tiled(M, w.N);
-  return certified ? vs_split(M, 128, 64).G : vs_split(M, 64, 256).G;
+  return certified ? vs_split(M, 128, 64).G : vs_split(M, 64, VS_EXACT_MAX_RANGES).G;
 }
 
 hipError_t launch_vocab_argmax(const _Float16 *h, const _Float16 *h_lo, long ldh, const VocabWeights &w, int M,
                                unsigned long long *pk, hipStream_t s) {
   if (M <= 0) return hipSuccess;
   if (!use_stream(w)) return launch_vocab_argmax_tiled(h, h_lo, ldh, w.Wt, M, w.N, w.K, pk, s);
-  return vs_launch_k<true, false>(h, h_lo, ldh, nullptr, nullptr, M, w, vs_split(M, 64, 256), pk, nullptr, nullptr, nullptr, 0, s);
+  return vs_launch_k<true, false>(h, h_lo, ldh, nullptr, nullptr, M, w, vs_split(M, 64, VS_EXACT_MAX_RANGES), pk, nullptr, nullptr, nullptr, 0, s);
 }
 
 // Certified single-pass arg-max.  With h = hi + lo, the head-only logit l'(v) = hi . w_v differs
